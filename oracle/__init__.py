@@ -1,0 +1,164 @@
+"""ctypes front-end of the fp64 CPU oracle (oracle/mole_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: the tests, the smoke check and the benchmark's
+CPU-baseline leg may import this; the product package never does.  Nothing here
+touches the HIP library, and the arithmetic all lives in the C file.
+
+Tensors are numpy arrays in storage format: float32, float64, or uint16 holding
+bfloat16 bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mole_oracle.c")
+_LIB = os.path.join(_HERE, "libmole_oracle.so")
+
+GELU_ERF, GELU_TANH = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (strict IEEE arithmetic: no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-ffp-contract=off",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.mole_oracle_gelu.restype = ctypes.c_double
+        _lib.mole_oracle_gelu.argtypes = [ctypes.c_double, ctypes.c_int]
+    return _lib
+
+
+def threads() -> int:
+    """Number of threads the oracle's parallel loops use (OpenMP default = visible cores)."""
+    n = os.environ.get("OMP_NUM_THREADS")
+    if n:
+        return int(n.split(",")[0])
+    try:
+        return len(os.sched_getaffinity(0))
+    except AttributeError:
+        return os.cpu_count() or 1
+
+
+def _code(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return 0
+    if a.dtype == np.uint16:
+        return 1
+    if a.dtype == np.float64:
+        return 2
+    raise TypeError(f"unsupported storage dtype {a.dtype}")
+
+
+def _p(a: Optional[np.ndarray]):
+    if a is None:
+        return None
+    assert a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _same(*arrs) -> int:
+    codes = {_code(a) for a in arrs if a is not None}
+    if len(codes) != 1:
+        raise TypeError("tensors that share a dtype argument must have one storage dtype")
+    return codes.pop()
+
+
+def gelu(x: float, act: int = GELU_ERF) -> float:
+    return float(lib().mole_oracle_gelu(float(x), int(act)))
+
+
+def gates(h: np.ndarray, W_r: np.ndarray) -> np.ndarray:
+    """Router equation: softmax over all N experts of h @ W_r.  h [T,d], W_r [d,N] -> [T,N] fp64."""
+    T, d = h.shape
+    d2, N = W_r.shape
+    assert d == d2
+    h = np.ascontiguousarray(h)
+    W_r = np.ascontiguousarray(W_r)
+    g = np.empty((T, N), dtype=np.float64)
+    rc = lib().mole_oracle_gates(_p(h), _code(h), _p(W_r), _code(W_r),
+                                 ctypes.c_int64(T), d, N, _p(g))
+    if rc:
+        raise RuntimeError(f"mole_oracle_gates rc={rc}")
+    return g
+
+
+def lookup_forward(table: np.ndarray, ids: np.ndarray, h: np.ndarray, W_r: np.ndarray,
+                   shared: Optional[np.ndarray] = None, residual: Optional[np.ndarray] = None
+                   ) -> Tuple[np.ndarray, np.ndarray, np.ndarray, int]:
+    """Inference-layer equation.  Returns (out [T,d] fp64, gates [T,N] fp64, rows [T] int64, err)."""
+    V, N, d = table.shape
+    T = int(ids.shape[0])
+    assert h.shape == (T, d) and W_r.shape == (d, N)
+    table = np.ascontiguousarray(table)
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    h, W_r = np.ascontiguousarray(h), np.ascontiguousarray(W_r)
+    shared = None if shared is None else np.ascontiguousarray(shared)
+    residual = None if residual is None else np.ascontiguousarray(residual)
+    act = _same(h, W_r, shared, residual)
+    out = np.empty((T, d), dtype=np.float64)
+    g = np.empty((T, N), dtype=np.float64)
+    rows = np.empty((T,), dtype=np.int64)
+    err = ctypes.c_int32(0)
+    rc = lib().mole_oracle_lookup_forward(
+        _p(table), _code(table), _p(ids), _p(h), _p(W_r), _p(shared), _p(residual), act,
+        ctypes.c_int64(T), ctypes.c_int64(V), d, N, _p(out), _p(g), _p(rows), ctypes.byref(err))
+    if rc:
+        raise RuntimeError(f"mole_oracle_lookup_forward rc={rc}")
+    return out, g, rows, int(err.value)
+
+
+def dedup(ids: np.ndarray, V: int) -> Tuple[np.ndarray, np.ndarray, int, int]:
+    """Canonical dedup map.  Returns (uniq [U] ascending, inv [T], U, err)."""
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    T = int(ids.shape[0])
+    uniq = np.empty((max(T, 1),), dtype=np.int32)
+    inv = np.empty((max(T, 1),), dtype=np.int32)
+    U = ctypes.c_int32(0)
+    err = ctypes.c_int32(0)
+    rc = lib().mole_oracle_dedup(_p(ids), ctypes.c_int64(T), ctypes.c_int64(V),
+                                 _p(uniq), _p(inv), ctypes.byref(U), ctypes.byref(err))
+    if rc:
+        raise RuntimeError(f"mole_oracle_dedup rc={rc}")
+    return uniq[:U.value].copy(), inv[:T].copy(), int(U.value), int(err.value)
+
+
+def build_lut(E: np.ndarray, W1: np.ndarray, W2: np.ndarray,
+              b1: Optional[np.ndarray] = None, b2: Optional[np.ndarray] = None,
+              norm_w: Optional[np.ndarray] = None, norm_eps: float = 1e-5,
+              act: int = GELU_ERF, rows: Optional[np.ndarray] = None) -> np.ndarray:
+    """LUT entry equation for the vocabulary rows in `rows` (all rows when None).
+    E [V,d], W1 [N,d,D], W2 [N,D,d] -> [n_rows, N, d] fp64."""
+    V, d = E.shape
+    N, d2, D = W1.shape
+    assert d2 == d and W2.shape == (N, D, d)
+    arrs = [np.ascontiguousarray(a) if a is not None else None for a in (E, W1, b1, W2, b2, norm_w)]
+    E, W1, b1, W2, b2, norm_w = arrs
+    dt = _same(*arrs)
+    if rows is not None:
+        rows = np.ascontiguousarray(rows, dtype=np.int32)
+        n_rows = int(rows.shape[0])
+    else:
+        n_rows = V
+    out = np.empty((n_rows, N, d), dtype=np.float64)
+    rc = lib().mole_oracle_build_lut(
+        _p(E), _p(W1), _p(b1), _p(W2), _p(b2), _p(norm_w), ctypes.c_double(norm_eps), dt,
+        ctypes.c_int64(V), d, D, N, int(act), _p(rows), ctypes.c_int64(n_rows), _p(out))
+    if rc:
+        raise RuntimeError(f"mole_oracle_build_lut rc={rc}")
+    return out

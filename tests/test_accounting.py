@@ -1,0 +1,54 @@
+"""The accounting helpers against the size figures the paper prints (tests/golden/paper_sizes.txt)."""
+import os
+
+import pytest
+
+from paper_2503_15798_amd import accounting as acc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "paper_sizes.txt")
+
+
+def _rows():
+    out = []
+    with open(GOLDEN) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if not line:
+                continue
+            kind, d, N, L, V, val, tol = line.split()
+            out.append((kind, int(d), int(N), int(L), int(V), float(val), float(tol)))
+    return out
+
+
+@pytest.mark.parametrize("kind,d,N,L,V,val,tol", _rows())
+def test_printed_sizes(kind, d, N, L, V, val, tol):
+    if kind == "loaded_per_token":
+        got = acc.params_loaded_per_token(d, N, L)
+    elif kind == "offloaded":
+        got = acc.params_offloaded(d, N, V, L)
+    elif kind == "lut_bytes":
+        got = acc.lut_bytes(d, N, V, L, elem_bytes=2)
+    elif kind == "bytes_per_token":
+        got = acc.lut_bytes_loaded_per_token(d, N, L, elem_bytes=2)
+    elif kind == "inconsistent_loaded_per_token":
+        # the printed figure is twice the paper's own formula; documented, not a pin
+        got = acc.params_loaded_per_token(d, N, L)
+        assert abs(val / got - 2.0) < 0.02
+        assert abs(acc.params_offloaded(d, N, V, L) / V - got) == 0
+        return
+    else:
+        raise AssertionError(kind)
+    assert abs(got - val) <= tol * val + 0.5, (kind, got, val)
+
+
+def test_forward_bytes_per_token():
+    # 2Nd rows + h + shared + out (2d each) + 4-byte id
+    assert acc.forward_bytes_per_token(1024, 16) == 38916
+    assert acc.forward_bytes_per_token(768, 16) == 29188
+    assert acc.forward_bytes_per_token(1024, 32) == 71684
+    assert acc.forward_bytes_per_token(64, 4, elem_bytes=4) == 4 * 4 * 64 + 3 * 4 * 64 + 4
+    assert acc.forward_bytes_per_token(1024, 16, residual=True) == 38916 + 2048
+    # rows dominate: 84 % at N=16
+    assert 0.84 < 2 * 16 * 1024 / acc.forward_bytes_per_token(1024, 16) < 0.85
+    assert acc.forward_bytes_moved(T=256, U=256, d=1024, N=16) == 256 * 38916 + 2 * 1024 * 16
+    assert acc.build_flops(50304, 1024, 4096, 16) == 4 * 50304 * 1024 * 4096 * 16
