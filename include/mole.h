@@ -1,0 +1,157 @@
+/*
+ * libmole -- the inference hot path of Mixture of Lookup Experts (MoLE, arXiv 2503.15798)
+ * for AMD MI355X (gfx950).  Plain C ABI: raw pointers and sizes, no framework types.
+ *
+ * The layer (paper Sec. 3.3, inference-layer equation, with the router of Sec. 3.2):
+ *
+ *     g      = SoftMax_j( h . r_j ),  j = 1..N            all N experts active, no top-k
+ *     h'     = sum_j g_j * LUT[id, j, :] + FFN_shared(h) + residual
+ *     LUT[i, j, :] = FFN_j(Embedding(i))                  built once, offline (LUT entry equation)
+ *
+ * Conventions for every call
+ *   - "dev" pointers are device memory (or host memory the GPU can address: pinned + mapped);
+ *     "host" pointers are ordinary host memory.  The caller owns every buffer and the stream.
+ *   - All calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = default
+ *     stream) and return without synchronising.  The library allocates nothing, keeps no
+ *     global state besides a thread-local error string, and never frees caller memory.
+ *   - Tensors are dense, row-major, in the element type named by `mole_dtype`
+ *     (MOLE_BF16: bfloat16 storage, fp32 arithmetic, one round-to-nearest-even at the store;
+ *      MOLE_F32: fp32 throughout).  Token ids, slots and maps are int32.
+ *   - Tensor pointers must be 16-byte aligned; d must be a multiple of 8 (bf16) / 4 (fp32);
+ *     1 <= N <= 64.
+ *   - Errors that the host can see (null required pointer, bad size, misalignment, workspace
+ *     too small, unsupported shape) return a status WITHOUT launching anything and set the
+ *     message returned by mole_last_error().  Errors only the device can see (a token id
+ *     outside [0, V)) cannot be returned synchronously: the token's routed term is taken as
+ *     zero and *err_flag is set to 1 (the caller zeroes err_flag beforehand and reads it after
+ *     synchronising).  T == 0 is MOLE_OK and launches nothing.
+ */
+#ifndef MOLE_H
+#define MOLE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MOLE_OK = 0,
+    MOLE_EINVAL = 1,        /* bad argument (null, negative, misaligned, inconsistent)      */
+    MOLE_EUNSUPPORTED = 2,  /* shape or dtype outside what the kernels are built for       */
+    MOLE_EWORKSPACE = 3,    /* workspace missing or smaller than mole_*_workspace() says  */
+    MOLE_EHIP = 4           /* a HIP runtime call failed (message holds hipGetErrorString) */
+} mole_status;
+
+typedef enum { MOLE_F32 = 0, MOLE_BF16 = 1 } mole_dtype;
+typedef enum { MOLE_GELU_ERF = 0, MOLE_GELU_TANH = 1 } mole_act;
+
+enum {
+    MOLE_FLAG_DEDUP = 1u    /* forward: `workspace` holds a plan written by mole_dedup_ids for
+                               these ids; each distinct id's rows are read once per group      */
+};
+
+/* Message of the last failing call on this thread ("" if none).  Never NULL. */
+const char *mole_last_error(void);
+
+/* ABI version, currently 1. */
+int mole_version(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Re-parameterization (Sec. 3.3, LUT entry equation):
+ *     LUT[v, j, :] = GELU(x_v . W1_j + b1_j) . W2_j + b2_j,   x_v = E[v]
+ * The expert is a two-matrix, non-gated FFN (the 4dD flop / 2dD parameter counts of Sec. 3.4).
+ * With norm_w != NULL, x_v = E[v] / sqrt(mean(E[v]^2) + norm_eps) * norm_w first (the RMSNorm
+ * the training listing applies to embedding states).
+ *   E [V,d] dev, W1 [N,d,D] dev, b1 [N,D] dev nullable, W2 [N,D,d] dev, b2 [N,d] dev nullable,
+ *   norm_w [d] dev nullable, LUT [V,N,d] dev out.  d and D multiples of 16.
+ * bf16: both GEMMs run on bf16 MFMA with fp32 accumulation; the hidden activation is carried
+ * as a bf16 high/low pair so that its rounding does not show in the result.
+ * workspace: dev, at least mole_build_lut_workspace() bytes (holds the hidden activations of a
+ * slab of vocabulary rows).  Returns MOLE_EWORKSPACE if it is smaller.
+ * ---------------------------------------------------------------------------------------- */
+size_t mole_build_lut_workspace(int64_t V, int d, int D, int N, mole_dtype dtype);
+mole_status mole_build_lut(const void *E, const void *W1, const void *b1,
+                           const void *W2, const void *b2,
+                           const void *norm_w, float norm_eps,
+                           void *LUT,
+                           int64_t V, int d, int D, int N, mole_dtype dtype, mole_act act,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Token-id dedup (an optimisation of the lookup of the inference listing; not in the paper):
+ *     uniq  = the distinct in-range ids, ascending        [T] dev out, first *n_uniq valid
+ *     inv[t] = index of ids[t] in uniq, -1 if out of range [T] dev out
+ *     *n_uniq = U                                          [1] dev out
+ * and, in `workspace`, a grouping plan for mole_lookup_forward(MOLE_FLAG_DEDUP): the tokens of
+ * each distinct id, cut into bounded groups.  One workgroup, presence bitmap in LDS.
+ * V <= 524288.  err_flag: [1] dev nullable, set to 1 if any id is outside [0, V).
+ * workspace: dev, at least mole_dedup_workspace(T, V) bytes.
+ * ---------------------------------------------------------------------------------------- */
+size_t mole_dedup_workspace(int T, int64_t V);
+mole_status mole_dedup_ids(const int32_t *ids, int T, int64_t V,
+                           int32_t *uniq, int32_t *inv, int32_t *n_uniq, int32_t *err_flag,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Fused MoLE layer forward (Sec. 3.2 router equation + Sec. 3.3 inference-layer equation):
+ *     z[t,j]  = sum_k h[t,k] * W_r[k,j]
+ *     g[t,:]  = softmax(z[t,:])
+ *     out[t,:] = sum_j g[t,j] * table[row(t), j, :] + shared_out[t,:] + residual[t,:]
+ *     row(t)  = slot ? slot[t] : ids[t]
+ *   table [rows,N,d] dev: the resident LUT (rows = V) or a staging buffer of fetched rows
+ *         (rows = U_cap, slot = inv of mole_dedup_ids); may be pinned host memory
+ *   ids [T] dev; slot [T] dev nullable; h [T,d] dev: router input (the post-attention-normed
+ *   state); W_r [d,N] dev (transpose of an nn.Linear(d,N) weight); shared_out [T,d] dev
+ *   nullable (= 0); residual [T,d] dev nullable (= 0); out [T,d] dev.
+ *   gates_dbg [T,N] fp32 dev nullable: the gates; rows_dbg [T] int64 dev nullable: row(t), or -1
+ *   if it was outside [0, rows).  err_flag [1] dev nullable.
+ *   flags: MOLE_FLAG_DEDUP -> workspace = plan of mole_dedup_ids(ids, T, ...) (and, if slot is
+ *   given, slot must be that call's inv).  Without the flag workspace may be NULL.
+ * ---------------------------------------------------------------------------------------- */
+mole_status mole_lookup_forward(const void *table, const int32_t *ids, const int32_t *slot,
+                                const void *h, const void *W_r,
+                                const void *shared_out, const void *residual,
+                                void *out, float *gates_dbg, int64_t *rows_dbg, int32_t *err_flag,
+                                int T, int64_t rows, int d, int N, mole_dtype dtype,
+                                unsigned flags,
+                                const void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* The same forward for L layers that share one id batch, in ONE launch: layer l uses
+ * table + l*table_stride, h + l*act_stride, W_r + l*d*N, shared_out/residual/out + l*act_stride
+ * (strides in ELEMENTS; act_stride >= T*d, table_stride >= rows*N*d).  Layers are independent
+ * here (each has its own h), which is what a decode-throughput measurement over a stack of
+ * MoLE layers needs; a real decoder calls the single-layer entry once per layer.
+ * gates_dbg [L,T,N], rows_dbg [T]. */
+mole_status mole_lookup_forward_layers(const void *table, int64_t table_stride,
+                                       const int32_t *ids, const int32_t *slot,
+                                       const void *h, const void *W_r,
+                                       const void *shared_out, const void *residual,
+                                       void *out, int64_t act_stride,
+                                       float *gates_dbg, int64_t *rows_dbg, int32_t *err_flag,
+                                       int L, int T, int64_t rows, int d, int N, mole_dtype dtype,
+                                       unsigned flags,
+                                       const void *workspace, size_t workspace_bytes,
+                                       void *hip_stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Offloaded-LUT row fetch (Sec. 3.3: the LUT lives off-chip, only looked-up rows are moved;
+ * the lookup line of the inference listing):
+ *     staging[l, u, :, :] = host_table[l, uniq[u], :, :]     u < *n_uniq, l < L
+ *   host_table: pinned, GPU-addressable host memory [L, V, N, d] (layer stride in elements)
+ *   uniq [>= *n_uniq] dev, n_uniq [1] dev: from mole_dedup_ids.  staging [L, U_cap, N, d] dev.
+ *   Rows u >= U_cap are not copied and set *err_flag.  The copy is done by a kernel reading
+ *   host memory with 16-byte loads (no per-row DMA descriptors).
+ * ---------------------------------------------------------------------------------------- */
+mole_status mole_offload_fetch(const void *host_table, int64_t host_layer_stride,
+                               const int32_t *uniq, const int32_t *n_uniq,
+                               void *staging, int64_t staging_layer_stride,
+                               int32_t *err_flag,
+                               int L, int U_cap, int64_t V, int d, int N, mole_dtype dtype,
+                               void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOLE_H */

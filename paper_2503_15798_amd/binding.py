@@ -1,0 +1,159 @@
+"""ctypes binding of libmole.so: one Python function per C entry point, same names.
+
+Argument marshalling only -- every step of the path runs in the library's HIP kernels.
+Tensor arguments are torch tensors living on the GPU (or pinned host tensors where the
+header allows host memory); their data pointers are passed through unchanged.  There is
+no CPU fallback: if the library is missing, or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmole.so")
+
+MOLE_OK, MOLE_EINVAL, MOLE_EUNSUPPORTED, MOLE_EWORKSPACE, MOLE_EHIP = range(5)
+MOLE_F32, MOLE_BF16 = 0, 1
+MOLE_GELU_ERF, MOLE_GELU_TANH = 0, 1
+MOLE_FLAG_DEDUP = 1
+
+_STATUS_NAMES = {0: "MOLE_OK", 1: "MOLE_EINVAL", 2: "MOLE_EUNSUPPORTED", 3: "MOLE_EWORKSPACE", 4: "MOLE_EHIP"}
+
+# every symbol include/mole.h declares
+EXPORTS = ("mole_last_error", "mole_version", "mole_build_lut_workspace", "mole_build_lut",
+           "mole_dedup_workspace", "mole_dedup_ids", "mole_lookup_forward",
+           "mole_lookup_forward_layers", "mole_offload_fetch")
+
+
+class MoleError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{_STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+        self.message = message
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libmole.so (built in-tree by paper_2503_15798_amd.build); raise if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} not found: build it with `python -m paper_2503_15798_amd.build` "
+                          "(there is no fallback path)")
+    L = ctypes.CDLL(LIB_PATH)
+    c_void, c_i32, c_i64, c_sz, c_f, c_u = (ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t,
+                                            ctypes.c_float, ctypes.c_uint)
+    L.mole_last_error.restype = ctypes.c_char_p
+    L.mole_last_error.argtypes = []
+    L.mole_version.restype = c_i32
+    L.mole_version.argtypes = []
+    L.mole_build_lut_workspace.restype = c_sz
+    L.mole_build_lut_workspace.argtypes = [c_i64, c_i32, c_i32, c_i32, c_i32]
+    L.mole_build_lut.restype = c_i32
+    L.mole_build_lut.argtypes = [c_void] * 6 + [c_f, c_void, c_i64, c_i32, c_i32, c_i32, c_i32, c_i32,
+                                                c_void, c_sz, c_void]
+    L.mole_dedup_workspace.restype = c_sz
+    L.mole_dedup_workspace.argtypes = [c_i32, c_i64]
+    L.mole_dedup_ids.restype = c_i32
+    L.mole_dedup_ids.argtypes = [c_void, c_i32, c_i64, c_void, c_void, c_void, c_void, c_void, c_sz, c_void]
+    L.mole_lookup_forward.restype = c_i32
+    L.mole_lookup_forward.argtypes = [c_void] * 11 + [c_i32, c_i64, c_i32, c_i32, c_i32, c_u, c_void, c_sz, c_void]
+    L.mole_lookup_forward_layers.restype = c_i32
+    L.mole_lookup_forward_layers.argtypes = ([c_void, c_i64] + [c_void] * 7 + [c_i64] + [c_void] * 3 +
+                                             [c_i32, c_i32, c_i64, c_i32, c_i32, c_i32, c_u, c_void, c_sz, c_void])
+    L.mole_offload_fetch.restype = c_i32
+    L.mole_offload_fetch.argtypes = [c_void, c_i64, c_void, c_void, c_void, c_i64, c_void,
+                                     c_i32, c_i32, c_i64, c_i32, c_i32, c_i32, c_void]
+    _lib = L
+    return L
+
+
+def _ptr(t) -> Optional[int]:
+    """Raw address of a tensor's storage (None stays NULL).  Integers pass through."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_contiguous():
+        raise ValueError("libmole takes dense row-major tensors")
+    return t.data_ptr()
+
+
+def _nbytes(t) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _check(status: int) -> None:
+    if status != MOLE_OK:
+        raise MoleError(status, lib().mole_last_error().decode())
+
+
+def mole_last_error() -> str:
+    return lib().mole_last_error().decode()
+
+
+def mole_version() -> int:
+    return lib().mole_version()
+
+
+def mole_build_lut_workspace(V: int, d: int, D: int, N: int, dtype: int) -> int:
+    return lib().mole_build_lut_workspace(V, d, D, N, dtype)
+
+
+def mole_build_lut(E, W1, b1, W2, b2, norm_w, norm_eps: float, LUT, V: int, d: int, D: int, N: int,
+                   dtype: int, act: int, workspace, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().mole_build_lut(_ptr(E), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), _ptr(norm_w), norm_eps,
+                                _ptr(LUT), V, d, D, N, dtype, act, _ptr(workspace), wb, _stream(stream)))
+
+
+def mole_dedup_workspace(T: int, V: int) -> int:
+    return lib().mole_dedup_workspace(T, V)
+
+
+def mole_dedup_ids(ids, T: int, V: int, uniq, inv, n_uniq, err_flag, workspace, stream=None,
+                   workspace_bytes: Optional[int] = None) -> None:
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().mole_dedup_ids(_ptr(ids), T, V, _ptr(uniq), _ptr(inv), _ptr(n_uniq), _ptr(err_flag),
+                                _ptr(workspace), wb, _stream(stream)))
+
+
+def mole_lookup_forward(table, ids, slot, h, W_r, shared_out, residual, out, gates_dbg, rows_dbg, err_flag,
+                        T: int, rows: int, d: int, N: int, dtype: int, flags: int = 0, workspace=None,
+                        stream=None, workspace_bytes: Optional[int] = None) -> None:
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().mole_lookup_forward(_ptr(table), _ptr(ids), _ptr(slot), _ptr(h), _ptr(W_r), _ptr(shared_out),
+                                     _ptr(residual), _ptr(out), _ptr(gates_dbg), _ptr(rows_dbg), _ptr(err_flag),
+                                     T, rows, d, N, dtype, flags, _ptr(workspace), wb, _stream(stream)))
+
+
+def mole_lookup_forward_layers(table, table_stride: int, ids, slot, h, W_r, shared_out, residual, out,
+                               act_stride: int, gates_dbg, rows_dbg, err_flag, L: int, T: int, rows: int,
+                               d: int, N: int, dtype: int, flags: int = 0, workspace=None, stream=None,
+                               workspace_bytes: Optional[int] = None) -> None:
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().mole_lookup_forward_layers(_ptr(table), table_stride, _ptr(ids), _ptr(slot), _ptr(h), _ptr(W_r),
+                                            _ptr(shared_out), _ptr(residual), _ptr(out), act_stride,
+                                            _ptr(gates_dbg), _ptr(rows_dbg), _ptr(err_flag), L, T, rows, d, N,
+                                            dtype, flags, _ptr(workspace), wb, _stream(stream)))
+
+
+def mole_offload_fetch(host_table, host_layer_stride: int, uniq, n_uniq, staging, staging_layer_stride: int,
+                       err_flag, L: int, U_cap: int, V: int, d: int, N: int, dtype: int, stream=None) -> None:
+    _check(lib().mole_offload_fetch(_ptr(host_table), host_layer_stride, _ptr(uniq), _ptr(n_uniq), _ptr(staging),
+                                    staging_layer_stride, _ptr(err_flag), L, U_cap, V, d, N, dtype,
+                                    _stream(stream)))

@@ -1,0 +1,439 @@
+// mole_build_lut: the re-parameterization LUT[v, j, :] = FFN_j(Embedding(v)).
+//
+// Paper: Sec. 3.3, LUT entry equation ("a single forward pass with the embedding layer's
+// weights as the input"), with the expert taken as a two-matrix FFN (Sec. 3.4: 4dD flops,
+// 2dD parameters) and GELU; optionally the RMSNorm the training listing applies to the
+// embedding states first.
+//
+// This is the one dense contraction of the library (4*V*d*D*N flop, 1.35e13 for one 410M
+// layer), so it runs on the matrix cores: v_mfma_f32_32x32x16_bf16, fp32 accumulation.
+//   GEMM 1:  A = E[v, :]           B = W1_j     epilogue: + b1, GELU, split into a bf16
+//                                                high part and a bf16 low part (two planes)
+//   GEMM 2:  A = [hi | lo] of GEMM1 B = W2_j     epilogue: + b2, round to bf16, stored
+//                                                straight into LUT[v, j, :] (row stride N*d)
+// Carrying the hidden activation as hi + lo makes its rounding error ~2^-17 instead of 2^-9,
+// so the only visible rounding is the final one; it costs a second pass over K in GEMM 2.
+// Both weight matrices are first transposed into K-contiguous form so that A and B tiles are
+// fetched the same way (16-byte pieces along K) and match the MFMA operand layout directly.
+//
+// Tile: 256 x 128 per workgroup of 4 waves (2 x 2), each wave 128 x 64 = 4 x 2 MFMA tiles,
+// K step 64 through LDS with 16 bytes of row padding (conflict-free 16-byte reads), next
+// K tile prefetched into registers while the current one is multiplied.
+#include "mole_internal.h"
+
+namespace {
+using namespace mole;
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int BM = 256, BN = 128, BK = 64;
+constexpr int LDS_ROW = BK * 2 + 16;   // bytes per tile row in LDS
+constexpr int GEMM_THREADS = 256;
+
+enum { EPI_STORE = 0, EPI_GELU_SPLIT = 1 };
+
+struct GemmArgs {
+    const uint16_t *A;       // [planes][M, K] row-major, K contiguous
+    int64_t lda, a_plane_stride, a_batch_stride;
+    int a_planes;
+    const uint16_t *Bt;      // [Nn, K] row-major (the transposed weight)
+    int64_t ldb, b_batch_stride;
+    const uint16_t *bias;    // [Nn] nullable
+    int64_t bias_batch_stride;
+    uint16_t *C;             // EPI_STORE: [M, ldc]; EPI_GELU_SPLIT: planes hi, lo
+    int64_t ldc, c_plane_stride, c_batch_stride;
+    int M, Nn, K;
+    int epilogue, act;
+};
+
+__device__ __forceinline__ float gelu_f(float x, int act)
+{
+    if (act == MOLE_GELU_TANH) {
+        const float k = 0.7978845608028654f;
+        return 0.5f * x * (1.0f + tanhf(k * (x + 0.044715f * x * x * x)));
+    }
+    return 0.5f * x * (1.0f + erff(x * 0.7071067811865476f));
+}
+
+__device__ __forceinline__ void gemm_fetch(uint4 (&ra)[8], uint4 (&rb)[4], const GemmArgs &g, const uint16_t *A,
+                                           const uint16_t *Bt, int kt, int ktiles_per_plane, int m0, int n0,
+                                           int prow, int pk)
+{
+    const int plane = kt / ktiles_per_plane;
+    const int kk = (kt - plane * ktiles_per_plane) * BK + pk * 8;
+    const uint16_t *Ap = A + plane * g.a_plane_stride;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int row = m0 + prow + i * 32;
+        ra[i] = row < g.M ? *reinterpret_cast<const uint4 *>(Ap + (int64_t)row * g.lda + kk)
+                          : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = n0 + prow + i * 32;
+        rb[i] = *reinterpret_cast<const uint4 *>(Bt + (int64_t)row * g.ldb + kk);
+    }
+}
+
+__device__ __forceinline__ void gemm_stash(const uint4 (&ra)[8], const uint4 (&rb)[4], unsigned char *As,
+                                           unsigned char *Bs, int prow, int pk)
+{
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        *reinterpret_cast<uint4 *>(As + (prow + i * 32) * LDS_ROW + pk * 16) = ra[i];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        *reinterpret_cast<uint4 *>(Bs + (prow + i * 32) * LDS_ROW + pk * 16) = rb[i];
+}
+
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_bf16_kernel(GemmArgs g)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char As[BM * LDS_ROW];
+    __shared__ __attribute__((aligned(16))) unsigned char Bs[BN * LDS_ROW];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    const int batch = blockIdx.z;
+    const uint16_t *A = g.A + batch * g.a_batch_stride;
+    const uint16_t *Bt = g.Bt + batch * g.b_batch_stride;
+
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                acc[i][j][e] = 0.f;
+
+    // staging registers: A tile = 256 rows x 8 pieces -> 8 per thread; B tile = 128 x 8 -> 4
+    uint4 ra[8], rb[4];
+    const int prow = tid >> 3, pk = tid & 7;   // piece (row, 16-byte column) for i = 0; +32 rows per i
+    const int ktiles_per_plane = g.K / BK;
+    const int ktiles = ktiles_per_plane * g.a_planes;
+
+    gemm_fetch(ra, rb, g, A, Bt, 0, ktiles_per_plane, m0, n0, prow, pk);
+    const int frow = lane & 31, fk = (lane >> 5) * 16;   // fragment row and byte offset of its K run
+    for (int kt = 0; kt < ktiles; ++kt) {
+        gemm_stash(ra, rb, As, Bs, prow, pk);
+        __syncthreads();
+        if (kt + 1 < ktiles)
+            gemm_fetch(ra, rb, g, A, Bt, kt + 1, ktiles_per_plane, m0, n0, prow, pk);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 af[4], bfr[2];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                af[i] = *reinterpret_cast<const bf16x8 *>(As + (wm * 128 + i * 32 + frow) * LDS_ROW + ks * 32 + fk);
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                bfr[j] = *reinterpret_cast<const bf16x8 *>(Bs + (wn * 64 + j * 32 + frow) * LDS_ROW + ks * 32 + fk);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    // epilogue.  Accumulator element e of lane l: column l % 32, row 8*(e/4) + 4*(l/32) + e%4.
+    const uint16_t *bias = g.bias ? g.bias + batch * g.bias_batch_stride : nullptr;
+    uint16_t *C = g.C + batch * g.c_batch_stride;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int col = n0 + wn * 64 + j * 32 + (lane & 31);
+        const float bv = bias ? bf16_to_f32(bias[col]) : 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = m0 + wm * 128 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                if (row >= g.M)
+                    continue;
+                float v = acc[i][j][e] + bv;
+                if (g.epilogue == EPI_GELU_SPLIT) {
+                    v = gelu_f(v, g.act);
+                    const uint32_t hi = f32_to_bf16_bits(v);
+                    const uint32_t lo = f32_to_bf16_bits(v - __uint_as_float(hi << 16));
+                    C[(int64_t)row * g.ldc + col] = (uint16_t)hi;
+                    C[g.c_plane_stride + (int64_t)row * g.ldc + col] = (uint16_t)lo;
+                } else {
+                    C[(int64_t)row * g.ldc + col] = (uint16_t)f32_to_bf16_bits(v);
+                }
+            }
+        }
+    }
+}
+
+// dst[b][c][r] = src[b][r][c]   (bf16, 32 x 32 tiles through LDS)
+__global__ __launch_bounds__(256) void transpose_kernel(const uint16_t *__restrict__ src,
+                                                         uint16_t *__restrict__ dst, int R, int Cn)
+{
+    __shared__ uint16_t tile[32][33];
+    const int64_t base = (int64_t)blockIdx.z * R * Cn;
+    const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+    for (int i = ty; i < 32; i += 8)
+        if (r0 + i < R && c0 + tx < Cn)
+            tile[i][tx] = src[base + (int64_t)(r0 + i) * Cn + c0 + tx];
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8)
+        if (c0 + i < Cn && r0 + tx < R)
+            dst[base + (int64_t)(c0 + i) * R + r0 + tx] = tile[tx][i];
+}
+
+// RMSNorm of the embedding rows, written as a bf16 hi plane and a bf16 lo plane.  One wave per row.
+__global__ __launch_bounds__(256) void rmsnorm_split_kernel(const uint16_t *__restrict__ E,
+                                                             const uint16_t *__restrict__ w, float eps,
+                                                             uint16_t *__restrict__ hi, uint16_t *__restrict__ lo,
+                                                             int64_t V, int d)
+{
+    const int64_t v = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (v >= V)
+        return;
+    float ss = 0.f;
+    for (int k = lane; k < d; k += 64) {
+        const float x = bf16_to_f32(E[v * d + k]);
+        ss = fmaf(x, x, ss);
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1)
+        ss += __shfl_xor(ss, o);
+    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+    for (int k = lane; k < d; k += 64) {
+        const float y = bf16_to_f32(E[v * d + k]) * inv * bf16_to_f32(w[k]);
+        const uint32_t h = f32_to_bf16_bits(y);
+        hi[v * d + k] = (uint16_t)h;
+        lo[v * d + k] = (uint16_t)f32_to_bf16_bits(y - __uint_as_float(h << 16));
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Plain path (fp32 storage, or bf16 shapes the MFMA tiles do not cover): fp32 arithmetic,
+// one thread per output element, hidden activations kept in fp32.
+// ------------------------------------------------------------------------------------------
+template <typename E> __device__ __forceinline__ float ldv(const E *p);
+template <> __device__ __forceinline__ float ldv<float>(const float *p) { return *p; }
+template <> __device__ __forceinline__ float ldv<uint16_t>(const uint16_t *p) { return bf16_to_f32(*p); }
+__device__ __forceinline__ void stv(float *p, float v) { *p = v; }
+__device__ __forceinline__ void stv(uint16_t *p, float v) { *p = (uint16_t)f32_to_bf16_bits(v); }
+
+template <typename E>
+__global__ __launch_bounds__(256) void plain_norm_kernel(const E *__restrict__ Em, const E *__restrict__ w, float eps,
+                                                          float *__restrict__ X, int64_t V, int d)
+{
+    const int64_t v = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (v >= V)
+        return;
+    float ss = 0.f;
+    for (int k = lane; k < d; k += 64) {
+        const float x = ldv(Em + v * d + k);
+        ss = fmaf(x, x, ss);
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1)
+        ss += __shfl_xor(ss, o);
+    const float inv = w ? 1.0f / sqrtf(ss / (float)d + eps) : 1.0f;
+    for (int k = lane; k < d; k += 64)
+        X[v * d + k] = ldv(Em + v * d + k) * inv * (w ? ldv(w + k) : 1.0f);
+}
+
+// H[v - v0, j, m] = GELU(sum_k X[v,k] W1[j,k,m] + b1[j,m]) for v in [v0, v0 + nv)
+template <typename E>
+__global__ __launch_bounds__(256) void plain_hidden_kernel(const float *__restrict__ X, const E *__restrict__ W1,
+                                                            const E *__restrict__ b1, float *__restrict__ H,
+                                                            int64_t v0, int nv, int d, int D, int N, int act)
+{
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t total = (int64_t)nv * N * D;
+    if (idx >= total)
+        return;
+    const int m = (int)(idx % D);
+    const int j = (int)((idx / D) % N);
+    const int64_t v = v0 + idx / ((int64_t)D * N);
+    float s = 0.f;
+    for (int k = 0; k < d; ++k)
+        s = fmaf(X[v * d + k], ldv(W1 + ((int64_t)j * d + k) * D + m), s);
+    if (b1)
+        s += ldv(b1 + (int64_t)j * D + m);
+    H[idx] = gelu_f(s, act);
+}
+
+template <typename E>
+__global__ __launch_bounds__(256) void plain_out_kernel(const float *__restrict__ H, const E *__restrict__ W2,
+                                                         const E *__restrict__ b2, E *__restrict__ LUT,
+                                                         int64_t v0, int nv, int d, int D, int N)
+{
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t total = (int64_t)nv * N * d;
+    if (idx >= total)
+        return;
+    const int c = (int)(idx % d);
+    const int j = (int)((idx / d) % N);
+    const int64_t vl = idx / ((int64_t)d * N);
+    const float *h = H + (vl * N + j) * D;
+    float s = 0.f;
+    for (int m = 0; m < D; ++m)
+        s = fmaf(h[m], ldv(W2 + ((int64_t)j * D + m) * d + c), s);
+    if (b2)
+        s += ldv(b2 + (int64_t)j * d + c);
+    stv(LUT + ((v0 + vl) * N + j) * d + c, s);
+}
+
+// ---- workspace layout --------------------------------------------------------------------
+constexpr int64_t SLAB_ROWS = 16384;   // vocabulary rows whose hidden activations are resident at once
+
+inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+inline bool mfma_shape(int64_t V, int d, int D, mole_dtype dt)
+{
+    (void)V;
+    return dt == MOLE_BF16 && d % BN == 0 && D % BN == 0 && d % BK == 0 && D % BK == 0;
+}
+
+struct BuildWs {
+    size_t w1t, w2t, xn, hid, total;
+    int64_t slab;
+};
+
+inline BuildWs build_ws(int64_t V, int d, int D, int N, mole_dtype dt)
+{
+    BuildWs w;
+    w.slab = V < SLAB_ROWS ? V : SLAB_ROWS;
+    size_t off = 0;
+    if (mfma_shape(V, d, D, dt)) {
+        w.w1t = off; off += align256((size_t)N * d * D * 2);
+        w.w2t = off; off += align256((size_t)N * d * D * 2);
+        w.xn = off;  off += align256((size_t)2 * V * d * 2);             // hi + lo planes (norm only)
+        w.hid = off; off += align256((size_t)N * 2 * w.slab * D * 2);    // hi + lo planes per expert
+    } else {
+        w.w1t = w.w2t = 0;
+        w.xn = off;  off += align256((size_t)V * d * 4);
+        w.hid = off; off += align256((size_t)w.slab * N * D * 4);
+    }
+    w.total = off;
+    return w;
+}
+
+template <typename E>
+mole_status build_plain(const void *Em, const void *W1, const void *b1, const void *W2, const void *b2,
+                        const void *norm_w, float eps, void *LUT, int64_t V, int d, int D, int N, int act,
+                        char *ws, const BuildWs &lay, hipStream_t st)
+{
+    float *X = reinterpret_cast<float *>(ws + lay.xn);
+    float *H = reinterpret_cast<float *>(ws + lay.hid);
+    hipLaunchKernelGGL(plain_norm_kernel<E>, dim3((unsigned)((V + 3) / 4)), dim3(256), 0, st,
+                       static_cast<const E *>(Em), static_cast<const E *>(norm_w), eps, X, V, d);
+    for (int64_t v0 = 0; v0 < V; v0 += lay.slab) {
+        const int nv = (int)((V - v0) < lay.slab ? (V - v0) : lay.slab);
+        const int64_t th = (int64_t)nv * N * D, to = (int64_t)nv * N * d;
+        hipLaunchKernelGGL(plain_hidden_kernel<E>, dim3((unsigned)((th + 255) / 256)), dim3(256), 0, st, X,
+                           static_cast<const E *>(W1), static_cast<const E *>(b1), H, v0, nv, d, D, N, act);
+        hipLaunchKernelGGL(plain_out_kernel<E>, dim3((unsigned)((to + 255) / 256)), dim3(256), 0, st, H,
+                           static_cast<const E *>(W2), static_cast<const E *>(b2), static_cast<E *>(LUT), v0, nv,
+                           d, D, N);
+    }
+    MOLE_HIP_CHECK(hipGetLastError());
+    return MOLE_OK;
+}
+
+mole_status build_mfma(const void *Em, const void *W1, const void *b1, const void *W2, const void *b2,
+                       const void *norm_w, float eps, void *LUT, int64_t V, int d, int D, int N, int act,
+                       char *ws, const BuildWs &lay, hipStream_t st)
+{
+    uint16_t *w1t = reinterpret_cast<uint16_t *>(ws + lay.w1t);   // [N, D, d]
+    uint16_t *w2t = reinterpret_cast<uint16_t *>(ws + lay.w2t);   // [N, d, D]
+    uint16_t *xn = reinterpret_cast<uint16_t *>(ws + lay.xn);
+    uint16_t *hid = reinterpret_cast<uint16_t *>(ws + lay.hid);   // [N][2][slab, D]
+    hipLaunchKernelGGL(transpose_kernel, dim3(D / 32, d / 32, N), dim3(256), 0, st,
+                       static_cast<const uint16_t *>(W1), w1t, d, D);
+    hipLaunchKernelGGL(transpose_kernel, dim3(d / 32, D / 32, N), dim3(256), 0, st,
+                       static_cast<const uint16_t *>(W2), w2t, D, d);
+    const uint16_t *X = static_cast<const uint16_t *>(Em);
+    int x_planes = 1;
+    if (norm_w) {
+        hipLaunchKernelGGL(rmsnorm_split_kernel, dim3((unsigned)((V + 3) / 4)), dim3(256), 0, st, X,
+                           static_cast<const uint16_t *>(norm_w), eps, xn, xn + V * d, V, d);
+        X = xn;
+        x_planes = 2;
+    }
+    for (int64_t v0 = 0; v0 < V; v0 += lay.slab) {
+        const int nv = (int)((V - v0) < lay.slab ? (V - v0) : lay.slab);
+        GemmArgs g1;
+        g1.A = X + v0 * d; g1.lda = d; g1.a_plane_stride = V * (int64_t)d; g1.a_batch_stride = 0;
+        g1.a_planes = x_planes;
+        g1.Bt = w1t; g1.ldb = d; g1.b_batch_stride = (int64_t)D * d;
+        g1.bias = static_cast<const uint16_t *>(b1); g1.bias_batch_stride = D;
+        g1.C = hid; g1.ldc = D; g1.c_plane_stride = lay.slab * D; g1.c_batch_stride = 2 * lay.slab * D;
+        g1.M = nv; g1.Nn = D; g1.K = d; g1.epilogue = EPI_GELU_SPLIT; g1.act = act;
+        hipLaunchKernelGGL(gemm_nt_bf16_kernel, dim3((nv + BM - 1) / BM, D / BN, N), dim3(GEMM_THREADS), 0, st, g1);
+        GemmArgs g2;
+        g2.A = hid; g2.lda = D; g2.a_plane_stride = lay.slab * D; g2.a_batch_stride = 2 * lay.slab * D;
+        g2.a_planes = 2;
+        g2.Bt = w2t; g2.ldb = D; g2.b_batch_stride = (int64_t)d * D;
+        g2.bias = static_cast<const uint16_t *>(b2); g2.bias_batch_stride = d;
+        g2.C = static_cast<uint16_t *>(LUT) + v0 * N * d; g2.ldc = (int64_t)N * d; g2.c_plane_stride = 0;
+        g2.c_batch_stride = d;
+        g2.M = nv; g2.Nn = d; g2.K = D; g2.epilogue = EPI_STORE; g2.act = act;
+        hipLaunchKernelGGL(gemm_nt_bf16_kernel, dim3((nv + BM - 1) / BM, d / BN, N), dim3(GEMM_THREADS), 0, st, g2);
+    }
+    MOLE_HIP_CHECK(hipGetLastError());
+    return MOLE_OK;
+}
+
+mole_status check_build_args(int64_t V, int d, int D, int N, mole_dtype dtype)
+{
+    if (dtype != MOLE_F32 && dtype != MOLE_BF16)
+        return fail(MOLE_EINVAL, "mole_build_lut: unknown dtype %d", (int)dtype);
+    if (V < 1 || d < 1 || D < 1)
+        return fail(MOLE_EINVAL, "mole_build_lut: bad size (V=%lld, d=%d, D=%d)", (long long)V, d, D);
+    if (N < 1 || N > 64)
+        return fail(MOLE_EUNSUPPORTED, "mole_build_lut: N=%d outside 1..64", N);
+    if (d % 16 || D % 16)
+        return fail(MOLE_EUNSUPPORTED, "mole_build_lut: d=%d and D=%d must be multiples of 16", d, D);
+    return MOLE_OK;
+}
+
+}  // namespace
+
+extern "C" size_t mole_build_lut_workspace(int64_t V, int d, int D, int N, mole_dtype dtype)
+{
+    if (check_build_args(V, d, D, N, dtype) != MOLE_OK)
+        return 0;
+    return build_ws(V, d, D, N, dtype).total;
+}
+
+extern "C" mole_status mole_build_lut(const void *E, const void *W1, const void *b1, const void *W2,
+                                      const void *b2, const void *norm_w, float norm_eps, void *LUT, int64_t V,
+                                      int d, int D, int N, mole_dtype dtype, mole_act act, void *workspace,
+                                      size_t workspace_bytes, void *hip_stream)
+{
+    clear_error();
+    const mole_status st = check_build_args(V, d, D, N, dtype);
+    if (st != MOLE_OK)
+        return st;
+    if (act != MOLE_GELU_ERF && act != MOLE_GELU_TANH)
+        return fail(MOLE_EINVAL, "mole_build_lut: unknown activation %d", (int)act);
+    if (!E || !W1 || !W2 || !LUT)
+        return fail(MOLE_EINVAL, "mole_build_lut: E, W1, W2 and LUT must not be NULL");
+    const void *ptrs[] = {E, W1, b1, W2, b2, norm_w, LUT, workspace};
+    for (const void *p : ptrs)
+        if (p && !aligned16(p))
+            return fail(MOLE_EINVAL, "mole_build_lut: pointer %p is not 16-byte aligned", p);
+    const BuildWs lay = build_ws(V, d, D, N, dtype);
+    if (!workspace || workspace_bytes < lay.total)
+        return fail(MOLE_EWORKSPACE, "mole_build_lut: workspace of %zu bytes needed, got %zu", lay.total,
+                    workspace ? workspace_bytes : (size_t)0);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    char *ws = static_cast<char *>(workspace);
+    if (mfma_shape(V, d, D, dtype))
+        return build_mfma(E, W1, b1, W2, b2, norm_w, norm_eps, LUT, V, d, D, N, (int)act, ws, lay, stream);
+    if (dtype == MOLE_F32)
+        return build_plain<float>(E, W1, b1, W2, b2, norm_w, norm_eps, LUT, V, d, D, N, (int)act, ws, lay, stream);
+    return build_plain<uint16_t>(E, W1, b1, W2, b2, norm_w, norm_eps, LUT, V, d, D, N, (int)act, ws, lay, stream);
+}

@@ -1,0 +1,572 @@
+// mole_lookup_forward: fused router + softmax + row gather + gate-weighted sum + adds.
+//
+// Paper: Sec. 3.2 (router equation: full softmax over all N experts) and Sec. 3.3
+// (inference-layer equation: h' = sum_j g_j v^id_j + FFN_shared(h) + h).
+//
+// The path is bound by HBM bandwidth (about 1.7 flop per byte), so there is no MFMA here.
+// Work unit = one "item": a block of N table rows (one token id) plus the 1..8 tokens that
+// read it.  One 64-lane wavefront owns an item:
+//   * lane l owns columns [512*c + 8*l, +8) of every row: every table access is a 16-byte
+//     load, a wavefront covers 1 KiB of a row per load, and all N loads of a 512-column chunk
+//     are issued back to back before anything waits on them;
+//   * the router weight lives in LDS for the life of the workgroup, stored as (k, k+1) bf16
+//     pairs so that the lane's 16-byte piece of h meets it without repacking; the N partial
+//     logits of the 64 lanes are folded with a halving butterfly (N/2 + N/4 + ... exchanges
+//     instead of 6 per logit), softmax runs on the folded values, gates go to a per-wave LDS
+//     slot;
+//   * the combine multiplies from registers and adds shared / residual in the epilogue, with
+//     a single round-to-nearest-even to bf16 at the store.
+// Waves never synchronise with each other after the router weight is in LDS.
+#include "mole_internal.h"
+
+namespace {
+using namespace mole;
+
+struct FwdArgs {
+    const void *table;
+    const int32_t *ids;
+    const int32_t *slot;
+    const void *h;
+    const void *W_r;
+    const void *shared;
+    const void *residual;
+    void *out;
+    float *gates_dbg;
+    int64_t *rows_dbg;
+    int32_t *err_flag;
+    const int32_t *plan;
+    int64_t table_stride;   // per layer, elements
+    int64_t act_stride;     // per layer, elements
+    int64_t rows;
+    int T, d, N, L;
+};
+
+struct Item {
+    int64_t row;   // row block index, or -1
+    int begin;     // first token (index into `order` when planned, token index otherwise)
+    int cnt;
+};
+
+// Decode item `item`.  Planned: groups written by mole_dedup_ids; otherwise one token per item.
+__device__ __forceinline__ Item get_item(const FwdArgs &a, int item, int n_uniq)
+{
+    Item it;
+    if (a.plan) {
+        const PlanLayout pl = plan_layout(a.T);
+        const int u = a.plan[pl.item_u + item];
+        it.begin = a.plan[pl.item_begin + item];
+        it.cnt = a.plan[pl.item_cnt + item];
+        it.row = (u >= n_uniq) ? -1 : (a.slot ? (int64_t)u : (int64_t)a.plan[pl.uniq + u]);
+    } else {
+        it.row = a.slot ? a.slot[item] : a.ids[item];
+        it.begin = item;
+        it.cnt = 1;
+    }
+    return it;
+}
+
+__device__ __forceinline__ int item_token(const FwdArgs &a, const Item &it, int i)
+{
+    return a.plan ? a.plan[plan_layout(a.T).order + it.begin + i] : it.begin;
+}
+
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// acc += h[k]*w[k] + h[k+1]*w[k+1] for one packed pair of bf16 operands
+__device__ __forceinline__ float mac2(float acc, uint32_t hp, uint32_t wp)
+{
+#ifdef MOLE_USE_DOT2
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, hp), __builtin_bit_cast(bf16x2, wp), acc, false);
+#else
+    acc = fmaf(bf16lo(hp), bf16lo(wp), acc);
+    return fmaf(bf16hi(hp), bf16hi(wp), acc);
+#endif
+}
+
+// Fold N per-lane partial sums over the 64 lanes.  Each step halves the number of values a
+// lane carries by trading one half with the lane `W` away.  Returns, in every lane, the full
+// sum of value j = lane >> log2(64/N).
+template <int N, int W>
+struct Fold {
+    static __device__ __forceinline__ float run(float *z, int lane)
+    {
+        if constexpr (N == 1) {
+            float v = z[0];
+#pragma unroll
+            for (int w = W; w >= 1; w >>= 1)
+                v += __shfl_xor(v, w);
+            return v;
+        } else {
+            const bool up = (lane & W) != 0;
+#pragma unroll
+            for (int i = 0; i < N / 2; ++i) {
+                const float send = up ? z[i] : z[i + N / 2];
+                const float keep = up ? z[i + N / 2] : z[i];
+                z[i] = keep + __shfl_xor(send, W);
+            }
+            return Fold<N / 2, W / 2>::run(z, lane);
+        }
+    }
+};
+
+template <int N>
+__device__ __forceinline__ void load_rows(uint4 (&r)[N], const uint16_t *rp, int col, int d, bool on)
+{
+    if (on) {
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+            r[j] = *reinterpret_cast<const uint4 *>(rp + (int64_t)j * d + col);
+    } else {
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+            r[j] = make_uint4(0, 0, 0, 0);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// bf16 fast path: N in {4, 8, 16, 32, 64}, d % 8 == 0, router weight fits in LDS.
+// grid = (workgroups, L); block = WPB waves.
+// ------------------------------------------------------------------------------------------
+template <int N, int WPB>
+__global__ __launch_bounds__(WPB * 64) __attribute__((amdgpu_waves_per_eu(N <= 16 ? 4 : 2)))
+void fwd_bf16_kernel(FwdArgs a)
+{
+    extern __shared__ uint4 smem[];
+    constexpr int NQ = N / 4;
+    constexpr int LPJ = 64 / N;   // lanes per expert after the fold
+    const int d = a.d;
+    const int kgroups = d >> 3;
+    const int layer = blockIdx.y;
+    const int n_w4 = kgroups * N;
+
+    // router weight -> LDS, as (W[k,j], W[k+1,j]) pairs, piece (q, jq, kg) at [(q*NQ+jq)*kgroups+kg]
+    {
+        const uint16_t *Wr = static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N;
+        for (int i = threadIdx.x; i < n_w4; i += WPB * 64) {
+            const int kg = i % kgroups;
+            const int pj = i / kgroups;
+            const int jq = pj % NQ;
+            const int q = pj / NQ;
+            const int k0 = kg * 8 + q * 2;
+            const uint2 w0 = *reinterpret_cast<const uint2 *>(Wr + (int64_t)k0 * N + jq * 4);
+            const uint2 w1 = *reinterpret_cast<const uint2 *>(Wr + (int64_t)(k0 + 1) * N + jq * 4);
+            uint4 v;
+            v.x = (w0.x & 0xffffu) | (w1.x << 16);
+            v.y = (w0.x >> 16) | (w1.x & 0xffff0000u);
+            v.z = (w0.y & 0xffffu) | (w1.y << 16);
+            v.w = (w0.y >> 16) | (w1.y & 0xffff0000u);
+            smem[i] = v;
+        }
+    }
+    __syncthreads();
+
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    float *gl = reinterpret_cast<float *>(smem + n_w4) + wave * (PLAN_GROUP * N);
+    const float4 *gl4 = reinterpret_cast<const float4 *>(gl);
+
+    int n_items = a.T, n_uniq = 0;
+    if (a.plan) {
+        if (a.plan[5] != PLAN_MAGIC || a.plan[2] != a.T) {
+            if (threadIdx.x == 0 && a.err_flag)
+                *a.err_flag = 2;
+            return;
+        }
+        n_items = a.plan[0];
+        n_uniq = a.plan[1];
+    }
+
+    const uint16_t *table = static_cast<const uint16_t *>(a.table) + (int64_t)layer * a.table_stride;
+    const int64_t act_off = (int64_t)layer * a.act_stride;
+    const uint16_t *hbase = static_cast<const uint16_t *>(a.h) + act_off;
+    const uint16_t *sbase = a.shared ? static_cast<const uint16_t *>(a.shared) + act_off : nullptr;
+    const uint16_t *rbase = a.residual ? static_cast<const uint16_t *>(a.residual) + act_off : nullptr;
+    uint16_t *obase = static_cast<uint16_t *>(a.out) + act_off;
+
+    for (int item = blockIdx.x * WPB + wave; item < n_items; item += gridDim.x * WPB) {
+        const Item it = get_item(a, item, n_uniq);
+        const bool valid = it.row >= 0 && it.row < a.rows;
+        if (!valid && lane == 0 && a.err_flag)
+            *a.err_flag = 1;
+        const uint16_t *rp = table + (valid ? it.row : 0) * (int64_t)N * d;
+
+        // rows of the first 512-column chunk: in flight while the router runs
+        uint4 r[N];
+        const int col0 = lane * 8;
+        load_rows<N>(r, rp, col0, d, valid && col0 < d);
+
+        // ---- router + softmax for each token of the item ----
+        for (int i = 0; i < it.cnt; ++i) {
+            const int t = item_token(a, it, i);
+            float z[N];
+#pragma unroll
+            for (int j = 0; j < N; ++j)
+                z[j] = 0.f;
+            for (int c0 = 0; c0 < d; c0 += 512) {
+                const int cc = c0 + col0;
+                if (cc < d) {
+                    const uint4 hv = *reinterpret_cast<const uint4 *>(hbase + (int64_t)t * d + cc);
+                    const uint32_t hp[4] = {hv.x, hv.y, hv.z, hv.w};
+                    const int kg = cc >> 3;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+                        for (int jq = 0; jq < NQ; ++jq) {
+                            const uint4 w = smem[(q * NQ + jq) * kgroups + kg];
+                            z[4 * jq + 0] = mac2(z[4 * jq + 0], hp[q], w.x);
+                            z[4 * jq + 1] = mac2(z[4 * jq + 1], hp[q], w.y);
+                            z[4 * jq + 2] = mac2(z[4 * jq + 2], hp[q], w.z);
+                            z[4 * jq + 3] = mac2(z[4 * jq + 3], hp[q], w.w);
+                        }
+                    }
+                }
+            }
+            const float zz = Fold<N, 32>::run(z, lane);   // logit of expert lane / LPJ
+            float m = zz;
+#pragma unroll
+            for (int w = 32; w >= LPJ; w >>= 1)
+                m = fmaxf(m, __shfl_xor(m, w));
+            const float e = __expf(zz - m);
+            float s = e;
+#pragma unroll
+            for (int w = 32; w >= LPJ; w >>= 1)
+                s += __shfl_xor(s, w);
+            const float g = e / s;
+            if ((lane & (LPJ - 1)) == 0) {
+                const int j = lane / LPJ;
+                gl[i * N + j] = g;
+                if (a.gates_dbg)
+                    a.gates_dbg[((int64_t)layer * a.T + t) * N + j] = g;
+            }
+            if (a.rows_dbg && layer == 0 && lane == 0)
+                a.rows_dbg[t] = valid ? it.row : -1;
+        }
+        wave_lds_fence();
+
+        // ---- gate-weighted sum of the rows, adds, store ----
+        for (int c0 = 0; c0 < d; c0 += 512) {
+            const int cc = c0 + col0;
+            const bool on = cc < d;
+            if (c0 > 0)
+                load_rows<N>(r, rp, cc, d, valid && on);
+            for (int i = 0; i < it.cnt; ++i) {
+                const int t = item_token(a, it, i);
+                const int64_t off = (int64_t)t * d + cc;
+                uint4 sv = make_uint4(0, 0, 0, 0), rv = make_uint4(0, 0, 0, 0);
+                if (on && sbase)
+                    sv = *reinterpret_cast<const uint4 *>(sbase + off);
+                if (on && rbase)
+                    rv = *reinterpret_cast<const uint4 *>(rbase + off);
+                float acc[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    acc[e] = 0.f;
+#pragma unroll
+                for (int jq = 0; jq < NQ; ++jq) {
+                    const float4 g4 = gl4[i * NQ + jq];
+                    const float gg[4] = {g4.x, g4.y, g4.z, g4.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const uint4 rr = r[4 * jq + e];
+                        acc[0] = fmaf(gg[e], bf16lo(rr.x), acc[0]);
+                        acc[1] = fmaf(gg[e], bf16hi(rr.x), acc[1]);
+                        acc[2] = fmaf(gg[e], bf16lo(rr.y), acc[2]);
+                        acc[3] = fmaf(gg[e], bf16hi(rr.y), acc[3]);
+                        acc[4] = fmaf(gg[e], bf16lo(rr.z), acc[4]);
+                        acc[5] = fmaf(gg[e], bf16hi(rr.z), acc[5]);
+                        acc[6] = fmaf(gg[e], bf16lo(rr.w), acc[6]);
+                        acc[7] = fmaf(gg[e], bf16hi(rr.w), acc[7]);
+                    }
+                }
+                acc[0] += bf16lo(sv.x) + bf16lo(rv.x);
+                acc[1] += bf16hi(sv.x) + bf16hi(rv.x);
+                acc[2] += bf16lo(sv.y) + bf16lo(rv.y);
+                acc[3] += bf16hi(sv.y) + bf16hi(rv.y);
+                acc[4] += bf16lo(sv.z) + bf16lo(rv.z);
+                acc[5] += bf16hi(sv.z) + bf16hi(rv.z);
+                acc[6] += bf16lo(sv.w) + bf16lo(rv.w);
+                acc[7] += bf16hi(sv.w) + bf16hi(rv.w);
+                if (on) {
+                    uint4 o;
+                    o.x = pack_bf16(acc[0], acc[1]);
+                    o.y = pack_bf16(acc[2], acc[3]);
+                    o.z = pack_bf16(acc[4], acc[5]);
+                    o.w = pack_bf16(acc[6], acc[7]);
+                    *reinterpret_cast<uint4 *>(obase + off) = o;
+                }
+            }
+        }
+        wave_lds_fence();
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Generic path: any 1 <= N <= 64, fp32 or bf16 storage, no LDS-resident router weight.
+// One wavefront per item; lanes stride over k (router) and over columns (combine).
+// ------------------------------------------------------------------------------------------
+template <typename E> __device__ __forceinline__ float ldf(const E *p);
+template <> __device__ __forceinline__ float ldf<float>(const float *p) { return *p; }
+template <> __device__ __forceinline__ float ldf<uint16_t>(const uint16_t *p) { return bf16_to_f32(*p); }
+__device__ __forceinline__ void stf(float *p, float v) { *p = v; }
+__device__ __forceinline__ void stf(uint16_t *p, float v) { *p = (uint16_t)f32_to_bf16_bits(v); }
+
+template <typename E>
+__global__ __launch_bounds__(256) void fwd_generic_kernel(FwdArgs a)
+{
+    __shared__ float gls[4][PLAN_GROUP * 64];
+    const int d = a.d, N = a.N;
+    const int layer = blockIdx.y;
+    const int wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    float *gl = gls[wave];
+
+    int n_items = a.T, n_uniq = 0;
+    if (a.plan) {
+        if (a.plan[5] != PLAN_MAGIC || a.plan[2] != a.T) {
+            if (threadIdx.x == 0 && a.err_flag)
+                *a.err_flag = 2;
+            return;
+        }
+        n_items = a.plan[0];
+        n_uniq = a.plan[1];
+    }
+    const E *table = static_cast<const E *>(a.table) + (int64_t)layer * a.table_stride;
+    const int64_t act_off = (int64_t)layer * a.act_stride;
+    const E *hbase = static_cast<const E *>(a.h) + act_off;
+    const E *Wr = static_cast<const E *>(a.W_r) + (int64_t)layer * d * N;
+    const E *sbase = a.shared ? static_cast<const E *>(a.shared) + act_off : nullptr;
+    const E *rbase = a.residual ? static_cast<const E *>(a.residual) + act_off : nullptr;
+    E *obase = static_cast<E *>(a.out) + act_off;
+
+    for (int item = blockIdx.x * 4 + wave; item < n_items; item += gridDim.x * 4) {
+        const Item it = get_item(a, item, n_uniq);
+        const bool valid = it.row >= 0 && it.row < a.rows;
+        if (!valid && lane == 0 && a.err_flag)
+            *a.err_flag = 1;
+        const E *rp = table + (valid ? it.row : 0) * (int64_t)N * d;
+
+        for (int i = 0; i < it.cnt; ++i) {
+            const int t = item_token(a, it, i);
+            const E *hr = hbase + (int64_t)t * d;
+            float zmine = -INFINITY;   // lane j keeps logit j
+            for (int j = 0; j < N; ++j) {
+                float p = 0.f;
+                for (int k = lane; k < d; k += 64)
+                    p = fmaf(ldf(hr + k), ldf(Wr + (int64_t)k * N + j), p);
+#pragma unroll
+                for (int w = 32; w >= 1; w >>= 1)
+                    p += __shfl_xor(p, w);
+                if (lane == j)
+                    zmine = p;
+            }
+            float m = zmine;
+#pragma unroll
+            for (int w = 32; w >= 1; w >>= 1)
+                m = fmaxf(m, __shfl_xor(m, w));
+            const float e = (lane < N) ? expf(zmine - m) : 0.f;
+            float s = e;
+#pragma unroll
+            for (int w = 32; w >= 1; w >>= 1)
+                s += __shfl_xor(s, w);
+            const float g = e / s;
+            if (lane < N) {
+                gl[i * N + lane] = g;
+                if (a.gates_dbg)
+                    a.gates_dbg[((int64_t)layer * a.T + t) * N + lane] = g;
+            }
+            if (a.rows_dbg && layer == 0 && lane == 0)
+                a.rows_dbg[t] = valid ? it.row : -1;
+        }
+        wave_lds_fence();
+
+        for (int c = lane; c < d; c += 64) {
+            for (int i = 0; i < it.cnt; ++i) {
+                const int t = item_token(a, it, i);
+                float acc = 0.f;
+                if (valid)
+                    for (int j = 0; j < N; ++j)
+                        acc = fmaf(gl[i * N + j], ldf(rp + (int64_t)j * d + c), acc);
+                const int64_t off = (int64_t)t * d + c;
+                if (sbase)
+                    acc += ldf(sbase + off);
+                if (rbase)
+                    acc += ldf(rbase + off);
+                stf(obase + off, acc);
+            }
+        }
+        wave_lds_fence();
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------
+constexpr size_t LDS_BYTES_PER_CU = 160 * 1024;
+
+int env_int(const char *name, int dflt)
+{
+    const char *s = getenv(name);
+    if (!s || !*s)
+        return dflt;
+    const int v = atoi(s);
+    return v > 0 ? v : dflt;
+}
+
+template <int N, int WPB>
+mole_status launch_fast(const FwdArgs &a, int items_bound, hipStream_t stream)
+{
+    const size_t lds = (size_t)a.d * N * 2 + (size_t)WPB * PLAN_GROUP * N * 4;
+    static size_t attr_set = 0;
+    if (lds > attr_set) {
+        MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_bf16_kernel<N, WPB>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = lds;
+    }
+    int per_cu = (int)(LDS_BYTES_PER_CU / lds);
+    const int wave_cap = 32 / WPB;   // at most 8 waves per SIMD
+    if (per_cu > wave_cap)
+        per_cu = wave_cap;
+    per_cu = env_int("MOLE_FWD_WGS_PER_CU", per_cu);
+    if (per_cu < 1)
+        per_cu = 1;
+    int64_t resident = (int64_t)num_cus() * per_cu;
+    int64_t gx = (items_bound + WPB - 1) / WPB;
+    int64_t cap = resident / a.L;
+    if (cap < 1)
+        cap = 1;
+    if (gx > cap)
+        gx = cap;
+    dim3 grid((unsigned)gx, (unsigned)a.L);
+    hipLaunchKernelGGL((fwd_bf16_kernel<N, WPB>), grid, dim3(WPB * 64), lds, stream, a);
+    MOLE_HIP_CHECK(hipGetLastError());
+    return MOLE_OK;
+}
+
+template <int N>
+mole_status launch_fast_n(const FwdArgs &a, int items_bound, hipStream_t stream)
+{
+    // wider workgroups when the router weight is large, so that LDS does not cap occupancy
+    const size_t wbytes = (size_t)a.d * N * 2;
+    int wpb = wbytes > 40 * 1024 ? 8 : 4;
+    if (wbytes > 80 * 1024)
+        wpb = 16;
+    wpb = env_int("MOLE_FWD_WPB", wpb);
+    switch (wpb) {
+    case 16: return launch_fast<N, 16>(a, items_bound, stream);
+    case 8: return launch_fast<N, 8>(a, items_bound, stream);
+    default: return launch_fast<N, 4>(a, items_bound, stream);
+    }
+}
+
+mole_status forward_impl(const void *table, int64_t table_stride, const int32_t *ids, const int32_t *slot,
+                         const void *h, const void *W_r, const void *shared_out, const void *residual,
+                         void *out, int64_t act_stride, float *gates_dbg, int64_t *rows_dbg,
+                         int32_t *err_flag, int L, int T, int64_t rows, int d, int N, mole_dtype dtype,
+                         unsigned flags, const void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    clear_error();
+    if (dtype != MOLE_F32 && dtype != MOLE_BF16)
+        return fail(MOLE_EINVAL, "mole_lookup_forward: unknown dtype %d", (int)dtype);
+    if (T < 0 || L < 1 || rows < 1 || d < 1)
+        return fail(MOLE_EINVAL, "mole_lookup_forward: bad size (T=%d, L=%d, rows=%lld, d=%d)", T, L,
+                    (long long)rows, d);
+    if (N < 1 || N > 64)
+        return fail(MOLE_EUNSUPPORTED, "mole_lookup_forward: N=%d outside 1..64", N);
+    const int dmul = dtype == MOLE_BF16 ? 8 : 4;
+    if (d % dmul)
+        return fail(MOLE_EUNSUPPORTED, "mole_lookup_forward: d=%d must be a multiple of %d", d, dmul);
+    if (flags & ~unsigned(MOLE_FLAG_DEDUP))
+        return fail(MOLE_EINVAL, "mole_lookup_forward: unknown flags 0x%x", flags);
+    if (T == 0)
+        return MOLE_OK;
+    if (!table || !ids || !h || !W_r || !out)
+        return fail(MOLE_EINVAL, "mole_lookup_forward: table, ids, h, W_r and out must not be NULL");
+    const void *ptrs[] = {table, h, W_r, shared_out, residual, out};
+    for (const void *p : ptrs)
+        if (p && !aligned16(p))
+            return fail(MOLE_EINVAL, "mole_lookup_forward: tensor pointer %p is not 16-byte aligned", p);
+    if (L > 1) {
+        if (act_stride < (int64_t)T * d || table_stride < rows * N * (int64_t)d)
+            return fail(MOLE_EINVAL, "mole_lookup_forward_layers: layer stride smaller than one layer");
+        if ((act_stride * (int64_t)elem_bytes(dtype)) % 16 || (table_stride * (int64_t)elem_bytes(dtype)) % 16)
+            return fail(MOLE_EINVAL, "mole_lookup_forward_layers: layer strides must keep 16-byte alignment");
+        if (L > 65535)
+            return fail(MOLE_EUNSUPPORTED, "mole_lookup_forward_layers: L=%d > 65535", L);
+    }
+    const int32_t *plan = nullptr;
+    int items_bound = T;
+    if (flags & MOLE_FLAG_DEDUP) {
+        const size_t need = (size_t)plan_layout(T).words * 4;
+        if (!workspace || workspace_bytes < need)
+            return fail(MOLE_EWORKSPACE, "mole_lookup_forward: MOLE_FLAG_DEDUP needs a %zu-byte plan, got %zu",
+                        need, workspace ? workspace_bytes : (size_t)0);
+        plan = static_cast<const int32_t *>(workspace);
+        items_bound = T + T / PLAN_GROUP + 2;
+    }
+
+    FwdArgs a;
+    a.table = table; a.ids = ids; a.slot = slot; a.h = h; a.W_r = W_r;
+    a.shared = shared_out; a.residual = residual; a.out = out;
+    a.gates_dbg = gates_dbg; a.rows_dbg = rows_dbg; a.err_flag = err_flag; a.plan = plan;
+    a.table_stride = table_stride; a.act_stride = act_stride; a.rows = rows;
+    a.T = T; a.d = d; a.N = N; a.L = L;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    const size_t lds_fast = (size_t)d * N * 2 + (size_t)16 * PLAN_GROUP * N * 4;
+    const bool fast = dtype == MOLE_BF16 && lds_fast <= LDS_BYTES_PER_CU && !getenv("MOLE_FWD_GENERIC");
+    if (fast) {
+        switch (N) {
+        case 4: return launch_fast_n<4>(a, items_bound, stream);
+        case 8: return launch_fast_n<8>(a, items_bound, stream);
+        case 16: return launch_fast_n<16>(a, items_bound, stream);
+        case 32: return launch_fast_n<32>(a, items_bound, stream);
+        case 64: return launch_fast_n<64>(a, items_bound, stream);
+        default: break;
+        }
+    }
+    int64_t gx = (items_bound + 3) / 4;
+    int64_t cap = (int64_t)num_cus() * 8 / L;
+    if (cap < 1)
+        cap = 1;
+    if (gx > cap)
+        gx = cap;
+    dim3 grid((unsigned)gx, (unsigned)L);
+    if (dtype == MOLE_F32)
+        hipLaunchKernelGGL(fwd_generic_kernel<float>, grid, dim3(256), 0, stream, a);
+    else
+        hipLaunchKernelGGL(fwd_generic_kernel<uint16_t>, grid, dim3(256), 0, stream, a);
+    MOLE_HIP_CHECK(hipGetLastError());
+    return MOLE_OK;
+}
+
+}  // namespace
+
+extern "C" mole_status mole_lookup_forward(const void *table, const int32_t *ids, const int32_t *slot,
+                                           const void *h, const void *W_r, const void *shared_out,
+                                           const void *residual, void *out, float *gates_dbg,
+                                           int64_t *rows_dbg, int32_t *err_flag, int T, int64_t rows, int d,
+                                           int N, mole_dtype dtype, unsigned flags, const void *workspace,
+                                           size_t workspace_bytes, void *hip_stream)
+{
+    return forward_impl(table, 0, ids, slot, h, W_r, shared_out, residual, out, 0, gates_dbg, rows_dbg,
+                        err_flag, 1, T, rows, d, N, dtype, flags, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" mole_status mole_lookup_forward_layers(const void *table, int64_t table_stride, const int32_t *ids,
+                                                  const int32_t *slot, const void *h, const void *W_r,
+                                                  const void *shared_out, const void *residual, void *out,
+                                                  int64_t act_stride, float *gates_dbg, int64_t *rows_dbg,
+                                                  int32_t *err_flag, int L, int T, int64_t rows, int d, int N,
+                                                  mole_dtype dtype, unsigned flags, const void *workspace,
+                                                  size_t workspace_bytes, void *hip_stream)
+{
+    return forward_impl(table, table_stride, ids, slot, h, W_r, shared_out, residual, out, act_stride,
+                        gates_dbg, rows_dbg, err_flag, L, T, rows, d, N, dtype, flags, workspace,
+                        workspace_bytes, hip_stream);
+}

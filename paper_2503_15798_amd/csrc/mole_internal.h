@@ -1,0 +1,73 @@
+// Internal helpers shared by libmole's translation units (not part of the ABI).
+#ifndef MOLE_INTERNAL_H
+#define MOLE_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mole.h"
+
+namespace mole {
+
+// Records a printf-style message for mole_last_error() and returns `st`.
+mole_status fail(mole_status st, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t elem_bytes(mole_dtype dt) { return dt == MOLE_F32 ? 4 : 2; }
+
+// Number of compute units of the current device (cached per process; 256 on MI355X).
+int num_cus();
+
+#define MOLE_HIP_CHECK(expr)                                                             \
+    do {                                                                                 \
+        hipError_t e_ = (expr);                                                          \
+        if (e_ != hipSuccess)                                                            \
+            return ::mole::fail(MOLE_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+// ---- grouping plan written by mole_dedup_ids and read by the forward kernels ----
+// int32 words: header[16] | uniq[T] | order[T] | item_u[cap] | item_begin[cap] | item_cnt[cap]
+//              | scratch counters[T+2]
+// cap = 2T + 2.  header: [0] n_items  [1] n_uniq  [2] T  [3] group cap  [4] V  [5] magic
+constexpr int PLAN_HEADER = 16;
+constexpr int PLAN_MAGIC = 0x4d4f4c45;   // "MOLE"
+constexpr int PLAN_GROUP = 8;            // at most this many tokens share one read of a row block
+struct PlanLayout {
+    int64_t uniq, order, item_u, item_begin, item_cnt, counters, words;
+    int cap;
+};
+__host__ __device__ inline PlanLayout plan_layout(int T)
+{
+    PlanLayout p;
+    p.cap = 2 * T + 2;
+    p.uniq = PLAN_HEADER;
+    p.order = p.uniq + T;
+    p.item_u = p.order + T;
+    p.item_begin = p.item_u + p.cap;
+    p.item_cnt = p.item_begin + p.cap;
+    p.counters = p.item_cnt + p.cap;
+    p.words = p.counters + T + 2;
+    p.words = (p.words + 3) & ~int64_t(3);
+    return p;
+}
+
+// ---- bf16 <-> fp32 on the device ----
+__device__ __forceinline__ float bf16lo(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16hi(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(uint32_t(b) << 16); }
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u)
+        return 0x7fc0u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+}  // namespace mole
+#endif

@@ -1,0 +1,91 @@
+// mole_offload_fetch: pull the looked-up rows of an off-chip LUT into a device staging buffer.
+//
+// Paper: Sec. 3.3 (after re-parameterization the LUT is offloaded to a storage tier and only
+// the d*N looked-up values per token and layer are loaded -- the LoadParam equation of Sec. 3.4)
+// and the lookup line of the inference listing (gather on the storage device, asynchronous
+// copy to the accelerator).
+//
+// Here the gather and the copy are one kernel: wavefronts read the pinned, GPU-mapped host
+// table directly with 16-byte loads and write HBM.  Only the distinct ids of the batch are
+// fetched (uniq / n_uniq from mole_dedup_ids), all L layers in one launch.  Each row block
+// (N*d elements) is cut into pieces of 64 lanes x 16 bytes; pieces are spread over the whole
+// grid so that many reads are in flight on the host link at once.
+#include "mole_internal.h"
+
+namespace {
+using namespace mole;
+
+__global__ __launch_bounds__(256) void fetch_kernel(const uint4 *__restrict__ host, int64_t host_ls16,
+                                                     const int32_t *__restrict__ uniq,
+                                                     const int32_t *__restrict__ n_uniq_p,
+                                                     uint4 *__restrict__ staging, int64_t stage_ls16,
+                                                     int32_t *err_flag, int L, int U_cap, int64_t V,
+                                                     int row16 /* 16-byte pieces per row block */)
+{
+    int U = *n_uniq_p;
+    if (U > U_cap) {
+        if (threadIdx.x == 0 && blockIdx.x == 0 && err_flag)
+            *err_flag = 1;
+        U = U_cap;
+    }
+    // work = (layer, u, 1 KiB piece); a wavefront takes one piece at a time
+    const int pieces = (row16 + 63) >> 6;
+    const int64_t total = (int64_t)L * U * pieces;
+    const int lane = threadIdx.x & 63;
+    const int64_t wave0 = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * (blockDim.x >> 6);
+    for (int64_t w = wave0; w < total; w += nwaves) {
+        const int p = (int)(w % pieces);
+        const int64_t lu = w / pieces;
+        const int u = (int)(lu % U);
+        const int l = (int)(lu / U);
+        const int64_t id = uniq[u];
+        const int i16 = p * 64 + lane;
+        if (i16 < row16 && id >= 0 && id < V) {
+            const uint4 v = host[l * host_ls16 + id * (int64_t)row16 + i16];
+            staging[l * stage_ls16 + (int64_t)u * row16 + i16] = v;
+        }
+    }
+}
+
+}  // namespace
+
+extern "C" mole_status mole_offload_fetch(const void *host_table, int64_t host_layer_stride, const int32_t *uniq,
+                                          const int32_t *n_uniq, void *staging, int64_t staging_layer_stride,
+                                          int32_t *err_flag, int L, int U_cap, int64_t V, int d, int N,
+                                          mole_dtype dtype, void *hip_stream)
+{
+    clear_error();
+    if (dtype != MOLE_F32 && dtype != MOLE_BF16)
+        return fail(MOLE_EINVAL, "mole_offload_fetch: unknown dtype %d", (int)dtype);
+    if (L < 1 || U_cap < 0 || V < 1 || d < 1 || N < 1)
+        return fail(MOLE_EINVAL, "mole_offload_fetch: bad size (L=%d, U_cap=%d, V=%lld, d=%d, N=%d)", L, U_cap,
+                    (long long)V, d, N);
+    const int64_t eb = (int64_t)elem_bytes(dtype);
+    const int64_t row_bytes = (int64_t)N * d * eb;
+    if (row_bytes % 16)
+        return fail(MOLE_EUNSUPPORTED, "mole_offload_fetch: a row block of %lld bytes is not a multiple of 16",
+                    (long long)row_bytes);
+    if (U_cap == 0)
+        return MOLE_OK;
+    if (!host_table || !uniq || !n_uniq || !staging)
+        return fail(MOLE_EINVAL, "mole_offload_fetch: host_table, uniq, n_uniq and staging must not be NULL");
+    if (!aligned16(host_table) || !aligned16(staging))
+        return fail(MOLE_EINVAL, "mole_offload_fetch: host_table and staging must be 16-byte aligned");
+    if (L > 1 && (host_layer_stride < V * N * (int64_t)d || staging_layer_stride < (int64_t)U_cap * N * d ||
+                  (host_layer_stride * eb) % 16 || (staging_layer_stride * eb) % 16))
+        return fail(MOLE_EINVAL, "mole_offload_fetch: layer strides too small or not 16-byte multiples");
+    const int row16 = (int)(row_bytes / 16);
+    const int pieces = (row16 + 63) / 64;
+    int64_t waves = (int64_t)L * U_cap * pieces;
+    int64_t blocks = (waves + 3) / 4;
+    const int64_t cap = (int64_t)num_cus() * 8;
+    if (blocks > cap)
+        blocks = cap;
+    hipLaunchKernelGGL(fetch_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<const uint4 *>(host_table), host_layer_stride * eb / 16, uniq, n_uniq,
+                       static_cast<uint4 *>(staging), staging_layer_stride * eb / 16, err_flag, L, U_cap, V,
+                       row16);
+    MOLE_HIP_CHECK(hipGetLastError());
+    return MOLE_OK;
+}

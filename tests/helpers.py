@@ -1,0 +1,40 @@
+"""Shared helpers of the test-suite: numpy storage arrays <-> torch device tensors, tolerances."""
+import numpy as np
+
+from paper_2503_15798_amd import binding as mb
+from paper_2503_15798_amd import workloads as wl
+
+# Tolerances of the comparison |gpu - ref| <= atol + rtol * |ref| (element by element).
+# bf16 storage with fp32 accumulation; fp32 throughout.
+TOL = {wl.BF16: dict(rtol=2e-2, atol=1e-3), wl.F32: dict(rtol=1e-5, atol=1e-6)}
+DT = {wl.F32: mb.MOLE_F32, wl.BF16: mb.MOLE_BF16}
+
+
+def to_dev(a, dtype, device="cuda"):
+    """numpy storage array (float32, or uint16 bf16 bits) -> torch tensor on the device."""
+    import torch
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a)
+    if dtype == wl.BF16 and a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(a).to(device)
+
+
+def to_host(t, dtype):
+    """torch tensor -> numpy storage array (uint16 bits for bf16)."""
+    import torch
+    if t.dtype == torch.bfloat16:
+        return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def assert_close(got_f64, ref_f64, dtype, what=""):
+    tol = TOL[dtype]
+    err = np.abs(got_f64 - ref_f64)
+    lim = tol["atol"] + tol["rtol"] * np.abs(ref_f64)
+    bad = err > lim
+    if bad.any():
+        i = np.unravel_index(np.argmax(err - lim), err.shape)
+        raise AssertionError(f"{what}: {bad.sum()} of {bad.size} elements out of tolerance; worst at {i}: "
+                             f"got {got_f64[i]!r}, ref {ref_f64[i]!r}, |err| {err[i]:.3e} > {lim[i]:.3e}")

@@ -1,0 +1,301 @@
+"""GPU parity of mole_lookup_forward / mole_lookup_forward_layers against the fp64 oracle.
+Everything goes through the C ABI (via the ctypes binding).  Inputs are seeded and synthetic."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2503_15798_amd import binding as mb
+from paper_2503_15798_amd import workloads as wl
+from helpers import DT, assert_close, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def torch_mod():
+    import torch
+    return torch
+
+
+def run_forward(w, table, ids, li, shared=True, residual=False, slot=None, rows=None, dedup=False,
+                want_dbg=True, table_dev=None):
+    """One call of mole_lookup_forward on numpy inputs; returns numpy outputs."""
+    torch = torch_mod()
+    dev = "cuda"
+    T = len(ids)
+    tab_d = table_dev if table_dev is not None else to_dev(table, w.dtype)
+    n_rows = rows if rows is not None else tab_d.shape[0]
+    ids_d = torch.from_numpy(np.ascontiguousarray(ids, dtype=np.int32)).to(dev)
+    slot_d = None if slot is None else torch.from_numpy(np.ascontiguousarray(slot, dtype=np.int32)).to(dev)
+    h_d, wr_d = to_dev(li["h"], w.dtype), to_dev(li["W_r"], w.dtype)
+    sh_d = to_dev(li["shared"], w.dtype) if shared else None
+    rs_d = to_dev(li["residual"], w.dtype) if residual else None
+    out_d = torch.full((max(T, 1), w.d), float("nan"), dtype=h_d.dtype, device=dev)
+    gates_d = torch.full((max(T, 1), w.N), -1.0, dtype=torch.float32, device=dev) if want_dbg else None
+    rows_d = torch.full((max(T, 1),), -7, dtype=torch.int64, device=dev) if want_dbg else None
+    err_d = torch.zeros((1,), dtype=torch.int32, device=dev)
+    flags, plan = 0, None
+    if dedup:
+        plan = torch.empty((mb.mole_dedup_workspace(T, w.V) // 4,), dtype=torch.int32, device=dev)
+        uq = torch.empty((max(T, 1),), dtype=torch.int32, device=dev)
+        iv = torch.empty((max(T, 1),), dtype=torch.int32, device=dev)
+        nu = torch.zeros((1,), dtype=torch.int32, device=dev)
+        mb.mole_dedup_ids(ids_d, T, w.V, uq, iv, nu, err_d, plan)
+        flags = mb.MOLE_FLAG_DEDUP
+    mb.mole_lookup_forward(tab_d, ids_d, slot_d, h_d, wr_d, sh_d, rs_d, out_d, gates_d, rows_d, err_d,
+                           T, n_rows, w.d, w.N, DT[w.dtype], flags, plan)
+    torch.cuda.synchronize()
+    res = dict(out=to_host(out_d, w.dtype)[:T], err=int(err_d.item()))
+    if want_dbg:
+        res["gates"] = gates_d.cpu().numpy()[:T]
+        res["rows"] = rows_d.cpu().numpy()[:T]
+    return res
+
+
+def check_against_oracle(w, table, ids, li, shared=True, residual=False, dedup=False):
+    ref_out, ref_g, ref_rows, ref_err = oracle.lookup_forward(
+        table, ids, li["h"], li["W_r"], li["shared"] if shared else None, li["residual"] if residual else None)
+    got = run_forward(w, table, ids, li, shared=shared, residual=residual, dedup=dedup)
+    np.testing.assert_array_equal(got["rows"], ref_rows)                     # gathered row indices: bit-exact
+    assert got["err"] == ref_err
+    assert_close(got["gates"].astype(np.float64), ref_g, wl.F32 if w.dtype == wl.F32 else wl.BF16, "gates")
+    assert_close(wl.storage_to_f64(got["out"], w.dtype), ref_out, w.dtype, f"out ({w.name})")
+    return got
+
+
+# ---- config 1: the tiny fp32 layer, table built by the (pinned) oracle ------------------------------
+def test_tiny_fp32_layer():
+    w = wl.CONFIGS["tiny"]
+    ew = wl.expert_weights(w)
+    table = oracle.build_lut(ew["E"], ew["W1"], ew["W2"]).astype(np.float32)
+    li, ids = wl.layer_inputs(w), wl.token_ids(w)
+    got = check_against_oracle(w, table, ids, li)
+    assert np.abs(got["gates"].sum(axis=1) - 1.0).max() < 1e-6                 # gates sum to one
+
+
+# ---- bf16 shapes: several tiles, ragged tails, every specialised N, generic N, d not a multiple of 512 ----
+@pytest.mark.parametrize("d,N,T,V", [
+    (1024, 16, 333, 4096),     # 410M-shaped rows, T not a multiple of the workgroup's tokens
+    (768, 16, 64, 4096),       # 160M-shaped: d = 1.5 chunks of 512 columns
+    (1024, 32, 203, 2048),     # prefill-shaped N
+    (2048, 4, 77, 1024),       # 1B-shaped
+    (256, 8, 130, 512),
+    (128, 64, 50, 300),
+    (520, 16, 9, 64),          # d = 512 + 8: a chunk with a single active lane
+    (64, 1, 40, 100),          # generic path
+    (1024, 5, 33, 256),        # generic path, N not a power of two
+    (512, 12, 31, 256),
+])
+@pytest.mark.parametrize("residual", [False, True])
+def test_bf16_shapes(d, N, T, V, residual):
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, T=T, L=1, name=f"bf16 d{d} N{N} T{T}")
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    li["W_r"] = wl.to_storage(wl.storage_to_f64(li["W_r"], w.dtype) * 5.0, w.dtype)    # gates well away from 1/N
+    check_against_oracle(w, table, ids, li, residual=residual)
+
+
+@pytest.mark.parametrize("d,N,T", [(64, 4, 256), (128, 16, 100), (32, 3, 17)])
+def test_fp32_shapes(d, N, T):
+    w = wl.scaled(wl.CONFIGS["tiny"], V=777, d=d, N=N, T=T, name=f"fp32 d{d} N{N}")
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    li["W_r"] = (li["W_r"] * np.float32(5.0)).astype(np.float32)
+    check_against_oracle(w, table, ids, li, residual=True)
+
+
+def test_routed_term_alone():
+    """Without the O(1) shared term the routed term (~0.02) carries the whole comparison."""
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=2048, T=100, L=1)
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    got = check_against_oracle(w, table, ids, li, shared=False)
+    assert np.abs(wl.storage_to_f64(got["out"], w.dtype)).mean() > 1e-3
+
+
+# ---- special cases with exact answers ----------------------------------------------------------------
+@pytest.mark.parametrize("N", [16, 5])
+def test_saturated_router_returns_the_row_exactly(N):
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=512, d=256, N=N, T=64, L=1)
+    table, ids = wl.random_table(w), wl.token_ids(w)
+    h = np.zeros((w.T, w.d), np.float32)
+    star, kk = np.arange(w.T) % N, np.arange(w.T)
+    h[np.arange(w.T), kk] = 1.0
+    Wr = np.zeros((w.d, N), np.float32)
+    Wr[kk, star] = 1.0e4
+    li = dict(h=wl.to_storage(h, w.dtype), W_r=wl.to_storage(Wr, w.dtype), shared=None, residual=None)
+    got = run_forward(w, table, ids, li, shared=False)
+    np.testing.assert_array_equal(wl.storage_to_f64(got["out"], w.dtype),
+                                  wl.storage_to_f64(table, w.dtype)[ids, star, :])
+    onehot = np.zeros((w.T, N), np.float32)
+    onehot[np.arange(w.T), star] = 1.0
+    np.testing.assert_array_equal(got["gates"], onehot)
+
+
+def test_zero_router_gives_mean_of_rows():
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=512, d=512, N=16, T=40, L=1)
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    li["W_r"] = np.zeros_like(li["W_r"])
+    got = run_forward(w, table, ids, li, shared=False)
+    np.testing.assert_array_equal(got["gates"], np.full((w.T, w.N), 1.0 / 16, np.float32))
+    ref = wl.storage_to_f64(table, w.dtype)[ids].mean(axis=1)
+    assert_close(wl.storage_to_f64(got["out"], w.dtype), ref, w.dtype, "mean of rows")
+
+
+# ---- edge cases --------------------------------------------------------------------------------------
+def test_single_token_and_no_tokens():
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=1024, T=1, L=1)
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    check_against_oracle(w, table, ids, li)
+    got = run_forward(w, table, ids[:0], {k: v[:0] if k != "W_r" else v for k, v in li.items()})
+    assert got["out"].shape[0] == 0 and got["err"] == 0
+
+
+@pytest.mark.parametrize("N", [16, 5])
+@pytest.mark.parametrize("dedup", [False, True])
+def test_out_of_range_ids(N, dedup):
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=300, d=256, N=N, T=40, L=1)
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    ids = ids.copy()
+    ids[[3, 17, 39]] = [300, -1, 2 ** 31 - 1]
+    ref_out, _, ref_rows, ref_err = oracle.lookup_forward(table, ids, li["h"], li["W_r"], li["shared"])
+    got = run_forward(w, table, ids, li, dedup=dedup)
+    assert got["err"] == 1 == ref_err
+    np.testing.assert_array_equal(got["rows"], ref_rows)
+    assert_close(wl.storage_to_f64(got["out"], w.dtype), ref_out, w.dtype, "out with bad ids")
+    np.testing.assert_array_equal(got["out"][[3, 17, 39]], li["shared"][[3, 17, 39]])     # routed term = 0
+
+
+def test_slot_indirection_reads_the_staging_rows():
+    """row(t) = slot[t]: a compacted table of the distinct ids gives the same output bit for bit."""
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=2048, d=512, T=128, L=1)
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    uniq, inv = np.unique(ids, return_inverse=True)
+    a = run_forward(w, table, ids, li)
+    b = run_forward(w, np.ascontiguousarray(table[uniq]), ids, li, slot=inv.astype(np.int32))
+    np.testing.assert_array_equal(a["out"], b["out"])
+    np.testing.assert_array_equal(b["rows"], inv)
+
+
+# ---- dedup flag, layer-batched launch, determinism ---------------------------------------------------
+@pytest.mark.parametrize("d,N,T,V,dist", [(1024, 16, 256, 4096, "zipf"), (1024, 32, 2000, 512, "zipf"),
+                                           (768, 16, 64, 50304, "zipf"), (256, 5, 300, 40, "uniform"),
+                                           (64, 4, 256, 1024, "uniform")])
+def test_dedup_flag_does_not_change_the_output(d, N, T, V, dist):
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, T=T, L=1, ids=dist)
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    a = check_against_oracle(w, table, ids, li, dedup=False)
+    b = check_against_oracle(w, table, ids, li, dedup=True)
+    np.testing.assert_array_equal(a["out"], b["out"])
+    np.testing.assert_array_equal(a["gates"], b["gates"])
+
+
+def test_heavy_repeats_are_split_into_bounded_groups():
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=64, d=256, N=16, T=500, L=1)
+    table, li = wl.random_table(w), wl.layer_inputs(w)
+    ids = np.full((w.T,), 7, np.int32)
+    ids[::50] = 9
+    check_against_oracle(w, table, ids, li, dedup=True)
+
+
+@pytest.mark.parametrize("dedup", [False, True])
+def test_layer_batched_launch_equals_per_layer_calls(dedup):
+    torch = torch_mod()
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=1024, d=512, N=16, T=70, L=3)
+    ids = wl.token_ids(w)
+    tabs = [wl.random_table(w, l) for l in range(w.L)]
+    lis = [wl.layer_inputs(w, l) for l in range(w.L)]
+    per_layer = [run_forward(w, tabs[l], ids, lis[l], residual=True, dedup=dedup) for l in range(w.L)]
+
+    stack = lambda key: to_dev(np.stack([li[key] for li in lis]), w.dtype)
+    tab_d = to_dev(np.stack(tabs), w.dtype)
+    ids_d = torch.from_numpy(ids).cuda()
+    h_d, wr_d, sh_d, rs_d = stack("h"), stack("W_r"), stack("shared"), stack("residual")
+    out_d = torch.zeros_like(h_d)
+    gates_d = torch.zeros((w.L, w.T, w.N), dtype=torch.float32, device="cuda")
+    rows_d = torch.zeros((w.T,), dtype=torch.int64, device="cuda")
+    err_d = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    flags, plan = 0, None
+    if dedup:
+        plan = torch.empty((mb.mole_dedup_workspace(w.T, w.V) // 4,), dtype=torch.int32, device="cuda")
+        uq, iv = torch.empty_like(ids_d), torch.empty_like(ids_d)
+        mb.mole_dedup_ids(ids_d, w.T, w.V, uq, iv, torch.zeros_like(err_d), err_d, plan)
+        flags = mb.MOLE_FLAG_DEDUP
+    mb.mole_lookup_forward_layers(tab_d, w.V * w.N * w.d, ids_d, None, h_d, wr_d, sh_d, rs_d, out_d, w.T * w.d,
+                                  gates_d, rows_d, err_d, w.L, w.T, w.V, w.d, w.N, DT[w.dtype], flags, plan)
+    torch.cuda.synchronize()
+    out = to_host(out_d, w.dtype)
+    for l in range(w.L):
+        np.testing.assert_array_equal(out[l], per_layer[l]["out"])
+        np.testing.assert_array_equal(gates_d[l].cpu().numpy(), per_layer[l]["gates"])
+    np.testing.assert_array_equal(rows_d.cpu().numpy(), ids)
+    assert int(err_d.item()) == 0
+
+
+def test_two_runs_are_bit_identical():
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=4096, T=256, L=1)
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    for dedup in (False, True):
+        a = run_forward(w, table, ids, li, dedup=dedup)
+        b = run_forward(w, table, ids, li, dedup=dedup)
+        np.testing.assert_array_equal(a["out"], b["out"])
+
+
+# ---- full benchmark sizes, in the launch configuration the benchmark times ---------------------------
+def _sampled_check(w, tab_d, ids, lis_d, out, layer, sample, torch):
+    """Oracle on a sample of tokens: their rows are copied back with plain indexing."""
+    sid = ids[sample]
+    rows_host = to_host(tab_d[torch.from_numpy(sid.astype(np.int64)).cuda()], w.dtype)       # [S,N,d]
+    li = {k: to_host(v[layer][torch.from_numpy(sample).cuda()] if k != "W_r" else v[layer], w.dtype)
+          for k, v in lis_d.items()}
+    ref, _, _, _ = oracle.lookup_forward(rows_host, np.arange(len(sample), dtype=np.int32), li["h"], li["W_r"],
+                                         li["shared"])
+    assert_close(wl.storage_to_f64(out[sample], w.dtype), ref, w.dtype, f"{w.name} layer {layer} sample")
+
+
+@pytest.mark.parametrize("name,dedup", [("prefill410m", False), ("prefill410m", True),
+                                        ("prefill410m_uniform", True), ("decode160m", False)])
+def test_full_size_single_layer_sampled(name, dedup):
+    torch = torch_mod()
+    w = wl.CONFIGS[name]
+    tab_d = wl.device_table(w, 0, "cuda")
+    assert tab_d.numel() * 2 > 2 ** 31 or name == "decode160m"       # byte offsets beyond 32 bits
+    ids = wl.token_ids(w)
+    li = wl.layer_inputs(w)
+    got = run_forward(w, None, ids, li, dedup=dedup, table_dev=tab_d, want_dbg=True)
+    np.testing.assert_array_equal(got["rows"], ids)
+    assert got["err"] == 0
+    rng = np.random.default_rng(1)
+    sample = np.unique(np.concatenate([rng.integers(0, w.T, 48), [0, w.T - 1], np.argsort(ids)[-4:]]))
+    lis_d = {k: to_dev(v, w.dtype)[None] for k, v in li.items() if k != "residual"}
+    _sampled_check(w, tab_d, ids, lis_d, got["out"], 0, sample, torch)
+    # properties that hold at any size: gates are a distribution; equal (id, h) would give equal rows
+    assert np.abs(got["gates"].sum(axis=1) - 1.0).max() < 1e-5 and (got["gates"] >= 0).all()
+
+
+@pytest.mark.parametrize("dedup", [False, True])
+def test_full_size_decode410m_all_layers_sampled(dedup):
+    """24 layers x 256 tokens in one launch over a 39.6 GB table set."""
+    torch = torch_mod()
+    w = wl.CONFIGS["decode410m"]
+    tabs = torch.empty((w.L, w.V, w.N, w.d), dtype=torch.bfloat16, device="cuda")
+    for l in range(w.L):
+        wl.device_table(w, l, "cuda", out=tabs[l])
+    ids = wl.token_ids(w)
+    lis = [wl.layer_inputs(w, l) for l in range(w.L)]
+    lis_d = {k: to_dev(np.stack([li[k] for li in lis]), w.dtype) for k in ("h", "W_r", "shared")}
+    ids_d = torch.from_numpy(ids).cuda()
+    out_d = torch.full_like(lis_d["h"], float("nan"))
+    err_d = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    flags, plan = 0, None
+    if dedup:
+        plan = torch.empty((mb.mole_dedup_workspace(w.T, w.V) // 4,), dtype=torch.int32, device="cuda")
+        uq, iv = torch.empty_like(ids_d), torch.empty_like(ids_d)
+        mb.mole_dedup_ids(ids_d, w.T, w.V, uq, iv, torch.zeros_like(err_d), err_d, plan)
+        flags = mb.MOLE_FLAG_DEDUP
+    mb.mole_lookup_forward_layers(tabs, w.V * w.N * w.d, ids_d, None, lis_d["h"], lis_d["W_r"], lis_d["shared"],
+                                  None, out_d, w.T * w.d, None, None, err_d, w.L, w.T, w.V, w.d, w.N,
+                                  DT[w.dtype], flags, plan)
+    torch.cuda.synchronize()
+    assert int(err_d.item()) == 0
+    out = to_host(out_d, w.dtype)
+    assert not np.isnan(wl.storage_to_f64(out, w.dtype)).any()
+    sample = np.unique(np.concatenate([np.random.default_rng(2).integers(0, w.T, 24), [0, w.T - 1]]))
+    for layer in (0, 11, 23):
+        _sampled_check(w, tabs[layer], ids, lis_d, out[layer], layer, sample, torch)

@@ -1,0 +1,97 @@
+"""GPU parity of the offloaded-LUT mode: rows fetched from pinned host memory are byte-identical to the
+host rows, and the staged forward equals the resident forward bit for bit (and the oracle within
+tolerance)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2503_15798_amd import binding as mb
+from paper_2503_15798_amd import workloads as wl
+from helpers import DT, assert_close, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("L,V,d,N,T,dtype", [(3, 3000, 1024, 16, 32, wl.BF16), (1, 500, 768, 16, 64, wl.BF16),
+                                             (2, 400, 64, 4, 50, wl.F32), (2, 300, 520, 5, 9, wl.BF16)])
+def test_fetch_then_forward(L, V, d, N, T, dtype):
+    import torch
+    w = wl.scaled(wl.CONFIGS["offload410m"], V=V, d=d, N=N, T=T, L=L, dtype=dtype)
+    tabs = np.stack([wl.random_table(w, l) for l in range(L)])                     # [L,V,N,d] storage
+    host_t = to_dev(tabs, dtype, device="cpu").pin_memory()
+    ids = wl.token_ids(w)
+    lis = [wl.layer_inputs(w, l) for l in range(L)]
+    ids_d = torch.from_numpy(ids).cuda()
+    uniq_d, inv_d = torch.empty_like(ids_d), torch.empty_like(ids_d)
+    nu_d = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    err_d = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    plan = torch.empty((mb.mole_dedup_workspace(T, V) // 4,), dtype=torch.int32, device="cuda")
+    mb.mole_dedup_ids(ids_d, T, V, uniq_d, inv_d, nu_d, err_d, plan)
+    U_cap = T
+    staging = torch.zeros((L, U_cap, N, d), dtype=host_t.dtype, device="cuda")
+    mb.mole_offload_fetch(host_t, V * N * d, uniq_d, nu_d, staging, U_cap * N * d, err_d, L, U_cap, V, d, N, DT[dtype])
+    torch.cuda.synchronize()
+    U = int(nu_d.item())
+    r_uniq, r_inv, r_U, _ = oracle.dedup(ids, V)
+    assert U == r_U
+    st = to_host(staging, dtype)
+    np.testing.assert_array_equal(st[:, :U], tabs[:, r_uniq])                      # byte-identical rows
+    assert (st[:, U:] == 0).all()                                                  # nothing else touched
+
+    stack = lambda key: to_dev(np.stack([li[key] for li in lis]), dtype)
+    h_d, wr_d, sh_d = stack("h"), stack("W_r"), stack("shared")
+    out_staged, out_res = torch.zeros_like(h_d), torch.zeros_like(h_d)
+    tab_d = to_dev(tabs, dtype)
+    for flags, pl in ((0, None), (mb.MOLE_FLAG_DEDUP, plan)):
+        mb.mole_lookup_forward_layers(staging, U_cap * N * d, ids_d, inv_d, h_d, wr_d, sh_d, None, out_staged,
+                                      T * d, None, None, err_d, L, T, U_cap, d, N, DT[dtype], flags, pl)
+        mb.mole_lookup_forward_layers(tab_d, V * N * d, ids_d, None, h_d, wr_d, sh_d, None, out_res, T * d,
+                                      None, None, err_d, L, T, V, d, N, DT[dtype], flags, pl)
+        torch.cuda.synchronize()
+        assert int(err_d.item()) == 0
+        a, b = to_host(out_staged, dtype), to_host(out_res, dtype)
+        np.testing.assert_array_equal(a, b)
+        for l in range(L):
+            ref, _, _, _ = oracle.lookup_forward(tabs[l], ids, lis[l]["h"], lis[l]["W_r"], lis[l]["shared"])
+            assert_close(wl.storage_to_f64(a[l], dtype), ref, dtype, f"staged forward layer {l}")
+
+
+def test_forward_straight_from_pinned_host_table():
+    """The table pointer may itself be pinned host memory: rows then cross the link inside the forward."""
+    import torch
+    w = wl.scaled(wl.CONFIGS["offload410m"], V=2000, T=32, L=1)
+    tab = wl.random_table(w)
+    host_t = to_dev(tab, w.dtype, device="cpu").pin_memory()
+    li, ids = wl.layer_inputs(w), wl.token_ids(w)
+    ids_d = torch.from_numpy(ids).cuda()
+    h_d, wr_d, sh_d = (to_dev(li[k], w.dtype) for k in ("h", "W_r", "shared"))
+    out_d = torch.zeros_like(h_d)
+    err_d = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    mb.mole_lookup_forward(host_t, ids_d, None, h_d, wr_d, sh_d, None, out_d, None, None, err_d, w.T, w.V, w.d, w.N,
+                           DT[w.dtype])
+    torch.cuda.synchronize()
+    ref, _, _, _ = oracle.lookup_forward(tab, ids, li["h"], li["W_r"], li["shared"])
+    assert_close(wl.storage_to_f64(to_host(out_d, w.dtype), w.dtype), ref, w.dtype, "host-table forward")
+
+
+def test_fetch_reports_overflowing_staging():
+    import torch
+    w = wl.scaled(wl.CONFIGS["offload410m"], V=500, d=64, N=4, T=64, L=1, ids="uniform")
+    tab = wl.random_table(w)
+    host_t = to_dev(tab, w.dtype, device="cpu").pin_memory()
+    ids = wl.token_ids(w)
+    ids_d = torch.from_numpy(ids).cuda()
+    uniq_d, inv_d = torch.empty_like(ids_d), torch.empty_like(ids_d)
+    nu_d = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    err_d = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    plan = torch.empty((mb.mole_dedup_workspace(w.T, w.V) // 4,), dtype=torch.int32, device="cuda")
+    mb.mole_dedup_ids(ids_d, w.T, w.V, uniq_d, inv_d, nu_d, err_d, plan)
+    U_cap = 8
+    staging = torch.zeros((U_cap + 4, w.N, w.d), dtype=host_t.dtype, device="cuda")
+    mb.mole_offload_fetch(host_t, 0, uniq_d, nu_d, staging, 0, err_d, 1, U_cap, w.V, w.d, w.N, DT[w.dtype])
+    torch.cuda.synchronize()
+    assert int(nu_d.item()) > U_cap and int(err_d.item()) == 1
+    st = to_host(staging, w.dtype)
+    uniq = uniq_d.cpu().numpy()
+    np.testing.assert_array_equal(st[:U_cap], tab[uniq[:U_cap]])
+    assert (st[U_cap:] == 0).all()                                                 # no write past the capacity
