@@ -1,0 +1,410 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoLE lookup-expert layer on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-extras]
+
+One "step" is one pass of the inference hot path over one batch of synthetic input: for the
+headline workload (410M-shaped decode: 24 MoLE layers x 256 tokens, N=16, d=1024, bf16 tables
+resident in HBM, Zipf(1.1) token ids) that is router + softmax + row gather + gate-weighted sum +
+shared-FFN add for all 24 layers.  Inputs are resident in HBM when the clock starts; 16
+pre-generated id batches rotate so that successive steps do not replay identical rows.
+The script prints ONE JSON line.  Besides the contract fields it carries
+  roofline      the forward kernel against the HBM roofline (algorithmic bytes / launch duration)
+  cpu_baseline  the fp64 CPU oracle timed on the host cores on the same workload
+  other         the remaining workloads (prefill, other batch sizes, dedup variants, offloaded
+                mode, LUT build), each with its own rates.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+HOST_LINK_GBS = 64.0            # PCIe Gen5 x16, one direction
+N_ID_BATCHES = 16
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="decode410m")
+    ap.add_argument("--no-extras", action="store_true", help="only the headline workload")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch a plain 1 GiB device copy (reference for rocprofv3 byte counters)")
+    return ap.parse_args()
+
+
+class Layers:
+    """Device-resident state of one workload: tables, router weights, activations, id batches."""
+
+    def __init__(self, w, torch, mb, wl, ids_kind=None):
+        self.w, self.torch, self.mb = w, torch, mb
+        dev = "cuda"
+        tdt = torch.bfloat16 if w.dtype == wl.BF16 else torch.float32
+        self.code = mb.MOLE_BF16 if w.dtype == wl.BF16 else mb.MOLE_F32
+        self.tabs = torch.empty((w.L, w.V, w.N, w.d), dtype=tdt, device=dev)
+        for l in range(w.L):
+            wl.device_table(w, l, dev, out=self.tabs[l])
+        g = torch.Generator(device=dev)
+        g.manual_seed(1000 + w.seed)
+        self.h = torch.randn((w.L, w.T, w.d), generator=g, device=dev).to(tdt)
+        self.shared = torch.randn((w.L, w.T, w.d), generator=g, device=dev).to(tdt)
+        self.W_r = (torch.randn((w.L, w.d, w.N), generator=g, device=dev) * 0.02).to(tdt)
+        self.out = torch.empty_like(self.h)
+        import numpy as np
+        ww = w if ids_kind is None else wl.scaled(w, ids=ids_kind)
+        self.ids_host = np.stack([wl.token_ids(ww, b) for b in range(N_ID_BATCHES)])
+        self.ids = torch.from_numpy(self.ids_host).to(dev)
+        self.err = torch.zeros((1,), dtype=torch.int32, device=dev)
+        self.plan = torch.empty((mb.mole_dedup_workspace(w.T, w.V) // 4,), dtype=torch.int32, device=dev)
+        self.uniq = torch.empty((w.T,), dtype=torch.int32, device=dev)
+        self.inv = torch.empty((w.T,), dtype=torch.int32, device=dev)
+        self.n_uniq = torch.zeros((1,), dtype=torch.int32, device=dev)
+
+    def forward(self, i, stream, dedup=False, table=None, slot=None, rows=None, table_stride=None):
+        w, mb = self.w, self.mb
+        tab = self.tabs if table is None else table
+        mb.mole_lookup_forward_layers(
+            tab, w.V * w.N * w.d if table_stride is None else table_stride, self.ids[i % N_ID_BATCHES], slot,
+            self.h, self.W_r, self.shared, None, self.out, w.T * w.d, None, None, self.err,
+            w.L, w.T, w.V if rows is None else rows, w.d, w.N, self.code,
+            mb.MOLE_FLAG_DEDUP if dedup else 0, self.plan if dedup else None, stream=stream)
+
+    def dedup(self, i, stream):
+        self.mb.mole_dedup_ids(self.ids[i % N_ID_BATCHES], self.w.T, self.w.V, self.uniq, self.inv, self.n_uniq,
+                               self.err, self.plan, stream=stream)
+
+    def distinct(self):
+        import numpy as np
+        return float(np.mean([len(np.unique(b)) for b in self.ids_host]))
+
+
+def time_steps(torch, stream, step, steps, warmup):
+    """`warmup` untimed, then exactly `steps` timed calls of step(i), all enqueued on `stream` and
+    bracketed by two HIP events recorded on that stream, with a device synchronisation on both
+    sides.  Returns milliseconds per step."""
+    with torch.cuda.stream(stream):
+        for i in range(warmup):
+            step(i)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        ev0 = torch.cuda.Event(enable_timing=True)
+        ev1 = torch.cuda.Event(enable_timing=True)
+        ev0.record(stream)
+        for i in range(steps):
+            step(warmup + i)
+        ev1.record(stream)
+        stream.synchronize()
+        torch.cuda.synchronize()
+    return ev0.elapsed_time(ev1) / steps
+
+
+def rates(w, acc, ms, distinct=None):
+    """tokens/s and GB/s for a forward over all layers of workload w taking `ms`."""
+    alg = acc.forward_bytes_per_token(w.d, w.N, w.elem_bytes) * w.T * w.L
+    out = {"ms": round(ms, 5), "layer_tokens_per_s": w.T * w.L / (ms * 1e-3), "tokens_per_s": w.T / (ms * 1e-3),
+           "algorithmic_GBps": alg / (ms * 1e-3) / 1e9,
+           "algorithmic_frac_of_hbm_peak": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    if distinct is not None:
+        moved = w.L * acc.forward_bytes_moved(w.T, int(round(distinct)), w.d, w.N, w.elem_bytes)
+        out["distinct_ids"] = distinct
+        out["moved_GBps"] = moved / (ms * 1e-3) / 1e9
+    return out
+
+
+def read_traffic(kernel_tag):
+    """HBM bytes per launch of the forward kernel from the committed rocprofv3 counter summary
+    (profiles/<tag>_hbm_traffic.txt: key=value lines), or None if there is none."""
+    path = os.path.join(ROOT, "profiles", f"{kernel_tag}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    kv = {}
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if "=" in line:
+            k, v = line.split("=", 1)
+            kv[k.strip()] = v.strip()
+    try:
+        return float(kv["hbm_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
+
+
+def cpu_baseline(L, torch, wl, steps=3):
+    """The fp64 oracle on the host cores, same workload: all layers x all tokens of id batch 0.
+    Only the looked-up rows are brought to the host (plain indexing; the copy is not timed)."""
+    import numpy as np
+    import oracle
+    w = L.w
+    ids = L.ids_host[0]
+    uniq, inv = np.unique(ids, return_inverse=True)
+    rows_t = torch.from_numpy(uniq.astype(np.int64)).cuda()
+
+    def host(t):
+        if t.dtype == torch.bfloat16:
+            return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+        return t.cpu().numpy()
+    per_layer = [(host(L.tabs[l][rows_t]), host(L.h[l]), host(L.W_r[l]), host(L.shared[l])) for l in range(w.L)]
+    inv32 = inv.astype(np.int32)
+    oracle.lib()
+    times = []
+    for _ in range(steps):
+        t0 = time.perf_counter()
+        for tab, h, wr, sh in per_layer:
+            oracle.lookup_forward(tab, inv32, h, wr, sh)
+        times.append(time.perf_counter() - t0)
+    sec = statistics.median(times)
+    return {"value": w.T * w.L / sec, "unit": "layer-tokens/s", "cores": oracle.threads(), "kind": "oracle",
+            "seconds_per_step": sec,
+            "sample": f"the whole step ({w.L} layers x {w.T} tokens, id batch 0), median of {steps} runs; "
+                      "rows gathered to the host beforehand, untimed"}, per_layer, inv32
+
+
+def check_against_oracle(L, torch, wl, per_layer, inv32, stream):
+    """One GPU step on id batch 0 compared with the oracle on a few layers (guards the numbers)."""
+    import numpy as np
+    import oracle
+    w = L.w
+    L.forward(0, stream)
+    torch.cuda.synchronize()
+    for l in sorted({0, w.L // 2, w.L - 1}):
+        tab, h, wr, sh = per_layer[l]
+        ref, _, _, _ = oracle.lookup_forward(tab, inv32, h, wr, sh)
+        got = L.out[l]
+        got = wl.storage_to_f64(got.contiguous().view(torch.int16).cpu().numpy().view(np.uint16), wl.BF16) \
+            if got.dtype == torch.bfloat16 else got.cpu().numpy().astype(np.float64)
+        if not np.all(np.abs(got - ref) <= 1e-3 + 2e-2 * np.abs(ref)):
+            raise RuntimeError(f"GPU output of layer {l} disagrees with the oracle")
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build measures ONE GPU (the MoLE lookup path of one device); --gpus {args.gpus} "
+              "is not supported -- token-parallel sharding with a replicated table needs no communication, "
+              "see DESIGN.md", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2503_15798_amd import accounting as acc
+    from paper_2503_15798_amd import binding as mb
+    from paper_2503_15798_amd import workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    mb.lib()     # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    stream = torch.cuda.Stream()
+    w = wl.CONFIGS[args.workload]
+
+    # ------------------------------------------------------------------ headline workload
+    L = Layers(w, torch, mb, wl)
+
+    def step(i):
+        L.forward(i, stream)
+    ms_step = time_steps(torch, stream, step, args.steps, args.warmup)
+    # the step is exactly one launch of the forward kernel, so the launch-to-launch average over the
+    # timed region is that kernel's duration (an upper bound: it includes the gap between launches)
+    ms_kernel = ms_step
+    if int(L.err.item()) != 0:
+        raise RuntimeError("error flag set by the forward kernel")
+    distinct = L.distinct()
+    table_bytes = int(L.tabs.numel() * L.tabs.element_size())
+    head = rates(w, acc, ms_step, distinct)
+    alg_bytes = acc.forward_bytes_per_token(w.d, w.N, w.elem_bytes) * w.T * w.L
+    achieved = alg_bytes / (ms_kernel * 1e-3) / 1e9
+    kernel_tag = f"fwd_bf16_stream_{w.name}"
+    roofline = {"bound": "hbm", "kernel": "fwd_bf16_stream_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(kernel_tag),
+                "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": ms_kernel,
+                "moved_GBps": w.L * acc.forward_bytes_moved(w.T, int(round(distinct)), w.d, w.N, w.elem_bytes)
+                / (ms_kernel * 1e-3) / 1e9}
+
+    cpu = None
+    if not args.no_cpu:
+        cpu, per_layer, inv32 = cpu_baseline(L, torch, wl)
+        check_against_oracle(L, torch, wl, per_layer, inv32, stream)
+        del per_layer
+
+    other = {}
+    if not args.no_extras:
+        other = extras(args, torch, mb, wl, acc, stream, L)
+    if args.calibrate_copy:
+        a = torch.empty((1 << 30,), dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+
+    line = {
+        "metric": "MoLE layer tokens/s (410M-shape decode step: 24 MoLE layers x 256 tokens, N=16, d=1024)",
+        "value": head["layer_tokens_per_s"], "unit": "layer-tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "layers": w.L, "tokens_per_step": w.T, "V": w.V, "d": w.d, "N": w.N,
+                   "ids": "zipf(1.1), 16 rotating batches", "mean_distinct_ids": distinct,
+                   "table_bytes": table_bytes,
+                   "step": "router + softmax + gather + gate-weighted sum + shared add, all layers, one launch",
+                   "decode_tokens_per_s": head["tokens_per_s"],
+                   "algorithmic_GBps": head["algorithmic_GBps"], "moved_GBps": head["moved_GBps"]},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "other": other,
+    }
+    print(json.dumps(line))
+
+
+def extras(args, torch, mb, wl, acc, stream, L):
+    """The other workloads and variants.  Each entry: ms, tokens/s, GB/s."""
+    import numpy as np
+    out = {}
+    steps, warm = max(20, args.steps // 4), max(5, args.warmup // 2)
+    w = L.w
+
+    def both(LL):
+        def f(i):
+            LL.dedup(i, stream)
+            LL.forward(i, stream, dedup=True)
+        return f
+
+    def plain(LL):
+        return lambda i: LL.forward(i, stream)
+
+    # headline shape: dedup + grouped forward, and the dedup kernel alone
+    ms = time_steps(torch, stream, both(L), steps, warm)
+    out["decode410m_dedup_plus_forward"] = rates(w, acc, ms, L.distinct())
+    ms = time_steps(torch, stream, lambda i: L.dedup(i, stream), steps, warm)
+    out["decode410m_dedup_kernel_ms"] = ms
+
+    # ---- offloaded mode on the same tables: all LUTs in pinned host memory, T = 32 ----
+    try:
+        out.update(offload_bench(torch, mb, wl, acc, stream, L, steps, warm))
+    except Exception as e:   # host memory may not allow 40 GB of pinned pages
+        out["offload410m"] = {"skipped": repr(e)}
+
+    # smaller decode batches on the same tables (latency-bound: microseconds are the result)
+    for T in (32, 1):
+        ww = wl.scaled(w, T=T, name=f"decode410m_t{T}")
+        LL = Layers.__new__(Layers)
+        LL.__dict__.update(L.__dict__)
+        LL.w = ww
+        LL.h, LL.shared, LL.out = L.h[:, :T].contiguous(), L.shared[:, :T].contiguous(), L.out[:, :T].contiguous()
+        LL.ids_host = np.stack([wl.token_ids(ww, b) for b in range(N_ID_BATCHES)])
+        LL.ids = torch.from_numpy(LL.ids_host).cuda()
+        ms = time_steps(torch, stream, plain(LL), steps, warm)
+        out[ww.name] = rates(ww, acc, ms, LL.distinct())
+    del L.tabs
+    torch.cuda.empty_cache()
+
+    for name in ("prefill410m", "prefill410m_uniform", "decode160m"):
+        ww = wl.CONFIGS[name]
+        LL = Layers(ww, torch, mb, wl)
+        ms = time_steps(torch, stream, plain(LL), steps, warm)
+        out[name] = rates(ww, acc, ms, LL.distinct())
+        ms = time_steps(torch, stream, both(LL), steps, warm)
+        out[name + "_dedup_plus_forward"] = rates(ww, acc, ms, LL.distinct())
+        ms = time_steps(torch, stream, lambda i: LL.dedup(i, stream), steps, warm)
+        out[name + "_dedup_kernel_ms"] = ms
+        del LL
+        torch.cuda.empty_cache()
+
+    out["build_lut_410m_layer"] = build_bench(torch, mb, wl, acc, stream)
+    return out
+
+
+def offload_bench(torch, mb, wl, acc, stream, L, steps, warm):
+    import numpy as np
+    w = wl.CONFIGS["offload410m"]
+    host = torch.empty(L.tabs.shape, dtype=L.tabs.dtype, pin_memory=True)
+    host.copy_(L.tabs)
+    torch.cuda.synchronize()
+    T, U_cap = w.T, w.T
+    ids_host = np.stack([wl.token_ids(w, b) for b in range(N_ID_BATCHES)])
+    ids = torch.from_numpy(ids_host).cuda()
+    uniq = torch.empty((T,), dtype=torch.int32, device="cuda")
+    inv = torch.empty((T,), dtype=torch.int32, device="cuda")
+    nu = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    err = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    plan = torch.empty((mb.mole_dedup_workspace(T, w.V) // 4,), dtype=torch.int32, device="cuda")
+    staging = torch.empty((w.L, U_cap, w.N, w.d), dtype=L.tabs.dtype, device="cuda")
+    h, sh, o = L.h[:, :T].contiguous(), L.shared[:, :T].contiguous(), L.out[:, :T].contiguous()
+    row_elems, code = w.N * w.d, mb.MOLE_BF16
+
+    def dedup(i):
+        mb.mole_dedup_ids(ids[i % N_ID_BATCHES], T, w.V, uniq, inv, nu, err, plan, stream=stream)
+
+    def fetch(i):
+        mb.mole_offload_fetch(host, w.V * row_elems, uniq, nu, staging, U_cap * row_elems, err, w.L, U_cap, w.V,
+                              w.d, w.N, code, stream=stream)
+
+    def fwd_staged(i):
+        mb.mole_lookup_forward_layers(staging, U_cap * row_elems, ids[i % N_ID_BATCHES], inv, h, L.W_r, sh, None, o,
+                                      T * w.d, None, None, err, w.L, T, U_cap, w.d, w.N, code, 0, None, stream=stream)
+
+    def fwd_direct(i):
+        mb.mole_lookup_forward_layers(host, w.V * row_elems, ids[i % N_ID_BATCHES], None, h, L.W_r, sh, None, o,
+                                      T * w.d, None, None, err, w.L, T, w.V, w.d, w.N, code, 0, None, stream=stream)
+
+    def full(i):
+        dedup(i)
+        fetch(i)
+        fwd_staged(i)
+    res = {}
+    U = float(np.mean([len(np.unique(b)) for b in ids_host]))
+    fetched = U * w.L * row_elems * 2
+    ms_full = time_steps(torch, stream, full, steps, warm)
+
+    def only_fetch(i):
+        fetch(i)
+    dedup(0)
+    ms_fetch = time_steps(torch, stream, only_fetch, steps, warm)
+    u0 = len(np.unique(ids_host[0]))
+    ms_direct = time_steps(torch, stream, lambda i: fwd_direct(i), steps, warm)
+    res["offload410m"] = {
+        "step": "dedup + fetch of the distinct rows of all 24 layers from pinned host memory + staged forward",
+        "tokens": T, "mean_distinct_ids": U, "ms": ms_full, "tokens_per_s": T / (ms_full * 1e-3),
+        "fetch_only_ms": ms_fetch, "fetch_GBps": u0 * w.L * row_elems * 2 / (ms_fetch * 1e-3) / 1e9,
+        "fetch_frac_of_host_link_peak": u0 * w.L * row_elems * 2 / (ms_fetch * 1e-3) / 1e9 / HOST_LINK_GBS,
+        "fetched_bytes_per_step": fetched, "host_table_bytes": int(host.numel() * 2),
+        "forward_reading_host_table_directly_ms": ms_direct,
+    }
+    del host
+    return res
+
+
+def build_bench(torch, mb, wl, acc, stream):
+    w = wl.CONFIGS["offload410m"]
+    g = torch.Generator(device="cuda")
+    g.manual_seed(77)
+    E = torch.randn((w.V, w.d), generator=g, device="cuda").to(torch.bfloat16)
+    W1 = (torch.randn((w.N, w.d, w.D), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+    W2 = (torch.randn((w.N, w.D, w.d), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+    lut = torch.empty((w.V, w.N, w.d), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty((mb.mole_build_lut_workspace(w.V, w.d, w.D, w.N, mb.MOLE_BF16),), dtype=torch.uint8, device="cuda")
+
+    def f(i):
+        mb.mole_build_lut(E, W1, None, W2, None, None, 0.0, lut, w.V, w.d, w.D, w.N, mb.MOLE_BF16, mb.MOLE_GELU_ERF,
+                          ws, stream=stream)
+    ms = time_steps(torch, stream, f, 3, 1)
+    flops = acc.build_flops(w.V, w.d, w.D, w.N)
+    executed = flops * 1.5      # the second GEMM runs over the hi and the lo plane of the hidden activation
+    return {"ms": ms, "algorithmic_TFLOPs": flops / (ms * 1e-3) / 1e12,
+            "algorithmic_frac_of_bf16_mfma_peak": flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "executed_mfma_TFLOPs": executed / (ms * 1e-3) / 1e12,
+            "vocab_rows_per_s": w.V / (ms * 1e-3)}
+
+
+if __name__ == "__main__":
+    main()

@@ -12,7 +12,8 @@ import os
 from typing import Optional
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmole.so")
+# MOLE_LIB overrides the library file (used to compare differently compiled builds)
+LIB_PATH = os.environ.get("MOLE_LIB") or os.path.join(_HERE, "libmole.so")
 
 MOLE_OK, MOLE_EINVAL, MOLE_EUNSUPPORTED, MOLE_EWORKSPACE, MOLE_EHIP = range(5)
 MOLE_F32, MOLE_BF16 = 0, 1

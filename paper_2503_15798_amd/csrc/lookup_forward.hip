@@ -115,13 +115,50 @@ struct Fold {
     }
 };
 
+__device__ __forceinline__ uint4 ld16(const uint16_t *p)
+{
+#ifdef MOLE_NT_ROWS
+    typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+#else
+    return *reinterpret_cast<const uint4 *>(p);
+#endif
+}
+
+// Activations are read once and written once per call.  Stores are always non-temporal; loads are
+// non-temporal (NTA) in the large-batch regime, where keeping them out of L2 / Infinity Cache leaves
+// more room for table rows (which ARE reused across tokens with equal ids).  For small batches the
+// plain load is used: it returns sooner, and latency is what bounds those launches.
+template <bool NTA>
+__device__ __forceinline__ uint4 ld16_stream(const uint16_t *p)
+{
+    if constexpr (NTA) {
+        typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+        return make_uint4(v.x, v.y, v.z, v.w);
+    } else {
+        return *reinterpret_cast<const uint4 *>(p);
+    }
+}
+__device__ __forceinline__ void st16_stream(uint16_t *p, const uint4 &o)
+{
+#ifndef MOLE_PLAIN_STORES
+    typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+    const u32x4 v = {o.x, o.y, o.z, o.w};
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(p));
+#else
+    *reinterpret_cast<uint4 *>(p) = o;
+#endif
+}
+
 template <int N>
 __device__ __forceinline__ void load_rows(uint4 (&r)[N], const uint16_t *rp, int col, int d, bool on)
 {
     if (on) {
 #pragma unroll
         for (int j = 0; j < N; ++j)
-            r[j] = *reinterpret_cast<const uint4 *>(rp + (int64_t)j * d + col);
+            r[j] = ld16(rp + (int64_t)j * d + col);
     } else {
 #pragma unroll
         for (int j = 0; j < N; ++j)
@@ -129,58 +166,132 @@ __device__ __forceinline__ void load_rows(uint4 (&r)[N], const uint16_t *rp, int
     }
 }
 
+// Router weight [d, N] -> LDS as (W[k,j], W[k+1,j]) bf16 pairs; the 16-byte piece holding
+// experts 4*jq..4*jq+3 of k-pair q of k-group kg sits at index (q*N/4 + jq)*kgroups + kg, so
+// that lanes (consecutive kg) read consecutive 16-byte pieces.
+template <int N>
+__device__ __forceinline__ void fill_router_lds(uint4 *smem, const uint16_t *Wr, int kgroups, int nthreads)
+{
+    constexpr int NQ = N / 4;
+    const int n_w4 = kgroups * N;
+    for (int i = threadIdx.x; i < n_w4; i += nthreads) {
+        const int kg = i % kgroups;
+        const int pj = i / kgroups;
+        const int jq = pj % NQ;
+        const int q = pj / NQ;
+        const int k0 = kg * 8 + q * 2;
+        const uint2 w0 = *reinterpret_cast<const uint2 *>(Wr + (int64_t)k0 * N + jq * 4);
+        const uint2 w1 = *reinterpret_cast<const uint2 *>(Wr + (int64_t)(k0 + 1) * N + jq * 4);
+        uint4 v;
+        v.x = (w0.x & 0xffffu) | (w1.x << 16);
+        v.y = (w0.x >> 16) | (w1.x & 0xffff0000u);
+        v.z = (w0.y & 0xffffu) | (w1.y << 16);
+        v.w = (w0.y >> 16) | (w1.y & 0xffff0000u);
+        smem[i] = v;
+    }
+}
+
+// Router equation for one token on one wavefront: returns, in lane l, the gate of expert
+// l / (64/N) (softmax over all N experts of h . r_j).
+template <int N, bool NTA>
+__device__ __forceinline__ float router_gate(const uint4 *smem, int kgroups, const uint16_t *hrow, int d, int lane)
+{
+    constexpr int NQ = N / 4;
+    constexpr int LPJ = 64 / N;
+    float z[N];
+#pragma unroll
+    for (int j = 0; j < N; ++j)
+        z[j] = 0.f;
+    for (int c0 = 0; c0 < d; c0 += 512) {
+        const int cc = c0 + lane * 8;
+        if (cc < d) {
+            const uint4 hv = ld16_stream<NTA>(hrow + cc);
+            const uint32_t hp[4] = {hv.x, hv.y, hv.z, hv.w};
+            const int kg = cc >> 3;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+#pragma unroll
+                for (int jq = 0; jq < NQ; ++jq) {
+                    const uint4 w = smem[(q * NQ + jq) * kgroups + kg];
+                    z[4 * jq + 0] = mac2(z[4 * jq + 0], hp[q], w.x);
+                    z[4 * jq + 1] = mac2(z[4 * jq + 1], hp[q], w.y);
+                    z[4 * jq + 2] = mac2(z[4 * jq + 2], hp[q], w.z);
+                    z[4 * jq + 3] = mac2(z[4 * jq + 3], hp[q], w.w);
+                }
+            }
+        }
+    }
+    const float zz = Fold<N, 32>::run(z, lane);
+    float m = zz;
+#pragma unroll
+    for (int w = 32; w >= LPJ; w >>= 1)
+        m = fmaxf(m, __shfl_xor(m, w));
+    const float e = __expf(zz - m);
+    float s = e;
+#pragma unroll
+    for (int w = 32; w >= LPJ; w >>= 1)
+        s += __shfl_xor(s, w);
+    return e / s;
+}
+
+// acc[0..7] += g * (the 8 bf16 values of one 16-byte piece)
+__device__ __forceinline__ void fma8(float (&acc)[8], float g, const uint4 &rr)
+{
+    acc[0] = fmaf(g, bf16lo(rr.x), acc[0]);
+    acc[1] = fmaf(g, bf16hi(rr.x), acc[1]);
+    acc[2] = fmaf(g, bf16lo(rr.y), acc[2]);
+    acc[3] = fmaf(g, bf16hi(rr.y), acc[3]);
+    acc[4] = fmaf(g, bf16lo(rr.z), acc[4]);
+    acc[5] = fmaf(g, bf16hi(rr.z), acc[5]);
+    acc[6] = fmaf(g, bf16lo(rr.w), acc[6]);
+    acc[7] = fmaf(g, bf16hi(rr.w), acc[7]);
+}
+
+__device__ __forceinline__ void add8(float (&acc)[8], const uint4 &v)
+{
+    acc[0] += bf16lo(v.x);
+    acc[1] += bf16hi(v.x);
+    acc[2] += bf16lo(v.y);
+    acc[3] += bf16hi(v.y);
+    acc[4] += bf16lo(v.z);
+    acc[5] += bf16hi(v.z);
+    acc[6] += bf16lo(v.w);
+    acc[7] += bf16hi(v.w);
+}
+
+__device__ __forceinline__ uint4 pack8(const float (&acc)[8])
+{
+    uint4 o;
+    o.x = pack_bf16(acc[0], acc[1]);
+    o.y = pack_bf16(acc[2], acc[3]);
+    o.z = pack_bf16(acc[4], acc[5]);
+    o.w = pack_bf16(acc[6], acc[7]);
+    return o;
+}
+
 // ------------------------------------------------------------------------------------------
-// bf16 fast path: N in {4, 8, 16, 32, 64}, d % 8 == 0, router weight fits in LDS.
-// grid = (workgroups, L); block = WPB waves.
+// bf16 streaming kernel (no grouping plan): one token per item.  The wave's N row registers
+// are a ring: as soon as row j of the current 512-column chunk has been multiplied in, the
+// same register is re-loaded with row j of the next chunk -- or of the wave's NEXT token when
+// this was the last chunk -- so N-1 16-byte loads per lane stay in flight through the router,
+// the multiply phase and the epilogue alike.
+// N in {4, 8, 16, 32, 64}, d % 8 == 0, router weight fits in LDS.  grid = (workgroups, L).
 // ------------------------------------------------------------------------------------------
-template <int N, int WPB>
+template <int N, int WPB, bool NTA>
 __global__ __launch_bounds__(WPB * 64) __attribute__((amdgpu_waves_per_eu(N <= 16 ? 4 : 2)))
-void fwd_bf16_kernel(FwdArgs a)
+void fwd_bf16_stream_kernel(FwdArgs a)
 {
     extern __shared__ uint4 smem[];
     constexpr int NQ = N / 4;
-    constexpr int LPJ = 64 / N;   // lanes per expert after the fold
+    constexpr int LPJ = 64 / N;
     const int d = a.d;
     const int kgroups = d >> 3;
     const int layer = blockIdx.y;
     const int n_w4 = kgroups * N;
-
-    // router weight -> LDS, as (W[k,j], W[k+1,j]) pairs, piece (q, jq, kg) at [(q*NQ+jq)*kgroups+kg]
-    {
-        const uint16_t *Wr = static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N;
-        for (int i = threadIdx.x; i < n_w4; i += WPB * 64) {
-            const int kg = i % kgroups;
-            const int pj = i / kgroups;
-            const int jq = pj % NQ;
-            const int q = pj / NQ;
-            const int k0 = kg * 8 + q * 2;
-            const uint2 w0 = *reinterpret_cast<const uint2 *>(Wr + (int64_t)k0 * N + jq * 4);
-            const uint2 w1 = *reinterpret_cast<const uint2 *>(Wr + (int64_t)(k0 + 1) * N + jq * 4);
-            uint4 v;
-            v.x = (w0.x & 0xffffu) | (w1.x << 16);
-            v.y = (w0.x >> 16) | (w1.x & 0xffff0000u);
-            v.z = (w0.y & 0xffffu) | (w1.y << 16);
-            v.w = (w0.y >> 16) | (w1.y & 0xffff0000u);
-            smem[i] = v;
-        }
-    }
-    __syncthreads();
-
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
-    float *gl = reinterpret_cast<float *>(smem + n_w4) + wave * (PLAN_GROUP * N);
-    const float4 *gl4 = reinterpret_cast<const float4 *>(gl);
-
-    int n_items = a.T, n_uniq = 0;
-    if (a.plan) {
-        if (a.plan[5] != PLAN_MAGIC || a.plan[2] != a.T) {
-            if (threadIdx.x == 0 && a.err_flag)
-                *a.err_flag = 2;
-            return;
-        }
-        n_items = a.plan[0];
-        n_uniq = a.plan[1];
-    }
+    const int col0 = lane * 8;
+    const int T = a.T;
 
     const uint16_t *table = static_cast<const uint16_t *>(a.table) + (int64_t)layer * a.table_stride;
     const int64_t act_off = (int64_t)layer * a.act_stride;
@@ -188,6 +299,131 @@ void fwd_bf16_kernel(FwdArgs a)
     const uint16_t *sbase = a.shared ? static_cast<const uint16_t *>(a.shared) + act_off : nullptr;
     const uint16_t *rbase = a.residual ? static_cast<const uint16_t *>(a.residual) + act_off : nullptr;
     uint16_t *obase = static_cast<uint16_t *>(a.out) + act_off;
+    const int32_t *rowsrc = a.slot ? a.slot : a.ids;
+    const int stride = gridDim.x * WPB;
+
+    // the first token's rows go in flight before the router weight is staged.  Lanes past the end
+    // of a ragged chunk load a clamped (valid) column; their results are never stored.
+    const int dlast = d - 8;
+    int item = blockIdx.x * WPB + wave;
+    int64_t row = item < T ? (int64_t)__builtin_amdgcn_readfirstlane(rowsrc[item]) : -1;
+    bool valid = row >= 0 && row < a.rows;
+    uint4 r[N];
+    if (valid) {
+        const uint16_t *rp0 = table + row * (int64_t)N * d;
+        const int fcol = min(col0, dlast);
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+            r[j] = ld16(rp0 + (int64_t)j * d + fcol);
+    }
+
+    fill_router_lds<N>(smem, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
+    __syncthreads();
+    float *gl = reinterpret_cast<float *>(smem + n_w4) + wave * (PLAN_GROUP * N);
+    const float4 *gl4 = reinterpret_cast<const float4 *>(gl);
+
+    for (; item < T; item += stride) {
+        const int t = item;
+        const int nitem = item + stride;
+        const int64_t nrow = nitem < T ? (int64_t)__builtin_amdgcn_readfirstlane(rowsrc[nitem]) : -1;
+        const bool nvalid = nrow >= 0 && nrow < a.rows;
+        if (!valid && lane == 0 && a.err_flag)
+            *a.err_flag = 1;
+        if (a.rows_dbg && layer == 0 && lane == 0)
+            a.rows_dbg[t] = valid ? row : -1;
+
+        const float g = router_gate<N, NTA>(smem, kgroups, hbase + (int64_t)t * d, d, lane);
+        if ((lane & (LPJ - 1)) == 0) {
+            gl[lane / LPJ] = g;
+            if (a.gates_dbg)
+                a.gates_dbg[((int64_t)layer * T + t) * N + lane / LPJ] = g;
+        }
+        wave_lds_fence();
+
+        const uint16_t *rp = table + (valid ? row : 0) * (int64_t)N * d;
+        const uint16_t *nrp = table + (nvalid ? nrow : 0) * (int64_t)N * d;
+        for (int c0 = 0; c0 < d; c0 += 512) {
+            const int cc = c0 + col0;
+            const bool on = cc < d;
+            const bool last = c0 + 512 >= d;
+            const int64_t off = (int64_t)t * d + cc;
+            uint4 sv = make_uint4(0, 0, 0, 0), rv = make_uint4(0, 0, 0, 0);
+            if (on && sbase)
+                sv = ld16_stream<NTA>(sbase + off);
+            if (on && rbase)
+                rv = ld16_stream<NTA>(rbase + off);
+            float acc[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                acc[e] = 0.f;
+            if (valid) {
+#pragma unroll
+                for (int jq = 0; jq < NQ; ++jq) {
+                    const float4 g4 = gl4[jq];
+                    fma8(acc, g4.x, r[4 * jq + 0]);
+                    fma8(acc, g4.y, r[4 * jq + 1]);
+                    fma8(acc, g4.z, r[4 * jq + 2]);
+                    fma8(acc, g4.w, r[4 * jq + 3]);
+                }
+            }
+            // refill the ring: next chunk of this token, or chunk 0 of the wave's next token
+            const uint16_t *fb = last ? nrp : rp;                      // wave-uniform
+            const int fcol = min(last ? col0 : cc + 512, dlast);
+            if (last ? nvalid : valid) {
+#pragma unroll
+                for (int j = 0; j < N; ++j)
+                    r[j] = ld16(fb + (int64_t)j * d + fcol);
+            }
+            add8(acc, sv);
+            add8(acc, rv);
+            if (on)
+                st16_stream(obase + off, pack8(acc));
+        }
+        wave_lds_fence();
+        row = nrow;
+        valid = nvalid;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// bf16 grouped kernel (plan of mole_dedup_ids): an item is one row block and the 1..8 tokens
+// that read it; the rows of a chunk are loaded once and multiplied for every token of the item.
+// ------------------------------------------------------------------------------------------
+template <int N, int WPB, bool NTA>
+__global__ __launch_bounds__(WPB * 64) __attribute__((amdgpu_waves_per_eu(N <= 16 ? 4 : 2)))
+void fwd_bf16_grouped_kernel(FwdArgs a)
+{
+    extern __shared__ uint4 smem[];
+    constexpr int NQ = N / 4;
+    constexpr int LPJ = 64 / N;
+    const int d = a.d;
+    const int kgroups = d >> 3;
+    const int layer = blockIdx.y;
+    const int n_w4 = kgroups * N;
+
+    fill_router_lds<N>(smem, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
+    __syncthreads();
+
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    float *gl = reinterpret_cast<float *>(smem + n_w4) + wave * (PLAN_GROUP * N);
+    const float4 *gl4 = reinterpret_cast<const float4 *>(gl);
+
+    if (a.plan[5] != PLAN_MAGIC || a.plan[2] != a.T) {
+        if (threadIdx.x == 0 && a.err_flag)
+            *a.err_flag = 2;
+        return;
+    }
+    const int n_items = a.plan[0];
+    const int n_uniq = a.plan[1];
+
+    const uint16_t *table = static_cast<const uint16_t *>(a.table) + (int64_t)layer * a.table_stride;
+    const int64_t act_off = (int64_t)layer * a.act_stride;
+    const uint16_t *hbase = static_cast<const uint16_t *>(a.h) + act_off;
+    const uint16_t *sbase = a.shared ? static_cast<const uint16_t *>(a.shared) + act_off : nullptr;
+    const uint16_t *rbase = a.residual ? static_cast<const uint16_t *>(a.residual) + act_off : nullptr;
+    uint16_t *obase = static_cast<uint16_t *>(a.out) + act_off;
+    const int col0 = lane * 8;
 
     for (int item = blockIdx.x * WPB + wave; item < n_items; item += gridDim.x * WPB) {
         const Item it = get_item(a, item, n_uniq);
@@ -198,58 +434,21 @@ void fwd_bf16_kernel(FwdArgs a)
 
         // rows of the first 512-column chunk: in flight while the router runs
         uint4 r[N];
-        const int col0 = lane * 8;
         load_rows<N>(r, rp, col0, d, valid && col0 < d);
 
-        // ---- router + softmax for each token of the item ----
         for (int i = 0; i < it.cnt; ++i) {
             const int t = item_token(a, it, i);
-            float z[N];
-#pragma unroll
-            for (int j = 0; j < N; ++j)
-                z[j] = 0.f;
-            for (int c0 = 0; c0 < d; c0 += 512) {
-                const int cc = c0 + col0;
-                if (cc < d) {
-                    const uint4 hv = *reinterpret_cast<const uint4 *>(hbase + (int64_t)t * d + cc);
-                    const uint32_t hp[4] = {hv.x, hv.y, hv.z, hv.w};
-                    const int kg = cc >> 3;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-#pragma unroll
-                        for (int jq = 0; jq < NQ; ++jq) {
-                            const uint4 w = smem[(q * NQ + jq) * kgroups + kg];
-                            z[4 * jq + 0] = mac2(z[4 * jq + 0], hp[q], w.x);
-                            z[4 * jq + 1] = mac2(z[4 * jq + 1], hp[q], w.y);
-                            z[4 * jq + 2] = mac2(z[4 * jq + 2], hp[q], w.z);
-                            z[4 * jq + 3] = mac2(z[4 * jq + 3], hp[q], w.w);
-                        }
-                    }
-                }
-            }
-            const float zz = Fold<N, 32>::run(z, lane);   // logit of expert lane / LPJ
-            float m = zz;
-#pragma unroll
-            for (int w = 32; w >= LPJ; w >>= 1)
-                m = fmaxf(m, __shfl_xor(m, w));
-            const float e = __expf(zz - m);
-            float s = e;
-#pragma unroll
-            for (int w = 32; w >= LPJ; w >>= 1)
-                s += __shfl_xor(s, w);
-            const float g = e / s;
+            const float g = router_gate<N, NTA>(smem, kgroups, hbase + (int64_t)t * d, d, lane);
             if ((lane & (LPJ - 1)) == 0) {
-                const int j = lane / LPJ;
-                gl[i * N + j] = g;
+                gl[i * N + lane / LPJ] = g;
                 if (a.gates_dbg)
-                    a.gates_dbg[((int64_t)layer * a.T + t) * N + j] = g;
+                    a.gates_dbg[((int64_t)layer * a.T + t) * N + lane / LPJ] = g;
             }
             if (a.rows_dbg && layer == 0 && lane == 0)
                 a.rows_dbg[t] = valid ? it.row : -1;
         }
         wave_lds_fence();
 
-        // ---- gate-weighted sum of the rows, adds, store ----
         for (int c0 = 0; c0 < d; c0 += 512) {
             const int cc = c0 + col0;
             const bool on = cc < d;
@@ -260,9 +459,9 @@ void fwd_bf16_kernel(FwdArgs a)
                 const int64_t off = (int64_t)t * d + cc;
                 uint4 sv = make_uint4(0, 0, 0, 0), rv = make_uint4(0, 0, 0, 0);
                 if (on && sbase)
-                    sv = *reinterpret_cast<const uint4 *>(sbase + off);
+                    sv = ld16_stream<NTA>(sbase + off);
                 if (on && rbase)
-                    rv = *reinterpret_cast<const uint4 *>(rbase + off);
+                    rv = ld16_stream<NTA>(rbase + off);
                 float acc[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
@@ -272,34 +471,13 @@ void fwd_bf16_kernel(FwdArgs a)
                     const float4 g4 = gl4[i * NQ + jq];
                     const float gg[4] = {g4.x, g4.y, g4.z, g4.w};
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const uint4 rr = r[4 * jq + e];
-                        acc[0] = fmaf(gg[e], bf16lo(rr.x), acc[0]);
-                        acc[1] = fmaf(gg[e], bf16hi(rr.x), acc[1]);
-                        acc[2] = fmaf(gg[e], bf16lo(rr.y), acc[2]);
-                        acc[3] = fmaf(gg[e], bf16hi(rr.y), acc[3]);
-                        acc[4] = fmaf(gg[e], bf16lo(rr.z), acc[4]);
-                        acc[5] = fmaf(gg[e], bf16hi(rr.z), acc[5]);
-                        acc[6] = fmaf(gg[e], bf16lo(rr.w), acc[6]);
-                        acc[7] = fmaf(gg[e], bf16hi(rr.w), acc[7]);
-                    }
+                    for (int e = 0; e < 4; ++e)
+                        fma8(acc, gg[e], r[4 * jq + e]);
                 }
-                acc[0] += bf16lo(sv.x) + bf16lo(rv.x);
-                acc[1] += bf16hi(sv.x) + bf16hi(rv.x);
-                acc[2] += bf16lo(sv.y) + bf16lo(rv.y);
-                acc[3] += bf16hi(sv.y) + bf16hi(rv.y);
-                acc[4] += bf16lo(sv.z) + bf16lo(rv.z);
-                acc[5] += bf16hi(sv.z) + bf16hi(rv.z);
-                acc[6] += bf16lo(sv.w) + bf16lo(rv.w);
-                acc[7] += bf16hi(sv.w) + bf16hi(rv.w);
-                if (on) {
-                    uint4 o;
-                    o.x = pack_bf16(acc[0], acc[1]);
-                    o.y = pack_bf16(acc[2], acc[3]);
-                    o.z = pack_bf16(acc[4], acc[5]);
-                    o.w = pack_bf16(acc[6], acc[7]);
-                    *reinterpret_cast<uint4 *>(obase + off) = o;
-                }
+                add8(acc, sv);
+                add8(acc, rv);
+                if (on)
+                    st16_stream(obase + off, pack8(acc));
             }
         }
         wave_lds_fence();
@@ -418,32 +596,50 @@ int env_int(const char *name, int dflt)
     return v > 0 ? v : dflt;
 }
 
+// Grid shape.  Every wave should get the same number of items, and all workgroups should be
+// resident at once (a second round would stage the router weight again and leave CUs idle at the
+// tail).  Residency per CU is bounded by LDS and by registers (4 waves per SIMD for N <= 16,
+// 2 above).  Returns the number of workgroups per layer.
 template <int N, int WPB>
-mole_status launch_fast(const FwdArgs &a, int items_bound, hipStream_t stream)
+int64_t grid_x(int items, int L, size_t lds)
 {
-    const size_t lds = (size_t)a.d * N * 2 + (size_t)WPB * PLAN_GROUP * N * 4;
-    static size_t attr_set = 0;
-    if (lds > attr_set) {
-        MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_bf16_kernel<N, WPB>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = lds;
-    }
     int per_cu = (int)(LDS_BYTES_PER_CU / lds);
-    const int wave_cap = 32 / WPB;   // at most 8 waves per SIMD
+    const int wave_cap = (N <= 16 ? 16 : 8) / WPB;
     if (per_cu > wave_cap)
         per_cu = wave_cap;
     per_cu = env_int("MOLE_FWD_WGS_PER_CU", per_cu);
     if (per_cu < 1)
         per_cu = 1;
-    int64_t resident = (int64_t)num_cus() * per_cu;
-    int64_t gx = (items_bound + WPB - 1) / WPB;
-    int64_t cap = resident / a.L;
+    const int64_t resident = (int64_t)num_cus() * per_cu;
+    int64_t cap = resident / L;
     if (cap < 1)
         cap = 1;
-    if (gx > cap)
-        gx = cap;
-    dim3 grid((unsigned)gx, (unsigned)a.L);
-    hipLaunchKernelGGL((fwd_bf16_kernel<N, WPB>), grid, dim3(WPB * 64), lds, stream, a);
+    // smallest items-per-wave whose grid fits: ceil(items / (WPB * ipw)) <= cap
+    int64_t gx = (items + WPB - 1) / WPB;
+    if (gx > cap) {
+        const int64_t ipw = (items + cap * WPB - 1) / (cap * WPB);
+        gx = (items + WPB * ipw - 1) / (WPB * ipw);
+    }
+    return gx < 1 ? 1 : gx;
+}
+
+template <int N, int WPB, bool NTA>
+mole_status launch_fast(const FwdArgs &a, int items_bound, hipStream_t stream)
+{
+    const size_t lds = (size_t)a.d * N * 2 + (size_t)WPB * PLAN_GROUP * N * 4;
+    static size_t attr_set = 0;
+    if (lds > attr_set) {
+        MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_bf16_stream_kernel<N, WPB, NTA>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_bf16_grouped_kernel<N, WPB, NTA>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = lds;
+    }
+    dim3 grid((unsigned)grid_x<N, WPB>(items_bound, a.L, lds), (unsigned)a.L);
+    if (a.plan)
+        hipLaunchKernelGGL((fwd_bf16_grouped_kernel<N, WPB, NTA>), grid, dim3(WPB * 64), lds, stream, a);
+    else
+        hipLaunchKernelGGL((fwd_bf16_stream_kernel<N, WPB, NTA>), grid, dim3(WPB * 64), lds, stream, a);
     MOLE_HIP_CHECK(hipGetLastError());
     return MOLE_OK;
 }
@@ -454,14 +650,12 @@ mole_status launch_fast_n(const FwdArgs &a, int items_bound, hipStream_t stream)
     // wider workgroups when the router weight is large, so that LDS does not cap occupancy
     const size_t wbytes = (size_t)a.d * N * 2;
     int wpb = wbytes > 40 * 1024 ? 8 : 4;
-    if (wbytes > 80 * 1024)
-        wpb = 16;
     wpb = env_int("MOLE_FWD_WPB", wpb);
-    switch (wpb) {
-    case 16: return launch_fast<N, 16>(a, items_bound, stream);
-    case 8: return launch_fast<N, 8>(a, items_bound, stream);
-    default: return launch_fast<N, 4>(a, items_bound, stream);
-    }
+    // large batches: keep the read-once activations out of the caches
+    const bool nta = env_int("MOLE_FWD_NTA", (int64_t)a.T * a.L >= 8192 ? 1 : 2) == 1;
+    if (wpb >= 8)
+        return nta ? launch_fast<N, 8, true>(a, items_bound, stream) : launch_fast<N, 8, false>(a, items_bound, stream);
+    return nta ? launch_fast<N, 4, true>(a, items_bound, stream) : launch_fast<N, 4, false>(a, items_bound, stream);
 }
 
 mole_status forward_impl(const void *table, int64_t table_stride, const int32_t *ids, const int32_t *slot,
@@ -518,7 +712,7 @@ mole_status forward_impl(const void *table, int64_t table_stride, const int32_t 
     a.T = T; a.d = d; a.N = N; a.L = L;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
-    const size_t lds_fast = (size_t)d * N * 2 + (size_t)16 * PLAN_GROUP * N * 4;
+    const size_t lds_fast = (size_t)d * N * 2 + (size_t)8 * PLAN_GROUP * N * 4;
     const bool fast = dtype == MOLE_BF16 && lds_fast <= LDS_BYTES_PER_CU && !getenv("MOLE_FWD_GENERIC");
     if (fast) {
         switch (N) {
