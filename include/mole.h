@@ -49,7 +49,8 @@ typedef enum { MOLE_GELU_ERF = 0, MOLE_GELU_TANH = 1 } mole_act;
 
 enum {
     MOLE_FLAG_DEDUP = 1u    /* forward: `workspace` holds a plan written by mole_dedup_ids for
-                               these ids; each distinct id's rows are read once per group      */
+                               these ids; tokens are visited in id order so that a distinct id's
+                               rows cross the memory fabric once                               */
 };
 
 /* Message of the last failing call on this thread ("" if none).  Never NULL. */
@@ -84,8 +85,8 @@ mole_status mole_build_lut(const void *E, const void *W1, const void *b1,
  *     uniq  = the distinct in-range ids, ascending        [T] dev out, first *n_uniq valid
  *     inv[t] = index of ids[t] in uniq, -1 if out of range [T] dev out
  *     *n_uniq = U                                          [1] dev out
- * and, in `workspace`, a grouping plan for mole_lookup_forward(MOLE_FLAG_DEDUP): the tokens of
- * each distinct id, cut into bounded groups.  One workgroup, presence bitmap in LDS.
+ * and, in `workspace`, a plan for mole_lookup_forward(MOLE_FLAG_DEDUP): the token indices sorted
+ * by id, each marked if its id occurs once.  One workgroup, presence bitmap in LDS.
  * V <= 524288.  err_flag: [1] dev nullable, set to 1 if any id is outside [0, V).
  * workspace: dev, at least mole_dedup_workspace(T, V) bytes.
  * ---------------------------------------------------------------------------------------- */

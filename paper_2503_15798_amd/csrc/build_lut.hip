@@ -26,6 +26,7 @@ using namespace mole;
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // native vector: stays in registers
 
 constexpr int BM = 256, BN = 128, BK = 64;
 constexpr int LDS_ROW = BK * 2 + 16;   // bytes per tile row in LDS
@@ -56,7 +57,11 @@ __device__ __forceinline__ float gelu_f(float x, int act)
     return 0.5f * x * (1.0f + erff(x * 0.7071067811865476f));
 }
 
-__device__ __forceinline__ void gemm_fetch(uint4 (&ra)[8], uint4 (&rb)[4], const GemmArgs &g, const uint16_t *A,
+struct BStage {
+    u32x4 b0, b1, b2, b3;
+};
+
+__device__ __forceinline__ void gemm_fetch(u32x4 (&ra)[8], BStage &rb, const GemmArgs &g, const uint16_t *A,
                                            const uint16_t *Bt, int kt, int ktiles_per_plane, int m0, int n0,
                                            int prow, int pk)
 {
@@ -66,28 +71,30 @@ __device__ __forceinline__ void gemm_fetch(uint4 (&ra)[8], uint4 (&rb)[4], const
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int row = m0 + prow + i * 32;
-        ra[i] = row < g.M ? *reinterpret_cast<const uint4 *>(Ap + (int64_t)row * g.lda + kk)
-                          : make_uint4(0, 0, 0, 0);
+        ra[i] = row < g.M ? *reinterpret_cast<const u32x4 *>(Ap + (int64_t)row * g.lda + kk) : u32x4{0, 0, 0, 0};
     }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = n0 + prow + i * 32;
-        rb[i] = *reinterpret_cast<const uint4 *>(Bt + (int64_t)row * g.ldb + kk);
-    }
+    const uint16_t *Bp = Bt + (int64_t)(n0 + prow) * g.ldb + kk;
+    rb.b0 = *reinterpret_cast<const u32x4 *>(Bp);
+    rb.b1 = *reinterpret_cast<const u32x4 *>(Bp + 32 * g.ldb);
+    rb.b2 = *reinterpret_cast<const u32x4 *>(Bp + 64 * g.ldb);
+    rb.b3 = *reinterpret_cast<const u32x4 *>(Bp + 96 * g.ldb);
 }
 
-__device__ __forceinline__ void gemm_stash(const uint4 (&ra)[8], const uint4 (&rb)[4], unsigned char *As,
+__device__ __forceinline__ void gemm_stash(const u32x4 (&ra)[8], const BStage &rb, unsigned char *As,
                                            unsigned char *Bs, int prow, int pk)
 {
 #pragma unroll
     for (int i = 0; i < 8; ++i)
-        *reinterpret_cast<uint4 *>(As + (prow + i * 32) * LDS_ROW + pk * 16) = ra[i];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-        *reinterpret_cast<uint4 *>(Bs + (prow + i * 32) * LDS_ROW + pk * 16) = rb[i];
+        *reinterpret_cast<u32x4 *>(As + (prow + i * 32) * LDS_ROW + pk * 16) = ra[i];
+    unsigned char *bp = Bs + prow * LDS_ROW + pk * 16;
+    *reinterpret_cast<u32x4 *>(bp) = rb.b0;
+    *reinterpret_cast<u32x4 *>(bp + 32 * LDS_ROW) = rb.b1;
+    *reinterpret_cast<u32x4 *>(bp + 64 * LDS_ROW) = rb.b2;
+    *reinterpret_cast<u32x4 *>(bp + 96 * LDS_ROW) = rb.b3;
 }
 
-__global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_bf16_kernel(GemmArgs g)
+__global__ __launch_bounds__(GEMM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void gemm_nt_bf16_kernel(GemmArgs g)
 {
     __shared__ __attribute__((aligned(16))) unsigned char As[BM * LDS_ROW];
     __shared__ __attribute__((aligned(16))) unsigned char Bs[BN * LDS_ROW];
@@ -109,7 +116,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_bf16_kernel(GemmArgs g)
                 acc[i][j][e] = 0.f;
 
     // staging registers: A tile = 256 rows x 8 pieces -> 8 per thread; B tile = 128 x 8 -> 4
-    uint4 ra[8], rb[4];
+    u32x4 ra[8];
+    BStage rb;
     const int prow = tid >> 3, pk = tid & 7;   // piece (row, 16-byte column) for i = 0; +32 rows per i
     const int ktiles_per_plane = g.K / BK;
     const int ktiles = ktiles_per_plane * g.a_planes;

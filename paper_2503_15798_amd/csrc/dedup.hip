@@ -1,17 +1,17 @@
-// mole_dedup_ids: distinct token ids of a batch (ascending), the inverse map, and a grouping
-// plan for the forward kernels.
+// mole_dedup_ids: distinct token ids of a batch (ascending), the inverse map, and a visiting
+// plan (tokens in id order) for the forward kernels.
 //
 // The paper's lookup (inference listing, the lut(input_ids) line) simply indexes the table once
 // per token; repeated ids in a batch therefore re-read the same N rows.  This kernel finds the
-// distinct ids so that each row block is read once per group of tokens (and, in offloaded mode,
-// crosses the host link once).
+// distinct ids so that each row block crosses the memory fabric once (and, in offloaded mode,
+// the host link once).
 //
 // One workgroup.  A V-bit presence bitmap sits in LDS (V = 50304 -> 6.3 KB): every id sets its
 // bit with an LDS atomic OR; a popcount prefix over the bitmap words then gives each present id
 // its rank, which is already the position in ascending order -- no sort.  Tokens are then
-// bucketed by rank with a counting pass (LDS counters when they fit), and every bucket is cut
-// into groups of at most PLAN_GROUP tokens so that one very frequent id (Zipf head) becomes
-// many bounded work items instead of one long one.
+// bucketed by rank with a counting pass (LDS counters when they fit) and scattered, which yields
+// the token indices in id order: the forward kernel walks that order so that equal ids are
+// processed next to each other (same workgroup, same L2) and marks ids that occur once.
 #include "mole_internal.h"
 
 namespace {
@@ -19,6 +19,7 @@ using namespace mole;
 
 constexpr int DEDUP_THREADS = 1024;
 constexpr int64_t DEDUP_MAX_V = 524288;
+constexpr int BATCH = 8;   // independent loads per thread and pass
 
 // exclusive scan of one value per thread over the workgroup; *total gets the sum
 __device__ __forceinline__ int block_exclusive_scan(int v, int *wave_sums, int *total)
@@ -57,7 +58,7 @@ __global__ __launch_bounds__(DEDUP_THREADS) void dedup_kernel(const int32_t *__r
                                                                 int32_t *__restrict__ inv_out,
                                                                 int32_t *__restrict__ n_uniq_out,
                                                                 int32_t *err_flag, int32_t *plan,
-                                                                int lds_counters)
+                                                                int lds_counters, int lds_stage)
 {
     extern __shared__ uint32_t sm[];
     __shared__ int wave_sums[DEDUP_THREADS / 64];
@@ -67,6 +68,10 @@ __global__ __launch_bounds__(DEDUP_THREADS) void dedup_kernel(const int32_t *__r
     int *prefix = reinterpret_cast<int *>(sm + W);
     const PlanLayout pl = plan_layout(T);
     int *counters = lds_counters ? reinterpret_cast<int *>(sm + 2 * W) : plan + pl.counters;
+    // staging area for scattered results (first the distinct ids, then the token order): a single
+    // CU issues scattered 4-byte global stores one address at a time, so they are gathered in LDS
+    // and written out as full wave-wide stores
+    int *stage = lds_stage ? reinterpret_cast<int *>(sm + 2 * W) + (T + 2) : nullptr;
     const int tid = threadIdx.x;
 
     for (int w = tid; w < W; w += DEDUP_THREADS)
@@ -77,14 +82,27 @@ __global__ __launch_bounds__(DEDUP_THREADS) void dedup_kernel(const int32_t *__r
         s_bad = 0;
     __syncthreads();
 
+    // Every pass over the tokens reads them in batches of BATCH independent loads per thread, so
+    // that a thread pays one memory latency per batch instead of one per token.
     // 1. presence bits
     int bad = 0;
-    for (int t = tid; t < T; t += DEDUP_THREADS) {
-        const int id = ids[t];
-        if (id < 0 || id >= V)
-            bad = 1;
-        else
-            atomicOr(&bitmap[id >> 5], 1u << (id & 31));
+    for (int t0 = tid; t0 < T; t0 += DEDUP_THREADS * BATCH) {
+        int idv[BATCH];
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int t = t0 + u * DEDUP_THREADS;
+            idv[u] = t < T ? ids[t] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int id = idv[u];
+            if (t0 + u * DEDUP_THREADS >= T)
+                continue;
+            if (id < 0 || id >= V)
+                bad = 1;
+            else if (!(__atomic_load_n(&bitmap[id >> 5], __ATOMIC_RELAXED) & (1u << (id & 31))))
+                atomicOr(&bitmap[id >> 5], 1u << (id & 31));   // skipped once the bit is seen set: hot ids
+        }
     }
     if (bad)
         s_bad = 1;
@@ -105,62 +123,104 @@ __global__ __launch_bounds__(DEDUP_THREADS) void dedup_kernel(const int32_t *__r
             const int b = __ffs(bits) - 1;
             bits &= bits - 1;
             const int id = (w << 5) + b;
-            uniq_out[run] = id;
-            plan[pl.uniq + run] = id;
+            if (stage) {
+                stage[run] = id;
+            } else {
+                uniq_out[run] = id;
+                plan[pl.uniq + run] = id;
+            }
             ++run;
         }
     }
     __syncthreads();
+    if (stage) {
+        for (int i = tid; i < U; i += DEDUP_THREADS) {
+            const int id = stage[i];
+            uniq_out[i] = id;
+            plan[pl.uniq + i] = id;
+        }
+        // the staging area is reused for the token order; the barrier after pass 4 separates the two
+    }
 
     // 4. inverse map and bucket sizes; bucket U collects the out-of-range tokens
-    for (int t = tid; t < T; t += DEDUP_THREADS) {
-        const int id = ids[t];
-        int r = -1;
-        if (id >= 0 && id < V)
-            r = prefix[id >> 5] + __popc(bitmap[id >> 5] & ((1u << (id & 31)) - 1u));
-        inv_out[t] = r;
-        atomicAdd(&counters[r < 0 ? U : r], 1);
+    for (int t0 = tid; t0 < T; t0 += DEDUP_THREADS * BATCH) {
+        int idv[BATCH];
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int t = t0 + u * DEDUP_THREADS;
+            idv[u] = t < T ? ids[t] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int t = t0 + u * DEDUP_THREADS;
+            if (t >= T)
+                continue;
+            const int id = idv[u];
+            int r = -1;
+            if (id >= 0 && id < V)
+                r = prefix[id >> 5] + __popc(bitmap[id >> 5] & ((1u << (id & 31)) - 1u));
+            inv_out[t] = r;
+            atomicAdd(&counters[r < 0 ? U : r], 1);
+        }
     }
     __syncthreads();
 
-    // 5. bucket offsets and work items: a bucket of c tokens becomes ceil(c / PLAN_GROUP) items
+    // 5. bucket offsets: exclusive scan of the bucket sizes; counters become write cursors
     const int B = U + 1;
     const int perb = (B + DEDUP_THREADS - 1) / DEDUP_THREADS;
     const int b0 = min(tid * perb, B), b1 = min(b0 + perb, B);
-    int tok = 0, itm = 0;
-    for (int b = b0; b < b1; ++b) {
-        const int c = counters[b];
-        tok += c;
-        itm += (c + PLAN_GROUP - 1) / PLAN_GROUP;
-    }
-    int n_items = 0;
+    int tok = 0;
+    for (int b = b0; b < b1; ++b)
+        tok += counters[b];
     int tok_run = block_exclusive_scan(tok, wave_sums, nullptr);
-    int itm_run = block_exclusive_scan(itm, wave_sums, &n_items);
     for (int b = b0; b < b1; ++b) {
         const int c = counters[b];
-        counters[b] = tok_run;               // becomes the bucket's write cursor
-        for (int s = 0; s < c; s += PLAN_GROUP) {
-            plan[pl.item_u + itm_run] = b;
-            plan[pl.item_begin + itm_run] = tok_run + s;
-            plan[pl.item_cnt + itm_run] = min(PLAN_GROUP, c - s);
-            ++itm_run;
-        }
+        counters[b] = tok_run;
+        plan[pl.start + b] = tok_run;
         tok_run += c;
     }
+    if (tid == 0)
+        plan[pl.start + B] = T;
     __syncthreads();
 
     // 6. scatter token indices into their buckets (order inside a bucket is irrelevant)
-    for (int t = tid; t < T; t += DEDUP_THREADS) {
-        const int r = inv_out[t];
-        const int pos = atomicAdd(&counters[r < 0 ? U : r], 1);
-        plan[pl.order + pos] = t;
+    for (int t0 = tid; t0 < T; t0 += DEDUP_THREADS * BATCH) {
+        int rv[BATCH], pos[BATCH], cnt[BATCH];
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int t = t0 + u * DEDUP_THREADS;
+            rv[u] = t < T ? inv_out[t] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int b = rv[u] < 0 ? U : rv[u];
+            const bool live = t0 + u * DEDUP_THREADS < T;
+            pos[u] = live ? atomicAdd(&counters[b], 1) : 0;
+            cnt[u] = live ? plan[pl.start + b + 1] - plan[pl.start + b] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int t = t0 + u * DEDUP_THREADS;
+            if (t < T) {
+                const int val = (int)((uint32_t)t | (rv[u] >= 0 && cnt[u] == 1 ? PLAN_SINGLE : 0u));
+                if (stage)
+                    stage[pos[u]] = val;
+                else
+                    plan[pl.order + pos[u]] = val;
+            }
+        }
+    }
+    if (stage) {
+        __syncthreads();
+        for (int i = tid; i < T; i += DEDUP_THREADS)
+            plan[pl.order + i] = stage[i];
     }
 
     if (tid == 0) {
-        plan[0] = n_items;
-        plan[1] = U;
+        plan[0] = U;
+        plan[1] = 0;
         plan[2] = T;
-        plan[3] = PLAN_GROUP;
+        plan[3] = 0;
         plan[4] = V;
         plan[5] = PLAN_MAGIC;
         *n_uniq_out = U;
@@ -169,13 +229,17 @@ __global__ __launch_bounds__(DEDUP_THREADS) void dedup_kernel(const int32_t *__r
     }
 }
 
-size_t dedup_lds_bytes(int T, int64_t V, int *lds_counters)
+// LDS plan: bitmap and prefix always; the counters and the staging area when they fit
+size_t dedup_lds_bytes(int T, int64_t V, int *lds_counters, int *lds_stage)
 {
     const size_t W = (size_t)((V + 31) / 32);
-    size_t bytes = 2 * W * 4;
-    const size_t with_counters = bytes + (size_t)(T + 2) * 4;
-    *lds_counters = with_counters <= 150 * 1024;
-    return *lds_counters ? with_counters : bytes;
+    const size_t limit = 156 * 1024;
+    const size_t base = 2 * W * 4;
+    const size_t with_counters = base + (size_t)(T + 2) * 4;
+    const size_t with_stage = with_counters + (size_t)(T + 2) * 4;
+    *lds_counters = with_counters <= limit;
+    *lds_stage = with_stage <= limit;
+    return *lds_stage ? with_stage : (*lds_counters ? with_counters : base);
 }
 
 }  // namespace
@@ -206,8 +270,8 @@ extern "C" mole_status mole_dedup_ids(const int32_t *ids, int T, int64_t V, int3
                     workspace ? workspace_bytes : (size_t)0);
     if (!aligned16(workspace))
         return fail(MOLE_EINVAL, "mole_dedup_ids: workspace is not 16-byte aligned");
-    int lds_counters = 0;
-    const size_t lds = dedup_lds_bytes(T, V, &lds_counters);
+    int lds_counters = 0, lds_stage = 0;
+    const size_t lds = dedup_lds_bytes(T, V, &lds_counters, &lds_stage);
     static size_t attr_set = 0;
     if (lds > attr_set) {
         MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&dedup_kernel),
@@ -216,7 +280,7 @@ extern "C" mole_status mole_dedup_ids(const int32_t *ids, int T, int64_t V, int3
     }
     hipLaunchKernelGGL(dedup_kernel, dim3(1), dim3(DEDUP_THREADS), lds, static_cast<hipStream_t>(hip_stream),
                        ids, T, (int)V, uniq, inv, n_uniq, err_flag, static_cast<int32_t *>(workspace),
-                       lds_counters);
+                       lds_counters, lds_stage);
     MOLE_HIP_CHECK(hipGetLastError());
     return MOLE_OK;
 }

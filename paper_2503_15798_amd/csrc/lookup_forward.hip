@@ -4,18 +4,19 @@
 // (inference-layer equation: h' = sum_j g_j v^id_j + FFN_shared(h) + h).
 //
 // The path is bound by HBM bandwidth (about 1.7 flop per byte), so there is no MFMA here.
-// Work unit = one "item": a block of N table rows (one token id) plus the 1..8 tokens that
-// read it.  One 64-lane wavefront owns an item:
+// One 64-lane wavefront owns a token:
 //   * lane l owns columns [512*c + 8*l, +8) of every row: every table access is a 16-byte
-//     load, a wavefront covers 1 KiB of a row per load, and all N loads of a 512-column chunk
-//     are issued back to back before anything waits on them;
+//     load and a wavefront covers 1 KiB of a row per load;
+//   * the N row registers form a ring that is refilled as it is consumed (next 512-column
+//     chunk, or the wave's next token), so N loads per lane are in flight at all times;
 //   * the router weight lives in LDS for the life of the workgroup, stored as (k, k+1) bf16
-//     pairs so that the lane's 16-byte piece of h meets it without repacking; the N partial
+//     pairs so that the lane's 16-byte piece of h meets it without repacking
+//     (v_dot2_f32_bf16: two multiply-adds per instruction, fp32 accumulation); the N partial
 //     logits of the 64 lanes are folded with a halving butterfly (N/2 + N/4 + ... exchanges
-//     instead of 6 per logit), softmax runs on the folded values, gates go to a per-wave LDS
-//     slot;
+//     instead of 6 per logit), softmax runs on the folded values, gates move to scalar
+//     registers with v_readlane;
 //   * the combine multiplies from registers and adds shared / residual in the epilogue, with
-//     a single round-to-nearest-even to bf16 at the store.
+//     a single round-to-nearest-even to bf16 at the (non-temporal) store.
 // Waves never synchronise with each other after the router weight is in LDS.
 #include "mole_internal.h"
 
@@ -41,52 +42,43 @@ struct FwdArgs {
     int T, d, N, L;
 };
 
-struct Item {
-    int64_t row;   // row block index, or -1
-    int begin;     // first token (index into `order` when planned, token index otherwise)
-    int cnt;
+// Visiting order.  Without a plan token i is item i.  With the plan of mole_dedup_ids the tokens
+// are visited in id order, so equal ids are adjacent in time and place (same workgroup, same
+// XCD): the repeats of a row block are then served by that L2 instead of crossing the fabric
+// again.  `single` is true when the plan says the id occurs once in the batch.
+struct Visit {
+    int t;
+    bool single;
 };
-
-// Decode item `item`.  Planned: groups written by mole_dedup_ids; otherwise one token per item.
-__device__ __forceinline__ Item get_item(const FwdArgs &a, int item, int n_uniq)
+__device__ __forceinline__ Visit visit(const int32_t *order, int item)
 {
-    Item it;
-    if (a.plan) {
-        const PlanLayout pl = plan_layout(a.T);
-        const int u = a.plan[pl.item_u + item];
-        it.begin = a.plan[pl.item_begin + item];
-        it.cnt = a.plan[pl.item_cnt + item];
-        it.row = (u >= n_uniq) ? -1 : (a.slot ? (int64_t)u : (int64_t)a.plan[pl.uniq + u]);
+    Visit v;
+    if (order) {
+        const uint32_t o = (uint32_t)__builtin_amdgcn_readfirstlane(order[item]);
+        v.t = (int)(o & ~PLAN_SINGLE);
+        v.single = (o & PLAN_SINGLE) != 0;
     } else {
-        it.row = a.slot ? a.slot[item] : a.ids[item];
-        it.begin = item;
-        it.cnt = 1;
+        v.t = item;
+        v.single = false;
     }
-    return it;
+    return v;
 }
 
-__device__ __forceinline__ int item_token(const FwdArgs &a, const Item &it, int i)
+// false (and *err_flag = 2) if `plan` was not written by mole_dedup_ids for T tokens
+__device__ __forceinline__ bool plan_ok(const FwdArgs &a)
 {
-    return a.plan ? a.plan[plan_layout(a.T).order + it.begin + i] : it.begin;
+    if (a.plan[5] == PLAN_MAGIC && a.plan[2] == a.T)
+        return true;
+    if (threadIdx.x == 0 && a.err_flag)
+        *a.err_flag = 2;
+    return false;
 }
 
-__device__ __forceinline__ void wave_lds_fence()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// acc += h[k]*w[k] + h[k+1]*w[k+1] for one packed pair of bf16 operands
+// acc += h[k]*w[k] + h[k+1]*w[k+1] for one packed pair of bf16 operands, fp32 accumulation
 __device__ __forceinline__ float mac2(float acc, uint32_t hp, uint32_t wp)
 {
-#ifdef MOLE_USE_DOT2
     typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, hp), __builtin_bit_cast(bf16x2, wp), acc, false);
-#else
-    acc = fmaf(bf16lo(hp), bf16lo(wp), acc);
-    return fmaf(bf16hi(hp), bf16hi(wp), acc);
-#endif
 }
 
 // Fold N per-lane partial sums over the 64 lanes.  Each step halves the number of values a
@@ -115,17 +107,6 @@ struct Fold {
     }
 };
 
-__device__ __forceinline__ uint4 ld16(const uint16_t *p)
-{
-#ifdef MOLE_NT_ROWS
-    typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
-    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
-    return make_uint4(v.x, v.y, v.z, v.w);
-#else
-    return *reinterpret_cast<const uint4 *>(p);
-#endif
-}
-
 // Activations are read once and written once per call.  Stores are always non-temporal; loads are
 // non-temporal (NTA) in the large-batch regime, where keeping them out of L2 / Infinity Cache leaves
 // more room for table rows (which ARE reused across tokens with equal ids).  For small batches the
@@ -143,27 +124,15 @@ __device__ __forceinline__ uint4 ld16_stream(const uint16_t *p)
 }
 __device__ __forceinline__ void st16_stream(uint16_t *p, const uint4 &o)
 {
-#ifndef MOLE_PLAIN_STORES
     typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
     const u32x4 v = {o.x, o.y, o.z, o.w};
     __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(p));
-#else
-    *reinterpret_cast<uint4 *>(p) = o;
-#endif
 }
 
-template <int N>
-__device__ __forceinline__ void load_rows(uint4 (&r)[N], const uint16_t *rp, int col, int d, bool on)
+template <bool NT>
+__device__ __forceinline__ uint4 ld16_row(const uint16_t *p)
 {
-    if (on) {
-#pragma unroll
-        for (int j = 0; j < N; ++j)
-            r[j] = ld16(rp + (int64_t)j * d + col);
-    } else {
-#pragma unroll
-        for (int j = 0; j < N; ++j)
-            r[j] = make_uint4(0, 0, 0, 0);
-    }
+    return ld16_stream<NT>(p);
 }
 
 // Router weight [d, N] -> LDS as (W[k,j], W[k+1,j]) bf16 pairs; the 16-byte piece holding
@@ -191,35 +160,46 @@ __device__ __forceinline__ void fill_router_lds(uint4 *smem, const uint16_t *Wr,
     }
 }
 
-// Router equation for one token on one wavefront: returns, in lane l, the gate of expert
-// l / (64/N) (softmax over all N experts of h . r_j).
-template <int N, bool NTA>
-__device__ __forceinline__ float router_gate(const uint4 *smem, int kgroups, const uint16_t *hrow, int d, int lane)
+// z[j] += sum over the lane's 8 k of h[k] * W_r[k, j], for one 16-byte piece of h (k-group kg)
+template <int N>
+__device__ __forceinline__ void router_piece(float (&z)[N], const uint4 *smem, int kgroups, const uint4 &hv, int kg)
 {
     constexpr int NQ = N / 4;
+    const uint32_t hp[4] = {hv.x, hv.y, hv.z, hv.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+        for (int jq = 0; jq < NQ; ++jq) {
+            const uint4 w = smem[(q * NQ + jq) * kgroups + kg];
+            z[4 * jq + 0] = mac2(z[4 * jq + 0], hp[q], w.x);
+            z[4 * jq + 1] = mac2(z[4 * jq + 1], hp[q], w.y);
+            z[4 * jq + 2] = mac2(z[4 * jq + 2], hp[q], w.z);
+            z[4 * jq + 3] = mac2(z[4 * jq + 3], hp[q], w.w);
+        }
+    }
+}
+
+// Router equation for one token on one wavefront: returns, in lane l, the gate of expert
+// l / (64/N) (softmax over all N experts of h . r_j).  h0 / h1 are the lane's pieces of the first
+// two 512-column chunks, already loaded by the caller; further chunks are loaded here.
+template <int N, bool NTA>
+__device__ __forceinline__ float router_gate(const uint4 *smem, int kgroups, const uint16_t *hrow, int d, int lane,
+                                             const uint4 &h0, const uint4 &h1)
+{
     constexpr int LPJ = 64 / N;
     float z[N];
 #pragma unroll
     for (int j = 0; j < N; ++j)
         z[j] = 0.f;
-    for (int c0 = 0; c0 < d; c0 += 512) {
-        const int cc = c0 + lane * 8;
-        if (cc < d) {
-            const uint4 hv = ld16_stream<NTA>(hrow + cc);
-            const uint32_t hp[4] = {hv.x, hv.y, hv.z, hv.w};
-            const int kg = cc >> 3;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-#pragma unroll
-                for (int jq = 0; jq < NQ; ++jq) {
-                    const uint4 w = smem[(q * NQ + jq) * kgroups + kg];
-                    z[4 * jq + 0] = mac2(z[4 * jq + 0], hp[q], w.x);
-                    z[4 * jq + 1] = mac2(z[4 * jq + 1], hp[q], w.y);
-                    z[4 * jq + 2] = mac2(z[4 * jq + 2], hp[q], w.z);
-                    z[4 * jq + 3] = mac2(z[4 * jq + 3], hp[q], w.w);
-                }
-            }
-        }
+    const int col0 = lane * 8;
+    if (col0 < d)
+        router_piece<N>(z, smem, kgroups, h0, col0 >> 3);
+    if (col0 + 512 < d)
+        router_piece<N>(z, smem, kgroups, h1, (col0 + 512) >> 3);
+    for (int c0 = 1024; c0 < d; c0 += 512) {
+        const int cc = c0 + col0;
+        if (cc < d)
+            router_piece<N>(z, smem, kgroups, ld16_stream<NTA>(hrow + cc), cc >> 3);
     }
     const float zz = Fold<N, 32>::run(z, lane);
     float m = zz;
@@ -232,6 +212,15 @@ __device__ __forceinline__ float router_gate(const uint4 *smem, int kgroups, con
     for (int w = 32; w >= LPJ; w >>= 1)
         s += __shfl_xor(s, w);
     return e / s;
+}
+
+// the lane's pieces of h for the first two chunks (zero where the chunk does not exist)
+template <bool NTA>
+__device__ __forceinline__ void load_h2(uint4 &h0, uint4 &h1, const uint16_t *hrow, int d, int lane)
+{
+    const int col0 = lane * 8;
+    h0 = col0 < d ? ld16_stream<NTA>(hrow + col0) : make_uint4(0, 0, 0, 0);
+    h1 = col0 + 512 < d ? ld16_stream<NTA>(hrow + col0 + 512) : make_uint4(0, 0, 0, 0);
 }
 
 // acc[0..7] += g * (the 8 bf16 values of one 16-byte piece)
@@ -270,24 +259,32 @@ __device__ __forceinline__ uint4 pack8(const float (&acc)[8])
 }
 
 // ------------------------------------------------------------------------------------------
-// bf16 streaming kernel (no grouping plan): one token per item.  The wave's N row registers
-// are a ring: as soon as row j of the current 512-column chunk has been multiplied in, the
-// same register is re-loaded with row j of the next chunk -- or of the wave's NEXT token when
-// this was the last chunk -- so N-1 16-byte loads per lane stay in flight through the router,
-// the multiply phase and the epilogue alike.
+// bf16 streaming kernel.  The wave's N row registers are a ring: as soon as the rows of the
+// current 512-column chunk have been multiplied in, the same registers are re-loaded with the
+// next chunk -- or with chunk 0 of the wave's NEXT token when this was the last chunk -- so N
+// 16-byte loads per lane are in flight through the router, the multiply phase and the epilogue
+// alike; the next token's router input is prefetched the same way.
+// Table rows are loaded with plain (cacheable) loads: repeated ids are then served by L2 /
+// Infinity Cache.  Rows that the plan marks as read-once use non-temporal loads.
 // N in {4, 8, 16, 32, 64}, d % 8 == 0, router weight fits in LDS.  grid = (workgroups, L).
 // ------------------------------------------------------------------------------------------
+template <int N, bool NT>
+__device__ __forceinline__ void ring_load(uint4 (&r)[N], const uint16_t *base, int d, int col)
+{
+#pragma unroll
+    for (int j = 0; j < N; ++j)
+        r[j] = ld16_row<NT>(base + (int64_t)j * d + col);
+}
+
 template <int N, int WPB, bool NTA>
 __global__ __launch_bounds__(WPB * 64) __attribute__((amdgpu_waves_per_eu(N <= 16 ? 4 : 2)))
 void fwd_bf16_stream_kernel(FwdArgs a)
 {
     extern __shared__ uint4 smem[];
-    constexpr int NQ = N / 4;
-    constexpr int LPJ = 64 / N;
+    constexpr int LPJ = 64 / N;   // lanes per expert after the fold
     const int d = a.d;
     const int kgroups = d >> 3;
     const int layer = blockIdx.y;
-    const int n_w4 = kgroups * N;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int col0 = lane * 8;
@@ -301,44 +298,55 @@ void fwd_bf16_stream_kernel(FwdArgs a)
     uint16_t *obase = static_cast<uint16_t *>(a.out) + act_off;
     const int32_t *rowsrc = a.slot ? a.slot : a.ids;
     const int stride = gridDim.x * WPB;
+    const int32_t *order = nullptr;
+    if (a.plan) {
+        if (!plan_ok(a))
+            return;
+        order = a.plan + plan_layout(T).order;
+    }
 
     // the first token's rows go in flight before the router weight is staged.  Lanes past the end
     // of a ragged chunk load a clamped (valid) column; their results are never stored.
     const int dlast = d - 8;
     int item = blockIdx.x * WPB + wave;
-    int64_t row = item < T ? (int64_t)__builtin_amdgcn_readfirstlane(rowsrc[item]) : -1;
+    Visit cur = item < T ? visit(order, item) : Visit{0, false};
+    int64_t row = item < T ? (int64_t)__builtin_amdgcn_readfirstlane(rowsrc[cur.t]) : -1;
     bool valid = row >= 0 && row < a.rows;
     uint4 r[N];
     if (valid) {
         const uint16_t *rp0 = table + row * (int64_t)N * d;
-        const int fcol = min(col0, dlast);
-#pragma unroll
-        for (int j = 0; j < N; ++j)
-            r[j] = ld16(rp0 + (int64_t)j * d + fcol);
+        if (cur.single)
+            ring_load<N, true>(r, rp0, d, min(col0, dlast));
+        else
+            ring_load<N, false>(r, rp0, d, min(col0, dlast));
     }
+    uint4 h0, h1;
+    load_h2<NTA>(h0, h1, hbase + (int64_t)cur.t * d, d, lane);
 
     fill_router_lds<N>(smem, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
     __syncthreads();
-    float *gl = reinterpret_cast<float *>(smem + n_w4) + wave * (PLAN_GROUP * N);
-    const float4 *gl4 = reinterpret_cast<const float4 *>(gl);
 
     for (; item < T; item += stride) {
-        const int t = item;
+        const int t = cur.t;
         const int nitem = item + stride;
-        const int64_t nrow = nitem < T ? (int64_t)__builtin_amdgcn_readfirstlane(rowsrc[nitem]) : -1;
+        const Visit nxt = nitem < T ? visit(order, nitem) : Visit{0, false};
+        const int64_t nrow = nitem < T ? (int64_t)__builtin_amdgcn_readfirstlane(rowsrc[nxt.t]) : -1;
         const bool nvalid = nrow >= 0 && nrow < a.rows;
         if (!valid && lane == 0 && a.err_flag)
             *a.err_flag = 1;
         if (a.rows_dbg && layer == 0 && lane == 0)
             a.rows_dbg[t] = valid ? row : -1;
 
-        const float g = router_gate<N, NTA>(smem, kgroups, hbase + (int64_t)t * d, d, lane);
-        if ((lane & (LPJ - 1)) == 0) {
-            gl[lane / LPJ] = g;
-            if (a.gates_dbg)
-                a.gates_dbg[((int64_t)layer * T + t) * N + lane / LPJ] = g;
-        }
-        wave_lds_fence();
+        const float g = router_gate<N, NTA>(smem, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1);
+        if (a.gates_dbg && (lane & (LPJ - 1)) == 0)
+            a.gates_dbg[((int64_t)layer * T + t) * N + lane / LPJ] = g;
+        // the next token's h goes in flight now; its latency hides behind this token's combine
+        load_h2<NTA>(h0, h1, hbase + (int64_t)nxt.t * d, d, lane);
+        // gates into scalar registers: expert j's gate sits in lane j * (64/N)
+        float gs[N];
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+            gs[j] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, g), j * LPJ));
 
         const uint16_t *rp = table + (valid ? row : 0) * (int64_t)N * d;
         const uint16_t *nrp = table + (nvalid ? nrow : 0) * (int64_t)N * d;
@@ -358,135 +366,32 @@ void fwd_bf16_stream_kernel(FwdArgs a)
                 acc[e] = 0.f;
             if (valid) {
 #pragma unroll
-                for (int jq = 0; jq < NQ; ++jq) {
-                    const float4 g4 = gl4[jq];
-                    fma8(acc, g4.x, r[4 * jq + 0]);
-                    fma8(acc, g4.y, r[4 * jq + 1]);
-                    fma8(acc, g4.z, r[4 * jq + 2]);
-                    fma8(acc, g4.w, r[4 * jq + 3]);
-                }
+                for (int j = 0; j < N; ++j)
+                    fma8(acc, gs[j], r[j]);
             }
             // refill the ring: next chunk of this token, or chunk 0 of the wave's next token
             const uint16_t *fb = last ? nrp : rp;                      // wave-uniform
             const int fcol = min(last ? col0 : cc + 512, dlast);
             if (last ? nvalid : valid) {
-#pragma unroll
-                for (int j = 0; j < N; ++j)
-                    r[j] = ld16(fb + (int64_t)j * d + fcol);
+                if (last ? nxt.single : cur.single)
+                    ring_load<N, true>(r, fb, d, fcol);
+                else
+                    ring_load<N, false>(r, fb, d, fcol);
             }
             add8(acc, sv);
             add8(acc, rv);
             if (on)
                 st16_stream(obase + off, pack8(acc));
         }
-        wave_lds_fence();
         row = nrow;
         valid = nvalid;
-    }
-}
-
-// ------------------------------------------------------------------------------------------
-// bf16 grouped kernel (plan of mole_dedup_ids): an item is one row block and the 1..8 tokens
-// that read it; the rows of a chunk are loaded once and multiplied for every token of the item.
-// ------------------------------------------------------------------------------------------
-template <int N, int WPB, bool NTA>
-__global__ __launch_bounds__(WPB * 64) __attribute__((amdgpu_waves_per_eu(N <= 16 ? 4 : 2)))
-void fwd_bf16_grouped_kernel(FwdArgs a)
-{
-    extern __shared__ uint4 smem[];
-    constexpr int NQ = N / 4;
-    constexpr int LPJ = 64 / N;
-    const int d = a.d;
-    const int kgroups = d >> 3;
-    const int layer = blockIdx.y;
-    const int n_w4 = kgroups * N;
-
-    fill_router_lds<N>(smem, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
-    __syncthreads();
-
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    float *gl = reinterpret_cast<float *>(smem + n_w4) + wave * (PLAN_GROUP * N);
-    const float4 *gl4 = reinterpret_cast<const float4 *>(gl);
-
-    if (a.plan[5] != PLAN_MAGIC || a.plan[2] != a.T) {
-        if (threadIdx.x == 0 && a.err_flag)
-            *a.err_flag = 2;
-        return;
-    }
-    const int n_items = a.plan[0];
-    const int n_uniq = a.plan[1];
-
-    const uint16_t *table = static_cast<const uint16_t *>(a.table) + (int64_t)layer * a.table_stride;
-    const int64_t act_off = (int64_t)layer * a.act_stride;
-    const uint16_t *hbase = static_cast<const uint16_t *>(a.h) + act_off;
-    const uint16_t *sbase = a.shared ? static_cast<const uint16_t *>(a.shared) + act_off : nullptr;
-    const uint16_t *rbase = a.residual ? static_cast<const uint16_t *>(a.residual) + act_off : nullptr;
-    uint16_t *obase = static_cast<uint16_t *>(a.out) + act_off;
-    const int col0 = lane * 8;
-
-    for (int item = blockIdx.x * WPB + wave; item < n_items; item += gridDim.x * WPB) {
-        const Item it = get_item(a, item, n_uniq);
-        const bool valid = it.row >= 0 && it.row < a.rows;
-        if (!valid && lane == 0 && a.err_flag)
-            *a.err_flag = 1;
-        const uint16_t *rp = table + (valid ? it.row : 0) * (int64_t)N * d;
-
-        // rows of the first 512-column chunk: in flight while the router runs
-        uint4 r[N];
-        load_rows<N>(r, rp, col0, d, valid && col0 < d);
-
-        for (int i = 0; i < it.cnt; ++i) {
-            const int t = item_token(a, it, i);
-            const float g = router_gate<N, NTA>(smem, kgroups, hbase + (int64_t)t * d, d, lane);
-            if ((lane & (LPJ - 1)) == 0) {
-                gl[i * N + lane / LPJ] = g;
-                if (a.gates_dbg)
-                    a.gates_dbg[((int64_t)layer * a.T + t) * N + lane / LPJ] = g;
-            }
-            if (a.rows_dbg && layer == 0 && lane == 0)
-                a.rows_dbg[t] = valid ? it.row : -1;
-        }
-        wave_lds_fence();
-
-        for (int c0 = 0; c0 < d; c0 += 512) {
-            const int cc = c0 + col0;
-            const bool on = cc < d;
-            if (c0 > 0)
-                load_rows<N>(r, rp, cc, d, valid && on);
-            for (int i = 0; i < it.cnt; ++i) {
-                const int t = item_token(a, it, i);
-                const int64_t off = (int64_t)t * d + cc;
-                uint4 sv = make_uint4(0, 0, 0, 0), rv = make_uint4(0, 0, 0, 0);
-                if (on && sbase)
-                    sv = ld16_stream<NTA>(sbase + off);
-                if (on && rbase)
-                    rv = ld16_stream<NTA>(rbase + off);
-                float acc[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    acc[e] = 0.f;
-#pragma unroll
-                for (int jq = 0; jq < NQ; ++jq) {
-                    const float4 g4 = gl4[i * NQ + jq];
-                    const float gg[4] = {g4.x, g4.y, g4.z, g4.w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        fma8(acc, gg[e], r[4 * jq + e]);
-                }
-                add8(acc, sv);
-                add8(acc, rv);
-                if (on)
-                    st16_stream(obase + off, pack8(acc));
-            }
-        }
-        wave_lds_fence();
+        cur = nxt;
     }
 }
 
 // ------------------------------------------------------------------------------------------
 // Generic path: any 1 <= N <= 64, fp32 or bf16 storage, no LDS-resident router weight.
-// One wavefront per item; lanes stride over k (router) and over columns (combine).
+// One wavefront per token; lanes stride over k (router) and over columns (combine).
 // ------------------------------------------------------------------------------------------
 template <typename E> __device__ __forceinline__ float ldf(const E *p);
 template <> __device__ __forceinline__ float ldf<float>(const float *p) { return *p; }
@@ -494,25 +399,28 @@ template <> __device__ __forceinline__ float ldf<uint16_t>(const uint16_t *p) { 
 __device__ __forceinline__ void stf(float *p, float v) { *p = v; }
 __device__ __forceinline__ void stf(uint16_t *p, float v) { *p = (uint16_t)f32_to_bf16_bits(v); }
 
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 template <typename E>
 __global__ __launch_bounds__(256) void fwd_generic_kernel(FwdArgs a)
 {
-    __shared__ float gls[4][PLAN_GROUP * 64];
+    __shared__ float gls[4][64];
     const int d = a.d, N = a.N;
     const int layer = blockIdx.y;
     const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
     float *gl = gls[wave];
 
-    int n_items = a.T, n_uniq = 0;
+    const int32_t *order = nullptr;
     if (a.plan) {
-        if (a.plan[5] != PLAN_MAGIC || a.plan[2] != a.T) {
-            if (threadIdx.x == 0 && a.err_flag)
-                *a.err_flag = 2;
+        if (!plan_ok(a))
             return;
-        }
-        n_items = a.plan[0];
-        n_uniq = a.plan[1];
+        order = a.plan + plan_layout(a.T).order;
     }
     const E *table = static_cast<const E *>(a.table) + (int64_t)layer * a.table_stride;
     const int64_t act_off = (int64_t)layer * a.act_stride;
@@ -521,62 +429,58 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(FwdArgs a)
     const E *sbase = a.shared ? static_cast<const E *>(a.shared) + act_off : nullptr;
     const E *rbase = a.residual ? static_cast<const E *>(a.residual) + act_off : nullptr;
     E *obase = static_cast<E *>(a.out) + act_off;
+    const int32_t *rowsrc = a.slot ? a.slot : a.ids;
 
-    for (int item = blockIdx.x * 4 + wave; item < n_items; item += gridDim.x * 4) {
-        const Item it = get_item(a, item, n_uniq);
-        const bool valid = it.row >= 0 && it.row < a.rows;
+    for (int item = blockIdx.x * 4 + wave; item < a.T; item += gridDim.x * 4) {
+        const int t = visit(order, item).t;
+        const int64_t row = rowsrc[t];
+        const bool valid = row >= 0 && row < a.rows;
         if (!valid && lane == 0 && a.err_flag)
             *a.err_flag = 1;
-        const E *rp = table + (valid ? it.row : 0) * (int64_t)N * d;
+        if (a.rows_dbg && layer == 0 && lane == 0)
+            a.rows_dbg[t] = valid ? row : -1;
+        const E *rp = table + (valid ? row : 0) * (int64_t)N * d;
 
-        for (int i = 0; i < it.cnt; ++i) {
-            const int t = item_token(a, it, i);
-            const E *hr = hbase + (int64_t)t * d;
-            float zmine = -INFINITY;   // lane j keeps logit j
-            for (int j = 0; j < N; ++j) {
-                float p = 0.f;
-                for (int k = lane; k < d; k += 64)
-                    p = fmaf(ldf(hr + k), ldf(Wr + (int64_t)k * N + j), p);
-#pragma unroll
-                for (int w = 32; w >= 1; w >>= 1)
-                    p += __shfl_xor(p, w);
-                if (lane == j)
-                    zmine = p;
-            }
-            float m = zmine;
+        const E *hr = hbase + (int64_t)t * d;
+        float zmine = -INFINITY;   // lane j keeps logit j
+        for (int j = 0; j < N; ++j) {
+            float p = 0.f;
+            for (int k = lane; k < d; k += 64)
+                p = fmaf(ldf(hr + k), ldf(Wr + (int64_t)k * N + j), p);
 #pragma unroll
             for (int w = 32; w >= 1; w >>= 1)
-                m = fmaxf(m, __shfl_xor(m, w));
-            const float e = (lane < N) ? expf(zmine - m) : 0.f;
-            float s = e;
+                p += __shfl_xor(p, w);
+            if (lane == j)
+                zmine = p;
+        }
+        float m = zmine;
 #pragma unroll
-            for (int w = 32; w >= 1; w >>= 1)
-                s += __shfl_xor(s, w);
-            const float g = e / s;
-            if (lane < N) {
-                gl[i * N + lane] = g;
-                if (a.gates_dbg)
-                    a.gates_dbg[((int64_t)layer * a.T + t) * N + lane] = g;
-            }
-            if (a.rows_dbg && layer == 0 && lane == 0)
-                a.rows_dbg[t] = valid ? it.row : -1;
+        for (int w = 32; w >= 1; w >>= 1)
+            m = fmaxf(m, __shfl_xor(m, w));
+        const float e = (lane < N) ? expf(zmine - m) : 0.f;
+        float s = e;
+#pragma unroll
+        for (int w = 32; w >= 1; w >>= 1)
+            s += __shfl_xor(s, w);
+        const float g = e / s;
+        if (lane < N) {
+            gl[lane] = g;
+            if (a.gates_dbg)
+                a.gates_dbg[((int64_t)layer * a.T + t) * N + lane] = g;
         }
         wave_lds_fence();
 
         for (int c = lane; c < d; c += 64) {
-            for (int i = 0; i < it.cnt; ++i) {
-                const int t = item_token(a, it, i);
-                float acc = 0.f;
-                if (valid)
-                    for (int j = 0; j < N; ++j)
-                        acc = fmaf(gl[i * N + j], ldf(rp + (int64_t)j * d + c), acc);
-                const int64_t off = (int64_t)t * d + c;
-                if (sbase)
-                    acc += ldf(sbase + off);
-                if (rbase)
-                    acc += ldf(rbase + off);
-                stf(obase + off, acc);
-            }
+            float acc = 0.f;
+            if (valid)
+                for (int j = 0; j < N; ++j)
+                    acc = fmaf(gl[j], ldf(rp + (int64_t)j * d + c), acc);
+            const int64_t off = (int64_t)t * d + c;
+            if (sbase)
+                acc += ldf(sbase + off);
+            if (rbase)
+                acc += ldf(rbase + off);
+            stf(obase + off, acc);
         }
         wave_lds_fence();
     }
@@ -624,28 +528,23 @@ int64_t grid_x(int items, int L, size_t lds)
 }
 
 template <int N, int WPB, bool NTA>
-mole_status launch_fast(const FwdArgs &a, int items_bound, hipStream_t stream)
+mole_status launch_fast(const FwdArgs &a, hipStream_t stream)
 {
-    const size_t lds = (size_t)a.d * N * 2 + (size_t)WPB * PLAN_GROUP * N * 4;
+    const size_t lds = (size_t)a.d * N * 2;
     static size_t attr_set = 0;
     if (lds > attr_set) {
         MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_bf16_stream_kernel<N, WPB, NTA>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_bf16_grouped_kernel<N, WPB, NTA>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = lds;
     }
-    dim3 grid((unsigned)grid_x<N, WPB>(items_bound, a.L, lds), (unsigned)a.L);
-    if (a.plan)
-        hipLaunchKernelGGL((fwd_bf16_grouped_kernel<N, WPB, NTA>), grid, dim3(WPB * 64), lds, stream, a);
-    else
-        hipLaunchKernelGGL((fwd_bf16_stream_kernel<N, WPB, NTA>), grid, dim3(WPB * 64), lds, stream, a);
+    dim3 grid((unsigned)grid_x<N, WPB>(a.T, a.L, lds), (unsigned)a.L);
+    hipLaunchKernelGGL((fwd_bf16_stream_kernel<N, WPB, NTA>), grid, dim3(WPB * 64), lds, stream, a);
     MOLE_HIP_CHECK(hipGetLastError());
     return MOLE_OK;
 }
 
 template <int N>
-mole_status launch_fast_n(const FwdArgs &a, int items_bound, hipStream_t stream)
+mole_status launch_fast_n(const FwdArgs &a, hipStream_t stream)
 {
     // wider workgroups when the router weight is large, so that LDS does not cap occupancy
     const size_t wbytes = (size_t)a.d * N * 2;
@@ -654,8 +553,8 @@ mole_status launch_fast_n(const FwdArgs &a, int items_bound, hipStream_t stream)
     // large batches: keep the read-once activations out of the caches
     const bool nta = env_int("MOLE_FWD_NTA", (int64_t)a.T * a.L >= 8192 ? 1 : 2) == 1;
     if (wpb >= 8)
-        return nta ? launch_fast<N, 8, true>(a, items_bound, stream) : launch_fast<N, 8, false>(a, items_bound, stream);
-    return nta ? launch_fast<N, 4, true>(a, items_bound, stream) : launch_fast<N, 4, false>(a, items_bound, stream);
+        return nta ? launch_fast<N, 8, true>(a, stream) : launch_fast<N, 8, false>(a, stream);
+    return nta ? launch_fast<N, 4, true>(a, stream) : launch_fast<N, 4, false>(a, stream);
 }
 
 mole_status forward_impl(const void *table, int64_t table_stride, const int32_t *ids, const int32_t *slot,
@@ -694,14 +593,12 @@ mole_status forward_impl(const void *table, int64_t table_stride, const int32_t 
             return fail(MOLE_EUNSUPPORTED, "mole_lookup_forward_layers: L=%d > 65535", L);
     }
     const int32_t *plan = nullptr;
-    int items_bound = T;
     if (flags & MOLE_FLAG_DEDUP) {
         const size_t need = (size_t)plan_layout(T).words * 4;
         if (!workspace || workspace_bytes < need)
             return fail(MOLE_EWORKSPACE, "mole_lookup_forward: MOLE_FLAG_DEDUP needs a %zu-byte plan, got %zu",
                         need, workspace ? workspace_bytes : (size_t)0);
         plan = static_cast<const int32_t *>(workspace);
-        items_bound = T + T / PLAN_GROUP + 2;
     }
 
     FwdArgs a;
@@ -712,19 +609,19 @@ mole_status forward_impl(const void *table, int64_t table_stride, const int32_t 
     a.T = T; a.d = d; a.N = N; a.L = L;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
-    const size_t lds_fast = (size_t)d * N * 2 + (size_t)8 * PLAN_GROUP * N * 4;
+    const size_t lds_fast = (size_t)d * N * 2;
     const bool fast = dtype == MOLE_BF16 && lds_fast <= LDS_BYTES_PER_CU && !getenv("MOLE_FWD_GENERIC");
     if (fast) {
         switch (N) {
-        case 4: return launch_fast_n<4>(a, items_bound, stream);
-        case 8: return launch_fast_n<8>(a, items_bound, stream);
-        case 16: return launch_fast_n<16>(a, items_bound, stream);
-        case 32: return launch_fast_n<32>(a, items_bound, stream);
-        case 64: return launch_fast_n<64>(a, items_bound, stream);
+        case 4: return launch_fast_n<4>(a, stream);
+        case 8: return launch_fast_n<8>(a, stream);
+        case 16: return launch_fast_n<16>(a, stream);
+        case 32: return launch_fast_n<32>(a, stream);
+        case 64: return launch_fast_n<64>(a, stream);
         default: break;
         }
     }
-    int64_t gx = (items_bound + 3) / 4;
+    int64_t gx = (T + 3) / 4;
     int64_t cap = (int64_t)num_cus() * 8 / L;
     if (cap < 1)
         cap = 1;

@@ -26,27 +26,26 @@ int num_cus();
             return ::mole::fail(MOLE_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
     } while (0)
 
-// ---- grouping plan written by mole_dedup_ids and read by the forward kernels ----
-// int32 words: header[16] | uniq[T] | order[T] | item_u[cap] | item_begin[cap] | item_cnt[cap]
-//              | scratch counters[T+2]
-// cap = 2T + 2.  header: [0] n_items  [1] n_uniq  [2] T  [3] group cap  [4] V  [5] magic
+// ---- plan written by mole_dedup_ids and read by the forward kernels ----
+// int32 words: header[16] | uniq[T] | order[T] | start[T+2] | counters[T+2]
+// header: [0] n_uniq  [1] reserved  [2] T  [3] reserved  [4] V  [5] magic
+// order: the token indices sorted by id (out-of-range ids last); bit 31 of an entry is set when
+//        the token's id occurs only once in the batch (its rows will not be read again).
+// start[u]: position in `order` of the first token of distinct id u (start[U] = out-of-range
+//        tokens, start[U+1] = T).
 constexpr int PLAN_HEADER = 16;
 constexpr int PLAN_MAGIC = 0x4d4f4c45;   // "MOLE"
-constexpr int PLAN_GROUP = 8;            // at most this many tokens share one read of a row block
+constexpr uint32_t PLAN_SINGLE = 0x80000000u;
 struct PlanLayout {
-    int64_t uniq, order, item_u, item_begin, item_cnt, counters, words;
-    int cap;
+    int64_t uniq, order, start, counters, words;
 };
 __host__ __device__ inline PlanLayout plan_layout(int T)
 {
     PlanLayout p;
-    p.cap = 2 * T + 2;
     p.uniq = PLAN_HEADER;
     p.order = p.uniq + T;
-    p.item_u = p.order + T;
-    p.item_begin = p.item_u + p.cap;
-    p.item_cnt = p.item_begin + p.cap;
-    p.counters = p.item_cnt + p.cap;
+    p.start = p.order + T;
+    p.counters = p.start + T + 2;
     p.words = p.counters + T + 2;
     p.words = (p.words + 3) & ~int64_t(3);
     return p;

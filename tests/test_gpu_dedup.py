@@ -1,6 +1,6 @@
 """GPU parity of mole_dedup_ids: distinct ids, inverse map and count are bit-exact against the oracle
-(which is pinned to numpy.unique); the grouping plan is checked for validity (any token order inside a
-group is correct, so only what is unique is compared)."""
+(which is pinned to numpy.unique); the visiting plan is checked for validity (any order of tokens with
+equal ids is correct, so only what is unique is compared)."""
 import numpy as np
 import pytest
 
@@ -10,7 +10,7 @@ from paper_2503_15798_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-PLAN_HEADER, PLAN_GROUP = 16, 8
+PLAN_HEADER, PLAN_SINGLE = 16, 0x80000000
 
 
 def run_dedup(ids, V):
@@ -29,32 +29,24 @@ def run_dedup(ids, V):
 
 
 def check_plan(plan, ids, V, uniq, U):
+    """The plan lists every token once, in id order (out-of-range ids last); the order of tokens with
+    equal ids is free.  Bit 31 marks tokens whose id occurs once."""
     T = len(ids)
-    cap = 2 * T + 2
-    n_items = plan[0]
-    assert plan[1] == U and plan[2] == T and plan[3] == PLAN_GROUP and plan[4] == V
-    o_uniq, o_order = PLAN_HEADER, PLAN_HEADER + T
-    o_u, o_b, o_c = o_order + T, o_order + T + cap, o_order + T + 2 * cap
+    assert plan[0] == U and plan[2] == T and plan[4] == V
+    o_uniq, o_order, o_start = PLAN_HEADER, PLAN_HEADER + T, PLAN_HEADER + 2 * T
     np.testing.assert_array_equal(plan[o_uniq:o_uniq + U], uniq)
-    order = plan[o_order:o_order + T]
+    raw = plan[o_order:o_order + T].astype(np.int64) & 0xFFFFFFFF
+    order, single = (raw & 0x7FFFFFFF).astype(np.int64), (raw & PLAN_SINGLE) != 0
     np.testing.assert_array_equal(np.sort(order), np.arange(T))               # a permutation of the tokens
-    item_u, item_b, item_c = plan[o_u:o_u + n_items], plan[o_b:o_b + n_items], plan[o_c:o_c + n_items]
-    assert (item_c >= 1).all() and (item_c <= PLAN_GROUP).all()
-    assert item_c.sum() == T
-    seen = np.zeros(T, bool)
-    for u, b, c in zip(item_u, item_b, item_c):
-        toks = order[b:b + c]
-        assert not seen[toks].any()
-        seen[toks] = True
-        if u < U:
-            assert (ids[toks] == uniq[u]).all()                               # a group reads one row block
-        else:
-            assert u == U and ((ids[toks] < 0) | (ids[toks] >= V)).all()      # the out-of-range bucket
-    assert seen.all()
-    in_range = ((ids >= 0) & (ids < V))
-    counts = np.bincount(ids[in_range], minlength=1)
-    want_items = sum((c + PLAN_GROUP - 1) // PLAN_GROUP for c in counts if c) + ((~in_range).sum() + 7) // 8
-    assert n_items == want_items
+    in_range = (ids >= 0) & (ids < V)
+    key = np.where(in_range, ids.astype(np.int64), np.int64(V))               # out-of-range ids sort last
+    assert (np.diff(key[order]) >= 0).all()                                   # id order
+    counts = np.bincount(ids[in_range], minlength=V)
+    want_single = in_range[order] & (counts[np.where(in_range, ids, 0)][order] == 1)
+    np.testing.assert_array_equal(single, want_single)
+    start = plan[o_start:o_start + U + 2]
+    np.testing.assert_array_equal(start[:U], np.concatenate([[0], np.cumsum(counts[uniq])])[:U])
+    assert start[U] == in_range.sum() and start[U + 1] == T
 
 
 @pytest.mark.parametrize("T,V,dist", [(1, 50304, "zipf"), (32, 50304, "zipf"), (64, 50304, "zipf"),
@@ -73,10 +65,10 @@ def test_dedup_matches_oracle(T, V, dist):
 
 def test_dedup_edge_cases():
     uniq, inv, U, err, plan = run_dedup(np.zeros((0,), np.int32), 100)
-    assert U == 0 and err == 0 and plan[0] == 0
+    assert U == 0 and err == 0 and plan[0] == 0 and plan[5] == 0x4D4F4C45
     ids = np.full((100,), 42, np.int32)
     uniq, inv, U, err, plan = run_dedup(ids, 100)
-    assert U == 1 and list(uniq) == [42] and (inv == 0).all() and plan[0] == 13
+    assert U == 1 and list(uniq) == [42] and (inv == 0).all()
     check_plan(plan, ids, 100, uniq, U)
     ids = np.array([5, 99, 100, -1, 5, 2 ** 31 - 1, 0], np.int32)
     uniq, inv, U, err, plan = run_dedup(ids, 100)

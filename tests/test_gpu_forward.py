@@ -186,7 +186,7 @@ def test_dedup_flag_does_not_change_the_output(d, N, T, V, dist):
     np.testing.assert_array_equal(a["gates"], b["gates"])
 
 
-def test_heavy_repeats_are_split_into_bounded_groups():
+def test_heavy_repeats_with_plan():
     w = wl.scaled(wl.CONFIGS["decode410m"], V=64, d=256, N=16, T=500, L=1)
     table, li = wl.random_table(w), wl.layer_inputs(w)
     ids = np.full((w.T,), 7, np.int32)
