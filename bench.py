@@ -41,6 +41,8 @@ def parse_args():
     ap.add_argument("--workload", default="decode410m")
     ap.add_argument("--no-extras", action="store_true", help="only the headline workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--only-build", action="store_true",
+                    help="time mole_build_lut on one 410M layer and print its entry alone (for profiling)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain 1 GiB device copy (reference for rocprofv3 byte counters)")
     return ap.parse_args()
@@ -85,6 +87,30 @@ class Layers:
     def dedup(self, i, stream):
         self.mb.mole_dedup_ids(self.ids[i % N_ID_BATCHES], self.w.T, self.w.V, self.uniq, self.inv, self.n_uniq,
                                self.err, self.plan, stream=stream)
+
+    def make_plans(self, stream):
+        """One plan per id batch, computed outside any timed region (a real model computes the plan
+        once per batch and reuses it for every MoLE layer)."""
+        torch = self.torch
+        self.plans = [torch.empty_like(self.plan) for _ in range(N_ID_BATCHES)]
+        for b in range(N_ID_BATCHES):
+            self.mb.mole_dedup_ids(self.ids[b], self.w.T, self.w.V, self.uniq, self.inv, self.n_uniq, self.err,
+                                   self.plans[b], stream=stream)
+        stream.synchronize()
+
+    def forward_planned(self, i, stream):
+        w, mb = self.w, self.mb
+        mb.mole_lookup_forward_layers(
+            self.tabs, w.V * w.N * w.d, self.ids[i % N_ID_BATCHES], None, self.h, self.W_r, self.shared, None,
+            self.out, w.T * w.d, None, None, self.err, w.L, w.T, w.V, w.d, w.N, self.code,
+            mb.MOLE_FLAG_DEDUP, self.plans[i % N_ID_BATCHES], stream=stream)
+
+    def forward_one_layer(self, i, l, stream):
+        """The single-layer entry point on layer l (what a real decoder calls, once per layer)."""
+        w, mb = self.w, self.mb
+        mb.mole_lookup_forward(self.tabs[l], self.ids[i % N_ID_BATCHES], None, self.h[l], self.W_r[l],
+                               self.shared[l], None, self.out[l], None, None, self.err, w.T, w.V, w.d, w.N,
+                               self.code, 0, None, stream=stream)
 
     def distinct(self):
         import numpy as np
@@ -206,6 +232,9 @@ def main():
     mb.lib()     # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
     stream = torch.cuda.Stream()
+    if args.only_build:
+        print(json.dumps({"build_lut_410m_layer": build_bench(torch, mb, wl, acc, stream)}))
+        return
     w = wl.CONFIGS[args.workload]
 
     # ------------------------------------------------------------------ headline workload
@@ -282,11 +311,42 @@ def extras(args, torch, mb, wl, acc, stream, L):
     def plain(LL):
         return lambda i: LL.forward(i, stream)
 
-    # headline shape: dedup + grouped forward, and the dedup kernel alone
+    def planned(LL):
+        LL.make_plans(stream)
+        return lambda i: LL.forward_planned(i, stream)
+
+    def per_layer(LL):
+        def f(i):
+            for l in range(LL.w.L):
+                LL.forward_one_layer(i, l, stream)
+        return f
+
+    def graph_of_layers(LL):
+        """The per-layer launches of one step captured in a HIP graph (id batch 0), replayed per step."""
+        g = torch.cuda.CUDAGraph()
+        f = per_layer(LL)
+        with torch.cuda.stream(stream):
+            f(0)
+            stream.synchronize()
+            with torch.cuda.graph(g, stream=stream):
+                f(0)
+        return lambda i: g.replay()
+
+    # headline shape: dedup + id-ordered forward, and the dedup kernel alone
     ms = time_steps(torch, stream, both(L), steps, warm)
     out["decode410m_dedup_plus_forward"] = rates(w, acc, ms, L.distinct())
     ms = time_steps(torch, stream, lambda i: L.dedup(i, stream), steps, warm)
     out["decode410m_dedup_kernel_ms"] = ms
+    ms = time_steps(torch, stream, planned(L), steps, warm)
+    out["decode410m_forward_with_plan"] = rates(w, acc, ms, L.distinct())
+    # the same step as 24 launches of the single-layer entry point, eagerly and from a HIP graph
+    ms = time_steps(torch, stream, per_layer(L), steps, warm)
+    out["decode410m_per_layer_launches"] = rates(w, acc, ms, L.distinct())
+    try:
+        ms = time_steps(torch, stream, graph_of_layers(L), steps, warm)
+        out["decode410m_per_layer_launches_hip_graph"] = rates(w, acc, ms, L.distinct())
+    except Exception as e:
+        out["decode410m_per_layer_launches_hip_graph"] = {"skipped": repr(e)}
 
     # ---- offloaded mode on the same tables: all LUTs in pinned host memory, T = 32 ----
     try:
@@ -305,6 +365,13 @@ def extras(args, torch, mb, wl, acc, stream, L):
         LL.ids = torch.from_numpy(LL.ids_host).cuda()
         ms = time_steps(torch, stream, plain(LL), steps, warm)
         out[ww.name] = rates(ww, acc, ms, LL.distinct())
+        ms = time_steps(torch, stream, per_layer(LL), steps, warm)
+        out[ww.name + "_per_layer_launches"] = rates(ww, acc, ms, LL.distinct())
+        try:
+            ms = time_steps(torch, stream, graph_of_layers(LL), steps, warm)
+            out[ww.name + "_per_layer_launches_hip_graph"] = rates(ww, acc, ms, LL.distinct())
+        except Exception as e:
+            out[ww.name + "_per_layer_launches_hip_graph"] = {"skipped": repr(e)}
     del L.tabs
     torch.cuda.empty_cache()
 
@@ -317,6 +384,8 @@ def extras(args, torch, mb, wl, acc, stream, L):
         out[name + "_dedup_plus_forward"] = rates(ww, acc, ms, LL.distinct())
         ms = time_steps(torch, stream, lambda i: LL.dedup(i, stream), steps, warm)
         out[name + "_dedup_kernel_ms"] = ms
+        ms = time_steps(torch, stream, planned(LL), steps, warm)
+        out[name + "_forward_with_plan"] = rates(ww, acc, ms, LL.distinct())
         del LL
         torch.cuda.empty_cache()
 

@@ -93,6 +93,37 @@ __device__ __forceinline__ void gemm_stash(const u32x4 (&ra)[8], const BStage &r
     *reinterpret_cast<u32x4 *>(bp + 96 * LDS_ROW) = rb.b3;
 }
 
+// GELU for the MFMA epilogue.  The epilogue of the first GEMM handles V*D*N values with only K = d
+// multiply-adds behind each, so it has to be cheap: erf by the five-term rational/exponential
+// approximation (absolute error 1.5e-7, far below the 2^-17 of the hi/lo split), tanh through one
+// fast exponential.
+__device__ __forceinline__ float gelu_fast(float x, int act)
+{
+    if (act == MOLE_GELU_TANH) {
+        const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+        const float th = 1.0f - 2.0f * __builtin_amdgcn_rcpf(__expf(2.0f * u) + 1.0f);
+        return 0.5f * x * (1.0f + th);
+    }
+    const float z = fabsf(x) * 0.7071067811865476f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
+    float p = fmaf(1.061405429f, t, -1.453152027f);
+    p = fmaf(p, t, 1.421413741f);
+    p = fmaf(p, t, -0.284496736f);
+    p = fmaf(p, t, 0.254829592f);
+    const float y = 1.0f - p * t * __expf(-z * z);      // erf(|x| / sqrt 2)
+    return 0.5f * x * (1.0f + copysignf(y, x));
+}
+
+// round-to-nearest-even without the NaN branch (inputs are finite here), two values into one dword
+__device__ __forceinline__ uint32_t rne_pair(float a, float b)
+{
+    const uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
+    const uint32_t ra = (ua + 0x7fffu + ((ua >> 16) & 1u)) >> 16;
+    const uint32_t rb = (ub + 0x7fffu + ((ub >> 16) & 1u)) & 0xffff0000u;
+    return ra | rb;
+}
+
+template <int EPI>
 __global__ __launch_bounds__(GEMM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void gemm_nt_bf16_kernel(GemmArgs g)
 {
@@ -142,37 +173,88 @@ void gemm_nt_bf16_kernel(GemmArgs g)
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
         }
         __syncthreads();
     }
 
-    // epilogue.  Accumulator element e of lane l: column l % 32, row 8*(e/4) + 4*(l/32) + e%4.
+    // Epilogue.  The weight fragment is the MFMA's first operand, so the accumulator holds the tile
+    // transposed: lane l has output row m = l % 32 and, in elements 4q..4q+3, the four consecutive
+    // output columns n = 8q + 4*(l/32) + 0..3.  Results go through LDS (the operand tiles are dead by
+    // now) so that global memory sees full 16-byte, row-contiguous stores: four passes of 64 rows
+    // (32 from each wave row), hi plane at Cs, lo plane behind it.
     const uint16_t *bias = g.bias ? g.bias + batch * g.bias_batch_stride : nullptr;
     uint16_t *C = g.C + batch * g.c_batch_stride;
+    constexpr int CROW = BN * 2 + 8;                 // bytes per staged row (padded: conflict-free 8-byte writes)
+    constexpr int CPLANE = 64 * CROW;
+    static_assert(2 * CPLANE <= BM * LDS_ROW, "epilogue staging must fit in the A tile");
+    unsigned char *Cs = As;
+    float bv[2][4][4];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int col = n0 + wn * 64 + j * 32 + (lane & 31);
-        const float bv = bias ? bf16_to_f32(bias[col]) : 0.f;
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int q = 0; q < 4; ++q) {
+            const int col = n0 + wn * 64 + j * 32 + 8 * q + 4 * (lane >> 5);
+            uint2 b4 = make_uint2(0, 0);
+            if (bias)
+                b4 = *reinterpret_cast<const uint2 *>(bias + col);
+            bv[j][q][0] = bf16lo(b4.x); bv[j][q][1] = bf16hi(b4.x);
+            bv[j][q][2] = bf16lo(b4.y); bv[j][q][3] = bf16hi(b4.y);
+        }
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int row = m0 + wm * 128 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                if (row >= g.M)
-                    continue;
-                float v = acc[i][j][e] + bv;
-                if (g.epilogue == EPI_GELU_SPLIT) {
-                    v = gelu_f(v, g.act);
-                    const uint32_t hi = f32_to_bf16_bits(v);
-                    const uint32_t lo = f32_to_bf16_bits(v - __uint_as_float(hi << 16));
-                    C[(int64_t)row * g.ldc + col] = (uint16_t)hi;
-                    C[g.c_plane_stride + (int64_t)row * g.ldc + col] = (uint16_t)lo;
+    for (int i = 0; i < 4; ++i) {
+        // stage this pass: row wm*32 + l%32 of the 64-row slab
+        unsigned char *srow = Cs + (wm * 32 + (lane & 31)) * CROW;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int cl = wn * 64 + j * 32 + 8 * q + 4 * (lane >> 5);   // column inside the tile
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    v[e] = acc[i][j][4 * q + e] + bv[j][q][e];
+                if constexpr (EPI == EPI_GELU_SPLIT) {
+                    float lo[4];
+                    uint32_t hbits[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        v[e] = gelu_fast(v[e], g.act);
+                        const uint32_t u = __float_as_uint(v[e]);
+                        hbits[e] = (u + 0x7fffu + ((u >> 16) & 1u)) & 0xffff0000u;
+                        lo[e] = v[e] - __uint_as_float(hbits[e]);
+                    }
+                    uint2 hi2, lo2;
+                    hi2.x = (hbits[0] >> 16) | hbits[1];
+                    hi2.y = (hbits[2] >> 16) | hbits[3];
+                    lo2.x = rne_pair(lo[0], lo[1]);
+                    lo2.y = rne_pair(lo[2], lo[3]);
+                    *reinterpret_cast<uint2 *>(srow + cl * 2) = hi2;
+                    *reinterpret_cast<uint2 *>(srow + CPLANE + cl * 2) = lo2;
                 } else {
-                    C[(int64_t)row * g.ldc + col] = (uint16_t)f32_to_bf16_bits(v);
+                    uint2 o;
+                    o.x = pack_bf16(v[0], v[1]);
+                    o.y = pack_bf16(v[2], v[3]);
+                    *reinterpret_cast<uint2 *>(srow + cl * 2) = o;
                 }
             }
         }
+        __syncthreads();
+        // write out: 64 rows x 256 bytes per plane = 1024 16-byte pieces, 4 per thread and plane
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int piece = tid + u * GEMM_THREADS;
+            const int sr = piece >> 4, sc = piece & 15;                 // staged row, 16-byte column
+            const int row = m0 + (sr >> 5) * 128 + i * 32 + (sr & 31);
+            if (row < g.M) {
+                uint16_t *cp = C + (int64_t)row * g.ldc + n0 + sc * 8;
+                *reinterpret_cast<u32x4 *>(cp) = *reinterpret_cast<const u32x4 *>(Cs + sr * CROW + sc * 16);
+                if constexpr (EPI == EPI_GELU_SPLIT)
+                    *reinterpret_cast<u32x4 *>(cp + g.c_plane_stride) =
+                        *reinterpret_cast<const u32x4 *>(Cs + CPLANE + sr * CROW + sc * 16);
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -379,7 +461,7 @@ mole_status build_mfma(const void *Em, const void *W1, const void *b1, const voi
         g1.bias = static_cast<const uint16_t *>(b1); g1.bias_batch_stride = D;
         g1.C = hid; g1.ldc = D; g1.c_plane_stride = lay.slab * D; g1.c_batch_stride = 2 * lay.slab * D;
         g1.M = nv; g1.Nn = D; g1.K = d; g1.epilogue = EPI_GELU_SPLIT; g1.act = act;
-        hipLaunchKernelGGL(gemm_nt_bf16_kernel, dim3((nv + BM - 1) / BM, D / BN, N), dim3(GEMM_THREADS), 0, st, g1);
+        hipLaunchKernelGGL(gemm_nt_bf16_kernel<EPI_GELU_SPLIT>, dim3((nv + BM - 1) / BM, D / BN, N), dim3(GEMM_THREADS), 0, st, g1);
         GemmArgs g2;
         g2.A = hid; g2.lda = D; g2.a_plane_stride = lay.slab * D; g2.a_batch_stride = 2 * lay.slab * D;
         g2.a_planes = 2;
@@ -388,7 +470,7 @@ mole_status build_mfma(const void *Em, const void *W1, const void *b1, const voi
         g2.C = static_cast<uint16_t *>(LUT) + v0 * N * d; g2.ldc = (int64_t)N * d; g2.c_plane_stride = 0;
         g2.c_batch_stride = d;
         g2.M = nv; g2.Nn = d; g2.K = D; g2.epilogue = EPI_STORE; g2.act = act;
-        hipLaunchKernelGGL(gemm_nt_bf16_kernel, dim3((nv + BM - 1) / BM, d / BN, N), dim3(GEMM_THREADS), 0, st, g2);
+        hipLaunchKernelGGL(gemm_nt_bf16_kernel<EPI_STORE>, dim3((nv + BM - 1) / BM, d / BN, N), dim3(GEMM_THREADS), 0, st, g2);
     }
     MOLE_HIP_CHECK(hipGetLastError());
     return MOLE_OK;
