@@ -112,6 +112,26 @@ class Layers:
                                self.shared[l], None, self.out[l], None, None, self.err, w.T, w.V, w.d, w.N,
                                self.code, 0, None, stream=stream)
 
+    def quantize(self, bits, block, scale_bytes):
+        """NF-quantise every layer's table on the device (mole_quantize_lut)."""
+        torch, mb, w = self.torch, self.mb, self.w
+        cb = mb.mole_nf_codes_bytes(w.V, w.N, w.d, bits)
+        sb = mb.mole_nf_scales_bytes(w.V, w.N, w.d, block, scale_bytes)
+        self.nf = dict(bits=bits, block=block, scale_bytes=scale_bytes,
+                       codes=torch.empty((w.L, cb), dtype=torch.uint8, device="cuda"),
+                       scales=torch.empty((w.L, sb), dtype=torch.uint8, device="cuda"))
+        for l in range(w.L):
+            mb.mole_quantize_lut(self.tabs[l], self.nf["codes"][l], self.nf["scales"][l], w.V, w.N, w.d, bits,
+                                 block, scale_bytes)
+        torch.cuda.synchronize()
+
+    def forward_nf(self, i, stream):
+        w, mb, q = self.w, self.mb, self.nf
+        mb.mole_lookup_forward_nf(q["codes"], q["codes"].shape[1], q["scales"], q["scales"].shape[1] // q["scale_bytes"],
+                                  self.ids[i % N_ID_BATCHES], None, self.h, self.W_r, self.shared, None, self.out,
+                                  w.T * w.d, None, None, self.err, w.L, w.T, w.V, w.d, w.N, q["bits"], q["block"],
+                                  q["scale_bytes"], 0, None, stream=stream)
+
     def distinct(self):
         import numpy as np
         return float(np.mean([len(np.unique(b)) for b in self.ids_host]))
@@ -348,6 +368,10 @@ def extras(args, torch, mb, wl, acc, stream, L):
     except Exception as e:
         out["decode410m_per_layer_launches_hip_graph"] = {"skipped": repr(e)}
 
+    # ---- NF4 / NF3 tables (Sec. 5.5 of the paper): quantised on the device, dequantised inside the forward
+    for tag, bits, block, sbytes in (("nf4", 4, 1024, 4), ("nf3", 3, 128, 2)):
+        out[f"decode410m_{tag}"] = nf_entry(L, acc, torch, stream, steps, warm, bits, block, sbytes)
+
     # ---- offloaded mode on the same tables: all LUTs in pinned host memory, T = 32 ----
     try:
         out.update(offload_bench(torch, mb, wl, acc, stream, L, steps, warm))
@@ -386,11 +410,32 @@ def extras(args, torch, mb, wl, acc, stream, L):
         out[name + "_dedup_kernel_ms"] = ms
         ms = time_steps(torch, stream, planned(LL), steps, warm)
         out[name + "_forward_with_plan"] = rates(ww, acc, ms, LL.distinct())
+        if name == "prefill410m_uniform":
+            out[name + "_nf4"] = nf_entry(LL, acc, torch, stream, steps, warm, 4, 1024, 4)
         del LL
         torch.cuda.empty_cache()
 
     out["build_lut_410m_layer"] = build_bench(torch, mb, wl, acc, stream)
     return out
+
+
+def nf_entry(LL, acc, torch, stream, steps, warm, bits, block, sbytes):
+    """Quantise LL's tables and time the dequantising forward; rates against its own (smaller) byte count."""
+    w = LL.w
+    t0 = time.perf_counter()
+    LL.quantize(bits, block, sbytes)
+    t_quant = time.perf_counter() - t0
+    ms = time_steps(torch, stream, lambda i: LL.forward_nf(i, stream), steps, warm)
+    alg = acc.nf_forward_bytes_per_token(w.d, w.N, bits, block, sbytes) * w.T * w.L
+    res = {"bits": bits, "block": block, "scale_bytes": sbytes, "ms": ms,
+           "layer_tokens_per_s": w.T * w.L / (ms * 1e-3), "algorithmic_bytes_per_launch": alg,
+           "algorithmic_GBps": alg / (ms * 1e-3) / 1e9, "algorithmic_frac_of_hbm_peak": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+           "table_bytes": acc.nf_table_bytes(w.V, w.N, w.d, bits, block, sbytes) * w.L,
+           "table_ratio_to_bf16": acc.nf_table_bytes(w.V, w.N, w.d, bits, block, sbytes) / (w.V * w.N * w.d * 2),
+           "quantise_all_layers_s": t_quant}
+    del LL.nf
+    torch.cuda.empty_cache()
+    return res
 
 
 def offload_bench(torch, mb, wl, acc, stream, L, steps, warm):

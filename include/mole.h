@@ -152,6 +152,47 @@ mole_status mole_offload_fetch(const void *host_table, int64_t host_layer_stride
                                int L, int U_cap, int64_t V, int d, int N, mole_dtype dtype,
                                void *hip_stream);
 
+/* ------------------------------------------------------------------------------------------
+ * NormalFloat-quantised tables (Sec. 5.5, Table 8: NF4 / NF3 post-training quantisation of the
+ * LUT with token-wise blocks of 768 / 128 elements -> 25.3 % / 19.5 % of the 16-bit size).
+ *
+ * NF-k levels: 2^k quantiles of N(0,1) normalised to [-1,1] with an exact zero (the data type of
+ * the QLoRA paper; the outermost quantile is taken at probability 1 - 1/(2*2^k)).
+ * mole_nf_codebook writes the 2^bits levels (ascending) to host memory and returns their count.
+ *
+ * Storage of a table [rows, N, d]:
+ *   codes  [rows, N, d*bits/8] bytes.  NF4: two codes per byte, element 2i in the low nibble.
+ *          NF3: every 8 consecutive elements form a 24-bit word (element e in bits 3e..3e+2);
+ *          per row the low 16 bits of all words first (d/4 bytes), then their high 8 bits (d/8).
+ *   scales [rows, N, d/block], fp32 (scale_bytes = 4) or bf16 (scale_bytes = 2): max |x| of the block
+ *          (buffer size from mole_nf_scales_bytes, which rounds up to 16 bytes).
+ * Rule: xn = x / scale in fp32 (0 if scale == 0); code = number of level midpoints below xn;
+ * value = level[code] * scale.  bits in {3, 4}; d a multiple of 8 (NF4) / 16 (NF3); block a
+ * multiple of 8 dividing d.  The paper's settings: (bits 4, block 768, scale_bytes 4) and
+ * (bits 3, block 128, scale_bytes 2).
+ *
+ * mole_quantize_lut: table bf16 [rows,N,d] dev -> codes, scales dev (sizes from the two helpers).
+ * mole_lookup_forward_nf: the fused forward of mole_lookup_forward_layers with the rows
+ * dequantised on the fly; activations bf16; codes_stride in BYTES per layer, scales_stride and
+ * act_stride in ELEMENTS per layer (ignored for L == 1).  N in {4, 8, 16, 32, 64}.
+ * ---------------------------------------------------------------------------------------- */
+int mole_nf_codebook(int bits, float *levels_host);
+size_t mole_nf_codes_bytes(int64_t rows, int N, int d, int bits);
+size_t mole_nf_scales_bytes(int64_t rows, int N, int d, int block, int scale_bytes);
+mole_status mole_quantize_lut(const void *table, void *codes, void *scales,
+                              int64_t rows, int N, int d, int bits, int block, int scale_bytes,
+                              void *hip_stream);
+mole_status mole_lookup_forward_nf(const void *codes, int64_t codes_stride,
+                                   const void *scales, int64_t scales_stride,
+                                   const int32_t *ids, const int32_t *slot,
+                                   const void *h, const void *W_r,
+                                   const void *shared_out, const void *residual,
+                                   void *out, int64_t act_stride,
+                                   float *gates_dbg, int64_t *rows_dbg, int32_t *err_flag,
+                                   int L, int T, int64_t rows, int d, int N,
+                                   int bits, int block, int scale_bytes, unsigned flags,
+                                   const void *workspace, size_t workspace_bytes, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

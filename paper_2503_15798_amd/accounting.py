@@ -47,3 +47,15 @@ def build_flops(V: int, d: int, D: int, N: int) -> int:
     """Two GEMMs of V x d x D per expert, 2 flop per multiply-add: 4*V*d*D*N (cf. the
     4*d*D per-token FFN cost of the complexity section)."""
     return 4 * V * d * D * N
+
+
+def nf_table_bytes(rows: int, N: int, d: int, bits: int, block: int, scale_bytes: int) -> int:
+    """Size of an NF-quantised table (Sec. 5.5, Table 8): bits per element plus one scale per block."""
+    return rows * N * (d * bits // 8 + (d // block) * scale_bytes)
+
+
+def nf_forward_bytes_per_token(d: int, N: int, bits: int, block: int, scale_bytes: int, residual: bool = False) -> int:
+    """Algorithmic bytes of the dequantising forward per (layer, token): packed rows and scales,
+    bf16 h / shared / out (+ residual), and the 4-byte id."""
+    acts = 3 + (1 if residual else 0)
+    return N * (d * bits // 8 + (d // block) * scale_bytes) + acts * 2 * d + 4

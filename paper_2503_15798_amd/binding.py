@@ -25,7 +25,8 @@ _STATUS_NAMES = {0: "MOLE_OK", 1: "MOLE_EINVAL", 2: "MOLE_EUNSUPPORTED", 3: "MOL
 # every symbol include/mole.h declares
 EXPORTS = ("mole_last_error", "mole_version", "mole_build_lut_workspace", "mole_build_lut",
            "mole_dedup_workspace", "mole_dedup_ids", "mole_lookup_forward",
-           "mole_lookup_forward_layers", "mole_offload_fetch")
+           "mole_lookup_forward_layers", "mole_offload_fetch", "mole_nf_codebook", "mole_nf_codes_bytes",
+           "mole_nf_scales_bytes", "mole_quantize_lut", "mole_lookup_forward_nf")
 
 
 class MoleError(RuntimeError):
@@ -70,6 +71,18 @@ def lib() -> ctypes.CDLL:
     L.mole_offload_fetch.restype = c_i32
     L.mole_offload_fetch.argtypes = [c_void, c_i64, c_void, c_void, c_void, c_i64, c_void,
                                      c_i32, c_i32, c_i64, c_i32, c_i32, c_i32, c_void]
+    L.mole_nf_codebook.restype = c_i32
+    L.mole_nf_codebook.argtypes = [c_i32, c_void]
+    L.mole_nf_codes_bytes.restype = c_sz
+    L.mole_nf_codes_bytes.argtypes = [c_i64, c_i32, c_i32, c_i32]
+    L.mole_nf_scales_bytes.restype = c_sz
+    L.mole_nf_scales_bytes.argtypes = [c_i64, c_i32, c_i32, c_i32, c_i32]
+    L.mole_quantize_lut.restype = c_i32
+    L.mole_quantize_lut.argtypes = [c_void, c_void, c_void, c_i64, c_i32, c_i32, c_i32, c_i32, c_i32, c_void]
+    L.mole_lookup_forward_nf.restype = c_i32
+    L.mole_lookup_forward_nf.argtypes = ([c_void, c_i64, c_void, c_i64] + [c_void] * 7 + [c_i64] + [c_void] * 3 +
+                                         [c_i32, c_i32, c_i64, c_i32, c_i32, c_i32, c_i32, c_i32, c_u, c_void, c_sz,
+                                          c_void])
     _lib = L
     return L
 
@@ -158,3 +171,35 @@ def mole_offload_fetch(host_table, host_layer_stride: int, uniq, n_uniq, staging
     _check(lib().mole_offload_fetch(_ptr(host_table), host_layer_stride, _ptr(uniq), _ptr(n_uniq), _ptr(staging),
                                     staging_layer_stride, _ptr(err_flag), L, U_cap, V, d, N, dtype,
                                     _stream(stream)))
+
+
+def mole_nf_codebook(bits: int):
+    """The 2^bits NF levels as a list of floats (empty for an unsupported width)."""
+    buf = (ctypes.c_float * 16)()
+    n = lib().mole_nf_codebook(bits, ctypes.cast(buf, ctypes.c_void_p))
+    return [buf[i] for i in range(n)]
+
+
+def mole_nf_codes_bytes(rows: int, N: int, d: int, bits: int) -> int:
+    return lib().mole_nf_codes_bytes(rows, N, d, bits)
+
+
+def mole_nf_scales_bytes(rows: int, N: int, d: int, block: int, scale_bytes: int) -> int:
+    return lib().mole_nf_scales_bytes(rows, N, d, block, scale_bytes)
+
+
+def mole_quantize_lut(table, codes, scales, rows: int, N: int, d: int, bits: int, block: int, scale_bytes: int,
+                      stream=None) -> None:
+    _check(lib().mole_quantize_lut(_ptr(table), _ptr(codes), _ptr(scales), rows, N, d, bits, block, scale_bytes,
+                                   _stream(stream)))
+
+
+def mole_lookup_forward_nf(codes, codes_stride: int, scales, scales_stride: int, ids, slot, h, W_r, shared_out,
+                           residual, out, act_stride: int, gates_dbg, rows_dbg, err_flag, L: int, T: int, rows: int,
+                           d: int, N: int, bits: int, block: int, scale_bytes: int, flags: int = 0, workspace=None,
+                           stream=None, workspace_bytes: Optional[int] = None) -> None:
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().mole_lookup_forward_nf(_ptr(codes), codes_stride, _ptr(scales), scales_stride, _ptr(ids), _ptr(slot),
+                                        _ptr(h), _ptr(W_r), _ptr(shared_out), _ptr(residual), _ptr(out), act_stride,
+                                        _ptr(gates_dbg), _ptr(rows_dbg), _ptr(err_flag), L, T, rows, d, N, bits, block,
+                                        scale_bytes, flags, _ptr(workspace), wb, _stream(stream)))

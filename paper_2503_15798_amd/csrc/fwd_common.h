@@ -1,0 +1,228 @@
+// Device helpers shared by the forward kernels (bf16 tables and NF-quantised tables): visiting
+// order, the LDS-resident router (Sec. 3.2 router equation), streaming loads and stores, epilogue.
+#ifndef MOLE_FWD_COMMON_H
+#define MOLE_FWD_COMMON_H
+
+#include "mole_internal.h"
+
+namespace mole {
+
+// Visiting order.  Without a plan token i is item i.  With the plan of mole_dedup_ids the tokens
+// are visited in id order, so equal ids are adjacent in time and place (same workgroup, same
+// XCD): the repeats of a row block are then served by that L2 instead of crossing the fabric
+// again.  `single` is true when the plan says the id occurs once in the batch.
+struct Visit {
+    int t;
+    bool single;
+};
+__device__ __forceinline__ Visit visit(const int32_t *order, int item)
+{
+    Visit v;
+    if (order) {
+        const uint32_t o = (uint32_t)__builtin_amdgcn_readfirstlane(order[item]);
+        v.t = (int)(o & ~PLAN_SINGLE);
+        v.single = (o & PLAN_SINGLE) != 0;
+    } else {
+        v.t = item;
+        v.single = false;
+    }
+    return v;
+}
+
+// false (and *err_flag = 2) if `plan` was not written by mole_dedup_ids for T tokens
+template <typename Args>
+__device__ __forceinline__ bool plan_ok(const Args &a)
+{
+    if (a.plan[5] == PLAN_MAGIC && a.plan[2] == a.T)
+        return true;
+    if (threadIdx.x == 0 && a.err_flag)
+        *a.err_flag = 2;
+    return false;
+}
+
+// acc += h[k]*w[k] + h[k+1]*w[k+1] for one packed pair of bf16 operands, fp32 accumulation
+__device__ __forceinline__ float mac2(float acc, uint32_t hp, uint32_t wp)
+{
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, hp), __builtin_bit_cast(bf16x2, wp), acc, false);
+}
+
+// Fold N per-lane partial sums over the 64 lanes.  Each step halves the number of values a
+// lane carries by trading one half with the lane `W` away.  Returns, in every lane, the full
+// sum of value j = lane >> log2(64/N).
+template <int N, int W>
+struct Fold {
+    static __device__ __forceinline__ float run(float *z, int lane)
+    {
+        if constexpr (N == 1) {
+            float v = z[0];
+#pragma unroll
+            for (int w = W; w >= 1; w >>= 1)
+                v += __shfl_xor(v, w);
+            return v;
+        } else {
+            const bool up = (lane & W) != 0;
+#pragma unroll
+            for (int i = 0; i < N / 2; ++i) {
+                const float send = up ? z[i] : z[i + N / 2];
+                const float keep = up ? z[i + N / 2] : z[i];
+                z[i] = keep + __shfl_xor(send, W);
+            }
+            return Fold<N / 2, W / 2>::run(z, lane);
+        }
+    }
+};
+
+// Activations are read once and written once per call.  Stores are always non-temporal; loads are
+// non-temporal (NTA) in the large-batch regime, where keeping them out of L2 / Infinity Cache leaves
+// more room for table rows (which ARE reused across tokens with equal ids).  For small batches the
+// plain load is used: it returns sooner, and latency is what bounds those launches.
+template <bool NTA>
+__device__ __forceinline__ uint4 ld16_stream(const uint16_t *p)
+{
+    if constexpr (NTA) {
+        typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+        return make_uint4(v.x, v.y, v.z, v.w);
+    } else {
+        return *reinterpret_cast<const uint4 *>(p);
+    }
+}
+__device__ __forceinline__ void st16_stream(uint16_t *p, const uint4 &o)
+{
+    typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+    const u32x4 v = {o.x, o.y, o.z, o.w};
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(p));
+}
+
+template <bool NT>
+__device__ __forceinline__ uint4 ld16_row(const uint16_t *p)
+{
+    return ld16_stream<NT>(p);
+}
+
+// Router weight [d, N] -> LDS as (W[k,j], W[k+1,j]) bf16 pairs; the 16-byte piece holding
+// experts 4*jq..4*jq+3 of k-pair q of k-group kg sits at index (q*N/4 + jq)*kgroups + kg, so
+// that lanes (consecutive kg) read consecutive 16-byte pieces.
+template <int N>
+__device__ __forceinline__ void fill_router_lds(uint4 *smem, const uint16_t *Wr, int kgroups, int nthreads)
+{
+    constexpr int NQ = N / 4;
+    const int n_w4 = kgroups * N;
+    for (int i = threadIdx.x; i < n_w4; i += nthreads) {
+        const int kg = i % kgroups;
+        const int pj = i / kgroups;
+        const int jq = pj % NQ;
+        const int q = pj / NQ;
+        const int k0 = kg * 8 + q * 2;
+        const uint2 w0 = *reinterpret_cast<const uint2 *>(Wr + (int64_t)k0 * N + jq * 4);
+        const uint2 w1 = *reinterpret_cast<const uint2 *>(Wr + (int64_t)(k0 + 1) * N + jq * 4);
+        uint4 v;
+        v.x = (w0.x & 0xffffu) | (w1.x << 16);
+        v.y = (w0.x >> 16) | (w1.x & 0xffff0000u);
+        v.z = (w0.y & 0xffffu) | (w1.y << 16);
+        v.w = (w0.y >> 16) | (w1.y & 0xffff0000u);
+        smem[i] = v;
+    }
+}
+
+// z[j] += sum over the lane's 8 k of h[k] * W_r[k, j], for one 16-byte piece of h (k-group kg)
+template <int N>
+__device__ __forceinline__ void router_piece(float (&z)[N], const uint4 *smem, int kgroups, const uint4 &hv, int kg)
+{
+    constexpr int NQ = N / 4;
+    const uint32_t hp[4] = {hv.x, hv.y, hv.z, hv.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+        for (int jq = 0; jq < NQ; ++jq) {
+            const uint4 w = smem[(q * NQ + jq) * kgroups + kg];
+            z[4 * jq + 0] = mac2(z[4 * jq + 0], hp[q], w.x);
+            z[4 * jq + 1] = mac2(z[4 * jq + 1], hp[q], w.y);
+            z[4 * jq + 2] = mac2(z[4 * jq + 2], hp[q], w.z);
+            z[4 * jq + 3] = mac2(z[4 * jq + 3], hp[q], w.w);
+        }
+    }
+}
+
+// Router equation for one token on one wavefront: returns, in lane l, the gate of expert
+// l / (64/N) (softmax over all N experts of h . r_j).  h0 / h1 are the lane's pieces of the first
+// two 512-column chunks, already loaded by the caller; further chunks are loaded here.
+template <int N, bool NTA>
+__device__ __forceinline__ float router_gate(const uint4 *smem, int kgroups, const uint16_t *hrow, int d, int lane,
+                                             const uint4 &h0, const uint4 &h1)
+{
+    constexpr int LPJ = 64 / N;
+    float z[N];
+#pragma unroll
+    for (int j = 0; j < N; ++j)
+        z[j] = 0.f;
+    const int col0 = lane * 8;
+    if (col0 < d)
+        router_piece<N>(z, smem, kgroups, h0, col0 >> 3);
+    if (col0 + 512 < d)
+        router_piece<N>(z, smem, kgroups, h1, (col0 + 512) >> 3);
+    for (int c0 = 1024; c0 < d; c0 += 512) {
+        const int cc = c0 + col0;
+        if (cc < d)
+            router_piece<N>(z, smem, kgroups, ld16_stream<NTA>(hrow + cc), cc >> 3);
+    }
+    const float zz = Fold<N, 32>::run(z, lane);
+    float m = zz;
+#pragma unroll
+    for (int w = 32; w >= LPJ; w >>= 1)
+        m = fmaxf(m, __shfl_xor(m, w));
+    const float e = __expf(zz - m);
+    float s = e;
+#pragma unroll
+    for (int w = 32; w >= LPJ; w >>= 1)
+        s += __shfl_xor(s, w);
+    return e / s;
+}
+
+// the lane's pieces of h for the first two chunks (zero where the chunk does not exist)
+template <bool NTA>
+__device__ __forceinline__ void load_h2(uint4 &h0, uint4 &h1, const uint16_t *hrow, int d, int lane)
+{
+    const int col0 = lane * 8;
+    h0 = col0 < d ? ld16_stream<NTA>(hrow + col0) : make_uint4(0, 0, 0, 0);
+    h1 = col0 + 512 < d ? ld16_stream<NTA>(hrow + col0 + 512) : make_uint4(0, 0, 0, 0);
+}
+
+// acc[0..7] += g * (the 8 bf16 values of one 16-byte piece)
+__device__ __forceinline__ void fma8(float (&acc)[8], float g, const uint4 &rr)
+{
+    acc[0] = fmaf(g, bf16lo(rr.x), acc[0]);
+    acc[1] = fmaf(g, bf16hi(rr.x), acc[1]);
+    acc[2] = fmaf(g, bf16lo(rr.y), acc[2]);
+    acc[3] = fmaf(g, bf16hi(rr.y), acc[3]);
+    acc[4] = fmaf(g, bf16lo(rr.z), acc[4]);
+    acc[5] = fmaf(g, bf16hi(rr.z), acc[5]);
+    acc[6] = fmaf(g, bf16lo(rr.w), acc[6]);
+    acc[7] = fmaf(g, bf16hi(rr.w), acc[7]);
+}
+
+__device__ __forceinline__ void add8(float (&acc)[8], const uint4 &v)
+{
+    acc[0] += bf16lo(v.x);
+    acc[1] += bf16hi(v.x);
+    acc[2] += bf16lo(v.y);
+    acc[3] += bf16hi(v.y);
+    acc[4] += bf16lo(v.z);
+    acc[5] += bf16hi(v.z);
+    acc[6] += bf16lo(v.w);
+    acc[7] += bf16hi(v.w);
+}
+
+__device__ __forceinline__ uint4 pack8(const float (&acc)[8])
+{
+    uint4 o;
+    o.x = pack_bf16(acc[0], acc[1]);
+    o.y = pack_bf16(acc[2], acc[3]);
+    o.z = pack_bf16(acc[4], acc[5]);
+    o.w = pack_bf16(acc[6], acc[7]);
+    return o;
+}
+
+}  // namespace mole
+#endif

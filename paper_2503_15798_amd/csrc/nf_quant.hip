@@ -1,0 +1,466 @@
+// NormalFloat-quantised lookup tables: quantiser and fused dequantising forward.
+//
+// Paper: Sec. 5.5 and Table 8 -- the 16-bit LUTs are post-training quantised to NF4 / NF3 (the
+// data types of the QLoRA paper) with token-wise blocks of 768 / 128 elements, which cuts storage
+// and per-token traffic to 25.3 % / 19.5 %.  Those ratios imply one 32-bit absmax per 768-element
+// NF4 block and one 16-bit absmax per 128-element NF3 block; both widths are supported for both
+// types (for a bf16 table the absmax is itself a bf16 value, so the 16-bit scale is exact).
+//
+// Format of one row (d elements) of expert j of id v:
+//   NF4: d/2 bytes, two codes per byte, element 2i in the low nibble;
+//   NF3: every 8 consecutive elements form a 24-bit word (element e in bits 3e..3e+2); the low 16
+//        bits of all words come first (d/4 bytes), then their high 8 bits (d/8 bytes) -- so that a
+//        lane's eight elements are one aligned 16-bit load and one 8-bit load, not a 3-byte access;
+//   scales: [rows, N, d/block] fp32 or bf16, in a buffer of their own.
+// Quantisation rule (every decision in fp32): s = max|x| over the block; xn = x / s (IEEE
+// division, 0 if s == 0); code = number of level midpoints below xn (a tie goes down);
+// dequantised value = level[code] * s.
+//
+// The forward kernel is the bf16 streaming kernel with the row ring replaced by code words: a
+// lane's eight columns of one row are 4 bytes (NF4) or 3 bytes (NF3), so ALL rows of a token's
+// 512-column chunk sit in N registers and the next chunk / next token is prefetched behind them.
+// Levels are looked up in a 16-entry fp32 table in LDS (one entry per bank: conflict-free).
+#include "fwd_common.h"
+#include "nf_codebook.h"
+
+namespace {
+using namespace mole;
+
+struct NfArgs {
+    const uint8_t *codes;
+    const void *scales;
+    const int32_t *ids;
+    const int32_t *slot;
+    const void *h;
+    const void *W_r;
+    const void *shared;
+    const void *residual;
+    void *out;
+    float *gates_dbg;
+    int64_t *rows_dbg;
+    int32_t *err_flag;
+    const int32_t *plan;
+    int64_t codes_stride;    // per layer, bytes
+    int64_t scales_stride;   // per layer, elements
+    int64_t act_stride;      // per layer, elements
+    int64_t rows;
+    int T, d, N, L;
+    int block;               // elements per scale
+};
+
+// A scale is fetched as a raw dword (the fp32 value, or the aligned dword holding the bf16 value) and
+// decoded only where it is used: any arithmetic right behind a load makes the compiler wait for that
+// load before it issues the next one, which serialises the N loads of a chunk (measured: 1.7x on the
+// whole kernel).
+__device__ __forceinline__ uint32_t load_scale_raw(const void *scales, int scale_bytes, int64_t idx)
+{
+    return static_cast<const uint32_t *>(scales)[scale_bytes == 4 ? idx : idx >> 1];
+}
+__device__ __forceinline__ float decode_scale(uint32_t raw, int scale_bytes, int odd)
+{
+    if (scale_bytes == 4)
+        return __uint_as_float(raw);
+    return odd ? bf16hi(raw) : bf16lo(raw);
+}
+
+// ------------------------------------------------------------------------------------------
+// quantiser: one wavefront per table row (d elements); lane l holds pieces of 8 elements
+// ------------------------------------------------------------------------------------------
+template <int BITS>
+__global__ __launch_bounds__(256) void nf_quantize_kernel(const uint16_t *__restrict__ table,
+                                                           uint8_t *__restrict__ codes, void *__restrict__ scales,
+                                                           int64_t n_rows, int d, int block, int scale_bytes)
+{
+    constexpr int NLEV = 1 << BITS;
+    const float *mids = BITS == 4 ? NF4_MIDPOINTS : NF3_MIDPOINTS;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= n_rows)
+        return;
+    const uint16_t *src = table + row * d;
+    const int row_bytes = d * BITS / 8;
+    uint8_t *dst = codes + row * row_bytes;
+    const int nblk = d / block;
+    for (int c0 = 0; c0 < d; c0 += 512) {
+        const int col = c0 + lane * 8;
+        const bool on = col < d;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (on)
+            v = *reinterpret_cast<const uint4 *>(src + col);
+        float x[8] = {bf16lo(v.x), bf16hi(v.x), bf16lo(v.y), bf16hi(v.y),
+                      bf16lo(v.z), bf16hi(v.z), bf16lo(v.w), bf16hi(v.w)};
+        float amax = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            amax = fmaxf(amax, fabsf(x[e]));
+        // absmax of each block that touches this chunk.  Blocks are multiples of 8 elements, so a
+        // lane's piece lies in one block.  When blocks cannot straddle a chunk boundary (block divides
+        // 512) the lanes of equal block index are reduced; otherwise the block is re-scanned whole.
+        const int blk = on ? col / block : -1;
+        float s = 0.f;
+        const int b_lo = c0 / block, b_hi = min(nblk - 1, (min(c0 + 512, d) - 1) / block);
+        for (int b = b_lo; b <= b_hi; ++b) {
+            float m = 0.f;
+            if (512 % block == 0) {
+                m = blk == b ? amax : 0.f;
+            } else {
+                for (int c1 = b * block + lane * 8; c1 < (b + 1) * block; c1 += 512) {
+                    const uint4 u = *reinterpret_cast<const uint4 *>(src + c1);
+                    m = fmaxf(m, fmaxf(fmaxf(fmaxf(fabsf(bf16lo(u.x)), fabsf(bf16hi(u.x))),
+                                             fmaxf(fabsf(bf16lo(u.y)), fabsf(bf16hi(u.y)))),
+                                       fmaxf(fmaxf(fabsf(bf16lo(u.z)), fabsf(bf16hi(u.z))),
+                                             fmaxf(fabsf(bf16lo(u.w)), fabsf(bf16hi(u.w))))));
+                }
+            }
+#pragma unroll
+            for (int w = 32; w >= 1; w >>= 1)
+                m = fmaxf(m, __shfl_xor(m, w));
+            if (blk == b)
+                s = m;
+            if (lane == 0 && b * block >= c0 && b * block < c0 + 512) {   // once: by the chunk where the block starts
+                const int64_t si = row * nblk + b;
+                if (scale_bytes == 4)
+                    static_cast<float *>(scales)[si] = m;
+                else
+                    static_cast<uint16_t *>(scales)[si] = (uint16_t)f32_to_bf16_bits(m);
+            }
+        }
+        if (!on)
+            continue;
+        uint32_t code[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float xn = s > 0.f ? x[e] / s : 0.f;
+            uint32_t c = 0;
+#pragma unroll
+            for (int i = 0; i < NLEV - 1; ++i)
+                c += xn > mids[i] ? 1u : 0u;
+            code[e] = c;
+        }
+        if (BITS == 4) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                w |= code[e] << (4 * e);
+            *reinterpret_cast<uint32_t *>(dst + col / 2) = w;
+        } else {
+            uint32_t w = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                w |= code[e] << (3 * e);
+            *reinterpret_cast<uint16_t *>(dst + col / 4) = (uint16_t)(w & 0xffffu);
+            dst[d / 4 + col / 8] = (uint8_t)(w >> 16);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// fused dequantising forward
+// ------------------------------------------------------------------------------------------
+// code word of the lane's 8 columns of row j, chunk at column `col`: NF4 one dword (4 bits per
+// element); NF3 the 24-bit word (3 bits per element) assembled from its two planes
+// (the two NF3 planes are kept as loaded and joined where they are used, see load_scale_raw)
+template <int BITS>
+__device__ __forceinline__ void load_codes(uint32_t &lo, uint32_t &hi, const uint8_t *rowp, int d, int col)
+{
+    if (BITS == 4) {
+        lo = *reinterpret_cast<const uint32_t *>(rowp + col / 2);
+        hi = 0;
+    } else {
+        lo = *reinterpret_cast<const uint16_t *>(rowp + col / 4);
+        hi = rowp[d / 4 + col / 8];
+    }
+}
+
+template <int BITS>
+__device__ __forceinline__ void dequant_fma8(float (&acc)[8], float gs, uint32_t w, const float *cb)
+{
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const uint32_t c = (w >> (BITS * e)) & ((1u << BITS) - 1u);
+        acc[e] = fmaf(gs, cb[c], acc[e]);
+    }
+}
+
+template <int N, int BITS, int WPB>
+__global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_bytes)
+{
+    extern __shared__ uint4 smem[];
+    constexpr int LPJ = 64 / N;
+    constexpr int NLEV = 1 << BITS;
+    const int d = a.d;
+    const int kgroups = d >> 3;
+    const int layer = blockIdx.y;
+    const int n_w4 = kgroups * N;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int col0 = lane * 8;
+    const int T = a.T;
+    const int row_bytes = d * BITS / 8;
+    const int nblk = d / a.block;
+
+    const uint8_t *codes = a.codes + (int64_t)layer * a.codes_stride;
+    const int64_t sc_off = (int64_t)layer * a.scales_stride;
+    const int64_t act_off = (int64_t)layer * a.act_stride;
+    const uint16_t *hbase = static_cast<const uint16_t *>(a.h) + act_off;
+    const uint16_t *sbase = a.shared ? static_cast<const uint16_t *>(a.shared) + act_off : nullptr;
+    const uint16_t *rbase = a.residual ? static_cast<const uint16_t *>(a.residual) + act_off : nullptr;
+    uint16_t *obase = static_cast<uint16_t *>(a.out) + act_off;
+    const int32_t *rowsrc = a.slot ? a.slot : a.ids;
+    const int stride = gridDim.x * WPB;
+    const int32_t *order = nullptr;
+    if (a.plan) {
+        if (!plan_ok(a))
+            return;
+        order = a.plan + plan_layout(T).order;
+    }
+
+    // level table behind the router weight
+    float *cb = reinterpret_cast<float *>(smem + n_w4);
+    if (threadIdx.x < NLEV)
+        cb[threadIdx.x] = BITS == 4 ? NF4_LEVELS[threadIdx.x] : NF3_LEVELS[threadIdx.x];
+    fill_router_lds<N>(smem, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
+    __syncthreads();
+
+    // code words and scales of the wave's first token go in flight before anything else
+    int sc_odd = 0;   // parity of the scale index of row 0 of the chunk held in sc[] (bf16 scales)
+    auto load_chunk = [&](uint32_t (&cw)[N], uint32_t (&ch)[N], uint32_t (&sc)[N], int64_t row, int col) {
+        const uint8_t *rp = codes + row * (int64_t)N * row_bytes;
+        const int64_t sidx = sc_off + row * (int64_t)N * nblk + col / a.block;
+        sc_odd = (int)(sidx & 1);
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            load_codes<BITS>(cw[j], ch[j], rp + (int64_t)j * row_bytes, d, col);
+            sc[j] = load_scale_raw(a.scales, scale_bytes, sidx + (int64_t)j * nblk);
+        }
+    };
+    const int dlast = d - 8;
+    int item = blockIdx.x * WPB + wave;
+    int t = item < T ? visit(order, item).t : 0;
+    int64_t row = item < T ? (int64_t)__builtin_amdgcn_readfirstlane(rowsrc[t]) : -1;
+    bool valid = row >= 0 && row < a.rows;
+    uint32_t cw[N], ch[N], sc[N];
+    if (valid)
+        load_chunk(cw, ch, sc, row, min(col0, dlast));
+    uint4 h0, h1;
+    load_h2<false>(h0, h1, hbase + (int64_t)t * d, d, lane);
+
+    for (; item < T; item += stride) {
+        const int nitem = item + stride;
+        const int nt = nitem < T ? visit(order, nitem).t : 0;
+        const int64_t nrow = nitem < T ? (int64_t)__builtin_amdgcn_readfirstlane(rowsrc[nt]) : -1;
+        const bool nvalid = nrow >= 0 && nrow < a.rows;
+        if (!valid && lane == 0 && a.err_flag)
+            *a.err_flag = 1;
+        if (a.rows_dbg && layer == 0 && lane == 0)
+            a.rows_dbg[t] = valid ? row : -1;
+
+        const float g = router_gate<N, false>(smem, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1);
+        if (a.gates_dbg && (lane & (LPJ - 1)) == 0)
+            a.gates_dbg[((int64_t)layer * T + t) * N + lane / LPJ] = g;
+        load_h2<false>(h0, h1, hbase + (int64_t)nt * d, d, lane);
+        float gs[N];
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+            gs[j] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, g), j * LPJ));
+
+        for (int c0 = 0; c0 < d; c0 += 512) {
+            const int cc = c0 + col0;
+            const bool on = cc < d;
+            const bool last = c0 + 512 >= d;
+            const int64_t off = (int64_t)t * d + cc;
+            uint4 sv = make_uint4(0, 0, 0, 0), rv = make_uint4(0, 0, 0, 0);
+            if (on && sbase)
+                sv = ld16_stream<true>(sbase + off);
+            if (on && rbase)
+                rv = ld16_stream<true>(rbase + off);
+            // the products gate x scale, then the registers are free for the next chunk's words
+            uint32_t w[N];
+            float gsc[N];
+#pragma unroll
+            for (int j = 0; j < N; ++j) {
+                w[j] = BITS == 4 ? cw[j] : (cw[j] | (ch[j] << 16));
+                gsc[j] = gs[j] * decode_scale(sc[j], scale_bytes, (sc_odd + j * nblk) & 1);
+            }
+            if (last ? nvalid : valid)
+                load_chunk(cw, ch, sc, last ? nrow : row, min(last ? col0 : cc + 512, dlast));
+            float acc[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                acc[e] = 0.f;
+            if (valid) {
+#pragma unroll
+                for (int j = 0; j < N; ++j)
+                    dequant_fma8<BITS>(acc, gsc[j], w[j], cb);
+            }
+            add8(acc, sv);
+            add8(acc, rv);
+            if (on)
+                st16_stream(obase + off, pack8(acc));
+        }
+        row = nrow;
+        valid = nvalid;
+        t = nt;
+    }
+}
+
+mole_status nf_params_status(int d, int bits, int block, int scale_bytes, const char *who)
+{
+    if (bits != 3 && bits != 4)
+        return fail(MOLE_EUNSUPPORTED, "%s: bits=%d, NF3 and NF4 are built", who, bits);
+    if (scale_bytes != 2 && scale_bytes != 4)
+        return fail(MOLE_EINVAL, "%s: scale_bytes=%d must be 2 (bf16) or 4 (fp32)", who, scale_bytes);
+    const int dmul = bits == 3 ? 16 : 8;
+    if (d < dmul || d % dmul || block < 8 || block % 8 || d % block)
+        return fail(MOLE_EUNSUPPORTED, "%s: d=%d must be a multiple of %d and block=%d a multiple of 8 dividing d",
+                    who, d, dmul, block);
+    return MOLE_OK;
+}
+
+template <int N, int BITS>
+mole_status launch_nf(const NfArgs &a, int scale_bytes, hipStream_t stream)
+{
+    constexpr int WPB = 4;
+    const size_t lds = (size_t)a.d * N * 2 + 64;
+    static size_t attr_set = 0;
+    if (lds > attr_set) {
+        MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_nf_kernel<N, BITS, WPB>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = lds;
+    }
+    int per_cu = (int)((160 * 1024) / lds);
+    if (per_cu > 4)
+        per_cu = 4;
+    if (per_cu < 1)
+        per_cu = 1;
+    int64_t cap = (int64_t)num_cus() * per_cu / a.L;
+    if (cap < 1)
+        cap = 1;
+    int64_t gx = (a.T + WPB - 1) / WPB;
+    if (gx > cap) {
+        const int64_t ipw = (a.T + cap * WPB - 1) / (cap * WPB);
+        gx = (a.T + WPB * ipw - 1) / (WPB * ipw);
+    }
+    hipLaunchKernelGGL((fwd_nf_kernel<N, BITS, WPB>), dim3((unsigned)gx, (unsigned)a.L), dim3(WPB * 64), lds, stream,
+                       a, scale_bytes);
+    MOLE_HIP_CHECK(hipGetLastError());
+    return MOLE_OK;
+}
+
+template <int BITS>
+mole_status launch_nf_n(const NfArgs &a, int scale_bytes, hipStream_t stream)
+{
+    switch (a.N) {
+    case 4: return launch_nf<4, BITS>(a, scale_bytes, stream);
+    case 8: return launch_nf<8, BITS>(a, scale_bytes, stream);
+    case 16: return launch_nf<16, BITS>(a, scale_bytes, stream);
+    case 32: return launch_nf<32, BITS>(a, scale_bytes, stream);
+    case 64: return launch_nf<64, BITS>(a, scale_bytes, stream);
+    default: return fail(MOLE_EUNSUPPORTED, "mole_lookup_forward_nf: N=%d, built for 4, 8, 16, 32, 64", a.N);
+    }
+}
+
+}  // namespace
+
+extern "C" int mole_nf_codebook(int bits, float *levels_host)
+{
+    if (!levels_host || (bits != 3 && bits != 4))
+        return 0;
+    const float *src = bits == 4 ? NF4_LEVELS : NF3_LEVELS;
+    for (int i = 0; i < (1 << bits); ++i)
+        levels_host[i] = src[i];
+    return 1 << bits;
+}
+
+extern "C" size_t mole_nf_codes_bytes(int64_t rows, int N, int d, int bits)
+{
+    if (rows < 0 || N < 1 || d < 8 || d % 8 || (bits != 3 && bits != 4))
+        return 0;
+    return (size_t)rows * N * (size_t)(d * bits / 8);
+}
+
+extern "C" size_t mole_nf_scales_bytes(int64_t rows, int N, int d, int block, int scale_bytes)
+{
+    if (rows < 0 || N < 1 || d < 8 || block < 8 || d % block || (scale_bytes != 2 && scale_bytes != 4))
+        return 0;
+    // rounded up to 16 bytes: bf16 scales are read as aligned dwords
+    return ((size_t)rows * N * (size_t)(d / block) * scale_bytes + 15) & ~(size_t)15;
+}
+
+extern "C" mole_status mole_quantize_lut(const void *table, void *codes, void *scales, int64_t rows, int N, int d,
+                                         int bits, int block, int scale_bytes, void *hip_stream)
+{
+    clear_error();
+    const mole_status ps = nf_params_status(d, bits, block, scale_bytes, "mole_quantize_lut");
+    if (ps != MOLE_OK)
+        return ps;
+    if (rows < 0 || N < 1 || N > 64)
+        return fail(MOLE_EINVAL, "mole_quantize_lut: bad size (rows=%lld, N=%d)", (long long)rows, N);
+    if (rows == 0)
+        return MOLE_OK;
+    if (!table || !codes || !scales)
+        return fail(MOLE_EINVAL, "mole_quantize_lut: table, codes and scales must not be NULL");
+    if (!aligned16(table) || !aligned16(codes) || !aligned16(scales))
+        return fail(MOLE_EINVAL, "mole_quantize_lut: buffers must be 16-byte aligned");
+    const int64_t n_rows = rows * N;
+    const unsigned blocks = (unsigned)((n_rows + 3) / 4);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (bits == 4)
+        hipLaunchKernelGGL(nf_quantize_kernel<4>, dim3(blocks), dim3(256), 0, st, static_cast<const uint16_t *>(table),
+                           static_cast<uint8_t *>(codes), scales, n_rows, d, block, scale_bytes);
+    else
+        hipLaunchKernelGGL(nf_quantize_kernel<3>, dim3(blocks), dim3(256), 0, st, static_cast<const uint16_t *>(table),
+                           static_cast<uint8_t *>(codes), scales, n_rows, d, block, scale_bytes);
+    MOLE_HIP_CHECK(hipGetLastError());
+    return MOLE_OK;
+}
+
+extern "C" mole_status mole_lookup_forward_nf(const void *codes, int64_t codes_stride, const void *scales,
+                                              int64_t scales_stride, const int32_t *ids, const int32_t *slot,
+                                              const void *h, const void *W_r, const void *shared_out,
+                                              const void *residual, void *out, int64_t act_stride, float *gates_dbg,
+                                              int64_t *rows_dbg, int32_t *err_flag, int L, int T, int64_t rows, int d,
+                                              int N, int bits, int block, int scale_bytes, unsigned flags,
+                                              const void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    clear_error();
+    const mole_status ps = nf_params_status(d, bits, block, scale_bytes, "mole_lookup_forward_nf");
+    if (ps != MOLE_OK)
+        return ps;
+    if (T < 0 || L < 1 || L > 65535 || rows < 1)
+        return fail(MOLE_EINVAL, "mole_lookup_forward_nf: bad size (T=%d, L=%d, rows=%lld)", T, L, (long long)rows);
+    if (flags & ~unsigned(MOLE_FLAG_DEDUP))
+        return fail(MOLE_EINVAL, "mole_lookup_forward_nf: unknown flags 0x%x", flags);
+    if ((size_t)d * N * 2 + 64 > 160 * 1024)
+        return fail(MOLE_EUNSUPPORTED, "mole_lookup_forward_nf: router weight of %d x %d does not fit in LDS", d, N);
+    if (T == 0)
+        return MOLE_OK;
+    if (!codes || !scales || !ids || !h || !W_r || !out)
+        return fail(MOLE_EINVAL, "mole_lookup_forward_nf: codes, scales, ids, h, W_r and out must not be NULL");
+    const void *ptrs[] = {codes, scales, h, W_r, shared_out, residual, out};
+    for (const void *p : ptrs)
+        if (p && !aligned16(p))
+            return fail(MOLE_EINVAL, "mole_lookup_forward_nf: tensor pointer %p is not 16-byte aligned", p);
+    if (L > 1) {
+        const int64_t cb = (int64_t)mole_nf_codes_bytes(rows, N, d, bits);
+        const int64_t se = rows * N * (int64_t)(d / block);
+        if (codes_stride < cb || scales_stride < se || act_stride < (int64_t)T * d || codes_stride % 16 ||
+            (scales_stride * scale_bytes) % 16 || (act_stride * 2) % 16)
+            return fail(MOLE_EINVAL, "mole_lookup_forward_nf: layer strides too small or not 16-byte multiples");
+    }
+    const int32_t *plan = nullptr;
+    if (flags & MOLE_FLAG_DEDUP) {
+        const size_t need = (size_t)plan_layout(T).words * 4;
+        if (!workspace || workspace_bytes < need)
+            return fail(MOLE_EWORKSPACE, "mole_lookup_forward_nf: MOLE_FLAG_DEDUP needs a %zu-byte plan, got %zu", need,
+                        workspace ? workspace_bytes : (size_t)0);
+        plan = static_cast<const int32_t *>(workspace);
+    }
+    NfArgs a;
+    a.codes = static_cast<const uint8_t *>(codes); a.scales = scales; a.ids = ids; a.slot = slot; a.h = h; a.W_r = W_r;
+    a.shared = shared_out; a.residual = residual; a.out = out; a.gates_dbg = gates_dbg; a.rows_dbg = rows_dbg;
+    a.err_flag = err_flag; a.plan = plan; a.codes_stride = codes_stride; a.scales_stride = scales_stride;
+    a.act_stride = act_stride; a.rows = rows; a.T = T; a.d = d; a.N = N; a.L = L; a.block = block;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    return bits == 4 ? launch_nf_n<4>(a, scale_bytes, stream) : launch_nf_n<3>(a, scale_bytes, stream);
+}

@@ -30,6 +30,15 @@ def test_printed_sizes(kind, d, N, L, V, val, tol):
         got = acc.lut_bytes(d, N, V, L, elem_bytes=2)
     elif kind == "bytes_per_token":
         got = acc.lut_bytes_loaded_per_token(d, N, L, elem_bytes=2)
+    elif kind.startswith("nf"):
+        bits, block, sb = (4, 768, 4) if kind.startswith("nf4") else (3, 128, 2)
+        full = acc.nf_table_bytes(V, N, d, bits, block, sb) * L
+        if kind.endswith("_ratio"):
+            got = full / acc.lut_bytes(d, N, V, L, elem_bytes=2)
+        elif kind.endswith("_lut_bytes"):
+            got = full
+        else:
+            got = acc.nf_table_bytes(1, N, d, bits, block, sb) * L
     elif kind == "inconsistent_loaded_per_token":
         # the printed figure is twice the paper's own formula; documented, not a pin
         got = acc.params_loaded_per_token(d, N, L)

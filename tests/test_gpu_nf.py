@@ -1,0 +1,140 @@
+"""GPU parity of the NF4 / NF3 path: mole_quantize_lut is bit-exact against the codec oracle (codes,
+packing and scales); mole_lookup_forward_nf matches the fp64 oracle forward run on the dequantised
+table."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import nf_codec as nf
+from paper_2503_15798_amd import binding as mb
+from paper_2503_15798_amd import workloads as wl
+from helpers import assert_close, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_quantize(table_bits, rows, N, d, bits, block, sb):
+    import torch
+    tab_d = to_dev(table_bits, wl.BF16)
+    codes = torch.zeros((mb.mole_nf_codes_bytes(rows, N, d, bits),), dtype=torch.uint8, device="cuda")
+    scales = torch.zeros((mb.mole_nf_scales_bytes(rows, N, d, block, sb),), dtype=torch.uint8, device="cuda")
+    mb.mole_quantize_lut(tab_d, codes, scales, rows, N, d, bits, block, sb)
+    torch.cuda.synchronize()
+    return codes, scales
+
+
+def scales_as_f32(scales_u8, sb):
+    raw = scales_u8.cpu().numpy()
+    return raw.view(np.float32) if sb == 4 else wl.bf16_bits_to_f32(raw.view(np.uint16))
+
+
+@pytest.mark.parametrize("bits,block,sb,d,N,V", [
+    (4, 768, 4, 768, 4, 300),       # the paper's NF4 setting on 160M rows: one block per row, spanning two chunks
+    (3, 128, 2, 768, 4, 300),       # the paper's NF3 setting
+    (4, 256, 2, 1024, 16, 128),     # 410M rows
+    (3, 1024, 4, 1024, 16, 64),
+    (4, 384, 4, 768, 2, 50),        # blocks that straddle the 512-column chunk boundary
+    (3, 48, 2, 96, 3, 40),          # small ragged shapes
+    (4, 8, 4, 2048, 4, 20),
+])
+def test_quantiser_is_bit_exact(bits, block, sb, d, N, V):
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, L=1, seed=bits * 7 + block)
+    table = wl.random_table(w)                                       # bf16 bits [V,N,d]
+    table[3, :, :] = 0                                               # all-zero blocks
+    table[5, 0, : min(64, d)] = wl.f32_to_bf16_bits(np.full(min(64, d), 3.0, np.float32))   # many equal maxima
+    codes_d, scales_d = gpu_quantize(table, V, N, d, bits, block, sb)
+    ref_codes, ref_scales = nf.quantize(wl.bf16_bits_to_f32(table), bits, block)
+    np.testing.assert_array_equal(scales_as_f32(scales_d, sb)[:ref_scales.size].reshape(ref_scales.shape), ref_scales)
+    got = codes_d.cpu().numpy().reshape(V, N, d * bits // 8)
+    np.testing.assert_array_equal(got, nf.pack(ref_codes, bits))                 # packed bytes, bit for bit
+    np.testing.assert_array_equal(nf.unpack(got, bits, d), ref_codes)
+
+
+def run_nf_forward(w, table, li, ids, bits, block, sb, L=1, dedup=False, residual=False):
+    import torch
+    tabs = table if L > 1 else [table]
+    packs = [gpu_quantize(t, w.V, w.N, w.d, bits, block, sb) for t in tabs]
+    codes_d = torch.stack([p[0] for p in packs])
+    scales_d = torch.stack([p[1] for p in packs])
+    lis = li if L > 1 else [li]
+    stack = lambda k: to_dev(np.stack([x[k] for x in lis]), wl.BF16)
+    h_d, wr_d, sh_d = stack("h"), stack("W_r"), stack("shared")
+    rs_d = stack("residual") if residual else None
+    ids_d = torch.from_numpy(ids).cuda()
+    out_d = torch.full_like(h_d, float("nan"))
+    T = len(ids)
+    gates_d = torch.zeros((L, T, w.N), dtype=torch.float32, device="cuda")
+    rows_d = torch.zeros((T,), dtype=torch.int64, device="cuda")
+    err = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    flags, plan = 0, None
+    if dedup:
+        plan = torch.empty((mb.mole_dedup_workspace(T, w.V) // 4,), dtype=torch.int32, device="cuda")
+        uq, iv = torch.empty_like(ids_d), torch.empty_like(ids_d)
+        mb.mole_dedup_ids(ids_d, T, w.V, uq, iv, torch.zeros_like(err), err, plan)
+        flags = mb.MOLE_FLAG_DEDUP
+    mb.mole_lookup_forward_nf(codes_d, codes_d.shape[1], scales_d, scales_d.shape[1] // sb, ids_d, None, h_d, wr_d,
+                              sh_d, rs_d, out_d, T * w.d, gates_d, rows_d, err, L, T, w.V, w.d, w.N, bits, block, sb,
+                              flags, plan)
+    torch.cuda.synchronize()
+    return to_host(out_d, wl.BF16), gates_d.cpu().numpy(), rows_d.cpu().numpy(), int(err.item())
+
+
+def oracle_nf_forward(table, li, ids, bits, block, residual=False):
+    codes, scales = nf.quantize(wl.bf16_bits_to_f32(table), bits, block)
+    deq = nf.dequantize(codes, scales, bits, block)                    # fp32 values the GPU sees after dequant
+    return oracle.lookup_forward(deq, ids, wl.storage_to_f64(li["h"], wl.BF16), wl.storage_to_f64(li["W_r"], wl.BF16),
+                                 wl.storage_to_f64(li["shared"], wl.BF16),
+                                 wl.storage_to_f64(li["residual"], wl.BF16) if residual else None)
+
+
+@pytest.mark.parametrize("bits,block,sb,d,N,T,V", [
+    (4, 768, 4, 768, 4, 100, 500),
+    (3, 128, 2, 768, 4, 100, 500),
+    (4, 256, 4, 1024, 16, 333, 1000),
+    (3, 128, 2, 1024, 16, 203, 1000),
+    (4, 512, 2, 1024, 32, 77, 300),
+    (3, 64, 4, 2048, 8, 40, 200),
+    (4, 104, 4, 520, 16, 9, 64),         # ragged last chunk
+    (3, 16, 2, 64, 64, 50, 100),
+])
+@pytest.mark.parametrize("dedup", [False, True])
+def test_forward_matches_oracle_on_dequantised_table(bits, block, sb, d, N, T, V, dedup):
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, T=T, L=1, name=f"nf{bits} d{d} N{N}")
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    li["W_r"] = wl.to_storage(wl.storage_to_f64(li["W_r"], w.dtype) * 5.0, w.dtype)
+    out, gates, rows, err = run_nf_forward(w, table, li, ids, bits, block, sb, dedup=dedup, residual=True)
+    ref, ref_g, ref_rows, ref_err = oracle_nf_forward(table, li, ids, bits, block, residual=True)
+    assert err == 0 == ref_err
+    np.testing.assert_array_equal(rows, ref_rows)
+    assert_close(gates[0].astype(np.float64), ref_g, wl.BF16, "gates")
+    assert_close(wl.storage_to_f64(out[0], wl.BF16), ref, wl.BF16, f"nf forward ({w.name})")
+
+
+def test_layers_and_bad_ids():
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=400, d=1024, N=16, T=64, L=3)
+    tabs = [wl.random_table(w, l) for l in range(w.L)]
+    lis = [wl.layer_inputs(w, l) for l in range(w.L)]
+    ids = wl.token_ids(w).copy()
+    ids[[2, 60]] = [400, -3]
+    out, gates, rows, err = run_nf_forward(w, tabs, lis, ids, 4, 256, 4, L=w.L)
+    assert err == 1
+    for l in range(w.L):
+        ref, _, ref_rows, _ = oracle_nf_forward(tabs[l], lis[l], ids, 4, 256)
+        assert_close(wl.storage_to_f64(out[l], wl.BF16), ref, wl.BF16, f"layer {l}")
+        np.testing.assert_array_equal(out[l][[2, 60]], lis[l]["shared"][[2, 60]])
+    np.testing.assert_array_equal(rows, ref_rows)
+
+
+def test_quantisation_error_is_what_the_levels_allow():
+    """Against the unquantised table the routed term moves by at most the level gap times the scales."""
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=300, d=768, N=4, T=80, L=1)
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    exact, g, _, _ = oracle.lookup_forward(table, ids, li["h"], li["W_r"], li["shared"])
+    for bits, block, sb in ((4, 768, 4), (3, 128, 2)):
+        out, _, _, _ = run_nf_forward(w, table, li, ids, bits, block, sb)
+        _, scales = nf.quantize(wl.bf16_bits_to_f32(table), bits, block)
+        gap = np.diff(nf.codebook(bits).astype(np.float64)).max() / 2
+        bound = (g[:, :, None] * np.repeat(scales[ids].astype(np.float64), block, axis=-1)).sum(axis=1) * gap
+        err = np.abs(wl.storage_to_f64(out[0], wl.BF16) - exact)
+        assert (err <= bound + 1e-3 + 2e-2 * np.abs(exact)).all()
+        assert err.mean() > 1e-4          # and it is not accidentally the unquantised table
