@@ -101,28 +101,42 @@ __device__ __forceinline__ uint4 ld16_row(const uint16_t *p)
     return ld16_stream<NT>(p);
 }
 
-// Router weight [d, N] -> LDS as (W[k,j], W[k+1,j]) bf16 pairs; the 16-byte piece holding
-// experts 4*jq..4*jq+3 of k-pair q of k-group kg sits at index (q*N/4 + jq)*kgroups + kg, so
-// that lanes (consecutive kg) read consecutive 16-byte pieces.
+// Router weight [d, N] -> LDS as (W[k,j], W[k+1,j]) bf16 pairs.  The 16-byte piece holding experts
+// 4*jq..4*jq+3 of k-pair q (k = 8*kg + 2*q, +1) of k-group kg sits at index
+// (q*N/4 + jq) * (kgroups + 1) + kg: lanes (consecutive kg) read consecutive pieces, and the one piece
+// of padding per plane spreads the planes over the banks for the fill's writes.
+// The fill reads W_r with consecutive threads on consecutive 8-byte pieces (row pairs are 2*N*2 bytes
+// of contiguous memory) and issues a batch of loads before it touches any of them.
+__host__ __device__ constexpr size_t router_lds_bytes(int d, int N) { return (size_t)N * ((d >> 3) + 1) * 16; }
+
 template <int N>
 __device__ __forceinline__ void fill_router_lds(uint4 *smem, const uint16_t *Wr, int kgroups, int nthreads)
 {
     constexpr int NQ = N / 4;
-    const int n_w4 = kgroups * N;
-    for (int i = threadIdx.x; i < n_w4; i += nthreads) {
-        const int kg = i % kgroups;
-        const int pj = i / kgroups;
-        const int jq = pj % NQ;
-        const int q = pj / NQ;
-        const int k0 = kg * 8 + q * 2;
-        const uint2 w0 = *reinterpret_cast<const uint2 *>(Wr + (int64_t)k0 * N + jq * 4);
-        const uint2 w1 = *reinterpret_cast<const uint2 *>(Wr + (int64_t)(k0 + 1) * N + jq * 4);
-        uint4 v;
-        v.x = (w0.x & 0xffffu) | (w1.x << 16);
-        v.y = (w0.x >> 16) | (w1.x & 0xffff0000u);
-        v.z = (w0.y & 0xffffu) | (w1.y << 16);
-        v.w = (w0.y >> 16) | (w1.y & 0xffff0000u);
-        smem[i] = v;
+    constexpr int B = 8;            // pieces per thread whose loads are issued before any is used
+    const int n_w4 = kgroups * N;   // = (d/2 k-pairs) * NQ pieces
+    for (int i0 = threadIdx.x; i0 < n_w4; i0 += nthreads * B) {
+        uint2 w0[B], w1[B];
+#pragma unroll
+        for (int u = 0; u < B; ++u) {
+            const int i = min(i0 + u * nthreads, n_w4 - 1);
+            const int jq = i % NQ, kp = i / NQ;
+            w0[u] = *reinterpret_cast<const uint2 *>(Wr + (int64_t)(2 * kp) * N + jq * 4);
+            w1[u] = *reinterpret_cast<const uint2 *>(Wr + (int64_t)(2 * kp + 1) * N + jq * 4);
+        }
+#pragma unroll
+        for (int u = 0; u < B; ++u) {
+            const int i = i0 + u * nthreads;
+            if (i < n_w4) {
+                const int jq = i % NQ, kp = i / NQ;
+                uint4 v;
+                v.x = (w0[u].x & 0xffffu) | (w1[u].x << 16);
+                v.y = (w0[u].x >> 16) | (w1[u].x & 0xffff0000u);
+                v.z = (w0[u].y & 0xffffu) | (w1[u].y << 16);
+                v.w = (w0[u].y >> 16) | (w1[u].y & 0xffff0000u);
+                smem[((kp & 3) * NQ + jq) * (kgroups + 1) + (kp >> 2)] = v;
+            }
+        }
     }
 }
 
@@ -136,7 +150,7 @@ __device__ __forceinline__ void router_piece(float (&z)[N], const uint4 *smem, i
     for (int q = 0; q < 4; ++q) {
 #pragma unroll
         for (int jq = 0; jq < NQ; ++jq) {
-            const uint4 w = smem[(q * NQ + jq) * kgroups + kg];
+            const uint4 w = smem[(q * NQ + jq) * (kgroups + 1) + kg];
             z[4 * jq + 0] = mac2(z[4 * jq + 0], hp[q], w.x);
             z[4 * jq + 1] = mac2(z[4 * jq + 1], hp[q], w.y);
             z[4 * jq + 2] = mac2(z[4 * jq + 2], hp[q], w.z);

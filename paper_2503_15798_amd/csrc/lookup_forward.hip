@@ -60,7 +60,11 @@ __device__ __forceinline__ void ring_load(uint4 (&r)[N], const uint16_t *base, i
         r[j] = ld16_row<NT>(base + (int64_t)j * d + col);
 }
 
-template <int N, int WPB, bool NTA>
+// SPLIT: small launches are bound by latency, not bandwidth.  There a work item is one 512-column
+// chunk of a token instead of a whole token, so that the chunks of a token are fetched and combined
+// by different waves at the same time (each computes the token's gates itself: the router is cheap
+// next to a second memory round trip).
+template <int N, int WPB, bool NTA, bool SPLIT>
 __global__ __launch_bounds__(WPB * 64) __attribute__((amdgpu_waves_per_eu(N <= 16 ? 4 : 2)))
 void fwd_bf16_stream_kernel(FwdArgs a)
 {
@@ -73,6 +77,8 @@ void fwd_bf16_stream_kernel(FwdArgs a)
     const int lane = threadIdx.x & 63;
     const int col0 = lane * 8;
     const int T = a.T;
+    const int nch = SPLIT ? (d + 511) >> 9 : 1;     // items per token
+    const int n_items = T * nch;
 
     const uint16_t *table = static_cast<const uint16_t *>(a.table) + (int64_t)layer * a.table_stride;
     const int64_t act_off = (int64_t)layer * a.act_stride;
@@ -89,20 +95,21 @@ void fwd_bf16_stream_kernel(FwdArgs a)
         order = a.plan + plan_layout(T).order;
     }
 
-    // the first token's rows go in flight before the router weight is staged.  Lanes past the end
+    // the first item's rows go in flight before the router weight is staged.  Lanes past the end
     // of a ragged chunk load a clamped (valid) column; their results are never stored.
     const int dlast = d - 8;
     int item = blockIdx.x * WPB + wave;
-    Visit cur = item < T ? visit(order, item) : Visit{0, false};
-    int64_t row = item < T ? (int64_t)__builtin_amdgcn_readfirstlane(rowsrc[cur.t]) : -1;
+    Visit cur = item < n_items ? visit(order, SPLIT ? item / nch : item) : Visit{0, false};
+    int cbase = SPLIT ? (item % nch) << 9 : 0;      // first column of this item
+    int64_t row = item < n_items ? (int64_t)__builtin_amdgcn_readfirstlane(rowsrc[cur.t]) : -1;
     bool valid = row >= 0 && row < a.rows;
     uint4 r[N];
     if (valid) {
         const uint16_t *rp0 = table + row * (int64_t)N * d;
         if (cur.single)
-            ring_load<N, true>(r, rp0, d, min(col0, dlast));
+            ring_load<N, true>(r, rp0, d, min(cbase + col0, dlast));
         else
-            ring_load<N, false>(r, rp0, d, min(col0, dlast));
+            ring_load<N, false>(r, rp0, d, min(cbase + col0, dlast));
     }
     uint4 h0, h1;
     load_h2<NTA>(h0, h1, hbase + (int64_t)cur.t * d, d, lane);
@@ -110,19 +117,21 @@ void fwd_bf16_stream_kernel(FwdArgs a)
     fill_router_lds<N>(smem, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
     __syncthreads();
 
-    for (; item < T; item += stride) {
+    for (; item < n_items; item += stride) {
         const int t = cur.t;
         const int nitem = item + stride;
-        const Visit nxt = nitem < T ? visit(order, nitem) : Visit{0, false};
-        const int64_t nrow = nitem < T ? (int64_t)__builtin_amdgcn_readfirstlane(rowsrc[nxt.t]) : -1;
+        const Visit nxt = nitem < n_items ? visit(order, SPLIT ? nitem / nch : nitem) : Visit{0, false};
+        const int ncbase = SPLIT ? (nitem % nch) << 9 : 0;
+        const int64_t nrow = nitem < n_items ? (int64_t)__builtin_amdgcn_readfirstlane(rowsrc[nxt.t]) : -1;
         const bool nvalid = nrow >= 0 && nrow < a.rows;
+        const bool reporter = !SPLIT || cbase == 0;    // one item per token reports flags and debug outputs
         if (!valid && lane == 0 && a.err_flag)
             *a.err_flag = 1;
-        if (a.rows_dbg && layer == 0 && lane == 0)
+        if (a.rows_dbg && layer == 0 && lane == 0 && reporter)
             a.rows_dbg[t] = valid ? row : -1;
 
         const float g = router_gate<N, NTA>(smem, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1);
-        if (a.gates_dbg && (lane & (LPJ - 1)) == 0)
+        if (a.gates_dbg && reporter && (lane & (LPJ - 1)) == 0)
             a.gates_dbg[((int64_t)layer * T + t) * N + lane / LPJ] = g;
         // the next token's h goes in flight now; its latency hides behind this token's combine
         load_h2<NTA>(h0, h1, hbase + (int64_t)nxt.t * d, d, lane);
@@ -134,10 +143,11 @@ void fwd_bf16_stream_kernel(FwdArgs a)
 
         const uint16_t *rp = table + (valid ? row : 0) * (int64_t)N * d;
         const uint16_t *nrp = table + (nvalid ? nrow : 0) * (int64_t)N * d;
-        for (int c0 = 0; c0 < d; c0 += 512) {
+        const int cend = SPLIT ? min(cbase + 512, d) : d;
+        for (int c0 = cbase; c0 < cend; c0 += 512) {
             const int cc = c0 + col0;
             const bool on = cc < d;
-            const bool last = c0 + 512 >= d;
+            const bool last = c0 + 512 >= cend;
             const int64_t off = (int64_t)t * d + cc;
             uint4 sv = make_uint4(0, 0, 0, 0), rv = make_uint4(0, 0, 0, 0);
             if (on && sbase)
@@ -153,9 +163,9 @@ void fwd_bf16_stream_kernel(FwdArgs a)
                 for (int j = 0; j < N; ++j)
                     fma8(acc, gs[j], r[j]);
             }
-            // refill the ring: next chunk of this token, or chunk 0 of the wave's next token
+            // refill the ring: next chunk of this item, or the first chunk of the wave's next item
             const uint16_t *fb = last ? nrp : rp;                      // wave-uniform
-            const int fcol = min(last ? col0 : cc + 512, dlast);
+            const int fcol = min(last ? ncbase + col0 : cc + 512, dlast);
             if (last ? nvalid : valid) {
                 if (last ? nxt.single : cur.single)
                     ring_load<N, true>(r, fb, d, fcol);
@@ -170,6 +180,7 @@ void fwd_bf16_stream_kernel(FwdArgs a)
         row = nrow;
         valid = nvalid;
         cur = nxt;
+        cbase = ncbase;
     }
 }
 
@@ -311,18 +322,19 @@ int64_t grid_x(int items, int L, size_t lds)
     return gx < 1 ? 1 : gx;
 }
 
-template <int N, int WPB, bool NTA>
+template <int N, int WPB, bool NTA, bool SPLIT>
 mole_status launch_fast(const FwdArgs &a, hipStream_t stream)
 {
-    const size_t lds = (size_t)a.d * N * 2;
+    const size_t lds = router_lds_bytes(a.d, N);
     static size_t attr_set = 0;
     if (lds > attr_set) {
-        MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_bf16_stream_kernel<N, WPB, NTA>),
+        MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_bf16_stream_kernel<N, WPB, NTA, SPLIT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = lds;
     }
-    dim3 grid((unsigned)grid_x<N, WPB>(a.T, a.L, lds), (unsigned)a.L);
-    hipLaunchKernelGGL((fwd_bf16_stream_kernel<N, WPB, NTA>), grid, dim3(WPB * 64), lds, stream, a);
+    const int items = SPLIT ? a.T * ((a.d + 511) / 512) : a.T;
+    dim3 grid((unsigned)grid_x<N, WPB>(items, a.L, lds), (unsigned)a.L);
+    hipLaunchKernelGGL((fwd_bf16_stream_kernel<N, WPB, NTA, SPLIT>), grid, dim3(WPB * 64), lds, stream, a);
     MOLE_HIP_CHECK(hipGetLastError());
     return MOLE_OK;
 }
@@ -336,9 +348,13 @@ mole_status launch_fast_n(const FwdArgs &a, hipStream_t stream)
     wpb = env_int("MOLE_FWD_WPB", wpb);
     // large batches: keep the read-once activations out of the caches
     const bool nta = env_int("MOLE_FWD_NTA", (int64_t)a.T * a.L >= 8192 ? 1 : 2) == 1;
+    // small launches: one chunk per item (latency regime); never together with the large-batch loads
+    const bool split = env_int("MOLE_FWD_SPLIT", (int64_t)a.T * a.L <= 2048 ? 1 : 2) == 1 && a.d > 512;
+    if (split)
+        return wpb >= 8 ? launch_fast<N, 8, false, true>(a, stream) : launch_fast<N, 4, false, true>(a, stream);
     if (wpb >= 8)
-        return nta ? launch_fast<N, 8, true>(a, stream) : launch_fast<N, 8, false>(a, stream);
-    return nta ? launch_fast<N, 4, true>(a, stream) : launch_fast<N, 4, false>(a, stream);
+        return nta ? launch_fast<N, 8, true, false>(a, stream) : launch_fast<N, 8, false, false>(a, stream);
+    return nta ? launch_fast<N, 4, true, false>(a, stream) : launch_fast<N, 4, false, false>(a, stream);
 }
 
 mole_status forward_impl(const void *table, int64_t table_stride, const int32_t *ids, const int32_t *slot,
@@ -393,7 +409,7 @@ mole_status forward_impl(const void *table, int64_t table_stride, const int32_t 
     a.T = T; a.d = d; a.N = N; a.L = L;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
-    const size_t lds_fast = (size_t)d * N * 2;
+    const size_t lds_fast = router_lds_bytes(d, N);
     const bool fast = dtype == MOLE_BF16 && lds_fast <= LDS_BYTES_PER_CU && !getenv("MOLE_FWD_GENERIC");
     if (fast) {
         switch (N) {

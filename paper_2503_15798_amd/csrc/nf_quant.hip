@@ -191,7 +191,6 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
     const int d = a.d;
     const int kgroups = d >> 3;
     const int layer = blockIdx.y;
-    const int n_w4 = kgroups * N;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int col0 = lane * 8;
@@ -216,7 +215,7 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
     }
 
     // level table behind the router weight
-    float *cb = reinterpret_cast<float *>(smem + n_w4);
+    float *cb = reinterpret_cast<float *>(smem + N * (kgroups + 1));
     if (threadIdx.x < NLEV)
         cb[threadIdx.x] = BITS == 4 ? NF4_LEVELS[threadIdx.x] : NF3_LEVELS[threadIdx.x];
     fill_router_lds<N>(smem, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
@@ -321,7 +320,7 @@ template <int N, int BITS>
 mole_status launch_nf(const NfArgs &a, int scale_bytes, hipStream_t stream)
 {
     constexpr int WPB = 4;
-    const size_t lds = (size_t)a.d * N * 2 + 64;
+    const size_t lds = router_lds_bytes(a.d, N) + 64;
     static size_t attr_set = 0;
     if (lds > attr_set) {
         MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_nf_kernel<N, BITS, WPB>),
@@ -431,7 +430,7 @@ extern "C" mole_status mole_lookup_forward_nf(const void *codes, int64_t codes_s
         return fail(MOLE_EINVAL, "mole_lookup_forward_nf: bad size (T=%d, L=%d, rows=%lld)", T, L, (long long)rows);
     if (flags & ~unsigned(MOLE_FLAG_DEDUP))
         return fail(MOLE_EINVAL, "mole_lookup_forward_nf: unknown flags 0x%x", flags);
-    if ((size_t)d * N * 2 + 64 > 160 * 1024)
+    if (router_lds_bytes(d, N) + 64 > 160 * 1024)
         return fail(MOLE_EUNSUPPORTED, "mole_lookup_forward_nf: router weight of %d x %d does not fit in LDS", d, N);
     if (T == 0)
         return MOLE_OK;

@@ -93,6 +93,26 @@ def test_bf16_shapes(d, N, T, V, residual):
     check_against_oracle(w, table, ids, li, residual=residual)
 
 
+@pytest.mark.parametrize("split", ["1", "2"])
+@pytest.mark.parametrize("wpb", ["4", "8"])
+@pytest.mark.parametrize("d,N,T,V", [(1024, 16, 333, 4096), (768, 16, 64, 4096), (1544, 8, 50, 300), (1024, 32, 203, 2048)])
+def test_launch_variants(monkeypatch, split, wpb, d, N, T, V):
+    """Both item granularities (whole token / one 512-column chunk) and both workgroup widths."""
+    monkeypatch.setenv("MOLE_FWD_SPLIT", split)
+    monkeypatch.setenv("MOLE_FWD_WPB", wpb)
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, T=T, L=1, name=f"split{split} wpb{wpb} d{d} N{N}")
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    ids = ids.copy()
+    ids[T // 2] = V + 5                                    # an out-of-range id in the middle of the stream
+    for dedup in (False, True):
+        ref_out, ref_g, ref_rows, ref_err = oracle.lookup_forward(table, ids, li["h"], li["W_r"], li["shared"], li["residual"])
+        got = run_forward(w, table, ids, li, residual=True, dedup=dedup)
+        assert got["err"] == 1 == ref_err
+        np.testing.assert_array_equal(got["rows"], ref_rows)
+        assert_close(got["gates"].astype(np.float64), ref_g, wl.BF16, "gates")
+        assert_close(wl.storage_to_f64(got["out"], w.dtype), ref_out, w.dtype, f"out ({w.name})")
+
+
 @pytest.mark.parametrize("d,N,T", [(64, 4, 256), (128, 16, 100), (32, 3, 17)])
 def test_fp32_shapes(d, N, T):
     w = wl.scaled(wl.CONFIGS["tiny"], V=777, d=d, N=N, T=T, name=f"fp32 d{d} N{N}")
