@@ -22,6 +22,7 @@ import os
 import statistics
 import sys
 import time
+import traceback
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
@@ -135,6 +136,15 @@ class Layers:
     def distinct(self):
         import numpy as np
         return float(np.mean([len(np.unique(b)) for b in self.ids_host]))
+
+
+def release_pinned(torch):
+    """Hand cached pinned host blocks back (torch rounds a pinned request up to a power of two and keeps
+    it; the box allows about 64 GiB of pinned memory in all)."""
+    import gc
+    gc.collect()
+    if hasattr(torch._C, "_host_emptyCache"):
+        torch._C._host_emptyCache()
 
 
 def time_steps(torch, stream, step, steps, warmup):
@@ -372,11 +382,21 @@ def extras(args, torch, mb, wl, acc, stream, L):
     for tag, bits, block, sbytes in (("nf4", 4, 1024, 4), ("nf3", 3, 128, 2)):
         out[f"decode410m_{tag}"] = nf_entry(L, acc, torch, stream, steps, warm, bits, block, sbytes)
 
+    # ---- storage tier: a few layers of the same tables in an id-major LUT file ----
+    try:
+        out["storage410m"] = storage_bench(torch, mb, wl, stream, L, steps, warm)
+    except Exception as e:
+        traceback.print_exc(file=sys.stderr)
+        out["storage410m"] = {"skipped": repr(e)}
+    release_pinned(torch)
+
     # ---- offloaded mode on the same tables: all LUTs in pinned host memory, T = 32 ----
     try:
         out.update(offload_bench(torch, mb, wl, acc, stream, L, steps, warm))
     except Exception as e:   # host memory may not allow 40 GB of pinned pages
+        traceback.print_exc(file=sys.stderr)
         out["offload410m"] = {"skipped": repr(e)}
+    release_pinned(torch)
 
     # smaller decode batches on the same tables (latency-bound: microseconds are the result)
     for T in (32, 1):
@@ -441,6 +461,7 @@ def nf_entry(LL, acc, torch, stream, steps, warm, bits, block, sbytes):
 def offload_bench(torch, mb, wl, acc, stream, L, steps, warm):
     import numpy as np
     w = wl.CONFIGS["offload410m"]
+    res = {}
     host = torch.empty(L.tabs.shape, dtype=L.tabs.dtype, pin_memory=True)
     host.copy_(L.tabs)
     torch.cuda.synchronize()
@@ -475,7 +496,6 @@ def offload_bench(torch, mb, wl, acc, stream, L, steps, warm):
         dedup(i)
         fetch(i)
         fwd_staged(i)
-    res = {}
     U = float(np.mean([len(np.unique(b)) for b in ids_host]))
     fetched = U * w.L * row_elems * 2
     ms_full = time_steps(torch, stream, full, steps, warm)
@@ -495,7 +515,150 @@ def offload_bench(torch, mb, wl, acc, stream, L, steps, warm):
         "forward_reading_host_table_directly_ms": ms_direct,
     }
     del host
+
+    # ---- the same tables id-major on the host ([V, L, N, d]: one contiguous 768 KiB block per id) ----
+    host_id = torch.empty((w.V, w.L, w.N, w.d), dtype=L.tabs.dtype, pin_memory=True)
+    for l in range(w.L):
+        host_id[:, l].copy_(L.tabs[l])
+    torch.cuda.synchronize()
+
+    def fetch_id(i, s=stream, bufs=None):
+        u, n, st = bufs or (uniq, nu, staging)
+        mb.mole_offload_fetch_idmajor(host_id, u, n, st, U_cap * row_elems, err, w.L, U_cap, w.V, w.d, w.N, code,
+                                      stream=s)
+
+    def full_id(i):
+        dedup(i)
+        fetch_id(i)
+        fwd_staged(i)
+    ms_full_id = time_steps(torch, stream, full_id, steps, warm)
+    dedup(0)
+    ms_fetch_id = time_steps(torch, stream, lambda i: fetch_id(i), steps, warm)
+
+    # double-buffered: the rows of step i+1 are fetched on a second stream while step i's forward runs
+    # (ids are known when a step starts; both streams at the default priority)
+    s2 = torch.cuda.Stream()
+    sets = []
+    for _ in range(2):
+        sets.append(dict(uniq=torch.empty_like(uniq), inv=torch.empty_like(inv), nu=torch.zeros_like(nu),
+                         plan=torch.empty_like(plan), staging=torch.empty_like(staging),
+                         fetched=torch.cuda.Event(), consumed=torch.cuda.Event()))
+
+    def prefetch(i):
+        b = sets[i % 2]
+        s2.wait_event(b["consumed"])
+        mb.mole_dedup_ids(ids[i % N_ID_BATCHES], T, w.V, b["uniq"], b["inv"], b["nu"], err, b["plan"], stream=s2)
+        fetch_id(i, s2, (b["uniq"], b["nu"], b["staging"]))
+        b["fetched"].record(s2)
+
+    def consume(i):
+        b = sets[i % 2]
+        stream.wait_event(b["fetched"])
+        mb.mole_lookup_forward_layers(b["staging"], U_cap * row_elems, ids[i % N_ID_BATCHES], b["inv"], h, L.W_r, sh,
+                                      None, o, T * w.d, None, None, err, w.L, T, U_cap, w.d, w.N, code, 0, None,
+                                      stream=stream)
+        b["consumed"].record(stream)
+
+    for b in sets:
+        b["consumed"].record(stream)
+    torch.cuda.synchronize()
+    n_pipe = steps + warm
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    prefetch(0)
+    for i in range(n_pipe):
+        if i == warm:
+            ev0.record(stream)
+        if i + 1 < n_pipe:
+            prefetch(i + 1)
+        consume(i)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    ms_pipe = ev0.elapsed_time(ev1) / steps
+    res["offload410m_id_major"] = {
+        "step": "as offload410m with the host table laid out [V, L, N, d]",
+        "ms": ms_full_id, "tokens_per_s": T / (ms_full_id * 1e-3), "fetch_only_ms": ms_fetch_id,
+        "fetch_GBps": u0 * w.L * row_elems * 2 / (ms_fetch_id * 1e-3) / 1e9,
+        "fetch_frac_of_host_link_peak": u0 * w.L * row_elems * 2 / (ms_fetch_id * 1e-3) / 1e9 / HOST_LINK_GBS,
+        "double_buffered_ms": ms_pipe, "double_buffered_tokens_per_s": T / (ms_pipe * 1e-3),
+        "double_buffered_fetch_GBps": fetched / (ms_pipe * 1e-3) / 1e9,
+    }
+    del host_id, sets
     return res
+
+
+def storage_bench(torch, mb, wl, stream, L, steps, warm, layers=4, threads=16):
+    """The table in a file (id-major), `layers` of the 24 layers to keep the file small: per step the
+    distinct ids go to the host, their rows are read from the file into pinned memory and pulled to the
+    device.  The file was just written, so reads are served by the page cache: this times the path, not a disk."""
+    import numpy as np
+    import tempfile
+    w = wl.CONFIGS["offload410m"]
+    T, U_cap, row_elems = w.T, w.T, w.N * w.d
+    path = os.path.join(tempfile.gettempdir(), f"mole_bench_{os.getpid()}.molelut")
+    f = mb.mole_lut_file_create(path, mb.MOLE_BF16, mb.MOLE_LAYOUT_ID_MAJOR, layers, w.V, w.N, w.d)
+    try:
+        t0 = time.perf_counter()
+        lay = torch.empty((w.V, w.N, w.d), dtype=L.tabs.dtype, pin_memory=True)
+        for l in range(layers):
+            lay.copy_(L.tabs[l])
+            torch.cuda.synchronize()
+            mb.mole_lut_file_write_layer(f, l, lay, threads)
+        handle, f = f, None
+        mb.mole_lut_file_close(handle)
+        t_write = time.perf_counter() - t0
+        f, desc = mb.mole_lut_file_open(path)
+        ids_host = np.stack([wl.token_ids(w, b) for b in range(N_ID_BATCHES)])
+        ids = torch.from_numpy(ids_host).cuda()
+        uniq = torch.empty((T,), dtype=torch.int32, device="cuda")
+        inv = torch.empty((T,), dtype=torch.int32, device="cuda")
+        nu = torch.zeros((1,), dtype=torch.int32, device="cuda")
+        err = torch.zeros((1,), dtype=torch.int32, device="cuda")
+        plan = torch.empty((mb.mole_dedup_workspace(T, w.V) // 4,), dtype=torch.int32, device="cuda")
+        uniq_h = torch.empty((T + 1,), dtype=torch.int32, pin_memory=True)
+        pinned = torch.empty((U_cap, layers, w.N, w.d), dtype=L.tabs.dtype, pin_memory=True)
+        staging = torch.empty((layers, U_cap, w.N, w.d), dtype=L.tabs.dtype, device="cuda")
+        h, sh, o = (x[:layers, :T].contiguous() for x in (L.h, L.shared, L.out))
+        both = torch.empty((T + 1,), dtype=torch.int32, device="cuda")
+        t_read = [0.0]
+
+        def step(i):
+            with torch.cuda.stream(stream):
+                mb.mole_dedup_ids(ids[i % N_ID_BATCHES], T, w.V, uniq, inv, nu, err, plan, stream=stream)
+                both[:T].copy_(uniq)
+                both[T:].copy_(nu)
+                uniq_h.copy_(both, non_blocking=True)
+                stream.synchronize()
+                U = int(uniq_h[T])
+                t1 = time.perf_counter()
+                mb.mole_lut_file_read_rows(f, uniq_h, U, pinned, threads)
+                t_read[0] += time.perf_counter() - t1
+                mb.mole_offload_fetch_idmajor(pinned, None, nu, staging, U_cap * row_elems, err, layers, U_cap,
+                                              U_cap, w.d, w.N, mb.MOLE_BF16, stream=stream)
+                mb.mole_lookup_forward_layers(staging, U_cap * row_elems, ids[i % N_ID_BATCHES], inv, h, L.W_r, sh,
+                                              None, o, T * w.d, None, None, err, layers, T, U_cap, w.d, w.N,
+                                              mb.MOLE_BF16, 0, None, stream=stream)
+        n = min(steps, 50)
+        for i in range(3):
+            step(i)
+        torch.cuda.synchronize()
+        t_read[0] = 0.0
+        t0 = time.perf_counter()
+        for i in range(n):
+            step(3 + i)
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) / n
+        U = float(np.mean([len(np.unique(b)) for b in ids_host]))
+        return {"step": "dedup, distinct ids to the host, rows read from an id-major LUT file into pinned memory "
+                        "(page cache, not a disk), pulled to the device, staged forward",
+                "layers_in_file": layers, "file_bytes": 4096 + layers * w.V * row_elems * 2, "reader_threads": threads,
+                "write_file_s": t_write, "steps": n, "wall_ms_per_step": wall * 1e3,
+                "read_rows_ms_per_step": t_read[0] / n * 1e3,
+                "read_rows_GBps": U * layers * row_elems * 2 / (t_read[0] / n) / 1e9,
+                "tokens_per_s": T / wall}
+    finally:
+        mb.mole_lut_file_close(f)
+        if os.path.exists(path):
+            os.remove(path)
 
 
 def build_bench(torch, mb, wl, acc, stream):

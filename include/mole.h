@@ -12,8 +12,9 @@
  *   - "dev" pointers are device memory (or host memory the GPU can address: pinned + mapped);
  *     "host" pointers are ordinary host memory.  The caller owns every buffer and the stream.
  *   - All calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = default
- *     stream) and return without synchronising.  The library allocates nothing, keeps no
- *     global state besides a thread-local error string, and never frees caller memory.
+ *     stream) and return without synchronising.  The library allocates no device memory, keeps
+ *     no global state besides a thread-local error string (and the handles of mole_lut_file_*),
+ *     and never frees caller memory.
  *   - Tensors are dense, row-major, in the element type named by `mole_dtype`
  *     (MOLE_BF16: bfloat16 storage, fp32 arithmetic, one round-to-nearest-even at the store;
  *      MOLE_F32: fp32 throughout).  Token ids, slots and maps are int32.
@@ -41,11 +42,16 @@ typedef enum {
     MOLE_EINVAL = 1,        /* bad argument (null, negative, misaligned, inconsistent)      */
     MOLE_EUNSUPPORTED = 2,  /* shape or dtype outside what the kernels are built for       */
     MOLE_EWORKSPACE = 3,    /* workspace missing or smaller than mole_*_workspace() says  */
-    MOLE_EHIP = 4           /* a HIP runtime call failed (message holds hipGetErrorString) */
+    MOLE_EHIP = 4,          /* a HIP runtime call failed (message holds hipGetErrorString) */
+    MOLE_EIO = 5            /* a file could not be created, opened, mapped or read (LUT files)  */
 } mole_status;
 
 typedef enum { MOLE_F32 = 0, MOLE_BF16 = 1 } mole_dtype;
 typedef enum { MOLE_GELU_ERF = 0, MOLE_GELU_TANH = 1 } mole_act;
+typedef enum {
+    MOLE_LAYOUT_LAYER_MAJOR = 0,   /* [L, V, N, d]: one table per layer                           */
+    MOLE_LAYOUT_ID_MAJOR = 1       /* [V, L, N, d]: the rows of all layers of an id are adjacent  */
+} mole_layout;
 
 enum {
     MOLE_FLAG_DEDUP = 1u    /* forward: `workspace` holds a plan written by mole_dedup_ids for
@@ -151,6 +157,57 @@ mole_status mole_offload_fetch(const void *host_table, int64_t host_layer_stride
                                int32_t *err_flag,
                                int L, int U_cap, int64_t V, int d, int N, mole_dtype dtype,
                                void *hip_stream);
+
+/* The same fetch from a host table laid out [V, L, N, d] (MOLE_LAYOUT_ID_MAJOR).  Token ids are
+ * known when a decoding step starts (the lookup is the first line of the inference listing), so
+ * the rows of all L layers are requested together; in this layout they are one contiguous block
+ * of L*N*d elements per id.  staging stays [L, U_cap, N, d] (what the forward reads).
+ * uniq == NULL means uniq[u] = u: the host buffer holds exactly the wanted rows, in order (for
+ * instance rows that mole_lut_file_read_rows has just put into pinned memory; then V = row count
+ * of that buffer). */
+mole_status mole_offload_fetch_idmajor(const void *host_table,
+                                       const int32_t *uniq, const int32_t *n_uniq,
+                                       void *staging, int64_t staging_layer_stride,
+                                       int32_t *err_flag,
+                                       int L, int U_cap, int64_t V, int d, int N, mole_dtype dtype,
+                                       void *hip_stream);
+
+/* ------------------------------------------------------------------------------------------
+ * LUT files: the tables as an artifact on a storage device (Sec. 3.3: the LUT is offloaded after
+ * re-parameterization; Sec. 4.1 offloading setting; Sec. 4.2: the tables sit on large storage
+ * devices).  The paper defines no format.  This one: a 4096-byte little-endian header
+ * ("MOLELUT\0", u32 version = 1, u32 header bytes, u32 dtype, u32 layout, i64 V, i32 L, i32 N,
+ * i32 d, u32 0, u64 payload bytes) followed by the raw table in the layout the header names.
+ * Host-only calls: no GPU work, no stream.  These are the only calls that keep state: a
+ * mole_lut_file owns a file descriptor and a mapping until mole_lut_file_close.
+ *   mole_lut_file_create: creates (truncates) `path`, sizes it, maps it read-write.
+ *   mole_lut_file_open:   opens read-only, validates the header against the file size, fills
+ *                         *desc (nullable).
+ *   mole_lut_file_payload: the mapped table (host memory, NOT GPU-addressable), NULL for NULL.
+ *   mole_lut_file_write_layer: copies one layer's table src_host [V, N, d] into its place in
+ *                         either layout, with `threads` host threads.
+ *   mole_lut_file_read_rows: dst_host[i, l, :, :] = table(l, ids_host[i]) for i < n, all l:
+ *                         dst is [n, L, N, d] whatever the file's layout (one pread per id for an
+ *                         id-major file, L for a layer-major one), `threads` reader threads
+ *                         (clamped to 1..64).  An id outside [0, V) fails with MOLE_EINVAL before
+ *                         anything is read.  dst_host may be pinned memory.
+ *   mole_lut_file_close:  syncs a written file, unmaps, closes, frees the handle; NULL is a no-op.
+ * ---------------------------------------------------------------------------------------- */
+typedef struct mole_lut_file mole_lut_file;
+typedef struct {
+    int32_t dtype;      /* mole_dtype  */
+    int32_t layout;     /* mole_layout */
+    int32_t L, N, d;
+    int32_t reserved;   /* 0 */
+    int64_t V;
+} mole_lut_desc;
+mole_status mole_lut_file_create(const char *path, const mole_lut_desc *desc, mole_lut_file **file);
+mole_status mole_lut_file_open(const char *path, mole_lut_file **file, mole_lut_desc *desc);
+void *mole_lut_file_payload(mole_lut_file *file);
+mole_status mole_lut_file_write_layer(mole_lut_file *file, int layer, const void *src_host, int threads);
+mole_status mole_lut_file_read_rows(mole_lut_file *file, const int32_t *ids_host, int n,
+                                    void *dst_host, int threads);
+mole_status mole_lut_file_close(mole_lut_file *file);
 
 /* ------------------------------------------------------------------------------------------
  * NormalFloat-quantised tables (Sec. 5.5, Table 8: NF4 / NF3 post-training quantisation of the

@@ -15,18 +15,29 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 # MOLE_LIB overrides the library file (used to compare differently compiled builds)
 LIB_PATH = os.environ.get("MOLE_LIB") or os.path.join(_HERE, "libmole.so")
 
-MOLE_OK, MOLE_EINVAL, MOLE_EUNSUPPORTED, MOLE_EWORKSPACE, MOLE_EHIP = range(5)
+MOLE_OK, MOLE_EINVAL, MOLE_EUNSUPPORTED, MOLE_EWORKSPACE, MOLE_EHIP, MOLE_EIO = range(6)
 MOLE_F32, MOLE_BF16 = 0, 1
 MOLE_GELU_ERF, MOLE_GELU_TANH = 0, 1
 MOLE_FLAG_DEDUP = 1
+MOLE_LAYOUT_LAYER_MAJOR, MOLE_LAYOUT_ID_MAJOR = 0, 1
 
-_STATUS_NAMES = {0: "MOLE_OK", 1: "MOLE_EINVAL", 2: "MOLE_EUNSUPPORTED", 3: "MOLE_EWORKSPACE", 4: "MOLE_EHIP"}
+_STATUS_NAMES = {0: "MOLE_OK", 1: "MOLE_EINVAL", 2: "MOLE_EUNSUPPORTED", 3: "MOLE_EWORKSPACE", 4: "MOLE_EHIP",
+                 5: "MOLE_EIO"}
 
 # every symbol include/mole.h declares
 EXPORTS = ("mole_last_error", "mole_version", "mole_build_lut_workspace", "mole_build_lut",
            "mole_dedup_workspace", "mole_dedup_ids", "mole_lookup_forward",
-           "mole_lookup_forward_layers", "mole_offload_fetch", "mole_nf_codebook", "mole_nf_codes_bytes",
+           "mole_lookup_forward_layers", "mole_offload_fetch", "mole_offload_fetch_idmajor",
+           "mole_lut_file_create", "mole_lut_file_open", "mole_lut_file_payload", "mole_lut_file_write_layer",
+           "mole_lut_file_read_rows", "mole_lut_file_close", "mole_nf_codebook", "mole_nf_codes_bytes",
            "mole_nf_scales_bytes", "mole_quantize_lut", "mole_lookup_forward_nf")
+
+
+class LutDesc(ctypes.Structure):
+    """mole_lut_desc of include/mole.h."""
+    _fields_ = [("dtype", ctypes.c_int32), ("layout", ctypes.c_int32), ("L", ctypes.c_int32),
+                ("N", ctypes.c_int32), ("d", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("V", ctypes.c_int64)]
 
 
 class MoleError(RuntimeError):
@@ -71,6 +82,21 @@ def lib() -> ctypes.CDLL:
     L.mole_offload_fetch.restype = c_i32
     L.mole_offload_fetch.argtypes = [c_void, c_i64, c_void, c_void, c_void, c_i64, c_void,
                                      c_i32, c_i32, c_i64, c_i32, c_i32, c_i32, c_void]
+    L.mole_offload_fetch_idmajor.restype = c_i32
+    L.mole_offload_fetch_idmajor.argtypes = [c_void, c_void, c_void, c_void, c_i64, c_void,
+                                             c_i32, c_i32, c_i64, c_i32, c_i32, c_i32, c_void]
+    L.mole_lut_file_create.restype = c_i32
+    L.mole_lut_file_create.argtypes = [ctypes.c_char_p, ctypes.POINTER(LutDesc), ctypes.POINTER(c_void)]
+    L.mole_lut_file_open.restype = c_i32
+    L.mole_lut_file_open.argtypes = [ctypes.c_char_p, ctypes.POINTER(c_void), ctypes.POINTER(LutDesc)]
+    L.mole_lut_file_payload.restype = c_void
+    L.mole_lut_file_payload.argtypes = [c_void]
+    L.mole_lut_file_write_layer.restype = c_i32
+    L.mole_lut_file_write_layer.argtypes = [c_void, c_i32, c_void, c_i32]
+    L.mole_lut_file_read_rows.restype = c_i32
+    L.mole_lut_file_read_rows.argtypes = [c_void, c_void, c_i32, c_void, c_i32]
+    L.mole_lut_file_close.restype = c_i32
+    L.mole_lut_file_close.argtypes = [c_void]
     L.mole_nf_codebook.restype = c_i32
     L.mole_nf_codebook.argtypes = [c_i32, c_void]
     L.mole_nf_codes_bytes.restype = c_sz
@@ -171,6 +197,46 @@ def mole_offload_fetch(host_table, host_layer_stride: int, uniq, n_uniq, staging
     _check(lib().mole_offload_fetch(_ptr(host_table), host_layer_stride, _ptr(uniq), _ptr(n_uniq), _ptr(staging),
                                     staging_layer_stride, _ptr(err_flag), L, U_cap, V, d, N, dtype,
                                     _stream(stream)))
+
+
+def mole_offload_fetch_idmajor(host_table, uniq, n_uniq, staging, staging_layer_stride: int, err_flag, L: int,
+                               U_cap: int, V: int, d: int, N: int, dtype: int, stream=None) -> None:
+    _check(lib().mole_offload_fetch_idmajor(_ptr(host_table), _ptr(uniq), _ptr(n_uniq), _ptr(staging),
+                                            staging_layer_stride, _ptr(err_flag), L, U_cap, V, d, N, dtype,
+                                            _stream(stream)))
+
+
+def mole_lut_file_create(path: str, dtype: int, layout: int, L: int, V: int, N: int, d: int) -> int:
+    """-> handle (an integer holding the mole_lut_file pointer)."""
+    desc = LutDesc(dtype, layout, L, N, d, 0, V)
+    handle = ctypes.c_void_p()
+    _check(lib().mole_lut_file_create(os.fsencode(path), ctypes.byref(desc), ctypes.byref(handle)))
+    return handle.value
+
+
+def mole_lut_file_open(path: str):
+    """-> (handle, LutDesc)."""
+    desc = LutDesc()
+    handle = ctypes.c_void_p()
+    _check(lib().mole_lut_file_open(os.fsencode(path), ctypes.byref(handle), ctypes.byref(desc)))
+    return handle.value, desc
+
+
+def mole_lut_file_payload(handle: int) -> Optional[int]:
+    """Address of the mapped table (host memory)."""
+    return lib().mole_lut_file_payload(handle)
+
+
+def mole_lut_file_write_layer(handle: int, layer: int, src_host, threads: int = 8) -> None:
+    _check(lib().mole_lut_file_write_layer(handle, layer, _ptr(src_host), threads))
+
+
+def mole_lut_file_read_rows(handle: int, ids_host, n: int, dst_host, threads: int = 8) -> None:
+    _check(lib().mole_lut_file_read_rows(handle, _ptr(ids_host), n, _ptr(dst_host), threads))
+
+
+def mole_lut_file_close(handle: Optional[int]) -> None:
+    _check(lib().mole_lut_file_close(handle))
 
 
 def mole_nf_codebook(bits: int):

@@ -10,13 +10,22 @@
 // fetched (uniq / n_uniq from mole_dedup_ids), all L layers in one launch.  Each row block
 // (N*d elements) is cut into pieces of 64 lanes x 16 bytes; pieces are spread over the whole
 // grid so that many reads are in flight on the host link at once.
+//
+// mole_offload_fetch_idmajor reads a host table laid out [V, L, N, d]: token ids are known when a
+// decoding step starts (the lookup is the first line of the inference listing), so the rows of every
+// layer can be requested at once, and with this layout they are one contiguous block per id.
 #include "mole_internal.h"
 
 namespace {
 using namespace mole;
 
+// ID_MAJOR: the host table is [V, L, N, d] (all layers of an id adjacent) and the work is ordered
+// so that consecutive wavefronts read consecutive KiB of one id's L*N*d block; otherwise the host
+// table is [L, V, N, d].  uniq == nullptr means uniq[u] = u (the host buffer already holds exactly
+// the wanted rows, e.g. rows read from a file).
+template <bool ID_MAJOR>
 __global__ __launch_bounds__(256) void fetch_kernel(const uint4 *__restrict__ host, int64_t host_ls16,
-                                                     const int32_t *__restrict__ uniq,
+                                                     int64_t host_rs16, const int32_t *__restrict__ uniq,
                                                      const int32_t *__restrict__ n_uniq_p,
                                                      uint4 *__restrict__ staging, int64_t stage_ls16,
                                                      int32_t *err_flag, int L, int U_cap, int64_t V,
@@ -28,6 +37,8 @@ __global__ __launch_bounds__(256) void fetch_kernel(const uint4 *__restrict__ ho
             *err_flag = 1;
         U = U_cap;
     }
+    if (U < 0)
+        U = 0;
     // work = (layer, u, 1 KiB piece); a wavefront takes one piece at a time
     const int pieces = (row16 + 63) >> 6;
     const int64_t total = (int64_t)L * U * pieces;
@@ -37,15 +48,69 @@ __global__ __launch_bounds__(256) void fetch_kernel(const uint4 *__restrict__ ho
     for (int64_t w = wave0; w < total; w += nwaves) {
         const int p = (int)(w % pieces);
         const int64_t lu = w / pieces;
-        const int u = (int)(lu % U);
-        const int l = (int)(lu / U);
-        const int64_t id = uniq[u];
+        int u, l;
+        if (ID_MAJOR) {
+            l = (int)(lu % L);
+            u = (int)(lu / L);
+        } else {
+            u = (int)(lu % U);
+            l = (int)(lu / U);
+        }
+        const int64_t id = uniq ? (int64_t)uniq[u] : (int64_t)u;
         const int i16 = p * 64 + lane;
         if (i16 < row16 && id >= 0 && id < V) {
-            const uint4 v = host[l * host_ls16 + id * (int64_t)row16 + i16];
+            const uint4 v = host[l * host_ls16 + id * host_rs16 + i16];
             staging[l * stage_ls16 + (int64_t)u * row16 + i16] = v;
         }
     }
+}
+
+mole_status fetch_impl(const char *who, bool id_major, const void *host_table, int64_t host_layer_stride,
+                       const int32_t *uniq, const int32_t *n_uniq, void *staging, int64_t staging_layer_stride,
+                       int32_t *err_flag, int L, int U_cap, int64_t V, int d, int N, mole_dtype dtype,
+                       void *hip_stream)
+{
+    clear_error();
+    if (dtype != MOLE_F32 && dtype != MOLE_BF16)
+        return fail(MOLE_EINVAL, "%s: unknown dtype %d", who, (int)dtype);
+    if (L < 1 || U_cap < 0 || V < 1 || d < 1 || N < 1)
+        return fail(MOLE_EINVAL, "%s: bad size (L=%d, U_cap=%d, V=%lld, d=%d, N=%d)", who, L, U_cap, (long long)V,
+                    d, N);
+    const int64_t eb = (int64_t)elem_bytes(dtype);
+    const int64_t row_bytes = (int64_t)N * d * eb;
+    if (row_bytes % 16)
+        return fail(MOLE_EUNSUPPORTED, "%s: a row block of %lld bytes is not a multiple of 16", who,
+                    (long long)row_bytes);
+    if (U_cap == 0)
+        return MOLE_OK;
+    if (!host_table || !n_uniq || !staging || (!uniq && !id_major))
+        return fail(MOLE_EINVAL, "%s: host_table, uniq, n_uniq and staging must not be NULL", who);
+    if (!aligned16(host_table) || !aligned16(staging))
+        return fail(MOLE_EINVAL, "%s: host_table and staging must be 16-byte aligned", who);
+    if (L > 1 && (staging_layer_stride < (int64_t)U_cap * N * d || (staging_layer_stride * eb) % 16))
+        return fail(MOLE_EINVAL, "%s: staging layer stride too small or not a 16-byte multiple", who);
+    if (!id_major && L > 1 && (host_layer_stride < V * N * (int64_t)d || (host_layer_stride * eb) % 16))
+        return fail(MOLE_EINVAL, "%s: host layer stride too small or not a 16-byte multiple", who);
+    const int row16 = (int)(row_bytes / 16);
+    const int pieces = (row16 + 63) / 64;
+    int64_t waves = (int64_t)L * U_cap * pieces;
+    int64_t blocks = (waves + 3) / 4;
+    const int64_t cap = (int64_t)num_cus() * 8;
+    if (blocks > cap)
+        blocks = cap;
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (id_major)
+        hipLaunchKernelGGL(fetch_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                           static_cast<const uint4 *>(host_table), (int64_t)row16, (int64_t)L * row16, uniq,
+                           n_uniq, static_cast<uint4 *>(staging), staging_layer_stride * eb / 16, err_flag, L,
+                           U_cap, V, row16);
+    else
+        hipLaunchKernelGGL(fetch_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                           static_cast<const uint4 *>(host_table), host_layer_stride * eb / 16, (int64_t)row16,
+                           uniq, n_uniq, static_cast<uint4 *>(staging), staging_layer_stride * eb / 16, err_flag,
+                           L, U_cap, V, row16);
+    MOLE_HIP_CHECK(hipGetLastError());
+    return MOLE_OK;
 }
 
 }  // namespace
@@ -55,37 +120,16 @@ extern "C" mole_status mole_offload_fetch(const void *host_table, int64_t host_l
                                           int32_t *err_flag, int L, int U_cap, int64_t V, int d, int N,
                                           mole_dtype dtype, void *hip_stream)
 {
-    clear_error();
-    if (dtype != MOLE_F32 && dtype != MOLE_BF16)
-        return fail(MOLE_EINVAL, "mole_offload_fetch: unknown dtype %d", (int)dtype);
-    if (L < 1 || U_cap < 0 || V < 1 || d < 1 || N < 1)
-        return fail(MOLE_EINVAL, "mole_offload_fetch: bad size (L=%d, U_cap=%d, V=%lld, d=%d, N=%d)", L, U_cap,
-                    (long long)V, d, N);
-    const int64_t eb = (int64_t)elem_bytes(dtype);
-    const int64_t row_bytes = (int64_t)N * d * eb;
-    if (row_bytes % 16)
-        return fail(MOLE_EUNSUPPORTED, "mole_offload_fetch: a row block of %lld bytes is not a multiple of 16",
-                    (long long)row_bytes);
-    if (U_cap == 0)
-        return MOLE_OK;
-    if (!host_table || !uniq || !n_uniq || !staging)
-        return fail(MOLE_EINVAL, "mole_offload_fetch: host_table, uniq, n_uniq and staging must not be NULL");
-    if (!aligned16(host_table) || !aligned16(staging))
-        return fail(MOLE_EINVAL, "mole_offload_fetch: host_table and staging must be 16-byte aligned");
-    if (L > 1 && (host_layer_stride < V * N * (int64_t)d || staging_layer_stride < (int64_t)U_cap * N * d ||
-                  (host_layer_stride * eb) % 16 || (staging_layer_stride * eb) % 16))
-        return fail(MOLE_EINVAL, "mole_offload_fetch: layer strides too small or not 16-byte multiples");
-    const int row16 = (int)(row_bytes / 16);
-    const int pieces = (row16 + 63) / 64;
-    int64_t waves = (int64_t)L * U_cap * pieces;
-    int64_t blocks = (waves + 3) / 4;
-    const int64_t cap = (int64_t)num_cus() * 8;
-    if (blocks > cap)
-        blocks = cap;
-    hipLaunchKernelGGL(fetch_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
-                       static_cast<const uint4 *>(host_table), host_layer_stride * eb / 16, uniq, n_uniq,
-                       static_cast<uint4 *>(staging), staging_layer_stride * eb / 16, err_flag, L, U_cap, V,
-                       row16);
-    MOLE_HIP_CHECK(hipGetLastError());
-    return MOLE_OK;
+    return fetch_impl("mole_offload_fetch", false, host_table, host_layer_stride, uniq, n_uniq, staging,
+                      staging_layer_stride, err_flag, L, U_cap, V, d, N, dtype, hip_stream);
+}
+
+extern "C" mole_status mole_offload_fetch_idmajor(const void *host_table, const int32_t *uniq,
+                                                  const int32_t *n_uniq, void *staging,
+                                                  int64_t staging_layer_stride, int32_t *err_flag, int L,
+                                                  int U_cap, int64_t V, int d, int N, mole_dtype dtype,
+                                                  void *hip_stream)
+{
+    return fetch_impl("mole_offload_fetch_idmajor", true, host_table, 0, uniq, n_uniq, staging,
+                      staging_layer_stride, err_flag, L, U_cap, V, d, N, dtype, hip_stream);
 }

@@ -134,6 +134,25 @@ def test_offload_fetch_rejects_bad_arguments():
     mb.mole_offload_fetch(**a)      # nothing to fetch: MOLE_OK without a launch
 
 
+def test_offload_fetch_idmajor_rejects_bad_arguments():
+    base = dict(host_table=A16, uniq=A16, n_uniq=A16, staging=A16, staging_layer_stride=8 * 4 * 64, err_flag=None,
+                L=2, U_cap=8, V=100, d=64, N=4, dtype=mb.MOLE_BF16, stream=0)
+    cases = [(dict(host_table=None), mb.MOLE_EINVAL), (dict(n_uniq=None), mb.MOLE_EINVAL),
+             (dict(staging=None), mb.MOLE_EINVAL), (dict(L=0), mb.MOLE_EINVAL), (dict(dtype=5), mb.MOLE_EINVAL),
+             (dict(d=3, N=1), mb.MOLE_EUNSUPPORTED), (dict(host_table=A16 + 4), mb.MOLE_EINVAL),
+             (dict(staging_layer_stride=8 * 4 * 64 - 8), mb.MOLE_EINVAL)]
+    for kw, status in cases:
+        a = dict(base)
+        a.update(kw)
+        with pytest.raises(mb.MoleError) as e:
+            mb.mole_offload_fetch_idmajor(**a)
+        assert e.value.status == status, kw
+        assert "mole_offload_fetch_idmajor" in e.value.message
+    a = dict(base)
+    a.update(U_cap=0)
+    mb.mole_offload_fetch_idmajor(**a)      # nothing to fetch: MOLE_OK without a launch
+
+
 def test_product_package_does_not_import_the_oracle():
     """The product path must never route through the CPU oracle: no import, no path, no dlopen."""
     pkg = os.path.join(ROOT, "paper_2503_15798_amd")
