@@ -123,6 +123,32 @@ def lookup_forward(table: np.ndarray, ids: np.ndarray, h: np.ndarray, W_r: np.nd
     return out, g, rows, int(err.value)
 
 
+def layer_forward(table: np.ndarray, ids: np.ndarray, x: np.ndarray, ln_w: np.ndarray, eps: float,
+                  W_r: np.ndarray, shared: Optional[np.ndarray] = None
+                  ) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray, int]:
+    """MoLE part of the inference listing from the post-attention state x (norm, router, lookup, adds).
+    Returns (out [T,d], gates [T,N], hn [T,d] (the normed state), rows [T], err)."""
+    V, N, d = table.shape
+    T = int(ids.shape[0])
+    assert x.shape == (T, d) and W_r.shape == (d, N) and ln_w.shape == (d,)
+    table = np.ascontiguousarray(table)
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    x, W_r, ln_w = np.ascontiguousarray(x), np.ascontiguousarray(W_r), np.ascontiguousarray(ln_w)
+    shared = None if shared is None else np.ascontiguousarray(shared)
+    act = _same(x, W_r, ln_w, shared)
+    out = np.empty((T, d), dtype=np.float64)
+    g = np.empty((T, N), dtype=np.float64)
+    hn = np.empty((T, d), dtype=np.float64)
+    rows = np.empty((T,), dtype=np.int64)
+    err = ctypes.c_int32(0)
+    rc = lib().mole_oracle_layer_forward(
+        _p(table), _code(table), _p(ids), _p(x), _p(ln_w), ctypes.c_double(eps), _p(W_r), _p(shared), act,
+        ctypes.c_int64(T), ctypes.c_int64(V), d, N, _p(out), _p(g), _p(hn), _p(rows), ctypes.byref(err))
+    if rc:
+        raise RuntimeError(f"mole_oracle_layer_forward rc={rc}")
+    return out, g, hn, rows, int(err.value)
+
+
 def dedup(ids: np.ndarray, V: int) -> Tuple[np.ndarray, np.ndarray, int, int]:
     """Canonical dedup map.  Returns (uniq [U] ascending, inv [T], U, err)."""
     ids = np.ascontiguousarray(ids, dtype=np.int32)

@@ -153,6 +153,74 @@ int mole_oracle_lookup_forward(const void *table, int table_dtype,
 }
 
 /*
+ * The MoLE part of the inference listing (Appendix, inference phase), from the state after attention:
+ *   hn[t,:]  = x[t,:] / sqrt(mean_k x[t,k]^2 + eps) * ln_w          post-attention RMSNorm
+ *   g[t,:]   = softmax(hn[t,:] . W_r)
+ *   out[t,c] = x[t,c] + shared[t,c] + sum_j g[t,j] * table[ids[t], j, c]
+ * x is both the norm's input and the residual.  hn is kept in fp64 (no rounding to storage).
+ * shared may be NULL (= 0).  gates_out, hn_out, rows, err nullable.
+ */
+int mole_oracle_layer_forward(const void *table, int table_dtype, const int32_t *ids,
+                              const void *x, const void *ln_w, double eps, const void *W_r,
+                              const void *shared, int act_dtype,
+                              int64_t T, int64_t V, int d, int N,
+                              double *out, double *gates_out, double *hn_out, int64_t *rows, int32_t *err)
+{
+    if (!table || !ids || !x || !ln_w || !W_r || !out || T < 0 || V <= 0 || d <= 0 || N <= 0)
+        return 1;
+    double *hn = (double *)malloc(sizeof(double) * (size_t)(T > 0 ? T : 1) * (size_t)d);
+    double *gates = (double *)malloc(sizeof(double) * (size_t)(T > 0 ? T : 1) * (size_t)N);
+    if (!hn || !gates) {
+        free(hn);
+        free(gates);
+        return 2;
+    }
+    for (int64_t t = 0; t < T; ++t) {
+        double ss = 0.0;
+        for (int k = 0; k < d; ++k) {
+            const double v = ld(x, act_dtype, t * d + k);
+            ss += v * v;
+        }
+        const double rs = 1.0 / sqrt(ss / (double)d + eps);
+        for (int k = 0; k < d; ++k)
+            hn[t * d + k] = ld(x, act_dtype, t * d + k) * rs * ld(ln_w, act_dtype, k);
+    }
+    int rc = mole_oracle_gates(hn, 2, W_r, act_dtype, T, d, N, gates);
+    if (rc) {
+        free(hn);
+        free(gates);
+        return rc;
+    }
+    int any_bad = 0;
+    for (int64_t t = 0; t < T; ++t) {
+        const int64_t id = ids[t];
+        const int ok = (id >= 0 && id < V);
+        if (!ok)
+            any_bad = 1;
+        if (rows)
+            rows[t] = ok ? id : -1;
+        for (int c = 0; c < d; ++c) {
+            double v = ld(x, act_dtype, t * d + c);
+            if (shared)
+                v += ld(shared, act_dtype, t * d + c);
+            if (ok)
+                for (int j = 0; j < N; ++j)
+                    v += gates[t * N + j] * ld(table, table_dtype, (id * N + j) * (int64_t)d + c);
+            out[t * d + c] = v;
+        }
+    }
+    if (gates_out)
+        memcpy(gates_out, gates, sizeof(double) * (size_t)T * (size_t)N);
+    if (hn_out)
+        memcpy(hn_out, hn, sizeof(double) * (size_t)T * (size_t)d);
+    if (err)
+        *err = any_bad;
+    free(hn);
+    free(gates);
+    return 0;
+}
+
+/*
  * Canonical dedup map: uniq = distinct in-range ids, ascending; inv[t] = index of ids[t] in uniq
  * (-1 for an id outside [0,V), which also sets *err).  Written as the definition: mark, then rank.
  */

@@ -324,6 +324,93 @@ def test_build_lut_optional_rmsnorm():
 # a planted mistake must be caught: the same checks fail on deliberately wrong variants
 # (the variants live here, on the CPU, as numpy code)
 # --------------------------------------------------------------------------------------------
+# --------------------------------------------------------------------------------------------
+# the layer from the post-attention state (inference listing): norm -> router -> lookup -> adds
+# --------------------------------------------------------------------------------------------
+def fused_case(dtype=np.float64, T=29, V=83, d=40, N=6, seed=3):
+    rng = np.random.default_rng(seed)
+    tab = rng.standard_normal((V, N, d))
+    x = rng.standard_normal((T, d)) * 3.0 + 0.5
+    ln_w = rng.uniform(0.5, 1.5, size=d)
+    W_r = rng.standard_normal((d, N)) * 0.4
+    shared = rng.standard_normal((T, d))
+    ids = rng.integers(0, V, size=T).astype(np.int32)
+    return tab, ids, x, ln_w, W_r, shared
+
+
+def test_layer_forward_matches_torch_rmsnorm_softmax_einsum():
+    """Independent evaluation with torch CPU ops in fp64, in the order of the inference listing."""
+    import torch
+    tab, ids, x, ln_w, W_r, shared = fused_case()
+    eps = 1e-5
+    out, g, hn, rows, err = oracle.layer_forward(tab, ids, x, ln_w, eps, W_r, shared)
+    xt = torch.from_numpy(x)
+    hn_t = xt * torch.rsqrt(xt.pow(2).mean(-1, keepdim=True) + eps) * torch.from_numpy(ln_w)
+    g_t = torch.softmax(hn_t @ torch.from_numpy(W_r), dim=-1)
+    looked = torch.from_numpy(tab)[torch.from_numpy(ids).long()]                   # [T,N,d]
+    out_t = xt + torch.from_numpy(shared) + (looked * g_t.unsqueeze(-1)).sum(dim=1)
+    assert err == 0 and np.array_equal(rows, ids)
+    np.testing.assert_allclose(hn, hn_t.numpy(), rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(g, g_t.numpy(), rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(out, out_t.numpy(), rtol=1e-12, atol=1e-13)
+
+
+def test_layer_forward_is_the_pinned_forward_after_a_numpy_norm():
+    tab, ids, x, ln_w, W_r, shared = fused_case(seed=8)
+    eps = 1e-6
+    out, g, hn, _, _ = oracle.layer_forward(tab, ids, x, ln_w, eps, W_r, shared)
+    hn_np = x / np.sqrt((x * x).mean(axis=1, keepdims=True) + eps) * ln_w
+    ref, g_ref, _, _ = oracle.lookup_forward(tab, ids, hn_np, W_r, shared, residual=x)
+    np.testing.assert_allclose(out, ref, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(g, g_ref, rtol=1e-12, atol=1e-15)
+    # without shared: the term is simply absent
+    out2, *_ = oracle.layer_forward(tab, ids, x, ln_w, eps, W_r, None)
+    np.testing.assert_allclose(out2, out - shared, rtol=1e-12, atol=1e-12)
+
+
+def test_layer_forward_invariants():
+    tab, ids, x, ln_w, W_r, shared = fused_case(seed=21)
+    # eps = 0: the normed state, hence the gates, do not change when a token's state is scaled
+    scale = np.linspace(0.1, 40.0, x.shape[0])[:, None]
+    _, g1, hn1, _, _ = oracle.layer_forward(tab, ids, x, ln_w, 0.0, W_r, shared)
+    _, g2, hn2, _, _ = oracle.layer_forward(tab, ids, x * scale, ln_w, 0.0, W_r, shared)
+    np.testing.assert_allclose(hn1, hn2, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(g1, g2, rtol=1e-11, atol=1e-15)
+    # unit weight, eps = 0: every normed row has mean square exactly 1
+    _, _, hn3, _, _ = oracle.layer_forward(tab, ids, x, np.ones_like(ln_w), 0.0, W_r, shared)
+    np.testing.assert_allclose((hn3 * hn3).mean(axis=1), 1.0, rtol=1e-13)
+    # a huge eps switches the router off: uniform gates, so out = x + shared + mean of the rows
+    out4, g4, _, _, _ = oracle.layer_forward(tab, ids, x, ln_w, 1e30, W_r, shared)
+    np.testing.assert_allclose(g4, 1.0 / tab.shape[1], rtol=1e-9)
+    np.testing.assert_allclose(out4, x + shared + tab[ids].mean(axis=1), rtol=1e-9, atol=1e-9)
+    # an id outside the table: routed term zero, flagged
+    bad = ids.copy()
+    bad[3] = tab.shape[0]
+    out5, _, _, rows5, err5 = oracle.layer_forward(tab, bad, x, ln_w, 1e-5, W_r, shared)
+    assert err5 == 1 and rows5[3] == -1
+    np.testing.assert_allclose(out5[3], x[3] + shared[3], rtol=0, atol=0)
+
+
+def test_layer_forward_pins_catch_planted_mistakes():
+    tab, ids, x, ln_w, W_r, shared = fused_case(seed=30)
+    eps = 1e-5
+    good, *_ = oracle.layer_forward(tab, ids, x, ln_w, eps, W_r, shared)
+    rms = np.sqrt((x * x).mean(axis=1, keepdims=True) + eps)
+
+    def layer(hn, res):
+        return res + shared + np.einsum("tn,tnd->td", np_softmax(hn @ W_r), tab[ids])
+    wrong = {
+        "router on the un-normed state": layer(x, x),
+        "norm weight dropped": layer(x / rms, x),
+        "normed state as residual": layer(x / rms * ln_w, x / rms * ln_w),
+        "mean subtracted (LayerNorm)": layer((x - x.mean(1, keepdims=True)) / rms * ln_w, x),
+        "sum instead of mean of squares": layer(x / np.sqrt((x * x).sum(1, keepdims=True) + eps) * ln_w, x),
+        "residual dropped": layer(x / rms * ln_w, 0 * x),
+    }
+    for name, bad in wrong.items():
+        assert not np.allclose(good, bad, rtol=1e-9, atol=1e-12), name
+
+
 def test_pins_catch_planted_mistakes():
     w = wl.scaled(wl.CONFIGS["tiny"], V=97, d=24, N=5, T=33)
     tab = wl.random_table(w).astype(np.float64)
