@@ -133,6 +133,31 @@ class Layers:
                                   w.T * w.d, None, None, self.err, w.L, w.T, w.V, w.d, w.N, q["bits"], q["block"],
                                   q["scale_bytes"], 0, None, stream=stream)
 
+    def forward_with_residual(self, i, stream):
+        """The layer as the inference listing has it, unfused: normed state in, residual added."""
+        w, mb = self.w, self.mb
+        mb.mole_lookup_forward_layers(
+            self.tabs, w.V * w.N * w.d, self.ids[i % N_ID_BATCHES], None, self.h, self.W_r, self.shared, self.x,
+            self.out, w.T * w.d, None, None, self.err, w.L, w.T, w.V, w.d, w.N, self.code, 0, None, stream=stream)
+
+    def forward_fused_norm(self, i, stream):
+        """mole_layer_forward: post-attention state in; norm and residual inside the kernel."""
+        w, mb = self.w, self.mb
+        mb.mole_layer_forward(
+            self.tabs, w.V * w.N * w.d, self.ids[i % N_ID_BATCHES], None, self.x, 1e-5, self.W_rn,
+            self.shared, self.out, w.T * w.d, None, None, self.err, w.L, w.T, w.V, w.d, w.N, self.code, 0, None,
+            stream=stream)
+
+    def make_norm_inputs(self):
+        torch, w = self.torch, self.w
+        g = torch.Generator(device="cuda")
+        g.manual_seed(2000 + w.seed)
+        self.x = (torch.randn((w.L, w.T, w.d), generator=g, device="cuda") * 2.0).to(self.h.dtype)
+        ln_w = (torch.rand((w.L, w.d), generator=g, device="cuda") + 0.5).to(self.h.dtype)
+        self.W_rn = torch.empty_like(self.W_r)
+        self.mb.mole_fold_router_norm(self.W_r, ln_w, self.W_rn, w.L, w.d, w.N, self.code)
+        torch.cuda.synchronize()
+
     def distinct(self):
         import numpy as np
         return float(np.mean([len(np.unique(b)) for b in self.ids_host]))
@@ -378,6 +403,10 @@ def extras(args, torch, mb, wl, acc, stream, L):
     except Exception as e:
         out["decode410m_per_layer_launches_hip_graph"] = {"skipped": repr(e)}
 
+    # ---- the whole listing step from the post-attention state: unfused (normed state + residual, 4 activation
+    # streams) against mole_layer_forward (norm and residual inside: 3 streams)
+    out.update(norm_entries(L, acc, torch, stream, steps, warm, "decode410m"))
+
     # ---- NF4 / NF3 tables (Sec. 5.5 of the paper): quantised on the device, dequantised inside the forward
     for tag, bits, block, sbytes in (("nf4", 4, 1024, 4), ("nf3", 3, 128, 2)):
         out[f"decode410m_{tag}"] = nf_entry(L, acc, torch, stream, steps, warm, bits, block, sbytes)
@@ -432,11 +461,27 @@ def extras(args, torch, mb, wl, acc, stream, L):
         out[name + "_forward_with_plan"] = rates(ww, acc, ms, LL.distinct())
         if name == "prefill410m_uniform":
             out[name + "_nf4"] = nf_entry(LL, acc, torch, stream, steps, warm, 4, 1024, 4)
+            out.update(norm_entries(LL, acc, torch, stream, steps, warm, name))
         del LL
         torch.cuda.empty_cache()
 
     out["build_lut_410m_layer"] = build_bench(torch, mb, wl, acc, stream)
     return out
+
+
+def norm_entries(LL, acc, torch, stream, steps, warm, name):
+    w = LL.w
+    LL.make_norm_inputs()
+    res = {}
+    for tag, fn, streams in (("with_residual", LL.forward_with_residual, 4), ("fused_norm", LL.forward_fused_norm, 3)):
+        ms = time_steps(torch, stream, lambda i: fn(i, stream), steps, warm)
+        alg = (w.N * w.d * w.elem_bytes + streams * w.d * w.elem_bytes + 4) * w.T * w.L
+        res[f"{name}_{tag}"] = {"ms": round(ms, 5), "layer_tokens_per_s": w.T * w.L / (ms * 1e-3),
+                                "activation_streams": streams, "algorithmic_bytes_per_launch": alg,
+                                "algorithmic_GBps": alg / (ms * 1e-3) / 1e9,
+                                "algorithmic_frac_of_hbm_peak": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    del LL.x, LL.W_rn
+    return res
 
 
 def nf_entry(LL, acc, torch, stream, steps, warm, bits, block, sbytes):

@@ -142,6 +142,33 @@ mole_status mole_lookup_forward_layers(const void *table, int64_t table_stride,
                                        const void *workspace, size_t workspace_bytes,
                                        void *hip_stream);
 
+/* The MoLE part of a decoder layer from the state AFTER attention, with the post-attention RMSNorm
+ * and the residual folded into the kernel (inference listing, "Shared Expert" / "Routed Expert"):
+ *     hn[t,:]  = x[t,:] / sqrt(mean_k x[t,k]^2 + ln_eps) * ln_w
+ *     g[t,:]   = softmax(hn[t,:] . W_r)
+ *     out[t,:] = x[t,:] + shared_out[t,:] + sum_j g[t,j] * table[row(t), j, :]
+ * Since hn . W_r = (1/rms(x)) * x . (diag(ln_w) W_r), the norm weight is folded into the router
+ * weight once, when the model is loaded:
+ *   mole_fold_router_norm: W_rn[l,k,j] = W_r[l,k,j] * ln_w[l,k]   (one rounding to the storage type)
+ *     W_r [L,d,N] dev, ln_w [L,d] dev, W_rn [L,d,N] dev out (may alias W_r).
+ *   mole_layer_forward: takes x and W_rn; a token's logits are scaled by its 1/rms, so the normed
+ *     state is never materialised, and x, read once, is both the norm's input and the residual.
+ *     x [T,d] dev: the state after the attention residual add; ln_eps >= 0; shared_out [T,d] dev
+ *     nullable: FFN_shared(hn), computed by the caller from the same normed state.  Everything
+ *     else as in mole_lookup_forward_layers (L = 1: strides ignored).
+ * Saves the 2d bytes per token of reading hn next to x. */
+mole_status mole_fold_router_norm(const void *W_r, const void *ln_w, void *W_rn,
+                                  int L, int d, int N, mole_dtype dtype, void *hip_stream);
+mole_status mole_layer_forward(const void *table, int64_t table_stride,
+                               const int32_t *ids, const int32_t *slot,
+                               const void *x, float ln_eps, const void *W_rn,
+                               const void *shared_out,
+                               void *out, int64_t act_stride,
+                               float *gates_dbg, int64_t *rows_dbg, int32_t *err_flag,
+                               int L, int T, int64_t rows, int d, int N, mole_dtype dtype,
+                               unsigned flags,
+                               const void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* ------------------------------------------------------------------------------------------
  * Offloaded-LUT row fetch (Sec. 3.3: the LUT lives off-chip, only looked-up rows are moved;
  * the lookup line of the inference listing):

@@ -47,26 +47,107 @@ __device__ __forceinline__ float mac2(float acc, uint32_t hp, uint32_t wp)
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, hp), __builtin_bit_cast(bf16x2, wp), acc, false);
 }
 
+// Cross-lane exchange without the LDS crossbar.  gfx950 has v_permlane32_swap / v_permlane16_swap
+// (swap the upper 32 lanes of one register with the lower 32 of another; swap the odd 16-lane rows
+// of one with the even rows of the other) and DPP modifiers that reach lane ^ 8 (row_ror:8 inside a
+// 16-lane row), ^ 2 and ^ 1 (quad_perm).  Only ^ 4 still goes through ds_bpermute.
+typedef __attribute__((ext_vector_type(2))) unsigned int swap_pair;
+
+// (a, b) -> (a with its upper 32 lanes replaced by b's lower 32, b with its lower 32 lanes replaced by
+// a's upper 32) for ROW = 32; the same with odd / even 16-lane rows for ROW = 16.  The two results
+// pass through an empty asm as integers: read directly as floats, hipcc (ROCm 7.2) uses the first
+// result for both.
+template <int ROW>
+__device__ __forceinline__ void lane_swap(float &a, float &b)
+{
+    static_assert(ROW == 32 || ROW == 16, "");
+    const unsigned ua = __builtin_bit_cast(unsigned, a), ub = __builtin_bit_cast(unsigned, b);
+    const swap_pair r = ROW == 32 ? __builtin_amdgcn_permlane32_swap(ua, ub, false, false)
+                                  : __builtin_amdgcn_permlane16_swap(ua, ub, false, false);
+    unsigned rx = r.x, ry = r.y;
+    asm("" : "+v"(rx), "+v"(ry));
+    a = __builtin_bit_cast(float, rx);
+    b = __builtin_bit_cast(float, ry);
+}
+
+struct OpAdd {
+    static __device__ __forceinline__ float run(float a, float b) { return a + b; }
+};
+struct OpMax {
+    static __device__ __forceinline__ float run(float a, float b) { return fmaxf(a, b); }
+};
+
+// value of lane (l ^ W) for W in {1, 2, 4, 8}
+template <int W>
+__device__ __forceinline__ float lane_xor(float v)
+{
+    static_assert(W == 1 || W == 2 || W == 4 || W == 8, "other distances use the swap instructions");
+    const int iv = __builtin_bit_cast(int, v);
+    if constexpr (W == 8)
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, iv, 0x128 /* row_ror:8 */, 0xf, 0xf, false));
+    else if constexpr (W == 2)
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, iv, 0x4E /* quad_perm:[2,3,0,1] */, 0xf, 0xf, false));
+    else if constexpr (W == 1)
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, iv, 0xB1 /* quad_perm:[1,0,3,2] */, 0xf, 0xf, false));
+    else
+        return __shfl_xor(v, 4);
+}
+
+// op(v[l], v[l ^ W]) in every lane, W in {1, ..., 32}
+template <int W, class Op>
+__device__ __forceinline__ float pair_reduce(float v)
+{
+    if constexpr (W == 32 || W == 16) {
+        // swapping a value with itself leaves (own half, own half) and (other half, other half)
+        float a = v, b = v;
+        lane_swap<W>(a, b);
+        return Op::run(a, b);
+    } else {
+        return Op::run(v, lane_xor<W>(v));
+    }
+}
+
+// op over the lanes that differ from l in the bits FROM, FROM/2, ..., TO (powers of two)
+template <int FROM, int TO, class Op>
+__device__ __forceinline__ float span_reduce(float v)
+{
+    if constexpr (FROM < TO) {
+        return v;
+    } else {
+        v = pair_reduce<FROM, Op>(v);
+        if constexpr (FROM > TO)
+            return span_reduce<FROM / 2, TO, Op>(v);
+        else
+            return v;
+    }
+}
+
 // Fold N per-lane partial sums over the 64 lanes.  Each step halves the number of values a
-// lane carries by trading one half with the lane `W` away.  Returns, in every lane, the full
-// sum of value j = lane >> log2(64/N).
+// lane carries by trading one half with the lane `W` away: lanes with bit W clear keep value i and
+// take the partner's value i, lanes with it set keep value i + N/2 and take the partner's.  For
+// W = 32 and 16 that trade is exactly one swap instruction on the pair (z[i], z[i + N/2]) followed by
+// an add.  Returns, in every lane, the full sum of value j = lane >> log2(64/N).
 template <int N, int W>
 struct Fold {
     static __device__ __forceinline__ float run(float *z, int lane)
     {
         if constexpr (N == 1) {
-            float v = z[0];
+            return span_reduce<W, 1, OpAdd>(z[0]);
+        } else if constexpr (W == 32 || W == 16) {
 #pragma unroll
-            for (int w = W; w >= 1; w >>= 1)
-                v += __shfl_xor(v, w);
-            return v;
+            for (int i = 0; i < N / 2; ++i) {
+                float a = z[i], b = z[i + N / 2];
+                lane_swap<W>(a, b);
+                z[i] = a + b;
+            }
+            return Fold<N / 2, W / 2>::run(z, lane);
         } else {
             const bool up = (lane & W) != 0;
 #pragma unroll
             for (int i = 0; i < N / 2; ++i) {
                 const float send = up ? z[i] : z[i + N / 2];
                 const float keep = up ? z[i + N / 2] : z[i];
-                z[i] = keep + __shfl_xor(send, W);
+                z[i] = keep + lane_xor<W>(send);
             }
             return Fold<N / 2, W / 2>::run(z, lane);
         }
@@ -162,16 +243,43 @@ __device__ __forceinline__ void router_piece(float (&z)[N], const uint4 *smem, i
 // Router equation for one token on one wavefront: returns, in lane l, the gate of expert
 // l / (64/N) (softmax over all N experts of h . r_j).  h0 / h1 are the lane's pieces of the first
 // two 512-column chunks, already loaded by the caller; further chunks are loaded here.
-template <int N, bool NTA>
+// sum of the squares of the 8 bf16 values of one 16-byte piece
+__device__ __forceinline__ float sumsq8(const uint4 &v)
+{
+    float s = bf16lo(v.x) * bf16lo(v.x);
+    s = fmaf(bf16hi(v.x), bf16hi(v.x), s);
+    s = fmaf(bf16lo(v.y), bf16lo(v.y), s);
+    s = fmaf(bf16hi(v.y), bf16hi(v.y), s);
+    s = fmaf(bf16lo(v.z), bf16lo(v.z), s);
+    s = fmaf(bf16hi(v.z), bf16hi(v.z), s);
+    s = fmaf(bf16lo(v.w), bf16lo(v.w), s);
+    s = fmaf(bf16hi(v.w), bf16hi(v.w), s);
+    return s;
+}
+
+// NORM: hrow is the state BEFORE an RMSNorm whose weight has been folded into the router weight
+// (h . W_r = (1/rms) * x . (diag(ln_w) W_r)); the logits are scaled by 1 / sqrt(mean(x^2) + eps) of
+// this token.
+template <int N, bool NTA, bool NORM = false>
 __device__ __forceinline__ float router_gate(const uint4 *smem, int kgroups, const uint16_t *hrow, int d, int lane,
-                                             const uint4 &h0, const uint4 &h1)
+                                             const uint4 &h0, const uint4 &h1, float eps = 0.f)
 {
     constexpr int LPJ = 64 / N;
+    const int col0 = lane * 8;
+    float rs = 1.f;
+    if constexpr (NORM) {
+        // 1 / rms first, while few registers are live (pieces past the end of the row were loaded as zeros)
+        float ss = sumsq8(h0) + sumsq8(h1);
+        for (int c0 = 1024; c0 < d; c0 += 512)
+            if (c0 + col0 < d)
+                ss += sumsq8(ld16_stream<NTA>(hrow + c0 + col0));
+        ss = span_reduce<32, 1, OpAdd>(ss);
+        rs = __builtin_amdgcn_rsqf(ss / (float)d + eps);
+    }
     float z[N];
 #pragma unroll
     for (int j = 0; j < N; ++j)
         z[j] = 0.f;
-    const int col0 = lane * 8;
     if (col0 < d)
         router_piece<N>(z, smem, kgroups, h0, col0 >> 3);
     if (col0 + 512 < d)
@@ -181,16 +289,10 @@ __device__ __forceinline__ float router_gate(const uint4 *smem, int kgroups, con
         if (cc < d)
             router_piece<N>(z, smem, kgroups, ld16_stream<NTA>(hrow + cc), cc >> 3);
     }
-    const float zz = Fold<N, 32>::run(z, lane);
-    float m = zz;
-#pragma unroll
-    for (int w = 32; w >= LPJ; w >>= 1)
-        m = fmaxf(m, __shfl_xor(m, w));
+    const float zz = Fold<N, 32>::run(z, lane) * rs;
+    const float m = span_reduce<32, LPJ, OpMax>(zz);
     const float e = __expf(zz - m);
-    float s = e;
-#pragma unroll
-    for (int w = 32; w >= LPJ; w >>= 1)
-        s += __shfl_xor(s, w);
+    const float s = span_reduce<32, LPJ, OpAdd>(e);
     return e / s;
 }
 

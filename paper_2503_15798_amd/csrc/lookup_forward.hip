@@ -36,6 +36,8 @@ struct FwdArgs {
     int64_t *rows_dbg;
     int32_t *err_flag;
     const int32_t *plan;
+    int norm;               // 1: h is the state BEFORE the RMSNorm in front of the router (weight folded into
+    float ln_eps;           //    W_r beforehand); it also serves as the residual
     int64_t table_stride;   // per layer, elements
     int64_t act_stride;     // per layer, elements
     int64_t rows;
@@ -64,12 +66,18 @@ __device__ __forceinline__ void ring_load(uint4 (&r)[N], const uint16_t *base, i
 // chunk of a token instead of a whole token, so that the chunks of a token are fetched and combined
 // by different waves at the same time (each computes the token's gates itself: the router is cheap
 // next to a second memory round trip).
-template <int N, int WPB, bool NTA, bool SPLIT>
+// NORM: a.h is the state after attention and a.W_r carries the norm weight (mole_fold_router_norm);
+// the token's 1/rms scales the logits and the same state is the residual of the epilogue.
+template <int N, int WPB, bool NTA, bool SPLIT, bool NORM>
 __global__ __launch_bounds__(WPB * 64) __attribute__((amdgpu_waves_per_eu(N <= 16 ? 4 : 2)))
 void fwd_bf16_stream_kernel(FwdArgs a)
 {
     extern __shared__ uint4 smem[];
     constexpr int LPJ = 64 / N;   // lanes per expert after the fold
+#ifndef MOLE_FWD_HOLD_X
+#define MOLE_FWD_HOLD_X (N != 16 || !NTA)
+#endif
+    constexpr bool HOLD_X = NORM && (MOLE_FWD_HOLD_X);
     const int d = a.d;
     const int kgroups = d >> 3;
     const int layer = blockIdx.y;
@@ -130,9 +138,10 @@ void fwd_bf16_stream_kernel(FwdArgs a)
         if (a.rows_dbg && layer == 0 && lane == 0 && reporter)
             a.rows_dbg[t] = valid ? row : -1;
 
-        const float g = router_gate<N, NTA>(smem, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1);
+        const float g = router_gate<N, NTA, NORM>(smem, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1, a.ln_eps);
         if (a.gates_dbg && reporter && (lane & (LPJ - 1)) == 0)
             a.gates_dbg[((int64_t)layer * T + t) * N + lane / LPJ] = g;
+        const uint4 x0 = h0, x1 = h1;                  // NORM: the residual of chunks 0 and 1
         // the next token's h goes in flight now; its latency hides behind this token's combine
         load_h2<NTA>(h0, h1, hbase + (int64_t)nxt.t * d, d, lane);
         // gates into scalar registers: expert j's gate sits in lane j * (64/N)
@@ -152,8 +161,18 @@ void fwd_bf16_stream_kernel(FwdArgs a)
             uint4 sv = make_uint4(0, 0, 0, 0), rv = make_uint4(0, 0, 0, 0);
             if (on && sbase)
                 sv = ld16_stream<NTA>(sbase + off);
-            if (on && rbase)
+            if constexpr (NORM) {
+                // the residual is the state itself: kept in registers unless that would spill (N = 16 with
+                // non-temporal loads sits at its 128-register budget), else read a second time
+                if (HOLD_X && c0 == 0)
+                    rv = x0;
+                else if (HOLD_X && c0 == 512)
+                    rv = x1;
+                else if (on)
+                    rv = ld16_stream<NTA>(hbase + off);
+            } else if (on && rbase) {
                 rv = ld16_stream<NTA>(rbase + off);
+            }
             float acc[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e)
@@ -221,6 +240,7 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(FwdArgs a)
     const int64_t act_off = (int64_t)layer * a.act_stride;
     const E *hbase = static_cast<const E *>(a.h) + act_off;
     const E *Wr = static_cast<const E *>(a.W_r) + (int64_t)layer * d * N;
+    const bool norm = a.norm != 0;
     const E *sbase = a.shared ? static_cast<const E *>(a.shared) + act_off : nullptr;
     const E *rbase = a.residual ? static_cast<const E *>(a.residual) + act_off : nullptr;
     E *obase = static_cast<E *>(a.out) + act_off;
@@ -237,11 +257,21 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(FwdArgs a)
         const E *rp = table + (valid ? row : 0) * (int64_t)N * d;
 
         const E *hr = hbase + (int64_t)t * d;
+        float rs = 1.f;            // with a norm in front of the router: 1 / rms of this token's state
+        if (norm) {
+            float ss = 0.f;
+            for (int k = lane; k < d; k += 64)
+                ss = fmaf(ldf(hr + k), ldf(hr + k), ss);
+#pragma unroll
+            for (int w = 32; w >= 1; w >>= 1)
+                ss += __shfl_xor(ss, w);
+            rs = 1.0f / sqrtf(ss / (float)d + a.ln_eps);
+        }
         float zmine = -INFINITY;   // lane j keeps logit j
         for (int j = 0; j < N; ++j) {
             float p = 0.f;
             for (int k = lane; k < d; k += 64)
-                p = fmaf(ldf(hr + k), ldf(Wr + (int64_t)k * N + j), p);
+                p = fmaf(ldf(hr + k) * rs, ldf(Wr + (int64_t)k * N + j), p);
 #pragma unroll
             for (int w = 32; w >= 1; w >>= 1)
                 p += __shfl_xor(p, w);
@@ -273,12 +303,24 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(FwdArgs a)
             const int64_t off = (int64_t)t * d + c;
             if (sbase)
                 acc += ldf(sbase + off);
-            if (rbase)
+            if (norm)
+                acc += ldf(hr + c);
+            else if (rbase)
                 acc += ldf(rbase + off);
             stf(obase + off, acc);
         }
         wave_lds_fence();
     }
+}
+
+// W_rn[l, k, j] = W_r[l, k, j] * ln_w[l, k], one rounding to the storage type.  ln_w is [L, d] and
+// W_r is [L, d, N], so row index (l, k) is simply element / N.
+template <typename E>
+__global__ __launch_bounds__(256) void fold_norm_kernel(const E *__restrict__ W, const E *__restrict__ lnw,
+                                                         E *__restrict__ out, int64_t total, int N)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256)
+        stf(out + i, ldf(W + i) * ldf(lnw + i / N));
 }
 
 // ------------------------------------------------------------------------------------------
@@ -322,21 +364,29 @@ int64_t grid_x(int items, int L, size_t lds)
     return gx < 1 ? 1 : gx;
 }
 
-template <int N, int WPB, bool NTA, bool SPLIT>
+template <int N, int WPB, bool NTA, bool SPLIT, bool NORM>
 mole_status launch_fast(const FwdArgs &a, hipStream_t stream)
 {
     const size_t lds = router_lds_bytes(a.d, N);
     static size_t attr_set = 0;
     if (lds > attr_set) {
-        MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_bf16_stream_kernel<N, WPB, NTA, SPLIT>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        MOLE_HIP_CHECK(hipFuncSetAttribute(
+            reinterpret_cast<const void *>(&fwd_bf16_stream_kernel<N, WPB, NTA, SPLIT, NORM>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = lds;
     }
     const int items = SPLIT ? a.T * ((a.d + 511) / 512) : a.T;
     dim3 grid((unsigned)grid_x<N, WPB>(items, a.L, lds), (unsigned)a.L);
-    hipLaunchKernelGGL((fwd_bf16_stream_kernel<N, WPB, NTA, SPLIT>), grid, dim3(WPB * 64), lds, stream, a);
+    hipLaunchKernelGGL((fwd_bf16_stream_kernel<N, WPB, NTA, SPLIT, NORM>), grid, dim3(WPB * 64), lds, stream, a);
     MOLE_HIP_CHECK(hipGetLastError());
     return MOLE_OK;
+}
+
+template <int N, int WPB, bool NTA, bool SPLIT>
+mole_status launch_fast(const FwdArgs &a, hipStream_t stream)
+{
+    return a.norm ? launch_fast<N, WPB, NTA, SPLIT, true>(a, stream)
+                  : launch_fast<N, WPB, NTA, SPLIT, false>(a, stream);
 }
 
 template <int N>
@@ -361,7 +411,8 @@ mole_status forward_impl(const void *table, int64_t table_stride, const int32_t 
                          const void *h, const void *W_r, const void *shared_out, const void *residual,
                          void *out, int64_t act_stride, float *gates_dbg, int64_t *rows_dbg,
                          int32_t *err_flag, int L, int T, int64_t rows, int d, int N, mole_dtype dtype,
-                         unsigned flags, const void *workspace, size_t workspace_bytes, void *hip_stream)
+                         unsigned flags, const void *workspace, size_t workspace_bytes, void *hip_stream,
+                         float ln_eps = 0.f, bool with_norm = false)
 {
     clear_error();
     if (dtype != MOLE_F32 && dtype != MOLE_BF16)
@@ -380,6 +431,8 @@ mole_status forward_impl(const void *table, int64_t table_stride, const int32_t 
         return MOLE_OK;
     if (!table || !ids || !h || !W_r || !out)
         return fail(MOLE_EINVAL, "mole_lookup_forward: table, ids, h, W_r and out must not be NULL");
+    if (with_norm && !(ln_eps >= 0.f))
+        return fail(MOLE_EINVAL, "mole_layer_forward: ln_eps = %g must be >= 0", (double)ln_eps);
     const void *ptrs[] = {table, h, W_r, shared_out, residual, out};
     for (const void *p : ptrs)
         if (p && !aligned16(p))
@@ -405,6 +458,7 @@ mole_status forward_impl(const void *table, int64_t table_stride, const int32_t 
     a.table = table; a.ids = ids; a.slot = slot; a.h = h; a.W_r = W_r;
     a.shared = shared_out; a.residual = residual; a.out = out;
     a.gates_dbg = gates_dbg; a.rows_dbg = rows_dbg; a.err_flag = err_flag; a.plan = plan;
+    a.norm = with_norm ? 1 : 0; a.ln_eps = ln_eps;
     a.table_stride = table_stride; a.act_stride = act_stride; a.rows = rows;
     a.T = T; a.d = d; a.N = N; a.L = L;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -460,4 +514,42 @@ extern "C" mole_status mole_lookup_forward_layers(const void *table, int64_t tab
     return forward_impl(table, table_stride, ids, slot, h, W_r, shared_out, residual, out, act_stride,
                         gates_dbg, rows_dbg, err_flag, L, T, rows, d, N, dtype, flags, workspace,
                         workspace_bytes, hip_stream);
+}
+
+extern "C" mole_status mole_layer_forward(const void *table, int64_t table_stride, const int32_t *ids,
+                                          const int32_t *slot, const void *x, float ln_eps, const void *W_rn,
+                                          const void *shared_out, void *out, int64_t act_stride,
+                                          float *gates_dbg, int64_t *rows_dbg, int32_t *err_flag, int L, int T,
+                                          int64_t rows, int d, int N, mole_dtype dtype, unsigned flags,
+                                          const void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return forward_impl(table, table_stride, ids, slot, x, W_rn, shared_out, nullptr, out, act_stride, gates_dbg,
+                        rows_dbg, err_flag, L, T, rows, d, N, dtype, flags, workspace, workspace_bytes, hip_stream,
+                        ln_eps, true);
+}
+
+extern "C" mole_status mole_fold_router_norm(const void *W_r, const void *ln_w, void *W_rn, int L, int d, int N,
+                                             mole_dtype dtype, void *hip_stream)
+{
+    clear_error();
+    if (dtype != MOLE_F32 && dtype != MOLE_BF16)
+        return fail(MOLE_EINVAL, "mole_fold_router_norm: unknown dtype %d", (int)dtype);
+    if (L < 1 || d < 1 || N < 1)
+        return fail(MOLE_EINVAL, "mole_fold_router_norm: bad size (L=%d, d=%d, N=%d)", L, d, N);
+    if (!W_r || !ln_w || !W_rn)
+        return fail(MOLE_EINVAL, "mole_fold_router_norm: W_r, ln_w and W_rn must not be NULL");
+    const int64_t rows = (int64_t)L * d;
+    const int64_t total = rows * N;
+    const unsigned blocks = (unsigned)((total + 255) / 256 < 65535 * 16 ? (total + 255) / 256 : 65535 * 16);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (dtype == MOLE_F32)
+        hipLaunchKernelGGL(fold_norm_kernel<float>, dim3(blocks), dim3(256), 0, stream,
+                           static_cast<const float *>(W_r), static_cast<const float *>(ln_w),
+                           static_cast<float *>(W_rn), total, N);
+    else
+        hipLaunchKernelGGL(fold_norm_kernel<uint16_t>, dim3(blocks), dim3(256), 0, stream,
+                           static_cast<const uint16_t *>(W_r), static_cast<const uint16_t *>(ln_w),
+                           static_cast<uint16_t *>(W_rn), total, N);
+    MOLE_HIP_CHECK(hipGetLastError());
+    return MOLE_OK;
 }

@@ -186,6 +186,19 @@ def layer_inputs(w: Workload, layer: int = 0, T: Optional[int] = None) -> Dict[s
     }
 
 
+def norm_inputs(w: Workload, layer: int = 0, T: Optional[int] = None) -> Dict[str, np.ndarray]:
+    """Inputs of the layer taken from the post-attention state: x [T,d] ~N(0,1) times a per-token scale
+    drawn log-uniformly from [1/8, 8] (so that a norm in front of the router matters), and the norm
+    weight ln_w [d] ~U(0.5, 1.5); storage dtype."""
+    T = w.T if T is None else T
+    rng = np.random.default_rng(w.seed * 1000003 + 101 * layer + 3)
+    scale = np.exp2(rng.uniform(-3.0, 3.0, size=(T, 1)))
+    return {
+        "x": to_storage(_normal(rng, (T, w.d), 1.0) * scale, w.dtype),
+        "ln_w": to_storage(rng.uniform(0.5, 1.5, size=(w.d,)), w.dtype),
+    }
+
+
 def token_ids(w: Workload, batch: int = 0, T: Optional[int] = None) -> np.ndarray:
     """Batch `batch` of token ids for the workload (different batches rotate through the table)."""
     T = w.T if T is None else T

@@ -134,6 +134,31 @@ def test_offload_fetch_rejects_bad_arguments():
     mb.mole_offload_fetch(**a)      # nothing to fetch: MOLE_OK without a launch
 
 
+def test_layer_forward_rejects_bad_arguments():
+    base = dict(table=A16, table_stride=0, ids=A16, slot=None, x=A16, ln_eps=1e-5, W_rn=A16,
+                shared_out=None, out=A16, act_stride=0, gates_dbg=None, rows_dbg=None, err_flag=None, L=1, T=4,
+                rows=10, d=64, N=4, dtype=mb.MOLE_BF16, flags=0, workspace=None, stream=0, workspace_bytes=0)
+    cases = [(dict(W_rn=None), mb.MOLE_EINVAL), (dict(ln_eps=-1.0), mb.MOLE_EINVAL),
+             (dict(ln_eps=float("nan")), mb.MOLE_EINVAL), (dict(x=None), mb.MOLE_EINVAL),
+             (dict(W_rn=A16 + 2), mb.MOLE_EINVAL), (dict(d=60), mb.MOLE_EUNSUPPORTED),
+             (dict(flags=mb.MOLE_FLAG_DEDUP), mb.MOLE_EWORKSPACE)]
+    for kw, status in cases:
+        a = dict(base)
+        a.update(kw)
+        with pytest.raises(mb.MoleError) as e:
+            mb.mole_layer_forward(**a)
+        assert e.value.status == status, kw
+    a = dict(base)
+    a.update(T=0)
+    mb.mole_layer_forward(**a)          # empty batch: MOLE_OK, nothing launched
+    for kw in (dict(W_r=None), dict(ln_w=None), dict(W_rn=None), dict(L=0), dict(d=0), dict(N=0), dict(dtype=4)):
+        a = dict(W_r=A16, ln_w=A16, W_rn=A16, L=1, d=64, N=4, dtype=mb.MOLE_BF16, stream=0)
+        a.update(kw)
+        with pytest.raises(mb.MoleError) as e:
+            mb.mole_fold_router_norm(**a)
+        assert e.value.status == mb.MOLE_EINVAL, kw
+
+
 def test_offload_fetch_idmajor_rejects_bad_arguments():
     base = dict(host_table=A16, uniq=A16, n_uniq=A16, staging=A16, staging_layer_stride=8 * 4 * 64, err_flag=None,
                 L=2, U_cap=8, V=100, d=64, N=4, dtype=mb.MOLE_BF16, stream=0)
