@@ -448,7 +448,8 @@ def extras(args, torch, mb, wl, acc, stream, L):
     del L.tabs
     torch.cuda.empty_cache()
 
-    for name in ("prefill410m", "prefill410m_uniform", "decode160m"):
+    for name in ("prefill410m", "prefill410m_uniform", "decode160m", "decode1b_4e", "decode410m_n2", "decode410m_n4",
+                 "decode410m_n8"):
         ww = wl.CONFIGS[name]
         LL = Layers(ww, torch, mb, wl)
         ms = time_steps(torch, stream, plain(LL), steps, warm)

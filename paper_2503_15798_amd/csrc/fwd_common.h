@@ -190,9 +190,12 @@ __device__ __forceinline__ uint4 ld16_row(const uint16_t *p)
 // of contiguous memory) and issues a batch of loads before it touches any of them.
 __host__ __device__ constexpr size_t router_lds_bytes(int d, int N) { return (size_t)N * ((d >> 3) + 1) * 16; }
 
-template <int N>
+// NREAL < N (= 4): the weight has only NREAL (= 2) columns; the missing experts get zero weights here and
+// are removed from the softmax in router_gate.
+template <int N, int NREAL = N>
 __device__ __forceinline__ void fill_router_lds(uint4 *smem, const uint16_t *Wr, int kgroups, int nthreads)
 {
+    static_assert(NREAL == N || (N == 4 && NREAL == 2), "padding is only provided from 2 to 4 experts");
     constexpr int NQ = N / 4;
     constexpr int B = 8;            // pieces per thread whose loads are issued before any is used
     const int n_w4 = kgroups * N;   // = (d/2 k-pairs) * NQ pieces
@@ -202,8 +205,13 @@ __device__ __forceinline__ void fill_router_lds(uint4 *smem, const uint16_t *Wr,
         for (int u = 0; u < B; ++u) {
             const int i = min(i0 + u * nthreads, n_w4 - 1);
             const int jq = i % NQ, kp = i / NQ;
-            w0[u] = *reinterpret_cast<const uint2 *>(Wr + (int64_t)(2 * kp) * N + jq * 4);
-            w1[u] = *reinterpret_cast<const uint2 *>(Wr + (int64_t)(2 * kp + 1) * N + jq * 4);
+            if constexpr (NREAL == N) {
+                w0[u] = *reinterpret_cast<const uint2 *>(Wr + (int64_t)(2 * kp) * N + jq * 4);
+                w1[u] = *reinterpret_cast<const uint2 *>(Wr + (int64_t)(2 * kp + 1) * N + jq * 4);
+            } else {
+                w0[u] = make_uint2(*reinterpret_cast<const uint32_t *>(Wr + (int64_t)(2 * kp) * NREAL), 0u);
+                w1[u] = make_uint2(*reinterpret_cast<const uint32_t *>(Wr + (int64_t)(2 * kp + 1) * NREAL), 0u);
+            }
         }
 #pragma unroll
         for (int u = 0; u < B; ++u) {
@@ -260,7 +268,7 @@ __device__ __forceinline__ float sumsq8(const uint4 &v)
 // NORM: hrow is the state BEFORE an RMSNorm whose weight has been folded into the router weight
 // (h . W_r = (1/rms) * x . (diag(ln_w) W_r)); the logits are scaled by 1 / sqrt(mean(x^2) + eps) of
 // this token.
-template <int N, bool NTA, bool NORM = false>
+template <int N, bool NTA, bool NORM = false, int NREAL = N>
 __device__ __forceinline__ float router_gate(const uint4 *smem, int kgroups, const uint16_t *hrow, int d, int lane,
                                              const uint4 &h0, const uint4 &h1, float eps = 0.f)
 {
@@ -289,7 +297,11 @@ __device__ __forceinline__ float router_gate(const uint4 *smem, int kgroups, con
         if (cc < d)
             router_piece<N>(z, smem, kgroups, ld16_stream<NTA>(hrow + cc), cc >> 3);
     }
-    const float zz = Fold<N, 32>::run(z, lane) * rs;
+    float zz = Fold<N, 32>::run(z, lane) * rs;
+    if constexpr (NREAL < N) {
+        if (lane / LPJ >= NREAL)
+            zz = -INFINITY;                 // a padded expert: gate exactly 0
+    }
     const float m = span_reduce<32, LPJ, OpMax>(zz);
     const float e = __expf(zz - m);
     const float s = span_reduce<32, LPJ, OpAdd>(e);

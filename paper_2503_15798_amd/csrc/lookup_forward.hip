@@ -52,7 +52,7 @@ struct FwdArgs {
 // alike; the next token's router input is prefetched the same way.
 // Table rows are loaded with plain (cacheable) loads: repeated ids are then served by L2 /
 // Infinity Cache.  Rows that the plan marks as read-once use non-temporal loads.
-// N in {4, 8, 16, 32, 64}, d % 8 == 0, router weight fits in LDS.  grid = (workgroups, L).
+// N in {2, 4, 8, 16, 32, 64}, d % 8 == 0, router weight fits in LDS.  grid = (workgroups, L).
 // ------------------------------------------------------------------------------------------
 template <int N, bool NT>
 __device__ __forceinline__ void ring_load(uint4 (&r)[N], const uint16_t *base, int d, int col)
@@ -73,7 +73,8 @@ __global__ __launch_bounds__(WPB * 64) __attribute__((amdgpu_waves_per_eu(N <= 1
 void fwd_bf16_stream_kernel(FwdArgs a)
 {
     extern __shared__ uint4 smem[];
-    constexpr int LPJ = 64 / N;   // lanes per expert after the fold
+    constexpr int NR = N < 4 ? 4 : N;   // experts the router is computed for (N = 2 is padded to 4)
+    constexpr int LPJ = 64 / NR;        // lanes per expert after the fold
 #ifndef MOLE_FWD_HOLD_X
 #define MOLE_FWD_HOLD_X (N != 16 || !NTA)
 #endif
@@ -122,7 +123,7 @@ void fwd_bf16_stream_kernel(FwdArgs a)
     uint4 h0, h1;
     load_h2<NTA>(h0, h1, hbase + (int64_t)cur.t * d, d, lane);
 
-    fill_router_lds<N>(smem, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
+    fill_router_lds<NR, N>(smem, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
     __syncthreads();
 
     for (; item < n_items; item += stride) {
@@ -138,8 +139,8 @@ void fwd_bf16_stream_kernel(FwdArgs a)
         if (a.rows_dbg && layer == 0 && lane == 0 && reporter)
             a.rows_dbg[t] = valid ? row : -1;
 
-        const float g = router_gate<N, NTA, NORM>(smem, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1, a.ln_eps);
-        if (a.gates_dbg && reporter && (lane & (LPJ - 1)) == 0)
+        const float g = router_gate<NR, NTA, NORM, N>(smem, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1, a.ln_eps);
+        if (a.gates_dbg && reporter && (lane & (LPJ - 1)) == 0 && lane / LPJ < N)
             a.gates_dbg[((int64_t)layer * T + t) * N + lane / LPJ] = g;
         const uint4 x0 = h0, x1 = h1;                  // NORM: the residual of chunks 0 and 1
         // the next token's h goes in flight now; its latency hides behind this token's combine
@@ -367,7 +368,7 @@ int64_t grid_x(int items, int L, size_t lds)
 template <int N, int WPB, bool NTA, bool SPLIT, bool NORM>
 mole_status launch_fast(const FwdArgs &a, hipStream_t stream)
 {
-    const size_t lds = router_lds_bytes(a.d, N);
+    const size_t lds = router_lds_bytes(a.d, N < 4 ? 4 : N);
     static size_t attr_set = 0;
     if (lds > attr_set) {
         MOLE_HIP_CHECK(hipFuncSetAttribute(
@@ -463,10 +464,11 @@ mole_status forward_impl(const void *table, int64_t table_stride, const int32_t 
     a.T = T; a.d = d; a.N = N; a.L = L;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
-    const size_t lds_fast = router_lds_bytes(d, N);
+    const size_t lds_fast = router_lds_bytes(d, N < 4 ? 4 : N);
     const bool fast = dtype == MOLE_BF16 && lds_fast <= LDS_BYTES_PER_CU && !getenv("MOLE_FWD_GENERIC");
     if (fast) {
         switch (N) {
+        case 2: return launch_fast_n<2>(a, stream);
         case 4: return launch_fast_n<4>(a, stream);
         case 8: return launch_fast_n<8>(a, stream);
         case 16: return launch_fast_n<16>(a, stream);

@@ -133,6 +133,11 @@ CONFIGS: Dict[str, Workload] = {
     "prefill410m":    Workload("prefill410m", 50304, 1024, 32, 4096, 1, 16384, BF16, "zipf", 4),
     "prefill410m_uniform": Workload("prefill410m_uniform", 50304, 1024, 32, 4096, 1, 16384, BF16, "uniform", 4),
     "offload410m":    Workload("offload410m", 50304, 1024, 16, 4096, 24, 32, BF16, "zipf", 5),
+    # further shapes of the paper: the 1B model with 4 experts (model table) and the expert-count ablation
+    "decode1b_4e":    Workload("decode1b_4e", 50304, 2048, 4, 8192, 16, 256, BF16, "zipf", 6),
+    "decode410m_n2":  Workload("decode410m_n2", 50304, 1024, 2, 4096, 24, 256, BF16, "zipf", 7),
+    "decode410m_n4":  Workload("decode410m_n4", 50304, 1024, 4, 4096, 24, 256, BF16, "zipf", 7),
+    "decode410m_n8":  Workload("decode410m_n8", 50304, 1024, 8, 4096, 24, 256, BF16, "zipf", 7),
 }
 
 

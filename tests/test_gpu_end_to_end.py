@@ -66,6 +66,75 @@ def test_built_table_reproduces_the_training_form_layer(name, kw):
     np.testing.assert_allclose(ref2, ref, rtol=1e-5 if w.dtype == wl.F32 else 1e-10, atol=1e-6 if w.dtype == wl.F32 else 1e-12)
 
 
+def training_listing_layer(ew, x, ln_w, W_r, shared, ids, dtype, eps):
+    """The MoLE part of the training listing from the post-attention state, numpy fp64, one token at a
+    time: post-attention RMSNorm -> router softmax; RMSNorm of the embedding -> every expert FFN;
+    residual + shared + gate-weighted sum.  Two storage steps are part of the reference because the
+    output is a cancellation of terms of size ~10 and their rounding shows at atol 1e-3: expert outputs
+    are rounded to the table's storage type, and the norm weight times the router weight is rounded to
+    the storage type (that product is what mole_fold_router_norm stores)."""
+    f = lambda a: wl.storage_to_f64(a, dtype)
+    E, W1, W2, nw = f(ew["E"]), f(ew["W1"]), f(ew["W2"]), f(ew["norm_w"])
+    x, ln_w, W_r, shared = f(x), f(ln_w), f(W_r), f(shared)
+    W_rn = f(wl.to_storage(W_r * ln_w[:, None], dtype))
+    out = np.zeros_like(x)
+    for t in range(x.shape[0]):
+        g = scipy.special.softmax((x[t] / np.sqrt(np.mean(x[t] ** 2) + eps)) @ W_rn)
+        e = E[ids[t]]
+        e = e / np.sqrt(np.mean(e ** 2) + eps) * nw
+        out[t] = x[t] + shared[t]
+        for j in range(W1.shape[0]):
+            a = e @ W1[j]
+            v = (0.5 * a * (1.0 + scipy.special.erf(a / np.sqrt(2.0)))) @ W2[j]
+            out[t] += g[j] * wl.storage_to_f64(wl.to_storage(v, dtype), dtype)
+    return out
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("tiny", {}),
+    ("decode410m", dict(V=600, d=256, D=512, N=16, T=100, L=1)),
+    ("decode1b_4e", dict(V=300, D=256, T=40, L=1)),                      # d = 2048, N = 4
+    ("decode410m_n2", dict(V=300, d=128, D=256, T=40, L=1)),
+])
+def test_built_table_reproduces_the_training_listing_layer(name, kw):
+    """Both norms of the listing in play: the embedding norm inside mole_build_lut, the post-attention norm
+    (folded into the router weight) and the residual inside mole_layer_forward."""
+    import torch
+    eps = 1e-5
+    w = wl.scaled(wl.CONFIGS[name], **kw)
+    ew, li, ni, ids = wl.expert_weights(w, norm=True), wl.layer_inputs(w), wl.norm_inputs(w), wl.token_ids(w)
+    dv = {k: to_dev(v, w.dtype) for k, v in ew.items()}
+    lut = torch.empty((w.V, w.N, w.d), dtype=dv["E"].dtype, device="cuda")
+    ws = torch.empty((mb.mole_build_lut_workspace(w.V, w.d, w.D, w.N, DT[w.dtype]),), dtype=torch.uint8, device="cuda")
+    mb.mole_build_lut(dv["E"], dv["W1"], None, dv["W2"], None, dv["norm_w"], eps, lut, w.V, w.d, w.D, w.N,
+                      DT[w.dtype], mb.MOLE_GELU_ERF, ws)
+    ids_d = torch.from_numpy(ids).cuda()
+    x_d, lw_d, wr_d, sh_d = (to_dev(a, w.dtype) for a in (ni["x"], ni["ln_w"], li["W_r"], li["shared"]))
+    wrn_d = torch.empty_like(wr_d)
+    mb.mole_fold_router_norm(wr_d, lw_d, wrn_d, 1, w.d, w.N, DT[w.dtype])
+    out_d = torch.empty_like(x_d)
+    err_d = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    mb.mole_layer_forward(lut, 0, ids_d, None, x_d, eps, wrn_d, sh_d, out_d, 0, None, None, err_d, 1, w.T, w.V, w.d,
+                          w.N, DT[w.dtype])
+    torch.cuda.synchronize()
+    assert int(err_d.item()) == 0
+    got = wl.storage_to_f64(to_host(out_d, w.dtype), w.dtype)
+    ref = training_listing_layer(ew, ni["x"], ni["ln_w"], li["W_r"], li["shared"], ids, w.dtype, eps)
+    tab = wl.to_storage(oracle.build_lut(ew["E"], ew["W1"], ew["W2"], norm_w=ew["norm_w"], norm_eps=eps), w.dtype)
+    # The device builds its table with fp32 accumulation, so an entry can land on the neighbouring bf16
+    # value (relative 2^-8); the gates sum to one, so the routed term moves by at most that fraction of the
+    # largest looked-up entry.  Where residual, shared and routed terms cancel, only atol is left, hence
+    # the explicit allowance.
+    extra = 2.0 ** -8 * np.abs(wl.storage_to_f64(tab, w.dtype)[ids]).max() if w.dtype == wl.BF16 else 0.0
+    assert_close(got, ref, w.dtype, f"listing layer end to end ({w.name} {kw})", extra_atol=extra)
+    # and through the oracle's two steps, with its table stored in the same type
+    s64 = lambda a: wl.storage_to_f64(a, w.dtype)
+    W_rn = s64(wl.to_storage(s64(li["W_r"]) * s64(ni["ln_w"])[:, None], w.dtype))
+    ref2, *_ = oracle.layer_forward(tab, ids, s64(ni["x"]), np.ones(w.d), eps, W_rn, s64(li["shared"]))
+    np.testing.assert_allclose(ref2, ref, rtol=1e-5 if w.dtype == wl.F32 else 1e-10,
+                               atol=1e-5 if w.dtype == wl.F32 else 1e-11)
+
+
 def test_plan_with_slot_and_staging():
     """MOLE_FLAG_DEDUP together with slot = inv on a staging buffer of the distinct rows."""
     import torch

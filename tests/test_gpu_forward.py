@@ -81,6 +81,8 @@ def test_tiny_fp32_layer():
     (256, 8, 130, 512),
     (128, 64, 50, 300),
     (520, 16, 9, 64),          # d = 512 + 8: a chunk with a single active lane
+    (1024, 2, 70, 512),        # two experts: the router is padded to four, the extra gates must be exactly 0
+    (520, 2, 9, 64),
     (64, 1, 40, 100),          # generic path
     (1024, 5, 33, 256),        # generic path, N not a power of two
     (512, 12, 31, 256),
@@ -270,12 +272,15 @@ def _sampled_check(w, tab_d, ids, lis_d, out, layer, sample, torch):
 
 
 @pytest.mark.parametrize("name,dedup", [("prefill410m", False), ("prefill410m", True),
-                                        ("prefill410m_uniform", True), ("decode160m", False)])
+                                        ("prefill410m_uniform", True), ("decode160m", False),
+                                        ("decode1b_4e", False), ("decode1b_4e", True), ("decode410m_n2", False),
+                                        ("decode410m_n4", True), ("decode410m_n8", False)])
 def test_full_size_single_layer_sampled(name, dedup):
     torch = torch_mod()
     w = wl.CONFIGS[name]
     tab_d = wl.device_table(w, 0, "cuda")
-    assert tab_d.numel() * 2 > 2 ** 31 or name == "decode160m"       # byte offsets beyond 32 bits
+    if name.startswith("prefill"):
+        assert tab_d.numel() * 2 > 2 ** 31                           # byte offsets beyond 32 bits
     ids = wl.token_ids(w)
     li = wl.layer_inputs(w)
     got = run_forward(w, None, ids, li, dedup=dedup, table_dev=tab_d, want_dbg=True)

@@ -66,7 +66,7 @@ def check(w, table, ids, inp, shared=True, dedup=False, eps=EPS):
     (520, 16, 9, 64),          # a chunk with a single active lane
     (64, 1, 40, 100),          # generic kernel
     (1024, 5, 33, 256),        # generic kernel, N not a power of two
-    (1024, 2, 45, 256),        # generic kernel, the smallest expert count of the ablation
+    (1024, 2, 45, 256),        # the smallest expert count of the ablation (router padded to four)
 ])
 @pytest.mark.parametrize("dedup", [False, True])
 def test_bf16_shapes(d, N, T, V, dedup):
