@@ -73,8 +73,12 @@ int mole_version(void);
  * the training listing applies to embedding states).
  *   E [V,d] dev, W1 [N,d,D] dev, b1 [N,D] dev nullable, W2 [N,D,d] dev, b2 [N,d] dev nullable,
  *   norm_w [d] dev nullable, LUT [V,N,d] dev out.  d and D multiples of 16.
- * bf16: both GEMMs run on bf16 MFMA with fp32 accumulation; the hidden activation is carried
- * as a bf16 high/low pair so that its rounding does not show in the result.
+ * bf16: both GEMMs run on the matrix cores with fp32 accumulation.  The hidden activation is
+ * not rounded to bf16 (that would show in the result): it is carried in fp16, with W2 converted to
+ * fp16 (exact), whenever a bound computed on the device (max |x_v|_2 * max |W1 column|_2 +
+ * max |b1|, and max |W2|) proves that nothing can leave the fp16 range; otherwise as a bf16
+ * high/low pair at 1.5 x the matrix work.  The environment variable MOLE_BUILD_HIDDEN = f16 | split
+ * forces either (for experiments).
  * workspace: dev, at least mole_build_lut_workspace() bytes (holds the hidden activations of a
  * slab of vocabulary rows).  Returns MOLE_EWORKSPACE if it is smaller.
  * ---------------------------------------------------------------------------------------- */

@@ -11,8 +11,16 @@
 //                                                high part and a bf16 low part (two planes)
 //   GEMM 2:  A = [hi | lo] of GEMM1 B = W2_j     epilogue: + b2, round to bf16, stored
 //                                                straight into LUT[v, j, :] (row stride N*d)
-// Carrying the hidden activation as hi + lo makes its rounding error ~2^-17 instead of 2^-9,
-// so the only visible rounding is the final one; it costs a second pass over K in GEMM 2.
+// A bf16 hidden activation would carry a rounding error of 2^-9, which shows in the result (the
+// table's own final rounding is the only one the tolerance budgets for).  Two ways around it:
+//   * fp16 hidden activation (2^-12) and GEMM 2 on the fp16 MFMA with W2 converted to fp16 (exact:
+//     fp16 has the wider significand).  Used whenever it provably cannot overflow: a bound kernel
+//     computes max_v |x_v|_2 * max_col |W1 col|_2 + max |b1| >= every pre-activation (Cauchy-Schwarz),
+//     and |GELU(a)| <= |a|; the bound and max |W2| must stay below 60000.
+//   * otherwise the activation is carried as a bf16 high part plus a bf16 low part (2^-17) and GEMM 2
+//     runs over both planes: 1.5 x the MFMA work, no range limit.
+// The choice is taken on the device (no host synchronisation): both variants of each GEMM are
+// launched and the one whose mode is not selected returns at once.
 // Both weight matrices are first transposed into K-contiguous form so that A and B tiles are
 // fetched the same way (16-byte pieces along K) and match the MFMA operand layout directly.
 //
@@ -21,10 +29,14 @@
 // K tile prefetched into registers while the current one is multiplied.
 #include "mole_internal.h"
 
+#include <stdlib.h>
+#include <string.h>
+
 namespace {
 using namespace mole;
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // native vector: stays in registers
 
@@ -32,7 +44,9 @@ constexpr int BM = 256, BN = 128, BK = 64;
 constexpr int LDS_ROW = BK * 2 + 16;   // bytes per tile row in LDS
 constexpr int GEMM_THREADS = 256;
 
-enum { EPI_STORE = 0, EPI_GELU_SPLIT = 1 };
+enum { EPI_STORE = 0, EPI_GELU_SPLIT = 1, EPI_GELU_F16 = 2 };
+enum { MODE_F16 = 1, MODE_SPLIT = 2 };   // how the hidden activation is carried (chosen on the device)
+constexpr float F16_SAFE = 60000.0f;
 
 struct GemmArgs {
     const uint16_t *A;       // [planes][M, K] row-major, K contiguous
@@ -46,6 +60,8 @@ struct GemmArgs {
     int64_t ldc, c_plane_stride, c_batch_stride;
     int M, Nn, K;
     int epilogue, act;
+    const int *mode;         // nullable: run only if *mode == run_mode
+    int run_mode;
 };
 
 __device__ __forceinline__ float gelu_f(float x, int act)
@@ -123,12 +139,15 @@ __device__ __forceinline__ uint32_t rne_pair(float a, float b)
     return ra | rb;
 }
 
-template <int EPI>
+// F16: both operands hold fp16 (GEMM 2 of the fp16 mode), else bf16.
+template <int EPI, bool F16>
 __global__ __launch_bounds__(GEMM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void gemm_nt_bf16_kernel(GemmArgs g)
+void gemm_nt_kernel(GemmArgs g)
 {
     __shared__ __attribute__((aligned(16))) unsigned char As[BM * LDS_ROW];
     __shared__ __attribute__((aligned(16))) unsigned char Bs[BN * LDS_ROW];
+    if (g.mode && *g.mode != g.run_mode)
+        return;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -162,18 +181,26 @@ void gemm_nt_bf16_kernel(GemmArgs g)
             gemm_fetch(ra, rb, g, A, Bt, kt + 1, ktiles_per_plane, m0, n0, prow, pk);
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 af[4], bfr[2];
+            u32x4 af[4], bfr[2];
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                af[i] = *reinterpret_cast<const bf16x8 *>(As + (wm * 128 + i * 32 + frow) * LDS_ROW + ks * 32 + fk);
+                af[i] = *reinterpret_cast<const u32x4 *>(As + (wm * 128 + i * 32 + frow) * LDS_ROW + ks * 32 + fk);
 #pragma unroll
             for (int j = 0; j < 2; ++j)
-                bfr[j] = *reinterpret_cast<const bf16x8 *>(Bs + (wn * 64 + j * 32 + frow) * LDS_ROW + ks * 32 + fk);
+                bfr[j] = *reinterpret_cast<const u32x4 *>(Bs + (wn * 64 + j * 32 + frow) * LDS_ROW + ks * 32 + fk);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < 2; ++j) {
+                    if constexpr (F16)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, bfr[j]),
+                                                                           __builtin_bit_cast(f16x8, af[i]),
+                                                                           acc[i][j], 0, 0, 0);
+                    else
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bfr[j]),
+                                                                            __builtin_bit_cast(bf16x8, af[i]),
+                                                                            acc[i][j], 0, 0, 0);
+                }
         }
         __syncthreads();
     }
@@ -231,6 +258,19 @@ void gemm_nt_bf16_kernel(GemmArgs g)
                     lo2.y = rne_pair(lo[2], lo[3]);
                     *reinterpret_cast<uint2 *>(srow + cl * 2) = hi2;
                     *reinterpret_cast<uint2 *>(srow + CPLANE + cl * 2) = lo2;
+                } else if constexpr (EPI == EPI_GELU_F16) {
+                    uint16_t hb[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        // the mode was only selected if no value can reach the fp16 range limit; the
+                        // clamp keeps a violated assumption finite
+                        const float a = fminf(fmaxf(gelu_fast(v[e], g.act), -65504.0f), 65504.0f);
+                        hb[e] = __builtin_bit_cast(uint16_t, (_Float16)a);      // round to nearest even
+                    }
+                    uint2 o;
+                    o.x = (uint32_t)hb[0] | ((uint32_t)hb[1] << 16);
+                    o.y = (uint32_t)hb[2] | ((uint32_t)hb[3] << 16);
+                    *reinterpret_cast<uint2 *>(srow + cl * 2) = o;
                 } else {
                     uint2 o;
                     o.x = pack_bf16(v[0], v[1]);
@@ -258,9 +298,12 @@ void gemm_nt_bf16_kernel(GemmArgs g)
     }
 }
 
-// dst[b][c][r] = src[b][r][c]   (bf16, 32 x 32 tiles through LDS)
+// dst[b][c][r] = src[b][r][c]   (bf16, 32 x 32 tiles through LDS).  dst16 (nullable) receives the same
+// transposed matrix converted to fp16 (exact for |x| in [2^-14, 65504]; smaller values become fp16
+// subnormals, absolute error below 3e-8).
 __global__ __launch_bounds__(256) void transpose_kernel(const uint16_t *__restrict__ src,
-                                                         uint16_t *__restrict__ dst, int R, int Cn)
+                                                         uint16_t *__restrict__ dst,
+                                                         uint16_t *__restrict__ dst16, int R, int Cn)
 {
     __shared__ uint16_t tile[32][33];
     const int64_t base = (int64_t)blockIdx.z * R * Cn;
@@ -271,8 +314,73 @@ __global__ __launch_bounds__(256) void transpose_kernel(const uint16_t *__restri
             tile[i][tx] = src[base + (int64_t)(r0 + i) * Cn + c0 + tx];
     __syncthreads();
     for (int i = ty; i < 32; i += 8)
-        if (c0 + i < Cn && r0 + tx < R)
-            dst[base + (int64_t)(c0 + i) * R + r0 + tx] = tile[tx][i];
+        if (c0 + i < Cn && r0 + tx < R) {
+            const uint16_t x = tile[tx][i];
+            dst[base + (int64_t)(c0 + i) * R + r0 + tx] = x;
+            if (dst16)
+                dst16[base + (int64_t)(c0 + i) * R + r0 + tx] = __builtin_bit_cast(uint16_t, (_Float16)bf16_to_f32(x));
+        }
+}
+
+// ---- choice of the hidden-activation format -----------------------------------------------
+// bound[0] = max over rows of sum of squares (rows of X), bound[1] = the same for the rows of W1^T
+// (= columns of W1), bound[2] = max |b1|, bound[3] = max |W2|.  Non-negative floats order like their
+// bit patterns, so the maxima are taken with integer atomics.
+__global__ __launch_bounds__(64) void bound_clear_kernel(unsigned *bound)
+{
+    if (threadIdx.x < 8)
+        bound[threadIdx.x] = 0u;
+}
+
+__global__ __launch_bounds__(256) void row_sumsq_max_kernel(const uint16_t *__restrict__ M, int64_t rows, int cols,
+                                                             unsigned *out)
+{
+    const int lane = threadIdx.x & 63;
+    float best = 0.f;
+    for (int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); r < rows; r += (int64_t)gridDim.x * 4) {
+        float ss = 0.f;
+        for (int k = lane * 8; k < cols; k += 512) {          // cols is a multiple of 16
+            const uint4 v = *reinterpret_cast<const uint4 *>(M + r * cols + k);
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                ss = fmaf(bf16lo(w[e]), bf16lo(w[e]), ss);
+                ss = fmaf(bf16hi(w[e]), bf16hi(w[e]), ss);
+            }
+        }
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1)
+            ss += __shfl_xor(ss, o);
+        best = fmaxf(best, ss);                               // a NaN row leaves best unchanged or NaN
+        if (!(ss == ss))
+            best = INFINITY;
+    }
+    if (lane == 0)
+        atomicMax(out, __float_as_uint(best));
+}
+
+__global__ __launch_bounds__(256) void abs_max_kernel(const uint16_t *__restrict__ x, int64_t n, unsigned *out)
+{
+    float best = 0.f;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        const float v = fabsf(bf16_to_f32(x[i]));
+        best = v == v ? fmaxf(best, v) : INFINITY;
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1)
+        best = fmaxf(best, __shfl_xor(best, o));
+    if ((threadIdx.x & 63) == 0)
+        atomicMax(out, __float_as_uint(best));
+}
+
+__global__ __launch_bounds__(64) void choose_mode_kernel(const unsigned *bound, int *mode, int forced)
+{
+    if (threadIdx.x != 0)
+        return;
+    const float pre = sqrtf(__uint_as_float(bound[0])) * sqrtf(__uint_as_float(bound[1])) * 1.01f +
+                      __uint_as_float(bound[2]);
+    const bool safe = pre <= F16_SAFE && __uint_as_float(bound[3]) <= F16_SAFE;   // false for NaN / inf
+    *mode = forced ? forced : (safe ? MODE_F16 : MODE_SPLIT);
 }
 
 // RMSNorm of the embedding rows, written as a bf16 hi plane and a bf16 lo plane.  One wave per row.
@@ -387,7 +495,7 @@ inline bool mfma_shape(int64_t V, int d, int D, mole_dtype dt)
 }
 
 struct BuildWs {
-    size_t w1t, w2t, xn, hid, total;
+    size_t w1t, w2t, w2t16, xn, hid, ctl, total;
     int64_t slab;
 };
 
@@ -399,15 +507,30 @@ inline BuildWs build_ws(int64_t V, int d, int D, int N, mole_dtype dt)
     if (mfma_shape(V, d, D, dt)) {
         w.w1t = off; off += align256((size_t)N * d * D * 2);
         w.w2t = off; off += align256((size_t)N * d * D * 2);
+        w.w2t16 = off; off += align256((size_t)N * d * D * 2);           // W2^T as fp16
         w.xn = off;  off += align256((size_t)2 * V * d * 2);             // hi + lo planes (norm only)
-        w.hid = off; off += align256((size_t)N * 2 * w.slab * D * 2);    // hi + lo planes per expert
+        w.hid = off; off += align256((size_t)N * 2 * w.slab * D * 2);    // hi + lo planes per expert, or one fp16 plane
+        w.ctl = off; off += 256;                                         // bounds [8] and the chosen mode
     } else {
-        w.w1t = w.w2t = 0;
+        w.w1t = w.w2t = w.w2t16 = w.ctl = 0;
         w.xn = off;  off += align256((size_t)V * d * 4);
         w.hid = off; off += align256((size_t)w.slab * N * D * 4);
     }
     w.total = off;
     return w;
+}
+
+// MOLE_BUILD_HIDDEN=f16 | split forces the format of the hidden activation (for tests and experiments)
+inline int env_mode()
+{
+    const char *e = getenv("MOLE_BUILD_HIDDEN");
+    if (!e)
+        return 0;
+    if (!strcmp(e, "f16"))
+        return MODE_F16;
+    if (!strcmp(e, "split"))
+        return MODE_SPLIT;
+    return 0;
 }
 
 template <typename E>
@@ -436,14 +559,17 @@ mole_status build_mfma(const void *Em, const void *W1, const void *b1, const voi
                        const void *norm_w, float eps, void *LUT, int64_t V, int d, int D, int N, int act,
                        char *ws, const BuildWs &lay, hipStream_t st)
 {
-    uint16_t *w1t = reinterpret_cast<uint16_t *>(ws + lay.w1t);   // [N, D, d]
-    uint16_t *w2t = reinterpret_cast<uint16_t *>(ws + lay.w2t);   // [N, d, D]
+    uint16_t *w1t = reinterpret_cast<uint16_t *>(ws + lay.w1t);       // [N, D, d]
+    uint16_t *w2t = reinterpret_cast<uint16_t *>(ws + lay.w2t);       // [N, d, D]
+    uint16_t *w2t16 = reinterpret_cast<uint16_t *>(ws + lay.w2t16);   // [N, d, D] fp16
     uint16_t *xn = reinterpret_cast<uint16_t *>(ws + lay.xn);
-    uint16_t *hid = reinterpret_cast<uint16_t *>(ws + lay.hid);   // [N][2][slab, D]
+    uint16_t *hid = reinterpret_cast<uint16_t *>(ws + lay.hid);       // [N][2][slab, D] bf16 or [N][slab, D] fp16
+    unsigned *bound = reinterpret_cast<unsigned *>(ws + lay.ctl);
+    int *mode = reinterpret_cast<int *>(ws + lay.ctl) + 8;
     hipLaunchKernelGGL(transpose_kernel, dim3(D / 32, d / 32, N), dim3(256), 0, st,
-                       static_cast<const uint16_t *>(W1), w1t, d, D);
+                       static_cast<const uint16_t *>(W1), w1t, static_cast<uint16_t *>(nullptr), d, D);
     hipLaunchKernelGGL(transpose_kernel, dim3(d / 32, D / 32, N), dim3(256), 0, st,
-                       static_cast<const uint16_t *>(W2), w2t, D, d);
+                       static_cast<const uint16_t *>(W2), w2t, w2t16, D, d);
     const uint16_t *X = static_cast<const uint16_t *>(Em);
     int x_planes = 1;
     if (norm_w) {
@@ -452,25 +578,51 @@ mole_status build_mfma(const void *Em, const void *W1, const void *b1, const voi
         X = xn;
         x_planes = 2;
     }
+    // format of the hidden activation: fp16 if it provably cannot overflow, else bf16 hi + lo
+    const unsigned cap = (unsigned)num_cus() * 8;
+    hipLaunchKernelGGL(bound_clear_kernel, dim3(1), dim3(64), 0, st, bound);
+    hipLaunchKernelGGL(row_sumsq_max_kernel, dim3((unsigned)((V + 3) / 4 < cap ? (V + 3) / 4 : cap)), dim3(256), 0, st,
+                       X, V, d, bound + 0);
+    const int64_t w1rows = (int64_t)N * D;
+    hipLaunchKernelGGL(row_sumsq_max_kernel, dim3((unsigned)((w1rows + 3) / 4 < cap ? (w1rows + 3) / 4 : cap)),
+                       dim3(256), 0, st, w1t, w1rows, d, bound + 1);
+    if (b1)
+        hipLaunchKernelGGL(abs_max_kernel, dim3(64), dim3(256), 0, st, static_cast<const uint16_t *>(b1),
+                           (int64_t)N * D, bound + 2);
+    hipLaunchKernelGGL(abs_max_kernel, dim3(cap), dim3(256), 0, st, w2t, (int64_t)N * d * D, bound + 3);
+    hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(64), 0, st, bound, mode, env_mode());
     for (int64_t v0 = 0; v0 < V; v0 += lay.slab) {
         const int nv = (int)((V - v0) < lay.slab ? (V - v0) : lay.slab);
+        const dim3 grid1((nv + BM - 1) / BM, D / BN, N), grid2((nv + BM - 1) / BM, d / BN, N);
         GemmArgs g1;
         g1.A = X + v0 * d; g1.lda = d; g1.a_plane_stride = V * (int64_t)d; g1.a_batch_stride = 0;
         g1.a_planes = x_planes;
         g1.Bt = w1t; g1.ldb = d; g1.b_batch_stride = (int64_t)D * d;
         g1.bias = static_cast<const uint16_t *>(b1); g1.bias_batch_stride = D;
-        g1.C = hid; g1.ldc = D; g1.c_plane_stride = lay.slab * D; g1.c_batch_stride = 2 * lay.slab * D;
-        g1.M = nv; g1.Nn = D; g1.K = d; g1.epilogue = EPI_GELU_SPLIT; g1.act = act;
-        hipLaunchKernelGGL(gemm_nt_bf16_kernel<EPI_GELU_SPLIT>, dim3((nv + BM - 1) / BM, D / BN, N), dim3(GEMM_THREADS), 0, st, g1);
+        g1.C = hid; g1.ldc = D; g1.M = nv; g1.Nn = D; g1.K = d; g1.act = act; g1.mode = mode;
         GemmArgs g2;
-        g2.A = hid; g2.lda = D; g2.a_plane_stride = lay.slab * D; g2.a_batch_stride = 2 * lay.slab * D;
-        g2.a_planes = 2;
-        g2.Bt = w2t; g2.ldb = D; g2.b_batch_stride = (int64_t)d * D;
+        g2.lda = D; g2.ldb = D; g2.b_batch_stride = (int64_t)d * D;
+        g2.A = hid;
         g2.bias = static_cast<const uint16_t *>(b2); g2.bias_batch_stride = d;
         g2.C = static_cast<uint16_t *>(LUT) + v0 * N * d; g2.ldc = (int64_t)N * d; g2.c_plane_stride = 0;
         g2.c_batch_stride = d;
-        g2.M = nv; g2.Nn = d; g2.K = D; g2.epilogue = EPI_STORE; g2.act = act;
-        hipLaunchKernelGGL(gemm_nt_bf16_kernel<EPI_STORE>, dim3((nv + BM - 1) / BM, d / BN, N), dim3(GEMM_THREADS), 0, st, g2);
+        g2.M = nv; g2.Nn = d; g2.K = D; g2.epilogue = EPI_STORE; g2.act = act; g2.mode = mode;
+
+        // fp16 mode: one plane, GEMM 2 on the fp16 MFMA
+        g1.epilogue = EPI_GELU_F16; g1.run_mode = MODE_F16;
+        g1.c_plane_stride = 0; g1.c_batch_stride = lay.slab * D;
+        hipLaunchKernelGGL((gemm_nt_kernel<EPI_GELU_F16, false>), grid1, dim3(GEMM_THREADS), 0, st, g1);
+        g2.run_mode = MODE_F16; g2.Bt = w2t16; g2.a_planes = 1;
+        g2.a_plane_stride = 0; g2.a_batch_stride = lay.slab * D;
+        hipLaunchKernelGGL((gemm_nt_kernel<EPI_STORE, true>), grid2, dim3(GEMM_THREADS), 0, st, g2);
+
+        // split mode: bf16 hi and lo planes, GEMM 2 over both
+        g1.epilogue = EPI_GELU_SPLIT; g1.run_mode = MODE_SPLIT;
+        g1.c_plane_stride = lay.slab * D; g1.c_batch_stride = 2 * lay.slab * D;
+        hipLaunchKernelGGL((gemm_nt_kernel<EPI_GELU_SPLIT, false>), grid1, dim3(GEMM_THREADS), 0, st, g1);
+        g2.run_mode = MODE_SPLIT; g2.Bt = w2t; g2.a_planes = 2;
+        g2.a_plane_stride = lay.slab * D; g2.a_batch_stride = 2 * lay.slab * D;
+        hipLaunchKernelGGL((gemm_nt_kernel<EPI_STORE, false>), grid2, dim3(GEMM_THREADS), 0, st, g2);
     }
     MOLE_HIP_CHECK(hipGetLastError());
     return MOLE_OK;

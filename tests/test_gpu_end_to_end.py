@@ -59,9 +59,12 @@ def test_built_table_reproduces_the_training_form_layer(name, kw):
     assert int(err_d.item()) == 0
     got = wl.storage_to_f64(to_host(out_d, w.dtype), w.dtype)
     ref = training_form_layer(ew, li, ids, w.dtype)
-    assert_close(got, ref, w.dtype, f"end to end ({w.name} {kw})")
-    # the same through the oracle's two steps, with its table stored in the same type
     tab = wl.to_storage(oracle.build_lut(ew["E"], ew["W1"], ew["W2"]), w.dtype)
+    # one storage ulp of the largest looked-up entry on top of the forward tolerance: the device's entry
+    # may be the neighbouring bf16 value of the reference's (fp32 against fp64 accumulation of the build)
+    extra = 2.0 ** -8 * np.abs(wl.storage_to_f64(tab, w.dtype)[ids]).max() if w.dtype == wl.BF16 else 0.0
+    assert_close(got, ref, w.dtype, f"end to end ({w.name} {kw})", extra_atol=extra)
+    # the same through the oracle's two steps, with its table stored in the same type
     ref2, _, _, _ = oracle.lookup_forward(tab, ids, li["h"], li["W_r"], li["shared"])
     np.testing.assert_allclose(ref2, ref, rtol=1e-5 if w.dtype == wl.F32 else 1e-10, atol=1e-6 if w.dtype == wl.F32 else 1e-12)
 
