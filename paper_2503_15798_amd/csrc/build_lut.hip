@@ -298,15 +298,263 @@ void gemm_nt_kernel(GemmArgs g)
     }
 }
 
+constexpr int BM2 = 256, BN2 = 256, THREADS2 = 512;
+
+// ------------------------------------------------------------------------------------------
+// 256 x 256 tile fed by direct global -> LDS loads (global_load_lds_dwordx4, gfx950): no staging
+// registers, no ds_write.  A wave-wide load drops lane l's 16 bytes at LDS base + 16*l, i.e. 1 KiB
+// contiguous = 8 tile rows of 128 bytes (K step 64: every row segment is a whole 128-byte line; with
+// 64-byte segments the same L2 delivers a third less).  Rows are therefore unpadded, and bank
+// conflicts are avoided by a swizzle applied on the global side: slot s of row r holds K piece
+// s ^ ((r >> 1) & 7), so the 16 rows a fragment read touches per pass cover all 64 banks.
+// Two stages of 64 KiB: step kt + 1 travels while step kt is multiplied.  8 waves (2 x 4), each
+// 128 x 64 outputs, two per SIMD.
+// ------------------------------------------------------------------------------------------
+constexpr int ROW3 = BK * 2;                        // bytes per tile row (128)
+constexpr int STAGE3 = (BM2 + BN2) * ROW3;          // 64 KiB
+constexpr int NSTAGE3 = 2;
+constexpr size_t LDS3 = (size_t)NSTAGE3 * STAGE3;
+
+#define MOLE_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+
+template <int EPI, bool F16>
+__global__ __launch_bounds__(THREADS2) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void gemm_nt_kernel_v3(GemmArgs g)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem3[];
+    if (g.mode && *g.mode != g.run_mode)
+        return;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 2, wn = wave & 3;
+    const int m0 = blockIdx.x * BM2, n0 = blockIdx.y * BN2;
+    const int batch = blockIdx.z;
+    const uint16_t *A = g.A + batch * g.a_batch_stride;
+    const uint16_t *Bt = g.Bt + batch * g.b_batch_stride;
+
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                acc[i][j][e] = 0.f;
+
+    // feed: per K step the tile pair is 64 chunks of 8 rows (A: 0..31, B: 32..63); wave w moves
+    // A chunks w, w + 8, w + 16, w + 24 and the same B chunks.  Lane l of a chunk load: row l >> 3,
+    // slot l & 7.
+    const int rr = lane >> 3, slot = lane & 7;
+    const uint16_t *gp[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int chunk = wave + 8 * (i & 3);
+        const int row = chunk * 8 + rr;                        // row inside the tile
+        const int piece = slot ^ ((row >> 1) & 7);             // K piece this lane fetches
+        if (i < 4)   // rows past M are clamped: their products are never stored
+            gp[i] = A + (int64_t)min(m0 + row, g.M - 1) * g.lda + piece * 8;
+        else
+            gp[i] = Bt + (int64_t)(n0 + row) * g.ldb + piece * 8;
+    }
+    const int ktiles_per_plane = g.K / BK;
+    const int ktiles = ktiles_per_plane * g.a_planes;
+    // load i (0..7) of K step kt; the eight loads of a step are issued one at a time between groups of
+    // MFMAs: a burst of them right after the barrier keeps every wave of the workgroup waiting in the
+    // memory pipeline's queue, and nothing feeds the matrix pipe meanwhile (measured: the step then
+    // takes compute time plus load-issue time)
+    int64_t cur_aoff = 0, cur_kk = 0;
+    unsigned char *cur_stage = smem3;
+    auto begin_issue = [&](int kt) {
+        const int plane = kt / ktiles_per_plane;
+        cur_kk = (kt - plane * ktiles_per_plane) * BK;
+        cur_aoff = plane * g.a_plane_stride + cur_kk;
+        cur_stage = smem3 + (kt & (NSTAGE3 - 1)) * STAGE3 + wave * 1024;
+    };
+    auto issue_one = [&](int i) {
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void *)(gp[i] + (i < 4 ? cur_aoff : cur_kk)),
+            (__attribute__((address_space(3))) void *)(cur_stage + (i < 4 ? 0 : BM2 * ROW3) + (i & 3) * 8192), 16, 0, 0);
+    };
+
+    // fragment addressing: row frow of a 32-row block, K piece 2*ks + (lane >> 5), swizzled
+    const int frow = lane & 31, swz = (frow >> 1) & 7, hi = lane >> 5;
+    const int a_base = (wm * 128 + frow) * ROW3, b_base = (BM2 + wn * 64 + frow) * ROW3;
+    struct Frag {
+        u32x4 a[4], b[2];
+    };
+    auto load_frag = [&](Frag &f, const unsigned char *stage, int ks) {
+        const int koff = ((2 * ks + hi) ^ swz) * 16;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            f.a[i] = *reinterpret_cast<const u32x4 *>(stage + a_base + i * 32 * ROW3 + koff);
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            f.b[j] = *reinterpret_cast<const u32x4 *>(stage + b_base + j * 32 * ROW3 + koff);
+    };
+    // four MFMAs: A blocks i0, i0 + 1 against both B blocks
+    auto multiply2 = [&](const Frag &f, int i0) {
+#pragma unroll
+        for (int i = i0; i < i0 + 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                if constexpr (F16)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, f.b[j]),
+                                                                       __builtin_bit_cast(f16x8, f.a[i]),
+                                                                       acc[i][j], 0, 0, 0);
+                else
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.b[j]),
+                                                                        __builtin_bit_cast(bf16x8, f.a[i]),
+                                                                        acc[i][j], 0, 0, 0);
+            }
+    };
+
+    begin_issue(0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        issue_one(i);
+    for (int kt = 0; kt < ktiles; ++kt) {
+        // Step kt has landed for this thread once nothing is outstanding (the next step is issued
+        // below); the barrier extends that to every thread's loads and also says that nobody reads
+        // the other stage any more.  A bare barrier: __syncthreads() adds fences the explicit waits
+        // make unnecessary.
+        MOLE_WAIT_VMCNT(0);
+        __builtin_amdgcn_s_barrier();
+#ifdef MOLE_EXP_NOLOAD
+        const bool more = false;
+#else
+        const bool more = kt + 1 < ktiles;
+#endif
+        if (more)
+            begin_issue(kt + 1);
+        const unsigned char *stage = smem3 + (kt & (NSTAGE3 - 1)) * STAGE3;
+        // Order of the step (kept by the scheduling barriers; left alone the compiler re-sorts the
+        // region to save registers): fragments of slice ks + 1 are requested before slice ks is
+        // multiplied, and one load of the next step goes out per group of four MFMAs.
+#define MOLE_STEP(LOADI, FRAG, I0)             \
+        if (more)                              \
+            issue_one(LOADI);                  \
+        __builtin_amdgcn_sched_barrier(0);     \
+        multiply2(FRAG, I0);                   \
+        __builtin_amdgcn_sched_barrier(0);
+        Frag f0, f1;
+        load_frag(f0, stage, 0);
+        load_frag(f1, stage, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        MOLE_STEP(0, f0, 0)
+        MOLE_STEP(1, f0, 2)
+        load_frag(f0, stage, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        MOLE_STEP(2, f1, 0)
+        MOLE_STEP(3, f1, 2)
+        load_frag(f1, stage, 3);
+        __builtin_amdgcn_sched_barrier(0);
+        MOLE_STEP(4, f0, 0)
+        MOLE_STEP(5, f0, 2)
+        MOLE_STEP(6, f1, 0)
+        MOLE_STEP(7, f1, 2)
+#undef MOLE_STEP
+        __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0): this wave's LDS reads of the stage are complete
+    }
+    __syncthreads();
+
+    // Epilogue: as in the 256 x 128 kernel (accumulator layout, staging through LDS, 16-byte stores),
+    // four passes of 64 rows (32 from each wave row) by 256 columns.
+    const uint16_t *bias = g.bias ? g.bias + batch * g.bias_batch_stride : nullptr;
+    uint16_t *C = g.C + batch * g.c_batch_stride;
+    constexpr int CROW = BN2 * 2 + 8;
+    constexpr int CPLANE = 64 * CROW;
+    static_assert(2 * CPLANE <= (int)LDS3, "epilogue staging must fit in the operand stages");
+    unsigned char *Cs = smem3;
+    float bv[2][4][4];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int col = n0 + wn * 64 + j * 32 + 8 * q + 4 * (lane >> 5);
+            uint2 b4 = make_uint2(0, 0);
+            if (bias)
+                b4 = *reinterpret_cast<const uint2 *>(bias + col);
+            bv[j][q][0] = bf16lo(b4.x); bv[j][q][1] = bf16hi(b4.x);
+            bv[j][q][2] = bf16lo(b4.y); bv[j][q][3] = bf16hi(b4.y);
+        }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        unsigned char *srow = Cs + (wm * 32 + (lane & 31)) * CROW;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int cl = wn * 64 + j * 32 + 8 * q + 4 * (lane >> 5);
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    v[e] = acc[i][j][4 * q + e] + bv[j][q][e];
+                if constexpr (EPI == EPI_GELU_SPLIT) {
+                    float lo[4];
+                    uint32_t hbits[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        v[e] = gelu_fast(v[e], g.act);
+                        const uint32_t u = __float_as_uint(v[e]);
+                        hbits[e] = (u + 0x7fffu + ((u >> 16) & 1u)) & 0xffff0000u;
+                        lo[e] = v[e] - __uint_as_float(hbits[e]);
+                    }
+                    uint2 hi2, lo2;
+                    hi2.x = (hbits[0] >> 16) | hbits[1];
+                    hi2.y = (hbits[2] >> 16) | hbits[3];
+                    lo2.x = rne_pair(lo[0], lo[1]);
+                    lo2.y = rne_pair(lo[2], lo[3]);
+                    *reinterpret_cast<uint2 *>(srow + cl * 2) = hi2;
+                    *reinterpret_cast<uint2 *>(srow + CPLANE + cl * 2) = lo2;
+                } else if constexpr (EPI == EPI_GELU_F16) {
+                    uint16_t hb[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float a = fminf(fmaxf(gelu_fast(v[e], g.act), -65504.0f), 65504.0f);
+                        hb[e] = __builtin_bit_cast(uint16_t, (_Float16)a);
+                    }
+                    uint2 o;
+                    o.x = (uint32_t)hb[0] | ((uint32_t)hb[1] << 16);
+                    o.y = (uint32_t)hb[2] | ((uint32_t)hb[3] << 16);
+                    *reinterpret_cast<uint2 *>(srow + cl * 2) = o;
+                } else {
+                    uint2 o;
+                    o.x = pack_bf16(v[0], v[1]);
+                    o.y = pack_bf16(v[2], v[3]);
+                    *reinterpret_cast<uint2 *>(srow + cl * 2) = o;
+                }
+            }
+        }
+        __syncthreads();
+        // write out: 64 rows x 512 bytes per plane = 2048 16-byte pieces, 4 per thread and plane
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int piece = tid + u * THREADS2;
+            const int sr = piece >> 5, sc = piece & 31;
+            const int row = m0 + (sr >> 5) * 128 + i * 32 + (sr & 31);
+            if (row < g.M) {
+                uint16_t *cp = C + (int64_t)row * g.ldc + n0 + sc * 8;
+                *reinterpret_cast<u32x4 *>(cp) = *reinterpret_cast<const u32x4 *>(Cs + sr * CROW + sc * 16);
+                if constexpr (EPI == EPI_GELU_SPLIT)
+                    *reinterpret_cast<u32x4 *>(cp + g.c_plane_stride) =
+                        *reinterpret_cast<const u32x4 *>(Cs + CPLANE + sr * CROW + sc * 16);
+            }
+        }
+        __syncthreads();
+    }
+}
+
 // dst[b][c][r] = src[b][r][c]   (bf16, 32 x 32 tiles through LDS).  dst16 (nullable) receives the same
 // transposed matrix converted to fp16 (exact for |x| in [2^-14, 65504]; smaller values become fp16
 // subnormals, absolute error below 3e-8).
 __global__ __launch_bounds__(256) void transpose_kernel(const uint16_t *__restrict__ src,
                                                          uint16_t *__restrict__ dst,
-                                                         uint16_t *__restrict__ dst16, int R, int Cn)
+                                                         uint16_t *__restrict__ dst16, int R, int Cn, int dst_ld)
 {
     __shared__ uint16_t tile[32][33];
     const int64_t base = (int64_t)blockIdx.z * R * Cn;
+    const int64_t dbase = (int64_t)blockIdx.z * Cn * dst_ld;     // dst rows (Cn of them) are dst_ld apart
     const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
     for (int i = ty; i < 32; i += 8)
@@ -316,9 +564,9 @@ __global__ __launch_bounds__(256) void transpose_kernel(const uint16_t *__restri
     for (int i = ty; i < 32; i += 8)
         if (c0 + i < Cn && r0 + tx < R) {
             const uint16_t x = tile[tx][i];
-            dst[base + (int64_t)(c0 + i) * R + r0 + tx] = x;
+            dst[dbase + (int64_t)(c0 + i) * dst_ld + r0 + tx] = x;
             if (dst16)
-                dst16[base + (int64_t)(c0 + i) * R + r0 + tx] = __builtin_bit_cast(uint16_t, (_Float16)bf16_to_f32(x));
+                dst16[dbase + (int64_t)(c0 + i) * dst_ld + r0 + tx] = __builtin_bit_cast(uint16_t, (_Float16)bf16_to_f32(x));
         }
 }
 
@@ -333,14 +581,14 @@ __global__ __launch_bounds__(64) void bound_clear_kernel(unsigned *bound)
 }
 
 __global__ __launch_bounds__(256) void row_sumsq_max_kernel(const uint16_t *__restrict__ M, int64_t rows, int cols,
-                                                             unsigned *out)
+                                                             int ld, unsigned *out)
 {
     const int lane = threadIdx.x & 63;
     float best = 0.f;
     for (int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); r < rows; r += (int64_t)gridDim.x * 4) {
         float ss = 0.f;
         for (int k = lane * 8; k < cols; k += 512) {          // cols is a multiple of 16
-            const uint4 v = *reinterpret_cast<const uint4 *>(M + r * cols + k);
+            const uint4 v = *reinterpret_cast<const uint4 *>(M + r * ld + k);
             const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -494,6 +742,11 @@ inline bool mfma_shape(int64_t V, int d, int D, mole_dtype dt)
     return dt == MOLE_BF16 && d % BN == 0 && D % BN == 0 && d % BK == 0 && D % BK == 0;
 }
 
+// Rows of the K-contiguous operands the library lays out itself are padded by 128 bytes: with a
+// power-of-two row stride every row of a tile starts in the same L2 channel, and because all workgroups
+// walk K in step the whole chip would queue on one or two channels at a time.
+constexpr int LD_PAD = 64;   // elements
+
 struct BuildWs {
     size_t w1t, w2t, w2t16, xn, hid, ctl, total;
     int64_t slab;
@@ -505,11 +758,11 @@ inline BuildWs build_ws(int64_t V, int d, int D, int N, mole_dtype dt)
     w.slab = V < SLAB_ROWS ? V : SLAB_ROWS;
     size_t off = 0;
     if (mfma_shape(V, d, D, dt)) {
-        w.w1t = off; off += align256((size_t)N * d * D * 2);
-        w.w2t = off; off += align256((size_t)N * d * D * 2);
-        w.w2t16 = off; off += align256((size_t)N * d * D * 2);           // W2^T as fp16
-        w.xn = off;  off += align256((size_t)2 * V * d * 2);             // hi + lo planes (norm only)
-        w.hid = off; off += align256((size_t)N * 2 * w.slab * D * 2);    // hi + lo planes per expert, or one fp16 plane
+        w.w1t = off; off += align256((size_t)N * D * (d + LD_PAD) * 2);
+        w.w2t = off; off += align256((size_t)N * d * (D + LD_PAD) * 2);
+        w.w2t16 = off; off += align256((size_t)N * d * (D + LD_PAD) * 2);          // W2^T as fp16
+        w.xn = off;  off += align256((size_t)2 * V * d * 2);                       // hi + lo planes (norm only)
+        w.hid = off; off += align256((size_t)N * 2 * w.slab * (D + LD_PAD) * 2);   // hi + lo planes per expert, or one fp16 plane
         w.ctl = off; off += 256;                                         // bounds [8] and the chosen mode
     } else {
         w.w1t = w.w2t = w.w2t16 = w.ctl = 0;
@@ -555,6 +808,27 @@ mole_status build_plain(const void *Em, const void *W1, const void *b1, const vo
     return MOLE_OK;
 }
 
+// launch one GEMM: the 256 x 256 direct-to-LDS kernel when the column count allows, else the 256 x 128 one
+template <int EPI, bool F16>
+mole_status launch_gemm(const GemmArgs &g, int batches, hipStream_t st)
+{
+    const bool big = g.Nn % BN2 == 0 && !getenv("MOLE_BUILD_SMALL_TILE");
+    if (big) {
+        static bool attr3_set = false;
+        if (!attr3_set) {
+            MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_nt_kernel_v3<EPI, F16>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS3));
+            attr3_set = true;
+        }
+        hipLaunchKernelGGL((gemm_nt_kernel_v3<EPI, F16>), dim3((g.M + BM2 - 1) / BM2, g.Nn / BN2, batches),
+                           dim3(THREADS2), LDS3, st, g);
+    } else {
+        hipLaunchKernelGGL((gemm_nt_kernel<EPI, F16>), dim3((g.M + BM - 1) / BM, g.Nn / BN, batches),
+                           dim3(GEMM_THREADS), 0, st, g);
+    }
+    return MOLE_OK;
+}
+
 mole_status build_mfma(const void *Em, const void *W1, const void *b1, const void *W2, const void *b2,
                        const void *norm_w, float eps, void *LUT, int64_t V, int d, int D, int N, int act,
                        char *ws, const BuildWs &lay, hipStream_t st)
@@ -566,10 +840,11 @@ mole_status build_mfma(const void *Em, const void *W1, const void *b1, const voi
     uint16_t *hid = reinterpret_cast<uint16_t *>(ws + lay.hid);       // [N][2][slab, D] bf16 or [N][slab, D] fp16
     unsigned *bound = reinterpret_cast<unsigned *>(ws + lay.ctl);
     int *mode = reinterpret_cast<int *>(ws + lay.ctl) + 8;
+    const int ldw1 = d + LD_PAD, ldh = D + LD_PAD;      // row strides of W1^T, and of W2^T and the hidden planes
     hipLaunchKernelGGL(transpose_kernel, dim3(D / 32, d / 32, N), dim3(256), 0, st,
-                       static_cast<const uint16_t *>(W1), w1t, static_cast<uint16_t *>(nullptr), d, D);
+                       static_cast<const uint16_t *>(W1), w1t, static_cast<uint16_t *>(nullptr), d, D, ldw1);
     hipLaunchKernelGGL(transpose_kernel, dim3(d / 32, D / 32, N), dim3(256), 0, st,
-                       static_cast<const uint16_t *>(W2), w2t, w2t16, D, d);
+                       static_cast<const uint16_t *>(W2), w2t, w2t16, D, d, ldh);
     const uint16_t *X = static_cast<const uint16_t *>(Em);
     int x_planes = 1;
     if (norm_w) {
@@ -582,26 +857,26 @@ mole_status build_mfma(const void *Em, const void *W1, const void *b1, const voi
     const unsigned cap = (unsigned)num_cus() * 8;
     hipLaunchKernelGGL(bound_clear_kernel, dim3(1), dim3(64), 0, st, bound);
     hipLaunchKernelGGL(row_sumsq_max_kernel, dim3((unsigned)((V + 3) / 4 < cap ? (V + 3) / 4 : cap)), dim3(256), 0, st,
-                       X, V, d, bound + 0);
+                       X, V, d, d, bound + 0);
     const int64_t w1rows = (int64_t)N * D;
     hipLaunchKernelGGL(row_sumsq_max_kernel, dim3((unsigned)((w1rows + 3) / 4 < cap ? (w1rows + 3) / 4 : cap)),
-                       dim3(256), 0, st, w1t, w1rows, d, bound + 1);
+                       dim3(256), 0, st, w1t, w1rows, d, ldw1, bound + 1);
     if (b1)
         hipLaunchKernelGGL(abs_max_kernel, dim3(64), dim3(256), 0, st, static_cast<const uint16_t *>(b1),
                            (int64_t)N * D, bound + 2);
-    hipLaunchKernelGGL(abs_max_kernel, dim3(cap), dim3(256), 0, st, w2t, (int64_t)N * d * D, bound + 3);
+    hipLaunchKernelGGL(abs_max_kernel, dim3(cap), dim3(256), 0, st, static_cast<const uint16_t *>(W2),
+                       (int64_t)N * d * D, bound + 3);
     hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(64), 0, st, bound, mode, env_mode());
     for (int64_t v0 = 0; v0 < V; v0 += lay.slab) {
         const int nv = (int)((V - v0) < lay.slab ? (V - v0) : lay.slab);
-        const dim3 grid1((nv + BM - 1) / BM, D / BN, N), grid2((nv + BM - 1) / BM, d / BN, N);
         GemmArgs g1;
         g1.A = X + v0 * d; g1.lda = d; g1.a_plane_stride = V * (int64_t)d; g1.a_batch_stride = 0;
         g1.a_planes = x_planes;
-        g1.Bt = w1t; g1.ldb = d; g1.b_batch_stride = (int64_t)D * d;
+        g1.Bt = w1t; g1.ldb = ldw1; g1.b_batch_stride = (int64_t)D * ldw1;
         g1.bias = static_cast<const uint16_t *>(b1); g1.bias_batch_stride = D;
-        g1.C = hid; g1.ldc = D; g1.M = nv; g1.Nn = D; g1.K = d; g1.act = act; g1.mode = mode;
+        g1.C = hid; g1.ldc = ldh; g1.M = nv; g1.Nn = D; g1.K = d; g1.act = act; g1.mode = mode;
         GemmArgs g2;
-        g2.lda = D; g2.ldb = D; g2.b_batch_stride = (int64_t)d * D;
+        g2.lda = ldh; g2.ldb = ldh; g2.b_batch_stride = (int64_t)d * ldh;
         g2.A = hid;
         g2.bias = static_cast<const uint16_t *>(b2); g2.bias_batch_stride = d;
         g2.C = static_cast<uint16_t *>(LUT) + v0 * N * d; g2.ldc = (int64_t)N * d; g2.c_plane_stride = 0;
@@ -610,19 +885,23 @@ mole_status build_mfma(const void *Em, const void *W1, const void *b1, const voi
 
         // fp16 mode: one plane, GEMM 2 on the fp16 MFMA
         g1.epilogue = EPI_GELU_F16; g1.run_mode = MODE_F16;
-        g1.c_plane_stride = 0; g1.c_batch_stride = lay.slab * D;
-        hipLaunchKernelGGL((gemm_nt_kernel<EPI_GELU_F16, false>), grid1, dim3(GEMM_THREADS), 0, st, g1);
+        g1.c_plane_stride = 0; g1.c_batch_stride = lay.slab * ldh;
+        if (mole_status e = launch_gemm<EPI_GELU_F16, false>(g1, N, st))
+            return e;
         g2.run_mode = MODE_F16; g2.Bt = w2t16; g2.a_planes = 1;
-        g2.a_plane_stride = 0; g2.a_batch_stride = lay.slab * D;
-        hipLaunchKernelGGL((gemm_nt_kernel<EPI_STORE, true>), grid2, dim3(GEMM_THREADS), 0, st, g2);
+        g2.a_plane_stride = 0; g2.a_batch_stride = lay.slab * ldh;
+        if (mole_status e = launch_gemm<EPI_STORE, true>(g2, N, st))
+            return e;
 
         // split mode: bf16 hi and lo planes, GEMM 2 over both
         g1.epilogue = EPI_GELU_SPLIT; g1.run_mode = MODE_SPLIT;
-        g1.c_plane_stride = lay.slab * D; g1.c_batch_stride = 2 * lay.slab * D;
-        hipLaunchKernelGGL((gemm_nt_kernel<EPI_GELU_SPLIT, false>), grid1, dim3(GEMM_THREADS), 0, st, g1);
+        g1.c_plane_stride = lay.slab * ldh; g1.c_batch_stride = 2 * lay.slab * ldh;
+        if (mole_status e = launch_gemm<EPI_GELU_SPLIT, false>(g1, N, st))
+            return e;
         g2.run_mode = MODE_SPLIT; g2.Bt = w2t; g2.a_planes = 2;
-        g2.a_plane_stride = lay.slab * D; g2.a_batch_stride = 2 * lay.slab * D;
-        hipLaunchKernelGGL((gemm_nt_kernel<EPI_STORE, false>), grid2, dim3(GEMM_THREADS), 0, st, g2);
+        g2.a_plane_stride = lay.slab * ldh; g2.a_batch_stride = 2 * lay.slab * ldh;
+        if (mole_status e = launch_gemm<EPI_STORE, false>(g2, N, st))
+            return e;
     }
     MOLE_HIP_CHECK(hipGetLastError());
     return MOLE_OK;

@@ -82,6 +82,75 @@ __global__ __launch_bounds__(256) void pattern(const uint4 *__restrict__ tab, co
         *sink = acc;
 }
 
+// The same row traffic through direct global -> LDS loads (global_load_lds_dwordx4): a wave-wide load
+// drops 1 KiB (one 512-column chunk of one row) into the wave's LDS buffer; the N rows of a chunk are then
+// read back from LDS.  BUFS = 2: the next chunk travels while the current one is read.
+template <int N, int WPB, int BUFS, int MIX>
+__global__ __launch_bounds__(WPB * 64) void pattern_dma(const uint4 *__restrict__ tab, const int *__restrict__ rows,
+                                                        int T, const uint4 *__restrict__ h,
+                                                        const uint4 *__restrict__ sh, uint4 *__restrict__ out,
+                                                        uint32_t *sink)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int wib = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = blockIdx.x * WPB + wib;
+    const int nw = gridDim.x * WPB;
+    unsigned char *buf = lds + (size_t)wib * BUFS * N * 1024;
+    auto issue = [&](int t, int c, int b) {
+        const uint4 *q = tab + (size_t)rows[t] * (N * 128) + c * 64 + lane;
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(q + j * 128),
+                                             (__attribute__((address_space(3))) void *)(buf + (b * N + j) * 1024),
+                                             16, 0, 0);
+    };
+    uint32_t acc = 0;
+    int item = 0;                       // chunks processed by this wave (selects the buffer)
+    if (BUFS == 2 && wave < T)
+        issue(wave, 0, 0);
+    for (int t = wave; t < T; t += nw) {
+        uint4 hv0 = make_uint4(0, 0, 0, 0), hv1 = hv0;
+        if (MIX & LOAD_H) {
+            hv0 = ld(h + (size_t)t * 128 + lane, MIX & NT_ACT);
+            hv1 = ld(h + (size_t)t * 128 + 64 + lane, MIX & NT_ACT);
+        }
+        for (int c = 0; c < 2; ++c, ++item) {
+            const int b = BUFS == 2 ? (item & 1) : 0;
+            uint4 s0 = make_uint4(0, 0, 0, 0);
+            if (MIX & LOAD_SHARED)
+                s0 = ld(sh + (size_t)t * 128 + c * 64 + lane, MIX & NT_ACT);
+            if (BUFS == 2) {
+                // next chunk (or the next token's first chunk) into the other buffer
+                const int tn = c == 0 ? t : t + nw, cn = c == 0 ? 1 : 0;
+                if (tn < T)
+                    issue(tn, cn, b ^ 1);
+                // the loads issued before those N (and the activation loads) have landed
+                if (tn < T)
+                    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+                else
+                    __builtin_amdgcn_s_waitcnt(0x0F70);
+            } else {
+                issue(t, c, 0);
+                __builtin_amdgcn_s_waitcnt(0x0F70);
+            }
+#pragma unroll
+            for (int j = 0; j < N; ++j) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(buf + (b * N + j) * 1024 + lane * 16);
+                acc ^= v.x ^ v.y ^ v.z ^ v.w;
+            }
+            __builtin_amdgcn_s_waitcnt(0xC07F);      // LDS reads done before the buffer is refilled
+            uint4 o = s0;
+            o.x ^= acc ^ hv0.x ^ hv1.y;
+            if (MIX & STORE_OUT)
+                st(out + (size_t)t * 128 + c * 64 + lane, o, MIX & NT_STORE);
+            else
+                acc += s0.y ^ hv0.z ^ hv1.w;
+        }
+    }
+    if (acc == 0x12345678u)
+        *sink = acc;
+}
+
 __global__ void stream_read(const uint4 *__restrict__ p, size_t n16, uint32_t *sink)
 {
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -171,6 +240,21 @@ void run(const uint4 *tab, size_t bytes, uint32_t *sink)
     RUN(LOAD_H | LOAD_SHARED | STORE_OUT | NT_STORE | NT_ACT, rb + 3 * a1, "full mix, non-temporal store and act loads")
     RUN(LOAD_H | LOAD_SHARED | STORE_OUT | NT_STORE | NT_ACT | NT_ROWS, rb + 3 * a1, "full mix, everything non-temporal")
 #undef RUN
+#define RUND(WPB, BUFS, MIX, BYTES, NAME)                                                          \
+    {                                                                                               \
+        const size_t lds = (size_t)WPB * BUFS * N * 1024;                                           \
+        CK(hipFuncSetAttribute(reinterpret_cast<const void *>(&pattern_dma<N, WPB, BUFS, MIX>),      \
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));              \
+        const int gd = 256 * (int)(160 * 1024 / lds);                                               \
+        const float us = time_us([&] { pattern_dma<N, WPB, BUFS, MIX><<<gd, WPB * 64, lds>>>(tab, drows, T, h, sh, out, sink); }, 10); \
+        printf("  %-44s %8.1f us  %5.2f TB/s\n", NAME, us, (BYTES) / us / 1e6);                     \
+    }
+    constexpr int W1 = 128 / N, W2 = 64 / N;    // waves per workgroup so that the buffers take 128 KiB
+    RUND(W1, 1, 0, rb, "to LDS, one buffer per wave: rows only")
+    RUND(W2, 2, 0, rb, "to LDS, two buffers per wave: rows only")
+    RUND(W1, 1, LOAD_H | LOAD_SHARED | STORE_OUT | NT_STORE | NT_ACT, rb + 3 * a1, "to LDS, one buffer: full mix, NT store + act")
+    RUND(W2, 2, LOAD_H | LOAD_SHARED | STORE_OUT | NT_STORE | NT_ACT, rb + 3 * a1, "to LDS, two buffers: full mix, NT store + act")
+#undef RUND
     CK(hipFree(drows));
     CK(hipFree(h));
     CK(hipFree(sh));
