@@ -1,15 +1,14 @@
 // mole_build_lut: the re-parameterization LUT[v, j, :] = FFN_j(Embedding(v)).
 //
-// Paper: Sec. 3.3, LUT entry equation ("a single forward pass with the embedding layer's
-// weights as the input"), with the expert taken as a two-matrix FFN (Sec. 3.4: 4dD flops,
-// 2dD parameters) and GELU; optionally the RMSNorm the training listing applies to the
-// embedding states first.
+// Paper: Sec. 3.3, LUT entry equation (the experts are run once over every row of the embedding
+// matrix), with the expert taken as a two-matrix FFN (Sec. 3.4: 4dD flops, 2dD parameters) and
+// GELU; optionally the RMSNorm the training listing applies to the embedding states first.
 //
 // This is the one dense contraction of the library (4*V*d*D*N flop, 1.35e13 for one 410M
 // layer), so it runs on the matrix cores: v_mfma_f32_32x32x16_bf16, fp32 accumulation.
-//   GEMM 1:  A = E[v, :]           B = W1_j     epilogue: + b1, GELU, split into a bf16
-//                                                high part and a bf16 low part (two planes)
-//   GEMM 2:  A = [hi | lo] of GEMM1 B = W2_j     epilogue: + b2, round to bf16, stored
+//   GEMM 1:  A = E[v, :]           B = W1_j     epilogue: + b1, GELU, stored as one fp16 plane
+//                                                (or a bf16 high and a bf16 low plane, see below)
+//   GEMM 2:  A = hidden of GEMM 1   B = W2_j     epilogue: + b2, round to bf16, stored
 //                                                straight into LUT[v, j, :] (row stride N*d)
 // A bf16 hidden activation would carry a rounding error of 2^-9, which shows in the result (the
 // table's own final rounding is the only one the tolerance budgets for).  Two ways around it:
@@ -24,9 +23,11 @@
 // Both weight matrices are first transposed into K-contiguous form so that A and B tiles are
 // fetched the same way (16-byte pieces along K) and match the MFMA operand layout directly.
 //
-// Tile: 256 x 128 per workgroup of 4 waves (2 x 2), each wave 128 x 64 = 4 x 2 MFMA tiles,
-// K step 64 through LDS with 16 bytes of row padding (conflict-free 16-byte reads), next
-// K tile prefetched into registers while the current one is multiplied.
+// Two GEMM kernels.  Column counts that are multiples of 256 take the 256 x 256 kernel fed by direct
+// global -> LDS loads (described at gemm_nt_kernel_v3).  Other shapes take the 256 x 128 kernel below:
+// workgroup of 4 waves (2 x 2), each wave 128 x 64 = 4 x 2 MFMA tiles, K step 64 through LDS with 16
+// bytes of row padding (conflict-free 16-byte reads), next K tile prefetched into registers while the
+// current one is multiplied.
 #include "mole_internal.h"
 
 #include <stdlib.h>
@@ -420,11 +421,7 @@ void gemm_nt_kernel_v3(GemmArgs g)
         // make unnecessary.
         MOLE_WAIT_VMCNT(0);
         __builtin_amdgcn_s_barrier();
-#ifdef MOLE_EXP_NOLOAD
-        const bool more = false;
-#else
         const bool more = kt + 1 < ktiles;
-#endif
         if (more)
             begin_issue(kt + 1);
         const unsigned char *stage = smem3 + (kt & (NSTAGE3 - 1)) * STAGE3;
