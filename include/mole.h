@@ -210,7 +210,8 @@ mole_status mole_offload_fetch_idmajor(const void *host_table,
  * ("MOLELUT\0", u32 version = 1, u32 header bytes, u32 dtype, u32 layout, i64 V, i32 L, i32 N,
  * i32 d, u32 0, u64 payload bytes) followed by the raw table in the layout the header names.
  * Host-only calls: no GPU work, no stream.  These are the only calls that keep state: a
- * mole_lut_file owns a file descriptor and a mapping until mole_lut_file_close.
+ * mole_lut_file owns a file descriptor, a mapping and its reader threads (started on first use,
+ * kept for later calls) until mole_lut_file_close.  Calls on one handle are serialised.
  *   mole_lut_file_create: creates (truncates) `path`, sizes it, maps it read-write.
  *   mole_lut_file_open:   opens read-only, validates the header against the file size, fills
  *                         *desc (nullable).

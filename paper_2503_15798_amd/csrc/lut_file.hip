@@ -32,9 +32,97 @@
 #include <unistd.h>
 
 #include <atomic>
+#include <chrono>
+#include <condition_variable>
+#include <functional>
+#include <mutex>
 #include <new>
 #include <thread>
 #include <vector>
+
+namespace {
+
+// Reader threads that live as long as the file handle: starting threads per call costs more than the
+// reads of a decoding step (a few hundred KiB per id).  Workers spin briefly for the next job before
+// they sleep on a condition variable.
+class WorkerPool {
+public:
+    ~WorkerPool()
+    {
+        {
+            std::lock_guard<std::mutex> lk(m_);
+            stop_ = true;
+            ++generation_;
+        }
+        cv_.notify_all();
+        for (auto &t : threads_)
+            t.join();
+    }
+    // body(index, n) on n workers (the caller is worker 0); returns when all are done
+    void run(int n, const std::function<void(int, int)> &body)
+    {
+        if (n <= 1) {
+            body(0, 1);
+            return;
+        }
+        while ((int)threads_.size() < n - 1) {
+            const int idx = (int)threads_.size() + 1;
+            threads_.emplace_back([this, idx] { loop(idx); });
+        }
+        {
+            std::lock_guard<std::mutex> lk(m_);
+            body_ = &body;
+            n_ = n;
+            pending_.store(n - 1, std::memory_order_relaxed);
+            generation_.fetch_add(1, std::memory_order_release);
+        }
+        cv_.notify_all();
+        body(0, n);
+        while (pending_.load(std::memory_order_acquire) != 0)
+            std::this_thread::yield();
+    }
+
+private:
+    void loop(int idx)
+    {
+        uint64_t seen = 0;
+        for (;;) {
+            // spin for about 50 us, then sleep
+            const auto t0 = std::chrono::steady_clock::now();
+            while (generation_.load(std::memory_order_acquire) == seen) {
+                if (std::chrono::steady_clock::now() - t0 > std::chrono::microseconds(50)) {
+                    std::unique_lock<std::mutex> lk(m_);
+                    cv_.wait(lk, [&] { return generation_.load(std::memory_order_acquire) != seen; });
+                    break;
+                }
+            }
+            const std::function<void(int, int)> *body;
+            int n;
+            {
+                std::lock_guard<std::mutex> lk(m_);
+                if (stop_)
+                    return;
+                seen = generation_.load(std::memory_order_relaxed);
+                body = body_;
+                n = n_;
+            }
+            if (idx < n) {
+                (*body)(idx, n);
+                pending_.fetch_sub(1, std::memory_order_release);
+            }
+        }
+    }
+    std::vector<std::thread> threads_;
+    std::mutex m_;
+    std::condition_variable cv_;
+    std::atomic<uint64_t> generation_{0};
+    std::atomic<int> pending_{0};
+    const std::function<void(int, int)> *body_ = nullptr;
+    int n_ = 0;
+    bool stop_ = false;
+};
+
+}  // namespace
 
 struct mole_lut_file {
     int fd;
@@ -43,6 +131,8 @@ struct mole_lut_file {
     size_t map_bytes;
     mole_lut_desc desc;
     int64_t row_bytes;   // N * d * element size
+    std::mutex call_mutex;   // calls that use the pool are serialised per handle
+    WorkerPool pool;
 };
 
 namespace {
@@ -86,8 +176,7 @@ inline uint64_t row_offset(const mole_lut_file *f, int l, int64_t v)
                                                   : ((uint64_t)l * f->desc.V + v) * rb;
 }
 
-template <class F>
-void run_threads(int threads, int64_t items, F &&body)
+int clamp_threads(int threads, int64_t items)
 {
     if (threads < 1)
         threads = 1;
@@ -95,16 +184,7 @@ void run_threads(int threads, int64_t items, F &&body)
         threads = 64;
     if ((int64_t)threads > items)
         threads = (int)(items > 0 ? items : 1);
-    if (threads == 1) {
-        body(0, 1);
-        return;
-    }
-    std::vector<std::thread> pool;
-    pool.reserve(threads);
-    for (int t = 0; t < threads; ++t)
-        pool.emplace_back([&body, t, threads] { body(t, threads); });
-    for (auto &th : pool)
-        th.join();
+    return threads;
 }
 
 bool pread_all(int fd, char *dst, uint64_t bytes, uint64_t off)
@@ -256,7 +336,8 @@ extern "C" mole_status mole_lut_file_write_layer(mole_lut_file *file, int layer,
     const char *src = static_cast<const char *>(src_host);
     const int64_t V = file->desc.V;
     const uint64_t rb = (uint64_t)file->row_bytes;
-    run_threads(threads, V, [&](int t, int nt) {
+    std::lock_guard<std::mutex> guard(file->call_mutex);
+    file->pool.run(clamp_threads(threads, V), [&](int t, int nt) {
         const int64_t v0 = V * t / nt, v1 = V * (t + 1) / nt;
         if (file->desc.layout == MOLE_LAYOUT_LAYER_MAJOR) {
             memcpy(payload + row_offset(file, layer, v0), src + (uint64_t)v0 * rb, (uint64_t)(v1 - v0) * rb);
@@ -291,7 +372,8 @@ extern "C" mole_status mole_lut_file_read_rows(mole_lut_file *file, const int32_
     const int64_t reads = id_major ? (int64_t)n : (int64_t)n * L;
     std::atomic<int> failed{0};
     char *dst = static_cast<char *>(dst_host);
-    run_threads(threads, reads, [&](int t, int nt) {
+    std::lock_guard<std::mutex> guard(file->call_mutex);
+    file->pool.run(clamp_threads(threads, reads), [&](int t, int nt) {
         for (int64_t r = t; r < reads && !failed.load(std::memory_order_relaxed); r += nt) {
             bool ok;
             if (id_major) {
