@@ -466,7 +466,7 @@ def extras(args, torch, mb, wl, acc, stream, L):
         del LL
         torch.cuda.empty_cache()
 
-    out["build_lut_410m_layer"] = build_bench(torch, mb, wl, acc, stream)
+    out["build_lut_410m_layer"] = build_bench(torch, mb, wl, acc, stream, with_cpu=not args.no_cpu)
     return out
 
 
@@ -552,6 +552,11 @@ def offload_bench(torch, mb, wl, acc, stream, L, steps, warm):
     ms_fetch = time_steps(torch, stream, only_fetch, steps, warm)
     u0 = len(np.unique(ids_host[0]))
     ms_direct = time_steps(torch, stream, lambda i: fwd_direct(i), steps, warm)
+    # the practical ceiling of the link: one plain pinned-to-device copy of a layer's table (1.65 GB)
+    dst = torch.empty_like(L.tabs[0])
+    ms_copy = time_steps(torch, stream, lambda i: dst.copy_(host[0], non_blocking=True), 3, 1)
+    copy_GBps = host[0].numel() * 2 / (ms_copy * 1e-3) / 1e9
+    del dst
     res["offload410m"] = {
         "step": "dedup + fetch of the distinct rows of all 24 layers from pinned host memory + staged forward",
         "tokens": T, "mean_distinct_ids": U, "ms": ms_full, "tokens_per_s": T / (ms_full * 1e-3),
@@ -559,6 +564,7 @@ def offload_bench(torch, mb, wl, acc, stream, L, steps, warm):
         "fetch_frac_of_host_link_peak": u0 * w.L * row_elems * 2 / (ms_fetch * 1e-3) / 1e9 / HOST_LINK_GBS,
         "fetched_bytes_per_step": fetched, "host_table_bytes": int(host.numel() * 2),
         "forward_reading_host_table_directly_ms": ms_direct,
+        "pinned_memcpy_GBps": copy_GBps,
     }
     del host
 
@@ -707,7 +713,7 @@ def storage_bench(torch, mb, wl, stream, L, steps, warm, layers=4, threads=16):
             os.remove(path)
 
 
-def build_bench(torch, mb, wl, acc, stream):
+def build_bench(torch, mb, wl, acc, stream, with_cpu=False):
     w = wl.CONFIGS["offload410m"]
     g = torch.Generator(device="cuda")
     g.manual_seed(77)
@@ -725,10 +731,24 @@ def build_bench(torch, mb, wl, acc, stream):
     # fp16 hidden activation (the library's choice for these inputs): executed = algorithmic flops; the
     # bf16 hi + lo variant runs the second GEMM over two planes
     executed = flops * (1.5 if os.environ.get("MOLE_BUILD_HIDDEN") == "split" else 1.0)
-    return {"ms": ms, "algorithmic_TFLOPs": flops / (ms * 1e-3) / 1e12,
-            "algorithmic_frac_of_bf16_mfma_peak": flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-            "executed_mfma_TFLOPs": executed / (ms * 1e-3) / 1e12,
-            "vocab_rows_per_s": w.V / (ms * 1e-3)}
+    res = {"ms": ms, "algorithmic_TFLOPs": flops / (ms * 1e-3) / 1e12,
+           "algorithmic_frac_of_bf16_mfma_peak": flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+           "executed_mfma_TFLOPs": executed / (ms * 1e-3) / 1e12,
+           "vocab_rows_per_s": w.V / (ms * 1e-3)}
+    if with_cpu:
+        # the fp64 oracle on a sample of vocabulary rows, extrapolated linearly to the whole table
+        import oracle
+        n = 64
+        rows = torch.arange(0, w.V, w.V // n, device="cuda")[:n]
+        host = lambda t: t.contiguous().view(torch.int16).cpu().numpy().view("uint16")
+        Eh, W1h, W2h = host(E[rows]), host(W1), host(W2)
+        t0 = time.perf_counter()
+        oracle.build_lut(Eh, W1h, W2h)
+        dt = time.perf_counter() - t0
+        res["cpu_oracle"] = {"sample_rows": n, "seconds": dt, "cores": oracle.threads(),
+                             "extrapolated_seconds_per_layer": dt / n * w.V,
+                             "note": "timed on the sample, extrapolated linearly to V rows"}
+    return res
 
 
 if __name__ == "__main__":

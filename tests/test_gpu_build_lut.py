@@ -85,3 +85,38 @@ def test_bf16_build_beyond_the_fp16_range():
     assert (np.abs(clipped - ref) > 100 * allowance + 1e-3 + 2e-2 * np.abs(ref)).any()   # saturation would be seen
     got = run_build(w, ew)
     assert_close(wl.storage_to_f64(got, w.dtype), ref, w.dtype, "bf16 LUT, large activations", extra_atol=allowance)
+
+
+def test_bf16_build_closed_forms():
+    w = wl.scaled(wl.CONFIGS["offload410m"], V=300, d=128, D=256, N=2)
+    ew = wl.expert_weights(w, bias=True)
+    ew0 = dict(ew, W2=np.zeros_like(ew["W2"]))
+    got = run_build(w, ew0)                       # second matrix zero -> the output bias everywhere
+    np.testing.assert_array_equal(got, np.broadcast_to(ew["b2"][None], got.shape))
+    ew1 = dict(ew, W1=np.zeros_like(ew["W1"]), b1=None)
+    got = run_build(w, ew1)                       # GELU(0) = 0 -> the output bias again
+    np.testing.assert_array_equal(got, np.broadcast_to(ew["b2"][None], got.shape))
+
+
+def test_410m_layer_sampled_rows():
+    """One full 410M layer (V=50304, d=1024, D=4096, N=16, bf16) built on the GPU; 512 seeded-random
+    vocabulary rows (plus tile-boundary rows) x all experts against the fp64 oracle (the whole table is
+    1.35e13 flop: too slow on the host)."""
+    import torch
+    w = wl.CONFIGS["offload410m"]
+    g = torch.Generator(device="cuda")
+    g.manual_seed(55)
+    E = torch.randn((w.V, w.d), generator=g, device="cuda").to(torch.bfloat16)
+    W1 = (torch.randn((w.N, w.d, w.D), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+    W2 = (torch.randn((w.N, w.D, w.d), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+    lut = torch.full((w.V, w.N, w.d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty((mb.mole_build_lut_workspace(w.V, w.d, w.D, w.N, mb.MOLE_BF16),), dtype=torch.uint8, device="cuda")
+    mb.mole_build_lut(E, W1, None, W2, None, None, 0.0, lut, w.V, w.d, w.D, w.N, mb.MOLE_BF16, mb.MOLE_GELU_ERF, ws)
+    torch.cuda.synchronize()
+    assert not torch.isnan(lut.float()).any()
+    rows = np.unique(np.concatenate([np.random.default_rng(8).integers(0, w.V, 506),
+                                     [0, 255, 256, 16383, 16384, w.V - 1]]))
+    rows_t = torch.from_numpy(rows.astype(np.int64)).cuda()
+    got = to_host(lut[rows_t], wl.BF16)
+    ref = oracle.build_lut(to_host(E[rows_t], wl.BF16), to_host(W1, wl.BF16), to_host(W2, wl.BF16))
+    assert_close(wl.storage_to_f64(got, wl.BF16), ref, wl.BF16, "410M LUT sample")
