@@ -24,7 +24,7 @@
 // fetched the same way (16-byte pieces along K) and match the MFMA operand layout directly.
 //
 // Two GEMM kernels.  Column counts that are multiples of 256 take the 256 x 256 kernel fed by direct
-// global -> LDS loads (described at gemm_nt_kernel_v3).  Other shapes take the 256 x 128 kernel below:
+// global -> LDS loads (described at gemm_nt_direct_kernel).  Other shapes take the 256 x 128 kernel below:
 // workgroup of 4 waves (2 x 2), each wave 128 x 64 = 4 x 2 MFMA tiles, K step 64 through LDS with 16
 // bytes of row padding (conflict-free 16-byte reads), next K tile prefetched into registers while the
 // current one is multiplied.
@@ -299,7 +299,7 @@ void gemm_nt_kernel(GemmArgs g)
     }
 }
 
-constexpr int BM2 = 256, BN2 = 256, THREADS2 = 512;
+constexpr int DBM = 256, DBN = 256, D_THREADS = 512;
 
 // ------------------------------------------------------------------------------------------
 // 256 x 256 tile fed by direct global -> LDS loads (global_load_lds_dwordx4, gfx950): no staging
@@ -311,25 +311,25 @@ constexpr int BM2 = 256, BN2 = 256, THREADS2 = 512;
 // Two stages of 64 KiB: step kt + 1 travels while step kt is multiplied.  8 waves (2 x 4), each
 // 128 x 64 outputs, two per SIMD.
 // ------------------------------------------------------------------------------------------
-constexpr int ROW3 = BK * 2;                        // bytes per tile row (128)
-constexpr int STAGE3 = (BM2 + BN2) * ROW3;          // 64 KiB
-constexpr int NSTAGE3 = 2;
-constexpr size_t LDS3 = (size_t)NSTAGE3 * STAGE3;
+constexpr int D_ROW_BYTES = BK * 2;                        // bytes per tile row (128)
+constexpr int D_STAGE_BYTES = (DBM + DBN) * D_ROW_BYTES;          // 64 KiB
+constexpr int D_STAGES = 2;
+constexpr size_t D_LDS_BYTES = (size_t)D_STAGES * D_STAGE_BYTES;
 
 #define MOLE_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 
 template <int EPI, bool F16>
-__global__ __launch_bounds__(THREADS2) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void gemm_nt_kernel_v3(GemmArgs g)
+__global__ __launch_bounds__(D_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void gemm_nt_direct_kernel(GemmArgs g)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem3[];
+    extern __shared__ __attribute__((aligned(16))) unsigned char dsmem[];
     if (g.mode && *g.mode != g.run_mode)
         return;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 2, wn = wave & 3;
-    const int m0 = blockIdx.x * BM2, n0 = blockIdx.y * BN2;
+    const int m0 = blockIdx.x * DBM, n0 = blockIdx.y * DBN;
     const int batch = blockIdx.z;
     const uint16_t *A = g.A + batch * g.a_batch_stride;
     const uint16_t *Bt = g.Bt + batch * g.b_batch_stride;
@@ -365,22 +365,22 @@ void gemm_nt_kernel_v3(GemmArgs g)
     // memory pipeline's queue, and nothing feeds the matrix pipe meanwhile (measured: the step then
     // takes compute time plus load-issue time)
     int64_t cur_aoff = 0, cur_kk = 0;
-    unsigned char *cur_stage = smem3;
+    unsigned char *cur_stage = dsmem;
     auto begin_issue = [&](int kt) {
         const int plane = kt / ktiles_per_plane;
         cur_kk = (kt - plane * ktiles_per_plane) * BK;
         cur_aoff = plane * g.a_plane_stride + cur_kk;
-        cur_stage = smem3 + (kt & (NSTAGE3 - 1)) * STAGE3 + wave * 1024;
+        cur_stage = dsmem + (kt & (D_STAGES - 1)) * D_STAGE_BYTES + wave * 1024;
     };
     auto issue_one = [&](int i) {
         __builtin_amdgcn_global_load_lds(
             (const __attribute__((address_space(1))) void *)(gp[i] + (i < 4 ? cur_aoff : cur_kk)),
-            (__attribute__((address_space(3))) void *)(cur_stage + (i < 4 ? 0 : BM2 * ROW3) + (i & 3) * 8192), 16, 0, 0);
+            (__attribute__((address_space(3))) void *)(cur_stage + (i < 4 ? 0 : DBM * D_ROW_BYTES) + (i & 3) * 8192), 16, 0, 0);
     };
 
     // fragment addressing: row frow of a 32-row block, K piece 2*ks + (lane >> 5), swizzled
     const int frow = lane & 31, swz = (frow >> 1) & 7, hi = lane >> 5;
-    const int a_base = (wm * 128 + frow) * ROW3, b_base = (BM2 + wn * 64 + frow) * ROW3;
+    const int a_base = (wm * 128 + frow) * D_ROW_BYTES, b_base = (DBM + wn * 64 + frow) * D_ROW_BYTES;
     struct Frag {
         u32x4 a[4], b[2];
     };
@@ -388,10 +388,10 @@ void gemm_nt_kernel_v3(GemmArgs g)
         const int koff = ((2 * ks + hi) ^ swz) * 16;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            f.a[i] = *reinterpret_cast<const u32x4 *>(stage + a_base + i * 32 * ROW3 + koff);
+            f.a[i] = *reinterpret_cast<const u32x4 *>(stage + a_base + i * 32 * D_ROW_BYTES + koff);
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-            f.b[j] = *reinterpret_cast<const u32x4 *>(stage + b_base + j * 32 * ROW3 + koff);
+            f.b[j] = *reinterpret_cast<const u32x4 *>(stage + b_base + j * 32 * D_ROW_BYTES + koff);
     };
     // four MFMAs: A blocks i0, i0 + 1 against both B blocks
     auto multiply2 = [&](const Frag &f, int i0) {
@@ -424,7 +424,7 @@ void gemm_nt_kernel_v3(GemmArgs g)
         const bool more = kt + 1 < ktiles;
         if (more)
             begin_issue(kt + 1);
-        const unsigned char *stage = smem3 + (kt & (NSTAGE3 - 1)) * STAGE3;
+        const unsigned char *stage = dsmem + (kt & (D_STAGES - 1)) * D_STAGE_BYTES;
         // Order of the step (kept by the scheduling barriers; left alone the compiler re-sorts the
         // region to save registers): fragments of slice ks + 1 are requested before slice ks is
         // multiplied, and one load of the next step goes out per group of four MFMAs.
@@ -459,10 +459,10 @@ void gemm_nt_kernel_v3(GemmArgs g)
     // four passes of 64 rows (32 from each wave row) by 256 columns.
     const uint16_t *bias = g.bias ? g.bias + batch * g.bias_batch_stride : nullptr;
     uint16_t *C = g.C + batch * g.c_batch_stride;
-    constexpr int CROW = BN2 * 2 + 8;
+    constexpr int CROW = DBN * 2 + 8;
     constexpr int CPLANE = 64 * CROW;
-    static_assert(2 * CPLANE <= (int)LDS3, "epilogue staging must fit in the operand stages");
-    unsigned char *Cs = smem3;
+    static_assert(2 * CPLANE <= (int)D_LDS_BYTES, "epilogue staging must fit in the operand stages");
+    unsigned char *Cs = dsmem;
     float bv[2][4][4];
 #pragma unroll
     for (int j = 0; j < 2; ++j)
@@ -527,7 +527,7 @@ void gemm_nt_kernel_v3(GemmArgs g)
         // write out: 64 rows x 512 bytes per plane = 2048 16-byte pieces, 4 per thread and plane
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int piece = tid + u * THREADS2;
+            const int piece = tid + u * D_THREADS;
             const int sr = piece >> 5, sc = piece & 31;
             const int row = m0 + (sr >> 5) * 128 + i * 32 + (sr & 31);
             if (row < g.M) {
@@ -809,16 +809,16 @@ mole_status build_plain(const void *Em, const void *W1, const void *b1, const vo
 template <int EPI, bool F16>
 mole_status launch_gemm(const GemmArgs &g, int batches, hipStream_t st)
 {
-    const bool big = g.Nn % BN2 == 0 && !getenv("MOLE_BUILD_SMALL_TILE");
+    const bool big = g.Nn % DBN == 0 && !getenv("MOLE_BUILD_SMALL_TILE");
     if (big) {
-        static bool attr3_set = false;
-        if (!attr3_set) {
-            MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_nt_kernel_v3<EPI, F16>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS3));
-            attr3_set = true;
+        static bool attr_set = false;
+        if (!attr_set) {
+            MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_nt_direct_kernel<EPI, F16>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)D_LDS_BYTES));
+            attr_set = true;
         }
-        hipLaunchKernelGGL((gemm_nt_kernel_v3<EPI, F16>), dim3((g.M + BM2 - 1) / BM2, g.Nn / BN2, batches),
-                           dim3(THREADS2), LDS3, st, g);
+        hipLaunchKernelGGL((gemm_nt_direct_kernel<EPI, F16>), dim3((g.M + DBM - 1) / DBM, g.Nn / DBN, batches),
+                           dim3(D_THREADS), D_LDS_BYTES, st, g);
     } else {
         hipLaunchKernelGGL((gemm_nt_kernel<EPI, F16>), dim3((g.M + BM - 1) / BM, g.Nn / BN, batches),
                            dim3(GEMM_THREADS), 0, st, g);
