@@ -567,6 +567,7 @@ def offload_bench(torch, mb, wl, acc, stream, L, steps, warm):
         "pinned_memcpy_GBps": copy_GBps,
     }
     del host
+    release_pinned(torch)
 
     # ---- the same tables id-major on the host ([V, L, N, d]: one contiguous 768 KiB block per id) ----
     host_id = torch.empty((w.V, w.L, w.N, w.d), dtype=L.tabs.dtype, pin_memory=True)

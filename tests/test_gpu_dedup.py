@@ -79,6 +79,32 @@ def test_dedup_edge_cases():
     check_plan(plan, ids, 100, uniq, U)
 
 
+@pytest.mark.parametrize("case", ["all equal", "out of range", "two hot ids", "all distinct", "edges of V"])
+def test_degenerate_large_batches(case):
+    """One id for everybody, ids outside the table throughout, two ids sharing the batch, all distinct
+    (descending), first / last ids of V and of a bitmap word."""
+    T, V = 6000, 50304
+    rng = np.random.default_rng(5)
+    if case == "all equal":
+        ids = np.full((T,), 777, np.int32)
+    elif case == "out of range":
+        ids = rng.integers(0, V, T).astype(np.int32)
+        ids[::7] = V + 3
+        ids[5::64] = -9
+    elif case == "two hot ids":
+        ids = np.where(rng.random(T) < 0.5, 31, 32).astype(np.int32)
+    elif case == "all distinct":
+        ids = np.arange(T, dtype=np.int32)[::-1].copy()
+    else:
+        ids = rng.choice(np.array([0, 1, 31, 32, V - 33, V - 32, V - 1], np.int32), T)
+    uniq, inv, U, err, plan = run_dedup(ids, V)
+    r_uniq, r_inv, r_U, r_err = oracle.dedup(ids, V)
+    assert U == r_U and err == r_err
+    np.testing.assert_array_equal(uniq, r_uniq)
+    np.testing.assert_array_equal(inv, r_inv)
+    check_plan(plan, ids, V, uniq, U)
+
+
 def test_expected_distinct_counts_of_the_workloads():
     """The Zipf(1.1) batches have the reuse the benchmark configurations rely on."""
     for name, lo, hi in [("decode410m", 120, 180), ("prefill410m", 3700, 4600), ("prefill410m_uniform", 13500, 14500)]:
