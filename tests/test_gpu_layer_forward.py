@@ -159,3 +159,36 @@ def test_fold_router_norm_is_a_rounded_row_scaling(dtype):
     torch.cuda.synchronize()
     want = wl.to_storage(wl.storage_to_f64(W, dtype) * wl.storage_to_f64(lw, dtype)[:, :, None], dtype)
     np.testing.assert_array_equal(to_host(out_d, dtype), want)
+
+
+@pytest.mark.parametrize("name,dedup", [("prefill410m_uniform", False), ("prefill410m", True), ("decode1b_4e", False)])
+def test_full_size_single_layer_sampled(name, dedup):
+    """Benchmark sizes in the benchmark's launch configuration; the oracle runs on a sample of tokens whose
+    rows are copied back with plain indexing."""
+    import torch
+    w = wl.CONFIGS[name]
+    tab_d = wl.device_table(w, 0, "cuda")
+    ids, inp = wl.token_ids(w), inputs(w)
+    ids_d = torch.from_numpy(ids).cuda()
+    x_d, lw_d, wr_d, sh_d = (to_dev(inp[k], w.dtype) for k in ("x", "ln_w", "W_r", "shared"))
+    mb.mole_fold_router_norm(wr_d, lw_d, wr_d, 1, w.d, w.N, DT[w.dtype])
+    out_d = torch.full_like(x_d, float("nan"))
+    err_d = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    flags, plan = 0, None
+    if dedup:
+        plan = torch.empty((mb.mole_dedup_workspace(w.T, w.V) // 4,), dtype=torch.int32, device="cuda")
+        uq, iv = torch.empty_like(ids_d), torch.empty_like(ids_d)
+        mb.mole_dedup_ids(ids_d, w.T, w.V, uq, iv, torch.zeros_like(err_d), err_d, plan)
+        flags = mb.MOLE_FLAG_DEDUP
+    mb.mole_layer_forward(tab_d, 0, ids_d, None, x_d, EPS, wr_d, sh_d, out_d, 0, None, None, err_d, 1, w.T, w.V, w.d,
+                          w.N, DT[w.dtype], flags, plan)
+    torch.cuda.synchronize()
+    assert int(err_d.item()) == 0
+    out = to_host(out_d, w.dtype)
+    assert not np.isnan(wl.storage_to_f64(out, w.dtype)).any()
+    sample = np.unique(np.concatenate([np.random.default_rng(6).integers(0, w.T, 48), [0, w.T - 1],
+                                       np.argsort(ids)[-3:]]))
+    rows = to_host(tab_d[torch.from_numpy(ids[sample].astype(np.int64)).cuda()], w.dtype)
+    ref, *_ = oracle.layer_forward(rows, np.arange(len(sample), dtype=np.int32), inp["x"][sample], inp["ln_w"], EPS,
+                                   inp["W_r"], inp["shared"][sample])
+    assert_close(wl.storage_to_f64(out[sample], w.dtype), ref, w.dtype, f"{name} fused-norm sample")

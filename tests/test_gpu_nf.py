@@ -138,3 +138,35 @@ def test_quantisation_error_is_what_the_levels_allow():
         err = np.abs(wl.storage_to_f64(out[0], wl.BF16) - exact)
         assert (err <= bound + 1e-3 + 2e-2 * np.abs(exact)).all()
         assert err.mean() > 1e-4          # and it is not accidentally the unquantised table
+
+
+@pytest.mark.parametrize("bits,block,sb", [(4, 1024, 4), (3, 128, 2)])
+def test_full_size_layer_sampled(bits, block, sb):
+    """One 410M layer at full size (V = 50304, N = 16, d = 1024, T = 256), the two formats the benchmark
+    times: quantised on the device; the oracle runs on a sample of tokens, whose rows are copied back as
+    bf16, quantised and dequantised by the codec oracle (the device quantiser is bit-exact, tested above)."""
+    import torch
+    w = wl.scaled(wl.CONFIGS["decode410m"], L=1)
+    tab_d = wl.device_table(w, 0, "cuda")
+    codes = torch.zeros((mb.mole_nf_codes_bytes(w.V, w.N, w.d, bits),), dtype=torch.uint8, device="cuda")
+    scales = torch.zeros((mb.mole_nf_scales_bytes(w.V, w.N, w.d, block, sb),), dtype=torch.uint8, device="cuda")
+    mb.mole_quantize_lut(tab_d, codes, scales, w.V, w.N, w.d, bits, block, sb)
+    li, ids = wl.layer_inputs(w), wl.token_ids(w)
+    h_d, wr_d, sh_d = (to_dev(li[k], wl.BF16) for k in ("h", "W_r", "shared"))
+    ids_d = torch.from_numpy(ids).cuda()
+    out_d = torch.full_like(h_d, float("nan"))
+    err = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    mb.mole_lookup_forward_nf(codes, 0, scales, 0, ids_d, None, h_d, wr_d, sh_d, None, out_d, 0, None, None, err, 1,
+                              w.T, w.V, w.d, w.N, bits, block, sb, 0, None)
+    torch.cuda.synchronize()
+    assert int(err.item()) == 0
+    out = to_host(out_d, wl.BF16)
+    assert not np.isnan(wl.storage_to_f64(out, wl.BF16)).any()
+    sample = np.unique(np.concatenate([np.random.default_rng(4).integers(0, w.T, 40), [0, w.T - 1]]))
+    rows = to_host(tab_d[torch.from_numpy(ids[sample].astype(np.int64)).cuda()], wl.BF16)          # [S,N,d] bf16 bits
+    c, sc = nf.quantize(wl.bf16_bits_to_f32(rows), bits, block)
+    deq = nf.dequantize(c, sc, bits, block)
+    f = lambda a: wl.storage_to_f64(a, wl.BF16)
+    ref, *_ = oracle.lookup_forward(deq, np.arange(len(sample), dtype=np.int32), f(li["h"][sample]), f(li["W_r"]),
+                                    f(li["shared"][sample]))
+    assert_close(f(out[sample]), ref, wl.BF16, f"NF{bits} full-size sample")
