@@ -172,13 +172,19 @@ __device__ __forceinline__ void load_codes(uint32_t &lo, uint32_t &hi, const uin
     }
 }
 
+// acc[e] += gs * level[code e of w], e = 0..7.  One LDS lookup per element is the cost of this
+// kernel, so every instruction around it counts: the level table is a statically allocated LDS array
+// (its address is a compile-time constant, so no base is added per lookup; a table inside the dynamic
+// area costs one more add per element), and the index is taken already scaled by four.
 template <int BITS>
-__device__ __forceinline__ void dequant_fma8(float (&acc)[8], float gs, uint32_t w, const float *cb)
+__device__ __forceinline__ void dequant_fma8(float (&acc)[8], float gs, uint32_t w, const float *levels)
 {
+    const unsigned char *base = reinterpret_cast<const unsigned char *>(levels);
+    constexpr uint32_t MASK = ((1u << BITS) - 1u) << 2;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        const uint32_t c = (w >> (BITS * e)) & ((1u << BITS) - 1u);
-        acc[e] = fmaf(gs, cb[c], acc[e]);
+        const uint32_t a = BITS * e >= 2 ? (w >> (BITS * e - 2)) & MASK : (w << (2 - BITS * e)) & MASK;
+        acc[e] = fmaf(gs, *reinterpret_cast<const float *>(base + a), acc[e]);
     }
 }
 
@@ -214,11 +220,11 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
         order = a.plan + plan_layout(T).order;
     }
 
-    // level table behind the router weight
-    float *cb = reinterpret_cast<float *>(smem + N * (kgroups + 1));
+    __shared__ float cb[NLEV];            // level table (static: see dequant_fma8)
+    uint4 *router = smem;
     if (threadIdx.x < NLEV)
         cb[threadIdx.x] = BITS == 4 ? NF4_LEVELS[threadIdx.x] : NF3_LEVELS[threadIdx.x];
-    fill_router_lds<N>(smem, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
+    fill_router_lds<N>(router, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
     __syncthreads();
 
     // code words and scales of the wave's first token go in flight before anything else
@@ -254,7 +260,7 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
         if (a.rows_dbg && layer == 0 && lane == 0)
             a.rows_dbg[t] = valid ? row : -1;
 
-        const float g = router_gate<N, false>(smem, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1);
+        const float g = router_gate<N, false>(router, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1);
         if (a.gates_dbg && (lane & (LPJ - 1)) == 0)
             a.gates_dbg[((int64_t)layer * T + t) * N + lane / LPJ] = g;
         load_h2<false>(h0, h1, hbase + (int64_t)nt * d, d, lane);
