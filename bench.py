@@ -332,13 +332,15 @@ def main():
         torch.cuda.synchronize()
 
     line = {
-        "metric": "MoLE layer tokens/s (410M-shape decode step: 24 MoLE layers x 256 tokens, N=16, d=1024)",
+        "metric": ("MoLE layer tokens/s (410M-shape decode step: 24 MoLE layers x 256 tokens, N=16, d=1024)"
+                   if w.name == "decode410m" else
+                   f"MoLE layer tokens/s ({w.name}: {w.L} MoLE layers x {w.T} tokens, N={w.N}, d={w.d})"),
         "value": head["layer_tokens_per_s"], "unit": "layer-tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": w.name, "layers": w.L, "tokens_per_step": w.T, "V": w.V, "d": w.d, "N": w.N,
-                   "ids": "zipf(1.1), 16 rotating batches", "mean_distinct_ids": distinct,
+                   "ids": ("zipf(1.1)" if w.ids == "zipf" else w.ids) + ", 16 rotating batches", "mean_distinct_ids": distinct,
                    "table_bytes": table_bytes,
                    "step": "router + softmax + gather + gate-weighted sum + shared add, all layers, one launch",
                    "decode_tokens_per_s": head["tokens_per_s"],
