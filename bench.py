@@ -192,6 +192,22 @@ def time_steps(torch, stream, step, steps, warmup):
     return ev0.elapsed_time(ev1) / steps
 
 
+def launch_spread(torch, stream, step, n=200):
+    """Launch-to-launch time of n further calls of step(i), each bracketed by its own HIP events on
+    `stream`: median, 10th and 90th percentile in microseconds (outside the timed region)."""
+    with torch.cuda.stream(stream):
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+        stream.synchronize()
+        evs[0].record(stream)
+        for i in range(n):
+            step(i)
+            evs[i + 1].record(stream)
+        stream.synchronize()
+    us = sorted(evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(n))
+    pick = lambda q: us[min(n - 1, int(q * n))]
+    return {"median": pick(0.5), "p10": pick(0.1), "p90": pick(0.9), "n": n}
+
+
 def rates(w, acc, ms, distinct=None):
     """tokens/s and GB/s for a forward over all layers of workload w taking `ms`."""
     alg = acc.forward_bytes_per_token(w.d, w.N, w.elem_bytes) * w.T * w.L
@@ -314,6 +330,8 @@ def main():
                 "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": ms_kernel,
                 "moved_GBps": w.L * acc.forward_bytes_moved(w.T, int(round(distinct)), w.d, w.N, w.elem_bytes)
                 / (ms_kernel * 1e-3) / 1e9}
+
+    roofline["launch_us"] = launch_spread(torch, stream, step)
 
     cpu = None
     if not args.no_cpu:

@@ -3,7 +3,9 @@
 // Paper: Sec. 3.2 (router equation: full softmax over all N experts) and Sec. 3.3
 // (inference-layer equation: h' = sum_j g_j v^id_j + FFN_shared(h) + h).
 //
-// The path is bound by HBM bandwidth (about 1.7 flop per byte), so there is no MFMA here.
+// The path is bound by HBM bandwidth (about 1.7 flop per byte); the streaming kernel below does its
+// arithmetic on the vector ALU.  (The run kernel further down, for large batches that come with a
+// plan, sums groups of tokens with equal ids on the matrix pipe.)
 // One 64-lane wavefront owns a token:
 //   * lane l owns columns [512*c + 8*l, +8) of every row: every table access is a 16-byte
 //     load and a wavefront covers 1 KiB of a row per load;
@@ -205,6 +207,314 @@ void fwd_bf16_stream_kernel(FwdArgs a)
 }
 
 // ------------------------------------------------------------------------------------------
+// Run kernel (needs the plan of mole_dedup_ids): the plan lists the tokens in id order, so tokens with
+// equal ids sit next to each other.  A wave takes G consecutive positions of that order (a span):
+//   1. router + softmax for each token of the span, as in the streaming kernel; the gates go to LDS,
+//      each split into two bf16 values hi + lo (hi = the gate rounded to bf16, lo = the rounded rest:
+//      16 significant bits, the products with bf16 table values are still exact in fp32);
+//   2. per 512-column chunk, the span is cut into groups of up to 4 positions with the same row block.
+//      The N row pieces of the chunk are fetched once per run (they stay in registers while the id
+//      does not change) and the gate-weighted sum of a whole group is taken on the matrix pipe:
+//      v_mfma_f32_4x4x4_16b_bf16 computes, in each of its 16 blocks of 4 lanes, a 4x4 product
+//      D[i][j] += sum_k A[i][k] B[k][j] where lane 4b+i supplies row i of A, lane 4b+j supplies column
+//      j of B and receives column j of D.  With A = the gates of the group's (up to) 4 tokens for 4
+//      experts and B = the lane's own column of those 4 experts' rows, every lane gets the sums of its
+//      own columns for 4 tokens at once, from bf16 table values as they are (no conversion on the
+//      vector ALU, which otherwise limits this kernel at N = 32: two instructions per table element).
+//   3. shared / residual are added and the result is rounded and stored per token, as elsewhere.
+// Row pieces come through buffer loads: base and size of the row block in a scalar descriptor, the
+// expert's offset in a scalar register, the lane's column offset the only vector operand.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// N 16-byte pieces (one per expert) of one 512-column chunk of a row block.  Lanes past the end of
+// the block read zeros (ragged last chunk); their results are never stored.
+template <int N, bool NT>
+__device__ __forceinline__ void ring_load_buf(uint4 (&r)[N], const uint16_t *block, int d, uint32_t lane_bytes,
+                                              int chunk_bytes)
+{
+    typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+    constexpr int RAW_32BIT = 0x00020000;   // untyped buffer, 32-bit data format
+    const __amdgpu_buffer_rsrc_t rs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(block), 0, N * d * 2, RAW_32BIT);
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, lane_bytes, j * d * 2 + chunk_bytes, NT ? 2 : 0);
+        r[j] = make_uint4(v.x, v.y, v.z, v.w);
+    }
+}
+
+typedef __attribute__((ext_vector_type(4))) short bf16x4_bits;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+__device__ __forceinline__ uint32_t dword_of(const uint4 &v, int i)
+{
+    return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w;
+}
+
+// acc[e][i] += sum over the 4 experts 4q .. 4q+3 of gate[token i][expert] * row[expert][lane's column e]
+// for the lane's 8 columns.  ga: this lane's A operand (gates of token lane & 3: hi in x, y; lo in z, w).
+template <int N>
+__device__ __forceinline__ void group_mfma(f32x4 (&acc)[8], const uint4 (&r)[N], int q, const uint4 &ga)
+{
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    const uint4 &r0 = r[4 * q];
+    const uint4 &r1 = 4 * q + 1 < N ? r[4 * q + 1] : zero;
+    const uint4 &r2 = 4 * q + 2 < N ? r[4 * q + 2] : zero;
+    const uint4 &r3 = 4 * q + 3 < N ? r[4 * q + 3] : zero;
+    bf16x4_bits bcol[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        // column e of the four rows: the low or high halves of dword e/2
+        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+        const uint32_t b01 = __builtin_amdgcn_perm(dword_of(r1, e >> 1), dword_of(r0, e >> 1), sel);
+        const uint32_t b23 = __builtin_amdgcn_perm(dword_of(r3, e >> 1), dword_of(r2, e >> 1), sel);
+        bcol[e] = __builtin_bit_cast(bf16x4_bits, make_uint2(b01, b23));
+    }
+    const bf16x4_bits ahi = __builtin_bit_cast(bf16x4_bits, make_uint2(ga.x, ga.y));
+    const bf16x4_bits alo = __builtin_bit_cast(bf16x4_bits, make_uint2(ga.z, ga.w));
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        acc[e] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(ahi, bcol[e], acc[e], 0, 0, 0);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        acc[e] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(alo, bcol[e], acc[e], 0, 0, 0);
+}
+
+constexpr int RUN_GROUP = 4;    // tokens per matrix instruction (its M dimension) = positions per span
+
+template <int N, int WPB, bool NORM>
+__global__ __launch_bounds__(WPB * 64) __attribute__((amdgpu_waves_per_eu(2)))
+void fwd_bf16_run_kernel(FwdArgs a)
+{
+    constexpr int G = RUN_GROUP;
+    extern __shared__ uint4 smem[];
+    constexpr int NR = N < 4 ? 4 : N;
+    constexpr int NQ = NR / 4;
+    constexpr int LPJ = 64 / NR;
+    const int d = a.d;
+    const int kgroups = d >> 3;
+    const int layer = blockIdx.y;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int col0 = lane * 8;
+    const int T = a.T;
+    const int nch = (d + 511) >> 9;
+    const int nspans = (T + G - 1) / G;
+
+    const uint16_t *table = static_cast<const uint16_t *>(a.table) + (int64_t)layer * a.table_stride;
+    const int64_t act_off = (int64_t)layer * a.act_stride;
+    const uint16_t *hbase = static_cast<const uint16_t *>(a.h) + act_off;
+    const uint16_t *sbase = a.shared ? static_cast<const uint16_t *>(a.shared) + act_off : nullptr;
+    const uint16_t *rbase = a.residual ? static_cast<const uint16_t *>(a.residual) + act_off : nullptr;
+    uint16_t *obase = static_cast<uint16_t *>(a.out) + act_off;
+    const int32_t *rowsrc = a.slot ? a.slot : a.ids;
+    const int stride = gridDim.x * WPB;
+    if (!plan_ok(a))
+        return;
+    const int32_t *order = a.plan + plan_layout(T).order;
+    // the wave's gates behind the router weight, for the span being combined and for the next one:
+    // [2][G][NQ] pieces of 16 bytes = 4 experts x (hi, lo)
+    uint4 *gq = smem + router_lds_bytes(d, NR) / 16 + wave * (2 * G * NQ);
+
+    // Span descriptor: lane i holds position i's plan entry (token index, read-once flag in bit 31)
+    // and row block; -1 = no such position / id outside the table.
+    struct Span { int32_t t, row; };
+    auto load_span = [&](int s) {
+        Span sp{-1, -1};
+        const int p = s * G + lane;
+        if (s < nspans && lane < G && p < T) {
+            sp.t = order[p];
+            const int32_t rr = rowsrc[sp.t & ~PLAN_SINGLE];
+            sp.row = rr >= 0 && rr < a.rows ? rr : -1;
+        }
+        return sp;
+    };
+    auto span_len = [&](int s) { return s < nspans ? min(G, T - s * G) : 0; };
+    auto token_of = [&](const Span &sp, int i) { return (int)(__builtin_amdgcn_readlane(sp.t, i) & ~PLAN_SINGLE); };
+    // group starting at position i: row block (wave-uniform), length 1..4, read-once flag
+    struct Group { int32_t row; int len; bool single; };
+    auto group_at = [&](const Span &sp, int i, int np) {
+        Group g;
+        g.row = __builtin_amdgcn_readlane(sp.row, i);
+        g.single = (uint32_t)__builtin_amdgcn_readlane(sp.t, i) >> 31;
+        g.len = 1;
+        if (g.row >= 0) {
+#pragma unroll
+            for (int m = 1; m < G; ++m)
+                if (g.len == m && i + m < np && __builtin_amdgcn_readlane(sp.row, i + m) == g.row)
+                    g.len = m + 1;
+        }
+        return g;
+    };
+    uint4 r[N];
+    auto issue_rows = [&](const Group &g, int c) {
+        if (g.row < 0)
+            return;
+        const uint16_t *block = table + (int64_t)g.row * N * d;
+        if (g.single)
+            ring_load_buf<N, true>(r, block, d, lane * 16u, c << 10);
+        else
+            ring_load_buf<N, false>(r, block, d, lane * 16u, c << 10);
+    };
+    // router + softmax of position j of span sp (its router input is in h0 / h1); the gates go to gdst
+    // as hi + lo bf16 pairs
+    auto gates_of = [&](const Span &sp, int j, const uint4 &h0, const uint4 &h1, uint4 *gdst) {
+        const int t = token_of(sp, j);
+        const int32_t row = __builtin_amdgcn_readlane(sp.row, j);
+        if (row < 0 && lane == 0 && a.err_flag)
+            *a.err_flag = 1;
+        if (a.rows_dbg && layer == 0 && lane == 0)
+            a.rows_dbg[t] = row;
+        const float g = router_gate<NR, false, NORM, N>(smem, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1, a.ln_eps);
+        if ((lane & (LPJ - 1)) == 0) {
+            const int e = lane / LPJ;
+            if (a.gates_dbg && e < N)
+                a.gates_dbg[((int64_t)layer * T + t) * N + e] = g;
+            const uint32_t hi = f32_to_bf16_bits(g);
+            const uint32_t lo = f32_to_bf16_bits(g - __uint_as_float(hi << 16));
+            uint16_t *piece = reinterpret_cast<uint16_t *>(gdst) + ((j * NQ + (e >> 2)) << 3);
+            piece[e & 3] = (uint16_t)hi;
+            piece[4 + (e & 3)] = (uint16_t)lo;
+        }
+    };
+
+    int s = blockIdx.x * WPB + wave;
+    int ns = s + stride;
+    Span cur_sp = load_span(s), nx_sp = load_span(ns);
+    int np = span_len(s);
+    Group cur = np > 0 ? group_at(cur_sp, 0, np) : Group{-1, 1, false};
+    if (np > 0)
+        issue_rows(cur, 0);
+    uint4 h0 = make_uint4(0, 0, 0, 0), h1 = h0;
+    if (np > 0)
+        load_h2<false>(h0, h1, hbase + (int64_t)token_of(cur_sp, 0) * d, d, lane);
+
+    fill_router_lds<NR, N>(smem, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
+    __syncthreads();
+
+    // gates of the wave's first span; those of every later span are computed between the items of
+    // the span before it, while that span's row pieces are in flight
+    int buf = 0;
+    for (int j = 0; j < np; ++j) {
+        const uint4 c0 = h0, c1 = h1;
+        if (j + 1 < np)
+            load_h2<false>(h0, h1, hbase + (int64_t)token_of(cur_sp, j + 1) * d, d, lane);
+        gates_of(cur_sp, j, c0, c1, gq);
+    }
+    wave_lds_fence();
+
+    while (np > 0) {
+        const int nns = ns + stride;
+        const Span nn_sp = load_span(nns);      // descriptors run two spans ahead of their use
+        const int nnp = span_len(ns);
+        int rj = 0;                             // next position of the next span whose gates are due
+        if (nnp > 0)
+            load_h2<false>(h0, h1, hbase + (int64_t)token_of(nx_sp, 0) * d, d, lane);
+        const uint4 *gcur = gq + buf * (G * NQ);
+        uint4 *gnext = gq + (buf ^ 1) * (G * NQ);
+
+        int i = 0, c = 0;
+        while (i < np) {
+            // the item after this one: next chunk of the group, else the next group of the span, else
+            // the first group of the next span
+            Group nxt = cur;
+            int nc = c + 1;
+            bool more = true;
+            if (nc >= nch) {
+                nc = 0;
+                if (i + cur.len < np)
+                    nxt = group_at(cur_sp, i + cur.len, np);
+                else if (nnp > 0)
+                    nxt = group_at(nx_sp, 0, nnp);
+                else
+                    more = false;
+            }
+            const int cc = (c << 9) + col0;
+            const bool on = cc < d;
+
+            // shared / residual pieces of the group's tokens go in flight before the products
+            uint4 sv[G], rv[G];
+            int tok[G];
+#pragma unroll
+            for (int m = 0; m < G; ++m) {
+                sv[m] = make_uint4(0, 0, 0, 0);
+                rv[m] = make_uint4(0, 0, 0, 0);
+                tok[m] = 0;
+                if (m < cur.len) {
+                    tok[m] = token_of(cur_sp, i + m);
+                    const int64_t off = (int64_t)tok[m] * d + cc;
+                    if (on && sbase)
+                        sv[m] = ld16_stream<false>(sbase + off);
+                    if (on && (NORM || rbase))
+                        rv[m] = ld16_stream<false>((NORM ? hbase : rbase) + off);
+                }
+            }
+
+            f32x4 acc[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (cur.row >= 0) {
+                // lane l supplies the gates of position min(i + (l & 3), G - 1); rows of D past the
+                // group's length are not used
+                const uint4 *ga = gcur + min(i + (lane & 3), G - 1) * NQ;
+#pragma unroll
+                for (int q = 0; q < NQ; ++q)
+                    group_mfma<N>(acc, r, q, ga[q]);
+            }
+            // the row registers are free: fetch the next item's pieces unless they are the ones held
+            if (more && !(nxt.row == cur.row && nc == c))
+                issue_rows(nxt, nc);
+
+#pragma unroll
+            for (int m = 0; m < G; ++m) {
+                if (m < cur.len) {
+                    float o[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        o[e] = acc[e][m];
+                    add8(o, sv[m]);
+                    add8(o, rv[m]);
+                    if (on)
+                        st16_stream(obase + (int64_t)tok[m] * d + cc, pack8(o));
+                }
+            }
+            // while those pieces travel: the gates of one position of the next span
+            if (rj < nnp) {
+                const uint4 c0 = h0, c1 = h1;
+                if (rj + 1 < nnp)
+                    load_h2<false>(h0, h1, hbase + (int64_t)token_of(nx_sp, rj + 1) * d, d, lane);
+                gates_of(nx_sp, rj, c0, c1, gnext);
+                ++rj;
+            }
+            if (nc == 0)
+                i += cur.len;
+            c = nc;
+            cur = nxt;
+        }
+        for (; rj < nnp; ++rj) {
+            const uint4 c0 = h0, c1 = h1;
+            if (rj + 1 < nnp)
+                load_h2<false>(h0, h1, hbase + (int64_t)token_of(nx_sp, rj + 1) * d, d, lane);
+            gates_of(nx_sp, rj, c0, c1, gnext);
+        }
+        wave_lds_fence();
+        buf ^= 1;
+        s = ns;
+        ns = nns;
+        cur_sp = nx_sp;
+        nx_sp = nn_sp;
+        np = nnp;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // Generic path: any 1 <= N <= 64, fp32 or bf16 storage, no LDS-resident router weight.
 // One wavefront per token; lanes stride over k (router) and over columns (combine).
 // ------------------------------------------------------------------------------------------
@@ -213,13 +523,6 @@ template <> __device__ __forceinline__ float ldf<float>(const float *p) { return
 template <> __device__ __forceinline__ float ldf<uint16_t>(const uint16_t *p) { return bf16_to_f32(*p); }
 __device__ __forceinline__ void stf(float *p, float v) { *p = v; }
 __device__ __forceinline__ void stf(uint16_t *p, float v) { *p = (uint16_t)f32_to_bf16_bits(v); }
-
-__device__ __forceinline__ void wave_lds_fence()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
 
 template <typename E>
 __global__ __launch_bounds__(256) void fwd_generic_kernel(FwdArgs a)
@@ -343,10 +646,10 @@ int env_int(const char *name, int dflt)
 // tail).  Residency per CU is bounded by LDS and by registers (4 waves per SIMD for N <= 16,
 // 2 above).  Returns the number of workgroups per layer.
 template <int N, int WPB>
-int64_t grid_x(int items, int L, size_t lds)
+int64_t grid_x(int items, int L, size_t lds, int waves_per_cu = N <= 16 ? 16 : 8)
 {
     int per_cu = (int)(LDS_BYTES_PER_CU / lds);
-    const int wave_cap = (N <= 16 ? 16 : 8) / WPB;
+    const int wave_cap = waves_per_cu / WPB;
     if (per_cu > wave_cap)
         per_cu = wave_cap;
     per_cu = env_int("MOLE_FWD_WGS_PER_CU", per_cu);
@@ -390,6 +693,24 @@ mole_status launch_fast(const FwdArgs &a, hipStream_t stream)
                   : launch_fast<N, WPB, NTA, SPLIT, false>(a, stream);
 }
 
+template <int N, int WPB, bool NORM>
+mole_status launch_run(const FwdArgs &a, hipStream_t stream)
+{
+    constexpr int NR = N < 4 ? 4 : N;
+    const size_t lds = router_lds_bytes(a.d, NR) + (size_t)WPB * 2 * RUN_GROUP * NR * sizeof(float);
+    static size_t attr_set = 0;
+    if (lds > attr_set) {
+        MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_bf16_run_kernel<N, WPB, NORM>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = lds;
+    }
+    const int spans = (a.T + RUN_GROUP - 1) / RUN_GROUP;
+    dim3 grid((unsigned)grid_x<N, WPB>(spans, a.L, lds, 8), (unsigned)a.L);    // two waves per SIMD
+    hipLaunchKernelGGL((fwd_bf16_run_kernel<N, WPB, NORM>), grid, dim3(WPB * 64), lds, stream, a);
+    MOLE_HIP_CHECK(hipGetLastError());
+    return MOLE_OK;
+}
+
 template <int N>
 mole_status launch_fast_n(const FwdArgs &a, hipStream_t stream)
 {
@@ -397,6 +718,18 @@ mole_status launch_fast_n(const FwdArgs &a, hipStream_t stream)
     const size_t wbytes = (size_t)a.d * N * 2;
     int wpb = wbytes > 40 * 1024 ? 8 : 4;
     wpb = env_int("MOLE_FWD_WPB", wpb);
+    // large batches with a plan: runs of equal ids share one fetch of their rows and the weighted sum
+    // runs on the matrix pipe (not for N = 64: rows and gates of one chunk would not fit the register
+    // file).  Four waves per workgroup measured best at every N (two workgroups per CU at N = 32).
+    if constexpr (N <= 32) {
+        constexpr size_t gate_lds = (size_t)8 * 2 * RUN_GROUP * 32 * sizeof(float);
+        if (a.plan && env_int("MOLE_FWD_RUN", (int64_t)a.T * a.L >= 8192 ? 1 : 2) == 1 &&
+            router_lds_bytes(a.d, N < 4 ? 4 : N) + gate_lds <= LDS_BYTES_PER_CU) {
+            if (env_int("MOLE_FWD_WPB", 4) >= 8)
+                return a.norm ? launch_run<N, 8, true>(a, stream) : launch_run<N, 8, false>(a, stream);
+            return a.norm ? launch_run<N, 4, true>(a, stream) : launch_run<N, 4, false>(a, stream);
+        }
+    }
     // large batches: keep the read-once activations out of the caches (not with a plan: there a token's
     // activation rows are visited in id order and the plain load measures 2.5 % faster)
     const bool nta = env_int("MOLE_FWD_NTA", (int64_t)a.T * a.L >= 8192 && !a.plan ? 1 : 2) == 1;

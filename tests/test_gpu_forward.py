@@ -216,6 +216,62 @@ def test_heavy_repeats_with_plan():
     check_against_oracle(w, table, ids, li, dedup=True)
 
 
+# ---- the run kernel (plan + large batch by default; forced here on small shapes) -----------------------
+@pytest.mark.parametrize("wpb", ["4", "8"])
+@pytest.mark.parametrize("d,N,T,V,dist", [
+    (1024, 32, 203, 64, "zipf"),       # long runs of equal ids, two chunks
+    (1024, 16, 333, 4096, "zipf"),     # mostly distinct ids
+    (768, 16, 64, 40, "uniform"),      # d = 1.5 chunks
+    (520, 8, 37, 16, "uniform"),       # a chunk with a single active lane
+    (1544, 8, 50, 300, "zipf"),        # four chunks
+    (1024, 2, 70, 32, "uniform"),      # two experts padded to one group of four
+    (2048, 4, 77, 50, "zipf"),
+    (256, 8, 130, 7, "uniform"),       # one chunk, runs longer than a span
+    (1024, 16, 1, 100, "zipf"),
+    (512, 32, 3, 100, "zipf"),
+])
+def test_run_kernel_shapes(monkeypatch, wpb, d, N, T, V, dist):
+    monkeypatch.setenv("MOLE_FWD_RUN", "1")
+    monkeypatch.setenv("MOLE_FWD_WPB", wpb)
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, T=T, L=1, ids=dist, name=f"run d{d} N{N} T{T} V{V}")
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    li["W_r"] = wl.to_storage(wl.storage_to_f64(li["W_r"], w.dtype) * 5.0, w.dtype)
+    ids = ids.copy()
+    if T > 8:
+        ids[[2, T // 2]] = [V + 5, -3]                     # out-of-range ids: sorted last by the plan
+    for residual in (False, True):
+        check_against_oracle(w, table, ids, li, residual=residual, dedup=True)
+
+
+def test_run_kernel_saturated_router_returns_the_row_exactly(monkeypatch):
+    """A gate of exactly 1 splits into hi = 1, lo = 0, and 0 into 0 + 0: the row comes back bit for bit."""
+    monkeypatch.setenv("MOLE_FWD_RUN", "1")
+    N = 16
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=24, d=1024, N=N, T=96, L=1, ids="uniform")
+    table, ids = wl.random_table(w), wl.token_ids(w)
+    h = np.zeros((w.T, w.d), np.float32)
+    star, kk = np.arange(w.T) % N, np.arange(w.T)
+    h[np.arange(w.T), kk] = 1.0
+    Wr = np.zeros((w.d, N), np.float32)
+    Wr[kk, star] = 1.0e4
+    li = dict(h=wl.to_storage(h, w.dtype), W_r=wl.to_storage(Wr, w.dtype), shared=None, residual=None)
+    got = run_forward(w, table, ids, li, shared=False, dedup=True)
+    np.testing.assert_array_equal(wl.storage_to_f64(got["out"], w.dtype),
+                                  wl.storage_to_f64(table, w.dtype)[ids, star, :])
+
+
+def test_run_kernel_with_slot_indirection(monkeypatch):
+    """Offloaded mode: the plan orders tokens by id, the rows come from the compacted staging table."""
+    monkeypatch.setenv("MOLE_FWD_RUN", "1")
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=300, d=1024, N=16, T=200, L=1)
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    uniq, inv = np.unique(ids, return_inverse=True)
+    ref_out, ref_g, _, _ = oracle.lookup_forward(table, ids, li["h"], li["W_r"], li["shared"])
+    got = run_forward(w, np.ascontiguousarray(table[uniq]), ids, li, slot=inv.astype(np.int32), dedup=True)
+    np.testing.assert_array_equal(got["rows"], inv)
+    assert_close(wl.storage_to_f64(got["out"], w.dtype), ref_out, w.dtype, "run kernel, staged rows")
+
+
 @pytest.mark.parametrize("dedup", [False, True])
 def test_layer_batched_launch_equals_per_layer_calls(dedup):
     torch = torch_mod()

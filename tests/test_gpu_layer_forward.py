@@ -91,6 +91,20 @@ def test_launch_variants(monkeypatch, split, wpb, nta, d, N, T, V):
     check(w, wl.random_table(w), ids, inp, dedup=True, shared=False)
 
 
+@pytest.mark.parametrize("d,N,T,V", [(1024, 32, 203, 64), (1024, 16, 333, 4096), (1544, 8, 50, 30), (520, 4, 37, 16),
+                                     (1024, 2, 45, 20)])
+def test_run_kernel(monkeypatch, d, N, T, V):
+    """The kernel that large planned batches take, forced on small shapes: the residual is the state
+    itself, re-read per chunk."""
+    monkeypatch.setenv("MOLE_FWD_RUN", "1")
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, T=T, L=1, name=f"norm run d{d} N{N} T{T}")
+    ids = wl.token_ids(w).copy()
+    ids[T // 3] = -2
+    inp = inputs(w)
+    check(w, wl.random_table(w), ids, inp, dedup=True)
+    check(w, wl.random_table(w), ids, inp, dedup=True, shared=False)
+
+
 @pytest.mark.parametrize("d,N,T", [(64, 4, 256), (128, 16, 100), (32, 3, 17)])
 def test_fp32_shapes(d, N, T):
     w = wl.scaled(wl.CONFIGS["tiny"], V=777, d=d, N=N, T=T, name=f"norm fp32 d{d} N{N}")
