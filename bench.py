@@ -290,8 +290,8 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build measures ONE GPU (the MoLE lookup path of one device); --gpus {args.gpus} "
-              "is not supported -- token-parallel sharding with a replicated table needs no communication, "
-              "see DESIGN.md", file=sys.stderr)
+              "is not supported (token-parallel sharding with a replicated table would need no "
+              "communication: every GPU would run this same path on its share of the tokens)", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2503_15798_amd import accounting as acc

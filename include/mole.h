@@ -120,10 +120,10 @@ mole_status mole_dedup_ids(const int32_t *ids, int T, int64_t V,
  *   if it was outside [0, rows).  err_flag [1] dev nullable.
  *   flags: MOLE_FLAG_DEDUP -> workspace = plan of mole_dedup_ids(ids, T, ...) (and, if slot is
  *   given, slot must be that call's inv).  Without the flag workspace may be NULL.  The flag does not
- *   change what is computed.  Below T * L = 8192 (layer, token) pairs the result is also bit-identical
- *   to the call without it; above, bf16 calls with N in {2, 4, 8, 16, 32} take the weighted sum of
- *   tokens with equal ids together on the matrix pipe (gates enter as a pair of bf16 values, 16
- *   significant bits), which changes the summation order.
+ *   change what is computed.  The result is also bit-identical to the call without it, except for
+ *   bf16 calls with N = 32 and T >= 8192: those take the weighted sum of tokens with equal ids
+ *   together on the matrix pipe (gates enter as a pair of bf16 values, 16 significant bits), which
+ *   changes the summation order.
  * ---------------------------------------------------------------------------------------- */
 mole_status mole_lookup_forward(const void *table, const int32_t *ids, const int32_t *slot,
                                 const void *h, const void *W_r,

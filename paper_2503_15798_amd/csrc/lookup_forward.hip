@@ -232,18 +232,23 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// N 16-byte pieces (one per expert) of one 512-column chunk of a row block.  Lanes past the end of
-// the block read zeros (ragged last chunk); their results are never stored.
-template <int N, bool NT>
-__device__ __forceinline__ void ring_load_buf(uint4 (&r)[N], const uint16_t *block, int d, uint32_t lane_bytes,
+// Row pieces come through buffer loads: base and size of a row block sit in a scalar descriptor, the
+// expert's offset in a scalar register, the lane's column offset is the only vector operand.  Lanes
+// past the end of the block read zeros (ragged last chunk); their results are never stored.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t row_block_rsrc(const uint16_t *block, int bytes)
+{
+    constexpr int RAW_32BIT = 0x00020000;   // untyped buffer, 32-bit data format
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(block), 0, bytes, RAW_32BIT);
+}
+
+// the 16-byte pieces of experts J0 .. J0+CNT-1 of one 512-column chunk
+template <int N, int J0, int CNT, bool NT>
+__device__ __forceinline__ void rows_load_buf(uint4 (&r)[N], __amdgpu_buffer_rsrc_t rs, int d, uint32_t lane_bytes,
                                               int chunk_bytes)
 {
     typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
-    constexpr int RAW_32BIT = 0x00020000;   // untyped buffer, 32-bit data format
-    const __amdgpu_buffer_rsrc_t rs =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(block), 0, N * d * 2, RAW_32BIT);
 #pragma unroll
-    for (int j = 0; j < N; ++j) {
+    for (int j = J0; j < J0 + CNT && j < N; ++j) {
         const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, lane_bytes, j * d * 2 + chunk_bytes, NT ? 2 : 0);
         r[j] = make_uint4(v.x, v.y, v.z, v.w);
     }
@@ -257,17 +262,15 @@ __device__ __forceinline__ uint32_t dword_of(const uint4 &v, int i)
     return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w;
 }
 
-// acc[e][i] += sum over the 4 experts 4q .. 4q+3 of gate[token i][expert] * row[expert][lane's column e]
-// for the lane's 8 columns.  ga: this lane's A operand (gates of token lane & 3: hi in x, y; lo in z, w).
-template <int N>
-__device__ __forceinline__ void group_mfma(f32x4 (&acc)[8], const uint4 (&r)[N], int q, const uint4 &ga)
+// B operands of expert quad Q: for each of the lane's 8 columns, the values of experts 4Q .. 4Q+3
+template <int N, int Q>
+__device__ __forceinline__ void quad_columns(bf16x4_bits (&bcol)[8], const uint4 (&r)[N])
 {
     const uint4 zero = make_uint4(0, 0, 0, 0);
-    const uint4 &r0 = r[4 * q];
-    const uint4 &r1 = 4 * q + 1 < N ? r[4 * q + 1] : zero;
-    const uint4 &r2 = 4 * q + 2 < N ? r[4 * q + 2] : zero;
-    const uint4 &r3 = 4 * q + 3 < N ? r[4 * q + 3] : zero;
-    bf16x4_bits bcol[8];
+    const uint4 &r0 = r[4 * Q];
+    const uint4 &r1 = 4 * Q + 1 < N ? r[4 * Q + 1] : zero;
+    const uint4 &r2 = 4 * Q + 2 < N ? r[4 * Q + 2] : zero;
+    const uint4 &r3 = 4 * Q + 3 < N ? r[4 * Q + 3] : zero;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         // column e of the four rows: the low or high halves of dword e/2
@@ -276,6 +279,12 @@ __device__ __forceinline__ void group_mfma(f32x4 (&acc)[8], const uint4 (&r)[N],
         const uint32_t b23 = __builtin_amdgcn_perm(dword_of(r3, e >> 1), dword_of(r2, e >> 1), sel);
         bcol[e] = __builtin_bit_cast(bf16x4_bits, make_uint2(b01, b23));
     }
+}
+
+// acc[e][i] += sum over the 4 experts of a quad of gate[token i][expert] * row[expert][lane's column e].
+// ga: this lane's A operand (gates of token lane & 3: hi in x, y; lo in z, w).
+__device__ __forceinline__ void quad_products(f32x4 (&acc)[8], const bf16x4_bits (&bcol)[8], const uint4 &ga)
+{
     const bf16x4_bits ahi = __builtin_bit_cast(bf16x4_bits, make_uint2(ga.x, ga.y));
     const bf16x4_bits alo = __builtin_bit_cast(bf16x4_bits, make_uint2(ga.z, ga.w));
 #pragma unroll
@@ -286,12 +295,40 @@ __device__ __forceinline__ void group_mfma(f32x4 (&acc)[8], const uint4 (&r)[N],
         acc[e] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(alo, bcol[e], acc[e], 0, 0, 0);
 }
 
+// One item: the products of all expert quads with the held row pieces; each quad's registers are
+// refilled with the next item's pieces (if FETCH) as soon as its operands have been built, so those
+// loads travel while the rest of this item runs.
+template <int N, int Q>
+__device__ __forceinline__ void item_quads(f32x4 (&acc)[8], uint4 (&r)[N], const uint4 *ga, bool compute, bool fetch,
+                                           bool fetch_once, __amdgpu_buffer_rsrc_t next_rs, int d, uint32_t lane_bytes,
+                                           int next_chunk_bytes)
+{
+    constexpr int NQ = (N + 3) / 4;
+    if constexpr (Q < NQ) {
+        bf16x4_bits bcol[8];
+        if (compute)
+            quad_columns<N, Q>(bcol, r);
+        if (fetch) {
+            if (fetch_once)     // rows the plan marks as read-once: non-temporal
+                rows_load_buf<N, 4 * Q, 4, true>(r, next_rs, d, lane_bytes, next_chunk_bytes);
+            else
+                rows_load_buf<N, 4 * Q, 4, false>(r, next_rs, d, lane_bytes, next_chunk_bytes);
+        }
+        if (compute)
+            quad_products(acc, bcol, ga[Q]);
+        __builtin_amdgcn_sched_barrier(0);      // keep the quads apart: hoisting all operand builds would spill
+        item_quads<N, Q + 1>(acc, r, ga, compute, fetch, fetch_once, next_rs, d, lane_bytes, next_chunk_bytes);
+    }
+}
+
 constexpr int RUN_GROUP = 4;    // tokens per matrix instruction (its M dimension) = positions per span
 
-template <int N, int WPB, bool NORM>
+// RES: a residual is added (NORM: the state itself, else a.residual)
+template <int N, int WPB, bool NORM, bool RES>
 __global__ __launch_bounds__(WPB * 64) __attribute__((amdgpu_waves_per_eu(2)))
 void fwd_bf16_run_kernel(FwdArgs a)
 {
+    static_assert(RES || !NORM, "the norm variant always adds the state");
     constexpr int G = RUN_GROUP;
     extern __shared__ uint4 smem[];
     constexpr int NR = N < 4 ? 4 : N;
@@ -356,11 +393,11 @@ void fwd_bf16_run_kernel(FwdArgs a)
     auto issue_rows = [&](const Group &g, int c) {
         if (g.row < 0)
             return;
-        const uint16_t *block = table + (int64_t)g.row * N * d;
+        const __amdgpu_buffer_rsrc_t rs = row_block_rsrc(table + (int64_t)g.row * N * d, N * d * 2);
         if (g.single)
-            ring_load_buf<N, true>(r, block, d, lane * 16u, c << 10);
+            rows_load_buf<N, 0, N, true>(r, rs, d, lane * 16u, c << 10);
         else
-            ring_load_buf<N, false>(r, block, d, lane * 16u, c << 10);
+            rows_load_buf<N, 0, N, false>(r, rs, d, lane * 16u, c << 10);
     };
     // router + softmax of position j of span sp (its router input is in h0 / h1); the gates go to gdst
     // as hi + lo bf16 pairs
@@ -381,6 +418,30 @@ void fwd_bf16_run_kernel(FwdArgs a)
             uint16_t *piece = reinterpret_cast<uint16_t *>(gdst) + ((j * NQ + (e >> 2)) << 3);
             piece[e & 3] = (uint16_t)hi;
             piece[4 + (e & 3)] = (uint16_t)lo;
+        }
+    };
+
+    // shared / residual pieces of chunk c for the (up to) 4 tokens of the group at position i of span sp
+    uint4 sv[G], rv[RES ? G : 1];
+    int tok[G];
+    auto load_act = [&](const Span &sp, int i, int len, int c) {
+        const int cc = (c << 9) + col0;
+#pragma unroll
+        for (int m = 0; m < G; ++m) {
+            sv[m] = make_uint4(0, 0, 0, 0);
+            if constexpr (RES)
+                rv[m] = make_uint4(0, 0, 0, 0);
+            tok[m] = 0;
+            if (m < len) {
+                tok[m] = token_of(sp, i + m);
+                const int64_t off = (int64_t)tok[m] * d + cc;
+                if (cc < d && sbase)
+                    sv[m] = ld16_stream<false>(sbase + off);
+                if constexpr (RES) {
+                    if (cc < d)
+                        rv[m] = ld16_stream<false>((NORM ? hbase : rbase) + off);
+                }
+            }
         }
     };
 
@@ -408,6 +469,8 @@ void fwd_bf16_run_kernel(FwdArgs a)
         gates_of(cur_sp, j, c0, c1, gq);
     }
     wave_lds_fence();
+    if (np > 0)
+        load_act(cur_sp, 0, cur.len, 0);
 
     while (np > 0) {
         const int nns = ns + stride;
@@ -438,39 +501,20 @@ void fwd_bf16_run_kernel(FwdArgs a)
             const int cc = (c << 9) + col0;
             const bool on = cc < d;
 
-            // shared / residual pieces of the group's tokens go in flight before the products
-            uint4 sv[G], rv[G];
-            int tok[G];
-#pragma unroll
-            for (int m = 0; m < G; ++m) {
-                sv[m] = make_uint4(0, 0, 0, 0);
-                rv[m] = make_uint4(0, 0, 0, 0);
-                tok[m] = 0;
-                if (m < cur.len) {
-                    tok[m] = token_of(cur_sp, i + m);
-                    const int64_t off = (int64_t)tok[m] * d + cc;
-                    if (on && sbase)
-                        sv[m] = ld16_stream<false>(sbase + off);
-                    if (on && (NORM || rbase))
-                        rv[m] = ld16_stream<false>((NORM ? hbase : rbase) + off);
-                }
-            }
-
             f32x4 acc[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (cur.row >= 0) {
+            {
                 // lane l supplies the gates of position min(i + (l & 3), G - 1); rows of D past the
-                // group's length are not used
+                // group's length are not used.  The next item's pieces replace the held ones quad by
+                // quad unless they are the same (same row block, same chunk).
                 const uint4 *ga = gcur + min(i + (lane & 3), G - 1) * NQ;
-#pragma unroll
-                for (int q = 0; q < NQ; ++q)
-                    group_mfma<N>(acc, r, q, ga[q]);
+                const bool fetch = more && nxt.row >= 0 && !(nxt.row == cur.row && nc == c);
+                const __amdgpu_buffer_rsrc_t nrs =
+                    row_block_rsrc(table + (int64_t)(fetch ? nxt.row : 0) * N * d, N * d * 2);
+                item_quads<N, 0>(acc, r, ga, cur.row >= 0, fetch, nxt.single, nrs, d, lane * 16u, nc << 10);
             }
-            // the row registers are free: fetch the next item's pieces unless they are the ones held
-            if (more && !(nxt.row == cur.row && nc == c))
-                issue_rows(nxt, nc);
 
 #pragma unroll
             for (int m = 0; m < G; ++m) {
@@ -480,12 +524,23 @@ void fwd_bf16_run_kernel(FwdArgs a)
                     for (int e = 0; e < 8; ++e)
                         o[e] = acc[e][m];
                     add8(o, sv[m]);
-                    add8(o, rv[m]);
+                    if constexpr (RES)
+                        add8(o, rv[m]);
                     if (on)
                         st16_stream(obase + (int64_t)tok[m] * d + cc, pack8(o));
                 }
             }
-            // while those pieces travel: the gates of one position of the next span
+            // the next item's shared / residual pieces go in flight now: they travel during the gates
+            // below and the next item's products
+            if (more) {
+                if (nc != 0)
+                    load_act(cur_sp, i, cur.len, nc);
+                else if (i + cur.len < np)
+                    load_act(cur_sp, i + cur.len, nxt.len, 0);
+                else
+                    load_act(nx_sp, 0, nxt.len, 0);
+            }
+            // while the row pieces travel: the gates of one position of the next span
             if (rj < nnp) {
                 const uint4 c0 = h0, c1 = h1;
                 if (rj + 1 < nnp)
@@ -693,20 +748,20 @@ mole_status launch_fast(const FwdArgs &a, hipStream_t stream)
                   : launch_fast<N, WPB, NTA, SPLIT, false>(a, stream);
 }
 
-template <int N, int WPB, bool NORM>
+template <int N, int WPB, bool NORM, bool RES>
 mole_status launch_run(const FwdArgs &a, hipStream_t stream)
 {
     constexpr int NR = N < 4 ? 4 : N;
     const size_t lds = router_lds_bytes(a.d, NR) + (size_t)WPB * 2 * RUN_GROUP * NR * sizeof(float);
     static size_t attr_set = 0;
     if (lds > attr_set) {
-        MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_bf16_run_kernel<N, WPB, NORM>),
+        MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_bf16_run_kernel<N, WPB, NORM, RES>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = lds;
     }
     const int spans = (a.T + RUN_GROUP - 1) / RUN_GROUP;
     dim3 grid((unsigned)grid_x<N, WPB>(spans, a.L, lds, 8), (unsigned)a.L);    // two waves per SIMD
-    hipLaunchKernelGGL((fwd_bf16_run_kernel<N, WPB, NORM>), grid, dim3(WPB * 64), lds, stream, a);
+    hipLaunchKernelGGL((fwd_bf16_run_kernel<N, WPB, NORM, RES>), grid, dim3(WPB * 64), lds, stream, a);
     MOLE_HIP_CHECK(hipGetLastError());
     return MOLE_OK;
 }
@@ -718,16 +773,19 @@ mole_status launch_fast_n(const FwdArgs &a, hipStream_t stream)
     const size_t wbytes = (size_t)a.d * N * 2;
     int wpb = wbytes > 40 * 1024 ? 8 : 4;
     wpb = env_int("MOLE_FWD_WPB", wpb);
-    // large batches with a plan: runs of equal ids share one fetch of their rows and the weighted sum
-    // runs on the matrix pipe (not for N = 64: rows and gates of one chunk would not fit the register
-    // file).  Four waves per workgroup measured best at every N (two workgroups per CU at N = 32).
+    // Large planned batches at N = 32 (where the streaming kernel is bound by its vector instructions,
+    // not by memory): groups of equal ids share one fetch of their rows and the weighted sum runs on
+    // the matrix pipe.  Measured against the streaming kernel in plan order: faster from T = 8192 on at
+    // N = 32 (65 / 106 us against 70 / 125 us at T = 8192 / 16384, Zipf ids), slower at N <= 16 and on
+    // many-layer launches with few tokens per layer; MOLE_FWD_RUN = 1 / 2 forces / forbids it for any
+    // N <= 32 (N = 64: rows and gates of one chunk would not fit the register file).
     if constexpr (N <= 32) {
-        constexpr size_t gate_lds = (size_t)8 * 2 * RUN_GROUP * 32 * sizeof(float);
-        if (a.plan && env_int("MOLE_FWD_RUN", (int64_t)a.T * a.L >= 8192 ? 1 : 2) == 1 &&
+        constexpr size_t gate_lds = (size_t)4 * 2 * RUN_GROUP * 32 * sizeof(float);
+        if (a.plan && env_int("MOLE_FWD_RUN", N == 32 && a.T >= 8192 ? 1 : 2) == 1 &&
             router_lds_bytes(a.d, N < 4 ? 4 : N) + gate_lds <= LDS_BYTES_PER_CU) {
-            if (env_int("MOLE_FWD_WPB", 4) >= 8)
-                return a.norm ? launch_run<N, 8, true>(a, stream) : launch_run<N, 8, false>(a, stream);
-            return a.norm ? launch_run<N, 4, true>(a, stream) : launch_run<N, 4, false>(a, stream);
+            if (a.norm)
+                return launch_run<N, 4, true, true>(a, stream);
+            return a.residual ? launch_run<N, 4, false, true>(a, stream) : launch_run<N, 4, false, false>(a, stream);
         }
     }
     // large batches: keep the read-once activations out of the caches (not with a plan: there a token's

@@ -217,7 +217,6 @@ def test_heavy_repeats_with_plan():
 
 
 # ---- the run kernel (plan + large batch by default; forced here on small shapes) -----------------------
-@pytest.mark.parametrize("wpb", ["4", "8"])
 @pytest.mark.parametrize("d,N,T,V,dist", [
     (1024, 32, 203, 64, "zipf"),       # long runs of equal ids, two chunks
     (1024, 16, 333, 4096, "zipf"),     # mostly distinct ids
@@ -230,9 +229,8 @@ def test_heavy_repeats_with_plan():
     (1024, 16, 1, 100, "zipf"),
     (512, 32, 3, 100, "zipf"),
 ])
-def test_run_kernel_shapes(monkeypatch, wpb, d, N, T, V, dist):
+def test_run_kernel_shapes(monkeypatch, d, N, T, V, dist):
     monkeypatch.setenv("MOLE_FWD_RUN", "1")
-    monkeypatch.setenv("MOLE_FWD_WPB", wpb)
     w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, T=T, L=1, ids=dist, name=f"run d{d} N{N} T{T} V{V}")
     table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
     li["W_r"] = wl.to_storage(wl.storage_to_f64(li["W_r"], w.dtype) * 5.0, w.dtype)
