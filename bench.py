@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="decode410m")
+    ap.add_argument("--plan", action="store_true",
+                    help="the timed step is the forward given a plan of mole_dedup_ids (plans computed "
+                         "beforehand, one per id batch); for profiling that path")
     ap.add_argument("--no-extras", action="store_true", help="only the headline workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--only-build", action="store_true",
@@ -311,8 +314,14 @@ def main():
     # ------------------------------------------------------------------ headline workload
     L = Layers(w, torch, mb, wl)
 
+    if args.plan:
+        L.make_plans(stream)
+
     def step(i):
-        L.forward(i, stream)
+        if args.plan:
+            L.forward_planned(i, stream)
+        else:
+            L.forward(i, stream)
     ms_step = time_steps(torch, stream, step, args.steps, args.warmup)
     # the step is exactly one launch of the forward kernel, so the launch-to-launch average over the
     # timed region is that kernel's duration (an upper bound: it includes the gap between launches)
@@ -324,8 +333,10 @@ def main():
     head = rates(w, acc, ms_step, distinct)
     alg_bytes = acc.forward_bytes_per_token(w.d, w.N, w.elem_bytes) * w.T * w.L
     achieved = alg_bytes / (ms_kernel * 1e-3) / 1e9
-    kernel_tag = f"fwd_bf16_stream_{w.name}"
-    roofline = {"bound": "hbm", "kernel": "fwd_bf16_stream_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+    # the kernel the launcher picks for this call (large planned batches at N = 32 take the run kernel)
+    kernel = "fwd_bf16_run_kernel" if args.plan and w.N == 32 and w.T >= 8192 else "fwd_bf16_stream_kernel"
+    kernel_tag = f"{kernel[:-7]}_{w.name}" + ("_plan" if args.plan else "")
+    roofline = {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(kernel_tag),
                 "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": ms_kernel,
                 "moved_GBps": w.L * acc.forward_bytes_moved(w.T, int(round(distinct)), w.d, w.N, w.elem_bytes)
@@ -360,7 +371,8 @@ def main():
         "config": {"workload": w.name, "layers": w.L, "tokens_per_step": w.T, "V": w.V, "d": w.d, "N": w.N,
                    "ids": ("zipf(1.1)" if w.ids == "zipf" else w.ids) + ", 16 rotating batches", "mean_distinct_ids": distinct,
                    "table_bytes": table_bytes,
-                   "step": "router + softmax + gather + gate-weighted sum + shared add, all layers, one launch",
+                   "step": "router + softmax + gather + gate-weighted sum + shared add, all layers, one launch"
+                           + (", tokens visited by the plan of mole_dedup_ids (computed beforehand)" if args.plan else ""),
                    "decode_tokens_per_s": head["tokens_per_s"],
                    "algorithmic_GBps": head["algorithmic_GBps"], "moved_GBps": head["moved_GBps"]},
         "roofline": roofline,
