@@ -229,6 +229,168 @@ __global__ __launch_bounds__(DEDUP_THREADS) void dedup_kernel(const int32_t *__r
     }
 }
 
+// Batches of at most PER * 1024 tokens: every thread keeps its PER tokens (id, rank, place inside the
+// bucket) in registers, so the ids are read from memory once, and the contended counting pass runs once:
+// the atomic add that sizes the buckets also hands each token its place inside its bucket.  Counters
+// and staging area are always in LDS here.
+template <int PER>
+__global__ __launch_bounds__(DEDUP_THREADS) void dedup_kernel_regs(const int32_t *__restrict__ ids, int T, int V,
+                                                                     int32_t *__restrict__ uniq_out,
+                                                                     int32_t *__restrict__ inv_out,
+                                                                     int32_t *__restrict__ n_uniq_out,
+                                                                     int32_t *err_flag, int32_t *plan)
+{
+    extern __shared__ uint32_t sm[];
+    __shared__ int wave_sums[DEDUP_THREADS / 64];
+    __shared__ int s_bad;
+    const int W = (V + 31) >> 5;
+    uint32_t *bitmap = sm;
+    int *prefix = reinterpret_cast<int *>(sm + W);
+    const PlanLayout pl = plan_layout(T);
+    int *counters = reinterpret_cast<int *>(sm + 2 * W);     // [T + 2]: bucket sizes, then bucket starts
+    int *stage = counters + (T + 2);                         // [T]
+    const int tid = threadIdx.x;
+
+    // the thread's tokens: t = tid + u * 1024 (coalesced), loaded before LDS is cleared
+    int idv[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const int t = tid + u * DEDUP_THREADS;
+        idv[u] = t < T ? ids[t] : 0;
+    }
+    for (int w = tid; w < W; w += DEDUP_THREADS)
+        bitmap[w] = 0u;
+    for (int i = tid; i < T + 2; i += DEDUP_THREADS)
+        counters[i] = 0;
+    if (tid == 0)
+        s_bad = 0;
+    __syncthreads();
+
+    // 1. presence bits
+    int bad = 0;
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const int id = idv[u];
+        if (tid + u * DEDUP_THREADS >= T)
+            continue;
+        if (id < 0 || id >= V)
+            bad = 1;
+        else if (!(__atomic_load_n(&bitmap[id >> 5], __ATOMIC_RELAXED) & (1u << (id & 31))))
+            atomicOr(&bitmap[id >> 5], 1u << (id & 31));
+    }
+    if (bad)
+        s_bad = 1;
+    __syncthreads();
+
+    // 2. / 3. rank of every bitmap word, distinct ids in ascending order
+    const int per = (W + DEDUP_THREADS - 1) / DEDUP_THREADS;
+    const int w0 = min(tid * per, W), w1 = min(w0 + per, W);
+    int local = 0;
+    for (int w = w0; w < w1; ++w)
+        local += __popc(bitmap[w]);
+    int U = 0;
+    int run = block_exclusive_scan(local, wave_sums, &U);
+    for (int w = w0; w < w1; ++w) {
+        prefix[w] = run;
+        uint32_t bits = bitmap[w];
+        while (bits) {
+            const int b = __ffs(bits) - 1;
+            bits &= bits - 1;
+            stage[run++] = (w << 5) + b;
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < U; i += DEDUP_THREADS) {
+        const int id = stage[i];
+        uniq_out[i] = id;
+        plan[pl.uniq + i] = id;
+    }
+
+    // 4. inverse map; the atomic add that sizes bucket r also gives the token its place in it.
+    //    Bucket U collects the out-of-range tokens.
+    int bucket[PER], place[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const int t = tid + u * DEDUP_THREADS;
+        bucket[u] = U;
+        place[u] = 0;
+        if (t < T) {
+            const int id = idv[u];
+            int r = -1;
+            if (id >= 0 && id < V)
+                r = prefix[id >> 5] + __popc(bitmap[id >> 5] & ((1u << (id & 31)) - 1u));
+            inv_out[t] = r;
+            bucket[u] = r < 0 ? U : r;
+            place[u] = atomicAdd(&counters[bucket[u]], 1);
+        }
+    }
+    __syncthreads();    // also: `stage` has been copied out and may be reused
+
+    // 5. bucket starts: exclusive scan of the sizes, in place; counters[U + 1] = T
+    const int B = U + 1;
+    const int perb = (B + DEDUP_THREADS - 1) / DEDUP_THREADS;
+    const int b0 = min(tid * perb, B), b1 = min(b0 + perb, B);
+    int tok = 0;
+    for (int b = b0; b < b1; ++b)
+        tok += counters[b];
+    int tok_run = block_exclusive_scan(tok, wave_sums, nullptr);
+    for (int b = b0; b < b1; ++b) {
+        const int c = counters[b];
+        counters[b] = tok_run;
+        plan[pl.start + b] = tok_run;
+        tok_run += c;
+    }
+    if (tid == 0) {
+        counters[B] = T;
+        plan[pl.start + B] = T;
+    }
+    __syncthreads();
+
+    // 6. token indices into their buckets, through LDS so that the order leaves as full-width stores
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const int t = tid + u * DEDUP_THREADS;
+        if (t < T) {
+            const int b = bucket[u];
+            const int first = counters[b];
+            const bool single = b < U && counters[b + 1] - first == 1;
+            stage[first + place[u]] = (int)((uint32_t)t | (single ? PLAN_SINGLE : 0u));
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < T; i += DEDUP_THREADS)
+        plan[pl.order + i] = stage[i];
+
+    if (tid == 0) {
+        plan[0] = U;
+        plan[1] = 0;
+        plan[2] = T;
+        plan[3] = 0;
+        plan[4] = V;
+        plan[5] = PLAN_MAGIC;
+        *n_uniq_out = U;
+        if (s_bad && err_flag)
+            *err_flag = 1;
+    }
+}
+
+template <int PER>
+hipError_t launch_regs(size_t lds, hipStream_t stream, const int32_t *ids, int T, int V, int32_t *uniq, int32_t *inv,
+                       int32_t *n_uniq, int32_t *err_flag, int32_t *plan)
+{
+    static size_t attr_set = 0;
+    if (lds > attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dedup_kernel_regs<PER>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess)
+            return e;
+        attr_set = lds;
+    }
+    hipLaunchKernelGGL(dedup_kernel_regs<PER>, dim3(1), dim3(DEDUP_THREADS), lds, stream, ids, T, V, uniq, inv, n_uniq,
+                       err_flag, plan);
+    return hipGetLastError();
+}
+
 // LDS plan: bitmap and prefix always; the counters and the staging area when they fit
 size_t dedup_lds_bytes(int T, int64_t V, int *lds_counters, int *lds_stage)
 {
@@ -272,15 +434,33 @@ extern "C" mole_status mole_dedup_ids(const int32_t *ids, int T, int64_t V, int3
         return fail(MOLE_EINVAL, "mole_dedup_ids: workspace is not 16-byte aligned");
     int lds_counters = 0, lds_stage = 0;
     const size_t lds = dedup_lds_bytes(T, V, &lds_counters, &lds_stage);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    int32_t *plan = static_cast<int32_t *>(workspace);
+    // up to 16 tokens per thread with everything staged in LDS: the register-resident kernel
+    if (lds_stage && T <= 16 * DEDUP_THREADS && !getenv("MOLE_DEDUP_GENERIC")) {
+        const int per = (T + DEDUP_THREADS - 1) / DEDUP_THREADS;
+        hipError_t e;
+        if (per <= 1)
+            e = launch_regs<1>(lds, stream, ids, T, (int)V, uniq, inv, n_uniq, err_flag, plan);
+        else if (per <= 2)
+            e = launch_regs<2>(lds, stream, ids, T, (int)V, uniq, inv, n_uniq, err_flag, plan);
+        else if (per <= 4)
+            e = launch_regs<4>(lds, stream, ids, T, (int)V, uniq, inv, n_uniq, err_flag, plan);
+        else if (per <= 8)
+            e = launch_regs<8>(lds, stream, ids, T, (int)V, uniq, inv, n_uniq, err_flag, plan);
+        else
+            e = launch_regs<16>(lds, stream, ids, T, (int)V, uniq, inv, n_uniq, err_flag, plan);
+        MOLE_HIP_CHECK(e);
+        return MOLE_OK;
+    }
     static size_t attr_set = 0;
     if (lds > attr_set) {
         MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&dedup_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = lds;
     }
-    hipLaunchKernelGGL(dedup_kernel, dim3(1), dim3(DEDUP_THREADS), lds, static_cast<hipStream_t>(hip_stream),
-                       ids, T, (int)V, uniq, inv, n_uniq, err_flag, static_cast<int32_t *>(workspace),
-                       lds_counters, lds_stage);
+    hipLaunchKernelGGL(dedup_kernel, dim3(1), dim3(DEDUP_THREADS), lds, stream, ids, T, (int)V, uniq, inv, n_uniq,
+                       err_flag, plan, lds_counters, lds_stage);
     MOLE_HIP_CHECK(hipGetLastError());
     return MOLE_OK;
 }
