@@ -63,6 +63,22 @@ def test_dedup_matches_oracle(T, V, dist):
     check_plan(plan, ids, V, uniq, U)
 
 
+@pytest.mark.parametrize("T,V,dist", [(256, 50304, "zipf"), (16384, 50304, "zipf"), (17000, 50304, "uniform"),
+                                      (20000, 50304, "zipf")])
+def test_generic_kernel(monkeypatch, T, V, dist):
+    """The kernel for batches beyond 16 tokens per thread (or V too large for the LDS staging area),
+    forced on sizes the register-resident one would take, with and without its LDS staging."""
+    monkeypatch.setenv("MOLE_DEDUP_GENERIC", "1")
+    ids = wl.make_ids(T, V, seed=T + 1, dist=dist)
+    ids[T // 2] = V + 1
+    uniq, inv, U, err, plan = run_dedup(ids, V)
+    r_uniq, r_inv, r_U, r_err = oracle.dedup(ids, V)
+    assert U == r_U and err == r_err == 1
+    np.testing.assert_array_equal(uniq, r_uniq)
+    np.testing.assert_array_equal(inv, r_inv)
+    check_plan(plan, ids, V, uniq, U)
+
+
 def test_dedup_edge_cases():
     uniq, inv, U, err, plan = run_dedup(np.zeros((0,), np.int32), 100)
     assert U == 0 and err == 0 and plan[0] == 0 and plan[5] == 0x4D4F4C45
