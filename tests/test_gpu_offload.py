@@ -56,6 +56,74 @@ def test_fetch_then_forward(L, V, d, N, T, dtype):
             assert_close(wl.storage_to_f64(a[l], dtype), ref, dtype, f"staged forward layer {l}")
 
 
+@pytest.mark.parametrize("layout", ["layer-major", "id-major"])
+def test_full_size_offload_step_sampled(layout):
+    """The benchmark's offloaded step at its real size: 24 tables of 50304 x 16 x 1024 bf16 (39.6 GB) in
+    pinned host memory, 32 Zipf tokens.  Fetched rows are compared byte for byte with the host table,
+    the staged forward bit for bit with the forward on the device-resident tables, and sampled tokens
+    of three layers with the oracle."""
+    import gc
+    import torch
+    w = wl.CONFIGS["offload410m"]
+    L, V, N, d, T = w.L, w.V, w.N, w.d, w.T
+    tabs = torch.empty((L, V, N, d), dtype=torch.bfloat16, device="cuda")
+    for l in range(L):
+        wl.device_table(w, l, "cuda", out=tabs[l])
+    if layout == "layer-major":
+        host = torch.empty((L, V, N, d), dtype=torch.bfloat16, pin_memory=True)
+        host.copy_(tabs)
+    else:
+        host = torch.empty((V, L, N, d), dtype=torch.bfloat16, pin_memory=True)
+        for l in range(L):
+            host[:, l].copy_(tabs[l])
+    torch.cuda.synchronize()
+    ids = wl.token_ids(w)
+    lis = [wl.layer_inputs(w, l) for l in range(L)]
+    lis_d = {k: to_dev(np.stack([li[k] for li in lis]), w.dtype) for k in ("h", "W_r", "shared")}
+    ids_d = torch.from_numpy(ids).cuda()
+    uniq_d, inv_d = torch.empty_like(ids_d), torch.empty_like(ids_d)
+    nu_d = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    err_d = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    plan = torch.empty((mb.mole_dedup_workspace(T, V) // 4,), dtype=torch.int32, device="cuda")
+    mb.mole_dedup_ids(ids_d, T, V, uniq_d, inv_d, nu_d, err_d, plan)
+    U_cap = T
+    staging = torch.zeros((L, U_cap, N, d), dtype=torch.bfloat16, device="cuda")
+    if layout == "layer-major":
+        mb.mole_offload_fetch(host, V * N * d, uniq_d, nu_d, staging, U_cap * N * d, err_d, L, U_cap, V, d, N,
+                              mb.MOLE_BF16)
+    else:
+        mb.mole_offload_fetch_idmajor(host, uniq_d, nu_d, staging, U_cap * N * d, err_d, L, U_cap, V, d, N,
+                                      mb.MOLE_BF16)
+    torch.cuda.synchronize()
+    U = int(nu_d.item())
+    r_uniq, r_inv, r_U, _ = oracle.dedup(ids, V)
+    assert U == r_U and int(err_d.item()) == 0
+    uq = torch.from_numpy(r_uniq.astype(np.int64))
+    want = host[:, uq] if layout == "layer-major" else host[uq].transpose(0, 1)
+    assert torch.equal(staging[:, :U].cpu().view(torch.int16), want.contiguous().view(torch.int16))
+    assert not staging[:, U:].any()
+
+    out_staged, out_res = torch.zeros_like(lis_d["h"]), torch.zeros_like(lis_d["h"])
+    mb.mole_lookup_forward_layers(staging, U_cap * N * d, ids_d, inv_d, lis_d["h"], lis_d["W_r"], lis_d["shared"],
+                                  None, out_staged, T * d, None, None, err_d, L, T, U_cap, d, N, mb.MOLE_BF16)
+    mb.mole_lookup_forward_layers(tabs, V * N * d, ids_d, None, lis_d["h"], lis_d["W_r"], lis_d["shared"], None,
+                                  out_res, T * d, None, None, err_d, L, T, V, d, N, mb.MOLE_BF16)
+    torch.cuda.synchronize()
+    assert int(err_d.item()) == 0
+    a, b = to_host(out_staged, w.dtype), to_host(out_res, w.dtype)
+    np.testing.assert_array_equal(a, b)
+    sample = np.arange(T)
+    for layer in (0, 11, 23):
+        rows_host = to_host(tabs[layer][torch.from_numpy(ids[sample].astype(np.int64)).cuda()], w.dtype)
+        ref, _, _, _ = oracle.lookup_forward(rows_host, np.arange(len(sample), dtype=np.int32), lis[layer]["h"][sample],
+                                             lis[layer]["W_r"], lis[layer]["shared"][sample])
+        assert_close(wl.storage_to_f64(a[layer][sample], w.dtype), ref, w.dtype, f"offloaded step, layer {layer}")
+    del host, want
+    gc.collect()
+    if hasattr(torch._C, "_host_emptyCache"):
+        torch._C._host_emptyCache()         # pinned requests are rounded up to a power of two and cached
+
+
 def test_forward_straight_from_pinned_host_table():
     """The table pointer may itself be pinned host memory: rows then cross the link inside the forward."""
     import torch
