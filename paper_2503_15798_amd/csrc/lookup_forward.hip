@@ -208,22 +208,25 @@ void fwd_bf16_stream_kernel(FwdArgs a)
 
 // ------------------------------------------------------------------------------------------
 // Run kernel (needs the plan of mole_dedup_ids): the plan lists the tokens in id order, so tokens with
-// equal ids sit next to each other.  A wave takes G consecutive positions of that order (a span):
-//   1. router + softmax for each token of the span, as in the streaming kernel; the gates go to LDS,
-//      each split into two bf16 values hi + lo (hi = the gate rounded to bf16, lo = the rounded rest:
-//      16 significant bits, the products with bf16 table values are still exact in fp32);
-//   2. per 512-column chunk, the span is cut into groups of up to 4 positions with the same row block.
-//      The N row pieces of the chunk are fetched once per run (they stay in registers while the id
-//      does not change) and the gate-weighted sum of a whole group is taken on the matrix pipe:
-//      v_mfma_f32_4x4x4_16b_bf16 computes, in each of its 16 blocks of 4 lanes, a 4x4 product
-//      D[i][j] += sum_k A[i][k] B[k][j] where lane 4b+i supplies row i of A, lane 4b+j supplies column
-//      j of B and receives column j of D.  With A = the gates of the group's (up to) 4 tokens for 4
-//      experts and B = the lane's own column of those 4 experts' rows, every lane gets the sums of its
-//      own columns for 4 tokens at once, from bf16 table values as they are (no conversion on the
-//      vector ALU, which otherwise limits this kernel at N = 32: two instructions per table element).
-//   3. shared / residual are added and the result is rounded and stored per token, as elsewhere.
-// Row pieces come through buffer loads: base and size of the row block in a scalar descriptor, the
-// expert's offset in a scalar register, the lane's column offset the only vector operand.
+// equal ids sit next to each other.  A wave takes 4 consecutive positions of that order (a span) and
+// cuts them into groups with the same row block; an item is one 512-column chunk of one group:
+//   * the N row pieces of the chunk are fetched once for the whole group, and the gate-weighted sums
+//     of its (up to) 4 tokens are taken together on the matrix pipe: v_mfma_f32_4x4x4_16b_bf16
+//     computes, in each of its 16 blocks of 4 lanes, a 4x4 product D[i][j] += sum_k A[i][k] B[k][j]
+//     where lane 4b+i supplies row i of A, lane 4b+j supplies column j of B and receives column j of
+//     D.  With A = the gates of the group's tokens for 4 experts and B = the lane's own column of
+//     those 4 experts' rows, every lane gets the sums of its own columns for 4 tokens at once, from
+//     bf16 table values as they are (no conversion on the vector ALU, which is what limits the
+//     streaming kernel at N = 32: two instructions per table element);
+//   * the matrix instruction takes bf16 operands, so each gate is split into hi + lo (hi = the gate
+//     rounded to bf16, lo = the rounded rest: 16 significant bits; the products with bf16 table
+//     values are still exact in fp32);
+//   * router and softmax are the streaming kernel's; the gates of a span are computed one position
+//     at a time between the items of the span before it and handed over through LDS;
+//   * the registers of an expert quad are refilled with the next item's pieces as soon as the
+//     quad's operands have been built, and the next item's shared / residual pieces are requested
+//     after this item's stores, so both travel while this item and the gates run;
+//   * shared / residual are added and the result is rounded and stored per token, as elsewhere.
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ void wave_lds_fence()
 {
