@@ -86,6 +86,9 @@ def test_tiny_fp32_layer():
     (64, 1, 40, 100),          # generic path
     (1024, 5, 33, 256),        # generic path, N not a power of two
     (512, 12, 31, 256),
+    (4096, 16, 20, 64),        # router weight of 131 KB: one workgroup per CU
+    (8192, 16, 10, 32),        # router weight too large for LDS: generic path
+    (4096, 32, 12, 32),        # the same at N = 32
 ])
 @pytest.mark.parametrize("residual", [False, True])
 def test_bf16_shapes(d, N, T, V, residual):
@@ -228,6 +231,8 @@ def test_heavy_repeats_with_plan():
     (256, 8, 130, 7, "uniform"),       # one chunk, runs longer than a span
     (1024, 16, 1, 100, "zipf"),
     (512, 32, 3, 100, "zipf"),
+    (2048, 32, 40, 10, "uniform"),     # N = 32 with a router weight of 132 KB: one workgroup per CU
+    (4096, 32, 12, 8, "uniform"),      # too large for the run kernel's LDS: falls back to the generic path
 ])
 def test_run_kernel_shapes(monkeypatch, d, N, T, V, dist):
     monkeypatch.setenv("MOLE_FWD_RUN", "1")
