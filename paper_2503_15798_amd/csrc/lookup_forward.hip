@@ -77,6 +77,8 @@ void fwd_bf16_stream_kernel(FwdArgs a)
     extern __shared__ uint4 smem[];
     constexpr int NR = N < 4 ? 4 : N;   // experts the router is computed for (N = 2 is padded to 4)
     constexpr int LPJ = 64 / NR;        // lanes per expert after the fold
+    constexpr int R = N > 32 ? 32 : N;  // row registers: at N = 64 the experts of a chunk pass through in two halves
+    constexpr int H = N / R;
 #ifndef MOLE_FWD_HOLD_X
 #define MOLE_FWD_HOLD_X (N != 16 || !NTA)
 #endif
@@ -114,13 +116,13 @@ void fwd_bf16_stream_kernel(FwdArgs a)
     int cbase = SPLIT ? (item % nch) << 9 : 0;      // first column of this item
     int64_t row = item < n_items ? (int64_t)__builtin_amdgcn_readfirstlane(rowsrc[cur.t]) : -1;
     bool valid = row >= 0 && row < a.rows;
-    uint4 r[N];
+    uint4 r[R];
     if (valid) {
         const uint16_t *rp0 = table + row * (int64_t)N * d;
         if (cur.single)
-            ring_load<N, true>(r, rp0, d, min(cbase + col0, dlast));
+            ring_load<R, true>(r, rp0, d, min(cbase + col0, dlast));
         else
-            ring_load<N, false>(r, rp0, d, min(cbase + col0, dlast));
+            ring_load<R, false>(r, rp0, d, min(cbase + col0, dlast));
     }
     uint4 h0, h1;
     load_h2<NTA>(h0, h1, hbase + (int64_t)cur.t * d, d, lane);
@@ -148,10 +150,12 @@ void fwd_bf16_stream_kernel(FwdArgs a)
         // the next token's h goes in flight now; its latency hides behind this token's combine
         load_h2<NTA>(h0, h1, hbase + (int64_t)nxt.t * d, d, lane);
         // gates into scalar registers: expert j's gate sits in lane j * (64/N)
-        float gs[N];
+        float gs[R];
+        if constexpr (H == 1) {
 #pragma unroll
-        for (int j = 0; j < N; ++j)
-            gs[j] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, g), j * LPJ));
+            for (int j = 0; j < N; ++j)
+                gs[j] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, g), j * LPJ));
+        }
 
         const uint16_t *rp = table + (valid ? row : 0) * (int64_t)N * d;
         const uint16_t *nrp = table + (nvalid ? nrow : 0) * (int64_t)N * d;
@@ -180,19 +184,45 @@ void fwd_bf16_stream_kernel(FwdArgs a)
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 acc[e] = 0.f;
-            if (valid) {
+            if constexpr (H == 1) {
+                if (valid) {
+    #pragma unroll
+                    for (int j = 0; j < N; ++j)
+                        fma8(acc, gs[j], r[j]);
+                }
+                // refill the ring: next chunk of this item, or the first chunk of the wave's next item
+                const uint16_t *fb = last ? nrp : rp;                      // wave-uniform
+                const int fcol = min(last ? ncbase + col0 : cc + 512, dlast);
+                if (last ? nvalid : valid) {
+                    if (last ? nxt.single : cur.single)
+                        ring_load<R, true>(r, fb, d, fcol);
+                    else
+                        ring_load<R, false>(r, fb, d, fcol);
+                }
+            } else {
+                // N = 64: the chunk's experts pass through the row registers in halves of 32
 #pragma unroll
-                for (int j = 0; j < N; ++j)
-                    fma8(acc, gs[j], r[j]);
-            }
-            // refill the ring: next chunk of this item, or the first chunk of the wave's next item
-            const uint16_t *fb = last ? nrp : rp;                      // wave-uniform
-            const int fcol = min(last ? ncbase + col0 : cc + 512, dlast);
-            if (last ? nvalid : valid) {
-                if (last ? nxt.single : cur.single)
-                    ring_load<N, true>(r, fb, d, fcol);
-                else
-                    ring_load<N, false>(r, fb, d, fcol);
+                for (int hf = 0; hf < H; ++hf) {
+#pragma unroll
+                    for (int j = 0; j < R; ++j)
+                        gs[j] = __builtin_bit_cast(
+                            float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, g), (hf * R + j) * LPJ));
+                    if (valid) {
+#pragma unroll
+                        for (int j = 0; j < R; ++j)
+                            fma8(acc, gs[j], r[j]);
+                    }
+                    // refill: the next half of this chunk, else the next chunk / the wave's next item
+                    const bool more_halves = hf + 1 < H;
+                    const uint16_t *fb = more_halves ? rp + (int64_t)(hf + 1) * R * d : (last ? nrp : rp);
+                    const int fcol = min(more_halves ? cc : (last ? ncbase + col0 : cc + 512), dlast);
+                    if (more_halves || !last ? valid : nvalid) {
+                        if (more_halves || !last ? cur.single : nxt.single)
+                            ring_load<R, true>(r, fb, d, fcol);
+                        else
+                            ring_load<R, false>(r, fb, d, fcol);
+                    }
+                }
             }
             add8(acc, sv);
             add8(acc, rv);

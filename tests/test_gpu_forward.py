@@ -80,6 +80,8 @@ def test_tiny_fp32_layer():
     (2048, 4, 77, 1024),       # 1B-shaped
     (256, 8, 130, 512),
     (128, 64, 50, 300),
+    (1024, 64, 75, 300),       # N = 64: the experts of a chunk pass through the row registers in two halves
+    (520, 64, 9, 64),
     (520, 16, 9, 64),          # d = 512 + 8: a chunk with a single active lane
     (1024, 2, 70, 512),        # two experts: the router is padded to four, the extra gates must be exactly 0
     (520, 2, 9, 64),
@@ -100,7 +102,8 @@ def test_bf16_shapes(d, N, T, V, residual):
 
 @pytest.mark.parametrize("split", ["1", "2"])
 @pytest.mark.parametrize("wpb", ["4", "8"])
-@pytest.mark.parametrize("d,N,T,V", [(1024, 16, 333, 4096), (768, 16, 64, 4096), (1544, 8, 50, 300), (1024, 32, 203, 2048)])
+@pytest.mark.parametrize("d,N,T,V", [(1024, 16, 333, 4096), (768, 16, 64, 4096), (1544, 8, 50, 300), (1024, 32, 203, 2048),
+                                     (1024, 64, 41, 100)])
 def test_launch_variants(monkeypatch, split, wpb, d, N, T, V):
     """Both item granularities (whole token / one 512-column chunk) and both workgroup widths."""
     monkeypatch.setenv("MOLE_FWD_SPLIT", split)

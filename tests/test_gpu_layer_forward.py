@@ -63,6 +63,7 @@ def check(w, table, ids, inp, shared=True, dedup=False, eps=EPS):
     (1544, 8, 50, 300),        # ragged third chunk
     (256, 8, 130, 512),
     (128, 64, 50, 300),
+    (1024, 64, 40, 100),       # N = 64: two halves of experts per chunk
     (520, 16, 9, 64),          # a chunk with a single active lane
     (64, 1, 40, 100),          # generic kernel
     (1024, 5, 33, 256),        # generic kernel, N not a power of two
