@@ -612,9 +612,42 @@ template <> __device__ __forceinline__ float ldf<uint16_t>(const uint16_t *p) { 
 __device__ __forceinline__ void stf(float *p, float v) { *p = v; }
 __device__ __forceinline__ void stf(uint16_t *p, float v) { *p = (uint16_t)f32_to_bf16_bits(v); }
 
+// 16-byte pieces of E: 8 bf16 or 4 fp32 values
+template <typename E> struct Piece;
+template <> struct Piece<uint16_t> {
+    static constexpr int VEC = 8;
+    static __device__ __forceinline__ void unpack(float (&v)[8], const uint4 &p)
+    {
+        v[0] = bf16lo(p.x); v[1] = bf16hi(p.x); v[2] = bf16lo(p.y); v[3] = bf16hi(p.y);
+        v[4] = bf16lo(p.z); v[5] = bf16hi(p.z); v[6] = bf16lo(p.w); v[7] = bf16hi(p.w);
+    }
+    static __device__ __forceinline__ uint4 pack(const float (&v)[8])
+    {
+        return make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]));
+    }
+};
+template <> struct Piece<float> {
+    static constexpr int VEC = 4;
+    static __device__ __forceinline__ void unpack(float (&v)[4], const uint4 &p)
+    {
+        v[0] = __uint_as_float(p.x); v[1] = __uint_as_float(p.y); v[2] = __uint_as_float(p.z); v[3] = __uint_as_float(p.w);
+    }
+    static __device__ __forceinline__ uint4 pack(const float (&v)[4])
+    {
+        return make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
+    }
+};
+
+// One wavefront per token.  Router: lanes stride over k and keep the partial logits of 16 experts at a
+// time (router rows are read in 16-byte pieces when a row of N values is a whole number of pieces);
+// the 64 lanes' partial sums are folded with the butterfly of the streaming kernel and the logits meet
+// in LDS for the softmax.  Combine: 16-byte pieces of the table rows, 8 rows in flight per lane, the
+// gates broadcast from LDS.
 template <typename E>
 __global__ __launch_bounds__(256) void fwd_generic_kernel(FwdArgs a)
 {
+    constexpr int VEC = Piece<E>::VEC;
+    constexpr int JB = 16;                  // experts per router pass
     __shared__ float gls[4][64];
     const int d = a.d, N = a.N;
     const int layer = blockIdx.y;
@@ -637,6 +670,7 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(FwdArgs a)
     const E *rbase = a.residual ? static_cast<const E *>(a.residual) + act_off : nullptr;
     E *obase = static_cast<E *>(a.out) + act_off;
     const int32_t *rowsrc = a.slot ? a.slot : a.ids;
+    const bool row_pieces = (N % VEC) == 0;     // router rows start on 16-byte boundaries
 
     for (int item = blockIdx.x * 4 + wave; item < a.T; item += gridDim.x * 4) {
         const int t = visit(order, item).t;
@@ -647,39 +681,53 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(FwdArgs a)
         if (a.rows_dbg && layer == 0 && lane == 0)
             a.rows_dbg[t] = valid ? row : -1;
         const E *rp = table + (valid ? row : 0) * (int64_t)N * d;
-
         const E *hr = hbase + (int64_t)t * d;
+
         float rs = 1.f;            // with a norm in front of the router: 1 / rms of this token's state
         if (norm) {
             float ss = 0.f;
             for (int k = lane; k < d; k += 64)
                 ss = fmaf(ldf(hr + k), ldf(hr + k), ss);
-#pragma unroll
-            for (int w = 32; w >= 1; w >>= 1)
-                ss += __shfl_xor(ss, w);
+            ss = span_reduce<32, 1, OpAdd>(ss);
             rs = 1.0f / sqrtf(ss / (float)d + a.ln_eps);
         }
-        float zmine = -INFINITY;   // lane j keeps logit j
-        for (int j = 0; j < N; ++j) {
-            float p = 0.f;
-            for (int k = lane; k < d; k += 64)
-                p = fmaf(ldf(hr + k) * rs, ldf(Wr + (int64_t)k * N + j), p);
+        // logits, 16 experts per pass; lane j of the pass's 16 ends up writing logit jb + j
+        for (int jb = 0; jb < N; jb += JB) {
+            float z[JB];
 #pragma unroll
-            for (int w = 32; w >= 1; w >>= 1)
-                p += __shfl_xor(p, w);
-            if (lane == j)
-                zmine = p;
+            for (int j = 0; j < JB; ++j)
+                z[j] = 0.f;
+            for (int k = lane; k < d; k += 64) {
+                const float hk = ldf(hr + k);
+                const E *wk = Wr + (int64_t)k * N + jb;
+                if (row_pieces) {
+#pragma unroll
+                    for (int p = 0; p < JB / VEC; ++p) {
+                        if (jb + p * VEC < N) {
+                            float w[VEC];
+                            Piece<E>::unpack(w, *reinterpret_cast<const uint4 *>(wk + p * VEC));
+#pragma unroll
+                            for (int e = 0; e < VEC; ++e)
+                                z[p * VEC + e] = fmaf(hk, w[e], z[p * VEC + e]);
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < JB; ++j)
+                        if (jb + j < N)
+                            z[j] = fmaf(hk, ldf(wk + j), z[j]);
+                }
+            }
+            const float zz = Fold<JB, 32>::run(z, lane);      // logit jb + (lane >> 2), in all 4 lanes of the group
+            if ((lane & 3) == 0 && jb + (lane >> 2) < N)
+                gl[jb + (lane >> 2)] = zz * rs;
         }
-        float m = zmine;
-#pragma unroll
-        for (int w = 32; w >= 1; w >>= 1)
-            m = fmaxf(m, __shfl_xor(m, w));
-        const float e = (lane < N) ? expf(zmine - m) : 0.f;
-        float s = e;
-#pragma unroll
-        for (int w = 32; w >= 1; w >>= 1)
-            s += __shfl_xor(s, w);
-        const float g = e / s;
+        wave_lds_fence();
+        const float zmine = lane < N ? gl[lane] : -INFINITY;   // lane j keeps logit j
+        const float m = span_reduce<32, 1, OpMax>(zmine);
+        const float e = lane < N ? expf(zmine - m) : 0.f;
+        const float g = e / span_reduce<32, 1, OpAdd>(e);
+        wave_lds_fence();
         if (lane < N) {
             gl[lane] = g;
             if (a.gates_dbg)
@@ -687,19 +735,46 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(FwdArgs a)
         }
         wave_lds_fence();
 
-        for (int c = lane; c < d; c += 64) {
-            float acc = 0.f;
-            if (valid)
-                for (int j = 0; j < N; ++j)
-                    acc = fmaf(gl[j], ldf(rp + (int64_t)j * d + c), acc);
-            const int64_t off = (int64_t)t * d + c;
-            if (sbase)
-                acc += ldf(sbase + off);
-            if (norm)
-                acc += ldf(hr + c);
-            else if (rbase)
-                acc += ldf(rbase + off);
-            stf(obase + off, acc);
+        for (int c0 = lane * VEC; c0 < d; c0 += 64 * VEC) {
+            float acc[VEC];
+#pragma unroll
+            for (int e2 = 0; e2 < VEC; ++e2)
+                acc[e2] = 0.f;
+            if (valid) {
+                for (int j0 = 0; j0 < N; j0 += 8) {
+                    uint4 piece[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        piece[u] = j0 + u < N ? *reinterpret_cast<const uint4 *>(rp + (int64_t)(j0 + u) * d + c0)
+                                              : make_uint4(0, 0, 0, 0);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        if (j0 + u < N) {
+                            const float gj = gl[j0 + u];
+                            float v[VEC];
+                            Piece<E>::unpack(v, piece[u]);
+#pragma unroll
+                            for (int e2 = 0; e2 < VEC; ++e2)
+                                acc[e2] = fmaf(gj, v[e2], acc[e2]);
+                        }
+                    }
+                }
+            }
+            const int64_t off = (int64_t)t * d + c0;
+            float v[VEC];
+            if (sbase) {
+                Piece<E>::unpack(v, *reinterpret_cast<const uint4 *>(sbase + off));
+#pragma unroll
+                for (int e2 = 0; e2 < VEC; ++e2)
+                    acc[e2] += v[e2];
+            }
+            if (norm || rbase) {
+                Piece<E>::unpack(v, *reinterpret_cast<const uint4 *>((norm ? hr + c0 : rbase + off)));
+#pragma unroll
+                for (int e2 = 0; e2 < VEC; ++e2)
+                    acc[e2] += v[e2];
+            }
+            *reinterpret_cast<uint4 *>(obase + off) = Piece<E>::pack(acc);
         }
         wave_lds_fence();
     }
