@@ -459,6 +459,14 @@ def extras(args, torch, mb, wl, acc, stream, L):
         out["offload410m"] = {"skipped": repr(e)}
     release_pinned(torch)
 
+    # ---- the same with NF4 tables: codes and scales of all layers in pinned host memory ----
+    try:
+        out["offload410m_nf4"] = offload_nf_bench(torch, mb, wl, stream, L, steps, warm, 4, 1024, 4)
+    except Exception as e:
+        traceback.print_exc(file=sys.stderr)
+        out["offload410m_nf4"] = {"skipped": repr(e)}
+    release_pinned(torch)
+
     # smaller decode batches on the same tables (latency-bound: microseconds are the result)
     for T in (32, 1):
         ww = wl.scaled(w, T=T, name=f"decode410m_t{T}")
@@ -668,6 +676,59 @@ def offload_bench(torch, mb, wl, acc, stream, L, steps, warm):
         "double_buffered_fetch_GBps": fetched / (ms_pipe * 1e-3) / 1e9,
     }
     del host_id, sets
+    return res
+
+
+def offload_nf_bench(torch, mb, wl, stream, L, steps, warm, bits, block, sbytes):
+    """Offloaded mode with a quantised table (Sec. 5.5 / Table 8 of the paper: quantising the LUT cuts the
+    bytes loaded per token): dedup + fetch of the distinct ids' code and scale rows of all layers from
+    pinned host memory + dequantising forward on the staged rows."""
+    import numpy as np
+    w = wl.CONFIGS["offload410m"]
+    T, U_cap = w.T, w.T
+    L.quantize(bits, block, sbytes)
+    code_row, scale_row = w.N * w.d * bits // 8, w.N * (w.d // block)
+    host_codes = L.nf["codes"][:, :w.V * code_row].cpu().pin_memory()
+    host_scales = L.nf["scales"][:, :w.V * scale_row * sbytes].cpu().pin_memory()
+    del L.nf
+    torch.cuda.empty_cache()
+    ids_host = np.stack([wl.token_ids(w, b) for b in range(N_ID_BATCHES)])
+    ids = torch.from_numpy(ids_host).cuda()
+    uniq = torch.empty((T,), dtype=torch.int32, device="cuda")
+    inv = torch.empty((T,), dtype=torch.int32, device="cuda")
+    nu = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    err = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    plan = torch.empty((mb.mole_dedup_workspace(T, w.V) // 4,), dtype=torch.int32, device="cuda")
+    st_codes = torch.empty((w.L, U_cap * code_row), dtype=torch.uint8, device="cuda")
+    st_scales = torch.empty((w.L, U_cap * scale_row * sbytes), dtype=torch.uint8, device="cuda")
+    h, sh, o = L.h[:, :T].contiguous(), L.shared[:, :T].contiguous(), L.out[:, :T].contiguous()
+
+    def fetch(i):
+        mb.mole_offload_fetch_nf(host_codes, w.V * code_row, host_scales, w.V * scale_row, uniq, nu, st_codes,
+                                 U_cap * code_row, st_scales, U_cap * scale_row, err, w.L, U_cap, w.V, w.d, w.N, bits,
+                                 block, sbytes, stream=stream)
+
+    def full(i):
+        mb.mole_dedup_ids(ids[i % N_ID_BATCHES], T, w.V, uniq, inv, nu, err, plan, stream=stream)
+        fetch(i)
+        mb.mole_lookup_forward_nf(st_codes, U_cap * code_row, st_scales, U_cap * scale_row, ids[i % N_ID_BATCHES], inv,
+                                  h, L.W_r, sh, None, o, T * w.d, None, None, err, w.L, T, U_cap, w.d, w.N, bits, block,
+                                  sbytes, 0, None, stream=stream)
+    ms_full = time_steps(torch, stream, full, steps, warm)
+    mb.mole_dedup_ids(ids[0], T, w.V, uniq, inv, nu, err, plan, stream=stream)
+    ms_fetch = time_steps(torch, stream, fetch, steps, warm)
+    if int(err.item()) != 0:
+        raise RuntimeError("error flag set in the offloaded NF step")
+    u0 = len(np.unique(ids_host[0]))
+    row_bytes = code_row + scale_row * sbytes
+    res = {"step": "dedup + fetch of the distinct ids' NF code and scale rows of all 24 layers from pinned host "
+                   "memory + dequantising forward on the staged rows",
+           "bits": bits, "block": block, "scale_bytes": sbytes, "tokens": T, "ms": ms_full,
+           "tokens_per_s": T / (ms_full * 1e-3), "fetch_only_ms": ms_fetch,
+           "fetched_bytes_per_id": w.L * row_bytes, "bf16_bytes_per_id": w.L * w.N * w.d * 2,
+           "fetch_GBps": u0 * w.L * row_bytes / (ms_fetch * 1e-3) / 1e9,
+           "host_table_bytes": int(host_codes.numel() + host_scales.numel())}
+    del host_codes, host_scales
     return res
 
 

@@ -286,6 +286,22 @@ mole_status mole_lookup_forward_nf(const void *codes, int64_t codes_stride,
                                    int bits, int block, int scale_bytes, unsigned flags,
                                    const void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Offloaded mode with a quantised table: the codes [L, V, N, d*bits/8] and scales [L, V, N, d/block]
+ * of all layers sit in pinned, GPU-mapped host memory; the rows of the distinct ids (uniq / n_uniq of
+ * mole_dedup_ids) are copied to staging_codes [L, U_cap, N, d*bits/8] and staging_scales
+ * [L, U_cap, N, d/block] on the device, ready for mole_lookup_forward_nf with slot = inv and
+ * rows = U_cap.  Code strides count BYTES per layer, scale strides ELEMENTS per layer, as in
+ * mole_lookup_forward_nf (ignored for L == 1).  Row sizes, strides and addresses must be even; the copy
+ * runs in units of 16 bytes when all of them allow it.  *n_uniq > U_cap sets *err_flag = 1 and
+ * fetches the first U_cap ids, as mole_offload_fetch does. */
+mole_status mole_offload_fetch_nf(const void *host_codes, int64_t host_codes_stride,
+                                  const void *host_scales, int64_t host_scales_stride,
+                                  const int32_t *uniq, const int32_t *n_uniq,
+                                  void *staging_codes, int64_t staging_codes_stride,
+                                  void *staging_scales, int64_t staging_scales_stride,
+                                  int32_t *err_flag, int L, int U_cap, int64_t V, int d, int N,
+                                  int bits, int block, int scale_bytes, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

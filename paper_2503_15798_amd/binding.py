@@ -30,7 +30,7 @@ EXPORTS = ("mole_last_error", "mole_version", "mole_build_lut_workspace", "mole_
            "mole_lookup_forward_layers", "mole_fold_router_norm", "mole_layer_forward", "mole_offload_fetch", "mole_offload_fetch_idmajor",
            "mole_lut_file_create", "mole_lut_file_open", "mole_lut_file_payload", "mole_lut_file_write_layer",
            "mole_lut_file_read_rows", "mole_lut_file_close", "mole_nf_codebook", "mole_nf_codes_bytes",
-           "mole_nf_scales_bytes", "mole_quantize_lut", "mole_lookup_forward_nf")
+           "mole_nf_scales_bytes", "mole_quantize_lut", "mole_lookup_forward_nf", "mole_offload_fetch_nf")
 
 
 class LutDesc(ctypes.Structure):
@@ -91,6 +91,9 @@ def lib() -> ctypes.CDLL:
     L.mole_offload_fetch_idmajor.restype = c_i32
     L.mole_offload_fetch_idmajor.argtypes = [c_void, c_void, c_void, c_void, c_i64, c_void,
                                              c_i32, c_i32, c_i64, c_i32, c_i32, c_i32, c_void]
+    L.mole_offload_fetch_nf.restype = c_i32
+    L.mole_offload_fetch_nf.argtypes = [c_void, c_i64, c_void, c_i64, c_void, c_void, c_void, c_i64, c_void, c_i64,
+                                        c_void, c_i32, c_i32, c_i64, c_i32, c_i32, c_i32, c_i32, c_i32, c_void]
     L.mole_lut_file_create.restype = c_i32
     L.mole_lut_file_create.argtypes = [ctypes.c_char_p, ctypes.POINTER(LutDesc), ctypes.POINTER(c_void)]
     L.mole_lut_file_open.restype = c_i32
@@ -225,6 +228,16 @@ def mole_offload_fetch_idmajor(host_table, uniq, n_uniq, staging, staging_layer_
     _check(lib().mole_offload_fetch_idmajor(_ptr(host_table), _ptr(uniq), _ptr(n_uniq), _ptr(staging),
                                             staging_layer_stride, _ptr(err_flag), L, U_cap, V, d, N, dtype,
                                             _stream(stream)))
+
+
+def mole_offload_fetch_nf(host_codes, host_codes_stride: int, host_scales, host_scales_stride: int, uniq, n_uniq,
+                          staging_codes, staging_codes_stride: int, staging_scales, staging_scales_stride: int,
+                          err_flag, L: int, U_cap: int, V: int, d: int, N: int, bits: int, block: int,
+                          scale_bytes: int, stream=None) -> None:
+    _check(lib().mole_offload_fetch_nf(_ptr(host_codes), host_codes_stride, _ptr(host_scales), host_scales_stride,
+                                       _ptr(uniq), _ptr(n_uniq), _ptr(staging_codes), staging_codes_stride,
+                                       _ptr(staging_scales), staging_scales_stride, _ptr(err_flag), L, U_cap, V, d, N,
+                                       bits, block, scale_bytes, _stream(stream)))
 
 
 def mole_lut_file_create(path: str, dtype: int, layout: int, L: int, V: int, N: int, d: int) -> int:

@@ -178,6 +178,31 @@ def test_offload_fetch_idmajor_rejects_bad_arguments():
     mb.mole_offload_fetch_idmajor(**a)      # nothing to fetch: MOLE_OK without a launch
 
 
+def test_offload_fetch_nf_rejects_bad_arguments():
+    V, N, d, U = 100, 4, 64, 8
+    base = dict(host_codes=A16, host_codes_stride=V * N * d // 2, host_scales=A16, host_scales_stride=V * N,
+                uniq=A16, n_uniq=A16, staging_codes=A16, staging_codes_stride=U * N * d // 2, staging_scales=A16,
+                staging_scales_stride=U * N, err_flag=None, L=2, U_cap=U, V=V, d=d, N=N, bits=4, block=64,
+                scale_bytes=4, stream=0)
+    cases = [(dict(bits=5), mb.MOLE_EUNSUPPORTED), (dict(scale_bytes=3), mb.MOLE_EINVAL), (dict(L=0), mb.MOLE_EINVAL),
+             (dict(d=60), mb.MOLE_EUNSUPPORTED), (dict(block=48), mb.MOLE_EUNSUPPORTED),
+             (dict(host_codes=None), mb.MOLE_EINVAL), (dict(host_scales=None), mb.MOLE_EINVAL),
+             (dict(uniq=None), mb.MOLE_EINVAL), (dict(staging_scales=None), mb.MOLE_EINVAL),
+             (dict(host_codes_stride=V * N * d // 2 - 2), mb.MOLE_EINVAL),        # smaller than one layer
+             (dict(staging_scales_stride=U * N - 1), mb.MOLE_EINVAL),
+             (dict(host_codes=A16 + 1), mb.MOLE_EUNSUPPORTED)]                     # odd address
+    for kw, status in cases:
+        a = dict(base)
+        a.update(kw)
+        with pytest.raises(mb.MoleError) as e:
+            mb.mole_offload_fetch_nf(**a)
+        assert e.value.status == status, kw
+        assert "mole_offload_fetch_nf" in e.value.message
+    a = dict(base)
+    a.update(U_cap=0)
+    mb.mole_offload_fetch_nf(**a)           # nothing to fetch: MOLE_OK without a launch
+
+
 def test_product_package_does_not_import_the_oracle():
     """The product path must never route through the CPU oracle: no import, no path, no dlopen."""
     pkg = os.path.join(ROOT, "paper_2503_15798_amd")

@@ -125,6 +125,88 @@ def test_layers_and_bad_ids():
     np.testing.assert_array_equal(rows, ref_rows)
 
 
+@pytest.mark.parametrize("bits,block,sb,d,N,T,V,L,pad", [
+    (4, 1024, 4, 1024, 16, 32, 600, 3, 0),      # the benchmark's NF4 setting: 16-byte units
+    (3, 128, 2, 1024, 16, 64, 600, 2, 0),       # NF3, bf16 scales
+    (4, 16, 2, 16, 4, 40, 50, 2, 0),            # 8-byte scale rows: 4-byte units
+    (4, 16, 2, 16, 4, 40, 50, 2, 1),            # scale layer stride of an odd number of bf16 values: 2-byte units
+])
+def test_offloaded_quantised_table(bits, block, sb, d, N, T, V, L, pad):
+    """Codes and scales of all layers in pinned host memory: the rows of the distinct ids arrive byte for
+    byte in the staging buffers, and the forward on them (slot = inverse map) equals the forward on the
+    device-resident quantised tables bit for bit."""
+    import torch
+    w = wl.scaled(wl.CONFIGS["offload410m"], V=V, d=d, N=N, T=T, L=L, name=f"nf{bits} offload")
+    tabs = [wl.random_table(w, l) for l in range(L)]
+    lis = [wl.layer_inputs(w, l) for l in range(L)]
+    ids = wl.token_ids(w)
+    packs = [gpu_quantize(t, V, N, d, bits, block, sb) for t in tabs]
+    code_row, scale_row = N * d * bits // 8, N * (d // block)                 # bytes / scale elements per id
+    codes_d = torch.stack([p[0][:V * code_row] for p in packs])              # [L, V * code_row] bytes
+    scales_d = torch.stack([p[1][:V * scale_row * sb] for p in packs])       # [L, V * scale_row * sb] bytes
+    ls_scale = V * scale_row + pad                                            # host layer stride, scale elements
+    host_codes = codes_d.cpu().pin_memory()
+    host_scales = torch.zeros((L, ls_scale * sb), dtype=torch.uint8).pin_memory()
+    host_scales[:, :V * scale_row * sb] = scales_d.cpu()
+
+    ids_d = torch.from_numpy(ids).cuda()
+    uniq_d, inv_d = torch.empty_like(ids_d), torch.empty_like(ids_d)
+    nu = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    err = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    plan = torch.empty((mb.mole_dedup_workspace(T, V) // 4,), dtype=torch.int32, device="cuda")
+    mb.mole_dedup_ids(ids_d, T, V, uniq_d, inv_d, nu, err, plan)
+    U_cap = T
+    st_codes = torch.zeros((L, U_cap * code_row), dtype=torch.uint8, device="cuda")
+    st_scales = torch.zeros((L, U_cap * scale_row * sb), dtype=torch.uint8, device="cuda")
+    mb.mole_offload_fetch_nf(host_codes, V * code_row, host_scales, ls_scale, uniq_d, nu, st_codes, U_cap * code_row,
+                             st_scales, U_cap * scale_row, err, L, U_cap, V, d, N, bits, block, sb)
+    torch.cuda.synchronize()
+    U = int(nu.item())
+    uniq = np.unique(ids)
+    assert U == len(uniq) and int(err.item()) == 0
+    uq = torch.from_numpy(uniq.astype(np.int64))
+    want_c = codes_d.cpu().view(L, V, code_row)[:, uq]
+    want_s = scales_d.cpu().view(L, V, scale_row * sb)[:, uq]
+    assert torch.equal(st_codes.cpu().view(L, U_cap, code_row)[:, :U], want_c)
+    assert torch.equal(st_scales.cpu().view(L, U_cap, scale_row * sb)[:, :U], want_s)
+    assert not st_codes.view(L, U_cap, code_row)[:, U:].any()
+
+    stack = lambda k: to_dev(np.stack([x[k] for x in lis]), wl.BF16)
+    h_d, wr_d, sh_d = stack("h"), stack("W_r"), stack("shared")
+    out_staged, out_res = torch.zeros_like(h_d), torch.zeros_like(h_d)
+    mb.mole_lookup_forward_nf(st_codes, U_cap * code_row, st_scales, U_cap * scale_row, ids_d, inv_d, h_d, wr_d, sh_d,
+                              None, out_staged, T * d, None, None, err, L, T, U_cap, d, N, bits, block, sb)
+    mb.mole_lookup_forward_nf(codes_d, V * code_row, scales_d, V * scale_row, ids_d, None, h_d, wr_d, sh_d, None,
+                              out_res, T * d, None, None, err, L, T, V, d, N, bits, block, sb)
+    torch.cuda.synchronize()
+    assert int(err.item()) == 0
+    a, b = to_host(out_staged, wl.BF16), to_host(out_res, wl.BF16)
+    np.testing.assert_array_equal(a, b)
+    ref, _, _, _ = oracle_nf_forward(tabs[L - 1], lis[L - 1], ids, bits, block)
+    assert_close(wl.storage_to_f64(a[L - 1], wl.BF16), ref, wl.BF16, "staged quantised forward")
+
+
+def test_offloaded_quantised_table_reports_overflowing_staging():
+    import torch
+    V, N, d, T = 100, 4, 64, 50
+    w = wl.scaled(wl.CONFIGS["offload410m"], V=V, d=d, N=N, T=T, L=1, ids="uniform")
+    codes, scales = gpu_quantize(wl.random_table(w), V, N, d, 4, 64, 4)
+    hc, hs = codes.cpu().pin_memory(), scales.cpu().pin_memory()
+    ids_d = torch.from_numpy(wl.token_ids(w)).cuda()
+    uq, iv = torch.empty_like(ids_d), torch.empty_like(ids_d)
+    nu = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    err = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    plan = torch.empty((mb.mole_dedup_workspace(T, V) // 4,), dtype=torch.int32, device="cuda")
+    mb.mole_dedup_ids(ids_d, T, V, uq, iv, nu, err, plan)
+    U_cap = 5
+    sc = torch.zeros((U_cap * N * d // 2 + 64,), dtype=torch.uint8, device="cuda")
+    ss = torch.zeros((U_cap * N * 4 + 64,), dtype=torch.uint8, device="cuda")
+    mb.mole_offload_fetch_nf(hc, 0, hs, 0, uq, nu, sc, 0, ss, 0, err, 1, U_cap, V, d, N, 4, 64, 4)
+    torch.cuda.synchronize()
+    assert int(nu.item()) > U_cap and int(err.item()) == 1
+    assert not sc[U_cap * N * d // 2:].any() and not ss[U_cap * N * 4:].any()      # nothing past the capacity
+
+
 def test_quantisation_error_is_what_the_levels_allow():
     """Against the unquantised table the routed term moves by at most the level gap times the scales."""
     w = wl.scaled(wl.CONFIGS["decode410m"], V=300, d=768, N=4, T=80, L=1)
