@@ -286,6 +286,19 @@ mole_status mole_lookup_forward_nf(const void *codes, int64_t codes_stride,
                                    int bits, int block, int scale_bytes, unsigned flags,
                                    const void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* mole_layer_forward with a quantised table: x is the state after attention, W_rn the router weight
+ * with the norm weight folded in (mole_fold_router_norm); out = x + shared_out + sum_j g_j * row_j with
+ * the rows dequantised on the fly.  Other arguments as in mole_lookup_forward_nf. */
+mole_status mole_layer_forward_nf(const void *codes, int64_t codes_stride,
+                                  const void *scales, int64_t scales_stride,
+                                  const int32_t *ids, const int32_t *slot,
+                                  const void *x, float ln_eps, const void *W_rn,
+                                  const void *shared_out, void *out, int64_t act_stride,
+                                  float *gates_dbg, int64_t *rows_dbg, int32_t *err_flag,
+                                  int L, int T, int64_t rows, int d, int N,
+                                  int bits, int block, int scale_bytes, unsigned flags,
+                                  const void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Offloaded mode with a quantised table: the codes [L, V, N, d*bits/8] and scales [L, V, N, d/block]
  * of all layers sit in pinned, GPU-mapped host memory; the rows of the distinct ids (uniq / n_uniq of
  * mole_dedup_ids) are copied to staging_codes [L, U_cap, N, d*bits/8] and staging_scales

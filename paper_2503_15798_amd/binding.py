@@ -30,7 +30,8 @@ EXPORTS = ("mole_last_error", "mole_version", "mole_build_lut_workspace", "mole_
            "mole_lookup_forward_layers", "mole_fold_router_norm", "mole_layer_forward", "mole_offload_fetch", "mole_offload_fetch_idmajor",
            "mole_lut_file_create", "mole_lut_file_open", "mole_lut_file_payload", "mole_lut_file_write_layer",
            "mole_lut_file_read_rows", "mole_lut_file_close", "mole_nf_codebook", "mole_nf_codes_bytes",
-           "mole_nf_scales_bytes", "mole_quantize_lut", "mole_lookup_forward_nf", "mole_offload_fetch_nf")
+           "mole_nf_scales_bytes", "mole_quantize_lut", "mole_lookup_forward_nf", "mole_offload_fetch_nf",
+           "mole_layer_forward_nf")
 
 
 class LutDesc(ctypes.Structure):
@@ -118,6 +119,11 @@ def lib() -> ctypes.CDLL:
     L.mole_lookup_forward_nf.argtypes = ([c_void, c_i64, c_void, c_i64] + [c_void] * 7 + [c_i64] + [c_void] * 3 +
                                          [c_i32, c_i32, c_i64, c_i32, c_i32, c_i32, c_i32, c_i32, c_u, c_void, c_sz,
                                           c_void])
+    L.mole_layer_forward_nf.restype = c_i32
+    L.mole_layer_forward_nf.argtypes = ([c_void, c_i64, c_void, c_i64, c_void, c_void, c_void, ctypes.c_float, c_void,
+                                         c_void, c_void, c_i64, c_void, c_void, c_void] +
+                                        [c_i32, c_i32, c_i64, c_i32, c_i32, c_i32, c_i32, c_i32, c_u, c_void, c_sz,
+                                         c_void])
     _lib = L
     return L
 
@@ -303,3 +309,14 @@ def mole_lookup_forward_nf(codes, codes_stride: int, scales, scales_stride: int,
                                         _ptr(h), _ptr(W_r), _ptr(shared_out), _ptr(residual), _ptr(out), act_stride,
                                         _ptr(gates_dbg), _ptr(rows_dbg), _ptr(err_flag), L, T, rows, d, N, bits, block,
                                         scale_bytes, flags, _ptr(workspace), wb, _stream(stream)))
+
+
+def mole_layer_forward_nf(codes, codes_stride: int, scales, scales_stride: int, ids, slot, x, ln_eps: float, W_rn,
+                          shared_out, out, act_stride: int, gates_dbg, rows_dbg, err_flag, L: int, T: int, rows: int,
+                          d: int, N: int, bits: int, block: int, scale_bytes: int, flags: int = 0, workspace=None,
+                          stream=None, workspace_bytes: Optional[int] = None) -> None:
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().mole_layer_forward_nf(_ptr(codes), codes_stride, _ptr(scales), scales_stride, _ptr(ids), _ptr(slot),
+                                       _ptr(x), ln_eps, _ptr(W_rn), _ptr(shared_out), _ptr(out), act_stride,
+                                       _ptr(gates_dbg), _ptr(rows_dbg), _ptr(err_flag), L, T, rows, d, N, bits, block,
+                                       scale_bytes, flags, _ptr(workspace), wb, _stream(stream)))

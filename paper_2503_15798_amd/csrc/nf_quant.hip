@@ -46,6 +46,8 @@ struct NfArgs {
     int64_t rows;
     int T, d, N, L;
     int block;               // elements per scale
+    float ln_eps;            // NORM variant: h is the state before the RMSNorm in front of the router (its weight
+                             // folded into W_r beforehand) and is added as the residual
 };
 
 // A scale is fetched as a raw dword (the fp32 value, or the aligned dword holding the bf16 value) and
@@ -188,7 +190,7 @@ __device__ __forceinline__ void dequant_fma8(float (&acc)[8], float gs, uint32_t
     }
 }
 
-template <int N, int BITS, int WPB>
+template <int N, int BITS, int WPB, bool NORM>
 __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_bytes)
 {
     extern __shared__ uint4 smem[];
@@ -260,7 +262,7 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
         if (a.rows_dbg && layer == 0 && lane == 0)
             a.rows_dbg[t] = valid ? row : -1;
 
-        const float g = router_gate<N, false>(router, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1);
+        const float g = router_gate<N, false, NORM>(router, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1, a.ln_eps);
         if (a.gates_dbg && (lane & (LPJ - 1)) == 0)
             a.gates_dbg[((int64_t)layer * T + t) * N + lane / LPJ] = g;
         load_h2<false>(h0, h1, hbase + (int64_t)nt * d, d, lane);
@@ -277,8 +279,8 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
             uint4 sv = make_uint4(0, 0, 0, 0), rv = make_uint4(0, 0, 0, 0);
             if (on && sbase)
                 sv = ld16_stream<true>(sbase + off);
-            if (on && rbase)
-                rv = ld16_stream<true>(rbase + off);
+            if (on && (NORM || rbase))          // NORM: the state itself, read a second time (an L2 hit)
+                rv = ld16_stream<true>((NORM ? hbase : rbase) + off);
             // the products gate x scale, then the registers are free for the next chunk's words
             uint32_t w[N];
             float gsc[N];
@@ -322,14 +324,14 @@ mole_status nf_params_status(int d, int bits, int block, int scale_bytes, const 
     return MOLE_OK;
 }
 
-template <int N, int BITS>
+template <int N, int BITS, bool NORM>
 mole_status launch_nf(const NfArgs &a, int scale_bytes, hipStream_t stream)
 {
     constexpr int WPB = 4;
     const size_t lds = router_lds_bytes(a.d, N) + 64;
     static size_t attr_set = 0;
     if (lds > attr_set) {
-        MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_nf_kernel<N, BITS, WPB>),
+        MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_nf_kernel<N, BITS, WPB, NORM>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = lds;
     }
@@ -346,23 +348,78 @@ mole_status launch_nf(const NfArgs &a, int scale_bytes, hipStream_t stream)
         const int64_t ipw = (a.T + cap * WPB - 1) / (cap * WPB);
         gx = (a.T + WPB * ipw - 1) / (WPB * ipw);
     }
-    hipLaunchKernelGGL((fwd_nf_kernel<N, BITS, WPB>), dim3((unsigned)gx, (unsigned)a.L), dim3(WPB * 64), lds, stream,
+    hipLaunchKernelGGL((fwd_nf_kernel<N, BITS, WPB, NORM>), dim3((unsigned)gx, (unsigned)a.L), dim3(WPB * 64), lds, stream,
                        a, scale_bytes);
     MOLE_HIP_CHECK(hipGetLastError());
     return MOLE_OK;
 }
 
-template <int BITS>
+template <int BITS, bool NORM>
 mole_status launch_nf_n(const NfArgs &a, int scale_bytes, hipStream_t stream)
 {
     switch (a.N) {
-    case 4: return launch_nf<4, BITS>(a, scale_bytes, stream);
-    case 8: return launch_nf<8, BITS>(a, scale_bytes, stream);
-    case 16: return launch_nf<16, BITS>(a, scale_bytes, stream);
-    case 32: return launch_nf<32, BITS>(a, scale_bytes, stream);
-    case 64: return launch_nf<64, BITS>(a, scale_bytes, stream);
+    case 4: return launch_nf<4, BITS, NORM>(a, scale_bytes, stream);
+    case 8: return launch_nf<8, BITS, NORM>(a, scale_bytes, stream);
+    case 16: return launch_nf<16, BITS, NORM>(a, scale_bytes, stream);
+    case 32: return launch_nf<32, BITS, NORM>(a, scale_bytes, stream);
+    case 64: return launch_nf<64, BITS, NORM>(a, scale_bytes, stream);
     default: return fail(MOLE_EUNSUPPORTED, "mole_lookup_forward_nf: N=%d, built for 4, 8, 16, 32, 64", a.N);
     }
+}
+
+// shared by mole_lookup_forward_nf and mole_layer_forward_nf (with_norm: h is the state x, W_r the folded weight)
+mole_status nf_forward_impl(const char *who, const void *codes, int64_t codes_stride, const void *scales,
+                            int64_t scales_stride, const int32_t *ids, const int32_t *slot, const void *h,
+                            const void *W_r, const void *shared_out, const void *residual, void *out,
+                            int64_t act_stride, float *gates_dbg, int64_t *rows_dbg, int32_t *err_flag, int L, int T,
+                            int64_t rows, int d, int N, int bits, int block, int scale_bytes, unsigned flags,
+                            const void *workspace, size_t workspace_bytes, void *hip_stream, bool with_norm,
+                            float ln_eps)
+{
+    clear_error();
+    const mole_status ps = nf_params_status(d, bits, block, scale_bytes, who);
+    if (ps != MOLE_OK)
+        return ps;
+    if (T < 0 || L < 1 || L > 65535 || rows < 1)
+        return fail(MOLE_EINVAL, "%s: bad size (T=%d, L=%d, rows=%lld)", who, T, L, (long long)rows);
+    if (flags & ~unsigned(MOLE_FLAG_DEDUP))
+        return fail(MOLE_EINVAL, "%s: unknown flags 0x%x", who, flags);
+    if (with_norm && !(ln_eps >= 0.f))
+        return fail(MOLE_EINVAL, "%s: ln_eps = %g must be >= 0", who, (double)ln_eps);
+    if (router_lds_bytes(d, N) + 64 > 160 * 1024)
+        return fail(MOLE_EUNSUPPORTED, "%s: router weight of %d x %d does not fit in LDS", who, d, N);
+    if (T == 0)
+        return MOLE_OK;
+    if (!codes || !scales || !ids || !h || !W_r || !out)
+        return fail(MOLE_EINVAL, "%s: codes, scales, ids, the state, the router weight and out must not be NULL", who);
+    const void *ptrs[] = {codes, scales, h, W_r, shared_out, residual, out};
+    for (const void *p : ptrs)
+        if (p && !aligned16(p))
+            return fail(MOLE_EINVAL, "%s: tensor pointer %p is not 16-byte aligned", who, p);
+    if (L > 1) {
+        const int64_t cb = (int64_t)mole_nf_codes_bytes(rows, N, d, bits);
+        const int64_t se = rows * N * (int64_t)(d / block);
+        if (codes_stride < cb || scales_stride < se || act_stride < (int64_t)T * d || codes_stride % 16 ||
+            (scales_stride * scale_bytes) % 16 || (act_stride * 2) % 16)
+            return fail(MOLE_EINVAL, "%s: layer strides too small or not 16-byte multiples", who);
+    }
+    const int32_t *plan = nullptr;
+    if (flags & MOLE_FLAG_DEDUP) {
+        const size_t need = (size_t)plan_layout(T).words * 4;
+        if (!workspace || workspace_bytes < need)
+            return fail(MOLE_EWORKSPACE, "%s: MOLE_FLAG_DEDUP needs a %zu-byte plan, got %zu", who, need,
+                        workspace ? workspace_bytes : (size_t)0);
+        plan = static_cast<const int32_t *>(workspace);
+    }
+    NfArgs a;
+    a.codes = static_cast<const uint8_t *>(codes); a.scales = scales; a.ids = ids; a.slot = slot; a.h = h; a.W_r = W_r;
+    a.shared = shared_out; a.residual = residual; a.out = out; a.gates_dbg = gates_dbg; a.rows_dbg = rows_dbg;
+    a.err_flag = err_flag; a.plan = plan; a.codes_stride = codes_stride; a.scales_stride = scales_stride;
+    a.act_stride = act_stride; a.rows = rows; a.T = T; a.d = d; a.N = N; a.L = L; a.block = block; a.ln_eps = ln_eps;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (with_norm)
+        return bits == 4 ? launch_nf_n<4, true>(a, scale_bytes, stream) : launch_nf_n<3, true>(a, scale_bytes, stream);
+    return bits == 4 ? launch_nf_n<4, false>(a, scale_bytes, stream) : launch_nf_n<3, false>(a, scale_bytes, stream);
 }
 
 }  // namespace
@@ -428,44 +485,20 @@ extern "C" mole_status mole_lookup_forward_nf(const void *codes, int64_t codes_s
                                               int N, int bits, int block, int scale_bytes, unsigned flags,
                                               const void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    clear_error();
-    const mole_status ps = nf_params_status(d, bits, block, scale_bytes, "mole_lookup_forward_nf");
-    if (ps != MOLE_OK)
-        return ps;
-    if (T < 0 || L < 1 || L > 65535 || rows < 1)
-        return fail(MOLE_EINVAL, "mole_lookup_forward_nf: bad size (T=%d, L=%d, rows=%lld)", T, L, (long long)rows);
-    if (flags & ~unsigned(MOLE_FLAG_DEDUP))
-        return fail(MOLE_EINVAL, "mole_lookup_forward_nf: unknown flags 0x%x", flags);
-    if (router_lds_bytes(d, N) + 64 > 160 * 1024)
-        return fail(MOLE_EUNSUPPORTED, "mole_lookup_forward_nf: router weight of %d x %d does not fit in LDS", d, N);
-    if (T == 0)
-        return MOLE_OK;
-    if (!codes || !scales || !ids || !h || !W_r || !out)
-        return fail(MOLE_EINVAL, "mole_lookup_forward_nf: codes, scales, ids, h, W_r and out must not be NULL");
-    const void *ptrs[] = {codes, scales, h, W_r, shared_out, residual, out};
-    for (const void *p : ptrs)
-        if (p && !aligned16(p))
-            return fail(MOLE_EINVAL, "mole_lookup_forward_nf: tensor pointer %p is not 16-byte aligned", p);
-    if (L > 1) {
-        const int64_t cb = (int64_t)mole_nf_codes_bytes(rows, N, d, bits);
-        const int64_t se = rows * N * (int64_t)(d / block);
-        if (codes_stride < cb || scales_stride < se || act_stride < (int64_t)T * d || codes_stride % 16 ||
-            (scales_stride * scale_bytes) % 16 || (act_stride * 2) % 16)
-            return fail(MOLE_EINVAL, "mole_lookup_forward_nf: layer strides too small or not 16-byte multiples");
-    }
-    const int32_t *plan = nullptr;
-    if (flags & MOLE_FLAG_DEDUP) {
-        const size_t need = (size_t)plan_layout(T).words * 4;
-        if (!workspace || workspace_bytes < need)
-            return fail(MOLE_EWORKSPACE, "mole_lookup_forward_nf: MOLE_FLAG_DEDUP needs a %zu-byte plan, got %zu", need,
-                        workspace ? workspace_bytes : (size_t)0);
-        plan = static_cast<const int32_t *>(workspace);
-    }
-    NfArgs a;
-    a.codes = static_cast<const uint8_t *>(codes); a.scales = scales; a.ids = ids; a.slot = slot; a.h = h; a.W_r = W_r;
-    a.shared = shared_out; a.residual = residual; a.out = out; a.gates_dbg = gates_dbg; a.rows_dbg = rows_dbg;
-    a.err_flag = err_flag; a.plan = plan; a.codes_stride = codes_stride; a.scales_stride = scales_stride;
-    a.act_stride = act_stride; a.rows = rows; a.T = T; a.d = d; a.N = N; a.L = L; a.block = block;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    return bits == 4 ? launch_nf_n<4>(a, scale_bytes, stream) : launch_nf_n<3>(a, scale_bytes, stream);
+    return nf_forward_impl("mole_lookup_forward_nf", codes, codes_stride, scales, scales_stride, ids, slot, h, W_r,
+                           shared_out, residual, out, act_stride, gates_dbg, rows_dbg, err_flag, L, T, rows, d, N, bits,
+                           block, scale_bytes, flags, workspace, workspace_bytes, hip_stream, false, 0.f);
+}
+
+extern "C" mole_status mole_layer_forward_nf(const void *codes, int64_t codes_stride, const void *scales,
+                                             int64_t scales_stride, const int32_t *ids, const int32_t *slot,
+                                             const void *x, float ln_eps, const void *W_rn, const void *shared_out,
+                                             void *out, int64_t act_stride, float *gates_dbg, int64_t *rows_dbg,
+                                             int32_t *err_flag, int L, int T, int64_t rows, int d, int N, int bits,
+                                             int block, int scale_bytes, unsigned flags, const void *workspace,
+                                             size_t workspace_bytes, void *hip_stream)
+{
+    return nf_forward_impl("mole_layer_forward_nf", codes, codes_stride, scales, scales_stride, ids, slot, x, W_rn,
+                           shared_out, nullptr, out, act_stride, gates_dbg, rows_dbg, err_flag, L, T, rows, d, N, bits,
+                           block, scale_bytes, flags, workspace, workspace_bytes, hip_stream, true, ln_eps);
 }

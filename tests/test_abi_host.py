@@ -178,6 +178,27 @@ def test_offload_fetch_idmajor_rejects_bad_arguments():
     mb.mole_offload_fetch_idmajor(**a)      # nothing to fetch: MOLE_OK without a launch
 
 
+def test_layer_forward_nf_rejects_bad_arguments():
+    base = dict(codes=A16, codes_stride=0, scales=A16, scales_stride=0, ids=A16, slot=None, x=A16, ln_eps=1e-5,
+                W_rn=A16, shared_out=None, out=A16, act_stride=0, gates_dbg=None, rows_dbg=None, err_flag=None, L=1,
+                T=4, rows=10, d=64, N=4, bits=4, block=64, scale_bytes=4, flags=0, workspace=None, stream=0,
+                workspace_bytes=0)
+    cases = [(dict(ln_eps=-1.0), mb.MOLE_EINVAL), (dict(ln_eps=float("nan")), mb.MOLE_EINVAL),
+             (dict(x=None), mb.MOLE_EINVAL), (dict(W_rn=None), mb.MOLE_EINVAL), (dict(bits=5), mb.MOLE_EUNSUPPORTED),
+             (dict(N=5), mb.MOLE_EUNSUPPORTED), (dict(x=A16 + 2), mb.MOLE_EINVAL),
+             (dict(flags=mb.MOLE_FLAG_DEDUP), mb.MOLE_EWORKSPACE)]
+    for kw, status in cases:
+        a = dict(base)
+        a.update(kw)
+        with pytest.raises(mb.MoleError) as e:
+            mb.mole_layer_forward_nf(**a)
+        assert e.value.status == status, kw
+        assert "mole_layer_forward_nf" in e.value.message or status == mb.MOLE_EUNSUPPORTED
+    a = dict(base)
+    a.update(T=0)
+    mb.mole_layer_forward_nf(**a)           # empty batch: MOLE_OK, nothing launched
+
+
 def test_offload_fetch_nf_rejects_bad_arguments():
     V, N, d, U = 100, 4, 64, 8
     base = dict(host_codes=A16, host_codes_stride=V * N * d // 2, host_scales=A16, host_scales_stride=V * N,

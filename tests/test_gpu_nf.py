@@ -207,6 +207,51 @@ def test_offloaded_quantised_table_reports_overflowing_staging():
     assert not sc[U_cap * N * d // 2:].any() and not ss[U_cap * N * 4:].any()      # nothing past the capacity
 
 
+@pytest.mark.parametrize("bits,block,sb,d,N,T,V", [
+    (4, 1024, 4, 1024, 16, 203, 500),
+    (3, 128, 2, 1024, 16, 64, 500),
+    (4, 512, 2, 1024, 32, 77, 300),
+    (4, 104, 4, 520, 8, 9, 64),          # ragged last chunk
+    (3, 64, 4, 2048, 4, 40, 200),        # four chunks
+])
+@pytest.mark.parametrize("dedup", [False, True])
+def test_layer_forward_on_quantised_table(bits, block, sb, d, N, T, V, dedup):
+    """mole_layer_forward_nf (state after attention in, RMSNorm and residual inside the kernel) against the
+    oracle of the inference listing run on the dequantised table."""
+    import torch
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, T=T, L=1, name=f"nf{bits} layer d{d} N{N}")
+    table, li, ni = wl.random_table(w), wl.layer_inputs(w), wl.norm_inputs(w, 0)
+    W_r = wl.to_storage(wl.storage_to_f64(li["W_r"], w.dtype) * 5.0, w.dtype)
+    ids = wl.token_ids(w).copy()
+    if T > 8:
+        ids[T // 3] = V + 2
+    codes, scales = gpu_quantize(table, V, N, d, bits, block, sb)
+    x_d, lw_d, wr_d, sh_d = (to_dev(a, wl.BF16) for a in (ni["x"], ni["ln_w"], W_r, li["shared"]))
+    wrn_d = torch.empty_like(wr_d)
+    mb.mole_fold_router_norm(wr_d, lw_d, wrn_d, 1, d, N, mb.MOLE_BF16)
+    ids_d = torch.from_numpy(ids).cuda()
+    out_d = torch.full_like(x_d, float("nan"))
+    gates_d = torch.zeros((T, N), dtype=torch.float32, device="cuda")
+    rows_d = torch.zeros((T,), dtype=torch.int64, device="cuda")
+    err = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    flags, plan = 0, None
+    if dedup:
+        plan = torch.empty((mb.mole_dedup_workspace(T, V) // 4,), dtype=torch.int32, device="cuda")
+        uq, iv = torch.empty_like(ids_d), torch.empty_like(ids_d)
+        mb.mole_dedup_ids(ids_d, T, V, uq, iv, torch.zeros_like(err), torch.zeros_like(err), plan)
+        flags = mb.MOLE_FLAG_DEDUP
+    mb.mole_layer_forward_nf(codes, 0, scales, 0, ids_d, None, x_d, 1e-5, wrn_d, sh_d, out_d, 0, gates_d, rows_d, err,
+                             1, T, V, d, N, bits, block, sb, flags, plan)
+    torch.cuda.synchronize()
+    q_codes, q_scales = nf.quantize(wl.bf16_bits_to_f32(table), bits, block)
+    deq = nf.dequantize(q_codes, q_scales, bits, block)
+    ref, ref_g, _, ref_rows, ref_err = oracle.layer_forward(deq, ids, ni["x"], ni["ln_w"], 1e-5, W_r, li["shared"])
+    assert int(err.item()) == ref_err
+    np.testing.assert_array_equal(rows_d.cpu().numpy(), ref_rows)
+    assert_close(gates_d.cpu().numpy().astype(np.float64), ref_g, wl.BF16, "gates")
+    assert_close(wl.storage_to_f64(to_host(out_d, wl.BF16), wl.BF16), ref, wl.BF16, f"layer forward nf ({w.name})")
+
+
 def test_quantisation_error_is_what_the_levels_allow():
     """Against the unquantised table the routed term moves by at most the level gap times the scales."""
     w = wl.scaled(wl.CONFIGS["decode410m"], V=300, d=768, N=4, T=80, L=1)
