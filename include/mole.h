@@ -46,7 +46,12 @@ typedef enum {
     MOLE_EIO = 5            /* a file could not be created, opened, mapped or read (LUT files)  */
 } mole_status;
 
-typedef enum { MOLE_F32 = 0, MOLE_BF16 = 1 } mole_dtype;
+typedef enum {
+    MOLE_F32 = 0,
+    MOLE_BF16 = 1,
+    MOLE_U8 = 2     /* raw bytes (d counts bytes per expert row): only for moving quantised tables through
+                       mole_lut_file_* and mole_offload_fetch / _idmajor; no arithmetic is defined on it */
+} mole_dtype;
 typedef enum { MOLE_GELU_ERF = 0, MOLE_GELU_TANH = 1 } mole_act;
 typedef enum {
     MOLE_LAYOUT_LAYER_MAJOR = 0,   /* [L, V, N, d]: one table per layer                           */
@@ -213,6 +218,8 @@ mole_status mole_offload_fetch_idmajor(const void *host_table,
  * devices).  The paper defines no format.  This one: a 4096-byte little-endian header
  * ("MOLELUT\0", u32 version = 1, u32 header bytes, u32 dtype, u32 layout, i64 V, i32 L, i32 N,
  * i32 d, u32 0, u64 payload bytes) followed by the raw table in the layout the header names.
+ * A quantised table is stored as two files of raw bytes (dtype MOLE_U8, d = bytes per expert row:
+ * d_model*bits/8 for the codes, (d_model/block)*scale_bytes for the scales).
  * Host-only calls: no GPU work, no stream.  These are the only calls that keep state: a
  * mole_lut_file owns a file descriptor, a mapping and its reader threads (started on first use,
  * kept for later calls) until mole_lut_file_close.  Calls on one handle are serialised.

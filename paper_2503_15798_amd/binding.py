@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("MOLE_LIB") or os.path.join(_HERE, "libmole.so")
 
 MOLE_OK, MOLE_EINVAL, MOLE_EUNSUPPORTED, MOLE_EWORKSPACE, MOLE_EHIP, MOLE_EIO = range(6)
-MOLE_F32, MOLE_BF16 = 0, 1
+MOLE_F32, MOLE_BF16, MOLE_U8 = 0, 1, 2
 MOLE_GELU_ERF, MOLE_GELU_TANH = 0, 1
 MOLE_FLAG_DEDUP = 1
 MOLE_LAYOUT_LAYER_MAJOR, MOLE_LAYOUT_ID_MAJOR = 0, 1

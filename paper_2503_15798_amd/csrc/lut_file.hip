@@ -154,7 +154,7 @@ static_assert(sizeof(Header) == 56, "header fields are packed without padding");
 
 mole_status check_desc(const char *who, const mole_lut_desc &c)
 {
-    if (c.dtype != MOLE_F32 && c.dtype != MOLE_BF16)
+    if (c.dtype != MOLE_F32 && c.dtype != MOLE_BF16 && c.dtype != MOLE_U8)
         return fail(MOLE_EINVAL, "%s: unknown dtype %d", who, c.dtype);
     if (c.layout != MOLE_LAYOUT_LAYER_MAJOR && c.layout != MOLE_LAYOUT_ID_MAJOR)
         return fail(MOLE_EINVAL, "%s: unknown layout %d", who, c.layout);

@@ -14,7 +14,7 @@ mole_status fail(mole_status st, const char *fmt, ...) __attribute__((format(pri
 void clear_error();
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-inline size_t elem_bytes(mole_dtype dt) { return dt == MOLE_F32 ? 4 : 2; }
+inline size_t elem_bytes(mole_dtype dt) { return dt == MOLE_F32 ? 4 : (dt == MOLE_U8 ? 1 : 2); }
 
 // Number of compute units of the current device (cached per process; 256 on MI355X).
 int num_cus();

@@ -77,7 +77,7 @@ mole_status fetch_impl(const char *who, bool id_major, const void *host_table, i
                        void *hip_stream)
 {
     clear_error();
-    if (dtype != MOLE_F32 && dtype != MOLE_BF16)
+    if (dtype != MOLE_F32 && dtype != MOLE_BF16 && dtype != MOLE_U8)
         return fail(MOLE_EINVAL, "%s: unknown dtype %d", who, (int)dtype);
     if (L < 1 || U_cap < 0 || V < 1 || d < 1 || N < 1)
         return fail(MOLE_EINVAL, "%s: bad size (L=%d, U_cap=%d, V=%lld, d=%d, N=%d)", who, L, U_cap, (long long)V,

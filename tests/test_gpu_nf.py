@@ -186,6 +186,69 @@ def test_offloaded_quantised_table(bits, block, sb, d, N, T, V, L, pad):
     assert_close(wl.storage_to_f64(a[L - 1], wl.BF16), ref, wl.BF16, "staged quantised forward")
 
 
+@pytest.mark.parametrize("bits,block,sb", [(4, 256, 4), (3, 128, 2)])
+def test_storage_tier_step_with_quantised_tables(tmp_path, bits, block, sb):
+    """The quantised table in two LUT files of raw bytes (codes, scales), id-major: the distinct ids' rows
+    are read into pinned memory, pulled to the device and fed to the dequantising forward, which then
+    equals the forward on the device-resident quantised tables bit for bit."""
+    import torch
+    L, V, d, N, T = 3, 800, 1024, 16, 48
+    w = wl.scaled(wl.CONFIGS["offload410m"], V=V, d=d, N=N, T=T, L=L, name=f"nf{bits} files")
+    tabs = [wl.random_table(w, l) for l in range(L)]
+    lis = [wl.layer_inputs(w, l) for l in range(L)]
+    ids = wl.token_ids(w)
+    packs = [gpu_quantize(t, V, N, d, bits, block, sb) for t in tabs]
+    cb, sbytes = d * bits // 8, (d // block) * sb                          # bytes per expert row
+    codes_d = torch.stack([p[0][:V * N * cb] for p in packs])
+    scales_d = torch.stack([p[1][:V * N * sbytes] for p in packs])
+    paths = {}
+    for name, src, width in (("codes", codes_d, cb), ("scales", scales_d, sbytes)):
+        paths[name] = str(tmp_path / f"{name}.molelut")
+        f = mb.mole_lut_file_create(paths[name], mb.MOLE_U8, mb.MOLE_LAYOUT_ID_MAJOR, L, V, N, width)
+        for l in range(L):
+            mb.mole_lut_file_write_layer(f, l, src[l].cpu(), 3)
+        mb.mole_lut_file_close(f)
+
+    ids_d = torch.from_numpy(ids).cuda()
+    uniq_d, inv_d = torch.empty_like(ids_d), torch.empty_like(ids_d)
+    nu = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    err = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    plan = torch.empty((mb.mole_dedup_workspace(T, V) // 4,), dtype=torch.int32, device="cuda")
+    mb.mole_dedup_ids(ids_d, T, V, uniq_d, inv_d, nu, err, plan)
+    U = int(nu.item())
+    uniq_h = uniq_d[:U].cpu()
+    U_cap = T
+    staged = {}
+    for name, width in (("codes", cb), ("scales", sbytes)):
+        f, desc = mb.mole_lut_file_open(paths[name])
+        try:
+            assert (desc.dtype, desc.L, desc.N, desc.d, desc.V) == (mb.MOLE_U8, L, N, width, V)
+            pinned = torch.zeros((U_cap, L, N, width), dtype=torch.uint8).pin_memory()
+            mb.mole_lut_file_read_rows(f, uniq_h, U, pinned, 3)
+        finally:
+            mb.mole_lut_file_close(f)
+        staged[name] = torch.zeros((L, U_cap * N * width), dtype=torch.uint8, device="cuda")
+        mb.mole_offload_fetch_idmajor(pinned, None, nu, staged[name], U_cap * N * width, err, L, U_cap, U_cap, width, N,
+                                      mb.MOLE_U8)
+    torch.cuda.synchronize()
+    uq = torch.from_numpy(np.unique(ids).astype(np.int64))
+    assert torch.equal(staged["codes"].cpu().view(L, U_cap, N * cb)[:, :U], codes_d.cpu().view(L, V, N * cb)[:, uq])
+    assert torch.equal(staged["scales"].cpu().view(L, U_cap, N * sbytes)[:, :U],
+                       scales_d.cpu().view(L, V, N * sbytes)[:, uq])
+
+    stack = lambda k: to_dev(np.stack([x[k] for x in lis]), wl.BF16)
+    h_d, wr_d, sh_d = stack("h"), stack("W_r"), stack("shared")
+    out_staged, out_res = torch.zeros_like(h_d), torch.zeros_like(h_d)
+    mb.mole_lookup_forward_nf(staged["codes"], U_cap * N * cb, staged["scales"], U_cap * N * (d // block), ids_d, inv_d,
+                              h_d, wr_d, sh_d, None, out_staged, T * d, None, None, err, L, T, U_cap, d, N, bits, block,
+                              sb)
+    mb.mole_lookup_forward_nf(codes_d, V * N * cb, scales_d, V * N * (d // block), ids_d, None, h_d, wr_d, sh_d, None,
+                              out_res, T * d, None, None, err, L, T, V, d, N, bits, block, sb)
+    torch.cuda.synchronize()
+    assert int(err.item()) == 0
+    np.testing.assert_array_equal(to_host(out_staged, wl.BF16), to_host(out_res, wl.BF16))
+
+
 def test_offloaded_quantised_table_reports_overflowing_staging():
     import torch
     V, N, d, T = 100, 4, 64, 50

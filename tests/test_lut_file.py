@@ -15,6 +15,8 @@ def tables(L, V, N, d, dtype, seed):
     rng = np.random.default_rng(seed)
     if dtype == mb.MOLE_BF16:
         return rng.integers(0, 1 << 16, size=(L, V, N, d), dtype=np.uint16)
+    if dtype == mb.MOLE_U8:
+        return rng.integers(0, 256, size=(L, V, N, d), dtype=np.uint8)      # raw bytes (quantised tables)
     return rng.standard_normal((L, V, N, d)).astype(np.float32)
 
 
@@ -23,6 +25,10 @@ def as_tensor(a):
     if a.dtype == np.uint16:
         return torch.from_numpy(a.view(np.int16).copy())
     return torch.from_numpy(a.copy())
+
+
+ELEM_BYTES = {mb.MOLE_F32: 4, mb.MOLE_BF16: 2, mb.MOLE_U8: 1}
+TORCH_DT = {mb.MOLE_F32: torch.float32, mb.MOLE_BF16: torch.int16, mb.MOLE_U8: torch.uint8}
 
 
 def write_file(path, tab, dtype, layout, threads=3):
@@ -35,7 +41,7 @@ def write_file(path, tab, dtype, layout, threads=3):
         mb.mole_lut_file_close(f)
 
 
-@pytest.mark.parametrize("dtype", [mb.MOLE_BF16, mb.MOLE_F32])
+@pytest.mark.parametrize("dtype", [mb.MOLE_BF16, mb.MOLE_F32, mb.MOLE_U8])
 @pytest.mark.parametrize("layout", [mb.MOLE_LAYOUT_LAYER_MAJOR, mb.MOLE_LAYOUT_ID_MAJOR])
 def test_bytes_on_disk_follow_the_documented_format(tmp_path, dtype, layout):
     L, V, N, d = 3, 37, 4, 24
@@ -43,7 +49,7 @@ def test_bytes_on_disk_follow_the_documented_format(tmp_path, dtype, layout):
     path = str(tmp_path / "t.molelut")
     write_file(path, tab, dtype, layout)
     raw = open(path, "rb").read()
-    eb = 2 if dtype == mb.MOLE_BF16 else 4
+    eb = ELEM_BYTES[dtype]
     assert len(raw) == 4096 + L * V * N * d * eb
     magic, ver, hb, dt, lay, v, l, n, dd, zero, pb = struct.unpack_from("<8sIIIIqiiiIQ", raw, 0)
     assert magic == b"MOLELUT\0" and ver == 1 and hb == 4096 and dt == dtype and lay == layout
@@ -54,7 +60,7 @@ def test_bytes_on_disk_follow_the_documented_format(tmp_path, dtype, layout):
     assert np.array_equal(payload.reshape(want.shape), want)
 
 
-@pytest.mark.parametrize("dtype", [mb.MOLE_BF16, mb.MOLE_F32])
+@pytest.mark.parametrize("dtype", [mb.MOLE_BF16, mb.MOLE_F32, mb.MOLE_U8])
 @pytest.mark.parametrize("layout", [mb.MOLE_LAYOUT_LAYER_MAJOR, mb.MOLE_LAYOUT_ID_MAJOR])
 @pytest.mark.parametrize("threads", [1, 5])
 def test_read_rows_is_a_gather_of_all_layers(tmp_path, dtype, layout, threads):
@@ -66,7 +72,7 @@ def test_read_rows_is_a_gather_of_all_layers(tmp_path, dtype, layout, threads):
     try:
         assert (desc.dtype, desc.layout, desc.L, desc.N, desc.d, desc.V) == (dtype, layout, L, N, d, V)
         ids = np.array([0, V - 1, 7, 7, 50, 3, 99, 0, 1], dtype=np.int32)
-        dst = torch.full((len(ids), L, N, d), -1, dtype=torch.int16 if dtype == mb.MOLE_BF16 else torch.float32)
+        dst = torch.full((len(ids), L, N, d), 7, dtype=TORCH_DT[dtype])
         mb.mole_lut_file_read_rows(f, torch.from_numpy(ids), len(ids), dst, threads)
         got = dst.numpy().view(tab.dtype)
         want = tab[:, ids].transpose(1, 0, 2, 3)            # [n, L, N, d]
@@ -75,7 +81,7 @@ def test_read_rows_is_a_gather_of_all_layers(tmp_path, dtype, layout, threads):
         addr = mb.mole_lut_file_payload(f)
         import ctypes
         nelem = L * V * N * d
-        ctype = ctypes.c_uint16 if dtype == mb.MOLE_BF16 else ctypes.c_float
+        ctype = {mb.MOLE_BF16: ctypes.c_uint16, mb.MOLE_F32: ctypes.c_float, mb.MOLE_U8: ctypes.c_uint8}[dtype]
         mapped = np.ctypeslib.as_array((ctype * nelem).from_address(addr))
         want_all = tab if layout == mb.MOLE_LAYOUT_LAYER_MAJOR else tab.transpose(1, 0, 2, 3)
         assert np.array_equal(mapped.reshape(want_all.shape), want_all)
