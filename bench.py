@@ -459,13 +459,14 @@ def extras(args, torch, mb, wl, acc, stream, L):
         out["offload410m"] = {"skipped": repr(e)}
     release_pinned(torch)
 
-    # ---- the same with NF4 tables: codes and scales of all layers in pinned host memory ----
-    try:
-        out["offload410m_nf4"] = offload_nf_bench(torch, mb, wl, stream, L, steps, warm, 4, 1024, 4)
-    except Exception as e:
-        traceback.print_exc(file=sys.stderr)
-        out["offload410m_nf4"] = {"skipped": repr(e)}
-    release_pinned(torch)
+    # ---- the same with NF4 / NF3 tables: codes and scales of all layers in pinned host memory ----
+    for tag, bits, block, sbytes in (("nf4", 4, 1024, 4), ("nf3", 3, 128, 2)):
+        try:
+            out[f"offload410m_{tag}"] = offload_nf_bench(torch, mb, wl, stream, L, steps, warm, bits, block, sbytes)
+        except Exception as e:
+            traceback.print_exc(file=sys.stderr)
+            out[f"offload410m_{tag}"] = {"skipped": repr(e)}
+        release_pinned(torch)
 
     # smaller decode batches on the same tables (latency-bound: microseconds are the result)
     for T in (32, 1):
