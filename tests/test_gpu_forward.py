@@ -137,6 +137,30 @@ def test_routed_term_alone():
     assert np.abs(wl.storage_to_f64(got["out"], w.dtype)).mean() > 1e-3
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_seeded_random_shapes(monkeypatch, seed):
+    """Shapes drawn from the documented ranges (d a multiple of 8 up to 2304, any N up to 64, small T and V),
+    with a random choice of residual, plan, out-of-range ids and of the launch switches: every dispatch
+    path (streaming, chunk items, run kernel, generic) against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    d = int(rng.integers(1, 289)) * 8
+    N = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 16, 24, 32, 33, 48, 64]))
+    T = int(rng.integers(1, 90))
+    V = int(rng.integers(max(2, T // 8), 400))
+    dedup, residual = bool(rng.integers(2)), bool(rng.integers(2))
+    for var in ("MOLE_FWD_SPLIT", "MOLE_FWD_NTA", "MOLE_FWD_RUN"):
+        monkeypatch.setenv(var, str(int(rng.integers(1, 3))))
+    monkeypatch.setenv("MOLE_FWD_WPB", str(int(rng.choice([4, 8]))))
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, T=T, L=1, ids=str(rng.choice(["zipf", "uniform"])),
+                  name=f"random seed {seed}: d{d} N{N} T{T} V{V} dedup{int(dedup)} res{int(residual)}")
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    li["W_r"] = wl.to_storage(wl.storage_to_f64(li["W_r"], w.dtype) * 5.0, w.dtype)
+    ids = ids.copy()
+    if rng.integers(2) and T > 2:
+        ids[int(rng.integers(T))] = V + int(rng.integers(1, 5))
+    check_against_oracle(w, table, ids, li, residual=residual, dedup=dedup)
+
+
 # ---- special cases with exact answers ----------------------------------------------------------------
 @pytest.mark.parametrize("N", [16, 5])
 def test_saturated_router_returns_the_row_exactly(N):

@@ -106,6 +106,26 @@ def test_run_kernel(monkeypatch, d, N, T, V):
     check(w, wl.random_table(w), ids, inp, dedup=True, shared=False)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_seeded_random_shapes(monkeypatch, seed):
+    """Shapes and launch switches drawn from the documented ranges: every dispatch path of the fused-norm
+    call against the oracle."""
+    rng = np.random.default_rng(2000 + seed)
+    d = int(rng.integers(1, 289)) * 8
+    N = int(rng.choice([1, 2, 3, 4, 8, 12, 16, 32, 40, 64]))
+    T = int(rng.integers(1, 90))
+    V = int(rng.integers(max(2, T // 8), 400))
+    for var in ("MOLE_FWD_SPLIT", "MOLE_FWD_NTA", "MOLE_FWD_RUN"):
+        monkeypatch.setenv(var, str(int(rng.integers(1, 3))))
+    monkeypatch.setenv("MOLE_FWD_WPB", str(int(rng.choice([4, 8]))))
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, T=T, L=1, ids=str(rng.choice(["zipf", "uniform"])),
+                  name=f"norm random seed {seed}: d{d} N{N} T{T} V{V}")
+    ids = wl.token_ids(w).copy()
+    if rng.integers(2) and T > 2:
+        ids[int(rng.integers(T))] = -1
+    check(w, wl.random_table(w), ids, inputs(w), shared=bool(rng.integers(2)), dedup=bool(rng.integers(2)))
+
+
 @pytest.mark.parametrize("d,N,T", [(64, 4, 256), (128, 16, 100), (32, 3, 17)])
 def test_fp32_shapes(d, N, T):
     w = wl.scaled(wl.CONFIGS["tiny"], V=777, d=d, N=N, T=T, name=f"norm fp32 d{d} N{N}")

@@ -110,6 +110,30 @@ def test_forward_matches_oracle_on_dequantised_table(bits, block, sb, d, N, T, V
     assert_close(wl.storage_to_f64(out[0], wl.BF16), ref, wl.BF16, f"nf forward ({w.name})")
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_seeded_random_shapes(seed):
+    """Bits, block, scale width, d, N and T drawn from what the quantised path documents."""
+    rng = np.random.default_rng(3000 + seed)
+    bits = int(rng.choice([3, 4]))
+    block = int(rng.choice([8, 16, 64, 128])) * (2 if bits == 3 else 1)
+    d = block * int(rng.integers(1, max(2, 1536 // block)))
+    sb = int(rng.choice([2, 4]))
+    N = int(rng.choice([4, 8, 16, 32, 64]))
+    T = int(rng.integers(1, 70))
+    V = int(rng.integers(max(2, T // 8), 300))
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, T=T, L=1, name=f"nf random seed {seed}: nf{bits} "
+                  f"block{block} sb{sb} d{d} N{N} T{T}")
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    li["W_r"] = wl.to_storage(wl.storage_to_f64(li["W_r"], w.dtype) * 5.0, w.dtype)
+    residual, dedup = bool(rng.integers(2)), bool(rng.integers(2))
+    out, gates, rows, err = run_nf_forward(w, table, li, ids, bits, block, sb, dedup=dedup, residual=residual)
+    ref, ref_g, ref_rows, ref_err = oracle_nf_forward(table, li, ids, bits, block, residual=residual)
+    assert err == 0 == ref_err
+    np.testing.assert_array_equal(rows, ref_rows)
+    assert_close(gates[0].astype(np.float64), ref_g, wl.BF16, "gates")
+    assert_close(wl.storage_to_f64(out[0], wl.BF16), ref, wl.BF16, f"nf forward ({w.name})")
+
+
 def test_layers_and_bad_ids():
     w = wl.scaled(wl.CONFIGS["decode410m"], V=400, d=1024, N=16, T=64, L=3)
     tabs = [wl.random_table(w, l) for l in range(w.L)]
