@@ -79,6 +79,25 @@ def test_generic_kernel(monkeypatch, T, V, dist):
     check_plan(plan, ids, V, uniq, U)
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_seeded_random_batches(monkeypatch, seed):
+    """T, V, the id distribution, the share of out-of-range ids and the kernel drawn at random."""
+    rng = np.random.default_rng(4000 + seed)
+    T = int(rng.choice([1, 2, 63, 64, 65, 1023, 1024, 1025, 4097, 9000, 16384, 16385, 30000]))
+    V = int(rng.choice([1, 2, 31, 32, 33, 1000, 50304, 200000]))
+    if rng.integers(3) == 0:
+        monkeypatch.setenv("MOLE_DEDUP_GENERIC", "1")
+    ids = wl.make_ids(T, V, seed=seed, dist=str(rng.choice(["zipf", "uniform"])))
+    bad = rng.random(T) < float(rng.choice([0.0, 0.01, 0.5]))
+    ids = np.where(bad, rng.choice(np.array([-1, V, V + 7, 2 ** 31 - 1], np.int64), T), ids).astype(np.int32)
+    uniq, inv, U, err, plan = run_dedup(ids, V)
+    r_uniq, r_inv, r_U, r_err = oracle.dedup(ids, V)
+    assert U == r_U and err == r_err
+    np.testing.assert_array_equal(uniq, r_uniq)
+    np.testing.assert_array_equal(inv, r_inv)
+    check_plan(plan, ids, V, uniq, U)
+
+
 def test_dedup_edge_cases():
     uniq, inv, U, err, plan = run_dedup(np.zeros((0,), np.int32), 100)
     assert U == 0 and err == 0 and plan[0] == 0 and plan[5] == 0x4D4F4C45
