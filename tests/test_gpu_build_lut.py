@@ -63,6 +63,30 @@ def test_bf16_build(monkeypatch, V, d, D, N, bias, norm, act, hidden):
     assert np.abs(ref).mean() > 1e-3
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_seeded_random_shapes(monkeypatch, seed):
+    """V, d, D, N, biases, norm, activation and the hidden format drawn at random: MFMA path (both tile
+    sizes, ragged row tiles) and plain path against the oracle."""
+    rng = np.random.default_rng(5000 + seed)
+    d = int(rng.choice([48, 64, 128, 192, 256, 320, 512]))
+    D = int(rng.choice([80, 128, 256, 384, 512, 768]))
+    N = int(rng.integers(1, 5))
+    V = int(rng.integers(1, 900))
+    bias, norm = bool(rng.integers(2)), bool(rng.integers(2))
+    act = mb.MOLE_GELU_TANH if rng.integers(2) else mb.MOLE_GELU_ERF
+    hidden = rng.choice(["", "f16", "split"])
+    if hidden:
+        monkeypatch.setenv("MOLE_BUILD_HIDDEN", str(hidden))
+    if rng.integers(2):
+        monkeypatch.setenv("MOLE_BUILD_SMALL_TILE", "1")
+    w = wl.scaled(wl.CONFIGS["offload410m"], V=V, d=d, D=D, N=N, name=f"build random seed {seed}: V{V} d{d} D{D} N{N}")
+    ew = wl.expert_weights(w, bias=bias, norm=norm)
+    got = run_build(w, ew, act=act)
+    ref = oracle.build_lut(ew["E"], ew["W1"], ew["W2"], b1=ew["b1"], b2=ew["b2"], norm_w=ew["norm_w"],
+                           act=oracle.GELU_TANH if act == mb.MOLE_GELU_TANH else oracle.GELU_ERF)
+    assert_close(wl.storage_to_f64(got, w.dtype), ref, w.dtype, f"LUT ({w.name})")
+
+
 def test_bf16_build_beyond_the_fp16_range():
     """Pre-activations of size ~1e4..1e5: many hidden activations exceed 65504, so an fp16 hidden plane
     would saturate.  The library must notice (its bound exceeds the limit) and carry hi + lo planes.
