@@ -567,6 +567,57 @@ __global__ __launch_bounds__(256) void transpose_kernel(const uint16_t *__restri
         }
 }
 
+// The same for R and Cn multiples of 64: 64 x 64 tiles, 16-byte accesses on both sides (128 contiguous
+// bytes per row segment), the transposition itself in 2-byte LDS reads.
+__global__ __launch_bounds__(256) void transpose64_kernel(const uint16_t *__restrict__ src,
+                                                           uint16_t *__restrict__ dst,
+                                                           uint16_t *__restrict__ dst16, int R, int Cn, int dst_ld)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t tile[64][72];      // rows of 144 bytes: 16-byte aligned
+    const int64_t base = (int64_t)blockIdx.z * R * Cn;
+    const int64_t dbase = (int64_t)blockIdx.z * Cn * dst_ld;
+    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int p = threadIdx.x + u * 256;            // piece: row p / 8, columns 8 * (p % 8) ..+7
+        const int r = p >> 3, cp = (p & 7) * 8;
+        *reinterpret_cast<uint4 *>(&tile[r][cp]) =
+            *reinterpret_cast<const uint4 *>(src + base + (int64_t)(r0 + r) * Cn + c0 + cp);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int p = threadIdx.x + u * 256;            // output piece: row c = p / 8, rows-of-src 8 * (p % 8) ..+7
+        const int c = p >> 3, rp = (p & 7) * 8;
+        uint16_t x[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            x[e] = tile[rp + e][c];
+        const int64_t o = dbase + (int64_t)(c0 + c) * dst_ld + r0 + rp;
+        *reinterpret_cast<uint4 *>(dst + o) =
+            make_uint4(x[0] | (uint32_t)x[1] << 16, x[2] | (uint32_t)x[3] << 16, x[4] | (uint32_t)x[5] << 16,
+                       x[6] | (uint32_t)x[7] << 16);
+        if (dst16) {
+            uint16_t hx[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                hx[e] = __builtin_bit_cast(uint16_t, (_Float16)bf16_to_f32(x[e]));
+            *reinterpret_cast<uint4 *>(dst16 + o) =
+                make_uint4(hx[0] | (uint32_t)hx[1] << 16, hx[2] | (uint32_t)hx[3] << 16, hx[4] | (uint32_t)hx[5] << 16,
+                           hx[6] | (uint32_t)hx[7] << 16);
+        }
+    }
+}
+
+// dst[b][c][r] = src[b][r][c] for N matrices of R x Cn: the 64 x 64 kernel when shapes and row stride allow
+void launch_transpose(const uint16_t *src, uint16_t *dst, uint16_t *dst16, int R, int Cn, int dst_ld, int N, hipStream_t st)
+{
+    if (R % 64 == 0 && Cn % 64 == 0 && dst_ld % 8 == 0)
+        hipLaunchKernelGGL(transpose64_kernel, dim3(Cn / 64, R / 64, N), dim3(256), 0, st, src, dst, dst16, R, Cn, dst_ld);
+    else
+        hipLaunchKernelGGL(transpose_kernel, dim3(Cn / 32, R / 32, N), dim3(256), 0, st, src, dst, dst16, R, Cn, dst_ld);
+}
+
 // ---- choice of the hidden-activation format -----------------------------------------------
 // bound[0] = max over rows of sum of squares (rows of X), bound[1] = the same for the rows of W1^T
 // (= columns of W1), bound[2] = max |b1|, bound[3] = max |W2|.  Non-negative floats order like their
@@ -577,45 +628,97 @@ __global__ __launch_bounds__(64) void bound_clear_kernel(unsigned *bound)
         bound[threadIdx.x] = 0u;
 }
 
+// sum of the squares of the 8 bf16 values of a 16-byte piece
+__device__ __forceinline__ float piece_sumsq(const uint4 &v, float ss)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        ss = fmaf(bf16lo(w[e]), bf16lo(w[e]), ss);
+        ss = fmaf(bf16hi(w[e]), bf16hi(w[e]), ss);
+    }
+    return ss;
+}
+
+// One atomicMax per workgroup, and none when the stored bound already covers the group's value: thousands
+// of atomics on one address are served one after the other and would cost more than the reduction's reads.
+__device__ __forceinline__ void group_max_to(unsigned *out, float wave_best)
+{
+    __shared__ float part[4];
+    if ((threadIdx.x & 63) == 0)
+        part[threadIdx.x >> 6] = wave_best;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float b = part[0];
+        for (int w = 1; w < (int)(blockDim.x >> 6); ++w)
+            b = (part[w] == part[w]) ? fmaxf(b, part[w]) : INFINITY;
+        const unsigned bits = __float_as_uint(b);        // b >= 0 and not NaN: the bit patterns order like the values
+        if (bits > __hip_atomic_load(out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+            atomicMax(out, bits);
+    }
+}
+
+// A wavefront takes RB rows at a time so that RB loads per lane are in flight (one row of 1024 values
+// is only two 16-byte pieces per lane: a row at a time is bound by latency).
 __global__ __launch_bounds__(256) void row_sumsq_max_kernel(const uint16_t *__restrict__ M, int64_t rows, int cols,
                                                              int ld, unsigned *out)
 {
+    constexpr int RB = 4;
     const int lane = threadIdx.x & 63;
     float best = 0.f;
-    for (int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); r < rows; r += (int64_t)gridDim.x * 4) {
-        float ss = 0.f;
-        for (int k = lane * 8; k < cols; k += 512) {          // cols is a multiple of 16
-            const uint4 v = *reinterpret_cast<const uint4 *>(M + r * ld + k);
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    for (int64_t r0 = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RB; r0 < rows; r0 += (int64_t)gridDim.x * 4 * RB) {
+        float ss[RB];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                ss = fmaf(bf16lo(w[e]), bf16lo(w[e]), ss);
-                ss = fmaf(bf16hi(w[e]), bf16hi(w[e]), ss);
-            }
+        for (int u = 0; u < RB; ++u)
+            ss[u] = 0.f;
+        for (int k = lane * 8; k < cols; k += 512) {          // cols is a multiple of 16
+            uint4 v[RB];
+#pragma unroll
+            for (int u = 0; u < RB; ++u)
+                v[u] = r0 + u < rows ? *reinterpret_cast<const uint4 *>(M + (r0 + u) * ld + k) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int u = 0; u < RB; ++u)
+                ss[u] = piece_sumsq(v[u], ss[u]);
         }
 #pragma unroll
-        for (int o = 32; o >= 1; o >>= 1)
-            ss += __shfl_xor(ss, o);
-        best = fmaxf(best, ss);                               // a NaN row leaves best unchanged or NaN
-        if (!(ss == ss))
-            best = INFINITY;
+        for (int u = 0; u < RB; ++u) {
+            float s1 = ss[u];
+#pragma unroll
+            for (int o = 32; o >= 1; o >>= 1)
+                s1 += __shfl_xor(s1, o);
+            best = fmaxf(best, s1);                           // a NaN row leaves best unchanged or NaN
+            if (!(s1 == s1))
+                best = INFINITY;
+        }
     }
-    if (lane == 0)
-        atomicMax(out, __float_as_uint(best));
+    group_max_to(out, best);
 }
 
+// max |x| over n bf16 values (x 16-byte aligned): 16-byte pieces, the last n % 8 values one by one
 __global__ __launch_bounds__(256) void abs_max_kernel(const uint16_t *__restrict__ x, int64_t n, unsigned *out)
 {
     float best = 0.f;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-        const float v = fabsf(bf16_to_f32(x[i]));
+    auto take = [&](float v) {
+        v = fabsf(v);
         best = v == v ? fmaxf(best, v) : INFINITY;
+    };
+    const int64_t n8 = n >> 3;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (int64_t)gridDim.x * 256) {
+        const uint4 v = reinterpret_cast<const uint4 *>(x)[i];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            take(bf16lo(w[e]));
+            take(bf16hi(w[e]));
+        }
     }
+    if (blockIdx.x == 0)
+        for (int64_t i = (n8 << 3) + threadIdx.x; i < n; i += 256)
+            take(bf16_to_f32(x[i]));
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1)
         best = fmaxf(best, __shfl_xor(best, o));
-    if ((threadIdx.x & 63) == 0)
-        atomicMax(out, __float_as_uint(best));
+    group_max_to(out, best);
 }
 
 __global__ __launch_bounds__(64) void choose_mode_kernel(const unsigned *bound, int *mode, int forced)
@@ -838,10 +941,8 @@ mole_status build_mfma(const void *Em, const void *W1, const void *b1, const voi
     unsigned *bound = reinterpret_cast<unsigned *>(ws + lay.ctl);
     int *mode = reinterpret_cast<int *>(ws + lay.ctl) + 8;
     const int ldw1 = d + LD_PAD, ldh = D + LD_PAD;      // row strides of W1^T, and of W2^T and the hidden planes
-    hipLaunchKernelGGL(transpose_kernel, dim3(D / 32, d / 32, N), dim3(256), 0, st,
-                       static_cast<const uint16_t *>(W1), w1t, static_cast<uint16_t *>(nullptr), d, D, ldw1);
-    hipLaunchKernelGGL(transpose_kernel, dim3(d / 32, D / 32, N), dim3(256), 0, st,
-                       static_cast<const uint16_t *>(W2), w2t, w2t16, D, d, ldh);
+    launch_transpose(static_cast<const uint16_t *>(W1), w1t, nullptr, d, D, ldw1, N, st);
+    launch_transpose(static_cast<const uint16_t *>(W2), w2t, w2t16, D, d, ldh, N, st);
     const uint16_t *X = static_cast<const uint16_t *>(Em);
     int x_planes = 1;
     if (norm_w) {
@@ -853,10 +954,11 @@ mole_status build_mfma(const void *Em, const void *W1, const void *b1, const voi
     // format of the hidden activation: fp16 if it provably cannot overflow, else bf16 hi + lo
     const unsigned cap = (unsigned)num_cus() * 8;
     hipLaunchKernelGGL(bound_clear_kernel, dim3(1), dim3(64), 0, st, bound);
-    hipLaunchKernelGGL(row_sumsq_max_kernel, dim3((unsigned)((V + 3) / 4 < cap ? (V + 3) / 4 : cap)), dim3(256), 0, st,
+    // (a workgroup takes 16 rows per round: 4 waves x 4 rows)
+    hipLaunchKernelGGL(row_sumsq_max_kernel, dim3((unsigned)((V + 15) / 16 < cap ? (V + 15) / 16 : cap)), dim3(256), 0, st,
                        X, V, d, d, bound + 0);
     const int64_t w1rows = (int64_t)N * D;
-    hipLaunchKernelGGL(row_sumsq_max_kernel, dim3((unsigned)((w1rows + 3) / 4 < cap ? (w1rows + 3) / 4 : cap)),
+    hipLaunchKernelGGL(row_sumsq_max_kernel, dim3((unsigned)((w1rows + 15) / 16 < cap ? (w1rows + 15) / 16 : cap)),
                        dim3(256), 0, st, w1t, w1rows, d, ldw1, bound + 1);
     if (b1)
         hipLaunchKernelGGL(abs_max_kernel, dim3(64), dim3(256), 0, st, static_cast<const uint16_t *>(b1),
