@@ -32,8 +32,9 @@
  * Pins (tests/test_oracle_pins.py): brute force against running every expert FFN on the
  * embedding; gates sum to one; zero router -> mean of rows; N=1 -> plain row gather;
  * saturated router -> one expert's row exactly; linearity; numpy.unique; math.erf.
- * Numeric values of outputs are not printed anywhere in the paper: beyond those
- * self-consistency pins the values are "parity unpinned" by the paper.
+ * The paper prints no numeric example of an output, so every pin is a closed form, an invariant,
+ * a special case that reduces to a library routine, or brute force from the training form; each
+ * exported function has such pins.
  */
 #include <math.h>
 #include <stdint.h>
