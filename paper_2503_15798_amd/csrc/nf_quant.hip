@@ -54,9 +54,13 @@ struct NfArgs {
 // decoded only where it is used: any arithmetic right behind a load makes the compiler wait for that
 // load before it issues the next one, which serialises the N loads of a chunk (measured: 1.7x on the
 // whole kernel).
-__device__ __forceinline__ uint32_t load_scale_raw(const void *scales, int scale_bytes, int64_t idx)
+//
+// Every load of a chunk is written as (wave-uniform 64-bit base) + (32-bit unsigned lane offset): that is
+// the scalar-base form of a global load, whose address costs no vector instruction.  With 64-bit lane
+// addresses each of the 2N loads of a chunk took three to five 64-bit vector adds and shifts.
+template <typename W> __device__ __forceinline__ uint32_t ld_uniform(const void *base, uint32_t lane_bytes)
 {
-    return static_cast<const uint32_t *>(scales)[scale_bytes == 4 ? idx : idx >> 1];
+    return *reinterpret_cast<const W *>(static_cast<const uint8_t *>(base) + (uint64_t)lane_bytes);
 }
 __device__ __forceinline__ float decode_scale(uint32_t raw, int scale_bytes, int odd)
 {
@@ -161,16 +165,16 @@ __global__ __launch_bounds__(256) void nf_quantize_kernel(const uint16_t *__rest
 // ------------------------------------------------------------------------------------------
 // code word of the lane's 8 columns of row j, chunk at column `col`: NF4 one dword (4 bits per
 // element); NF3 the 24-bit word (3 bits per element) assembled from its two planes
-// (the two NF3 planes are kept as loaded and joined where they are used, see load_scale_raw)
+// (the two NF3 planes are kept as loaded and joined where they are used, see ld_uniform)
 template <int BITS>
-__device__ __forceinline__ void load_codes(uint32_t &lo, uint32_t &hi, const uint8_t *rowp, int d, int col)
+__device__ __forceinline__ void load_codes(uint32_t &lo, uint32_t &hi, const uint8_t *rowp, uint32_t vo_lo, uint32_t vo_hi)
 {
     if (BITS == 4) {
-        lo = *reinterpret_cast<const uint32_t *>(rowp + col / 2);
+        lo = ld_uniform<uint32_t>(rowp, vo_lo);
         hi = 0;
     } else {
-        lo = *reinterpret_cast<const uint16_t *>(rowp + col / 4);
-        hi = rowp[d / 4 + col / 8];
+        lo = ld_uniform<uint16_t>(rowp, vo_lo);
+        hi = ld_uniform<uint8_t>(rowp, vo_hi);
     }
 }
 
@@ -230,15 +234,42 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
     __syncthreads();
 
     // code words and scales of the wave's first token go in flight before anything else
-    int sc_odd = 0;   // parity of the scale index of row 0 of the chunk held in sc[] (bf16 scales)
+    // col / block by a multiplication: exact for col < d <= 65535 (col * block < 2^32)
+    const uint32_t block_magic = (uint32_t)(0x100000000ull / (uint32_t)a.block) + 1u;
+    const int sbytes_is4 = scale_bytes == 4;
+    int sc_odd = 0;   // parity of the scale index of row 0 of the chunk held in sc[] (bf16 scales; per lane)
     auto load_chunk = [&](uint32_t (&cw)[N], uint32_t (&ch)[N], uint32_t (&sc)[N], int64_t row, int col) {
-        const uint8_t *rp = codes + row * (int64_t)N * row_bytes;
-        const int64_t sidx = sc_off + row * (int64_t)N * nblk + col / a.block;
-        sc_odd = (int)(sidx & 1);
+        const uint8_t *rp = codes + row * (int64_t)N * row_bytes;                       // uniform
+        const int64_t s0 = sc_off + row * (int64_t)N * nblk;                            // uniform: scale index of (row, 0, 0)
+        const uint32_t q = __umulhi((uint32_t)col, block_magic);                        // the lane's block within the row
+        const uint32_t vo_lo = BITS == 4 ? (uint32_t)col >> 1 : (uint32_t)col >> 2;
+        const uint32_t vo_hi = (uint32_t)(d >> 2) + ((uint32_t)col >> 3);
+        // Expert j's data lie j row_bytes (codes) and j nblk scales further on: those steps go into the lane
+        // offset (one 32-bit add per load) so that one base serves all N loads; a base per expert would
+        // need 4N scalar registers.  bf16 scales are read as the aligned dword that holds them: with
+        // e = p0 + q the lane's element index relative to the even element at or below s0, expert j's scale
+        // is in dword (e + j nblk) >> 1, which advances by exactly nblk per two experts.
+        const uint32_t p0 = sbytes_is4 ? 0u : (uint32_t)s0 & 1u;
+        const uint32_t e0 = p0 + q;
+        uint32_t vs[2] = {sbytes_is4 ? e0 << 2 : (e0 >> 1) << 2,
+                          sbytes_is4 ? (e0 + (uint32_t)nblk) << 2 : ((e0 + (uint32_t)nblk) >> 1) << 2};
+        const uint32_t vs_step = sbytes_is4 ? (uint32_t)nblk << 3 : (uint32_t)nblk << 2;   // bytes per two experts
+        sc_odd = (int)(e0 & 1u);
+        const uint8_t *sbase = static_cast<const uint8_t *>(a.scales) + (sbytes_is4 ? s0 << 2 : (s0 >> 1) << 2);
+        uint32_t vc_lo = vo_lo, vc_hi = vo_hi;
 #pragma unroll
         for (int j = 0; j < N; ++j) {
-            load_codes<BITS>(cw[j], ch[j], rp + (int64_t)j * row_bytes, d, col);
-            sc[j] = load_scale_raw(a.scales, scale_bytes, sidx + (int64_t)j * nblk);
+            load_codes<BITS>(cw[j], ch[j], rp, vc_lo, vc_hi);
+            sc[j] = ld_uniform<uint32_t>(sbase, vs[j & 1]);
+            vc_lo += (uint32_t)row_bytes;
+            vs[j & 1] += vs_step;
+            // keep these running sums: rewritten as offset + j * step they need a scalar register per product
+            asm volatile("" : "+v"(vc_lo));
+            asm volatile("" : "+v"(vs[j & 1]));
+            if (BITS == 3) {
+                vc_hi += (uint32_t)row_bytes;
+                asm volatile("" : "+v"(vc_hi));
+            }
         }
     };
     const int dlast = d - 8;
@@ -287,7 +318,7 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
 #pragma unroll
             for (int j = 0; j < N; ++j) {
                 w[j] = BITS == 4 ? cw[j] : (cw[j] | (ch[j] << 16));
-                gsc[j] = gs[j] * decode_scale(sc[j], scale_bytes, (sc_odd + j * nblk) & 1);
+                gsc[j] = gs[j] * decode_scale(sc[j], scale_bytes, (j & 1) ? sc_odd ^ (nblk & 1) : sc_odd);
             }
             if (last ? nvalid : valid)
                 load_chunk(cw, ch, sc, last ? nrow : row, min(last ? col0 : cc + 512, dlast));
