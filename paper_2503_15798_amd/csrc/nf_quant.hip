@@ -19,7 +19,8 @@
 // The forward kernel is the bf16 streaming kernel with the row ring replaced by code words: a
 // lane's eight columns of one row are 4 bytes (NF4) or 3 bytes (NF3), so ALL rows of a token's
 // 512-column chunk sit in N registers and the next chunk / next token is prefetched behind them.
-// Levels are looked up in a 16-entry fp32 table in LDS (one entry per bank: conflict-free).
+// Levels are looked up two at a time (the same column of two experts) in a table of fp16 pairs in LDS and
+// multiplied by the fp16 pair of the experts' weights in one dot-product instruction.
 #include "fwd_common.h"
 #include "nf_codebook.h"
 
@@ -178,20 +179,52 @@ __device__ __forceinline__ void load_codes(uint32_t &lo, uint32_t &hi, const uin
     }
 }
 
-// acc[e] += gs * level[code e of w], e = 0..7.  One LDS lookup per element is the cost of this
-// kernel, so every instruction around it counts: the level table is a statically allocated LDS array
-// (its address is a compile-time constant, so no base is added per lookup; a table inside the dynamic
-// area costs one more add per element), and the index is taken already scaled by four.
-template <int BITS>
-__device__ __forceinline__ void dequant_fma8(float (&acc)[8], float gs, uint32_t w, const float *levels)
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+
+// eight fp32 values to bf16, round to nearest even, with the packed conversion instruction (one per pair);
+// this kernel is bound by vector instruction issue, and the integer sequence costs about twelve per pair
+__device__ __forceinline__ uint4 pack8_cvt(const float (&acc)[8])
 {
-    const unsigned char *base = reinterpret_cast<const unsigned char *>(levels);
-    constexpr uint32_t MASK = ((1u << BITS) - 1u) << 2;
+    uint32_t o[4];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const uint32_t a = BITS * e >= 2 ? (w >> (BITS * e - 2)) & MASK : (w << (2 - BITS * e)) & MASK;
-        acc[e] = fmaf(gs, *reinterpret_cast<const float *>(base + a), acc[e]);
+    for (int i = 0; i < 4; ++i)
+        o[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(float2_t{acc[2 * i], acc[2 * i + 1]}, bf16x2_t));
+    return make_uint4(o[0], o[1], o[2], o[3]);
+}
+constexpr size_t PAIR_TABLE_LDS = 1024;   // static LDS of the forward kernel: 256 pairs for NF4 (64 for NF3)
+
+// acc[e] += ga * level[code e of wa] + gb * level[code e of wb], e = 0..7, for the code words of TWO experts
+// and their weights gab = (ga, gb) as an fp16 pair.  The two codes of a column are merged into one index
+// (2 * BITS bits), the pair table returns both levels as an fp16 pair, and one v_dot2_f32_f16 multiplies
+// and adds both (products exact, fp32 accumulation).  Per element that is 1.4 vector instructions (index,
+// half a lookup, half a dot product) against 3 (shift, mask, fma) with one lookup per code.  The pair
+// table is a statically allocated LDS array: its address is a compile-time constant, so no base is added
+// per lookup.
+template <int BITS>
+__device__ __forceinline__ void dequant_pair8(float (&acc)[8], half2_t gab, uint32_t wa, uint32_t wb, const uint32_t *pairs)
+{
+    const unsigned char *base = reinterpret_cast<const unsigned char *>(pairs);
+    // x[0]: the merged indices of the even columns, x[1]: of the odd columns
+    uint32_t x[2];
+    constexpr int F = 2 * BITS;                                   // bits per merged index
+    if (BITS == 4) {
+        x[0] = (wa & 0x0F0F0F0Fu) | ((wb << 4) & 0xF0F0F0F0u);
+        x[1] = ((wa >> 4) & 0x0F0F0F0Fu) | (wb & 0xF0F0F0F0u);
+    } else {
+        constexpr uint32_t M0 = 0x1C71C7u;                        // bits 0-2 of every 6-bit field of a 24-bit word
+        x[0] = (wa & M0) | ((wb << 3) & (M0 << 3));
+        x[1] = ((wa >> 3) & M0) | (wb & (M0 << 3));
     }
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int o = 0; o < 2; ++o) {
+            const uint32_t a = ((x[o] >> (F * k)) & ((1u << F) - 1u)) << 2;
+            const uint32_t lv = *reinterpret_cast<const uint32_t *>(base + a);
+            acc[2 * k + o] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, lv), gab, acc[2 * k + o], false);
+        }
 }
 
 template <int N, int BITS, int WPB, bool NORM>
@@ -226,10 +259,14 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
         order = a.plan + plan_layout(T).order;
     }
 
-    __shared__ float cb[NLEV];            // level table (static: see dequant_fma8)
+    // pair table (static: see dequant_pair8): entry a | b << BITS holds (level[a], level[b]) as fp16
+    __shared__ uint32_t cb2[NLEV * NLEV];
     uint4 *router = smem;
-    if (threadIdx.x < NLEV)
-        cb[threadIdx.x] = BITS == 4 ? NF4_LEVELS[threadIdx.x] : NF3_LEVELS[threadIdx.x];
+    for (int i = threadIdx.x; i < NLEV * NLEV; i += WPB * 64) {
+        const float *lv = BITS == 4 ? NF4_LEVELS : NF3_LEVELS;
+        const half2_t pr = {(_Float16)lv[i & (NLEV - 1)], (_Float16)lv[i >> BITS]};
+        cb2[i] = __builtin_bit_cast(uint32_t, pr);
+    }
     fill_router_lds<N>(router, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
     __syncthreads();
 
@@ -312,14 +349,23 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
                 sv = ld16_stream<true>(sbase + off);
             if (on && (NORM || rbase))          // NORM: the state itself, read a second time (an L2 hit)
                 rv = ld16_stream<true>((NORM ? hbase : rbase) + off);
-            // the products gate x scale, then the registers are free for the next chunk's words
+            // the products gate x scale as fp16 pairs, then the registers are free for the next chunk's
+            // words.  They are divided by their largest (m, restored at the end) so that any table scale
+            // fits fp16: the largest weight is 1, and one below 6e-5 of it keeps an absolute error of 3e-8.
             uint32_t w[N];
             float gsc[N];
+            float m = 1.17549435e-38f;
 #pragma unroll
             for (int j = 0; j < N; ++j) {
                 w[j] = BITS == 4 ? cw[j] : (cw[j] | (ch[j] << 16));
                 gsc[j] = gs[j] * decode_scale(sc[j], scale_bytes, (j & 1) ? sc_odd ^ (nblk & 1) : sc_odd);
+                m = fmaxf(m, fabsf(gsc[j]));
             }
+            const float rm = __builtin_amdgcn_rcpf(m);
+            half2_t gp[N / 2];
+#pragma unroll
+            for (int j = 0; j < N; j += 2)
+                gp[j / 2] = half2_t{(_Float16)(gsc[j] * rm), (_Float16)(gsc[j + 1] * rm)};
             if (last ? nvalid : valid)
                 load_chunk(cw, ch, sc, last ? nrow : row, min(last ? col0 : cc + 512, dlast));
             float acc[8];
@@ -328,13 +374,16 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
                 acc[e] = 0.f;
             if (valid) {
 #pragma unroll
-                for (int j = 0; j < N; ++j)
-                    dequant_fma8<BITS>(acc, gsc[j], w[j], cb);
+                for (int j = 0; j < N; j += 2)
+                    dequant_pair8<BITS>(acc, gp[j / 2], w[j], w[j + 1], cb2);
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    acc[e] *= m;
             }
             add8(acc, sv);
             add8(acc, rv);
             if (on)
-                st16_stream(obase + off, pack8(acc));
+                st16_stream(obase + off, pack8_cvt(acc));
         }
         row = nrow;
         valid = nvalid;
@@ -366,7 +415,7 @@ mole_status launch_nf(const NfArgs &a, int scale_bytes, hipStream_t stream)
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = lds;
     }
-    int per_cu = (int)((160 * 1024) / lds);
+    int per_cu = (int)((160 * 1024) / (lds + PAIR_TABLE_LDS));
     if (per_cu > 4)
         per_cu = 4;
     if (per_cu < 1)
@@ -417,7 +466,7 @@ mole_status nf_forward_impl(const char *who, const void *codes, int64_t codes_st
         return fail(MOLE_EINVAL, "%s: unknown flags 0x%x", who, flags);
     if (with_norm && !(ln_eps >= 0.f))
         return fail(MOLE_EINVAL, "%s: ln_eps = %g must be >= 0", who, (double)ln_eps);
-    if (router_lds_bytes(d, N) + 64 > 160 * 1024)
+    if (router_lds_bytes(d, N) + 64 + PAIR_TABLE_LDS > 160 * 1024)
         return fail(MOLE_EUNSUPPORTED, "%s: router weight of %d x %d does not fit in LDS", who, d, N);
     if (T == 0)
         return MOLE_OK;
