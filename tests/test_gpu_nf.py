@@ -354,6 +354,26 @@ def test_quantisation_error_is_what_the_levels_allow():
         assert err.mean() > 1e-4          # and it is not accidentally the unquantised table
 
 
+@pytest.mark.parametrize("bits,block,sb,N", [(4, 256, 4, 16), (3, 128, 2, 8), (4, 1024, 2, 32)])
+@pytest.mark.parametrize("k", [-60, 40])
+def test_forward_is_invariant_under_power_of_two_table_scales(bits, block, sb, N, k):
+    """The kernel carries gate x scale in fp16 relative to the largest of a chunk, so a table of very small
+    or very large values must neither underflow nor overflow: scaling table and shared term by 2^k
+    (exact in bf16; codes unchanged, scales times 2^k) scales the output by exactly 2^k."""
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=200, d=1024, N=N, T=70, L=1, seed=90 + bits)
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    out0, _, _, err0 = run_nf_forward(w, table, li, ids, bits, block, sb)
+    ref, _, _, _ = oracle_nf_forward(table, li, ids, bits, block)
+    assert_close(wl.storage_to_f64(out0[0], wl.BF16), ref, wl.BF16, "unscaled")
+    f = 2.0 ** k
+    table_k = wl.to_storage(wl.storage_to_f64(table, wl.BF16) * f, wl.BF16)
+    li_k = dict(li, shared=wl.to_storage(wl.storage_to_f64(li["shared"], wl.BF16) * f, wl.BF16))
+    np.testing.assert_array_equal(wl.storage_to_f64(table_k, wl.BF16), wl.storage_to_f64(table, wl.BF16) * f)
+    outk, _, _, errk = run_nf_forward(w, table_k, li_k, ids, bits, block, sb)
+    assert err0 == errk == 0
+    np.testing.assert_array_equal(wl.storage_to_f64(outk[0], wl.BF16), wl.storage_to_f64(out0[0], wl.BF16) * f)
+
+
 @pytest.mark.parametrize("bits,block,sb", [(4, 1024, 4), (3, 128, 2)])
 def test_full_size_layer_sampled(bits, block, sb):
     """One 410M layer at full size (V = 50304, N = 16, d = 1024, T = 256), the two formats the benchmark
