@@ -352,5 +352,20 @@ __device__ __forceinline__ uint4 pack8(const float (&acc)[8])
     return o;
 }
 
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+
+// eight fp32 values to bf16, round to nearest even, with the packed conversion instruction (one per pair);
+// for the kernels that are bound by vector instruction issue: the integer sequence of pack8 costs about
+// twelve instructions per pair.  (NaN inputs give the instruction's quiet NaN, not 0x7fc0.)
+__device__ __forceinline__ uint4 pack8_cvt(const float (&acc)[8])
+{
+    uint32_t o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        o[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(float2_t{acc[2 * i], acc[2 * i + 1]}, bf16x2_t));
+    return make_uint4(o[0], o[1], o[2], o[3]);
+}
+
 }  // namespace mole
 #endif

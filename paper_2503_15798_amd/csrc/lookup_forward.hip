@@ -227,7 +227,7 @@ void fwd_bf16_stream_kernel(FwdArgs a)
             add8(acc, sv);
             add8(acc, rv);
             if (on)
-                st16_stream(obase + off, pack8(acc));
+                st16_stream(obase + off, N >= 32 ? pack8_cvt(acc) : pack8(acc));
         }
         row = nrow;
         valid = nvalid;
@@ -560,7 +560,7 @@ void fwd_bf16_run_kernel(FwdArgs a)
                     if constexpr (RES)
                         add8(o, rv[m]);
                     if (on)
-                        st16_stream(obase + (int64_t)tok[m] * d + cc, pack8(o));
+                        st16_stream(obase + (int64_t)tok[m] * d + cc, pack8_cvt(o));
                 }
             }
             // the next item's shared / residual pieces go in flight now: they travel during the gates

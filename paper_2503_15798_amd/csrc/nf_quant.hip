@@ -180,19 +180,6 @@ __device__ __forceinline__ void load_codes(uint32_t &lo, uint32_t &hi, const uin
 }
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-typedef float float2_t __attribute__((ext_vector_type(2)));
-
-// eight fp32 values to bf16, round to nearest even, with the packed conversion instruction (one per pair);
-// this kernel is bound by vector instruction issue, and the integer sequence costs about twelve per pair
-__device__ __forceinline__ uint4 pack8_cvt(const float (&acc)[8])
-{
-    uint32_t o[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-        o[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(float2_t{acc[2 * i], acc[2 * i + 1]}, bf16x2_t));
-    return make_uint4(o[0], o[1], o[2], o[3]);
-}
 constexpr size_t PAIR_TABLE_LDS = 1024;   // static LDS of the forward kernel: 256 pairs for NF4 (64 for NF3)
 
 // acc[e] += ga * level[code e of wa] + gb * level[code e of wb], e = 0..7, for the code words of TWO experts
