@@ -13,8 +13,10 @@
  *     "host" pointers are ordinary host memory.  The caller owns every buffer and the stream.
  *   - All calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = default
  *     stream) and return without synchronising.  The library allocates no device memory, keeps
- *     no global state besides a thread-local error string (and the handles of mole_lut_file_*),
- *     and never frees caller memory.
+ *     no global state besides a thread-local error string, the handles of mole_lut_file_* and
+ *     process-wide caches of device properties and kernel launch attributes (set idempotently,
+ *     so calls may come from several host threads, each on its own stream), and never frees
+ *     caller memory.
  *   - Tensors are dense, row-major, in the element type named by `mole_dtype`
  *     (MOLE_BF16: bfloat16 storage, fp32 arithmetic, one round-to-nearest-even at the store;
  *      MOLE_F32: fp32 throughout).  Token ids, slots and maps are int32.

@@ -914,12 +914,9 @@ mole_status launch_gemm(const GemmArgs &g, int batches, hipStream_t st)
 {
     const bool big = g.Nn % DBN == 0 && !getenv("MOLE_BUILD_SMALL_TILE");
     if (big) {
-        static bool attr_set = false;
-        if (!attr_set) {
-            MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_nt_direct_kernel<EPI, F16>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)D_LDS_BYTES));
-            attr_set = true;
-        }
+        static std::atomic<size_t> lds_seen{0};
+        MOLE_HIP_CHECK(ensure_dynamic_lds(lds_seen, reinterpret_cast<const void *>(&gemm_nt_direct_kernel<EPI, F16>),
+                                          D_LDS_BYTES));
         hipLaunchKernelGGL((gemm_nt_direct_kernel<EPI, F16>), dim3((g.M + DBM - 1) / DBM, g.Nn / DBN, batches),
                            dim3(D_THREADS), D_LDS_BYTES, st, g);
     } else {

@@ -23,14 +23,14 @@ void clear_error() { g_err[0] = '\0'; }
 
 int num_cus()
 {
-    static int cached = 0;
-    if (cached > 0)
-        return cached;
+    static std::atomic<int> cached{0};
+    if (cached.load(std::memory_order_relaxed) > 0)
+        return cached.load(std::memory_order_relaxed);
     int dev = 0, n = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
         return 256;   // MI355X; not cached, so a later call can still learn the real count
-    cached = n;
+    cached.store(n, std::memory_order_relaxed);
     return n;
 }
 

@@ -378,14 +378,10 @@ template <int PER>
 hipError_t launch_regs(size_t lds, hipStream_t stream, const int32_t *ids, int T, int V, int32_t *uniq, int32_t *inv,
                        int32_t *n_uniq, int32_t *err_flag, int32_t *plan)
 {
-    static size_t attr_set = 0;
-    if (lds > attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dedup_kernel_regs<PER>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess)
-            return e;
-        attr_set = lds;
-    }
+    static std::atomic<size_t> lds_seen{0};
+    const hipError_t e = ensure_dynamic_lds(lds_seen, reinterpret_cast<const void *>(&dedup_kernel_regs<PER>), lds);
+    if (e != hipSuccess)
+        return e;
     hipLaunchKernelGGL(dedup_kernel_regs<PER>, dim3(1), dim3(DEDUP_THREADS), lds, stream, ids, T, V, uniq, inv, n_uniq,
                        err_flag, plan);
     return hipGetLastError();
@@ -453,12 +449,8 @@ extern "C" mole_status mole_dedup_ids(const int32_t *ids, int T, int64_t V, int3
         MOLE_HIP_CHECK(e);
         return MOLE_OK;
     }
-    static size_t attr_set = 0;
-    if (lds > attr_set) {
-        MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&dedup_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = lds;
-    }
+    static std::atomic<size_t> lds_seen{0};
+    MOLE_HIP_CHECK(ensure_dynamic_lds(lds_seen, reinterpret_cast<const void *>(&dedup_kernel), lds));
     hipLaunchKernelGGL(dedup_kernel, dim3(1), dim3(DEDUP_THREADS), lds, stream, ids, T, (int)V, uniq, inv, n_uniq,
                        err_flag, plan, lds_counters, lds_stage);
     MOLE_HIP_CHECK(hipGetLastError());

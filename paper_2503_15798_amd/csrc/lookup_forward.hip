@@ -835,13 +835,9 @@ template <int N, int WPB, bool NTA, bool SPLIT, bool NORM>
 mole_status launch_fast(const FwdArgs &a, hipStream_t stream)
 {
     const size_t lds = router_lds_bytes(a.d, N < 4 ? 4 : N);
-    static size_t attr_set = 0;
-    if (lds > attr_set) {
-        MOLE_HIP_CHECK(hipFuncSetAttribute(
-            reinterpret_cast<const void *>(&fwd_bf16_stream_kernel<N, WPB, NTA, SPLIT, NORM>),
-            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = lds;
-    }
+    static std::atomic<size_t> lds_seen{0};
+    MOLE_HIP_CHECK(ensure_dynamic_lds(
+        lds_seen, reinterpret_cast<const void *>(&fwd_bf16_stream_kernel<N, WPB, NTA, SPLIT, NORM>), lds));
     const int items = SPLIT ? a.T * ((a.d + 511) / 512) : a.T;
     dim3 grid((unsigned)grid_x<N, WPB>(items, a.L, lds), (unsigned)a.L);
     hipLaunchKernelGGL((fwd_bf16_stream_kernel<N, WPB, NTA, SPLIT, NORM>), grid, dim3(WPB * 64), lds, stream, a);
@@ -861,12 +857,9 @@ mole_status launch_run(const FwdArgs &a, hipStream_t stream)
 {
     constexpr int NR = N < 4 ? 4 : N;
     const size_t lds = router_lds_bytes(a.d, NR) + (size_t)WPB * 2 * RUN_GROUP * NR * sizeof(float);
-    static size_t attr_set = 0;
-    if (lds > attr_set) {
-        MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_bf16_run_kernel<N, WPB, NORM, RES>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = lds;
-    }
+    static std::atomic<size_t> lds_seen{0};
+    MOLE_HIP_CHECK(ensure_dynamic_lds(lds_seen, reinterpret_cast<const void *>(&fwd_bf16_run_kernel<N, WPB, NORM, RES>),
+                                      lds));
     const int spans = (a.T + RUN_GROUP - 1) / RUN_GROUP;
     dim3 grid((unsigned)grid_x<N, WPB>(spans, a.L, lds, 8), (unsigned)a.L);    // two waves per SIMD
     hipLaunchKernelGGL((fwd_bf16_run_kernel<N, WPB, NORM, RES>), grid, dim3(WPB * 64), lds, stream, a);

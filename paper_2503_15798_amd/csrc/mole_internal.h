@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "mole.h"
 
 namespace mole {
@@ -18,6 +20,22 @@ inline size_t elem_bytes(mole_dtype dt) { return dt == MOLE_F32 ? 4 : (dt == MOL
 
 // Number of compute units of the current device (cached per process; 256 on MI355X).
 int num_cus();
+
+// Raises a kernel's dynamic-LDS limit to `lds` bytes unless a call has already raised it that far.  `seen`
+// is the per-kernel cache (a function-local static): callers on several threads may race to set the same
+// attribute, which is harmless, but must not tear the cached size.
+inline hipError_t ensure_dynamic_lds(std::atomic<size_t> &seen, const void *kernel, size_t lds)
+{
+    if (lds <= seen.load(std::memory_order_relaxed))
+        return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess) {
+        size_t cur = seen.load(std::memory_order_relaxed);
+        while (cur < lds && !seen.compare_exchange_weak(cur, lds, std::memory_order_relaxed)) {
+        }
+    }
+    return e;
+}
 
 #define MOLE_HIP_CHECK(expr)                                                             \
     do {                                                                                 \

@@ -396,12 +396,8 @@ mole_status launch_nf(const NfArgs &a, int scale_bytes, hipStream_t stream)
 {
     constexpr int WPB = 4;
     const size_t lds = router_lds_bytes(a.d, N) + 64;
-    static size_t attr_set = 0;
-    if (lds > attr_set) {
-        MOLE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_nf_kernel<N, BITS, WPB, NORM>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = lds;
-    }
+    static std::atomic<size_t> lds_seen{0};
+    MOLE_HIP_CHECK(ensure_dynamic_lds(lds_seen, reinterpret_cast<const void *>(&fwd_nf_kernel<N, BITS, WPB, NORM>), lds));
     int per_cu = (int)((160 * 1024) / (lds + PAIR_TABLE_LDS));
     if (per_cu > 4)
         per_cu = 4;
