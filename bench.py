@@ -47,6 +47,8 @@ def parse_args():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--only-build", action="store_true",
                     help="time mole_build_lut on one 410M layer and print its entry alone (for profiling)")
+    ap.add_argument("--only-nf", action="store_true",
+                    help="only the dequantising forward on --workload, NF4 and NF3 (used for its profile)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain 1 GiB device copy (reference for rocprofv3 byte counters)")
     return ap.parse_args()
@@ -313,6 +315,10 @@ def main():
 
     # ------------------------------------------------------------------ headline workload
     L = Layers(w, torch, mb, wl)
+    if args.only_nf:
+        print(json.dumps({f"{w.name}_{tag}": nf_entry(L, acc, torch, stream, args.steps, args.warmup, bits, block, sb)
+                          for tag, bits, block, sb in (("nf4", 4, 1024, 4), ("nf3", 3, 128, 2))}))
+        return
 
     if args.plan:
         L.make_plans(stream)
