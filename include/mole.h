@@ -276,7 +276,7 @@ mole_status mole_lut_file_close(mole_lut_file *file);
  * mole_quantize_lut: table bf16 [rows,N,d] dev -> codes, scales dev (sizes from the two helpers).
  * mole_lookup_forward_nf: the fused forward of mole_lookup_forward_layers with the rows
  * dequantised on the fly; activations bf16; codes_stride in BYTES per layer, scales_stride and
- * act_stride in ELEMENTS per layer (ignored for L == 1).  N in {4, 8, 16, 32, 64}.
+ * act_stride in ELEMENTS per layer (ignored for L == 1).  N in {2, 4, 8, 16, 32, 64}.
  * ---------------------------------------------------------------------------------------- */
 int mole_nf_codebook(int bits, float *levels_host);
 size_t mole_nf_codes_bytes(int64_t rows, int N, int d, int bits);

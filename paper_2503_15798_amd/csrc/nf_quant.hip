@@ -218,7 +218,8 @@ template <int N, int BITS, int WPB, bool NORM>
 __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_bytes)
 {
     extern __shared__ uint4 smem[];
-    constexpr int LPJ = 64 / N;
+    constexpr int NR = N < 4 ? 4 : N;   // experts the router is computed for (N = 2 is padded to 4)
+    constexpr int LPJ = 64 / NR;        // lanes per expert after the fold
     constexpr int NLEV = 1 << BITS;
     const int d = a.d;
     const int kgroups = d >> 3;
@@ -254,7 +255,7 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
         const half2_t pr = {(_Float16)lv[i & (NLEV - 1)], (_Float16)lv[i >> BITS]};
         cb2[i] = __builtin_bit_cast(uint32_t, pr);
     }
-    fill_router_lds<N>(router, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
+    fill_router_lds<NR, N>(router, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
     __syncthreads();
 
     // code words and scales of the wave's first token go in flight before anything else
@@ -317,8 +318,8 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
         if (a.rows_dbg && layer == 0 && lane == 0)
             a.rows_dbg[t] = valid ? row : -1;
 
-        const float g = router_gate<N, false, NORM>(router, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1, a.ln_eps);
-        if (a.gates_dbg && (lane & (LPJ - 1)) == 0)
+        const float g = router_gate<NR, false, NORM, N>(router, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1, a.ln_eps);
+        if (a.gates_dbg && (lane & (LPJ - 1)) == 0 && lane / LPJ < N)
             a.gates_dbg[((int64_t)layer * T + t) * N + lane / LPJ] = g;
         load_h2<false>(h0, h1, hbase + (int64_t)nt * d, d, lane);
         float gs[N];
@@ -395,7 +396,7 @@ template <int N, int BITS, bool NORM>
 mole_status launch_nf(const NfArgs &a, int scale_bytes, hipStream_t stream)
 {
     constexpr int WPB = 4;
-    const size_t lds = router_lds_bytes(a.d, N) + 64;
+    const size_t lds = router_lds_bytes(a.d, N < 4 ? 4 : N) + 64;
     static std::atomic<size_t> lds_seen{0};
     MOLE_HIP_CHECK(ensure_dynamic_lds(lds_seen, reinterpret_cast<const void *>(&fwd_nf_kernel<N, BITS, WPB, NORM>), lds));
     int per_cu = (int)((160 * 1024) / (lds + PAIR_TABLE_LDS));
@@ -421,12 +422,13 @@ template <int BITS, bool NORM>
 mole_status launch_nf_n(const NfArgs &a, int scale_bytes, hipStream_t stream)
 {
     switch (a.N) {
+    case 2: return launch_nf<2, BITS, NORM>(a, scale_bytes, stream);
     case 4: return launch_nf<4, BITS, NORM>(a, scale_bytes, stream);
     case 8: return launch_nf<8, BITS, NORM>(a, scale_bytes, stream);
     case 16: return launch_nf<16, BITS, NORM>(a, scale_bytes, stream);
     case 32: return launch_nf<32, BITS, NORM>(a, scale_bytes, stream);
     case 64: return launch_nf<64, BITS, NORM>(a, scale_bytes, stream);
-    default: return fail(MOLE_EUNSUPPORTED, "mole_lookup_forward_nf: N=%d, built for 4, 8, 16, 32, 64", a.N);
+    default: return fail(MOLE_EUNSUPPORTED, "mole_lookup_forward_nf: N=%d, built for 2, 4, 8, 16, 32, 64", a.N);
     }
 }
 
@@ -449,7 +451,7 @@ mole_status nf_forward_impl(const char *who, const void *codes, int64_t codes_st
         return fail(MOLE_EINVAL, "%s: unknown flags 0x%x", who, flags);
     if (with_norm && !(ln_eps >= 0.f))
         return fail(MOLE_EINVAL, "%s: ln_eps = %g must be >= 0", who, (double)ln_eps);
-    if (router_lds_bytes(d, N) + 64 + PAIR_TABLE_LDS > 160 * 1024)
+    if (router_lds_bytes(d, N < 4 ? 4 : N) + 64 + PAIR_TABLE_LDS > 160 * 1024)
         return fail(MOLE_EUNSUPPORTED, "%s: router weight of %d x %d does not fit in LDS", who, d, N);
     if (T == 0)
         return MOLE_OK;

@@ -96,6 +96,8 @@ def oracle_nf_forward(table, li, ids, bits, block, residual=False):
     (3, 64, 4, 2048, 8, 40, 200),
     (4, 104, 4, 520, 16, 9, 64),         # ragged last chunk
     (3, 16, 2, 64, 64, 50, 100),
+    (4, 1024, 4, 1024, 2, 90, 300),      # two experts: the router is padded to four
+    (3, 128, 2, 768, 2, 61, 300),
 ])
 @pytest.mark.parametrize("dedup", [False, True])
 def test_forward_matches_oracle_on_dequantised_table(bits, block, sb, d, N, T, V, dedup):
@@ -118,7 +120,7 @@ def test_seeded_random_shapes(seed):
     block = int(rng.choice([8, 16, 64, 128])) * (2 if bits == 3 else 1)
     d = block * int(rng.integers(1, max(2, 1536 // block)))
     sb = int(rng.choice([2, 4]))
-    N = int(rng.choice([4, 8, 16, 32, 64]))
+    N = int(rng.choice([2, 4, 8, 16, 32, 64]))
     T = int(rng.integers(1, 70))
     V = int(rng.integers(max(2, T // 8), 300))
     w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, T=T, L=1, name=f"nf random seed {seed}: nf{bits} "
