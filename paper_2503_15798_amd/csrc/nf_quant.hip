@@ -221,6 +221,10 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
     constexpr int NR = N < 4 ? 4 : N;   // experts the router is computed for (N = 2 is padded to 4)
     constexpr int LPJ = 64 / NR;        // lanes per expert after the fold
     constexpr int NLEV = 1 << BITS;
+    // The experts of a chunk pass through the code-word registers R at a time (N = 32: two halves, N = 64:
+    // four quarters): with all N in registers the kernel runs at two waves per SIMD or fewer.
+    constexpr int R = N > 16 ? 16 : N;
+    constexpr int H = N / R;
     const int d = a.d;
     const int kgroups = d >> 3;
     const int layer = blockIdx.y;
@@ -263,15 +267,16 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
     const uint32_t block_magic = (uint32_t)(0x100000000ull / (uint32_t)a.block) + 1u;
     const int sbytes_is4 = scale_bytes == 4;
     int sc_odd = 0;   // parity of the scale index of row 0 of the chunk held in sc[] (bf16 scales; per lane)
-    auto load_chunk = [&](uint32_t (&cw)[N], uint32_t (&ch)[N], uint32_t (&sc)[N], int64_t row, int col) {
-        const uint8_t *rp = codes + row * (int64_t)N * row_bytes;                       // uniform
-        const int64_t s0 = sc_off + row * (int64_t)N * nblk;                            // uniform: scale index of (row, 0, 0)
+    auto load_part = [&](uint32_t (&cw)[R], uint32_t (&ch)[R], uint32_t (&sc)[R], int64_t row, int col, int part) {
+        const int64_t e_row = row * (int64_t)N + part * R;                              // first expert row of the part
+        const uint8_t *rp = codes + e_row * row_bytes;                                  // uniform
+        const int64_t s0 = sc_off + e_row * nblk;                                       // uniform: scale index of its block 0
         const uint32_t q = __umulhi((uint32_t)col, block_magic);                        // the lane's block within the row
         const uint32_t vo_lo = BITS == 4 ? (uint32_t)col >> 1 : (uint32_t)col >> 2;
         const uint32_t vo_hi = (uint32_t)(d >> 2) + ((uint32_t)col >> 3);
         // Expert j's data lie j row_bytes (codes) and j nblk scales further on: those steps go into the lane
-        // offset (one 32-bit add per load) so that one base serves all N loads; a base per expert would
-        // need 4N scalar registers.  bf16 scales are read as the aligned dword that holds them: with
+        // offset (one 32-bit add per load) so that one base serves all R loads; a base per expert would
+        // need 4R scalar registers.  bf16 scales are read as the aligned dword that holds them: with
         // e = p0 + q the lane's element index relative to the even element at or below s0, expert j's scale
         // is in dword (e + j nblk) >> 1, which advances by exactly nblk per two experts.
         const uint32_t p0 = sbytes_is4 ? 0u : (uint32_t)s0 & 1u;
@@ -283,7 +288,7 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
         const uint8_t *sbase = static_cast<const uint8_t *>(a.scales) + (sbytes_is4 ? s0 << 2 : (s0 >> 1) << 2);
         uint32_t vc_lo = vo_lo, vc_hi = vo_hi;
 #pragma unroll
-        for (int j = 0; j < N; ++j) {
+        for (int j = 0; j < R; ++j) {
             load_codes<BITS>(cw[j], ch[j], rp, vc_lo, vc_hi);
             sc[j] = ld_uniform<uint32_t>(sbase, vs[j & 1]);
             vc_lo += (uint32_t)row_bytes;
@@ -302,9 +307,9 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
     int t = item < T ? visit(order, item).t : 0;
     int64_t row = item < T ? (int64_t)__builtin_amdgcn_readfirstlane(rowsrc[t]) : -1;
     bool valid = row >= 0 && row < a.rows;
-    uint32_t cw[N], ch[N], sc[N];
+    uint32_t cw[R], ch[R], sc[R];
     if (valid)
-        load_chunk(cw, ch, sc, row, min(col0, dlast));
+        load_part(cw, ch, sc, row, min(col0, dlast), 0);
     uint4 h0, h1;
     load_h2<false>(h0, h1, hbase + (int64_t)t * d, d, lane);
 
@@ -322,10 +327,13 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
         if (a.gates_dbg && (lane & (LPJ - 1)) == 0 && lane / LPJ < N)
             a.gates_dbg[((int64_t)layer * T + t) * N + lane / LPJ] = g;
         load_h2<false>(h0, h1, hbase + (int64_t)nt * d, d, lane);
-        float gs[N];
+        // gates into scalar registers: expert j's gate sits in lane j * LPJ (taken per part when there are several)
+        float gs[R];
+        if constexpr (H == 1) {
 #pragma unroll
-        for (int j = 0; j < N; ++j)
-            gs[j] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, g), j * LPJ));
+            for (int j = 0; j < N; ++j)
+                gs[j] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, g), j * LPJ));
+        }
 
         for (int c0 = 0; c0 < d; c0 += 512) {
             const int cc = c0 + col0;
@@ -337,36 +345,52 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
                 sv = ld16_stream<true>(sbase + off);
             if (on && (NORM || rbase))          // NORM: the state itself, read a second time (an L2 hit)
                 rv = ld16_stream<true>((NORM ? hbase : rbase) + off);
-            // the products gate x scale as fp16 pairs, then the registers are free for the next chunk's
-            // words.  They are divided by their largest (m, restored at the end) so that any table scale
-            // fits fp16: the largest weight is 1, and one below 6e-5 of it keeps an absolute error of 3e-8.
-            uint32_t w[N];
-            float gsc[N];
-            float m = 1.17549435e-38f;
-#pragma unroll
-            for (int j = 0; j < N; ++j) {
-                w[j] = BITS == 4 ? cw[j] : (cw[j] | (ch[j] << 16));
-                gsc[j] = gs[j] * decode_scale(sc[j], scale_bytes, (j & 1) ? sc_odd ^ (nblk & 1) : sc_odd);
-                m = fmaxf(m, fabsf(gsc[j]));
-            }
-            const float rm = __builtin_amdgcn_rcpf(m);
-            half2_t gp[N / 2];
-#pragma unroll
-            for (int j = 0; j < N; j += 2)
-                gp[j / 2] = half2_t{(_Float16)(gsc[j] * rm), (_Float16)(gsc[j + 1] * rm)};
-            if (last ? nvalid : valid)
-                load_chunk(cw, ch, sc, last ? nrow : row, min(last ? col0 : cc + 512, dlast));
             float acc[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 acc[e] = 0.f;
-            if (valid) {
 #pragma unroll
-                for (int j = 0; j < N; j += 2)
-                    dequant_pair8<BITS>(acc, gp[j / 2], w[j], w[j + 1], cb2);
+            for (int part = 0; part < H; ++part) {
+                if constexpr (H > 1) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    acc[e] *= m;
+                    for (int j = 0; j < R; ++j)
+                        gs[j] = __builtin_bit_cast(
+                            float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, g), (part * R + j) * LPJ));
+                }
+                // the products gate x scale as fp16 pairs, then the registers are free for the next part's
+                // words.  They are divided by their largest (m, restored at the end) so that any table scale
+                // fits fp16: the largest weight is 1, and one below 6e-5 of it keeps an absolute error of 3e-8.
+                uint32_t w[R];
+                float gsc[R];
+                float m = 1.17549435e-38f;
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    w[j] = BITS == 4 ? cw[j] : (cw[j] | (ch[j] << 16));
+                    gsc[j] = gs[j] * decode_scale(sc[j], scale_bytes, (j & 1) ? sc_odd ^ (nblk & 1) : sc_odd);
+                    m = fmaxf(m, fabsf(gsc[j]));
+                }
+                const float rm = __builtin_amdgcn_rcpf(m);
+                half2_t gp[R / 2];
+#pragma unroll
+                for (int j = 0; j < R; j += 2)
+                    gp[j / 2] = half2_t{(_Float16)(gsc[j] * rm), (_Float16)(gsc[j + 1] * rm)};
+                // refill: the next part of this chunk, else the next chunk / the wave's next token
+                const bool more = part + 1 < H;
+                if (more || !last ? valid : nvalid)
+                    load_part(cw, ch, sc, more || !last ? row : nrow,
+                              min(more ? cc : (last ? col0 : cc + 512), dlast), more ? part + 1 : 0);
+                if (valid) {
+                    float pa[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        pa[e] = 0.f;
+#pragma unroll
+                    for (int j = 0; j < R; j += 2)
+                        dequant_pair8<BITS>(pa, gp[j / 2], w[j], w[j + 1], cb2);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        acc[e] = fmaf(pa[e], m, acc[e]);
+                }
             }
             add8(acc, sv);
             add8(acc, rv);
@@ -395,7 +419,9 @@ mole_status nf_params_status(int d, int bits, int block, int scale_bytes, const 
 template <int N, int BITS, bool NORM>
 mole_status launch_nf(const NfArgs &a, int scale_bytes, hipStream_t stream)
 {
-    constexpr int WPB = 4;
+    // N >= 32: the router weight (64 KiB at N = 32, d = 1024) leaves room for two workgroups per CU, so the
+    // waves that the registers allow (three or four per SIMD) have to come from larger workgroups
+    constexpr int WPB = N >= 32 ? 8 : 4;
     const size_t lds = router_lds_bytes(a.d, N < 4 ? 4 : N) + 64;
     static std::atomic<size_t> lds_seen{0};
     MOLE_HIP_CHECK(ensure_dynamic_lds(lds_seen, reinterpret_cast<const void *>(&fwd_nf_kernel<N, BITS, WPB, NORM>), lds));
