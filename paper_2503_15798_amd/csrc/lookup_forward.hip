@@ -71,13 +71,13 @@ __device__ __forceinline__ void ring_load(uint4 (&r)[N], const uint16_t *base, i
 // NORM: a.h is the state after attention and a.W_r carries the norm weight (mole_fold_router_norm);
 // the token's 1/rms scales the logits and the same state is the residual of the epilogue.
 template <int N, int WPB, bool NTA, bool SPLIT, bool NORM>
-__global__ __launch_bounds__(WPB * 64) __attribute__((amdgpu_waves_per_eu(N <= 16 ? 4 : 2)))
+__global__ __launch_bounds__(WPB * 64) __attribute__((amdgpu_waves_per_eu(N <= 32 ? 4 : 2)))
 void fwd_bf16_stream_kernel(FwdArgs a)
 {
     extern __shared__ uint4 smem[];
     constexpr int NR = N < 4 ? 4 : N;   // experts the router is computed for (N = 2 is padded to 4)
     constexpr int LPJ = 64 / NR;        // lanes per expert after the fold
-    constexpr int R = N > 32 ? 32 : N;  // row registers: at N = 64 the experts of a chunk pass through in two halves
+    constexpr int R = N > 16 ? 16 : N;  // row registers: above 16 experts a chunk's rows pass through in parts of 16
     constexpr int H = N / R;
 #ifndef MOLE_FWD_HOLD_X
 #define MOLE_FWD_HOLD_X (N != 16 || !NTA)
@@ -200,7 +200,7 @@ void fwd_bf16_stream_kernel(FwdArgs a)
                         ring_load<R, false>(r, fb, d, fcol);
                 }
             } else {
-                // N = 64: the chunk's experts pass through the row registers in halves of 32
+                // N > 16: the chunk's experts pass through the row registers in parts of R
 #pragma unroll
                 for (int hf = 0; hf < H; ++hf) {
 #pragma unroll
@@ -809,7 +809,7 @@ int env_int(const char *name, int dflt)
 // tail).  Residency per CU is bounded by LDS and by registers (4 waves per SIMD for N <= 16,
 // 2 above).  Returns the number of workgroups per layer.
 template <int N, int WPB>
-int64_t grid_x(int items, int L, size_t lds, int waves_per_cu = N <= 16 ? 16 : 8)
+int64_t grid_x(int items, int L, size_t lds, int waves_per_cu = N <= 32 ? 16 : 8)
 {
     int per_cu = (int)(LDS_BYTES_PER_CU / lds);
     const int wave_cap = waves_per_cu / WPB;
