@@ -809,7 +809,7 @@ int env_int(const char *name, int dflt)
 // tail).  Residency per CU is bounded by LDS and by registers (4 waves per SIMD for N <= 16,
 // 2 above).  Returns the number of workgroups per layer.
 template <int N, int WPB>
-int64_t grid_x(int items, int L, size_t lds, int waves_per_cu = N <= 32 ? 16 : 8)
+int64_t grid_x(int items, int L, size_t lds, int waves_per_cu = N <= 32 ? 16 : 8, bool halve_items = false)
 {
     int per_cu = (int)(LDS_BYTES_PER_CU / lds);
     const int wave_cap = waves_per_cu / WPB;
@@ -825,7 +825,12 @@ int64_t grid_x(int items, int L, size_t lds, int waves_per_cu = N <= 32 ? 16 : 8
     // smallest items-per-wave whose grid fits: ceil(items / (WPB * ipw)) <= cap
     int64_t gx = (items + WPB - 1) / WPB;
     if (gx > cap) {
-        const int64_t ipw = (items + cap * WPB - 1) / (cap * WPB);
+        int64_t ipw = (items + cap * WPB - 1) / (cap * WPB);
+        // halve_items (the streaming kernel at N >= 32: eight-wave workgroups, two per CU): from four items per
+        // wave on, twice as many workgroups with half the items each even out the tail (T = 16384: 211 ->
+        // 202 us with uniform ids, 116 -> 108 us with Zipf ids; one item per wave is worse again)
+        if (halve_items && ipw >= 4 && !env_int("MOLE_FWD_WGS_PER_CU", 0))
+            ipw = (ipw + 1) / 2;
         gx = (items + WPB * ipw - 1) / (WPB * ipw);
     }
     return gx < 1 ? 1 : gx;
@@ -839,7 +844,7 @@ mole_status launch_fast(const FwdArgs &a, hipStream_t stream)
     MOLE_HIP_CHECK(ensure_dynamic_lds(
         lds_seen, reinterpret_cast<const void *>(&fwd_bf16_stream_kernel<N, WPB, NTA, SPLIT, NORM>), lds));
     const int items = SPLIT ? a.T * ((a.d + 511) / 512) : a.T;
-    dim3 grid((unsigned)grid_x<N, WPB>(items, a.L, lds), (unsigned)a.L);
+    dim3 grid((unsigned)grid_x<N, WPB>(items, a.L, lds, N <= 32 ? 16 : 8, N >= 32), (unsigned)a.L);
     hipLaunchKernelGGL((fwd_bf16_stream_kernel<N, WPB, NTA, SPLIT, NORM>), grid, dim3(WPB * 64), lds, stream, a);
     MOLE_HIP_CHECK(hipGetLastError());
     return MOLE_OK;

@@ -435,7 +435,11 @@ mole_status launch_nf(const NfArgs &a, int scale_bytes, hipStream_t stream)
         cap = 1;
     int64_t gx = (a.T + WPB - 1) / WPB;
     if (gx > cap) {
-        const int64_t ipw = (a.T + cap * WPB - 1) / (cap * WPB);
+        int64_t ipw = (a.T + cap * WPB - 1) / (cap * WPB);
+        // NF4 at N >= 32: from four tokens per wave on, twice the workgroups with half the tokens each even out
+        // the tail (T = 16384: 101 -> 92 us); NF3 (three waves per SIMD) gains nothing from it
+        if (N >= 32 && BITS == 4 && ipw >= 4)
+            ipw = (ipw + 1) / 2;
         gx = (a.T + WPB * ipw - 1) / (WPB * ipw);
     }
     hipLaunchKernelGGL((fwd_nf_kernel<N, BITS, WPB, NORM>), dim3((unsigned)gx, (unsigned)a.L), dim3(WPB * 64), lds, stream,
