@@ -277,6 +277,10 @@ mole_status mole_lut_file_close(mole_lut_file *file);
  * mole_lookup_forward_nf: the fused forward of mole_lookup_forward_layers with the rows
  * dequantised on the fly; activations bf16; codes_stride in BYTES per layer, scales_stride and
  * act_stride in ELEMENTS per layer (ignored for L == 1).  N in {2, 4, 8, 16, 32, 64}.
+ * Arithmetic: gates in fp32 (as reported through gates_dbg); the levels and, per 512-column chunk,
+ * the products gate * scale divided by their largest are rounded to fp16, multiplied exactly and
+ * accumulated in fp32 (relative error about 2^-10 per term, independent of the table's magnitude);
+ * shared / residual terms are added in fp32 and the result is rounded once to bf16.
  * ---------------------------------------------------------------------------------------- */
 int mole_nf_codebook(int bits, float *levels_host);
 size_t mole_nf_codes_bytes(int64_t rows, int N, int d, int bits);
