@@ -276,7 +276,9 @@ mole_status mole_lut_file_close(mole_lut_file *file);
  * mole_quantize_lut: table bf16 [rows,N,d] dev -> codes, scales dev (sizes from the two helpers).
  * mole_lookup_forward_nf: the fused forward of mole_lookup_forward_layers with the rows
  * dequantised on the fly; activations bf16; codes_stride in BYTES per layer, scales_stride and
- * act_stride in ELEMENTS per layer (ignored for L == 1).  N in {2, 4, 8, 16, 32, 64}.
+ * act_stride in ELEMENTS per layer (ignored for L == 1).  N in {2, 4, 8, 16, 32, 64}; the router
+ * weight, d * max(N, 4) * 2 bytes, has to fit in LDS next to the level table (about 158 KiB),
+ * else MOLE_EUNSUPPORTED.
  * Arithmetic: gates in fp32 (as reported through gates_dbg); the levels and, per 512-column chunk,
  * the products gate * scale divided by their largest are rounded to fp16, multiplied exactly and
  * accumulated in fp32 (relative error about 2^-10 per term, independent of the table's magnitude);
