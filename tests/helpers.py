@@ -40,3 +40,15 @@ def assert_close(got_f64, ref_f64, dtype, what="", extra_atol=0.0):
         i = np.unravel_index(np.argmax(err - lim), err.shape)
         raise AssertionError(f"{what}: {bad.sum()} of {bad.size} elements out of tolerance; worst at {i}: "
                              f"got {got_f64[i]!r}, ref {ref_f64[i]!r}, |err| {err[i]:.3e} > {lim[i]:.3e}")
+
+
+def folded_router(ln_w, W_r, dtype, d):
+    """(unit norm weight, router weight with the norm weight folded in and rounded to the storage type):
+    what mole_fold_router_norm stores, computed on the host -- the product of two stored values rounded
+    once has the same bits either way.  The outputs of the fused-norm calls are compared with the oracle
+    on these (the rounding of the folded weight shifts the gates within their tolerance, which can exceed
+    atol on an output where state, shared and routed terms cancel)."""
+    import numpy as np
+    from paper_2503_15798_amd import workloads as wl
+    folded = wl.to_storage(wl.storage_to_f64(ln_w, dtype)[:, None] * wl.storage_to_f64(W_r, dtype), dtype)
+    return wl.to_storage(np.ones(d), dtype), folded

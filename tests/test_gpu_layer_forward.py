@@ -6,7 +6,7 @@ import pytest
 import oracle
 from paper_2503_15798_amd import binding as mb
 from paper_2503_15798_amd import workloads as wl
-from helpers import DT, assert_close, to_dev, to_host
+from helpers import DT, assert_close, folded_router, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 EPS = 1e-5
@@ -54,9 +54,7 @@ def check(w, table, ids, inp, shared=True, dedup=False, eps=EPS):
     cancel, that shift of the routed term alone can exceed atol."""
     sh = inp["shared"] if shared else None
     _, ref_g, _, ref_rows, ref_err = oracle.layer_forward(table, ids, inp["x"], inp["ln_w"], eps, inp["W_r"], sh)
-    folded = wl.to_storage(wl.storage_to_f64(inp["ln_w"], w.dtype)[:, None] * wl.storage_to_f64(inp["W_r"], w.dtype),
-                           w.dtype)
-    ones = wl.to_storage(np.ones(w.d), w.dtype)
+    ones, folded = folded_router(inp["ln_w"], inp["W_r"], w.dtype, w.d)
     ref_out, ref_gf, _, _, _ = oracle.layer_forward(table, ids, inp["x"], ones, eps, folded, sh)
     got = run(w, table, ids, inp, shared=shared, dedup=dedup, eps=eps)
     np.testing.assert_array_equal(got["rows"], ref_rows)
@@ -163,8 +161,8 @@ def test_layers_in_one_launch_match_single_layer_calls():
     torch.cuda.synchronize()
     out = to_host(out_d, w.dtype)
     for l in range(L):
-        ref, *_ = oracle.layer_forward(tabs[l], ids, inps[l]["x"], inps[l]["ln_w"], EPS, inps[l]["W_r"],
-                                       inps[l]["shared"])
+        ones, folded = folded_router(inps[l]["ln_w"], inps[l]["W_r"], w.dtype, d)
+        ref, *_ = oracle.layer_forward(tabs[l], ids, inps[l]["x"], ones, EPS, folded, inps[l]["shared"])
         assert_close(wl.storage_to_f64(out[l], w.dtype), ref, w.dtype, f"layer {l}")
         single = run(w, tabs[l], ids, inps[l])
         np.testing.assert_array_equal(single["out"], out[l])
@@ -235,6 +233,7 @@ def test_full_size_single_layer_sampled(name, dedup):
     sample = np.unique(np.concatenate([np.random.default_rng(6).integers(0, w.T, 48), [0, w.T - 1],
                                        np.argsort(ids)[-3:]]))
     rows = to_host(tab_d[torch.from_numpy(ids[sample].astype(np.int64)).cuda()], w.dtype)
-    ref, *_ = oracle.layer_forward(rows, np.arange(len(sample), dtype=np.int32), inp["x"][sample], inp["ln_w"], EPS,
-                                   inp["W_r"], inp["shared"][sample])
+    ones, folded = folded_router(inp["ln_w"], inp["W_r"], w.dtype, w.d)
+    ref, *_ = oracle.layer_forward(rows, np.arange(len(sample), dtype=np.int32), inp["x"][sample], ones, EPS,
+                                   folded, inp["shared"][sample])
     assert_close(wl.storage_to_f64(out[sample], w.dtype), ref, w.dtype, f"{name} fused-norm sample")

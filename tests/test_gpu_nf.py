@@ -8,7 +8,7 @@ import oracle
 from oracle import nf_codec as nf
 from paper_2503_15798_amd import binding as mb
 from paper_2503_15798_amd import workloads as wl
-from helpers import assert_close, to_dev, to_host
+from helpers import assert_close, folded_router, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -336,7 +336,9 @@ def test_layer_forward_on_quantised_table(bits, block, sb, d, N, T, V, dedup):
     torch.cuda.synchronize()
     q_codes, q_scales = nf.quantize(wl.bf16_bits_to_f32(table), bits, block)
     deq = nf.dequantize(q_codes, q_scales, bits, block)
-    ref, ref_g, _, ref_rows, ref_err = oracle.layer_forward(deq, ids, ni["x"], ni["ln_w"], 1e-5, W_r, li["shared"])
+    _, ref_g, _, ref_rows, ref_err = oracle.layer_forward(deq, ids, ni["x"], ni["ln_w"], 1e-5, W_r, li["shared"])
+    ones, folded = folded_router(ni["ln_w"], W_r, wl.BF16, d)
+    ref, *_ = oracle.layer_forward(deq, ids, ni["x"], ones, 1e-5, folded, li["shared"])
     assert int(err.item()) == ref_err
     np.testing.assert_array_equal(rows_d.cpu().numpy(), ref_rows)
     assert_close(gates_d.cpu().numpy().astype(np.float64), ref_g, wl.BF16, "gates")
