@@ -52,3 +52,19 @@ def folded_router(ln_w, W_r, dtype, d):
     from paper_2503_15798_amd import workloads as wl
     folded = wl.to_storage(wl.storage_to_f64(ln_w, dtype)[:, None] * wl.storage_to_f64(W_r, dtype), dtype)
     return wl.to_storage(np.ones(d), dtype), folded
+
+
+def fold_gate_allowance(x, ln_w, W_r, eps, dtype, ref_g):
+    """Absolute allowance [T, N] on the gates of a fused-norm call against the layer with the UNFOLDED norm
+    weight: every element of the folded weight carries an independent rounding error of at most one unit
+    roundoff u of the storage type (standard deviation at most u |w| / sqrt 3), so logit j of a token
+    moves by a sum of d independent terms; six standard deviations of it, and |dg_j| <= 2 g_j max_j |dz_j|
+    to first order."""
+    import numpy as np
+    from paper_2503_15798_amd import workloads as wl
+    u = 2.0 ** -9 if dtype == wl.BF16 else 2.0 ** -24
+    x64 = wl.storage_to_f64(x, dtype)
+    xn = x64 / np.sqrt((x64 ** 2).mean(axis=1, keepdims=True) + eps)
+    wf = wl.storage_to_f64(ln_w, dtype)[:, None] * wl.storage_to_f64(W_r, dtype)
+    dz = 6.0 * u / np.sqrt(3.0) * np.sqrt((xn ** 2) @ (wf ** 2))
+    return 2.0 * dz.max(axis=1, keepdims=True) * ref_g

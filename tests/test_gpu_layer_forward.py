@@ -6,7 +6,7 @@ import pytest
 import oracle
 from paper_2503_15798_amd import binding as mb
 from paper_2503_15798_amd import workloads as wl
-from helpers import DT, assert_close, folded_router, to_dev, to_host
+from helpers import DT, assert_close, fold_gate_allowance, folded_router, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 EPS = 1e-5
@@ -50,8 +50,8 @@ def check(w, table, ids, inp, shared=True, dedup=False, eps=EPS):
     against the same oracle given what the call is defined on: the norm weight folded into the router
     weight and rounded to the storage type (the product of two stored values, rounded once: the same bits
     on the host as on the device), unit norm weight.  The two differ by the rounding of the folded weight,
-    which moves a gate by up to about 1 % when the logits are large; where state, shared and routed terms
-    cancel, that shift of the routed term alone can exceed atol."""
+    which moves a gate by a few per cent when d and the logits are large (allowance: fold_gate_allowance);
+    where state, shared and routed terms cancel, that shift of the routed term alone can exceed atol."""
     sh = inp["shared"] if shared else None
     _, ref_g, _, ref_rows, ref_err = oracle.layer_forward(table, ids, inp["x"], inp["ln_w"], eps, inp["W_r"], sh)
     ones, folded = folded_router(inp["ln_w"], inp["W_r"], w.dtype, w.d)
@@ -59,7 +59,8 @@ def check(w, table, ids, inp, shared=True, dedup=False, eps=EPS):
     got = run(w, table, ids, inp, shared=shared, dedup=dedup, eps=eps)
     np.testing.assert_array_equal(got["rows"], ref_rows)
     assert got["err"] == ref_err
-    assert_close(got["gates"].astype(np.float64), ref_g, w.dtype, f"gates ({w.name})")
+    assert_close(got["gates"].astype(np.float64), ref_g, w.dtype, f"gates ({w.name})",
+                 extra_atol=fold_gate_allowance(inp["x"], inp["ln_w"], inp["W_r"], eps, w.dtype, ref_g))
     assert_close(got["gates"].astype(np.float64), ref_gf, w.dtype, f"gates, folded weight ({w.name})")
     assert_close(wl.storage_to_f64(got["out"], w.dtype), ref_out, w.dtype, f"out ({w.name})")
 

@@ -8,7 +8,7 @@ import oracle
 from oracle import nf_codec as nf
 from paper_2503_15798_amd import binding as mb
 from paper_2503_15798_amd import workloads as wl
-from helpers import assert_close, folded_router, to_dev, to_host
+from helpers import assert_close, fold_gate_allowance, folded_router, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -341,7 +341,8 @@ def test_layer_forward_on_quantised_table(bits, block, sb, d, N, T, V, dedup):
     ref, *_ = oracle.layer_forward(deq, ids, ni["x"], ones, 1e-5, folded, li["shared"])
     assert int(err.item()) == ref_err
     np.testing.assert_array_equal(rows_d.cpu().numpy(), ref_rows)
-    assert_close(gates_d.cpu().numpy().astype(np.float64), ref_g, wl.BF16, "gates")
+    assert_close(gates_d.cpu().numpy().astype(np.float64), ref_g, wl.BF16, "gates",
+                 extra_atol=fold_gate_allowance(ni["x"], ni["ln_w"], W_r, 1e-5, wl.BF16, ref_g))
     assert_close(wl.storage_to_f64(to_host(out_d, wl.BF16), wl.BF16), ref, wl.BF16, f"layer forward nf ({w.name})")
 
 
