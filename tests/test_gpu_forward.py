@@ -161,6 +161,21 @@ def test_seeded_random_shapes(monkeypatch, seed):
     check_against_oracle(w, table, ids, li, residual=residual, dedup=dedup)
 
 
+@pytest.mark.parametrize("d,N,T,V,dedup,residual", [
+    (1032, 32, 16384, 900, False, True),     # N = 32: rows in two parts of 16, doubled grid, ragged third chunk
+    (520, 32, 20000, 2500, False, False),
+    (1024, 64, 9001, 400, False, True),      # N = 64: four parts
+    (1544, 32, 16384, 1200, True, False),    # with a plan: the run kernel
+    (768, 16, 20000, 700, False, True),
+])
+def test_large_batches_with_many_experts(d, N, T, V, dedup, residual):
+    """Whole outputs of large single-layer batches against the oracle (the full-size tests sample theirs)."""
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, T=T, L=1, name=f"large d{d} N{N} T{T}")
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    li["W_r"] = wl.to_storage(wl.storage_to_f64(li["W_r"], w.dtype) * 5.0, w.dtype)
+    check_against_oracle(w, table, ids, li, residual=residual, dedup=dedup)
+
+
 # ---- special cases with exact answers ----------------------------------------------------------------
 @pytest.mark.parametrize("N", [16, 5])
 def test_saturated_router_returns_the_row_exactly(N):
