@@ -138,6 +138,22 @@ def test_seeded_random_shapes(seed):
     assert_close(wl.storage_to_f64(out[0], wl.BF16), ref, wl.BF16, f"nf forward ({w.name})")
 
 
+@pytest.mark.parametrize("bits,block,sb,d,N,T,V,dedup", [
+    (4, 1024, 4, 1024, 32, 16384, 800, False),   # N = 32: two parts of 16 experts, eight waves, doubled grid
+    (3, 128, 2, 1536, 32, 9001, 500, True),
+    (4, 128, 2, 512, 64, 16384, 300, False),     # four parts
+])
+def test_large_batches_with_many_experts(bits, block, sb, d, N, T, V, dedup):
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, T=T, L=1, name=f"nf{bits} large d{d} N{N} T{T}")
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    out, gates, rows, err = run_nf_forward(w, table, li, ids, bits, block, sb, dedup=dedup, residual=True)
+    ref, ref_g, ref_rows, ref_err = oracle_nf_forward(table, li, ids, bits, block, residual=True)
+    assert err == 0 == ref_err
+    np.testing.assert_array_equal(rows, ref_rows)
+    assert_close(gates[0].astype(np.float64), ref_g, wl.BF16, "gates")
+    assert_close(wl.storage_to_f64(out[0], wl.BF16), ref, wl.BF16, f"nf forward ({w.name})")
+
+
 def test_layers_and_bad_ids():
     w = wl.scaled(wl.CONFIGS["decode410m"], V=400, d=1024, N=16, T=64, L=3)
     tabs = [wl.random_table(w, l) for l in range(w.L)]
