@@ -43,6 +43,8 @@ def parse_args():
     ap.add_argument("--plan", action="store_true",
                     help="the timed step is the forward given a plan of mole_dedup_ids (plans computed "
                          "beforehand, one per id batch); for profiling that path")
+    ap.add_argument("--runs", action="store_true",
+                    help="with --plan: also pass MOLE_FLAG_RUNS (tokens with equal ids summed together on the matrix pipe)")
     ap.add_argument("--no-extras", action="store_true", help="only the headline workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--only-build", action="store_true",
@@ -104,12 +106,12 @@ class Layers:
                                    self.plans[b], stream=stream)
         stream.synchronize()
 
-    def forward_planned(self, i, stream):
+    def forward_planned(self, i, stream, runs=False):
         w, mb = self.w, self.mb
         mb.mole_lookup_forward_layers(
             self.tabs, w.V * w.N * w.d, self.ids[i % N_ID_BATCHES], None, self.h, self.W_r, self.shared, None,
             self.out, w.T * w.d, None, None, self.err, w.L, w.T, w.V, w.d, w.N, self.code,
-            mb.MOLE_FLAG_DEDUP, self.plans[i % N_ID_BATCHES], stream=stream)
+            mb.MOLE_FLAG_DEDUP | (mb.MOLE_FLAG_RUNS if runs else 0), self.plans[i % N_ID_BATCHES], stream=stream)
 
     def forward_one_layer(self, i, l, stream):
         """The single-layer entry point on layer l (what a real decoder calls, once per layer)."""
@@ -325,7 +327,7 @@ def main():
 
     def step(i):
         if args.plan:
-            L.forward_planned(i, stream)
+            L.forward_planned(i, stream, runs=args.runs)
         else:
             L.forward(i, stream)
     ms_step = time_steps(torch, stream, step, args.steps, args.warmup)
@@ -339,8 +341,8 @@ def main():
     head = rates(w, acc, ms_step, distinct)
     alg_bytes = acc.forward_bytes_per_token(w.d, w.N, w.elem_bytes) * w.T * w.L
     achieved = alg_bytes / (ms_kernel * 1e-3) / 1e9
-    # the kernel the launcher picks for this call (large planned batches at N = 32 take the run kernel)
-    kernel = "fwd_bf16_run_kernel" if args.plan and w.N == 32 and w.T >= 8192 else "fwd_bf16_stream_kernel"
+    # the kernel the launcher picks for this call (--runs passes MOLE_FLAG_RUNS: the run kernel for N <= 32)
+    kernel = "fwd_bf16_run_kernel" if args.plan and args.runs and w.N <= 32 else "fwd_bf16_stream_kernel"
     kernel_tag = f"{kernel[:-7]}_{w.name}" + ("_plan" if args.plan else "")
     roofline = {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(kernel_tag),
@@ -507,6 +509,9 @@ def extras(args, torch, mb, wl, acc, stream, L):
         out[name + "_dedup_kernel_ms"] = ms
         ms = time_steps(torch, stream, planned(LL), steps, warm)
         out[name + "_forward_with_plan"] = rates(ww, acc, ms, LL.distinct())
+        if name.startswith("prefill"):      # MOLE_FLAG_RUNS: equal ids summed together on the matrix pipe
+            ms = time_steps(torch, stream, lambda i: LL.forward_planned(i, stream, runs=True), steps, warm)
+            out[name + "_forward_with_plan_runs"] = rates(ww, acc, ms, LL.distinct())
         if name == "prefill410m_uniform":
             out[name + "_nf4"] = nf_entry(LL, acc, torch, stream, steps, warm, 4, 1024, 4)
             out.update(norm_entries(LL, acc, torch, stream, steps, warm, name))

@@ -61,9 +61,13 @@ typedef enum {
 } mole_layout;
 
 enum {
-    MOLE_FLAG_DEDUP = 1u    /* forward: `workspace` holds a plan written by mole_dedup_ids for
+    MOLE_FLAG_DEDUP = 1u,   /* forward: `workspace` holds a plan written by mole_dedup_ids for
                                these ids; tokens are visited in id order so that a distinct id's
                                rows cross the memory fabric once                               */
+    MOLE_FLAG_RUNS = 2u     /* with MOLE_FLAG_DEDUP, bf16, N <= 32: the caller expects long runs of
+                               equal ids (about eight tokens per distinct id or more); tokens with
+                               equal ids then share one fetch of their rows and are summed together
+                               on the matrix pipe.  Ignored for other dtypes and N            */
 };
 
 /* Message of the last failing call on this thread ("" if none).  Never NULL. */
@@ -127,10 +131,11 @@ mole_status mole_dedup_ids(const int32_t *ids, int T, int64_t V,
  *   if it was outside [0, rows).  err_flag [1] dev nullable.
  *   flags: MOLE_FLAG_DEDUP -> workspace = plan of mole_dedup_ids(ids, T, ...) (and, if slot is
  *   given, slot must be that call's inv).  Without the flag workspace may be NULL.  The flag does not
- *   change what is computed.  The result is also bit-identical to the call without it, except for
- *   bf16 calls with N = 32 and T >= 8192: those take the weighted sum of tokens with equal ids
- *   together on the matrix pipe (gates enter as a pair of bf16 values, 16 significant bits), which
- *   changes the summation order.
+ *   change what is computed, and the result is bit-identical to the call without it.
+ *   MOLE_FLAG_RUNS (only together with MOLE_FLAG_DEDUP) is a hint for batches with many tokens per
+ *   distinct id; the weighted sum of tokens with equal ids is then taken together on the matrix
+ *   pipe (gates enter as a pair of bf16 values, 16 significant bits), which changes the summation
+ *   order: same tolerance, not the same bits.
  * ---------------------------------------------------------------------------------------- */
 mole_status mole_lookup_forward(const void *table, const int32_t *ids, const int32_t *slot,
                                 const void *h, const void *W_r,

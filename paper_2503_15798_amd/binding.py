@@ -19,6 +19,7 @@ MOLE_OK, MOLE_EINVAL, MOLE_EUNSUPPORTED, MOLE_EWORKSPACE, MOLE_EHIP, MOLE_EIO = 
 MOLE_F32, MOLE_BF16, MOLE_U8 = 0, 1, 2
 MOLE_GELU_ERF, MOLE_GELU_TANH = 0, 1
 MOLE_FLAG_DEDUP = 1
+MOLE_FLAG_RUNS = 2
 MOLE_LAYOUT_LAYER_MAJOR, MOLE_LAYOUT_ID_MAJOR = 0, 1
 
 _STATUS_NAMES = {0: "MOLE_OK", 1: "MOLE_EINVAL", 2: "MOLE_EUNSUPPORTED", 3: "MOLE_EWORKSPACE", 4: "MOLE_EHIP",

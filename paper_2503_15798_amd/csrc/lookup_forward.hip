@@ -873,21 +873,22 @@ mole_status launch_run(const FwdArgs &a, hipStream_t stream)
 }
 
 template <int N>
-mole_status launch_fast_n(const FwdArgs &a, hipStream_t stream)
+mole_status launch_fast_n(const FwdArgs &a, hipStream_t stream, bool long_runs)
 {
     // wider workgroups when the router weight is large, so that LDS does not cap occupancy
     const size_t wbytes = (size_t)a.d * N * 2;
     int wpb = wbytes > 40 * 1024 ? 8 : 4;
     wpb = env_int("MOLE_FWD_WPB", wpb);
-    // Large planned batches at N = 32 (where the streaming kernel is bound by its vector instructions,
-    // not by memory): groups of equal ids share one fetch of their rows and the weighted sum runs on
-    // the matrix pipe.  Measured against the streaming kernel in plan order: faster from T = 8192 on at
-    // N = 32 (65 / 106 us against 70 / 125 us at T = 8192 / 16384, Zipf ids), slower at N <= 16 and on
-    // many-layer launches with few tokens per layer; MOLE_FWD_RUN = 1 / 2 forces / forbids it for any
-    // N <= 32 (N = 64: rows and gates of one chunk would not fit the register file).
+    // MOLE_FLAG_RUNS (the caller expects long runs of equal ids in the plan): groups of equal ids share one
+    // fetch of their rows and the weighted sum runs on the matrix pipe.  Against the streaming kernel in plan
+    // order it wins from about eight tokens per distinct id on (N = 32, T = 16384: 54 against 73 us at 256
+    // tokens per id, 73 against 77 us at 8) and loses below (130 against 122 us at 2; Zipf(1.1) ids over a
+    // 50 k vocabulary: 105 against 100 us), which is why it is the caller's choice and not the default.
+    // MOLE_FWD_RUN = 1 / 2 forces / forbids it (N = 64: rows and gates of one chunk would not fit the
+    // register file).
     if constexpr (N <= 32) {
         constexpr size_t gate_lds = (size_t)4 * 2 * RUN_GROUP * 32 * sizeof(float);
-        if (a.plan && env_int("MOLE_FWD_RUN", N == 32 && a.T >= 8192 ? 1 : 2) == 1 &&
+        if (a.plan && env_int("MOLE_FWD_RUN", long_runs ? 1 : 2) == 1 &&
             router_lds_bytes(a.d, N < 4 ? 4 : N) + gate_lds <= LDS_BYTES_PER_CU) {
             if (a.norm)
                 return launch_run<N, 4, true, true>(a, stream);
@@ -924,8 +925,11 @@ mole_status forward_impl(const void *table, int64_t table_stride, const int32_t 
     const int dmul = dtype == MOLE_BF16 ? 8 : 4;
     if (d % dmul)
         return fail(MOLE_EUNSUPPORTED, "mole_lookup_forward: d=%d must be a multiple of %d", d, dmul);
-    if (flags & ~unsigned(MOLE_FLAG_DEDUP))
+    if (flags & ~unsigned(MOLE_FLAG_DEDUP | MOLE_FLAG_RUNS))
         return fail(MOLE_EINVAL, "mole_lookup_forward: unknown flags 0x%x", flags);
+    if ((flags & MOLE_FLAG_RUNS) && !(flags & MOLE_FLAG_DEDUP))
+        return fail(MOLE_EINVAL, "mole_lookup_forward: MOLE_FLAG_RUNS needs MOLE_FLAG_DEDUP and its plan");
+    const bool long_runs = (flags & MOLE_FLAG_RUNS) != 0;
     if (T == 0)
         return MOLE_OK;
     if (!table || !ids || !h || !W_r || !out)
@@ -966,12 +970,12 @@ mole_status forward_impl(const void *table, int64_t table_stride, const int32_t 
     const bool fast = dtype == MOLE_BF16 && lds_fast <= LDS_BYTES_PER_CU && !getenv("MOLE_FWD_GENERIC");
     if (fast) {
         switch (N) {
-        case 2: return launch_fast_n<2>(a, stream);
-        case 4: return launch_fast_n<4>(a, stream);
-        case 8: return launch_fast_n<8>(a, stream);
-        case 16: return launch_fast_n<16>(a, stream);
-        case 32: return launch_fast_n<32>(a, stream);
-        case 64: return launch_fast_n<64>(a, stream);
+        case 2: return launch_fast_n<2>(a, stream, long_runs);
+        case 4: return launch_fast_n<4>(a, stream, long_runs);
+        case 8: return launch_fast_n<8>(a, stream, long_runs);
+        case 16: return launch_fast_n<16>(a, stream, long_runs);
+        case 32: return launch_fast_n<32>(a, stream, long_runs);
+        case 64: return launch_fast_n<64>(a, stream, long_runs);
         default: break;
         }
     }

@@ -60,6 +60,7 @@ def fwd(**kw):
     (dict(flags=8), mb.MOLE_EINVAL, "unknown flags"),
     (dict(h=A16 + 4), mb.MOLE_EINVAL, "16-byte aligned"),
     (dict(flags=mb.MOLE_FLAG_DEDUP), mb.MOLE_EWORKSPACE, "plan"),
+    (dict(flags=mb.MOLE_FLAG_RUNS), mb.MOLE_EINVAL, "MOLE_FLAG_RUNS needs MOLE_FLAG_DEDUP"),
     (dict(flags=mb.MOLE_FLAG_DEDUP, workspace=A16, workspace_bytes=64), mb.MOLE_EWORKSPACE, "plan"),
 ])
 def test_forward_rejects_bad_arguments_without_launching(kw, status, needle):

@@ -17,7 +17,7 @@ def torch_mod():
 
 
 def run_forward(w, table, ids, li, shared=True, residual=False, slot=None, rows=None, dedup=False,
-                want_dbg=True, table_dev=None):
+                want_dbg=True, table_dev=None, runs=False):
     """One call of mole_lookup_forward on numpy inputs; returns numpy outputs."""
     torch = torch_mod()
     dev = "cuda"
@@ -40,7 +40,7 @@ def run_forward(w, table, ids, li, shared=True, residual=False, slot=None, rows=
         iv = torch.empty((max(T, 1),), dtype=torch.int32, device=dev)
         nu = torch.zeros((1,), dtype=torch.int32, device=dev)
         mb.mole_dedup_ids(ids_d, T, w.V, uq, iv, nu, err_d, plan)
-        flags = mb.MOLE_FLAG_DEDUP
+        flags = mb.MOLE_FLAG_DEDUP | (mb.MOLE_FLAG_RUNS if runs else 0)
     mb.mole_lookup_forward(tab_d, ids_d, slot_d, h_d, wr_d, sh_d, rs_d, out_d, gates_d, rows_d, err_d,
                            T, n_rows, w.d, w.N, DT[w.dtype], flags, plan)
     torch.cuda.synchronize()
@@ -51,10 +51,10 @@ def run_forward(w, table, ids, li, shared=True, residual=False, slot=None, rows=
     return res
 
 
-def check_against_oracle(w, table, ids, li, shared=True, residual=False, dedup=False):
+def check_against_oracle(w, table, ids, li, shared=True, residual=False, dedup=False, runs=False):
     ref_out, ref_g, ref_rows, ref_err = oracle.lookup_forward(
         table, ids, li["h"], li["W_r"], li["shared"] if shared else None, li["residual"] if residual else None)
-    got = run_forward(w, table, ids, li, shared=shared, residual=residual, dedup=dedup)
+    got = run_forward(w, table, ids, li, shared=shared, residual=residual, dedup=dedup, runs=runs)
     np.testing.assert_array_equal(got["rows"], ref_rows)                     # gathered row indices: bit-exact
     assert got["err"] == ref_err
     assert_close(got["gates"].astype(np.float64), ref_g, wl.F32 if w.dtype == wl.F32 else wl.BF16, "gates")
@@ -161,19 +161,35 @@ def test_seeded_random_shapes(monkeypatch, seed):
     check_against_oracle(w, table, ids, li, residual=residual, dedup=dedup)
 
 
-@pytest.mark.parametrize("d,N,T,V,dedup,residual", [
-    (1032, 32, 16384, 900, False, True),     # N = 32: rows in two parts of 16, doubled grid, ragged third chunk
-    (520, 32, 20000, 2500, False, False),
-    (1024, 64, 9001, 400, False, True),      # N = 64: four parts
-    (1544, 32, 16384, 1200, True, False),    # with a plan: the run kernel
-    (768, 16, 20000, 700, False, True),
+@pytest.mark.parametrize("d,N,T,V,dedup,runs,residual", [
+    (1032, 32, 16384, 900, False, False, True),   # N = 32: rows in two parts of 16, doubled grid, ragged third chunk
+    (520, 32, 20000, 2500, False, False, False),
+    (1024, 64, 9001, 400, False, False, True),    # N = 64: four parts
+    (1544, 32, 16384, 1200, True, False, False),  # with a plan: the streaming kernel in id order
+    (1544, 32, 16384, 1200, True, True, False),   # MOLE_FLAG_RUNS: the run kernel
+    (1024, 16, 9001, 300, True, True, True),
+    (768, 16, 20000, 700, False, False, True),
 ])
-def test_large_batches_with_many_experts(d, N, T, V, dedup, residual):
+def test_large_batches_with_many_experts(d, N, T, V, dedup, runs, residual):
     """Whole outputs of large single-layer batches against the oracle (the full-size tests sample theirs)."""
     w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, T=T, L=1, name=f"large d{d} N{N} T{T}")
     table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
     li["W_r"] = wl.to_storage(wl.storage_to_f64(li["W_r"], w.dtype) * 5.0, w.dtype)
-    check_against_oracle(w, table, ids, li, residual=residual, dedup=dedup)
+    check_against_oracle(w, table, ids, li, residual=residual, dedup=dedup, runs=runs)
+
+
+def test_plan_does_not_change_a_bit_and_the_run_hint_stays_in_tolerance():
+    """MOLE_FLAG_DEDUP alone: the same bits as the plain call.  MOLE_FLAG_RUNS: another summation order."""
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=500, d=1024, N=32, T=9000, L=1, name="flags N32")
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    plain = run_forward(w, table, ids, li, residual=True)
+    planned = run_forward(w, table, ids, li, residual=True, dedup=True)
+    hinted = run_forward(w, table, ids, li, residual=True, dedup=True, runs=True)
+    np.testing.assert_array_equal(plain["out"], planned["out"])
+    np.testing.assert_array_equal(plain["gates"], planned["gates"])
+    assert_close(wl.storage_to_f64(hinted["out"], w.dtype), wl.storage_to_f64(plain["out"], w.dtype), w.dtype,
+                 "run hint against the plain call")
+    assert not np.array_equal(hinted["out"], plain["out"])      # it did take the other kernel
 
 
 # ---- special cases with exact answers ----------------------------------------------------------------
@@ -261,7 +277,7 @@ def test_heavy_repeats_with_plan():
     check_against_oracle(w, table, ids, li, dedup=True)
 
 
-# ---- the run kernel (plan + large batch by default; forced here on small shapes) -----------------------
+# ---- the run kernel (MOLE_FLAG_RUNS; forced here through the environment on small shapes) ---------------
 @pytest.mark.parametrize("d,N,T,V,dist", [
     (1024, 32, 203, 64, "zipf"),       # long runs of equal ids, two chunks
     (1024, 16, 333, 4096, "zipf"),     # mostly distinct ids
