@@ -280,7 +280,8 @@ mole_status mole_lut_file_close(mole_lut_file *file);
  *
  * mole_quantize_lut: table bf16 [rows,N,d] dev -> codes, scales dev (sizes from the two helpers).
  * mole_lookup_forward_nf: the fused forward of mole_lookup_forward_layers with the rows
- * dequantised on the fly; activations bf16; codes_stride in BYTES per layer, scales_stride and
+ * dequantised on the fly; activations bf16; flags: MOLE_FLAG_DEDUP or 0 (MOLE_FLAG_RUNS is not
+ * accepted here); codes_stride in BYTES per layer, scales_stride and
  * act_stride in ELEMENTS per layer (ignored for L == 1).  N in {2, 4, 8, 16, 32, 64}; the router
  * weight, d * max(N, 4) * 2 bytes, has to fit in LDS next to the level table (about 158 KiB),
  * else MOLE_EUNSUPPORTED.
