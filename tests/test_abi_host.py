@@ -234,3 +234,18 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert not pat.search(text), f"{f} reaches for the oracle"
+
+
+def test_bench_refuses_more_than_one_gpu_and_runs_nothing_without_one():
+    """bench.py measures one GPU: --gpus N > 1 exits with a message that says so; without a GPU it exits
+    before touching the library (no CPU fallback)."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+    import torch
+    if not torch.cuda.is_available():
+        r = subprocess.run([sys.executable, os.path.join(root, "bench.py")], capture_output=True, text=True)
+        assert r.returncode == 3 and "no GPU" in r.stderr and r.stdout.strip() == ""
