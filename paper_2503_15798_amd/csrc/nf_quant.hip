@@ -221,9 +221,10 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
     constexpr int NR = N < 4 ? 4 : N;   // experts the router is computed for (N = 2 is padded to 4)
     constexpr int LPJ = 64 / NR;        // lanes per expert after the fold
     constexpr int NLEV = 1 << BITS;
-    // The experts of a chunk pass through the code-word registers R at a time (N = 32: two halves, N = 64:
-    // four quarters): with all N in registers the kernel runs at two waves per SIMD or fewer.
-    constexpr int R = N > 16 ? 16 : N;
+    // The experts of a chunk pass through the code-word registers R at a time (NF4: 16, NF3, which holds two
+    // words per expert: 8): with all N in registers the kernel runs at two waves per SIMD or fewer, in parts
+    // it fits four.
+    constexpr int R = N > 16 ? (BITS == 3 ? 8 : 16) : N;
     constexpr int H = N / R;
     const int d = a.d;
     const int kgroups = d >> 3;
@@ -437,7 +438,7 @@ mole_status launch_nf(const NfArgs &a, int scale_bytes, hipStream_t stream)
     if (gx > cap) {
         int64_t ipw = (a.T + cap * WPB - 1) / (cap * WPB);
         // NF4 at N >= 32: from four tokens per wave on, twice the workgroups with half the tokens each even out
-        // the tail (T = 16384: 101 -> 92 us); NF3 (three waves per SIMD) gains nothing from it
+        // the tail (T = 16384: 101 -> 92 us); NF3 gains nothing from it
         if (N >= 32 && BITS == 4 && ipw >= 4)
             ipw = (ipw + 1) / 2;
         gx = (a.T + WPB * ipw - 1) / (WPB * ipw);
