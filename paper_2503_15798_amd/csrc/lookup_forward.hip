@@ -900,6 +900,10 @@ mole_status launch_fast_n(const FwdArgs &a, hipStream_t stream, bool long_runs)
     const bool nta = env_int("MOLE_FWD_NTA", (int64_t)a.T * a.L >= 8192 && !a.plan ? 1 : 2) == 1;
     // small launches: one chunk per item (latency regime); never together with the large-batch loads
     const bool split = env_int("MOLE_FWD_SPLIT", (int64_t)a.T * a.L <= 2048 ? 1 : 2) == 1 && a.d > 512;
+    // chunk items of many layers in one launch: eight waves share a staged router weight instead of four
+    // (24 layers x 32 tokens: 11.7 -> 11.2 us; a single layer is faster with the smaller workgroups)
+    if (split && a.L >= 8 && (int64_t)a.T * ((a.d + 511) / 512) >= 64 && !getenv("MOLE_FWD_WPB"))
+        wpb = 8;
     if (split)
         return wpb >= 8 ? launch_fast<N, 8, false, true>(a, stream) : launch_fast<N, 4, false, true>(a, stream);
     if (wpb >= 8)
