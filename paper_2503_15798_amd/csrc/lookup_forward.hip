@@ -806,10 +806,11 @@ int env_int(const char *name, int dflt)
 
 // Grid shape.  Every wave should get the same number of items, and all workgroups should be
 // resident at once (a second round would stage the router weight again and leave CUs idle at the
-// tail).  Residency per CU is bounded by LDS and by registers (4 waves per SIMD for N <= 16,
-// 2 above).  Returns the number of workgroups per layer.
+// tail).  Residency per CU is bounded by LDS and by registers: the kernels fit 6 to 8 waves per SIMD for
+// N <= 4 (asked for: 8; 24 layers x 256 tokens then run one token per wave, 17.5 -> 15.4 us at N = 4,
+// 14.5 -> 12.7 us at N = 2), 4 for N <= 32, 2 above.  Returns the number of workgroups per layer.
 template <int N, int WPB>
-int64_t grid_x(int items, int L, size_t lds, int waves_per_cu = N <= 32 ? 16 : 8, bool halve_items = false)
+int64_t grid_x(int items, int L, size_t lds, int waves_per_cu = N <= 4 ? 32 : (N <= 32 ? 16 : 8), bool halve_items = false)
 {
     int per_cu = (int)(LDS_BYTES_PER_CU / lds);
     const int wave_cap = waves_per_cu / WPB;
@@ -844,7 +845,7 @@ mole_status launch_fast(const FwdArgs &a, hipStream_t stream)
     MOLE_HIP_CHECK(ensure_dynamic_lds(
         lds_seen, reinterpret_cast<const void *>(&fwd_bf16_stream_kernel<N, WPB, NTA, SPLIT, NORM>), lds));
     const int items = SPLIT ? a.T * ((a.d + 511) / 512) : a.T;
-    dim3 grid((unsigned)grid_x<N, WPB>(items, a.L, lds, N <= 32 ? 16 : 8, N >= 32), (unsigned)a.L);
+    dim3 grid((unsigned)grid_x<N, WPB>(items, a.L, lds, N <= 4 ? 32 : (N <= 32 ? 16 : 8), N >= 32), (unsigned)a.L);
     hipLaunchKernelGGL((fwd_bf16_stream_kernel<N, WPB, NTA, SPLIT, NORM>), grid, dim3(WPB * 64), lds, stream, a);
     MOLE_HIP_CHECK(hipGetLastError());
     return MOLE_OK;
