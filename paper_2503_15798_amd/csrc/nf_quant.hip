@@ -427,8 +427,9 @@ mole_status launch_nf(const NfArgs &a, int scale_bytes, hipStream_t stream)
     static std::atomic<size_t> lds_seen{0};
     MOLE_HIP_CHECK(ensure_dynamic_lds(lds_seen, reinterpret_cast<const void *>(&fwd_nf_kernel<N, BITS, WPB, NORM>), lds));
     int per_cu = (int)((160 * 1024) / (lds + PAIR_TABLE_LDS));
-    if (per_cu > 4)
-        per_cu = 4;
+    constexpr int WG_CAP = N <= 4 ? 8 : 4;       // waves per SIMD the registers allow (four-wave workgroups)
+    if (per_cu > WG_CAP)
+        per_cu = WG_CAP;
     if (per_cu < 1)
         per_cu = 1;
     int64_t cap = (int64_t)num_cus() * per_cu / a.L;
