@@ -394,7 +394,8 @@ def extras(args, torch, mb, wl, acc, stream, L):
     """The other workloads and variants.  Each entry: ms, tokens/s, GB/s."""
     import numpy as np
     out = {}
-    steps, warm = max(20, args.steps // 4), max(5, args.warmup // 2)
+    # warm-up covers every id batch once, so that no batch's rows are touched for the first time in a timed step
+    steps, warm = max(20, args.steps // 4), max(N_ID_BATCHES, args.warmup // 2)
     w = L.w
 
     def both(LL):
