@@ -237,8 +237,8 @@ void fwd_bf16_stream_kernel(FwdArgs a)
 }
 
 // ------------------------------------------------------------------------------------------
-// Run kernel (needs the plan of mole_dedup_ids): the plan lists the tokens in id order, so tokens with
-// equal ids sit next to each other.  A wave takes 4 consecutive positions of that order (a span) and
+// Run kernel (MOLE_FLAG_RUNS; needs the plan of mole_dedup_ids): the plan lists the tokens in id order, so
+// tokens with equal ids sit next to each other.  A wave takes 4 consecutive positions of that order (a span) and
 // cuts them into groups with the same row block; an item is one 512-column chunk of one group:
 //   * the N row pieces of the chunk are fetched once for the whole group, and the gate-weighted sums
 //     of its (up to) 4 tokens are taken together on the matrix pipe: v_mfma_f32_4x4x4_16b_bf16
