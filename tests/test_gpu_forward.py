@@ -192,6 +192,17 @@ def test_plan_does_not_change_a_bit_and_the_run_hint_stays_in_tolerance():
     assert not np.array_equal(hinted["out"], plain["out"])      # it did take the other kernel
 
 
+@pytest.mark.parametrize("cfg,d,N", [("decode410m", 512, 64), ("tiny", 64, 4), ("decode410m", 256, 5)])
+def test_run_hint_is_ignored_where_it_does_not_apply(cfg, d, N):
+    """MOLE_FLAG_RUNS is defined for bf16 and N <= 32 (powers of two): elsewhere the call is the planned one."""
+    w = wl.scaled(wl.CONFIGS[cfg], V=300, d=d, N=N, T=500, L=1, name=f"hint ignored {cfg} N{N}")
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    planned = run_forward(w, table, ids, li, dedup=True)
+    hinted = run_forward(w, table, ids, li, dedup=True, runs=True)
+    np.testing.assert_array_equal(planned["out"], hinted["out"])
+    check_against_oracle(w, table, ids, li, dedup=True, runs=True)
+
+
 # ---- special cases with exact answers ----------------------------------------------------------------
 @pytest.mark.parametrize("N", [16, 5])
 def test_saturated_router_returns_the_row_exactly(N):
