@@ -845,7 +845,7 @@ def build_bench(torch, mb, wl, acc, stream, with_cpu=False):
     if with_cpu:
         # the fp64 oracle on a sample of vocabulary rows, extrapolated linearly to the whole table
         import oracle
-        n = 64
+        n = 512
         rows = torch.arange(0, w.V, w.V // n, device="cuda")[:n]
         host = lambda t: t.contiguous().view(torch.int16).cpu().numpy().view("uint16")
         Eh, W1h, W2h = host(E[rows]), host(W1), host(W2)
