@@ -246,7 +246,7 @@ def read_traffic(kernel_tag):
         return None
 
 
-def cpu_baseline(L, torch, wl, steps=3):
+def cpu_baseline(L, torch, wl, steps=21):
     """The fp64 oracle on the host cores, same workload: all layers x all tokens of id batch 0.
     Only the looked-up rows are brought to the host (plain indexing; the copy is not timed)."""
     import numpy as np
