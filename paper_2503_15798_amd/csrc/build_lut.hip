@@ -121,14 +121,17 @@ __device__ __forceinline__ float gelu_fast(float x, int act)
         const float th = 1.0f - 2.0f * __builtin_amdgcn_rcpf(__expf(2.0f * u) + 1.0f);
         return 0.5f * x * (1.0f + th);
     }
-    const float z = fabsf(x) * 0.7071067811865476f;
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
-    float p = fmaf(1.061405429f, t, -1.453152027f);
-    p = fmaf(p, t, 1.421413741f);
-    p = fmaf(p, t, -0.284496736f);
-    p = fmaf(p, t, 0.254829592f);
-    const float y = 1.0f - p * t * __expf(-z * z);      // erf(|x| / sqrt 2)
-    return 0.5f * x * (1.0f + copysignf(y, x));
+    // x Phi(x) with Phi(-|x|) = erfc(|x| / sqrt 2) / 2 =: c: the result is max(x, 0) - |x| c for either sign.
+    // c = q(t) e with t = 1 / (1 + p |x| / sqrt 2), q the five-term polynomial (coefficients halved),
+    // e = exp(-x^2 / 2) = 2^(-x^2 log2(e) / 2); the constants of z = |x| / sqrt 2 are folded in.
+    const float ax = fabsf(x);
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.7071067811865476f, ax, 1.0f));
+    float q = fmaf(0.5f * 1.061405429f, t, 0.5f * -1.453152027f);
+    q = fmaf(q, t, 0.5f * 1.421413741f);
+    q = fmaf(q, t, 0.5f * -0.284496736f);
+    q = fmaf(q, t, 0.5f * 0.254829592f);
+    const float e = __builtin_amdgcn_exp2f(x * x * -0.7213475204444817f);
+    return fmaxf(x, 0.0f) - ax * (q * t * e);
 }
 
 // round-to-nearest-even without the NaN branch (inputs are finite here), two values into one dword
