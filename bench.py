@@ -151,7 +151,7 @@ class Layers:
         """mole_layer_forward: post-attention state in; norm and residual inside the kernel."""
         w, mb = self.w, self.mb
         mb.mole_layer_forward(
-            self.tabs, w.V * w.N * w.d, self.ids[i % N_ID_BATCHES], None, self.x, 1e-5, self.W_rn,
+            self.tabs, w.V * w.N * w.d, self.ids[i % N_ID_BATCHES], None, self.x, self.ln_w, 1e-5, self.W_r,
             self.shared, self.out, w.T * w.d, None, None, self.err, w.L, w.T, w.V, w.d, w.N, self.code, 0, None,
             stream=stream)
 
@@ -160,9 +160,7 @@ class Layers:
         g = torch.Generator(device="cuda")
         g.manual_seed(2000 + w.seed)
         self.x = (torch.randn((w.L, w.T, w.d), generator=g, device="cuda") * 2.0).to(self.h.dtype)
-        ln_w = (torch.rand((w.L, w.d), generator=g, device="cuda") + 0.5).to(self.h.dtype)
-        self.W_rn = torch.empty_like(self.W_r)
-        self.mb.mole_fold_router_norm(self.W_r, ln_w, self.W_rn, w.L, w.d, w.N, self.code)
+        self.ln_w = (torch.rand((w.L, w.d), generator=g, device="cuda") + 0.5).to(self.h.dtype)
         torch.cuda.synchronize()
 
     def distinct(self):
@@ -534,7 +532,7 @@ def norm_entries(LL, acc, torch, stream, steps, warm, name):
                                 "activation_streams": streams, "algorithmic_bytes_per_launch": alg,
                                 "algorithmic_GBps": alg / (ms * 1e-3) / 1e9,
                                 "algorithmic_frac_of_hbm_peak": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
-    del LL.x, LL.W_rn
+    del LL.x, LL.ln_w
     return res
 
 

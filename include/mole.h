@@ -23,11 +23,18 @@
  *   - Tensor pointers must be 16-byte aligned; d must be a multiple of 8 (bf16) / 4 (fp32);
  *     1 <= N <= 64.
  *   - Errors that the host can see (null required pointer, bad size, misalignment, workspace
- *     too small, unsupported shape) return a status WITHOUT launching anything and set the
- *     message returned by mole_last_error().  Errors only the device can see (a token id
- *     outside [0, V)) cannot be returned synchronously: the token's routed term is taken as
- *     zero and *err_flag is set to 1 (the caller zeroes err_flag beforehand and reads it after
- *     synchronising).  T == 0 is MOLE_OK and launches nothing.
+ *     too small, unsupported shape, a current device that is not a gfx950 part) return a status
+ *     WITHOUT launching anything and set the message returned by mole_last_error().
+ *   - Errors only the device can see cannot be returned synchronously; they set bits of
+ *     *err_flag (the caller zeroes err_flag beforehand and reads it after synchronising):
+ *       bit 0 (value 1): a token id (or slot) outside [0, rows): that token's routed term is
+ *                        taken as zero; the rest of its output is computed as usual;
+ *       bit 1 (value 2): MOLE_FLAG_DEDUP was given but `workspace` does not hold a plan that
+ *                        mole_dedup_ids wrote for a batch of T tokens: the plan is ignored, the
+ *                        tokens are visited in their own order and the output is the same as
+ *                        without the flag.  (A plan of another batch of the same T is not
+ *                        detected; it only changes the visiting order, never the result.)
+ *     T == 0 is MOLE_OK and launches nothing.
  */
 #ifndef MOLE_H
 #define MOLE_H
@@ -73,8 +80,21 @@ enum {
 /* Message of the last failing call on this thread ("" if none).  Never NULL. */
 const char *mole_last_error(void);
 
-/* ABI version, currently 1. */
+/* ABI version, currently 2 (2: mole_layer_forward / _nf take the norm weight itself; mole_set_tuning;
+ * a no-allocation entry point). */
 int mole_version(void);
+
+/* Tuning knobs, for experiments and tests; normal use needs none.  `name` is one of
+ * "MOLE_FWD_WPB" (waves per workgroup of the forward kernels, 4 or 8), "MOLE_FWD_WGS_PER_CU",
+ * "MOLE_FWD_NTA" (1 = non-temporal activation loads, 2 = plain), "MOLE_FWD_SPLIT" (1 = one
+ * 512-column chunk per work item, 2 = whole tokens), "MOLE_FWD_RUN" (1 / 2 = force / forbid the
+ * kernel of MOLE_FLAG_RUNS for planned calls), "MOLE_FWD_GENERIC" (1 = generic forward kernel),
+ * "MOLE_DEDUP_GENERIC" (1 = generic dedup kernel), "MOLE_BUILD_HIDDEN" (1 = fp16, 2 = bf16 hi/lo
+ * hidden activation), "MOLE_BUILD_SMALL_TILE" (1 = the 256 x 128 GEMM).  value 0 restores the
+ * library's own choice.  Each knob starts from the environment variable of the same name, read once
+ * when the first knob is looked up.  Process-wide; takes effect for calls issued afterwards.
+ * MOLE_EINVAL for an unknown name or a negative value. */
+mole_status mole_set_tuning(const char *name, int value);
 
 /* ------------------------------------------------------------------------------------------
  * Re-parameterization (Sec. 3.3, LUT entry equation):
@@ -163,25 +183,21 @@ mole_status mole_lookup_forward_layers(const void *table, int64_t table_stride,
                                        void *hip_stream);
 
 /* The MoLE part of a decoder layer from the state AFTER attention, with the post-attention RMSNorm
- * and the residual folded into the kernel (inference listing, "Shared Expert" / "Routed Expert"):
+ * and the residual inside the kernel (inference listing, "Shared Expert" / "Routed Expert"):
  *     hn[t,:]  = x[t,:] / sqrt(mean_k x[t,k]^2 + ln_eps) * ln_w
  *     g[t,:]   = softmax(hn[t,:] . W_r)
  *     out[t,:] = x[t,:] + shared_out[t,:] + sum_j g[t,j] * table[row(t), j, :]
- * Since hn . W_r = (1/rms(x)) * x . (diag(ln_w) W_r), the norm weight is folded into the router
- * weight once, when the model is loaded:
- *   mole_fold_router_norm: W_rn[l,k,j] = W_r[l,k,j] * ln_w[l,k]   (one rounding to the storage type)
- *     W_r [L,d,N] dev, ln_w [L,d] dev, W_rn [L,d,N] dev out (may alias W_r).
- *   mole_layer_forward: takes x and W_rn; a token's logits are scaled by its 1/rms, so the normed
- *     state is never materialised, and x, read once, is both the norm's input and the residual.
- *     x [T,d] dev: the state after the attention residual add; ln_eps >= 0; shared_out [T,d] dev
- *     nullable: FFN_shared(hn), computed by the caller from the same normed state.  Everything
- *     else as in mole_lookup_forward_layers (L = 1: strides ignored).
+ * The normed state is never materialised: hn . r_j = (1 / rms(x)) * sum_k (x_k ln_w_k) W_r[k,j], and the
+ * products x_k ln_w_k enter the router exactly (bf16 storage: as a pair of bf16 values; fp32 storage:
+ * one fp32 rounding), so the gates carry fp32 rounding errors only, as in mole_lookup_forward.  x, read
+ * once, is both the norm's input and the residual.
+ *   x [T,d] dev: the state after the attention residual add; ln_w [d] dev ([L,d] for L layers); ln_eps >= 0;
+ *   W_r [d,N] dev ([L,d,N]); shared_out [T,d] dev nullable: FFN_shared(hn), computed by the caller from
+ *   the same normed state.  Everything else as in mole_lookup_forward_layers (L = 1: strides ignored).
  * Saves the 2d bytes per token of reading hn next to x. */
-mole_status mole_fold_router_norm(const void *W_r, const void *ln_w, void *W_rn,
-                                  int L, int d, int N, mole_dtype dtype, void *hip_stream);
 mole_status mole_layer_forward(const void *table, int64_t table_stride,
                                const int32_t *ids, const int32_t *slot,
-                               const void *x, float ln_eps, const void *W_rn,
+                               const void *x, const void *ln_w, float ln_eps, const void *W_r,
                                const void *shared_out,
                                void *out, int64_t act_stride,
                                float *gates_dbg, int64_t *rows_dbg, int32_t *err_flag,
@@ -307,13 +323,13 @@ mole_status mole_lookup_forward_nf(const void *codes, int64_t codes_stride,
                                    int bits, int block, int scale_bytes, unsigned flags,
                                    const void *workspace, size_t workspace_bytes, void *hip_stream);
 
-/* mole_layer_forward with a quantised table: x is the state after attention, W_rn the router weight
- * with the norm weight folded in (mole_fold_router_norm); out = x + shared_out + sum_j g_j * row_j with
- * the rows dequantised on the fly.  Other arguments as in mole_lookup_forward_nf. */
+/* mole_layer_forward with a quantised table: x is the state after attention, ln_w [L,d] the weight of the
+ * RMSNorm the router reads it through; out = x + shared_out + sum_j g_j * row_j with the rows dequantised
+ * on the fly.  Other arguments as in mole_lookup_forward_nf. */
 mole_status mole_layer_forward_nf(const void *codes, int64_t codes_stride,
                                   const void *scales, int64_t scales_stride,
                                   const int32_t *ids, const int32_t *slot,
-                                  const void *x, float ln_eps, const void *W_rn,
+                                  const void *x, const void *ln_w, float ln_eps, const void *W_r,
                                   const void *shared_out, void *out, int64_t act_stride,
                                   float *gates_dbg, int64_t *rows_dbg, int32_t *err_flag,
                                   int L, int T, int64_t rows, int d, int N,

@@ -28,7 +28,7 @@ _STATUS_NAMES = {0: "MOLE_OK", 1: "MOLE_EINVAL", 2: "MOLE_EUNSUPPORTED", 3: "MOL
 # every symbol include/mole.h declares
 EXPORTS = ("mole_last_error", "mole_version", "mole_build_lut_workspace", "mole_build_lut",
            "mole_dedup_workspace", "mole_dedup_ids", "mole_lookup_forward",
-           "mole_lookup_forward_layers", "mole_fold_router_norm", "mole_layer_forward", "mole_offload_fetch", "mole_offload_fetch_idmajor",
+           "mole_lookup_forward_layers", "mole_set_tuning", "mole_layer_forward", "mole_offload_fetch", "mole_offload_fetch_idmajor",
            "mole_lut_file_create", "mole_lut_file_open", "mole_lut_file_payload", "mole_lut_file_write_layer",
            "mole_lut_file_read_rows", "mole_lut_file_close", "mole_nf_codebook", "mole_nf_codes_bytes",
            "mole_nf_scales_bytes", "mole_quantize_lut", "mole_lookup_forward_nf", "mole_offload_fetch_nf",
@@ -81,10 +81,10 @@ def lib() -> ctypes.CDLL:
     L.mole_lookup_forward_layers.restype = c_i32
     L.mole_lookup_forward_layers.argtypes = ([c_void, c_i64] + [c_void] * 7 + [c_i64] + [c_void] * 3 +
                                              [c_i32, c_i32, c_i64, c_i32, c_i32, c_i32, c_u, c_void, c_sz, c_void])
+    L.mole_set_tuning.restype = c_i32
+    L.mole_set_tuning.argtypes = [ctypes.c_char_p, c_i32]
     L.mole_layer_forward.restype = c_i32
-    L.mole_fold_router_norm.restype = c_i32
-    L.mole_fold_router_norm.argtypes = [c_void, c_void, c_void, c_i32, c_i32, c_i32, c_i32, c_void]
-    L.mole_layer_forward.argtypes = ([c_void, c_i64, c_void, c_void, c_void, c_f, c_void, c_void, c_void,
+    L.mole_layer_forward.argtypes = ([c_void, c_i64, c_void, c_void, c_void, c_void, c_f, c_void, c_void, c_void,
                                       c_i64, c_void, c_void, c_void] +
                                      [c_i32, c_i32, c_i64, c_i32, c_i32, c_i32, c_u, c_void, c_sz, c_void])
     L.mole_offload_fetch.restype = c_i32
@@ -121,8 +121,8 @@ def lib() -> ctypes.CDLL:
                                          [c_i32, c_i32, c_i64, c_i32, c_i32, c_i32, c_i32, c_i32, c_u, c_void, c_sz,
                                           c_void])
     L.mole_layer_forward_nf.restype = c_i32
-    L.mole_layer_forward_nf.argtypes = ([c_void, c_i64, c_void, c_i64, c_void, c_void, c_void, ctypes.c_float, c_void,
-                                         c_void, c_void, c_i64, c_void, c_void, c_void] +
+    L.mole_layer_forward_nf.argtypes = ([c_void, c_i64, c_void, c_i64, c_void, c_void, c_void, c_void, ctypes.c_float,
+                                         c_void, c_void, c_void, c_i64, c_void, c_void, c_void] +
                                         [c_i32, c_i32, c_i64, c_i32, c_i32, c_i32, c_i32, c_i32, c_u, c_void, c_sz,
                                          c_void])
     _lib = L
@@ -208,17 +208,17 @@ def mole_lookup_forward_layers(table, table_stride: int, ids, slot, h, W_r, shar
                                             dtype, flags, _ptr(workspace), wb, _stream(stream)))
 
 
-def mole_fold_router_norm(W_r, ln_w, W_rn, L: int, d: int, N: int, dtype: int, stream=None) -> None:
-    _check(lib().mole_fold_router_norm(_ptr(W_r), _ptr(ln_w), _ptr(W_rn), L, d, N, dtype, _stream(stream)))
+def mole_set_tuning(name: str, value: int) -> None:
+    _check(lib().mole_set_tuning(name.encode(), value))
 
 
-def mole_layer_forward(table, table_stride: int, ids, slot, x, ln_eps: float, W_rn, shared_out, out,
+def mole_layer_forward(table, table_stride: int, ids, slot, x, ln_w, ln_eps: float, W_r, shared_out, out,
                        act_stride: int, gates_dbg, rows_dbg, err_flag, L: int, T: int, rows: int, d: int, N: int,
                        dtype: int, flags: int = 0, workspace=None, stream=None,
                        workspace_bytes: Optional[int] = None) -> None:
     wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
-    _check(lib().mole_layer_forward(_ptr(table), table_stride, _ptr(ids), _ptr(slot), _ptr(x), ln_eps,
-                                    _ptr(W_rn), _ptr(shared_out), _ptr(out), act_stride, _ptr(gates_dbg),
+    _check(lib().mole_layer_forward(_ptr(table), table_stride, _ptr(ids), _ptr(slot), _ptr(x), _ptr(ln_w), ln_eps,
+                                    _ptr(W_r), _ptr(shared_out), _ptr(out), act_stride, _ptr(gates_dbg),
                                     _ptr(rows_dbg), _ptr(err_flag), L, T, rows, d, N, dtype, flags,
                                     _ptr(workspace), wb, _stream(stream)))
 
@@ -312,12 +312,12 @@ def mole_lookup_forward_nf(codes, codes_stride: int, scales, scales_stride: int,
                                         scale_bytes, flags, _ptr(workspace), wb, _stream(stream)))
 
 
-def mole_layer_forward_nf(codes, codes_stride: int, scales, scales_stride: int, ids, slot, x, ln_eps: float, W_rn,
-                          shared_out, out, act_stride: int, gates_dbg, rows_dbg, err_flag, L: int, T: int, rows: int,
+def mole_layer_forward_nf(codes, codes_stride: int, scales, scales_stride: int, ids, slot, x, ln_w, ln_eps: float,
+                          W_r, shared_out, out, act_stride: int, gates_dbg, rows_dbg, err_flag, L: int, T: int, rows: int,
                           d: int, N: int, bits: int, block: int, scale_bytes: int, flags: int = 0, workspace=None,
                           stream=None, workspace_bytes: Optional[int] = None) -> None:
     wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
     _check(lib().mole_layer_forward_nf(_ptr(codes), codes_stride, _ptr(scales), scales_stride, _ptr(ids), _ptr(slot),
-                                       _ptr(x), ln_eps, _ptr(W_rn), _ptr(shared_out), _ptr(out), act_stride,
+                                       _ptr(x), _ptr(ln_w), ln_eps, _ptr(W_r), _ptr(shared_out), _ptr(out), act_stride,
                                        _ptr(gates_dbg), _ptr(rows_dbg), _ptr(err_flag), L, T, rows, d, N, bits, block,
                                        scale_bytes, flags, _ptr(workspace), wb, _stream(stream)))

@@ -56,20 +56,5 @@ def build(extra_flags=(), lib_path: str = LIB, verbose: bool = False) -> str:
     return lib_path
 
 
-PROBE = os.path.join(HERE, "hbm_probe")
-
-
-def build_probe(verbose: bool = False) -> str:
-    """Compile the stand-alone bandwidth probe (csrc/hbm_probe.hip) next to the library."""
-    cmd = [_hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-o", PROBE, os.path.join(CSRC, "hbm_probe.hip")]
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hbm_probe build failed:\n" + res.stderr)
-    if verbose:
-        print("built", PROBE)
-    return PROBE
-
-
 if __name__ == "__main__":
     build(extra_flags=sys.argv[1:], verbose=True)
-    build_probe(verbose=True)

@@ -876,17 +876,11 @@ inline BuildWs build_ws(int64_t V, int d, int D, int N, mole_dtype dt)
     return w;
 }
 
-// MOLE_BUILD_HIDDEN=f16 | split forces the format of the hidden activation (for tests and experiments)
-inline int env_mode()
+// the knob MOLE_BUILD_HIDDEN (1 = f16, 2 = split) forces the format of the hidden activation (tests, experiments)
+inline int forced_mode()
 {
-    const char *e = getenv("MOLE_BUILD_HIDDEN");
-    if (!e)
-        return 0;
-    if (!strcmp(e, "f16"))
-        return MODE_F16;
-    if (!strcmp(e, "split"))
-        return MODE_SPLIT;
-    return 0;
+    const int v = knob(KNOB_BUILD_HIDDEN);
+    return v == 1 ? MODE_F16 : (v == 2 ? MODE_SPLIT : 0);
 }
 
 template <typename E>
@@ -915,7 +909,7 @@ mole_status build_plain(const void *Em, const void *W1, const void *b1, const vo
 template <int EPI, bool F16>
 mole_status launch_gemm(const GemmArgs &g, int batches, hipStream_t st)
 {
-    const bool big = g.Nn % DBN == 0 && !getenv("MOLE_BUILD_SMALL_TILE");
+    const bool big = g.Nn % DBN == 0 && knob(KNOB_BUILD_SMALL_TILE) != 1;
     if (big) {
         static std::atomic<size_t> lds_seen{0};
         MOLE_HIP_CHECK(ensure_dynamic_lds(lds_seen, reinterpret_cast<const void *>(&gemm_nt_direct_kernel<EPI, F16>),
@@ -965,7 +959,7 @@ mole_status build_mfma(const void *Em, const void *W1, const void *b1, const voi
                            (int64_t)N * D, bound + 2);
     hipLaunchKernelGGL(abs_max_kernel, dim3(cap), dim3(256), 0, st, static_cast<const uint16_t *>(W2),
                        (int64_t)N * d * D, bound + 3);
-    hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(64), 0, st, bound, mode, env_mode());
+    hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(64), 0, st, bound, mode, forced_mode());
     for (int64_t v0 = 0; v0 < V; v0 += lay.slab) {
         const int nv = (int)((V - v0) < lay.slab ? (V - v0) : lay.slab);
         GemmArgs g1;
@@ -1049,6 +1043,7 @@ extern "C" mole_status mole_build_lut(const void *E, const void *W1, const void 
     if (!workspace || workspace_bytes < lay.total)
         return fail(MOLE_EWORKSPACE, "mole_build_lut: workspace of %zu bytes needed, got %zu", lay.total,
                     workspace ? workspace_bytes : (size_t)0);
+    MOLE_ARCH_CHECK("mole_build_lut");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     char *ws = static_cast<char *>(workspace);
     if (mfma_shape(V, d, D, dtype))

@@ -428,12 +428,13 @@ extern "C" mole_status mole_dedup_ids(const int32_t *ids, int T, int64_t V, int3
                     workspace ? workspace_bytes : (size_t)0);
     if (!aligned16(workspace))
         return fail(MOLE_EINVAL, "mole_dedup_ids: workspace is not 16-byte aligned");
+    MOLE_ARCH_CHECK("mole_dedup_ids");
     int lds_counters = 0, lds_stage = 0;
     const size_t lds = dedup_lds_bytes(T, V, &lds_counters, &lds_stage);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     int32_t *plan = static_cast<int32_t *>(workspace);
     // up to 16 tokens per thread with everything staged in LDS: the register-resident kernel
-    if (lds_stage && T <= 16 * DEDUP_THREADS && !getenv("MOLE_DEDUP_GENERIC")) {
+    if (lds_stage && T <= 16 * DEDUP_THREADS && knob(KNOB_DEDUP_GENERIC) != 1) {
         const int per = (T + DEDUP_THREADS - 1) / DEDUP_THREADS;
         hipError_t e;
         if (per <= 1)

@@ -29,14 +29,15 @@ __device__ __forceinline__ Visit visit(const int32_t *order, int item)
     return v;
 }
 
-// false (and *err_flag = 2) if `plan` was not written by mole_dedup_ids for T tokens
+// false (and bit 1 of *err_flag set) if `plan` was not written by mole_dedup_ids for T tokens; the kernels then visit
+// the tokens in their own order, so the output is still the defined one
 template <typename Args>
 __device__ __forceinline__ bool plan_ok(const Args &a)
 {
     if (a.plan[5] == PLAN_MAGIC && a.plan[2] == a.T)
         return true;
     if (threadIdx.x == 0 && a.err_flag)
-        *a.err_flag = 2;
+        atomicOr(a.err_flag, 2);
     return false;
 }
 
@@ -248,6 +249,52 @@ __device__ __forceinline__ void router_piece(float (&z)[N], const uint4 *smem, i
     }
 }
 
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+
+// two fp32 values to a packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(float2_t{lo, hi}, bf16x2_t));
+}
+
+// The same for a piece of the state x that the router reads through an RMSNorm with weight w:
+// z[j] += sum_k (x[k] * w[k]) * W_r[k, j].  A product x[k] * w[k] of two bf16 values has at most 16 significant
+// bits: it enters the dot products EXACTLY as hi + lo, hi = the product rounded to bf16, lo = the rest (at
+// most 8 significant bits, so a bf16 value itself).  Each router weight is read from LDS once and multiplied
+// with both.  One k-pair at a time, so that only one (hi, lo) pair is live.
+template <int N>
+__device__ __forceinline__ void router_piece_scaled(float (&z)[N], const uint4 *smem, int kgroups, const uint4 &xv,
+                                                    const uint32_t *wv, int kg)
+{
+    constexpr int NQ = N / 4;
+    const uint32_t xp[4] = {xv.x, xv.y, xv.z, xv.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t wq = wv[q];
+        const float a0 = bf16lo(xp[q]) * bf16lo(wq), a1 = bf16hi(xp[q]) * bf16hi(wq);
+        const uint32_t hi = cvt_pk_bf16(a0, a1);
+        const uint32_t lo = cvt_pk_bf16(a0 - bf16lo(hi), a1 - bf16hi(hi));
+#pragma unroll
+        for (int jq = 0; jq < NQ; ++jq) {
+            const uint4 w = smem[(q * NQ + jq) * (kgroups + 1) + kg];
+            z[4 * jq + 0] = mac2(mac2(z[4 * jq + 0], hi, w.x), lo, w.x);
+            z[4 * jq + 1] = mac2(mac2(z[4 * jq + 1], hi, w.y), lo, w.y);
+            z[4 * jq + 2] = mac2(mac2(z[4 * jq + 2], hi, w.z), lo, w.z);
+            z[4 * jq + 3] = mac2(mac2(z[4 * jq + 3], hi, w.w), lo, w.w);
+        }
+    }
+}
+
+// The norm weight [d] sits in LDS behind the router weight when the kernel applies the RMSNorm itself
+// (one 16-byte piece per k-group, read by the lane that owns the k-group).
+__host__ __device__ constexpr size_t norm_lds_bytes(int d) { return (size_t)d * 2; }
+__device__ __forceinline__ void fill_norm_lds(uint4 *lnw_lds, const uint16_t *ln_w, int kgroups, int nthreads)
+{
+    for (int i = threadIdx.x; i < kgroups; i += nthreads)
+        lnw_lds[i] = *reinterpret_cast<const uint4 *>(ln_w + 8 * i);
+}
+
 // Router equation for one token on one wavefront: returns, in lane l, the gate of expert
 // l / (64/N) (softmax over all N experts of h . r_j).  h0 / h1 are the lane's pieces of the first
 // two 512-column chunks, already loaded by the caller; further chunks are loaded here.
@@ -265,12 +312,15 @@ __device__ __forceinline__ float sumsq8(const uint4 &v)
     return s;
 }
 
-// NORM: hrow is the state BEFORE an RMSNorm whose weight has been folded into the router weight
-// (h . W_r = (1/rms) * x . (diag(ln_w) W_r)); the logits are scaled by 1 / sqrt(mean(x^2) + eps) of
-// this token.
+// NORM: hrow is the state x BEFORE the RMSNorm in front of the router (inference listing: the router reads the
+// post-attention-normed state).  With hn = x / rms(x) * ln_w the logits are
+//     hn . r_j = (1 / rms(x)) * sum_k (x_k ln_w_k) W_r[k, j],
+// and x_k ln_w_k enters the dot products exactly, as a pair of bf16 values (router_piece_scaled), so the only
+// roundings are those of the fp32 accumulation and of 1 / rms.  lnw: the norm weight in LDS.
 template <int N, bool NTA, bool NORM = false, int NREAL = N>
 __device__ __forceinline__ float router_gate(const uint4 *smem, int kgroups, const uint16_t *hrow, int d, int lane,
-                                             const uint4 &h0, const uint4 &h1, float eps = 0.f)
+                                             const uint4 &h0, const uint4 &h1, float eps = 0.f,
+                                             const uint4 *lnw = nullptr)
 {
     constexpr int LPJ = 64 / N;
     const int col0 = lane * 8;
@@ -288,14 +338,20 @@ __device__ __forceinline__ float router_gate(const uint4 *smem, int kgroups, con
 #pragma unroll
     for (int j = 0; j < N; ++j)
         z[j] = 0.f;
+    auto piece = [&](const uint4 &hv, int kg) {
+        if constexpr (NORM)
+            router_piece_scaled<N>(z, smem, kgroups, hv, reinterpret_cast<const uint32_t *>(lnw + kg), kg);
+        else
+            router_piece<N>(z, smem, kgroups, hv, kg);
+    };
     if (col0 < d)
-        router_piece<N>(z, smem, kgroups, h0, col0 >> 3);
+        piece(h0, col0 >> 3);
     if (col0 + 512 < d)
-        router_piece<N>(z, smem, kgroups, h1, (col0 + 512) >> 3);
+        piece(h1, (col0 + 512) >> 3);
     for (int c0 = 1024; c0 < d; c0 += 512) {
         const int cc = c0 + col0;
         if (cc < d)
-            router_piece<N>(z, smem, kgroups, ld16_stream<NTA>(hrow + cc), cc >> 3);
+            piece(ld16_stream<NTA>(hrow + cc), cc >> 3);
     }
     float zz = Fold<N, 32>::run(z, lane) * rs;
     if constexpr (NREAL < N) {
@@ -352,19 +408,13 @@ __device__ __forceinline__ uint4 pack8(const float (&acc)[8])
     return o;
 }
 
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-typedef float float2_t __attribute__((ext_vector_type(2)));
-
 // eight fp32 values to bf16, round to nearest even, with the packed conversion instruction (one per pair);
 // for the kernels that are bound by vector instruction issue: the integer sequence of pack8 costs about
 // twelve instructions per pair.  (NaN inputs give the instruction's quiet NaN, not 0x7fc0.)
 __device__ __forceinline__ uint4 pack8_cvt(const float (&acc)[8])
 {
-    uint32_t o[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-        o[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(float2_t{acc[2 * i], acc[2 * i + 1]}, bf16x2_t));
-    return make_uint4(o[0], o[1], o[2], o[3]);
+    return make_uint4(cvt_pk_bf16(acc[0], acc[1]), cvt_pk_bf16(acc[2], acc[3]), cvt_pk_bf16(acc[4], acc[5]),
+                      cvt_pk_bf16(acc[6], acc[7]));
 }
 
 }  // namespace mole

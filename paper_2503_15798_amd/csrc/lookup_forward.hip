@@ -38,8 +38,8 @@ struct FwdArgs {
     int64_t *rows_dbg;
     int32_t *err_flag;
     const int32_t *plan;
-    int norm;               // 1: h is the state BEFORE the RMSNorm in front of the router (weight folded into
-    float ln_eps;           //    W_r beforehand); it also serves as the residual
+    const void *ln_w;       // [L, d] weight of the RMSNorm in front of the router, or NULL.  Not NULL: h is the
+    float ln_eps;           // state BEFORE that norm; the kernel applies it and adds the state as the residual
     int64_t table_stride;   // per layer, elements
     int64_t act_stride;     // per layer, elements
     int64_t rows;
@@ -68,8 +68,9 @@ __device__ __forceinline__ void ring_load(uint4 (&r)[N], const uint16_t *base, i
 // chunk of a token instead of a whole token, so that the chunks of a token are fetched and combined
 // by different waves at the same time (each computes the token's gates itself: the router is cheap
 // next to a second memory round trip).
-// NORM: a.h is the state after attention and a.W_r carries the norm weight (mole_fold_router_norm);
-// the token's 1/rms scales the logits and the same state is the residual of the epilogue.
+// NORM: a.h is the state after attention and a.ln_w the weight of the RMSNorm the router reads it through;
+// the state times the norm weight enters the router exactly (router_gate), the token's 1/rms scales the
+// logits, and the same state is the residual of the epilogue.
 template <int N, int WPB, bool NTA, bool SPLIT, bool NORM>
 __global__ __launch_bounds__(WPB * 64) __attribute__((amdgpu_waves_per_eu(N <= 32 ? 4 : 2)))
 void fwd_bf16_stream_kernel(FwdArgs a)
@@ -77,12 +78,11 @@ void fwd_bf16_stream_kernel(FwdArgs a)
     extern __shared__ uint4 smem[];
     constexpr int NR = N < 4 ? 4 : N;   // experts the router is computed for (N = 2 is padded to 4)
     constexpr int LPJ = 64 / NR;        // lanes per expert after the fold
-    constexpr int R = N > 16 ? 16 : N;  // row registers: above 16 experts a chunk's rows pass through in parts of 16
+    constexpr int R = N > 16 ? (NORM && N == 32 ? 8 : 16) : N;  // row registers: above 16 experts a chunk's rows pass through in parts
     constexpr int H = N / R;
-#ifndef MOLE_FWD_HOLD_X
-#define MOLE_FWD_HOLD_X (N != 16 || !NTA)
-#endif
-    constexpr bool HOLD_X = NORM && (MOLE_FWD_HOLD_X);
+    // NORM: the state is also the residual; its two pieces stay in registers through the combine except in
+    // the variant that sits at its 128-register budget (N = 16 with non-temporal loads), which reads them again
+    constexpr bool HOLD_X = NORM && N < 16;
     const int d = a.d;
     const int kgroups = d >> 3;
     const int layer = blockIdx.y;
@@ -102,11 +102,8 @@ void fwd_bf16_stream_kernel(FwdArgs a)
     const int32_t *rowsrc = a.slot ? a.slot : a.ids;
     const int stride = gridDim.x * WPB;
     const int32_t *order = nullptr;
-    if (a.plan) {
-        if (!plan_ok(a))
-            return;
+    if (a.plan && plan_ok(a))      // a foreign plan: flagged, tokens visited in their own order
         order = a.plan + plan_layout(T).order;
-    }
 
     // the first item's rows go in flight before the router weight is staged.  Lanes past the end
     // of a ragged chunk load a clamped (valid) column; their results are never stored.
@@ -128,6 +125,10 @@ void fwd_bf16_stream_kernel(FwdArgs a)
     load_h2<NTA>(h0, h1, hbase + (int64_t)cur.t * d, d, lane);
 
     fill_router_lds<NR, N>(smem, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
+    const uint4 *lnw = smem + router_lds_bytes(d, NR) / 16;     // NORM: the norm weight behind the router weight
+    if constexpr (NORM)
+        fill_norm_lds(smem + router_lds_bytes(d, NR) / 16, static_cast<const uint16_t *>(a.ln_w) + (int64_t)layer * d,
+                      kgroups, WPB * 64);
     __syncthreads();
 
     for (; item < n_items; item += stride) {
@@ -139,11 +140,11 @@ void fwd_bf16_stream_kernel(FwdArgs a)
         const bool nvalid = nrow >= 0 && nrow < a.rows;
         const bool reporter = !SPLIT || cbase == 0;    // one item per token reports flags and debug outputs
         if (!valid && lane == 0 && a.err_flag)
-            *a.err_flag = 1;
+            atomicOr(a.err_flag, 1);
         if (a.rows_dbg && layer == 0 && lane == 0 && reporter)
             a.rows_dbg[t] = valid ? row : -1;
 
-        const float g = router_gate<NR, NTA, NORM, N>(smem, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1, a.ln_eps);
+        const float g = router_gate<NR, NTA, NORM, N>(smem, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1, a.ln_eps, lnw);
         if (a.gates_dbg && reporter && (lane & (LPJ - 1)) == 0 && lane / LPJ < N)
             a.gates_dbg[((int64_t)layer * T + t) * N + lane / LPJ] = g;
         const uint4 x0 = h0, x1 = h1;                  // NORM: the residual of chunks 0 and 1
@@ -385,12 +386,12 @@ void fwd_bf16_run_kernel(FwdArgs a)
     uint16_t *obase = static_cast<uint16_t *>(a.out) + act_off;
     const int32_t *rowsrc = a.slot ? a.slot : a.ids;
     const int stride = gridDim.x * WPB;
-    if (!plan_ok(a))
-        return;
-    const int32_t *order = a.plan + plan_layout(T).order;
+    // a foreign plan is flagged and replaced by the identity order (every token its own group)
+    const int32_t *order = plan_ok(a) ? a.plan + plan_layout(T).order : nullptr;
     // the wave's gates behind the router weight, for the span being combined and for the next one:
     // [2][G][NQ] pieces of 16 bytes = 4 experts x (hi, lo)
-    uint4 *gq = smem + router_lds_bytes(d, NR) / 16 + wave * (2 * G * NQ);
+    const uint4 *lnw = smem + router_lds_bytes(d, NR) / 16;     // NORM: the norm weight, then the gates
+    uint4 *gq = smem + (router_lds_bytes(d, NR) + (NORM ? norm_lds_bytes(d) : 0)) / 16 + wave * (2 * G * NQ);
 
     // Span descriptor: lane i holds position i's plan entry (token index, read-once flag in bit 31)
     // and row block; -1 = no such position / id outside the table.
@@ -399,7 +400,7 @@ void fwd_bf16_run_kernel(FwdArgs a)
         Span sp{-1, -1};
         const int p = s * G + lane;
         if (s < nspans && lane < G && p < T) {
-            sp.t = order[p];
+            sp.t = order ? order[p] : p;
             const int32_t rr = rowsrc[sp.t & ~PLAN_SINGLE];
             sp.row = rr >= 0 && rr < a.rows ? rr : -1;
         }
@@ -438,10 +439,10 @@ void fwd_bf16_run_kernel(FwdArgs a)
         const int t = token_of(sp, j);
         const int32_t row = __builtin_amdgcn_readlane(sp.row, j);
         if (row < 0 && lane == 0 && a.err_flag)
-            *a.err_flag = 1;
+            atomicOr(a.err_flag, 1);
         if (a.rows_dbg && layer == 0 && lane == 0)
             a.rows_dbg[t] = row;
-        const float g = router_gate<NR, false, NORM, N>(smem, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1, a.ln_eps);
+        const float g = router_gate<NR, false, NORM, N>(smem, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1, a.ln_eps, lnw);
         if ((lane & (LPJ - 1)) == 0) {
             const int e = lane / LPJ;
             if (a.gates_dbg && e < N)
@@ -490,6 +491,9 @@ void fwd_bf16_run_kernel(FwdArgs a)
         load_h2<false>(h0, h1, hbase + (int64_t)token_of(cur_sp, 0) * d, d, lane);
 
     fill_router_lds<NR, N>(smem, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
+    if constexpr (NORM)
+        fill_norm_lds(smem + router_lds_bytes(d, NR) / 16, static_cast<const uint16_t *>(a.ln_w) + (int64_t)layer * d,
+                      kgroups, WPB * 64);
     __syncthreads();
 
     // gates of the wave's first span; those of every later span are computed between the items of
@@ -656,16 +660,14 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(FwdArgs a)
     float *gl = gls[wave];
 
     const int32_t *order = nullptr;
-    if (a.plan) {
-        if (!plan_ok(a))
-            return;
+    if (a.plan && plan_ok(a))      // a foreign plan: flagged, tokens visited in their own order
         order = a.plan + plan_layout(a.T).order;
-    }
     const E *table = static_cast<const E *>(a.table) + (int64_t)layer * a.table_stride;
     const int64_t act_off = (int64_t)layer * a.act_stride;
     const E *hbase = static_cast<const E *>(a.h) + act_off;
     const E *Wr = static_cast<const E *>(a.W_r) + (int64_t)layer * d * N;
-    const bool norm = a.norm != 0;
+    const E *lnw = a.ln_w ? static_cast<const E *>(a.ln_w) + (int64_t)layer * d : nullptr;
+    const bool norm = lnw != nullptr;
     const E *sbase = a.shared ? static_cast<const E *>(a.shared) + act_off : nullptr;
     const E *rbase = a.residual ? static_cast<const E *>(a.residual) + act_off : nullptr;
     E *obase = static_cast<E *>(a.out) + act_off;
@@ -677,7 +679,7 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(FwdArgs a)
         const int64_t row = rowsrc[t];
         const bool valid = row >= 0 && row < a.rows;
         if (!valid && lane == 0 && a.err_flag)
-            *a.err_flag = 1;
+            atomicOr(a.err_flag, 1);
         if (a.rows_dbg && layer == 0 && lane == 0)
             a.rows_dbg[t] = valid ? row : -1;
         const E *rp = table + (valid ? row : 0) * (int64_t)N * d;
@@ -698,7 +700,8 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(FwdArgs a)
             for (int j = 0; j < JB; ++j)
                 z[j] = 0.f;
             for (int k = lane; k < d; k += 64) {
-                const float hk = ldf(hr + k);
+                // with the norm: x_k * ln_w_k (exact in fp32 for bf16 storage), scaled by 1 / rms after the sum
+                const float hk = norm ? ldf(hr + k) * ldf(lnw + k) : ldf(hr + k);
                 const E *wk = Wr + (int64_t)k * N + jb;
                 if (row_pieces) {
 #pragma unroll
@@ -780,29 +783,10 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(FwdArgs a)
     }
 }
 
-// W_rn[l, k, j] = W_r[l, k, j] * ln_w[l, k], one rounding to the storage type.  ln_w is [L, d] and
-// W_r is [L, d, N], so row index (l, k) is simply element / N.
-template <typename E>
-__global__ __launch_bounds__(256) void fold_norm_kernel(const E *__restrict__ W, const E *__restrict__ lnw,
-                                                         E *__restrict__ out, int64_t total, int N)
-{
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256)
-        stf(out + i, ldf(W + i) * ldf(lnw + i / N));
-}
-
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
 constexpr size_t LDS_BYTES_PER_CU = 160 * 1024;
-
-int env_int(const char *name, int dflt)
-{
-    const char *s = getenv(name);
-    if (!s || !*s)
-        return dflt;
-    const int v = atoi(s);
-    return v > 0 ? v : dflt;
-}
 
 // Grid shape.  Every wave should get the same number of items, and all workgroups should be
 // resident at once (a second round would stage the router weight again and leave CUs idle at the
@@ -816,7 +800,7 @@ int64_t grid_x(int items, int L, size_t lds, int waves_per_cu = N <= 4 ? 32 : (N
     const int wave_cap = waves_per_cu / WPB;
     if (per_cu > wave_cap)
         per_cu = wave_cap;
-    per_cu = env_int("MOLE_FWD_WGS_PER_CU", per_cu);
+    per_cu = knob_or(KNOB_FWD_WGS_PER_CU, per_cu);
     if (per_cu < 1)
         per_cu = 1;
     const int64_t resident = (int64_t)num_cus() * per_cu;
@@ -830,7 +814,7 @@ int64_t grid_x(int items, int L, size_t lds, int waves_per_cu = N <= 4 ? 32 : (N
         // halve_items (the streaming kernel at N >= 32: eight-wave workgroups, two per CU): from four items per
         // wave on, twice as many workgroups with half the items each even out the tail (T = 16384: 211 ->
         // 202 us with uniform ids, 116 -> 108 us with Zipf ids; one item per wave is worse again)
-        if (halve_items && ipw >= 4 && !env_int("MOLE_FWD_WGS_PER_CU", 0))
+        if (halve_items && ipw >= 4 && !knob(KNOB_FWD_WGS_PER_CU))
             ipw = (ipw + 1) / 2;
         gx = (items + WPB * ipw - 1) / (WPB * ipw);
     }
@@ -840,7 +824,7 @@ int64_t grid_x(int items, int L, size_t lds, int waves_per_cu = N <= 4 ? 32 : (N
 template <int N, int WPB, bool NTA, bool SPLIT, bool NORM>
 mole_status launch_fast(const FwdArgs &a, hipStream_t stream)
 {
-    const size_t lds = router_lds_bytes(a.d, N < 4 ? 4 : N);
+    const size_t lds = router_lds_bytes(a.d, N < 4 ? 4 : N) + (NORM ? norm_lds_bytes(a.d) : 0);
     static std::atomic<size_t> lds_seen{0};
     MOLE_HIP_CHECK(ensure_dynamic_lds(
         lds_seen, reinterpret_cast<const void *>(&fwd_bf16_stream_kernel<N, WPB, NTA, SPLIT, NORM>), lds));
@@ -854,7 +838,7 @@ mole_status launch_fast(const FwdArgs &a, hipStream_t stream)
 template <int N, int WPB, bool NTA, bool SPLIT>
 mole_status launch_fast(const FwdArgs &a, hipStream_t stream)
 {
-    return a.norm ? launch_fast<N, WPB, NTA, SPLIT, true>(a, stream)
+    return a.ln_w ? launch_fast<N, WPB, NTA, SPLIT, true>(a, stream)
                   : launch_fast<N, WPB, NTA, SPLIT, false>(a, stream);
 }
 
@@ -862,7 +846,8 @@ template <int N, int WPB, bool NORM, bool RES>
 mole_status launch_run(const FwdArgs &a, hipStream_t stream)
 {
     constexpr int NR = N < 4 ? 4 : N;
-    const size_t lds = router_lds_bytes(a.d, NR) + (size_t)WPB * 2 * RUN_GROUP * NR * sizeof(float);
+    const size_t lds = router_lds_bytes(a.d, NR) + (NORM ? norm_lds_bytes(a.d) : 0) +
+                       (size_t)WPB * 2 * RUN_GROUP * NR * sizeof(float);
     static std::atomic<size_t> lds_seen{0};
     MOLE_HIP_CHECK(ensure_dynamic_lds(lds_seen, reinterpret_cast<const void *>(&fwd_bf16_run_kernel<N, WPB, NORM, RES>),
                                       lds));
@@ -879,7 +864,7 @@ mole_status launch_fast_n(const FwdArgs &a, hipStream_t stream, bool long_runs)
     // wider workgroups when the router weight is large, so that LDS does not cap occupancy
     const size_t wbytes = (size_t)a.d * N * 2;
     int wpb = wbytes > 40 * 1024 ? 8 : 4;
-    wpb = env_int("MOLE_FWD_WPB", wpb);
+    wpb = knob_or(KNOB_FWD_WPB, wpb);
     // MOLE_FLAG_RUNS (the caller expects long runs of equal ids in the plan): groups of equal ids share one
     // fetch of their rows and the weighted sum runs on the matrix pipe.  Against the streaming kernel in plan
     // order it wins from about eight tokens per distinct id on (N = 32, T = 16384: 54 against 73 us at 256
@@ -889,21 +874,21 @@ mole_status launch_fast_n(const FwdArgs &a, hipStream_t stream, bool long_runs)
     // register file).
     if constexpr (N <= 32) {
         constexpr size_t gate_lds = (size_t)4 * 2 * RUN_GROUP * 32 * sizeof(float);
-        if (a.plan && env_int("MOLE_FWD_RUN", long_runs ? 1 : 2) == 1 &&
-            router_lds_bytes(a.d, N < 4 ? 4 : N) + gate_lds <= LDS_BYTES_PER_CU) {
-            if (a.norm)
+        if (a.plan && knob_or(KNOB_FWD_RUN, long_runs ? 1 : 2) == 1 &&
+            router_lds_bytes(a.d, N < 4 ? 4 : N) + norm_lds_bytes(a.d) + gate_lds <= LDS_BYTES_PER_CU) {
+            if (a.ln_w)
                 return launch_run<N, 4, true, true>(a, stream);
             return a.residual ? launch_run<N, 4, false, true>(a, stream) : launch_run<N, 4, false, false>(a, stream);
         }
     }
     // large batches: keep the read-once activations out of the caches (not with a plan: there a token's
     // activation rows are visited in id order and the plain load measures 2.5 % faster)
-    const bool nta = env_int("MOLE_FWD_NTA", (int64_t)a.T * a.L >= 8192 && !a.plan ? 1 : 2) == 1;
+    const bool nta = knob_or(KNOB_FWD_NTA, (int64_t)a.T * a.L >= 8192 && !a.plan ? 1 : 2) == 1;
     // small launches: one chunk per item (latency regime); never together with the large-batch loads
-    const bool split = env_int("MOLE_FWD_SPLIT", (int64_t)a.T * a.L <= 2048 ? 1 : 2) == 1 && a.d > 512;
+    const bool split = knob_or(KNOB_FWD_SPLIT, (int64_t)a.T * a.L <= 2048 ? 1 : 2) == 1 && a.d > 512;
     // chunk items of many layers in one launch: eight waves share a staged router weight instead of four
     // (24 layers x 32 tokens: 11.7 -> 11.2 us; a single layer is faster with the smaller workgroups)
-    if (split && a.L >= 8 && (int64_t)a.T * ((a.d + 511) / 512) >= 64 && !getenv("MOLE_FWD_WPB"))
+    if (split && a.L >= 8 && (int64_t)a.T * ((a.d + 511) / 512) >= 64 && !knob(KNOB_FWD_WPB))
         wpb = 8;
     if (split)
         return wpb >= 8 ? launch_fast<N, 8, false, true>(a, stream) : launch_fast<N, 4, false, true>(a, stream);
@@ -917,7 +902,7 @@ mole_status forward_impl(const void *table, int64_t table_stride, const int32_t 
                          void *out, int64_t act_stride, float *gates_dbg, int64_t *rows_dbg,
                          int32_t *err_flag, int L, int T, int64_t rows, int d, int N, mole_dtype dtype,
                          unsigned flags, const void *workspace, size_t workspace_bytes, void *hip_stream,
-                         float ln_eps = 0.f, bool with_norm = false)
+                         float ln_eps = 0.f, const void *ln_w = nullptr, bool with_norm = false)
 {
     clear_error();
     if (dtype != MOLE_F32 && dtype != MOLE_BF16)
@@ -939,8 +924,14 @@ mole_status forward_impl(const void *table, int64_t table_stride, const int32_t 
         return MOLE_OK;
     if (!table || !ids || !h || !W_r || !out)
         return fail(MOLE_EINVAL, "mole_lookup_forward: table, ids, h, W_r and out must not be NULL");
+    if (with_norm && !ln_w)
+        return fail(MOLE_EINVAL, "mole_layer_forward: ln_w must not be NULL");
     if (with_norm && !(ln_eps >= 0.f))
         return fail(MOLE_EINVAL, "mole_layer_forward: ln_eps = %g must be >= 0", (double)ln_eps);
+    if (ln_w && !aligned16(ln_w))
+        return fail(MOLE_EINVAL, "mole_layer_forward: ln_w %p is not 16-byte aligned", ln_w);
+    if (ln_w && L > 1 && ((int64_t)d * elem_bytes(dtype)) % 16)
+        return fail(MOLE_EUNSUPPORTED, "mole_layer_forward: with L > 1 a norm-weight row of d=%d must be a 16-byte multiple", d);
     const void *ptrs[] = {table, h, W_r, shared_out, residual, out};
     for (const void *p : ptrs)
         if (p && !aligned16(p))
@@ -962,17 +953,18 @@ mole_status forward_impl(const void *table, int64_t table_stride, const int32_t 
         plan = static_cast<const int32_t *>(workspace);
     }
 
+    MOLE_ARCH_CHECK("mole_lookup_forward");
     FwdArgs a;
     a.table = table; a.ids = ids; a.slot = slot; a.h = h; a.W_r = W_r;
     a.shared = shared_out; a.residual = residual; a.out = out;
     a.gates_dbg = gates_dbg; a.rows_dbg = rows_dbg; a.err_flag = err_flag; a.plan = plan;
-    a.norm = with_norm ? 1 : 0; a.ln_eps = ln_eps;
+    a.ln_w = with_norm ? ln_w : nullptr; a.ln_eps = ln_eps;
     a.table_stride = table_stride; a.act_stride = act_stride; a.rows = rows;
     a.T = T; a.d = d; a.N = N; a.L = L;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
-    const size_t lds_fast = router_lds_bytes(d, N < 4 ? 4 : N);
-    const bool fast = dtype == MOLE_BF16 && lds_fast <= LDS_BYTES_PER_CU && !getenv("MOLE_FWD_GENERIC");
+    const size_t lds_fast = router_lds_bytes(d, N < 4 ? 4 : N) + (with_norm ? norm_lds_bytes(d) : 0);
+    const bool fast = dtype == MOLE_BF16 && lds_fast <= LDS_BYTES_PER_CU && knob(KNOB_FWD_GENERIC) != 1;
     if (fast) {
         switch (N) {
         case 2: return launch_fast_n<2>(a, stream, long_runs);
@@ -1026,39 +1018,13 @@ extern "C" mole_status mole_lookup_forward_layers(const void *table, int64_t tab
 }
 
 extern "C" mole_status mole_layer_forward(const void *table, int64_t table_stride, const int32_t *ids,
-                                          const int32_t *slot, const void *x, float ln_eps, const void *W_rn,
-                                          const void *shared_out, void *out, int64_t act_stride,
+                                          const int32_t *slot, const void *x, const void *ln_w, float ln_eps,
+                                          const void *W_r, const void *shared_out, void *out, int64_t act_stride,
                                           float *gates_dbg, int64_t *rows_dbg, int32_t *err_flag, int L, int T,
                                           int64_t rows, int d, int N, mole_dtype dtype, unsigned flags,
                                           const void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    return forward_impl(table, table_stride, ids, slot, x, W_rn, shared_out, nullptr, out, act_stride, gates_dbg,
+    return forward_impl(table, table_stride, ids, slot, x, W_r, shared_out, nullptr, out, act_stride, gates_dbg,
                         rows_dbg, err_flag, L, T, rows, d, N, dtype, flags, workspace, workspace_bytes, hip_stream,
-                        ln_eps, true);
-}
-
-extern "C" mole_status mole_fold_router_norm(const void *W_r, const void *ln_w, void *W_rn, int L, int d, int N,
-                                             mole_dtype dtype, void *hip_stream)
-{
-    clear_error();
-    if (dtype != MOLE_F32 && dtype != MOLE_BF16)
-        return fail(MOLE_EINVAL, "mole_fold_router_norm: unknown dtype %d", (int)dtype);
-    if (L < 1 || d < 1 || N < 1)
-        return fail(MOLE_EINVAL, "mole_fold_router_norm: bad size (L=%d, d=%d, N=%d)", L, d, N);
-    if (!W_r || !ln_w || !W_rn)
-        return fail(MOLE_EINVAL, "mole_fold_router_norm: W_r, ln_w and W_rn must not be NULL");
-    const int64_t rows = (int64_t)L * d;
-    const int64_t total = rows * N;
-    const unsigned blocks = (unsigned)((total + 255) / 256 < 65535 * 16 ? (total + 255) / 256 : 65535 * 16);
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (dtype == MOLE_F32)
-        hipLaunchKernelGGL(fold_norm_kernel<float>, dim3(blocks), dim3(256), 0, stream,
-                           static_cast<const float *>(W_r), static_cast<const float *>(ln_w),
-                           static_cast<float *>(W_rn), total, N);
-    else
-        hipLaunchKernelGGL(fold_norm_kernel<uint16_t>, dim3(blocks), dim3(256), 0, stream,
-                           static_cast<const uint16_t *>(W_r), static_cast<const uint16_t *>(ln_w),
-                           static_cast<uint16_t *>(W_rn), total, N);
-    MOLE_HIP_CHECK(hipGetLastError());
-    return MOLE_OK;
+                        ln_eps, ln_w, true);
 }

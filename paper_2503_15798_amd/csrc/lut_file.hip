@@ -160,6 +160,14 @@ mole_status check_desc(const char *who, const mole_lut_desc &c)
         return fail(MOLE_EINVAL, "%s: unknown layout %d", who, c.layout);
     if (c.L < 1 || c.N < 1 || c.d < 1 || c.V < 1)
         return fail(MOLE_EINVAL, "%s: bad size (L=%d, V=%lld, N=%d, d=%d)", who, c.L, (long long)c.V, c.N, c.d);
+    // the payload size L * V * N * d * element bytes must be representable: a header whose product wraps
+    // around could otherwise pass the comparison with the file size
+    uint64_t bytes = (uint64_t)c.L;
+    if (__builtin_mul_overflow(bytes, (uint64_t)c.V, &bytes) || __builtin_mul_overflow(bytes, (uint64_t)c.N, &bytes) ||
+        __builtin_mul_overflow(bytes, (uint64_t)c.d, &bytes) ||
+        __builtin_mul_overflow(bytes, (uint64_t)elem_bytes((mole_dtype)c.dtype), &bytes) || bytes > (uint64_t)1 << 62)
+        return fail(MOLE_EINVAL, "%s: table of L=%d x V=%lld x N=%d x d=%d elements is too large to address", who, c.L,
+                    (long long)c.V, c.N, c.d);
     return MOLE_OK;
 }
 

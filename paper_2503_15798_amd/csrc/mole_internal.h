@@ -21,6 +21,32 @@ inline size_t elem_bytes(mole_dtype dt) { return dt == MOLE_F32 ? 4 : (dt == MOL
 // Number of compute units of the current device (cached per process; 256 on MI355X).
 int num_cus();
 
+// MOLE_OK if the current device is a gfx950 part (the only code object in the library); MOLE_EUNSUPPORTED
+// with a message otherwise.  Checked once per process and device, before the first launch of an entry point.
+mole_status check_arch(const char *who);
+
+// Tuning knobs (experiments and tests; normal use needs none).  Each is read from the environment variable of
+// the same name ONCE, at its first use in the process; mole_set_tuning() overrides it at run time.
+// 0 = the library's own choice.
+enum Knob {
+    KNOB_FWD_WPB,           // MOLE_FWD_WPB          waves per workgroup of the forward kernels: 4 or 8
+    KNOB_FWD_WGS_PER_CU,    // MOLE_FWD_WGS_PER_CU   resident workgroups per CU the grid is sized for
+    KNOB_FWD_NTA,           // MOLE_FWD_NTA          1 = non-temporal activation loads, 2 = plain
+    KNOB_FWD_SPLIT,         // MOLE_FWD_SPLIT        1 = one 512-column chunk per work item, 2 = whole tokens
+    KNOB_FWD_RUN,           // MOLE_FWD_RUN          1 / 2 = force / forbid the run kernel for planned calls
+    KNOB_FWD_GENERIC,       // MOLE_FWD_GENERIC      1 = the generic forward kernel for every shape
+    KNOB_DEDUP_GENERIC,     // MOLE_DEDUP_GENERIC    1 = the generic dedup kernel for every size
+    KNOB_BUILD_HIDDEN,      // MOLE_BUILD_HIDDEN     1 (or "f16") / 2 (or "split"): hidden activation of the build
+    KNOB_BUILD_SMALL_TILE,  // MOLE_BUILD_SMALL_TILE 1 = the 256 x 128 GEMM for every shape
+    KNOB_COUNT
+};
+int knob(Knob k);
+inline int knob_or(Knob k, int dflt)
+{
+    const int v = knob(k);
+    return v > 0 ? v : dflt;
+}
+
 // Raises a kernel's dynamic-LDS limit to `lds` bytes unless a call has already raised it that far.  `seen`
 // is the per-kernel cache (a function-local static): callers on several threads may race to set the same
 // attribute, which is harmless, but must not tear the cached size.
@@ -36,6 +62,13 @@ inline hipError_t ensure_dynamic_lds(std::atomic<size_t> &seen, const void *kern
     }
     return e;
 }
+
+#define MOLE_ARCH_CHECK(who)                          \
+    do {                                              \
+        const mole_status st_ = ::mole::check_arch(who); \
+        if (st_ != MOLE_OK)                           \
+            return st_;                               \
+    } while (0)
 
 #define MOLE_HIP_CHECK(expr)                                                             \
     do {                                                                                 \

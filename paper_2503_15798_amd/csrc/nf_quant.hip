@@ -47,8 +47,8 @@ struct NfArgs {
     int64_t rows;
     int T, d, N, L;
     int block;               // elements per scale
-    float ln_eps;            // NORM variant: h is the state before the RMSNorm in front of the router (its weight
-                             // folded into W_r beforehand) and is added as the residual
+    const void *ln_w;        // NORM variant: [L, d] weight of the RMSNorm in front of the router; h is the state
+    float ln_eps;            // before that norm and is added as the residual
 };
 
 // A scale is fetched as a raw dword (the fp32 value, or the aligned dword holding the bf16 value) and
@@ -246,11 +246,8 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
     const int32_t *rowsrc = a.slot ? a.slot : a.ids;
     const int stride = gridDim.x * WPB;
     const int32_t *order = nullptr;
-    if (a.plan) {
-        if (!plan_ok(a))
-            return;
+    if (a.plan && plan_ok(a))      // a foreign plan: flagged, tokens visited in their own order
         order = a.plan + plan_layout(T).order;
-    }
 
     // pair table (static: see dequant_pair8): entry a | b << BITS holds (level[a], level[b]) as fp16
     __shared__ uint32_t cb2[NLEV * NLEV];
@@ -261,6 +258,10 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
         cb2[i] = __builtin_bit_cast(uint32_t, pr);
     }
     fill_router_lds<NR, N>(router, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
+    const uint4 *lnw = smem + router_lds_bytes(d, NR) / 16;     // NORM: the norm weight behind the router weight
+    if constexpr (NORM)
+        fill_norm_lds(smem + router_lds_bytes(d, NR) / 16, static_cast<const uint16_t *>(a.ln_w) + (int64_t)layer * d,
+                      kgroups, WPB * 64);
     __syncthreads();
 
     // code words and scales of the wave's first token go in flight before anything else
@@ -320,11 +321,11 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
         const int64_t nrow = nitem < T ? (int64_t)__builtin_amdgcn_readfirstlane(rowsrc[nt]) : -1;
         const bool nvalid = nrow >= 0 && nrow < a.rows;
         if (!valid && lane == 0 && a.err_flag)
-            *a.err_flag = 1;
+            atomicOr(a.err_flag, 1);
         if (a.rows_dbg && layer == 0 && lane == 0)
             a.rows_dbg[t] = valid ? row : -1;
 
-        const float g = router_gate<NR, false, NORM, N>(router, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1, a.ln_eps);
+        const float g = router_gate<NR, false, NORM, N>(router, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1, a.ln_eps, lnw);
         if (a.gates_dbg && (lane & (LPJ - 1)) == 0 && lane / LPJ < N)
             a.gates_dbg[((int64_t)layer * T + t) * N + lane / LPJ] = g;
         load_h2<false>(h0, h1, hbase + (int64_t)nt * d, d, lane);
@@ -423,7 +424,7 @@ mole_status launch_nf(const NfArgs &a, int scale_bytes, hipStream_t stream)
     // N >= 32: the router weight (64 KiB at N = 32, d = 1024) leaves room for two workgroups per CU, so the
     // waves that the registers allow (three or four per SIMD) have to come from larger workgroups
     constexpr int WPB = N >= 32 ? 8 : 4;
-    const size_t lds = router_lds_bytes(a.d, N < 4 ? 4 : N) + 64;
+    const size_t lds = router_lds_bytes(a.d, N < 4 ? 4 : N) + (NORM ? norm_lds_bytes(a.d) : 0) + 64;
     static std::atomic<size_t> lds_seen{0};
     MOLE_HIP_CHECK(ensure_dynamic_lds(lds_seen, reinterpret_cast<const void *>(&fwd_nf_kernel<N, BITS, WPB, NORM>), lds));
     int per_cu = (int)((160 * 1024) / (lds + PAIR_TABLE_LDS));
@@ -464,13 +465,13 @@ mole_status launch_nf_n(const NfArgs &a, int scale_bytes, hipStream_t stream)
     }
 }
 
-// shared by mole_lookup_forward_nf and mole_layer_forward_nf (with_norm: h is the state x, W_r the folded weight)
+// shared by mole_lookup_forward_nf and mole_layer_forward_nf (ln_w given: h is the state x before the norm)
 mole_status nf_forward_impl(const char *who, const void *codes, int64_t codes_stride, const void *scales,
                             int64_t scales_stride, const int32_t *ids, const int32_t *slot, const void *h,
                             const void *W_r, const void *shared_out, const void *residual, void *out,
                             int64_t act_stride, float *gates_dbg, int64_t *rows_dbg, int32_t *err_flag, int L, int T,
                             int64_t rows, int d, int N, int bits, int block, int scale_bytes, unsigned flags,
-                            const void *workspace, size_t workspace_bytes, void *hip_stream, bool with_norm,
+                            const void *workspace, size_t workspace_bytes, void *hip_stream, const void *ln_w,
                             float ln_eps)
 {
     clear_error();
@@ -479,11 +480,16 @@ mole_status nf_forward_impl(const char *who, const void *codes, int64_t codes_st
         return ps;
     if (T < 0 || L < 1 || L > 65535 || rows < 1)
         return fail(MOLE_EINVAL, "%s: bad size (T=%d, L=%d, rows=%lld)", who, T, L, (long long)rows);
+    if (N != 2 && N != 4 && N != 8 && N != 16 && N != 32 && N != 64)
+        return fail(MOLE_EUNSUPPORTED, "%s: N=%d, built for 2, 4, 8, 16, 32, 64", who, N);
     if (flags & ~unsigned(MOLE_FLAG_DEDUP))
         return fail(MOLE_EINVAL, "%s: unknown flags 0x%x", who, flags);
+    const bool with_norm = ln_w != nullptr;
     if (with_norm && !(ln_eps >= 0.f))
         return fail(MOLE_EINVAL, "%s: ln_eps = %g must be >= 0", who, (double)ln_eps);
-    if (router_lds_bytes(d, N < 4 ? 4 : N) + 64 + PAIR_TABLE_LDS > 160 * 1024)
+    if (with_norm && !aligned16(ln_w))
+        return fail(MOLE_EINVAL, "%s: ln_w %p is not 16-byte aligned", who, ln_w);
+    if (router_lds_bytes(d, N < 4 ? 4 : N) + (with_norm ? norm_lds_bytes(d) : 0) + 64 + PAIR_TABLE_LDS > 160 * 1024)
         return fail(MOLE_EUNSUPPORTED, "%s: router weight of %d x %d does not fit in LDS", who, d, N);
     if (T == 0)
         return MOLE_OK;
@@ -508,11 +514,12 @@ mole_status nf_forward_impl(const char *who, const void *codes, int64_t codes_st
                         workspace ? workspace_bytes : (size_t)0);
         plan = static_cast<const int32_t *>(workspace);
     }
+    MOLE_ARCH_CHECK(who);
     NfArgs a;
     a.codes = static_cast<const uint8_t *>(codes); a.scales = scales; a.ids = ids; a.slot = slot; a.h = h; a.W_r = W_r;
     a.shared = shared_out; a.residual = residual; a.out = out; a.gates_dbg = gates_dbg; a.rows_dbg = rows_dbg;
     a.err_flag = err_flag; a.plan = plan; a.codes_stride = codes_stride; a.scales_stride = scales_stride;
-    a.act_stride = act_stride; a.rows = rows; a.T = T; a.d = d; a.N = N; a.L = L; a.block = block; a.ln_eps = ln_eps;
+    a.act_stride = act_stride; a.rows = rows; a.T = T; a.d = d; a.N = N; a.L = L; a.block = block; a.ln_w = ln_w; a.ln_eps = ln_eps;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (with_norm)
         return bits == 4 ? launch_nf_n<4, true>(a, scale_bytes, stream) : launch_nf_n<3, true>(a, scale_bytes, stream);
@@ -561,6 +568,7 @@ extern "C" mole_status mole_quantize_lut(const void *table, void *codes, void *s
         return fail(MOLE_EINVAL, "mole_quantize_lut: table, codes and scales must not be NULL");
     if (!aligned16(table) || !aligned16(codes) || !aligned16(scales))
         return fail(MOLE_EINVAL, "mole_quantize_lut: buffers must be 16-byte aligned");
+    MOLE_ARCH_CHECK("mole_quantize_lut");
     const int64_t n_rows = rows * N;
     const unsigned blocks = (unsigned)((n_rows + 3) / 4);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -584,18 +592,23 @@ extern "C" mole_status mole_lookup_forward_nf(const void *codes, int64_t codes_s
 {
     return nf_forward_impl("mole_lookup_forward_nf", codes, codes_stride, scales, scales_stride, ids, slot, h, W_r,
                            shared_out, residual, out, act_stride, gates_dbg, rows_dbg, err_flag, L, T, rows, d, N, bits,
-                           block, scale_bytes, flags, workspace, workspace_bytes, hip_stream, false, 0.f);
+                           block, scale_bytes, flags, workspace, workspace_bytes, hip_stream, nullptr, 0.f);
 }
 
 extern "C" mole_status mole_layer_forward_nf(const void *codes, int64_t codes_stride, const void *scales,
                                              int64_t scales_stride, const int32_t *ids, const int32_t *slot,
-                                             const void *x, float ln_eps, const void *W_rn, const void *shared_out,
+                                             const void *x, const void *ln_w, float ln_eps, const void *W_r,
+                                             const void *shared_out,
                                              void *out, int64_t act_stride, float *gates_dbg, int64_t *rows_dbg,
                                              int32_t *err_flag, int L, int T, int64_t rows, int d, int N, int bits,
                                              int block, int scale_bytes, unsigned flags, const void *workspace,
                                              size_t workspace_bytes, void *hip_stream)
 {
-    return nf_forward_impl("mole_layer_forward_nf", codes, codes_stride, scales, scales_stride, ids, slot, x, W_rn,
+    if (!ln_w) {
+        clear_error();
+        return fail(MOLE_EINVAL, "mole_layer_forward_nf: ln_w must not be NULL");
+    }
+    return nf_forward_impl("mole_layer_forward_nf", codes, codes_stride, scales, scales_stride, ids, slot, x, W_r,
                            shared_out, nullptr, out, act_stride, gates_dbg, rows_dbg, err_flag, L, T, rows, d, N, bits,
-                           block, scale_bytes, flags, workspace, workspace_bytes, hip_stream, true, ln_eps);
+                           block, scale_bytes, flags, workspace, workspace_bytes, hip_stream, ln_w, ln_eps);
 }

@@ -97,6 +97,7 @@ mole_status fetch_impl(const char *who, bool id_major, const void *host_table, i
         return fail(MOLE_EINVAL, "%s: staging layer stride too small or not a 16-byte multiple", who);
     if (!id_major && L > 1 && (host_layer_stride < V * N * (int64_t)d || (host_layer_stride * eb) % 16))
         return fail(MOLE_EINVAL, "%s: host layer stride too small or not a 16-byte multiple", who);
+    MOLE_ARCH_CHECK(who);
     const int row16 = (int)(row_bytes / 16);
     const int pieces = (row16 + 63) / 64;
     int64_t waves = (int64_t)L * U_cap * pieces;
@@ -203,6 +204,7 @@ extern "C" mole_status mole_offload_fetch_nf(const void *host_codes, int64_t hos
                    staging_scales_stride * scale_bytes, L, U_cap, V, scale_row, &scale_unit);
     if (st != MOLE_OK)
         return st;
+    MOLE_ARCH_CHECK(who);
     fetch_rows(code_unit, host_codes, host_codes_stride, uniq, n_uniq, staging_codes, staging_codes_stride, err_flag, L,
                U_cap, V, code_row, stream);
     fetch_rows(scale_unit, host_scales, host_scales_stride * scale_bytes, uniq, n_uniq, staging_scales,

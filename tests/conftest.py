@@ -27,3 +27,18 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def tuning():
+    """Set tuning knobs of the library for one test (mole_set_tuning); every knob set is restored to the
+    library's own choice afterwards."""
+    from paper_2503_15798_amd import binding as mb
+    touched = []
+
+    def set_knob(name, value):
+        mb.mole_set_tuning(name, int(value))
+        touched.append(name)
+    yield set_knob
+    for name in touched:
+        mb.mole_set_tuning(name, 0)

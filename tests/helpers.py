@@ -42,29 +42,14 @@ def assert_close(got_f64, ref_f64, dtype, what="", extra_atol=0.0):
                              f"got {got_f64[i]!r}, ref {ref_f64[i]!r}, |err| {err[i]:.3e} > {lim[i]:.3e}")
 
 
-def folded_router(ln_w, W_r, dtype, d):
-    """(unit norm weight, router weight with the norm weight folded in and rounded to the storage type):
-    what mole_fold_router_norm stores, computed on the host -- the product of two stored values rounded
-    once has the same bits either way.  The outputs of the fused-norm calls are compared with the oracle
-    on these (the rounding of the folded weight shifts the gates within their tolerance, which can exceed
-    atol on an output where state, shared and routed terms cancel)."""
-    import numpy as np
-    from paper_2503_15798_amd import workloads as wl
-    folded = wl.to_storage(wl.storage_to_f64(ln_w, dtype)[:, None] * wl.storage_to_f64(W_r, dtype), dtype)
-    return wl.to_storage(np.ones(d), dtype), folded
-
-
-def fold_gate_allowance(x, ln_w, W_r, eps, dtype, ref_g):
-    """Absolute allowance [T, N] on the gates of a fused-norm call against the layer with the UNFOLDED norm
-    weight: every element of the folded weight carries an independent rounding error of at most one unit
-    roundoff u of the storage type (standard deviation at most u |w| / sqrt 3), so logit j of a token
-    moves by a sum of d independent terms; six standard deviations of it, and |dg_j| <= 2 g_j max_j |dz_j|
-    to first order."""
-    import numpy as np
-    from paper_2503_15798_amd import workloads as wl
-    u = 2.0 ** -9 if dtype == wl.BF16 else 2.0 ** -24
-    x64 = wl.storage_to_f64(x, dtype)
-    xn = x64 / np.sqrt((x64 ** 2).mean(axis=1, keepdims=True) + eps)
-    wf = wl.storage_to_f64(ln_w, dtype)[:, None] * wl.storage_to_f64(W_r, dtype)
-    dz = 6.0 * u / np.sqrt(3.0) * np.sqrt((xn ** 2) @ (wf ** 2))
-    return 2.0 * dz.max(axis=1, keepdims=True) * ref_g
+def gathered_rows(tab_d, ids):
+    """(rows [U, N, d] storage array on the host, inv [T] int32) for the distinct in-range ids of a batch:
+    the rows of a device table that a forward over `ids` looks up, copied back by plain indexing (no
+    library call), and the position of every token's row among them.  Lets the oracle run on tables that
+    exist only on the device."""
+    import torch
+    ids = np.asarray(ids)
+    uniq, inv = np.unique(ids, return_inverse=True)
+    rows = tab_d[torch.from_numpy(uniq.astype(np.int64)).to(tab_d.device)]
+    dtype = wl.BF16 if rows.dtype == torch.bfloat16 else wl.F32
+    return to_host(rows, dtype), inv.astype(np.int32)

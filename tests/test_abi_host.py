@@ -24,7 +24,7 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert set(syms) == set(mb.EXPORTS)
     for s in syms:
         assert getattr(lib, s) is not None
-    assert mb.mole_version() == 1
+    assert mb.mole_version() == 2
     assert mb.mole_last_error() == ""
 
 
@@ -136,12 +136,13 @@ def test_offload_fetch_rejects_bad_arguments():
 
 
 def test_layer_forward_rejects_bad_arguments():
-    base = dict(table=A16, table_stride=0, ids=A16, slot=None, x=A16, ln_eps=1e-5, W_rn=A16,
+    base = dict(table=A16, table_stride=0, ids=A16, slot=None, x=A16, ln_w=A16, ln_eps=1e-5, W_r=A16,
                 shared_out=None, out=A16, act_stride=0, gates_dbg=None, rows_dbg=None, err_flag=None, L=1, T=4,
                 rows=10, d=64, N=4, dtype=mb.MOLE_BF16, flags=0, workspace=None, stream=0, workspace_bytes=0)
-    cases = [(dict(W_rn=None), mb.MOLE_EINVAL), (dict(ln_eps=-1.0), mb.MOLE_EINVAL),
+    cases = [(dict(W_r=None), mb.MOLE_EINVAL), (dict(ln_w=None), mb.MOLE_EINVAL), (dict(ln_eps=-1.0), mb.MOLE_EINVAL),
              (dict(ln_eps=float("nan")), mb.MOLE_EINVAL), (dict(x=None), mb.MOLE_EINVAL),
-             (dict(W_rn=A16 + 2), mb.MOLE_EINVAL), (dict(d=60), mb.MOLE_EUNSUPPORTED),
+             (dict(W_r=A16 + 2), mb.MOLE_EINVAL), (dict(ln_w=A16 + 2), mb.MOLE_EINVAL),
+             (dict(d=60), mb.MOLE_EUNSUPPORTED),
              (dict(flags=mb.MOLE_FLAG_DEDUP), mb.MOLE_EWORKSPACE)]
     for kw, status in cases:
         a = dict(base)
@@ -152,12 +153,16 @@ def test_layer_forward_rejects_bad_arguments():
     a = dict(base)
     a.update(T=0)
     mb.mole_layer_forward(**a)          # empty batch: MOLE_OK, nothing launched
-    for kw in (dict(W_r=None), dict(ln_w=None), dict(W_rn=None), dict(L=0), dict(d=0), dict(N=0), dict(dtype=4)):
-        a = dict(W_r=A16, ln_w=A16, W_rn=A16, L=1, d=64, N=4, dtype=mb.MOLE_BF16, stream=0)
-        a.update(kw)
+
+
+def test_set_tuning():
+    """Knobs are named after their environment variables; an unknown name or a negative value is refused."""
+    mb.mole_set_tuning("MOLE_FWD_SPLIT", 2)
+    mb.mole_set_tuning("MOLE_FWD_SPLIT", 0)
+    for name, value in (("MOLE_NO_SUCH_KNOB", 1), ("MOLE_FWD_WPB", -1)):
         with pytest.raises(mb.MoleError) as e:
-            mb.mole_fold_router_norm(**a)
-        assert e.value.status == mb.MOLE_EINVAL, kw
+            mb.mole_set_tuning(name, value)
+        assert e.value.status == mb.MOLE_EINVAL
 
 
 def test_offload_fetch_idmajor_rejects_bad_arguments():
@@ -180,12 +185,13 @@ def test_offload_fetch_idmajor_rejects_bad_arguments():
 
 
 def test_layer_forward_nf_rejects_bad_arguments():
-    base = dict(codes=A16, codes_stride=0, scales=A16, scales_stride=0, ids=A16, slot=None, x=A16, ln_eps=1e-5,
-                W_rn=A16, shared_out=None, out=A16, act_stride=0, gates_dbg=None, rows_dbg=None, err_flag=None, L=1,
+    base = dict(codes=A16, codes_stride=0, scales=A16, scales_stride=0, ids=A16, slot=None, x=A16, ln_w=A16,
+                ln_eps=1e-5, W_r=A16, shared_out=None, out=A16, act_stride=0, gates_dbg=None, rows_dbg=None, err_flag=None, L=1,
                 T=4, rows=10, d=64, N=4, bits=4, block=64, scale_bytes=4, flags=0, workspace=None, stream=0,
                 workspace_bytes=0)
     cases = [(dict(ln_eps=-1.0), mb.MOLE_EINVAL), (dict(ln_eps=float("nan")), mb.MOLE_EINVAL),
-             (dict(x=None), mb.MOLE_EINVAL), (dict(W_rn=None), mb.MOLE_EINVAL), (dict(bits=5), mb.MOLE_EUNSUPPORTED),
+             (dict(x=None), mb.MOLE_EINVAL), (dict(W_r=None), mb.MOLE_EINVAL), (dict(ln_w=None), mb.MOLE_EINVAL),
+             (dict(bits=5), mb.MOLE_EUNSUPPORTED),
              (dict(N=5), mb.MOLE_EUNSUPPORTED), (dict(x=A16 + 2), mb.MOLE_EINVAL),
              (dict(flags=mb.MOLE_FLAG_DEDUP), mb.MOLE_EWORKSPACE)]
     for kw, status in cases:

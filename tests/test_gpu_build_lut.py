@@ -49,11 +49,11 @@ def test_fp32_options(bias, norm, act):
     (100, 48, 80, 3, True, False, mb.MOLE_GELU_ERF),        # shape outside the MFMA tiles: plain path
 ])
 @pytest.mark.parametrize("hidden", [None, "f16", "split"])
-def test_bf16_build(monkeypatch, V, d, D, N, bias, norm, act, hidden):
+def test_bf16_build(tuning, V, d, D, N, bias, norm, act, hidden):
     """hidden: the format the hidden activation is carried in -- chosen by the library (fp16 here, the
     values are small) or forced to either variant."""
     if hidden:
-        monkeypatch.setenv("MOLE_BUILD_HIDDEN", hidden)
+        tuning("MOLE_BUILD_HIDDEN", {"f16": 1, "split": 2}[hidden])
     w = wl.scaled(wl.CONFIGS["offload410m"], V=V, d=d, D=D, N=N)
     ew = wl.expert_weights(w, bias=bias, norm=norm)
     got = run_build(w, ew, act=act)
@@ -64,7 +64,7 @@ def test_bf16_build(monkeypatch, V, d, D, N, bias, norm, act, hidden):
 
 
 @pytest.mark.parametrize("seed", range(10))
-def test_seeded_random_shapes(monkeypatch, seed):
+def test_seeded_random_shapes(tuning, seed):
     """V, d, D, N, biases, norm, activation and the hidden format drawn at random: MFMA path (both tile
     sizes, ragged row tiles) and plain path against the oracle."""
     rng = np.random.default_rng(5000 + seed)
@@ -76,9 +76,9 @@ def test_seeded_random_shapes(monkeypatch, seed):
     act = mb.MOLE_GELU_TANH if rng.integers(2) else mb.MOLE_GELU_ERF
     hidden = rng.choice(["", "f16", "split"])
     if hidden:
-        monkeypatch.setenv("MOLE_BUILD_HIDDEN", str(hidden))
+        tuning("MOLE_BUILD_HIDDEN", {"f16": 1, "split": 2}[str(hidden)])
     if rng.integers(2):
-        monkeypatch.setenv("MOLE_BUILD_SMALL_TILE", "1")
+        tuning("MOLE_BUILD_SMALL_TILE", "1")
     w = wl.scaled(wl.CONFIGS["offload410m"], V=V, d=d, D=D, N=N, name=f"build random seed {seed}: V{V} d{d} D{D} N{N}")
     ew = wl.expert_weights(w, bias=bias, norm=norm)
     got = run_build(w, ew, act=act)

@@ -65,10 +65,10 @@ def test_dedup_matches_oracle(T, V, dist):
 
 @pytest.mark.parametrize("T,V,dist", [(256, 50304, "zipf"), (16384, 50304, "zipf"), (17000, 50304, "uniform"),
                                       (20000, 50304, "zipf")])
-def test_generic_kernel(monkeypatch, T, V, dist):
+def test_generic_kernel(tuning, T, V, dist):
     """The kernel for batches beyond 16 tokens per thread (or V too large for the LDS staging area),
     forced on sizes the register-resident one would take, with and without its LDS staging."""
-    monkeypatch.setenv("MOLE_DEDUP_GENERIC", "1")
+    tuning("MOLE_DEDUP_GENERIC", "1")
     ids = wl.make_ids(T, V, seed=T + 1, dist=dist)
     ids[T // 2] = V + 1
     uniq, inv, U, err, plan = run_dedup(ids, V)
@@ -80,13 +80,13 @@ def test_generic_kernel(monkeypatch, T, V, dist):
 
 
 @pytest.mark.parametrize("seed", range(16))
-def test_seeded_random_batches(monkeypatch, seed):
+def test_seeded_random_batches(tuning, seed):
     """T, V, the id distribution, the share of out-of-range ids and the kernel drawn at random."""
     rng = np.random.default_rng(4000 + seed)
     T = int(rng.choice([1, 2, 63, 64, 65, 1023, 1024, 1025, 4097, 9000, 16384, 16385, 30000]))
     V = int(rng.choice([1, 2, 31, 32, 33, 1000, 50304, 200000]))
     if rng.integers(3) == 0:
-        monkeypatch.setenv("MOLE_DEDUP_GENERIC", "1")
+        tuning("MOLE_DEDUP_GENERIC", "1")
     ids = wl.make_ids(T, V, seed=seed, dist=str(rng.choice(["zipf", "uniform"])))
     bad = rng.random(T) < float(rng.choice([0.0, 0.01, 0.5]))
     ids = np.where(bad, rng.choice(np.array([-1, V, V + 7, 2 ** 31 - 1], np.int64), T), ids).astype(np.int32)

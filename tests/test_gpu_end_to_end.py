@@ -72,17 +72,15 @@ def test_built_table_reproduces_the_training_form_layer(name, kw):
 def training_listing_layer(ew, x, ln_w, W_r, shared, ids, dtype, eps):
     """The MoLE part of the training listing from the post-attention state, numpy fp64, one token at a
     time: post-attention RMSNorm -> router softmax; RMSNorm of the embedding -> every expert FFN;
-    residual + shared + gate-weighted sum.  Two storage steps are part of the reference because the
-    output is a cancellation of terms of size ~10 and their rounding shows at atol 1e-3: expert outputs
-    are rounded to the table's storage type, and the norm weight times the router weight is rounded to
-    the storage type (that product is what mole_fold_router_norm stores)."""
+    residual + shared + gate-weighted sum.  One storage step is part of the reference because the
+    output is a cancellation of terms of size ~10 and its rounding shows at atol 1e-3: expert outputs
+    are rounded to the table's storage type (the table is a stored re-parameterization)."""
     f = lambda a: wl.storage_to_f64(a, dtype)
     E, W1, W2, nw = f(ew["E"]), f(ew["W1"]), f(ew["W2"]), f(ew["norm_w"])
     x, ln_w, W_r, shared = f(x), f(ln_w), f(W_r), f(shared)
-    W_rn = f(wl.to_storage(W_r * ln_w[:, None], dtype))
     out = np.zeros_like(x)
     for t in range(x.shape[0]):
-        g = scipy.special.softmax((x[t] / np.sqrt(np.mean(x[t] ** 2) + eps)) @ W_rn)
+        g = scipy.special.softmax((x[t] / np.sqrt(np.mean(x[t] ** 2) + eps) * ln_w) @ W_r)
         e = E[ids[t]]
         e = e / np.sqrt(np.mean(e ** 2) + eps) * nw
         out[t] = x[t] + shared[t]
@@ -101,7 +99,7 @@ def training_listing_layer(ew, x, ln_w, W_r, shared, ids, dtype, eps):
 ])
 def test_built_table_reproduces_the_training_listing_layer(name, kw):
     """Both norms of the listing in play: the embedding norm inside mole_build_lut, the post-attention norm
-    (folded into the router weight) and the residual inside mole_layer_forward."""
+    and the residual inside mole_layer_forward."""
     import torch
     eps = 1e-5
     w = wl.scaled(wl.CONFIGS[name], **kw)
@@ -113,11 +111,9 @@ def test_built_table_reproduces_the_training_listing_layer(name, kw):
                       DT[w.dtype], mb.MOLE_GELU_ERF, ws)
     ids_d = torch.from_numpy(ids).cuda()
     x_d, lw_d, wr_d, sh_d = (to_dev(a, w.dtype) for a in (ni["x"], ni["ln_w"], li["W_r"], li["shared"]))
-    wrn_d = torch.empty_like(wr_d)
-    mb.mole_fold_router_norm(wr_d, lw_d, wrn_d, 1, w.d, w.N, DT[w.dtype])
     out_d = torch.empty_like(x_d)
     err_d = torch.zeros((1,), dtype=torch.int32, device="cuda")
-    mb.mole_layer_forward(lut, 0, ids_d, None, x_d, eps, wrn_d, sh_d, out_d, 0, None, None, err_d, 1, w.T, w.V, w.d,
+    mb.mole_layer_forward(lut, 0, ids_d, None, x_d, lw_d, eps, wr_d, sh_d, out_d, 0, None, None, err_d, 1, w.T, w.V, w.d,
                           w.N, DT[w.dtype])
     torch.cuda.synchronize()
     assert int(err_d.item()) == 0
@@ -132,8 +128,7 @@ def test_built_table_reproduces_the_training_listing_layer(name, kw):
     assert_close(got, ref, w.dtype, f"listing layer end to end ({w.name} {kw})", extra_atol=extra)
     # and through the oracle's two steps, with its table stored in the same type
     s64 = lambda a: wl.storage_to_f64(a, w.dtype)
-    W_rn = s64(wl.to_storage(s64(li["W_r"]) * s64(ni["ln_w"])[:, None], w.dtype))
-    ref2, *_ = oracle.layer_forward(tab, ids, s64(ni["x"]), np.ones(w.d), eps, W_rn, s64(li["shared"]))
+    ref2, *_ = oracle.layer_forward(tab, ids, s64(ni["x"]), s64(ni["ln_w"]), eps, s64(li["W_r"]), s64(li["shared"]))
     np.testing.assert_allclose(ref2, ref, rtol=1e-5 if w.dtype == wl.F32 else 1e-10,
                                atol=1e-5 if w.dtype == wl.F32 else 1e-11)
 
@@ -163,21 +158,30 @@ def test_plan_with_slot_and_staging():
 
 
 @pytest.mark.parametrize("N", [16, 5])
-def test_foreign_plan_is_refused_on_the_device(N):
-    """A workspace that mole_dedup_ids did not write for this T sets err_flag = 2 and writes nothing."""
+def test_foreign_plan_is_flagged_and_ignored(N):
+    """A workspace that mole_dedup_ids did not write for this T sets bit 1 of err_flag; the tokens are then
+    visited in their own order and the output is the one of the call without the flag (here, with an id
+    outside the table as well, both bits are reported)."""
     import torch
     w = wl.scaled(wl.CONFIGS["decode410m"], V=500, d=256, N=N, T=64, L=1)
     table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
-    ids_d = torch.from_numpy(ids).cuda()
-    h_d, wr_d = to_dev(li["h"], w.dtype), to_dev(li["W_r"], w.dtype)
-    out_d = torch.full_like(h_d, 7.0)
-    err = torch.zeros((1,), dtype=torch.int32, device="cuda")
-    junk = torch.zeros((mb.mole_dedup_workspace(w.T, w.V) // 4,), dtype=torch.int32, device="cuda")
-    mb.mole_lookup_forward(to_dev(table, w.dtype), ids_d, None, h_d, wr_d, None, None, out_d, None, None, err,
-                           w.T, w.V, w.d, w.N, DT[w.dtype], mb.MOLE_FLAG_DEDUP, junk)
-    torch.cuda.synchronize()
-    assert int(err.item()) == 2
-    assert (out_d.float() == 7.0).all()
+    for bad_id, flags_want in ((False, 2), (True, 3)):
+        ids = ids.copy()
+        if bad_id:
+            ids[5] = w.V
+        ids_d = torch.from_numpy(ids).cuda()
+        h_d, wr_d = to_dev(li["h"], w.dtype), to_dev(li["W_r"], w.dtype)
+        out_d = torch.full_like(h_d, 7.0)
+        err = torch.zeros((1,), dtype=torch.int32, device="cuda")
+        junk = torch.zeros((mb.mole_dedup_workspace(w.T, w.V) // 4,), dtype=torch.int32, device="cuda")
+        for runs in (0, mb.MOLE_FLAG_RUNS):
+            err.zero_()
+            mb.mole_lookup_forward(to_dev(table, w.dtype), ids_d, None, h_d, wr_d, None, None, out_d, None, None, err,
+                                   w.T, w.V, w.d, w.N, DT[w.dtype], mb.MOLE_FLAG_DEDUP | runs, junk)
+            torch.cuda.synchronize()
+            assert int(err.item()) == flags_want
+            ref, _, _, _ = oracle.lookup_forward(table, ids, li["h"], li["W_r"])
+            assert_close(wl.storage_to_f64(to_host(out_d, w.dtype), w.dtype), ref, w.dtype, "foreign plan ignored")
 
 
 def test_hip_graph_replay_matches_eager():

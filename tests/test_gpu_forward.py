@@ -6,7 +6,7 @@ import pytest
 import oracle
 from paper_2503_15798_amd import binding as mb
 from paper_2503_15798_amd import workloads as wl
-from helpers import DT, assert_close, to_dev, to_host
+from helpers import DT, assert_close, gathered_rows, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -104,10 +104,10 @@ def test_bf16_shapes(d, N, T, V, residual):
 @pytest.mark.parametrize("wpb", ["4", "8"])
 @pytest.mark.parametrize("d,N,T,V", [(1024, 16, 333, 4096), (768, 16, 64, 4096), (1544, 8, 50, 300), (1024, 32, 203, 2048),
                                      (1024, 64, 41, 100)])
-def test_launch_variants(monkeypatch, split, wpb, d, N, T, V):
+def test_launch_variants(tuning, split, wpb, d, N, T, V):
     """Both item granularities (whole token / one 512-column chunk) and both workgroup widths."""
-    monkeypatch.setenv("MOLE_FWD_SPLIT", split)
-    monkeypatch.setenv("MOLE_FWD_WPB", wpb)
+    tuning("MOLE_FWD_SPLIT", split)
+    tuning("MOLE_FWD_WPB", wpb)
     w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, T=T, L=1, name=f"split{split} wpb{wpb} d{d} N{N}")
     table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
     ids = ids.copy()
@@ -138,7 +138,7 @@ def test_routed_term_alone():
 
 
 @pytest.mark.parametrize("seed", range(24))
-def test_seeded_random_shapes(monkeypatch, seed):
+def test_seeded_random_shapes(tuning, seed):
     """Shapes drawn from the documented ranges (d a multiple of 8 up to 2304, any N up to 64, small T and V),
     with a random choice of residual, plan, out-of-range ids and of the launch switches: every dispatch
     path (streaming, chunk items, run kernel, generic) against the oracle."""
@@ -149,8 +149,8 @@ def test_seeded_random_shapes(monkeypatch, seed):
     V = int(rng.integers(max(2, T // 8), 400))
     dedup, residual = bool(rng.integers(2)), bool(rng.integers(2))
     for var in ("MOLE_FWD_SPLIT", "MOLE_FWD_NTA", "MOLE_FWD_RUN"):
-        monkeypatch.setenv(var, str(int(rng.integers(1, 3))))
-    monkeypatch.setenv("MOLE_FWD_WPB", str(int(rng.choice([4, 8]))))
+        tuning(var, str(int(rng.integers(1, 3))))
+    tuning("MOLE_FWD_WPB", str(int(rng.choice([4, 8]))))
     w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, T=T, L=1, ids=str(rng.choice(["zipf", "uniform"])),
                   name=f"random seed {seed}: d{d} N{N} T{T} V{V} dedup{int(dedup)} res{int(residual)}")
     table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
@@ -303,8 +303,8 @@ def test_heavy_repeats_with_plan():
     (2048, 32, 40, 10, "uniform"),     # N = 32 with a router weight of 132 KB: one workgroup per CU
     (4096, 32, 12, 8, "uniform"),      # too large for the run kernel's LDS: falls back to the generic path
 ])
-def test_run_kernel_shapes(monkeypatch, d, N, T, V, dist):
-    monkeypatch.setenv("MOLE_FWD_RUN", "1")
+def test_run_kernel_shapes(tuning, d, N, T, V, dist):
+    tuning("MOLE_FWD_RUN", "1")
     w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, T=T, L=1, ids=dist, name=f"run d{d} N{N} T{T} V{V}")
     table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
     li["W_r"] = wl.to_storage(wl.storage_to_f64(li["W_r"], w.dtype) * 5.0, w.dtype)
@@ -315,9 +315,9 @@ def test_run_kernel_shapes(monkeypatch, d, N, T, V, dist):
         check_against_oracle(w, table, ids, li, residual=residual, dedup=True)
 
 
-def test_run_kernel_saturated_router_returns_the_row_exactly(monkeypatch):
+def test_run_kernel_saturated_router_returns_the_row_exactly(tuning):
     """A gate of exactly 1 splits into hi = 1, lo = 0, and 0 into 0 + 0: the row comes back bit for bit."""
-    monkeypatch.setenv("MOLE_FWD_RUN", "1")
+    tuning("MOLE_FWD_RUN", "1")
     N = 16
     w = wl.scaled(wl.CONFIGS["decode410m"], V=24, d=1024, N=N, T=96, L=1, ids="uniform")
     table, ids = wl.random_table(w), wl.token_ids(w)
@@ -332,9 +332,9 @@ def test_run_kernel_saturated_router_returns_the_row_exactly(monkeypatch):
                                   wl.storage_to_f64(table, w.dtype)[ids, star, :])
 
 
-def test_run_kernel_with_slot_indirection(monkeypatch):
+def test_run_kernel_with_slot_indirection(tuning):
     """Offloaded mode: the plan orders tokens by id, the rows come from the compacted staging table."""
-    monkeypatch.setenv("MOLE_FWD_RUN", "1")
+    tuning("MOLE_FWD_RUN", "1")
     w = wl.scaled(wl.CONFIGS["decode410m"], V=300, d=1024, N=16, T=200, L=1)
     table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
     uniq, inv = np.unique(ids, return_inverse=True)
@@ -387,68 +387,101 @@ def test_two_runs_are_bit_identical():
         np.testing.assert_array_equal(a["out"], b["out"])
 
 
-# ---- full benchmark sizes, in the launch configuration the benchmark times ---------------------------
-def _sampled_check(w, tab_d, ids, lis_d, out, layer, sample, torch):
-    """Oracle on a sample of tokens: their rows are copied back with plain indexing."""
-    sid = ids[sample]
-    rows_host = to_host(tab_d[torch.from_numpy(sid.astype(np.int64)).cuda()], w.dtype)       # [S,N,d]
-    li = {k: to_host(v[layer][torch.from_numpy(sample).cuda()] if k != "W_r" else v[layer], w.dtype)
-          for k, v in lis_d.items()}
-    ref, _, _, _ = oracle.lookup_forward(rows_host, np.arange(len(sample), dtype=np.int32), li["h"], li["W_r"],
-                                         li["shared"])
-    assert_close(wl.storage_to_f64(out[sample], w.dtype), ref, w.dtype, f"{w.name} layer {layer} sample")
+# ---- full benchmark sizes, in the launch configuration the benchmark times: WHOLE outputs ---------------
+# The tables exist only on the device (up to 39.6 GB); the rows a batch looks up are copied back by plain
+# indexing and the oracle runs on all tokens of all layers.
+def _plan_for(torch, ids_d, T, V, err_d):
+    plan = torch.empty((mb.mole_dedup_workspace(T, V) // 4,), dtype=torch.int32, device="cuda")
+    uq, iv = torch.empty_like(ids_d), torch.empty_like(ids_d)
+    mb.mole_dedup_ids(ids_d, T, V, uq, iv, torch.zeros_like(err_d), err_d, plan)
+    return plan
 
 
-@pytest.mark.parametrize("name,dedup", [("prefill410m", False), ("prefill410m", True),
-                                        ("prefill410m_uniform", True), ("decode160m", False),
-                                        ("decode1b_4e", False), ("decode1b_4e", True), ("decode410m_n2", False),
-                                        ("decode410m_n4", True), ("decode410m_n8", False)])
-def test_full_size_single_layer_sampled(name, dedup):
+def _whole_output_check(w, tabs_d, ids, lis, out, what):
+    """out [L, T, d] storage array against the oracle, every layer, every token."""
+    for l in range(w.L):
+        rows, inv = gathered_rows(tabs_d[l], ids)
+        ref, _, _, err = oracle.lookup_forward(rows, inv, lis[l]["h"], lis[l]["W_r"], lis[l]["shared"])
+        assert err == 0
+        assert_close(wl.storage_to_f64(out[l], w.dtype), ref, w.dtype, f"{what} layer {l}")
+
+
+@pytest.mark.parametrize("name,mode", [
+    ("prefill410m", "plain"), ("prefill410m", "plan"), ("prefill410m", "plan+runs"),
+    ("prefill410m_uniform", "plain"), ("prefill410m_uniform", "plan"),
+    ("decode1b_4e", "plain"), ("decode1b_4e", "plan"), ("decode410m_n2", "plain"), ("decode410m_n4", "plan"),
+    ("decode410m_n8", "plain")])
+def test_full_size_single_layer(name, mode):
+    """One layer of the benchmark shapes through the single-layer entry point: all T tokens (16384 for the
+    prefills, whose 3.3 GB table puts row offsets beyond 32 bits) against the oracle."""
     torch = torch_mod()
-    w = wl.CONFIGS[name]
+    w = wl.scaled(wl.CONFIGS[name], L=1)
     tab_d = wl.device_table(w, 0, "cuda")
     if name.startswith("prefill"):
         assert tab_d.numel() * 2 > 2 ** 31                           # byte offsets beyond 32 bits
-    ids = wl.token_ids(w)
-    li = wl.layer_inputs(w)
-    got = run_forward(w, None, ids, li, dedup=dedup, table_dev=tab_d, want_dbg=True)
+    ids, li = wl.token_ids(w), wl.layer_inputs(w)
+    got = run_forward(w, None, ids, li, dedup=mode != "plain", runs=mode == "plan+runs", table_dev=tab_d, want_dbg=True)
     np.testing.assert_array_equal(got["rows"], ids)
     assert got["err"] == 0
-    rng = np.random.default_rng(1)
-    sample = np.unique(np.concatenate([rng.integers(0, w.T, 48), [0, w.T - 1], np.argsort(ids)[-4:]]))
-    lis_d = {k: to_dev(v, w.dtype)[None] for k, v in li.items() if k != "residual"}
-    _sampled_check(w, tab_d, ids, lis_d, got["out"], 0, sample, torch)
-    # properties that hold at any size: gates are a distribution; equal (id, h) would give equal rows
-    assert np.abs(got["gates"].sum(axis=1) - 1.0).max() < 1e-5 and (got["gates"] >= 0).all()
+    _whole_output_check(w, tab_d[None], ids, [li], got["out"][None], f"{name} ({mode})")
+    ref_g = oracle.gates(li["h"], li["W_r"])
+    assert_close(got["gates"].astype(np.float64), ref_g, wl.BF16, f"{name} gates")
 
 
-@pytest.mark.parametrize("dedup", [False, True])
-def test_full_size_decode410m_all_layers_sampled(dedup):
-    """24 layers x 256 tokens in one launch over a 39.6 GB table set."""
+@pytest.fixture(scope="module")
+def tables_410m():
+    """The 24 tables of the 410M decode configuration (39.6 GB), generated once for the tests below."""
     torch = torch_mod()
     w = wl.CONFIGS["decode410m"]
     tabs = torch.empty((w.L, w.V, w.N, w.d), dtype=torch.bfloat16, device="cuda")
     for l in range(w.L):
         wl.device_table(w, l, "cuda", out=tabs[l])
-    ids = wl.token_ids(w)
-    lis = [wl.layer_inputs(w, l) for l in range(w.L)]
+    yield tabs
+    del tabs
+    torch.cuda.empty_cache()
+
+
+def _layers_step(w, tabs, ids, lis, plan_mode):
+    """One launch of the layer-batched entry point as bench.py issues it; returns out [L, T, d] on the host."""
+    torch = torch_mod()
     lis_d = {k: to_dev(np.stack([li[k] for li in lis]), w.dtype) for k in ("h", "W_r", "shared")}
     ids_d = torch.from_numpy(ids).cuda()
     out_d = torch.full_like(lis_d["h"], float("nan"))
     err_d = torch.zeros((1,), dtype=torch.int32, device="cuda")
     flags, plan = 0, None
-    if dedup:
-        plan = torch.empty((mb.mole_dedup_workspace(w.T, w.V) // 4,), dtype=torch.int32, device="cuda")
-        uq, iv = torch.empty_like(ids_d), torch.empty_like(ids_d)
-        mb.mole_dedup_ids(ids_d, w.T, w.V, uq, iv, torch.zeros_like(err_d), err_d, plan)
+    if plan_mode:
+        plan = _plan_for(torch, ids_d, w.T, w.V, err_d)
         flags = mb.MOLE_FLAG_DEDUP
     mb.mole_lookup_forward_layers(tabs, w.V * w.N * w.d, ids_d, None, lis_d["h"], lis_d["W_r"], lis_d["shared"],
                                   None, out_d, w.T * w.d, None, None, err_d, w.L, w.T, w.V, w.d, w.N,
                                   DT[w.dtype], flags, plan)
     torch.cuda.synchronize()
     assert int(err_d.item()) == 0
-    out = to_host(out_d, w.dtype)
-    assert not np.isnan(wl.storage_to_f64(out, w.dtype)).any()
-    sample = np.unique(np.concatenate([np.random.default_rng(2).integers(0, w.T, 24), [0, w.T - 1]]))
-    for layer in (0, 11, 23):
-        _sampled_check(w, tabs[layer], ids, lis_d, out[layer], layer, sample, torch)
+    return to_host(out_d, w.dtype)
+
+
+@pytest.mark.parametrize("T", [1, 32, 256])
+@pytest.mark.parametrize("plan_mode", [False, True])
+def test_full_size_decode410m_all_layers(tables_410m, T, plan_mode):
+    """24 layers x T tokens in one launch over the 39.6 GB table set, for the three batch sizes of the decode
+    configuration (each takes another dispatch: chunk items in wide workgroups at T = 1 and 32, whole tokens
+    at 256): every output element of every layer against the oracle."""
+    w = wl.scaled(wl.CONFIGS["decode410m"], T=T, name=f"decode410m T={T}")
+    ids = wl.token_ids(w)
+    lis = [wl.layer_inputs(w, l) for l in range(w.L)]
+    out = _layers_step(w, tables_410m, ids, lis, plan_mode)
+    _whole_output_check(w, tables_410m, ids, lis, out, f"{w.name} plan={plan_mode}")
+
+
+@pytest.mark.parametrize("plan_mode", [False, True])
+def test_full_size_decode160m_all_layers(plan_mode):
+    """The 160M decode step as bench.py launches it: 12 layers x 64 tokens, d = 768 (1.5 chunks), one launch."""
+    torch = torch_mod()
+    w = wl.CONFIGS["decode160m"]
+    tabs = torch.empty((w.L, w.V, w.N, w.d), dtype=torch.bfloat16, device="cuda")
+    for l in range(w.L):
+        wl.device_table(w, l, "cuda", out=tabs[l])
+    ids = wl.token_ids(w)
+    lis = [wl.layer_inputs(w, l) for l in range(w.L)]
+    out = _layers_step(w, tabs, ids, lis, plan_mode)
+    _whole_output_check(w, tabs, ids, lis, out, f"decode160m plan={plan_mode}")

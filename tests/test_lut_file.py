@@ -137,6 +137,14 @@ def test_errors(tmp_path):
     with pytest.raises(mb.MoleError) as e:
         mb.mole_lut_file_open(badmagic)
     assert e.value.status == mb.MOLE_EINVAL
+    # a crafted header whose size product wraps around 2^64 back to the real payload size: L * V * N * d * 2 =
+    # 64 * (10 + 2^58) = 640 + 2^64.  It must be refused, not mapped as a table of 2^58 rows.
+    wrap = str(tmp_path / "wrap.molelut")
+    assert struct.unpack_from("<q", raw, 24)[0] == V
+    open(wrap, "wb").write(raw[:24] + struct.pack("<q", V + (1 << 58)) + raw[32:])
+    with pytest.raises(mb.MoleError) as e:
+        mb.mole_lut_file_open(wrap)
+    assert e.value.status == mb.MOLE_EINVAL and "too large" in e.value.message
     short = str(tmp_path / "short.molelut")
     open(short, "wb").write(raw[:100])
     with pytest.raises(mb.MoleError) as e:
