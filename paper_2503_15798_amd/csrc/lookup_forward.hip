@@ -78,10 +78,13 @@ void fwd_bf16_stream_kernel(FwdArgs a)
     extern __shared__ uint4 smem[];
     constexpr int NR = N < 4 ? 4 : N;   // experts the router is computed for (N = 2 is padded to 4)
     constexpr int LPJ = 64 / NR;        // lanes per expert after the fold
-    constexpr int R = N > 16 ? (NORM && N == 32 ? 8 : 16) : N;  // row registers: above 16 experts a chunk's rows pass through in parts
+    // row registers: above 16 experts a chunk's rows pass through in parts of 16 (of 8 in the N = 32 norm variant,
+    // whose router keeps more values live: with 16 it spills 40 to 80 registers and takes 290 instead of 235 us on
+    // the 16384-token prefill)
+    constexpr int R = N > 16 ? (NORM && N == 32 ? 8 : 16) : N;
     constexpr int H = N / R;
-    // NORM: the state is also the residual; its two pieces stay in registers through the combine except in
-    // the variant that sits at its 128-register budget (N = 16 with non-temporal loads), which reads them again
+    // NORM: the state is also the residual; below 16 experts its two pieces stay in registers through the
+    // combine, from 16 experts on (kernels at their 128-register budget) they are read again (an L2 hit)
     constexpr bool HOLD_X = NORM && N < 16;
     const int d = a.d;
     const int kgroups = d >> 3;
