@@ -182,6 +182,27 @@ mole_status mole_lookup_forward_layers(const void *table, int64_t table_stride,
                                        const void *workspace, size_t workspace_bytes,
                                        void *hip_stream);
 
+/* For callers that cannot allocate device memory and so have no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The same result as
+ *     mole_dedup_ids(ids, T, V, ...) followed by mole_lookup_forward(..., MOLE_FLAG_DEDUP, plan)
+ * (bit for bit the output of mole_lookup_forward without flags, rows read in id order), with the plan,
+ * the distinct ids, the inverse map and their count kept in a fixed array of 393 KiB in device memory
+ * that belongs to the library: each GPU the library runs on holds one copy until the process ends.
+ * The call allocates nothing, on the device or through any library, and never synchronises.
+ *   T <= MOLE_NOALLOC_MAX_T, else MOLE_EUNSUPPORTED (then use the two calls with a workspace of your own);
+ *   V <= 524288 (as mole_dedup_ids); no slot indirection and no debug outputs; other arguments and
+ *   err_flag as in mole_lookup_forward.
+ * All calls on one GPU share that GPU's array, and the array keeps the last call's contents (every word
+ * a call reads it has written itself first): calls that overlap in time on one GPU -- from several
+ * streams or host threads -- race and must be serialised by the caller. */
+#define MOLE_NOALLOC_MAX_T 16384
+mole_status mole_lookup_forward_noalloc(const void *table, const int32_t *ids,
+                                        const void *h, const void *W_r,
+                                        const void *shared_out, const void *residual,
+                                        void *out, int32_t *err_flag,
+                                        int T, int64_t V, int d, int N, mole_dtype dtype,
+                                        void *hip_stream);
+
 /* The MoLE part of a decoder layer from the state AFTER attention, with the post-attention RMSNorm
  * and the residual inside the kernel (inference listing, "Shared Expert" / "Routed Expert"):
  *     hn[t,:]  = x[t,:] / sqrt(mean_k x[t,k]^2 + ln_eps) * ln_w

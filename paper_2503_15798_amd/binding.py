@@ -21,6 +21,7 @@ MOLE_GELU_ERF, MOLE_GELU_TANH = 0, 1
 MOLE_FLAG_DEDUP = 1
 MOLE_FLAG_RUNS = 2
 MOLE_LAYOUT_LAYER_MAJOR, MOLE_LAYOUT_ID_MAJOR = 0, 1
+MOLE_NOALLOC_MAX_T = 16384
 
 _STATUS_NAMES = {0: "MOLE_OK", 1: "MOLE_EINVAL", 2: "MOLE_EUNSUPPORTED", 3: "MOLE_EWORKSPACE", 4: "MOLE_EHIP",
                  5: "MOLE_EIO"}
@@ -32,7 +33,7 @@ EXPORTS = ("mole_last_error", "mole_version", "mole_build_lut_workspace", "mole_
            "mole_lut_file_create", "mole_lut_file_open", "mole_lut_file_payload", "mole_lut_file_write_layer",
            "mole_lut_file_read_rows", "mole_lut_file_close", "mole_nf_codebook", "mole_nf_codes_bytes",
            "mole_nf_scales_bytes", "mole_quantize_lut", "mole_lookup_forward_nf", "mole_offload_fetch_nf",
-           "mole_layer_forward_nf")
+           "mole_layer_forward_nf", "mole_lookup_forward_noalloc")
 
 
 class LutDesc(ctypes.Structure):
@@ -81,6 +82,8 @@ def lib() -> ctypes.CDLL:
     L.mole_lookup_forward_layers.restype = c_i32
     L.mole_lookup_forward_layers.argtypes = ([c_void, c_i64] + [c_void] * 7 + [c_i64] + [c_void] * 3 +
                                              [c_i32, c_i32, c_i64, c_i32, c_i32, c_i32, c_u, c_void, c_sz, c_void])
+    L.mole_lookup_forward_noalloc.restype = c_i32
+    L.mole_lookup_forward_noalloc.argtypes = [c_void] * 8 + [c_i32, c_i64, c_i32, c_i32, c_i32, c_void]
     L.mole_set_tuning.restype = c_i32
     L.mole_set_tuning.argtypes = [ctypes.c_char_p, c_i32]
     L.mole_layer_forward.restype = c_i32
@@ -206,6 +209,13 @@ def mole_lookup_forward_layers(table, table_stride: int, ids, slot, h, W_r, shar
                                             _ptr(shared_out), _ptr(residual), _ptr(out), act_stride,
                                             _ptr(gates_dbg), _ptr(rows_dbg), _ptr(err_flag), L, T, rows, d, N,
                                             dtype, flags, _ptr(workspace), wb, _stream(stream)))
+
+
+def mole_lookup_forward_noalloc(table, ids, h, W_r, shared_out, residual, out, err_flag, T: int, V: int, d: int, N: int,
+                                dtype: int, stream=None) -> None:
+    _check(lib().mole_lookup_forward_noalloc(_ptr(table), _ptr(ids), _ptr(h), _ptr(W_r), _ptr(shared_out),
+                                             _ptr(residual), _ptr(out), _ptr(err_flag), T, V, d, N, dtype,
+                                             _stream(stream)))
 
 
 def mole_set_tuning(name: str, value: int) -> None:
