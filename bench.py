@@ -8,11 +8,17 @@ headline workload (410M-shaped decode: 24 MoLE layers x 256 tokens, N=16, d=1024
 resident in HBM, Zipf(1.1) token ids) that is router + softmax + row gather + gate-weighted sum +
 shared-FFN add for all 24 layers.  Inputs are resident in HBM when the clock starts; 16
 pre-generated id batches rotate so that successive steps do not replay identical rows.
-The script prints ONE JSON line.  Besides the contract fields it carries
-  roofline      the forward kernel against the HBM roofline (algorithmic bytes / launch duration)
+The script prints ONE JSON line (kept under 8 KB).  Besides the contract fields it carries
+  roofline      the forward kernel against the HBM roofline: `achieved` / `frac` on the algorithmic bytes
+                (every token's own rows) over the launch duration, `traffic` / `traffic_frac` on the
+                counter-measured bytes (rocprofv3 summary under profiles/, with the hash of the kernel
+                sources it was taken on), `moved_frac` on the bytes that have to move (each distinct id
+                once), and `also`: the same fractions for the other configurations (prefill with uniform
+                and Zipf ids, with the plan; small decode batches; offload fetch against the host link; LUT
+                build against the MFMA peak)
   cpu_baseline  the fp64 CPU oracle timed on the host cores on the same workload
-  other         the remaining workloads (prefill, other batch sizes, dedup variants, offloaded
-                mode, LUT build), each with its own rates.
+  other_ms      milliseconds of every other workload and variant; --full adds their complete entries
+                under `other`.
 """
 from __future__ import annotations
 
@@ -46,6 +52,7 @@ def parse_args():
     ap.add_argument("--runs", action="store_true",
                     help="with --plan: also pass MOLE_FLAG_RUNS (tokens with equal ids summed together on the matrix pipe)")
     ap.add_argument("--no-extras", action="store_true", help="only the headline workload")
+    ap.add_argument("--full", action="store_true", help="also print the complete entries of the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--only-build", action="store_true",
                     help="time mole_build_lut on one 410M layer and print its entry alone (for profiling)")
@@ -216,22 +223,40 @@ def launch_spread(torch, stream, step, n=200):
 def rates(w, acc, ms, distinct=None):
     """tokens/s and GB/s for a forward over all layers of workload w taking `ms`."""
     alg = acc.forward_bytes_per_token(w.d, w.N, w.elem_bytes) * w.T * w.L
+    # the algorithmic rate counts every token's own rows, so with repeated ids it can exceed what HBM delivers:
+    # it is a rate, never a fraction of the peak; the fraction is taken on the bytes that have to move
     out = {"ms": round(ms, 5), "layer_tokens_per_s": w.T * w.L / (ms * 1e-3), "tokens_per_s": w.T / (ms * 1e-3),
-           "algorithmic_GBps": alg / (ms * 1e-3) / 1e9,
-           "algorithmic_frac_of_hbm_peak": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+           "algorithmic_GBps": alg / (ms * 1e-3) / 1e9}
     if distinct is not None:
         moved = w.L * acc.forward_bytes_moved(w.T, int(round(distinct)), w.d, w.N, w.elem_bytes)
         out["distinct_ids"] = distinct
+        out["moved_bytes"] = moved
         out["moved_GBps"] = moved / (ms * 1e-3) / 1e9
+        out["moved_frac_of_hbm_peak"] = out["moved_GBps"] / HBM_PEAK_GBS
     return out
 
 
+KERNEL_SOURCES = ("lookup_forward.hip", "fwd_common.h", "mole_internal.h")
+
+
+def kernel_source_hash():
+    """Hash of the forward kernels' sources: a counter summary under profiles/ records the hash it was taken
+    on, so a summary of an older kernel is recognised as such."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2503_15798_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def read_traffic(kernel_tag):
-    """HBM bytes per launch of the forward kernel from the committed rocprofv3 counter summary
-    (profiles/<tag>_hbm_traffic.txt: key=value lines), or None if there is none."""
+    """(HBM bytes per launch, provenance) of the forward kernel from the committed rocprofv3 counter
+    summary (profiles/<tag>_hbm_traffic.txt: key=value lines); (None, None) if there is none.  Counters
+    cannot be read inside this run; `current` says whether the summary was taken on today's kernel sources."""
     path = os.path.join(ROOT, "profiles", f"{kernel_tag}_hbm_traffic.txt")
     if not os.path.exists(path):
-        return None
+        return None, None
     kv = {}
     for line in open(path):
         line = line.split("#")[0].strip()
@@ -239,9 +264,13 @@ def read_traffic(kernel_tag):
             k, v = line.split("=", 1)
             kv[k.strip()] = v.strip()
     try:
-        return float(kv["hbm_bytes_per_launch"])
+        traffic = float(kv["hbm_bytes_per_launch"])
     except (KeyError, ValueError):
-        return None
+        return None, None
+    sha = kv.get("kernel_source_sha")
+    return traffic, {"file": os.path.relpath(path, ROOT), "kernel_source_sha": sha,
+                     "current": sha == kernel_source_hash(),
+                     "counters": "FETCH_SIZE x 2.0 + WRITE_SIZE (L2 misses and write-backs: Infinity Cache hits included)"}
 
 
 def cpu_baseline(L, torch, wl, steps=21):
@@ -342,11 +371,14 @@ def main():
     # the kernel the launcher picks for this call (--runs passes MOLE_FLAG_RUNS: the run kernel for N <= 32)
     kernel = "fwd_bf16_run_kernel" if args.plan and args.runs and w.N <= 32 else "fwd_bf16_stream_kernel"
     kernel_tag = f"{kernel[:-7]}_{w.name}" + ("_plan" if args.plan else "")
+    traffic, traffic_src = read_traffic(kernel_tag)
+    moved_bytes = w.L * acc.forward_bytes_moved(w.T, int(round(distinct)), w.d, w.N, w.elem_bytes)
     roofline = {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(kernel_tag),
-                "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": ms_kernel,
-                "moved_GBps": w.L * acc.forward_bytes_moved(w.T, int(round(distinct)), w.d, w.N, w.elem_bytes)
-                / (ms_kernel * 1e-3) / 1e9}
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                "traffic_frac": None if traffic is None else traffic / (ms_kernel * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "traffic_source": traffic_src,
+                "algorithmic_bytes_per_launch": alg_bytes, "moved_bytes_per_launch": moved_bytes,
+                "moved_frac": moved_bytes / (ms_kernel * 1e-3) / 1e9 / HBM_PEAK_GBS, "kernel_ms": ms_kernel}
 
     roofline["launch_us"] = launch_spread(torch, stream, step)
 
@@ -359,6 +391,7 @@ def main():
     other = {}
     if not args.no_extras:
         other = extras(args, torch, mb, wl, acc, stream, L)
+        roofline["also"] = also_list(other)
     if args.calibrate_copy:
         a = torch.empty((1 << 30,), dtype=torch.uint8, device="cuda")
         b = torch.empty_like(a)
@@ -383,9 +416,59 @@ def main():
                    "algorithmic_GBps": head["algorithmic_GBps"], "moved_GBps": head["moved_GBps"]},
         "roofline": roofline,
         "cpu_baseline": cpu,
-        "other": other,
+        "other_ms": {k: round(v["ms"] if isinstance(v, dict) else v, 5) for k, v in other.items()
+                     if not isinstance(v, dict) or "ms" in v},
     }
+    if args.full:
+        line["other"] = other
     print(json.dumps(line))
+
+
+def also_list(o):
+    """The other configurations against their rooflines, in the shape of `roofline` (short: the driver keeps
+    this part of the line).  HBM entries are taken on the bytes that have to move (each distinct id's rows
+    once + activations); with uniform ids and no plan nearly every token has its own rows and the
+    algorithmic bytes are what the counters read."""
+    out = []
+
+    def hbm(name, what, key="moved_GBps"):
+        e = o.get(name)
+        if isinstance(e, dict) and key in e:
+            out.append({"workload": name, "what": what, "bound": "hbm", "achieved": round(e[key], 1),
+                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(e[key] / HBM_PEAK_GBS, 4),
+                        "us": round(e["ms"] * 1e3, 2), "bytes": key.split("_")[0]})
+    hbm("prefill410m_uniform", "N=32, 16384 tokens, uniform ids (no-reuse control), no plan", "algorithmic_GBps")
+    hbm("prefill410m_uniform_forward_with_plan", "the same with the plan of mole_dedup_ids")
+    hbm("prefill410m_uniform_dedup_plus_forward", "the same, dedup inside the timed step")
+    hbm("prefill410m", "N=32, 16384 tokens, Zipf ids, no plan")
+    hbm("prefill410m_forward_with_plan", "the same with the plan")
+    hbm("prefill410m_dedup_plus_forward", "the same, dedup inside the timed step")
+    hbm("decode410m_forward_with_plan", "headline step with the plan")
+    hbm("decode410m_dedup_plus_forward", "headline step, dedup inside the timed step")
+    hbm("decode160m", "12 layers x 64 tokens, d=768 (latency regime)")
+    hbm("decode410m_t32", "24 layers x 32 tokens (latency regime)")
+    hbm("decode410m_t1", "24 layers x 1 token (latency regime)")
+    hbm("decode1b_4e", "16 layers x 256 tokens, d=2048, N=4")
+    for tag in ("nf4", "nf3"):
+        e = o.get(f"decode410m_{tag}")
+        if isinstance(e, dict):
+            out.append({"workload": f"decode410m_{tag}", "what": "dequantising forward, on its own (smaller) byte count",
+                        "bound": "hbm", "achieved": round(e["algorithmic_GBps"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": round(e["algorithmic_GBps"] / HBM_PEAK_GBS, 4), "us": round(e["ms"] * 1e3, 2),
+                        "bytes": "algorithmic"})
+    e = o.get("offload410m")
+    if isinstance(e, dict) and "fetch_GBps" in e:
+        out.append({"workload": "offload410m", "what": "fetch of the distinct rows of 24 layers from pinned host memory",
+                    "bound": "host link", "achieved": round(e["fetch_GBps"], 2), "peak": HOST_LINK_GBS, "unit": "GB/s",
+                    "frac": round(e["fetch_GBps"] / HOST_LINK_GBS, 4), "us": round(e["fetch_only_ms"] * 1e3, 1),
+                    "step_us": round(e["ms"] * 1e3, 1)})
+    e = o.get("build_lut_410m_layer")
+    if isinstance(e, dict) and "algorithmic_TFLOPs" in e:
+        out.append({"workload": "build_lut_410m_layer", "what": "mole_build_lut, one 410M layer (16 experts, V=50304)",
+                    "bound": "mfma", "achieved": round(e["algorithmic_TFLOPs"], 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(e["algorithmic_TFLOPs"] / MFMA_BF16_PEAK_TFLOPS, 4),
+                    "us": round(e["ms"] * 1e3, 1)})
+    return out
 
 
 def extras(args, torch, mb, wl, acc, stream, L):
@@ -530,8 +613,7 @@ def norm_entries(LL, acc, torch, stream, steps, warm, name):
         alg = (w.N * w.d * w.elem_bytes + streams * w.d * w.elem_bytes + 4) * w.T * w.L
         res[f"{name}_{tag}"] = {"ms": round(ms, 5), "layer_tokens_per_s": w.T * w.L / (ms * 1e-3),
                                 "activation_streams": streams, "algorithmic_bytes_per_launch": alg,
-                                "algorithmic_GBps": alg / (ms * 1e-3) / 1e9,
-                                "algorithmic_frac_of_hbm_peak": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+                                "algorithmic_GBps": alg / (ms * 1e-3) / 1e9}
     del LL.x, LL.ln_w
     return res
 
@@ -546,7 +628,7 @@ def nf_entry(LL, acc, torch, stream, steps, warm, bits, block, sbytes):
     alg = acc.nf_forward_bytes_per_token(w.d, w.N, bits, block, sbytes) * w.T * w.L
     res = {"bits": bits, "block": block, "scale_bytes": sbytes, "ms": ms,
            "layer_tokens_per_s": w.T * w.L / (ms * 1e-3), "algorithmic_bytes_per_launch": alg,
-           "algorithmic_GBps": alg / (ms * 1e-3) / 1e9, "algorithmic_frac_of_hbm_peak": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+           "algorithmic_GBps": alg / (ms * 1e-3) / 1e9,
            "table_bytes": acc.nf_table_bytes(w.V, w.N, w.d, bits, block, sbytes) * w.L,
            "table_ratio_to_bf16": acc.nf_table_bytes(w.V, w.N, w.d, bits, block, sbytes) / (w.V * w.N * w.d * 2),
            "quantise_all_layers_s": t_quant}

@@ -188,3 +188,40 @@ def build_lut(E: np.ndarray, W1: np.ndarray, W2: np.ndarray,
     if rc:
         raise RuntimeError(f"mole_oracle_build_lut rc={rc}")
     return out
+
+
+def shared_ffn(x: np.ndarray, W1: np.ndarray, W2: np.ndarray, b1: Optional[np.ndarray] = None,
+               b2: Optional[np.ndarray] = None, act: int = GELU_ERF) -> np.ndarray:
+    """Shared expert: GELU(x @ W1.T + b1) @ W2.T + b2.  x [T,d], W1 [D,d], W2 [d,D] (linear-layer weights as
+    stored, [out, in]) -> [T,d] fp64."""
+    T, d = x.shape
+    D, d2 = W1.shape
+    assert d2 == d and W2.shape == (d, D)
+    arrs = [np.ascontiguousarray(a) if a is not None else None for a in (x, W1, b1, W2, b2)]
+    x, W1, b1, W2, b2 = arrs
+    dt = _same(*arrs)
+    out = np.empty((T, d), dtype=np.float64)
+    rc = lib().mole_oracle_shared_ffn(_p(x), _p(W1), _p(b1), _p(W2), _p(b2), dt, ctypes.c_int64(T), d, D, int(act),
+                                      _p(out))
+    if rc:
+        raise RuntimeError(f"mole_oracle_shared_ffn rc={rc}")
+    return out
+
+
+def _f64(a: Optional[np.ndarray]) -> Optional[np.ndarray]:
+    """Storage array (float32, float64 or bf16 bits) widened exactly to fp64."""
+    if a is None:
+        return None
+    if a.dtype == np.uint16:
+        return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)
+
+
+def layer_with_shared_ffn(table: np.ndarray, ids: np.ndarray, h: np.ndarray, W_r: np.ndarray,
+                          W1: np.ndarray, W2: np.ndarray, b1: Optional[np.ndarray] = None,
+                          b2: Optional[np.ndarray] = None, residual: Optional[np.ndarray] = None,
+                          act: int = GELU_ERF) -> Tuple[np.ndarray, np.ndarray, np.ndarray, int]:
+    """Inference-layer equation with the shared expert evaluated here: sum_j g_j v_j + FFN_shared(h) + residual.
+    The shared term stays in fp64 between the two steps.  Returns (out, gates, rows, err)."""
+    shared = shared_ffn(h, W1, W2, b1, b2, act)
+    return lookup_forward(table, ids, _f64(h), _f64(W_r), shared, _f64(residual))

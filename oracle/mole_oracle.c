@@ -29,12 +29,17 @@
  *   - an id outside [0,V) contributes a zero routed term and raises the error flag;
  *   - dedup map is the canonical one: distinct ids ascending, inv = position in that list.
  *
+ *   - the shared expert FFN_shared is read the same way as a routed expert (its 4dD_s flop count in the
+ *     complexity table): two matrices, GELU in between, optional biases; its weights are taken in the
+ *     layout a linear layer stores them ([out, in]);
+ *
  * Pins (tests/test_oracle_pins.py): brute force against running every expert FFN on the
  * embedding; gates sum to one; zero router -> mean of rows; N=1 -> plain row gather;
  * saturated router -> one expert's row exactly; linearity; numpy.unique; math.erf.
  * The paper prints no numeric example of an output, so every pin is a closed form, an invariant,
  * a special case that reduces to a library routine, or brute force from the training form; each
- * exported function has such pins.
+ * exported function has such pins (shared FFN: numpy matmul with all sizes distinct, math.erf, closed
+ * forms for zero weights and zero input, linearity in the second matrix, planted mistakes).
  */
 #include <math.h>
 #include <stdint.h>
@@ -321,6 +326,46 @@ int mole_oracle_build_lut(const void *E, const void *W1, const void *b1,
             }
         }
         free(x);
+        free(a);
+    }
+    return 0;
+}
+
+/*
+ * Shared expert of the layer (inference listing, "Shared Expert": shared_output = mlp(hidden_states); the
+ * FFN_shared(h) term of the inference-layer equation), as a two-matrix FFN:
+ *   a[m]     = sum_k x[t,k] * W1[m,k] + b1[m]          m = 0..D-1
+ *   out[t,c] = sum_m GELU(a[m]) * W2[c,m] + b2[c]      c = 0..d-1
+ * x [T,d]; W1 [D,d] and W2 [d,D] are stored as a linear layer stores its weight ([out, in]); b1 [D], b2 [d]
+ * nullable.  out is [T,d] in double.
+ */
+int mole_oracle_shared_ffn(const void *x, const void *W1, const void *b1, const void *W2, const void *b2,
+                           int dtype, int64_t T, int d, int D, int act, double *out)
+{
+    if (!x || !W1 || !W2 || !out || T < 0 || d <= 0 || D <= 0)
+        return 1;
+#pragma omp parallel
+    {
+        double *a = (double *)malloc(sizeof(double) * (size_t)D);
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t t = 0; t < T; ++t) {
+            for (int m = 0; m < D; ++m) {
+                double s = 0.0;
+                for (int k = 0; k < d; ++k)
+                    s += ld(x, dtype, t * d + k) * ld(W1, dtype, (int64_t)m * d + k);
+                if (b1)
+                    s += ld(b1, dtype, m);
+                a[m] = mole_oracle_gelu(s, act);
+            }
+            for (int c = 0; c < d; ++c) {
+                double s = 0.0;
+                for (int m = 0; m < D; ++m)
+                    s += a[m] * ld(W2, dtype, (int64_t)c * D + m);
+                if (b2)
+                    s += ld(b2, dtype, c);
+                out[t * d + c] = s;
+            }
+        }
         free(a);
     }
     return 0;

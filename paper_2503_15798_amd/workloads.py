@@ -191,6 +191,21 @@ def layer_inputs(w: Workload, layer: int = 0, T: Optional[int] = None) -> Dict[s
     }
 
 
+def shared_ffn_weights(w: Workload, D_s: int, layer: int = 0, bias: bool = True) -> Dict[str, np.ndarray]:
+    """Shared expert of a layer: W1 [D_s, d] and W2 [d, D_s] ~N(0, 0.02), stored as a linear layer stores its
+    weight ([out, in]); optional biases b1 [D_s], b2 [d] ~N(0, 0.1); storage dtype."""
+    rng = np.random.default_rng(w.seed * 1000003 + 101 * layer + 4)
+    out = {
+        "W1": to_storage(_normal(rng, (D_s, w.d), 0.02), w.dtype),
+        "W2": to_storage(_normal(rng, (w.d, D_s), 0.02), w.dtype),
+        "b1": None, "b2": None,
+    }
+    if bias:
+        out["b1"] = to_storage(_normal(rng, (D_s,), 0.1), w.dtype)
+        out["b2"] = to_storage(_normal(rng, (w.d,), 0.1), w.dtype)
+    return out
+
+
 def norm_inputs(w: Workload, layer: int = 0, T: Optional[int] = None) -> Dict[str, np.ndarray]:
     """Inputs of the layer taken from the post-attention state: x [T,d] ~N(0,1) times a per-token scale
     drawn log-uniformly from [1/8, 8] (so that a norm in front of the router matters), and the norm

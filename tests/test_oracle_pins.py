@@ -411,6 +411,98 @@ def test_layer_forward_pins_catch_planted_mistakes():
         assert not np.allclose(good, bad, rtol=1e-9, atol=1e-12), name
 
 
+# --------------------------------------------------------------------------------------------
+# shared expert (two-matrix FFN on the router's input) and the layer that evaluates it itself
+# --------------------------------------------------------------------------------------------
+def np_shared_ffn(x, W1, W2, b1=None, b2=None):
+    a = x @ W1.T
+    if b1 is not None:
+        a = a + b1
+    out = np_gelu_erf(a) @ W2.T
+    return out if b2 is None else out + b2
+
+
+def _ffn_case(T=7, d=12, D=20, bias=True, seed=3):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((T, d))
+    W1, W2 = rng.standard_normal((D, d)) * 0.3, rng.standard_normal((d, D)) * 0.3
+    b1, b2 = (rng.standard_normal(D) * 0.2, rng.standard_normal(d) * 0.2) if bias else (None, None)
+    return x, W1, W2, b1, b2
+
+
+@pytest.mark.parametrize("bias", [False, True])
+def test_shared_ffn_matches_numpy_matmul(bias):
+    """All sizes distinct (T, d, D = 7, 12, 20), so a transposed operand or a swapped bias cannot pass."""
+    x, W1, W2, b1, b2 = _ffn_case(bias=bias)
+    np.testing.assert_allclose(oracle.shared_ffn(x, W1, W2, b1, b2), np_shared_ffn(x, W1, W2, b1, b2), rtol=1e-12,
+                               atol=1e-13)
+    # tanh form against its textbook formula
+    a = x @ W1.T + (0 if b1 is None else b1)
+    th = 0.5 * a * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (a + 0.044715 * a ** 3)))
+    want = th @ W2.T + (0 if b2 is None else b2)
+    np.testing.assert_allclose(oracle.shared_ffn(x, W1, W2, b1, b2, act=oracle.GELU_TANH), want, rtol=1e-12, atol=1e-13)
+
+
+def test_shared_ffn_closed_forms():
+    x, W1, W2, b1, b2 = _ffn_case()
+    T, d = x.shape
+    # second matrix zero: the output is its bias, whatever the input
+    np.testing.assert_array_equal(oracle.shared_ffn(x, W1, np.zeros_like(W2), b1, b2), np.tile(b2, (T, 1)))
+    # zero input and no first bias: GELU(0) = 0, again only the second bias is left
+    np.testing.assert_array_equal(oracle.shared_ffn(np.zeros_like(x), W1, W2, None, b2), np.tile(b2, (T, 1)))
+    # zero input with a first bias: one row GELU(b1) @ W2.T + b2 for every token, GELU from math.erf
+    g = np.array([0.5 * v * (1.0 + math.erf(v / math.sqrt(2.0))) for v in b1])
+    np.testing.assert_allclose(oracle.shared_ffn(np.zeros_like(x), W1, W2, b1, b2), np.tile(g @ W2.T + b2, (T, 1)),
+                               rtol=1e-12, atol=1e-14)
+    # linear in the second matrix, and tokens are independent
+    np.testing.assert_allclose(oracle.shared_ffn(x, W1, 2.0 * W2, b1, None), 2.0 * oracle.shared_ffn(x, W1, W2, b1, None),
+                               rtol=1e-13)
+    np.testing.assert_array_equal(oracle.shared_ffn(x[2:5], W1, W2, b1, b2), oracle.shared_ffn(x, W1, W2, b1, b2)[2:5])
+    # bf16 storage is widened exactly
+    xb, W1b, W2b = (wl.to_storage(a, wl.BF16) for a in (x, W1, W2))
+    f = lambda a: wl.storage_to_f64(a, wl.BF16)
+    np.testing.assert_allclose(oracle.shared_ffn(xb, W1b, W2b), np_shared_ffn(f(xb), f(W1b), f(W2b)), rtol=1e-12,
+                               atol=1e-13)
+
+
+def test_layer_with_shared_ffn_is_the_layer_equation():
+    """sum_j g_j v_j + FFN_shared(h) + residual with every term from an independent numpy expression."""
+    rng = np.random.default_rng(8)
+    V, N, d, D, T = 30, 5, 12, 20, 9
+    table = rng.standard_normal((V, N, d))
+    ids = rng.integers(0, V, T).astype(np.int32)
+    h, res = rng.standard_normal((T, d)), rng.standard_normal((T, d))
+    W_r = rng.standard_normal((d, N)) * 0.5
+    _, W1, W2, b1, b2 = _ffn_case(T=T, d=d, D=D, seed=9)
+    out, g, rows, err = oracle.layer_with_shared_ffn(table, ids, h, W_r, W1, W2, b1, b2, residual=res)
+    gates = np_softmax(h @ W_r)
+    want = np.einsum("tn,tnd->td", gates, table[ids]) + np_shared_ffn(h, W1, W2, b1, b2) + res
+    np.testing.assert_allclose(out, want, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(g, gates, rtol=1e-12)
+    np.testing.assert_array_equal(rows, ids)
+    assert err == 0
+    # the shared expert reads the router's input (the normed state), not the residual
+    assert not np.allclose(out, np.einsum("tn,tnd->td", gates, table[ids]) + np_shared_ffn(res, W1, W2, b1, b2) + res)
+
+
+def test_shared_ffn_pins_catch_planted_mistakes():
+    """Wrong variants of the shared expert, written in numpy, must fail the comparison the right one passes."""
+    x, W1, W2, b1, b2 = _ffn_case(T=6, d=8, D=8)        # square, so that transposed variants are well-formed
+    ref = oracle.shared_ffn(x, W1, W2, b1, b2)
+    wrong = {
+        "first matrix transposed": np_gelu_erf(x @ W1 + b1) @ W2.T + b2,
+        "second matrix transposed": np_gelu_erf(x @ W1.T + b1) @ W2 + b2,
+        "no activation": (x @ W1.T + b1) @ W2.T + b2,
+        "activation after the second matrix": np_gelu_erf((x @ W1.T + b1) @ W2.T + b2),
+        "first bias after the activation": (np_gelu_erf(x @ W1.T) + b1) @ W2.T + b2,
+        "second bias dropped": np_gelu_erf(x @ W1.T + b1) @ W2.T,
+        "gated (SwiGLU-like) form": (np_gelu_erf(x @ W1.T + b1) * (x @ W1.T)) @ W2.T + b2,
+    }
+    np.testing.assert_allclose(ref, np_shared_ffn(x, W1, W2, b1, b2), rtol=1e-12, atol=1e-13)
+    for name, val in wrong.items():
+        assert not np.allclose(ref, val, rtol=1e-6, atol=1e-8), name
+
+
 def test_pins_catch_planted_mistakes():
     w = wl.scaled(wl.CONFIGS["tiny"], V=97, d=24, N=5, T=33)
     tab = wl.random_table(w).astype(np.float64)
