@@ -597,11 +597,54 @@ def extras(args, torch, mb, wl, acc, stream, L):
         if name == "prefill410m_uniform":
             out[name + "_nf4"] = nf_entry(LL, acc, torch, stream, steps, warm, 4, 1024, 4)
             out.update(norm_entries(LL, acc, torch, stream, steps, warm, name))
+            out.update(shared_ffn_entries(LL, acc, torch, mb, stream, steps, warm, name))
         del LL
         torch.cuda.empty_cache()
 
     out["build_lut_410m_layer"] = build_bench(torch, mb, wl, acc, stream, with_cpu=not args.no_cpu)
     return out
+
+
+def shared_ffn_entries(LL, acc, torch, mb, stream, steps, warm, name):
+    """One layer with its shared expert (D_s = 4 d): mole_shared_ffn_forward (gather and combine in the second
+    product's epilogue) against the same layer with the shared expert computed by torch's own bf16 GEMMs
+    (linear, GELU, linear -> shared_out in HBM) followed by mole_lookup_forward.  Layer 0 of the workload."""
+    import torch.nn.functional as F
+    w = LL.w
+    D_s = 4 * w.d
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3000 + w.seed)
+    W1 = (torch.randn((D_s, w.d), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+    W2 = (torch.randn((w.d, D_s), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+    b1 = (torch.randn((D_s,), generator=g, device="cuda") * 0.1).to(torch.bfloat16)
+    b2 = (torch.randn((w.d,), generator=g, device="cuda") * 0.1).to(torch.bfloat16)
+    res = torch.randn((w.T, w.d), generator=g, device="cuda").to(torch.bfloat16)
+    ws = torch.empty((mb.mole_shared_ffn_workspace(w.T, w.d, D_s, w.N),), dtype=torch.uint8, device="cuda")
+    tab, h, W_r, out = LL.tabs[0], LL.h[0], LL.W_r[0], LL.out[0]
+
+    def fused(i):
+        mb.mole_shared_ffn_forward(tab, LL.ids[i % N_ID_BATCHES], None, h, W_r, W1, b1, W2, b2, res, out, None, LL.err,
+                                   w.T, w.V, w.d, D_s, w.N, LL.code, mb.MOLE_GELU_ERF, ws, stream=stream)
+
+    def torch_ffn(i):
+        return F.linear(F.gelu(F.linear(h, W1, b1)), W2, b2)
+
+    def unfused(i):
+        sh = torch_ffn(i)
+        mb.mole_lookup_forward(tab, LL.ids[i % N_ID_BATCHES], None, h, W_r, sh, res, out, None, None, LL.err, w.T, w.V,
+                               w.d, w.N, LL.code, 0, None, stream=stream)
+
+    def lookup_only(i):
+        mb.mole_lookup_forward(tab, LL.ids[i % N_ID_BATCHES], None, h, W_r, LL.shared[0], res, out, None, None, LL.err,
+                               w.T, w.V, w.d, w.N, LL.code, 0, None, stream=stream)
+    flops = 4.0 * w.T * w.d * D_s
+    out_d = {}
+    for tag, fn in (("fused", fused), ("torch_gemms_then_lookup", unfused), ("torch_gemms_alone", torch_ffn),
+                    ("lookup_alone", lookup_only)):
+        ms = time_steps(torch, stream, fn, max(5, steps // 4), 3)
+        out_d[f"{name}_shared_ffn_{tag}"] = {"ms": ms, "tokens_per_s": w.T / (ms * 1e-3), "D_s": D_s,
+                                             "ffn_TFLOPs": None if tag == "lookup_alone" else flops / (ms * 1e-3) / 1e12}
+    return out_d
 
 
 def norm_entries(LL, acc, torch, stream, steps, warm, name):

@@ -226,6 +226,28 @@ mole_status mole_layer_forward(const void *table, int64_t table_stride,
                                unsigned flags,
                                const void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The layer with its shared expert evaluated inside the call (Sec. 3.3, inference-layer equation; the
+ * "Shared Expert" and "Routed Expert" lines of the inference listing):
+ *     s[t,:]   = GELU(h[t,:] . W1^T + b1) . W2^T + b2          FFN_shared(h): two matrices, as a routed expert
+ *     g[t,:]   = softmax(h[t,:] . W_r)
+ *     out[t,:] = residual[t,:] + s[t,:] + sum_j g[t,j] * table[row(t), j, :]
+ * Both products run on the matrix cores; the gather and the gate-weighted sum run in the epilogue of the
+ * second one, so s is never written to memory (mole_lookup_forward takes it as shared_out instead).
+ *   h [T,d] dev: the router's and the shared expert's input (the post-attention-normed state);
+ *   W1 [D_s,d], W2 [d,D_s] dev: the weights as a linear layer stores them ([out, in]); b1 [D_s], b2 [d] dev
+ *   nullable; residual [T,d] dev nullable; table, ids, slot, W_r, gates_dbg, err_flag, rows as in
+ *   mole_lookup_forward.  bf16 only; d and D_s multiples of 128; N in {2, 4, 8, 16, 32, 64} with the
+ *   router weight fitting in LDS; other shapes return MOLE_EUNSUPPORTED.
+ * The hidden activation is carried as a bf16 high + low pair (relative 2^-17), fp32 accumulation, one
+ * rounding of out.  workspace: dev, mole_shared_ffn_workspace(T, d, D_s, N) bytes (hidden activation, gates). */
+size_t mole_shared_ffn_workspace(int T, int d, int D_s, int N);
+mole_status mole_shared_ffn_forward(const void *table, const int32_t *ids, const int32_t *slot,
+                                    const void *h, const void *W_r,
+                                    const void *W1, const void *b1, const void *W2, const void *b2,
+                                    const void *residual, void *out, float *gates_dbg, int32_t *err_flag,
+                                    int T, int64_t rows, int d, int D_s, int N, mole_dtype dtype, mole_act act,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* ------------------------------------------------------------------------------------------
  * Offloaded-LUT row fetch (Sec. 3.3: the LUT lives off-chip, only looked-up rows are moved;
  * the lookup line of the inference listing):

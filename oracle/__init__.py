@@ -223,5 +223,6 @@ def layer_with_shared_ffn(table: np.ndarray, ids: np.ndarray, h: np.ndarray, W_r
                           act: int = GELU_ERF) -> Tuple[np.ndarray, np.ndarray, np.ndarray, int]:
     """Inference-layer equation with the shared expert evaluated here: sum_j g_j v_j + FFN_shared(h) + residual.
     The shared term stays in fp64 between the two steps.  Returns (out, gates, rows, err)."""
-    shared = shared_ffn(h, W1, W2, b1, b2, act)
-    return lookup_forward(table, ids, _f64(h), _f64(W_r), shared, _f64(residual))
+    h64 = _f64(h)      # widened once: the C loops then read doubles instead of converting per multiply
+    shared = shared_ffn(h64, _f64(W1), _f64(W2), _f64(b1), _f64(b2), act)
+    return lookup_forward(table, ids, h64, _f64(W_r), shared, _f64(residual))

@@ -33,7 +33,8 @@ EXPORTS = ("mole_last_error", "mole_version", "mole_build_lut_workspace", "mole_
            "mole_lut_file_create", "mole_lut_file_open", "mole_lut_file_payload", "mole_lut_file_write_layer",
            "mole_lut_file_read_rows", "mole_lut_file_close", "mole_nf_codebook", "mole_nf_codes_bytes",
            "mole_nf_scales_bytes", "mole_quantize_lut", "mole_lookup_forward_nf", "mole_offload_fetch_nf",
-           "mole_layer_forward_nf", "mole_lookup_forward_noalloc")
+           "mole_layer_forward_nf", "mole_lookup_forward_noalloc", "mole_shared_ffn_workspace",
+           "mole_shared_ffn_forward")
 
 
 class LutDesc(ctypes.Structure):
@@ -84,6 +85,11 @@ def lib() -> ctypes.CDLL:
                                              [c_i32, c_i32, c_i64, c_i32, c_i32, c_i32, c_u, c_void, c_sz, c_void])
     L.mole_lookup_forward_noalloc.restype = c_i32
     L.mole_lookup_forward_noalloc.argtypes = [c_void] * 8 + [c_i32, c_i64, c_i32, c_i32, c_i32, c_void]
+    L.mole_shared_ffn_workspace.restype = c_sz
+    L.mole_shared_ffn_workspace.argtypes = [c_i32, c_i32, c_i32, c_i32]
+    L.mole_shared_ffn_forward.restype = c_i32
+    L.mole_shared_ffn_forward.argtypes = [c_void] * 13 + [c_i32, c_i64, c_i32, c_i32, c_i32, c_i32, c_i32, c_void, c_sz,
+                                                          c_void]
     L.mole_set_tuning.restype = c_i32
     L.mole_set_tuning.argtypes = [ctypes.c_char_p, c_i32]
     L.mole_layer_forward.restype = c_i32
@@ -216,6 +222,19 @@ def mole_lookup_forward_noalloc(table, ids, h, W_r, shared_out, residual, out, e
     _check(lib().mole_lookup_forward_noalloc(_ptr(table), _ptr(ids), _ptr(h), _ptr(W_r), _ptr(shared_out),
                                              _ptr(residual), _ptr(out), _ptr(err_flag), T, V, d, N, dtype,
                                              _stream(stream)))
+
+
+def mole_shared_ffn_workspace(T: int, d: int, D_s: int, N: int) -> int:
+    return lib().mole_shared_ffn_workspace(T, d, D_s, N)
+
+
+def mole_shared_ffn_forward(table, ids, slot, h, W_r, W1, b1, W2, b2, residual, out, gates_dbg, err_flag, T: int,
+                            rows: int, d: int, D_s: int, N: int, dtype: int, act: int, workspace, stream=None,
+                            workspace_bytes: Optional[int] = None) -> None:
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().mole_shared_ffn_forward(_ptr(table), _ptr(ids), _ptr(slot), _ptr(h), _ptr(W_r), _ptr(W1), _ptr(b1),
+                                         _ptr(W2), _ptr(b2), _ptr(residual), _ptr(out), _ptr(gates_dbg), _ptr(err_flag),
+                                         T, rows, d, D_s, N, dtype, act, _ptr(workspace), wb, _stream(stream)))
 
 
 def mole_set_tuning(name: str, value: int) -> None:

@@ -28,522 +28,13 @@
 // workgroup of 4 waves (2 x 2), each wave 128 x 64 = 4 x 2 MFMA tiles, K step 64 through LDS with 16
 // bytes of row padding (conflict-free 16-byte reads), next K tile prefetched into registers while the
 // current one is multiplied.
-#include "mole_internal.h"
+#include "gemm_nt.h"
 
 #include <stdlib.h>
 #include <string.h>
 
 namespace {
 using namespace mole;
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // native vector: stays in registers
-
-constexpr int BM = 256, BN = 128, BK = 64;
-constexpr int LDS_ROW = BK * 2 + 16;   // bytes per tile row in LDS
-constexpr int GEMM_THREADS = 256;
-
-enum { EPI_STORE = 0, EPI_GELU_SPLIT = 1, EPI_GELU_F16 = 2 };
-enum { MODE_F16 = 1, MODE_SPLIT = 2 };   // how the hidden activation is carried (chosen on the device)
-constexpr float F16_SAFE = 60000.0f;
-
-struct GemmArgs {
-    const uint16_t *A;       // [planes][M, K] row-major, K contiguous
-    int64_t lda, a_plane_stride, a_batch_stride;
-    int a_planes;
-    const uint16_t *Bt;      // [Nn, K] row-major (the transposed weight)
-    int64_t ldb, b_batch_stride;
-    const uint16_t *bias;    // [Nn] nullable
-    int64_t bias_batch_stride;
-    uint16_t *C;             // EPI_STORE: [M, ldc]; EPI_GELU_SPLIT: planes hi, lo
-    int64_t ldc, c_plane_stride, c_batch_stride;
-    int M, Nn, K;
-    int epilogue, act;
-    const int *mode;         // nullable: run only if *mode == run_mode
-    int run_mode;
-};
-
-__device__ __forceinline__ float gelu_f(float x, int act)
-{
-    if (act == MOLE_GELU_TANH) {
-        const float k = 0.7978845608028654f;
-        return 0.5f * x * (1.0f + tanhf(k * (x + 0.044715f * x * x * x)));
-    }
-    return 0.5f * x * (1.0f + erff(x * 0.7071067811865476f));
-}
-
-struct BStage {
-    u32x4 b0, b1, b2, b3;
-};
-
-__device__ __forceinline__ void gemm_fetch(u32x4 (&ra)[8], BStage &rb, const GemmArgs &g, const uint16_t *A,
-                                           const uint16_t *Bt, int kt, int ktiles_per_plane, int m0, int n0,
-                                           int prow, int pk)
-{
-    const int plane = kt / ktiles_per_plane;
-    const int kk = (kt - plane * ktiles_per_plane) * BK + pk * 8;
-    const uint16_t *Ap = A + plane * g.a_plane_stride;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int row = m0 + prow + i * 32;
-        ra[i] = row < g.M ? *reinterpret_cast<const u32x4 *>(Ap + (int64_t)row * g.lda + kk) : u32x4{0, 0, 0, 0};
-    }
-    const uint16_t *Bp = Bt + (int64_t)(n0 + prow) * g.ldb + kk;
-    rb.b0 = *reinterpret_cast<const u32x4 *>(Bp);
-    rb.b1 = *reinterpret_cast<const u32x4 *>(Bp + 32 * g.ldb);
-    rb.b2 = *reinterpret_cast<const u32x4 *>(Bp + 64 * g.ldb);
-    rb.b3 = *reinterpret_cast<const u32x4 *>(Bp + 96 * g.ldb);
-}
-
-__device__ __forceinline__ void gemm_stash(const u32x4 (&ra)[8], const BStage &rb, unsigned char *As,
-                                           unsigned char *Bs, int prow, int pk)
-{
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-        *reinterpret_cast<u32x4 *>(As + (prow + i * 32) * LDS_ROW + pk * 16) = ra[i];
-    unsigned char *bp = Bs + prow * LDS_ROW + pk * 16;
-    *reinterpret_cast<u32x4 *>(bp) = rb.b0;
-    *reinterpret_cast<u32x4 *>(bp + 32 * LDS_ROW) = rb.b1;
-    *reinterpret_cast<u32x4 *>(bp + 64 * LDS_ROW) = rb.b2;
-    *reinterpret_cast<u32x4 *>(bp + 96 * LDS_ROW) = rb.b3;
-}
-
-// GELU for the MFMA epilogue.  The epilogue of the first GEMM handles V*D*N values with only K = d
-// multiply-adds behind each, so it has to be cheap: erf by the five-term rational/exponential
-// approximation (absolute error 1.5e-7, far below the 2^-17 of the hi/lo split), tanh through one
-// fast exponential.
-__device__ __forceinline__ float gelu_fast(float x, int act)
-{
-    if (act == MOLE_GELU_TANH) {
-        const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-        const float th = 1.0f - 2.0f * __builtin_amdgcn_rcpf(__expf(2.0f * u) + 1.0f);
-        return 0.5f * x * (1.0f + th);
-    }
-    // x Phi(x) with Phi(-|x|) = erfc(|x| / sqrt 2) / 2 =: c: the result is max(x, 0) - |x| c for either sign.
-    // c = q(t) e with t = 1 / (1 + p |x| / sqrt 2), q the five-term polynomial (coefficients halved),
-    // e = exp(-x^2 / 2) = 2^(-x^2 log2(e) / 2); the constants of z = |x| / sqrt 2 are folded in.
-    const float ax = fabsf(x);
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.7071067811865476f, ax, 1.0f));
-    float q = fmaf(0.5f * 1.061405429f, t, 0.5f * -1.453152027f);
-    q = fmaf(q, t, 0.5f * 1.421413741f);
-    q = fmaf(q, t, 0.5f * -0.284496736f);
-    q = fmaf(q, t, 0.5f * 0.254829592f);
-    const float e = __builtin_amdgcn_exp2f(x * x * -0.7213475204444817f);
-    return fmaxf(x, 0.0f) - ax * (q * t * e);
-}
-
-// round-to-nearest-even without the NaN branch (inputs are finite here), two values into one dword
-__device__ __forceinline__ uint32_t rne_pair(float a, float b)
-{
-    const uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
-    const uint32_t ra = (ua + 0x7fffu + ((ua >> 16) & 1u)) >> 16;
-    const uint32_t rb = (ub + 0x7fffu + ((ub >> 16) & 1u)) & 0xffff0000u;
-    return ra | rb;
-}
-
-// F16: both operands hold fp16 (GEMM 2 of the fp16 mode), else bf16.
-template <int EPI, bool F16>
-__global__ __launch_bounds__(GEMM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void gemm_nt_kernel(GemmArgs g)
-{
-    __shared__ __attribute__((aligned(16))) unsigned char As[BM * LDS_ROW];
-    __shared__ __attribute__((aligned(16))) unsigned char Bs[BN * LDS_ROW];
-    if (g.mode && *g.mode != g.run_mode)
-        return;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
-    const int batch = blockIdx.z;
-    const uint16_t *A = g.A + batch * g.a_batch_stride;
-    const uint16_t *Bt = g.Bt + batch * g.b_batch_stride;
-
-    f32x16 acc[4][2];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e)
-                acc[i][j][e] = 0.f;
-
-    // staging registers: A tile = 256 rows x 8 pieces -> 8 per thread; B tile = 128 x 8 -> 4
-    u32x4 ra[8];
-    BStage rb;
-    const int prow = tid >> 3, pk = tid & 7;   // piece (row, 16-byte column) for i = 0; +32 rows per i
-    const int ktiles_per_plane = g.K / BK;
-    const int ktiles = ktiles_per_plane * g.a_planes;
-
-    gemm_fetch(ra, rb, g, A, Bt, 0, ktiles_per_plane, m0, n0, prow, pk);
-    const int frow = lane & 31, fk = (lane >> 5) * 16;   // fragment row and byte offset of its K run
-    for (int kt = 0; kt < ktiles; ++kt) {
-        gemm_stash(ra, rb, As, Bs, prow, pk);
-        __syncthreads();
-        if (kt + 1 < ktiles)
-            gemm_fetch(ra, rb, g, A, Bt, kt + 1, ktiles_per_plane, m0, n0, prow, pk);
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            u32x4 af[4], bfr[2];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                af[i] = *reinterpret_cast<const u32x4 *>(As + (wm * 128 + i * 32 + frow) * LDS_ROW + ks * 32 + fk);
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-                bfr[j] = *reinterpret_cast<const u32x4 *>(Bs + (wn * 64 + j * 32 + frow) * LDS_ROW + ks * 32 + fk);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    if constexpr (F16)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, bfr[j]),
-                                                                           __builtin_bit_cast(f16x8, af[i]),
-                                                                           acc[i][j], 0, 0, 0);
-                    else
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bfr[j]),
-                                                                            __builtin_bit_cast(bf16x8, af[i]),
-                                                                            acc[i][j], 0, 0, 0);
-                }
-        }
-        __syncthreads();
-    }
-
-    // Epilogue.  The weight fragment is the MFMA's first operand, so the accumulator holds the tile
-    // transposed: lane l has output row m = l % 32 and, in elements 4q..4q+3, the four consecutive
-    // output columns n = 8q + 4*(l/32) + 0..3.  Results go through LDS (the operand tiles are dead by
-    // now) so that global memory sees full 16-byte, row-contiguous stores: four passes of 64 rows
-    // (32 from each wave row), hi plane at Cs, lo plane behind it.
-    const uint16_t *bias = g.bias ? g.bias + batch * g.bias_batch_stride : nullptr;
-    uint16_t *C = g.C + batch * g.c_batch_stride;
-    constexpr int CROW = BN * 2 + 8;                 // bytes per staged row (padded: conflict-free 8-byte writes)
-    constexpr int CPLANE = 64 * CROW;
-    static_assert(2 * CPLANE <= BM * LDS_ROW, "epilogue staging must fit in the A tile");
-    unsigned char *Cs = As;
-    float bv[2][4][4];
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int col = n0 + wn * 64 + j * 32 + 8 * q + 4 * (lane >> 5);
-            uint2 b4 = make_uint2(0, 0);
-            if (bias)
-                b4 = *reinterpret_cast<const uint2 *>(bias + col);
-            bv[j][q][0] = bf16lo(b4.x); bv[j][q][1] = bf16hi(b4.x);
-            bv[j][q][2] = bf16lo(b4.y); bv[j][q][3] = bf16hi(b4.y);
-        }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        // stage this pass: row wm*32 + l%32 of the 64-row slab
-        unsigned char *srow = Cs + (wm * 32 + (lane & 31)) * CROW;
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int cl = wn * 64 + j * 32 + 8 * q + 4 * (lane >> 5);   // column inside the tile
-                float v[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    v[e] = acc[i][j][4 * q + e] + bv[j][q][e];
-                if constexpr (EPI == EPI_GELU_SPLIT) {
-                    float lo[4];
-                    uint32_t hbits[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        v[e] = gelu_fast(v[e], g.act);
-                        const uint32_t u = __float_as_uint(v[e]);
-                        hbits[e] = (u + 0x7fffu + ((u >> 16) & 1u)) & 0xffff0000u;
-                        lo[e] = v[e] - __uint_as_float(hbits[e]);
-                    }
-                    uint2 hi2, lo2;
-                    hi2.x = (hbits[0] >> 16) | hbits[1];
-                    hi2.y = (hbits[2] >> 16) | hbits[3];
-                    lo2.x = rne_pair(lo[0], lo[1]);
-                    lo2.y = rne_pair(lo[2], lo[3]);
-                    *reinterpret_cast<uint2 *>(srow + cl * 2) = hi2;
-                    *reinterpret_cast<uint2 *>(srow + CPLANE + cl * 2) = lo2;
-                } else if constexpr (EPI == EPI_GELU_F16) {
-                    uint16_t hb[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        // the mode was only selected if no value can reach the fp16 range limit; the
-                        // clamp keeps a violated assumption finite
-                        const float a = fminf(fmaxf(gelu_fast(v[e], g.act), -65504.0f), 65504.0f);
-                        hb[e] = __builtin_bit_cast(uint16_t, (_Float16)a);      // round to nearest even
-                    }
-                    uint2 o;
-                    o.x = (uint32_t)hb[0] | ((uint32_t)hb[1] << 16);
-                    o.y = (uint32_t)hb[2] | ((uint32_t)hb[3] << 16);
-                    *reinterpret_cast<uint2 *>(srow + cl * 2) = o;
-                } else {
-                    uint2 o;
-                    o.x = pack_bf16(v[0], v[1]);
-                    o.y = pack_bf16(v[2], v[3]);
-                    *reinterpret_cast<uint2 *>(srow + cl * 2) = o;
-                }
-            }
-        }
-        __syncthreads();
-        // write out: 64 rows x 256 bytes per plane = 1024 16-byte pieces, 4 per thread and plane
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int piece = tid + u * GEMM_THREADS;
-            const int sr = piece >> 4, sc = piece & 15;                 // staged row, 16-byte column
-            const int row = m0 + (sr >> 5) * 128 + i * 32 + (sr & 31);
-            if (row < g.M) {
-                uint16_t *cp = C + (int64_t)row * g.ldc + n0 + sc * 8;
-                *reinterpret_cast<u32x4 *>(cp) = *reinterpret_cast<const u32x4 *>(Cs + sr * CROW + sc * 16);
-                if constexpr (EPI == EPI_GELU_SPLIT)
-                    *reinterpret_cast<u32x4 *>(cp + g.c_plane_stride) =
-                        *reinterpret_cast<const u32x4 *>(Cs + CPLANE + sr * CROW + sc * 16);
-            }
-        }
-        __syncthreads();
-    }
-}
-
-constexpr int DBM = 256, DBN = 256, D_THREADS = 512;
-
-// ------------------------------------------------------------------------------------------
-// 256 x 256 tile fed by direct global -> LDS loads (global_load_lds_dwordx4, gfx950): no staging
-// registers, no ds_write.  A wave-wide load drops lane l's 16 bytes at LDS base + 16*l, i.e. 1 KiB
-// contiguous = 8 tile rows of 128 bytes (K step 64: every row segment is a whole 128-byte line; with
-// 64-byte segments the same L2 delivers a third less).  Rows are therefore unpadded, and bank
-// conflicts are avoided by a swizzle applied on the global side: slot s of row r holds K piece
-// s ^ ((r >> 1) & 7), so the 16 rows a fragment read touches per pass cover all 64 banks.
-// Two stages of 64 KiB: step kt + 1 travels while step kt is multiplied.  8 waves (2 x 4), each
-// 128 x 64 outputs, two per SIMD.
-// ------------------------------------------------------------------------------------------
-constexpr int D_ROW_BYTES = BK * 2;                        // bytes per tile row (128)
-constexpr int D_STAGE_BYTES = (DBM + DBN) * D_ROW_BYTES;          // 64 KiB
-constexpr int D_STAGES = 2;
-constexpr size_t D_LDS_BYTES = (size_t)D_STAGES * D_STAGE_BYTES;
-
-#define MOLE_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
-
-template <int EPI, bool F16>
-__global__ __launch_bounds__(D_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void gemm_nt_direct_kernel(GemmArgs g)
-{
-    extern __shared__ __attribute__((aligned(16))) unsigned char dsmem[];
-    if (g.mode && *g.mode != g.run_mode)
-        return;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 2, wn = wave & 3;
-    const int m0 = blockIdx.x * DBM, n0 = blockIdx.y * DBN;
-    const int batch = blockIdx.z;
-    const uint16_t *A = g.A + batch * g.a_batch_stride;
-    const uint16_t *Bt = g.Bt + batch * g.b_batch_stride;
-
-    f32x16 acc[4][2];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e)
-                acc[i][j][e] = 0.f;
-
-    // feed: per K step the tile pair is 64 chunks of 8 rows (A: 0..31, B: 32..63); wave w moves
-    // A chunks w, w + 8, w + 16, w + 24 and the same B chunks.  Lane l of a chunk load: row l >> 3,
-    // slot l & 7.
-    const int rr = lane >> 3, slot = lane & 7;
-    const uint16_t *gp[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int chunk = wave + 8 * (i & 3);
-        const int row = chunk * 8 + rr;                        // row inside the tile
-        const int piece = slot ^ ((row >> 1) & 7);             // K piece this lane fetches
-        if (i < 4)   // rows past M are clamped: their products are never stored
-            gp[i] = A + (int64_t)min(m0 + row, g.M - 1) * g.lda + piece * 8;
-        else
-            gp[i] = Bt + (int64_t)(n0 + row) * g.ldb + piece * 8;
-    }
-    const int ktiles_per_plane = g.K / BK;
-    const int ktiles = ktiles_per_plane * g.a_planes;
-    // load i (0..7) of K step kt; the eight loads of a step are issued one at a time between groups of
-    // MFMAs: a burst of them right after the barrier keeps every wave of the workgroup waiting in the
-    // memory pipeline's queue, and nothing feeds the matrix pipe meanwhile (measured: the step then
-    // takes compute time plus load-issue time)
-    int64_t cur_aoff = 0, cur_kk = 0;
-    unsigned char *cur_stage = dsmem;
-    auto begin_issue = [&](int kt) {
-        const int plane = kt / ktiles_per_plane;
-        cur_kk = (kt - plane * ktiles_per_plane) * BK;
-        cur_aoff = plane * g.a_plane_stride + cur_kk;
-        cur_stage = dsmem + (kt & (D_STAGES - 1)) * D_STAGE_BYTES + wave * 1024;
-    };
-    auto issue_one = [&](int i) {
-        __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void *)(gp[i] + (i < 4 ? cur_aoff : cur_kk)),
-            (__attribute__((address_space(3))) void *)(cur_stage + (i < 4 ? 0 : DBM * D_ROW_BYTES) + (i & 3) * 8192), 16, 0, 0);
-    };
-
-    // fragment addressing: row frow of a 32-row block, K piece 2*ks + (lane >> 5), swizzled
-    const int frow = lane & 31, swz = (frow >> 1) & 7, hi = lane >> 5;
-    const int a_base = (wm * 128 + frow) * D_ROW_BYTES, b_base = (DBM + wn * 64 + frow) * D_ROW_BYTES;
-    struct Frag {
-        u32x4 a[4], b[2];
-    };
-    auto load_frag = [&](Frag &f, const unsigned char *stage, int ks) {
-        const int koff = ((2 * ks + hi) ^ swz) * 16;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            f.a[i] = *reinterpret_cast<const u32x4 *>(stage + a_base + i * 32 * D_ROW_BYTES + koff);
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-            f.b[j] = *reinterpret_cast<const u32x4 *>(stage + b_base + j * 32 * D_ROW_BYTES + koff);
-    };
-    // four MFMAs: A blocks i0, i0 + 1 against both B blocks
-    auto multiply2 = [&](const Frag &f, int i0) {
-#pragma unroll
-        for (int i = i0; i < i0 + 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                if constexpr (F16)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, f.b[j]),
-                                                                       __builtin_bit_cast(f16x8, f.a[i]),
-                                                                       acc[i][j], 0, 0, 0);
-                else
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.b[j]),
-                                                                        __builtin_bit_cast(bf16x8, f.a[i]),
-                                                                        acc[i][j], 0, 0, 0);
-            }
-    };
-
-    begin_issue(0);
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-        issue_one(i);
-    for (int kt = 0; kt < ktiles; ++kt) {
-        // Step kt has landed for this thread once nothing is outstanding (the next step is issued
-        // below); the barrier extends that to every thread's loads and also says that nobody reads
-        // the other stage any more.  A bare barrier: __syncthreads() adds fences the explicit waits
-        // make unnecessary.
-        MOLE_WAIT_VMCNT(0);
-        __builtin_amdgcn_s_barrier();
-        const bool more = kt + 1 < ktiles;
-        if (more)
-            begin_issue(kt + 1);
-        const unsigned char *stage = dsmem + (kt & (D_STAGES - 1)) * D_STAGE_BYTES;
-        // Order of the step (kept by the scheduling barriers; left alone the compiler re-sorts the
-        // region to save registers): fragments of slice ks + 1 are requested before slice ks is
-        // multiplied, and one load of the next step goes out per group of four MFMAs.
-#define MOLE_STEP(LOADI, FRAG, I0)             \
-        if (more)                              \
-            issue_one(LOADI);                  \
-        __builtin_amdgcn_sched_barrier(0);     \
-        multiply2(FRAG, I0);                   \
-        __builtin_amdgcn_sched_barrier(0);
-        Frag f0, f1;
-        load_frag(f0, stage, 0);
-        load_frag(f1, stage, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        MOLE_STEP(0, f0, 0)
-        MOLE_STEP(1, f0, 2)
-        load_frag(f0, stage, 2);
-        __builtin_amdgcn_sched_barrier(0);
-        MOLE_STEP(2, f1, 0)
-        MOLE_STEP(3, f1, 2)
-        load_frag(f1, stage, 3);
-        __builtin_amdgcn_sched_barrier(0);
-        MOLE_STEP(4, f0, 0)
-        MOLE_STEP(5, f0, 2)
-        MOLE_STEP(6, f1, 0)
-        MOLE_STEP(7, f1, 2)
-#undef MOLE_STEP
-        __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0): this wave's LDS reads of the stage are complete
-    }
-    __syncthreads();
-
-    // Epilogue: as in the 256 x 128 kernel (accumulator layout, staging through LDS, 16-byte stores),
-    // four passes of 64 rows (32 from each wave row) by 256 columns.
-    const uint16_t *bias = g.bias ? g.bias + batch * g.bias_batch_stride : nullptr;
-    uint16_t *C = g.C + batch * g.c_batch_stride;
-    constexpr int CROW = DBN * 2 + 8;
-    constexpr int CPLANE = 64 * CROW;
-    static_assert(2 * CPLANE <= (int)D_LDS_BYTES, "epilogue staging must fit in the operand stages");
-    unsigned char *Cs = dsmem;
-    float bv[2][4][4];
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int col = n0 + wn * 64 + j * 32 + 8 * q + 4 * (lane >> 5);
-            uint2 b4 = make_uint2(0, 0);
-            if (bias)
-                b4 = *reinterpret_cast<const uint2 *>(bias + col);
-            bv[j][q][0] = bf16lo(b4.x); bv[j][q][1] = bf16hi(b4.x);
-            bv[j][q][2] = bf16lo(b4.y); bv[j][q][3] = bf16hi(b4.y);
-        }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        unsigned char *srow = Cs + (wm * 32 + (lane & 31)) * CROW;
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int cl = wn * 64 + j * 32 + 8 * q + 4 * (lane >> 5);
-                float v[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    v[e] = acc[i][j][4 * q + e] + bv[j][q][e];
-                if constexpr (EPI == EPI_GELU_SPLIT) {
-                    float lo[4];
-                    uint32_t hbits[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        v[e] = gelu_fast(v[e], g.act);
-                        const uint32_t u = __float_as_uint(v[e]);
-                        hbits[e] = (u + 0x7fffu + ((u >> 16) & 1u)) & 0xffff0000u;
-                        lo[e] = v[e] - __uint_as_float(hbits[e]);
-                    }
-                    uint2 hi2, lo2;
-                    hi2.x = (hbits[0] >> 16) | hbits[1];
-                    hi2.y = (hbits[2] >> 16) | hbits[3];
-                    lo2.x = rne_pair(lo[0], lo[1]);
-                    lo2.y = rne_pair(lo[2], lo[3]);
-                    *reinterpret_cast<uint2 *>(srow + cl * 2) = hi2;
-                    *reinterpret_cast<uint2 *>(srow + CPLANE + cl * 2) = lo2;
-                } else if constexpr (EPI == EPI_GELU_F16) {
-                    uint16_t hb[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float a = fminf(fmaxf(gelu_fast(v[e], g.act), -65504.0f), 65504.0f);
-                        hb[e] = __builtin_bit_cast(uint16_t, (_Float16)a);
-                    }
-                    uint2 o;
-                    o.x = (uint32_t)hb[0] | ((uint32_t)hb[1] << 16);
-                    o.y = (uint32_t)hb[2] | ((uint32_t)hb[3] << 16);
-                    *reinterpret_cast<uint2 *>(srow + cl * 2) = o;
-                } else {
-                    uint2 o;
-                    o.x = pack_bf16(v[0], v[1]);
-                    o.y = pack_bf16(v[2], v[3]);
-                    *reinterpret_cast<uint2 *>(srow + cl * 2) = o;
-                }
-            }
-        }
-        __syncthreads();
-        // write out: 64 rows x 512 bytes per plane = 2048 16-byte pieces, 4 per thread and plane
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int piece = tid + u * D_THREADS;
-            const int sr = piece >> 5, sc = piece & 31;
-            const int row = m0 + (sr >> 5) * 128 + i * 32 + (sr & 31);
-            if (row < g.M) {
-                uint16_t *cp = C + (int64_t)row * g.ldc + n0 + sc * 8;
-                *reinterpret_cast<u32x4 *>(cp) = *reinterpret_cast<const u32x4 *>(Cs + sr * CROW + sc * 16);
-                if constexpr (EPI == EPI_GELU_SPLIT)
-                    *reinterpret_cast<u32x4 *>(cp + g.c_plane_stride) =
-                        *reinterpret_cast<const u32x4 *>(Cs + CPLANE + sr * CROW + sc * 16);
-            }
-        }
-        __syncthreads();
-    }
-}
 
 // dst[b][c][r] = src[b][r][c]   (bf16, 32 x 32 tiles through LDS).  dst16 (nullable) receives the same
 // transposed matrix converted to fp16 (exact for |x| in [2^-14, 65504]; smaller values become fp16
@@ -905,24 +396,6 @@ mole_status build_plain(const void *Em, const void *W1, const void *b1, const vo
     return MOLE_OK;
 }
 
-// launch one GEMM: the 256 x 256 direct-to-LDS kernel when the column count allows, else the 256 x 128 one
-template <int EPI, bool F16>
-mole_status launch_gemm(const GemmArgs &g, int batches, hipStream_t st)
-{
-    const bool big = g.Nn % DBN == 0 && knob(KNOB_BUILD_SMALL_TILE) != 1;
-    if (big) {
-        static std::atomic<size_t> lds_seen{0};
-        MOLE_HIP_CHECK(ensure_dynamic_lds(lds_seen, reinterpret_cast<const void *>(&gemm_nt_direct_kernel<EPI, F16>),
-                                          D_LDS_BYTES));
-        hipLaunchKernelGGL((gemm_nt_direct_kernel<EPI, F16>), dim3((g.M + DBM - 1) / DBM, g.Nn / DBN, batches),
-                           dim3(D_THREADS), D_LDS_BYTES, st, g);
-    } else {
-        hipLaunchKernelGGL((gemm_nt_kernel<EPI, F16>), dim3((g.M + BM - 1) / BM, g.Nn / BN, batches),
-                           dim3(GEMM_THREADS), 0, st, g);
-    }
-    return MOLE_OK;
-}
-
 mole_status build_mfma(const void *Em, const void *W1, const void *b1, const void *W2, const void *b2,
                        const void *norm_w, float eps, void *LUT, int64_t V, int d, int D, int N, int act,
                        char *ws, const BuildWs &lay, hipStream_t st)
@@ -962,13 +435,13 @@ mole_status build_mfma(const void *Em, const void *W1, const void *b1, const voi
     hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(64), 0, st, bound, mode, forced_mode());
     for (int64_t v0 = 0; v0 < V; v0 += lay.slab) {
         const int nv = (int)((V - v0) < lay.slab ? (V - v0) : lay.slab);
-        GemmArgs g1;
+        GemmArgs g1{};
         g1.A = X + v0 * d; g1.lda = d; g1.a_plane_stride = V * (int64_t)d; g1.a_batch_stride = 0;
         g1.a_planes = x_planes;
         g1.Bt = w1t; g1.ldb = ldw1; g1.b_batch_stride = (int64_t)D * ldw1;
         g1.bias = static_cast<const uint16_t *>(b1); g1.bias_batch_stride = D;
         g1.C = hid; g1.ldc = ldh; g1.M = nv; g1.Nn = D; g1.K = d; g1.act = act; g1.mode = mode;
-        GemmArgs g2;
+        GemmArgs g2{};
         g2.lda = ldh; g2.ldb = ldh; g2.b_batch_stride = (int64_t)d * ldh;
         g2.A = hid;
         g2.bias = static_cast<const uint16_t *>(b2); g2.bias_batch_stride = d;
