@@ -21,34 +21,39 @@ constexpr int DEDUP_THREADS = 1024;
 constexpr int64_t DEDUP_MAX_V = 524288;
 constexpr int BATCH = 8;   // independent loads per thread and pass
 
-// exclusive scan of one value per thread over the workgroup; *total gets the sum
+// inclusive scan over the 64 lanes of a wave: DPP row shifts (row_shr:1, 2, 4, 8, zero fill) give the scan inside
+// each row of 16 lanes, the three row totals are then added to the rows above them
+__device__ __forceinline__ int wave_inclusive_scan(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);
+    const int t0 = __builtin_amdgcn_readlane(v, 15), t1 = __builtin_amdgcn_readlane(v, 31),
+              t2 = __builtin_amdgcn_readlane(v, 47);
+    const int lane = threadIdx.x & 63;
+    return v + (lane >= 16 ? t0 : 0) + (lane >= 32 ? t1 : 0) + (lane >= 48 ? t2 : 0);
+}
+
+// exclusive scan of one value per thread over the workgroup; *total gets the sum.  One barrier: every use
+// in a kernel gets a wave_sums array of its own, so none has to be protected against the one before.
+constexpr int DEDUP_WAVES = DEDUP_THREADS / 64;
 __device__ __forceinline__ int block_exclusive_scan(int v, int *wave_sums, int *total)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int incl = v;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int n = __shfl_up(incl, o);
-        if (lane >= o)
-            incl += n;
-    }
-    __syncthreads();   // protects wave_sums against a previous use
+    const int incl = wave_inclusive_scan(v);
     if (lane == 63)
         wave_sums[wave] = incl;
     __syncthreads();
-    int base = 0;
-    const int nw = blockDim.x >> 6;
-    for (int w = 0; w < nw; ++w) {
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < DEDUP_WAVES; ++w) {
         const int s = wave_sums[w];
-        if (w < wave)
-            base += s;
+        base += w < wave ? s : 0;
+        tot += s;
     }
-    if (total) {
-        int tot = 0;
-        for (int w = 0; w < nw; ++w)
-            tot += wave_sums[w];
+    if (total)
         *total = tot;
-    }
     return base + incl - v;
 }
 
@@ -61,7 +66,7 @@ __global__ __launch_bounds__(DEDUP_THREADS) void dedup_kernel(const int32_t *__r
                                                                 int lds_counters, int lds_stage)
 {
     extern __shared__ uint32_t sm[];
-    __shared__ int wave_sums[DEDUP_THREADS / 64];
+    __shared__ int wave_sums[2][DEDUP_WAVES];
     __shared__ int s_bad;
     const int W = (V + 31) >> 5;
     uint32_t *bitmap = sm;
@@ -115,7 +120,7 @@ __global__ __launch_bounds__(DEDUP_THREADS) void dedup_kernel(const int32_t *__r
     for (int w = w0; w < w1; ++w)
         local += __popc(bitmap[w]);
     int U = 0;
-    int run = block_exclusive_scan(local, wave_sums, &U);
+    int run = block_exclusive_scan(local, wave_sums[0], &U);
     for (int w = w0; w < w1; ++w) {
         prefix[w] = run;
         uint32_t bits = bitmap[w];
@@ -172,7 +177,7 @@ __global__ __launch_bounds__(DEDUP_THREADS) void dedup_kernel(const int32_t *__r
     int tok = 0;
     for (int b = b0; b < b1; ++b)
         tok += counters[b];
-    int tok_run = block_exclusive_scan(tok, wave_sums, nullptr);
+    int tok_run = block_exclusive_scan(tok, wave_sums[1], nullptr);
     for (int b = b0; b < b1; ++b) {
         const int c = counters[b];
         counters[b] = tok_run;
@@ -241,11 +246,11 @@ __global__ __launch_bounds__(DEDUP_THREADS) void dedup_kernel_regs(const int32_t
                                                                      int32_t *err_flag, int32_t *plan)
 {
     extern __shared__ uint32_t sm[];
-    __shared__ int wave_sums[DEDUP_THREADS / 64];
+    __shared__ int wave_sums[2][DEDUP_WAVES];
     __shared__ int s_bad;
     const int W = (V + 31) >> 5;
-    uint32_t *bitmap = sm;
-    int *prefix = reinterpret_cast<int *>(sm + W);
+    uint32_t *bitmap = sm;                                   // [W] presence bits
+    int *prefix = reinterpret_cast<int *>(sm + W);           // [W] distinct ids below the word
     const PlanLayout pl = plan_layout(T);
     int *counters = reinterpret_cast<int *>(sm + 2 * W);     // [T + 2]: bucket sizes, then bucket starts
     int *stage = counters + (T + 2);                         // [T]
@@ -266,7 +271,7 @@ __global__ __launch_bounds__(DEDUP_THREADS) void dedup_kernel_regs(const int32_t
         s_bad = 0;
     __syncthreads();
 
-    // 1. presence bits
+    // 1. presence bits (the atomic is skipped once the bit is seen set: hot ids)
     int bad = 0;
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
@@ -289,10 +294,10 @@ __global__ __launch_bounds__(DEDUP_THREADS) void dedup_kernel_regs(const int32_t
     for (int w = w0; w < w1; ++w)
         local += __popc(bitmap[w]);
     int U = 0;
-    int run = block_exclusive_scan(local, wave_sums, &U);
+    int run = block_exclusive_scan(local, wave_sums[0], &U);
     for (int w = w0; w < w1; ++w) {
-        prefix[w] = run;
         uint32_t bits = bitmap[w];
+        prefix[w] = run;
         while (bits) {
             const int b = __ffs(bits) - 1;
             bits &= bits - 1;
@@ -306,24 +311,23 @@ __global__ __launch_bounds__(DEDUP_THREADS) void dedup_kernel_regs(const int32_t
         plan[pl.uniq + i] = id;
     }
 
-    // 4. inverse map; the atomic add that sizes bucket r also gives the token its place in it.
-    //    Bucket U collects the out-of-range tokens.
+    // 4. inverse map (all ranks first, so that their LDS reads travel together); then the atomic add that sizes
+    //    bucket r also gives the token its place in it.  Bucket U collects the out-of-range tokens.
     int bucket[PER], place[PER];
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
         const int t = tid + u * DEDUP_THREADS;
-        bucket[u] = U;
-        place[u] = 0;
-        if (t < T) {
-            const int id = idv[u];
-            int r = -1;
-            if (id >= 0 && id < V)
-                r = prefix[id >> 5] + __popc(bitmap[id >> 5] & ((1u << (id & 31)) - 1u));
+        const int id = idv[u];
+        int r = -1;
+        if (t < T && id >= 0 && id < V)
+            r = prefix[id >> 5] + __popc(bitmap[id >> 5] & ((1u << (id & 31)) - 1u));
+        bucket[u] = r < 0 ? U : r;
+        if (t < T)
             inv_out[t] = r;
-            bucket[u] = r < 0 ? U : r;
-            place[u] = atomicAdd(&counters[bucket[u]], 1);
-        }
     }
+#pragma unroll
+    for (int u = 0; u < PER; ++u)
+        place[u] = tid + u * DEDUP_THREADS < T ? atomicAdd(&counters[bucket[u]], 1) : 0;
     __syncthreads();    // also: `stage` has been copied out and may be reused
 
     // 5. bucket starts: exclusive scan of the sizes, in place; counters[U + 1] = T
@@ -333,18 +337,17 @@ __global__ __launch_bounds__(DEDUP_THREADS) void dedup_kernel_regs(const int32_t
     int tok = 0;
     for (int b = b0; b < b1; ++b)
         tok += counters[b];
-    int tok_run = block_exclusive_scan(tok, wave_sums, nullptr);
+    int tok_run = block_exclusive_scan(tok, wave_sums[1], nullptr);
     for (int b = b0; b < b1; ++b) {
         const int c = counters[b];
         counters[b] = tok_run;
-        plan[pl.start + b] = tok_run;
         tok_run += c;
     }
-    if (tid == 0) {
+    if (tid == 0)
         counters[B] = T;
-        plan[pl.start + B] = T;
-    }
     __syncthreads();
+    for (int i = tid; i <= B; i += DEDUP_THREADS)       // the starts leave as full-width stores
+        plan[pl.start + i] = counters[i];
 
     // 6. token indices into their buckets, through LDS so that the order leaves as full-width stores
 #pragma unroll
