@@ -238,8 +238,10 @@ mole_status mole_layer_forward(const void *table, int64_t table_stride,
  *   nullable; residual [T,d] dev nullable; table, ids, slot, W_r, gates_dbg, err_flag, rows as in
  *   mole_lookup_forward.  bf16 only; d and D_s multiples of 128; N in {2, 4, 8, 16, 32, 64} with the
  *   router weight fitting in LDS; other shapes return MOLE_EUNSUPPORTED.
- * The hidden activation is carried as a bf16 high + low pair (relative 2^-17), fp32 accumulation, one
- * rounding of out.  workspace: dev, mole_shared_ffn_workspace(T, d, D_s, N) bytes (hidden activation, gates). */
+ * The hidden activation is carried as in mole_build_lut: in fp16 when a bound computed on the device (max
+ * |h_t|_2 * max |W1 row|_2 + max |b1|, and max |W2|) rules out fp16 overflow, else as a bf16 high + low pair;
+ * fp32 accumulation, one rounding of out.  The knob MOLE_BUILD_HIDDEN forces either.
+ * workspace: dev, mole_shared_ffn_workspace(T, d, D_s, N) bytes (hidden activation, gates, W2 as fp16). */
 size_t mole_shared_ffn_workspace(int T, int d, int D_s, int N);
 mole_status mole_shared_ffn_forward(const void *table, const int32_t *ids, const int32_t *slot,
                                     const void *h, const void *W_r,

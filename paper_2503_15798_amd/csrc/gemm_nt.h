@@ -599,5 +599,139 @@ mole_status launch_gemm(const GemmArgs &g, int batches, hipStream_t st)
     return MOLE_OK;
 }
 
+// ---- choice of the hidden-activation format -----------------------------------------------
+// bound[0] = max over rows of sum of squares (rows of X), bound[1] = the same for the rows of W1^T
+// (= columns of W1), bound[2] = max |b1|, bound[3] = max |W2|.  Non-negative floats order like their
+// bit patterns, so the maxima are taken with integer atomics.
+__global__ __launch_bounds__(64) void bound_clear_kernel(unsigned *bound)
+{
+    if (threadIdx.x < 8)
+        bound[threadIdx.x] = 0u;
+}
+
+// sum of the squares of the 8 bf16 values of a 16-byte piece
+__device__ __forceinline__ float piece_sumsq(const uint4 &v, float ss)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        ss = fmaf(bf16lo(w[e]), bf16lo(w[e]), ss);
+        ss = fmaf(bf16hi(w[e]), bf16hi(w[e]), ss);
+    }
+    return ss;
+}
+
+// One atomicMax per workgroup, and none when the stored bound already covers the group's value: thousands
+// of atomics on one address are served one after the other and would cost more than the reduction's reads.
+__device__ __forceinline__ void group_max_to(unsigned *out, float wave_best)
+{
+    __shared__ float part[4];
+    if ((threadIdx.x & 63) == 0)
+        part[threadIdx.x >> 6] = wave_best;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float b = part[0];
+        for (int w = 1; w < (int)(blockDim.x >> 6); ++w)
+            b = (part[w] == part[w]) ? fmaxf(b, part[w]) : INFINITY;
+        const unsigned bits = __float_as_uint(b);        // b >= 0 and not NaN: the bit patterns order like the values
+        if (bits > __hip_atomic_load(out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+            atomicMax(out, bits);
+    }
+}
+
+// A wavefront takes RB rows at a time so that RB loads per lane are in flight (one row of 1024 values
+// is only two 16-byte pieces per lane: a row at a time is bound by latency).
+__global__ __launch_bounds__(256) void row_sumsq_max_kernel(const uint16_t *__restrict__ M, int64_t rows, int cols,
+                                                             int ld, unsigned *out)
+{
+    constexpr int RB = 4;
+    const int lane = threadIdx.x & 63;
+    float best = 0.f;
+    for (int64_t r0 = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RB; r0 < rows; r0 += (int64_t)gridDim.x * 4 * RB) {
+        float ss[RB];
+#pragma unroll
+        for (int u = 0; u < RB; ++u)
+            ss[u] = 0.f;
+        for (int k = lane * 8; k < cols; k += 512) {          // cols is a multiple of 16
+            uint4 v[RB];
+#pragma unroll
+            for (int u = 0; u < RB; ++u)
+                v[u] = r0 + u < rows ? *reinterpret_cast<const uint4 *>(M + (r0 + u) * ld + k) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int u = 0; u < RB; ++u)
+                ss[u] = piece_sumsq(v[u], ss[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < RB; ++u) {
+            float s1 = ss[u];
+#pragma unroll
+            for (int o = 32; o >= 1; o >>= 1)
+                s1 += __shfl_xor(s1, o);
+            best = fmaxf(best, s1);                           // a NaN row leaves best unchanged or NaN
+            if (!(s1 == s1))
+                best = INFINITY;
+        }
+    }
+    group_max_to(out, best);
+}
+
+// max |x| over n bf16 values (x 16-byte aligned): 16-byte pieces, the last n % 8 values one by one
+__global__ __launch_bounds__(256) void abs_max_kernel(const uint16_t *__restrict__ x, int64_t n, unsigned *out)
+{
+    float best = 0.f;
+    auto take = [&](float v) {
+        v = fabsf(v);
+        best = v == v ? fmaxf(best, v) : INFINITY;
+    };
+    const int64_t n8 = n >> 3;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (int64_t)gridDim.x * 256) {
+        const uint4 v = reinterpret_cast<const uint4 *>(x)[i];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            take(bf16lo(w[e]));
+            take(bf16hi(w[e]));
+        }
+    }
+    if (blockIdx.x == 0)
+        for (int64_t i = (n8 << 3) + threadIdx.x; i < n; i += 256)
+            take(bf16_to_f32(x[i]));
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1)
+        best = fmaxf(best, __shfl_xor(best, o));
+    group_max_to(out, best);
+}
+
+__global__ __launch_bounds__(64) void choose_mode_kernel(const unsigned *bound, int *mode, int forced)
+{
+    if (threadIdx.x != 0)
+        return;
+    const float pre = sqrtf(__uint_as_float(bound[0])) * sqrtf(__uint_as_float(bound[1])) * 1.01f +
+                      __uint_as_float(bound[2]);
+    const bool safe = pre <= F16_SAFE && __uint_as_float(bound[3]) <= F16_SAFE;   // false for NaN / inf
+    *mode = forced ? forced : (safe ? MODE_F16 : MODE_SPLIT);
+}
+
+// dst[r, 0..cols) = fp16(src[r, 0..cols)) for bf16 src with row stride cols and dst row stride dst_ld (exact for
+// |x| in [2^-14, 65504]; smaller values become fp16 subnormals, absolute error below 3e-8).  cols % 8 == 0.
+__global__ __launch_bounds__(256) void bf16_to_f16_rows_kernel(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
+                                                                int64_t rows, int cols, int dst_ld)
+{
+    const int per_row = cols >> 3;
+    const int64_t total = rows * per_row;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int64_t r = i / per_row;
+        const int c = (int)(i - r * per_row) * 8;
+        const uint4 v = *reinterpret_cast<const uint4 *>(src + r * cols + c);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        uint32_t o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            o[e] = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)bf16lo(w[e])) |
+                   ((uint32_t)__builtin_bit_cast(uint16_t, (_Float16)bf16hi(w[e])) << 16);
+        *reinterpret_cast<uint4 *>(dst + r * dst_ld + c) = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
 }  // namespace
 #endif

@@ -6,11 +6,14 @@
 // Three launches:
 //   1. router_gates_kernel   gates [T, N] fp32 (router weight in LDS, one wave per token: the router of the
 //                            forward kernels)
-//   2. GEMM 1 on the matrix cores: hidden = GELU(h . W1^T + b1), kept as a bf16 hi + lo pair (2^-17: a plain
-//      bf16 hidden activation would show in the result at the tolerance the layer is held to)
-//   3. GEMM 2 over both planes: hidden . W2^T + b2, whose EPILOGUE adds the residual and the gate-weighted
-//      sum of the token's table rows to each output tile before the single rounding: FFN_shared(h) never
-//      exists in memory.
+//   2. GEMM 1 on the matrix cores: hidden = GELU(h . W1^T + b1).  A plain bf16 hidden activation (2^-9) would
+//      show in the result at the tolerance the layer is held to, so it is carried as in the LUT build: in fp16
+//      (2^-12), with GEMM 2 on the fp16 matrix instruction and W2 converted to fp16 (exact), whenever a bound
+//      computed on the device (max |h_t|_2 * max |W1 row|_2 + max |b1|, and max |W2|) rules out fp16 overflow;
+//      else as a bf16 hi + lo pair (2^-17) with GEMM 2 over both planes.  Both variants are launched, the one
+//      not chosen returns at once (no host synchronisation).
+//   3. GEMM 2: hidden . W2^T + b2, whose EPILOGUE adds the residual and the gate-weighted sum of the token's
+//      table rows to each output tile before the single rounding: FFN_shared(h) never exists in memory.
 // The weights come as a linear layer stores them ([out, in]), which is the K-contiguous form the GEMM
 // kernels read, so nothing is transposed per call.
 #include "gemm_nt.h"
@@ -65,17 +68,19 @@ mole_status launch_router(const uint16_t *h, const uint16_t *W_r, float *gates, 
 }
 
 struct FfnWs {
-    size_t hid, gates, total;
+    size_t hid, gates, w2f16, ctl, total;
     int64_t ldh;
 };
 
-inline FfnWs ffn_ws(int T, int D_s, int N)
+inline FfnWs ffn_ws(int T, int d, int D_s, int N)
 {
     FfnWs w;
     w.ldh = D_s + 64;        // rows padded by 128 bytes: tile rows must not all start in one L2 channel
     size_t off = 0;
-    w.hid = off;   off += align256((size_t)2 * T * w.ldh * 2);      // bf16 hi and lo planes
+    w.hid = off;   off += align256((size_t)2 * T * w.ldh * 2);      // bf16 hi and lo planes, or one fp16 plane
     w.gates = off; off += align256((size_t)T * N * 4);
+    w.w2f16 = off; off += align256((size_t)d * w.ldh * 2);          // W2 as fp16, rows padded like the hidden planes
+    w.ctl = off;   off += 256;                                      // bounds [8] and the chosen mode
     w.total = off;
     return w;
 }
@@ -104,7 +109,7 @@ extern "C" size_t mole_shared_ffn_workspace(int T, int d, int D_s, int N)
 {
     if (check_args(T, 1, d, D_s, N, MOLE_BF16) != MOLE_OK)
         return 0;
-    return ffn_ws(T, D_s, N).total;
+    return ffn_ws(T, d, D_s, N).total;
 }
 
 extern "C" mole_status mole_shared_ffn_forward(const void *table, const int32_t *ids, const int32_t *slot, const void *h,
@@ -128,7 +133,7 @@ extern "C" mole_status mole_shared_ffn_forward(const void *table, const int32_t 
     for (const void *p : ptrs)
         if (p && !aligned16(p))
             return fail(MOLE_EINVAL, "mole_shared_ffn_forward: pointer %p is not 16-byte aligned", p);
-    const FfnWs lay = ffn_ws(T, D_s, N);
+    const FfnWs lay = ffn_ws(T, d, D_s, N);
     if (!workspace || workspace_bytes < lay.total)
         return fail(MOLE_EWORKSPACE, "mole_shared_ffn_forward: workspace of %zu bytes needed, got %zu", lay.total,
                     workspace ? workspace_bytes : (size_t)0);
@@ -151,25 +156,50 @@ extern "C" mole_status mole_shared_ffn_forward(const void *table, const int32_t 
     if (rs != MOLE_OK)
         return rs;
 
-    // GEMM 1: hidden = GELU(h . W1^T + b1) as bf16 hi and lo planes [2][T, ldh]
+    // format of the hidden activation, chosen on the device: fp16 if it provably cannot overflow, else bf16 hi + lo
+    unsigned *bound = reinterpret_cast<unsigned *>(ws + lay.ctl);
+    int *mode = reinterpret_cast<int *>(ws + lay.ctl) + 8;
+    uint16_t *w2f16 = reinterpret_cast<uint16_t *>(ws + lay.w2f16);
+    const uint16_t *w1 = static_cast<const uint16_t *>(W1), *w2 = static_cast<const uint16_t *>(W2);
+    const unsigned cap = (unsigned)num_cus() * 8;
+    auto blocks16 = [&](int64_t rows_) { return (unsigned)((rows_ + 15) / 16 < cap ? (rows_ + 15) / 16 : cap); };
+    hipLaunchKernelGGL(bound_clear_kernel, dim3(1), dim3(64), 0, st, bound);
+    hipLaunchKernelGGL(row_sumsq_max_kernel, dim3(blocks16(T)), dim3(256), 0, st, hp, (int64_t)T, d, d, bound + 0);
+    hipLaunchKernelGGL(row_sumsq_max_kernel, dim3(blocks16(D_s)), dim3(256), 0, st, w1, (int64_t)D_s, d, d, bound + 1);
+    if (b1)
+        hipLaunchKernelGGL(abs_max_kernel, dim3(16), dim3(256), 0, st, static_cast<const uint16_t *>(b1), (int64_t)D_s,
+                           bound + 2);
+    hipLaunchKernelGGL(abs_max_kernel, dim3(cap), dim3(256), 0, st, w2, (int64_t)d * D_s, bound + 3);
+    const int forced = knob(KNOB_BUILD_HIDDEN) == 1 ? MODE_F16 : (knob(KNOB_BUILD_HIDDEN) == 2 ? MODE_SPLIT : 0);
+    hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(64), 0, st, bound, mode, forced);
+    hipLaunchKernelGGL(bf16_to_f16_rows_kernel, dim3(cap), dim3(256), 0, st, w2, w2f16, (int64_t)d, D_s, (int)lay.ldh);
+
+    // GEMM 1: hidden = GELU(h . W1^T + b1); GEMM 2's epilogue finishes the layer.  fp16 variant, then hi + lo variant.
     GemmArgs g1{};
     g1.A = hp; g1.lda = d; g1.a_planes = 1;
-    g1.Bt = static_cast<const uint16_t *>(W1); g1.ldb = d;
+    g1.Bt = w1; g1.ldb = d;
     g1.bias = static_cast<const uint16_t *>(b1);
-    g1.C = hid; g1.ldc = lay.ldh; g1.c_plane_stride = (int64_t)T * lay.ldh;
-    g1.M = T; g1.Nn = D_s; g1.K = d; g1.epilogue = EPI_GELU_SPLIT; g1.act = (int)act;
-    if (mole_status e = launch_gemm<EPI_GELU_SPLIT, false>(g1, 1, st))
-        return e;
-
-    // GEMM 2 over both planes; its epilogue finishes the layer
+    g1.C = hid; g1.ldc = lay.ldh;
+    g1.M = T; g1.Nn = D_s; g1.K = d; g1.act = (int)act; g1.mode = mode;
     GemmArgs g2{};
-    g2.A = hid; g2.lda = lay.ldh; g2.a_planes = 2; g2.a_plane_stride = (int64_t)T * lay.ldh;
-    g2.Bt = static_cast<const uint16_t *>(W2); g2.ldb = D_s;
+    g2.A = hid; g2.lda = lay.ldh;
     g2.bias = static_cast<const uint16_t *>(b2);
     g2.C = static_cast<uint16_t *>(out); g2.ldc = d;
-    g2.M = T; g2.Nn = d; g2.K = D_s; g2.epilogue = EPI_LOOKUP; g2.act = (int)act;
+    g2.M = T; g2.Nn = d; g2.K = D_s; g2.epilogue = EPI_LOOKUP; g2.act = (int)act; g2.mode = mode;
     g2.table = static_cast<const uint16_t *>(table); g2.rowsrc = slot ? slot : ids; g2.gates = gates;
     g2.residual = static_cast<const uint16_t *>(residual); g2.table_rows = rows; g2.n_experts = N; g2.err_flag = err_flag;
+
+    g1.epilogue = EPI_GELU_F16; g1.run_mode = MODE_F16; g1.c_plane_stride = 0;
+    if (mole_status e = launch_gemm<EPI_GELU_F16, false>(g1, 1, st))
+        return e;
+    g2.run_mode = MODE_F16; g2.a_planes = 1; g2.a_plane_stride = 0; g2.Bt = w2f16; g2.ldb = lay.ldh;
+    if (mole_status e = launch_gemm<EPI_LOOKUP, true>(g2, 1, st))
+        return e;
+
+    g1.epilogue = EPI_GELU_SPLIT; g1.run_mode = MODE_SPLIT; g1.c_plane_stride = (int64_t)T * lay.ldh;
+    if (mole_status e = launch_gemm<EPI_GELU_SPLIT, false>(g1, 1, st))
+        return e;
+    g2.run_mode = MODE_SPLIT; g2.a_planes = 2; g2.a_plane_stride = (int64_t)T * lay.ldh; g2.Bt = w2; g2.ldb = D_s;
     if (mole_status e = launch_gemm<EPI_LOOKUP, false>(g2, 1, st))
         return e;
     MOLE_HIP_CHECK(hipGetLastError());

@@ -51,7 +51,11 @@ def check(w, D_s, table, ids, li, fw, residual=True, act=mb.MOLE_GELU_ERF):
     (256, 256, 2, 40, 50, False, False),        # two experts (router padded to four)
     (512, 1024, 64, 130, 64, True, True),       # N = 64
 ])
-def test_shapes(d, D_s, N, T, V, bias, residual):
+@pytest.mark.parametrize("hidden", [0, 1, 2])
+def test_shapes(tuning, d, D_s, N, T, V, bias, residual, hidden):
+    """hidden: the format the hidden activation is carried in -- chosen by the library (fp16 here: the values are
+    small), forced to fp16, forced to the bf16 hi + lo pair."""
+    tuning("MOLE_BUILD_HIDDEN", hidden)
     w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, T=T, L=1, name=f"shared ffn d{d} Ds{D_s} N{N} T{T}")
     table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w).copy()
     li["W_r"] = wl.to_storage(wl.storage_to_f64(li["W_r"], w.dtype) * 5.0, w.dtype)
@@ -61,14 +65,14 @@ def test_shapes(d, D_s, N, T, V, bias, residual):
 
 
 def test_tanh_form_and_large_hidden_values():
-    """GELU in its tanh form; first-layer weights scaled so that hidden activations reach the hundreds (the hi + lo
-    carriage has no range limit)."""
+    """GELU in its tanh form; then first-layer weights scaled so that pre-activations can leave the fp16 range (the
+    bound is then violated and the library must take the hi + lo pair, which has no range limit)."""
     w = wl.scaled(wl.CONFIGS["decode410m"], V=300, d=256, N=16, T=150, L=1, name="shared ffn tanh")
     table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
     fw = wl.shared_ffn_weights(w, 512)
     check(w, 512, table, ids, li, fw, act=mb.MOLE_GELU_TANH)
-    fw["W1"] = wl.to_storage(wl.storage_to_f64(fw["W1"], w.dtype) * 400.0, w.dtype)
-    fw["W2"] = wl.to_storage(wl.storage_to_f64(fw["W2"], w.dtype) / 400.0, w.dtype)
+    fw["W1"] = wl.to_storage(wl.storage_to_f64(fw["W1"], w.dtype) * 40000.0, w.dtype)
+    fw["W2"] = wl.to_storage(wl.storage_to_f64(fw["W2"], w.dtype) / 40000.0, w.dtype)
     check(w, 512, table, ids, li, fw)
 
 
