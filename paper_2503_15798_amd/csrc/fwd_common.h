@@ -338,20 +338,28 @@ __device__ __forceinline__ float router_gate(const uint4 *smem, int kgroups, con
 #pragma unroll
     for (int j = 0; j < N; ++j)
         z[j] = 0.f;
-    auto piece = [&](const uint4 &hv, int kg) {
-        if constexpr (NORM)
-            router_piece_scaled<N>(z, smem, kgroups, hv, reinterpret_cast<const uint32_t *>(lnw + kg), kg);
-        else
-            router_piece<N>(z, smem, kgroups, hv, kg);
-    };
-    if (col0 < d)
-        piece(h0, col0 >> 3);
-    if (col0 + 512 < d)
-        piece(h1, (col0 + 512) >> 3);
-    for (int c0 = 1024; c0 < d; c0 += 512) {
-        const int cc = c0 + col0;
-        if (cc < d)
-            piece(ld16_stream<NTA>(hrow + cc), cc >> 3);
+    if constexpr (NORM) {
+        if (col0 < d)
+            router_piece_scaled<N>(z, smem, kgroups, h0, reinterpret_cast<const uint32_t *>(lnw + (col0 >> 3)), col0 >> 3);
+        if (col0 + 512 < d)
+            router_piece_scaled<N>(z, smem, kgroups, h1, reinterpret_cast<const uint32_t *>(lnw + ((col0 + 512) >> 3)),
+                                   (col0 + 512) >> 3);
+        for (int c0 = 1024; c0 < d; c0 += 512) {
+            const int cc = c0 + col0;
+            if (cc < d)
+                router_piece_scaled<N>(z, smem, kgroups, ld16_stream<NTA>(hrow + cc),
+                                       reinterpret_cast<const uint32_t *>(lnw + (cc >> 3)), cc >> 3);
+        }
+    } else {
+        if (col0 < d)
+            router_piece<N>(z, smem, kgroups, h0, col0 >> 3);
+        if (col0 + 512 < d)
+            router_piece<N>(z, smem, kgroups, h1, (col0 + 512) >> 3);
+        for (int c0 = 1024; c0 < d; c0 += 512) {
+            const int cc = c0 + col0;
+            if (cc < d)
+                router_piece<N>(z, smem, kgroups, ld16_stream<NTA>(hrow + cc), cc >> 3);
+        }
     }
     float zz = Fold<N, 32>::run(z, lane) * rs;
     if constexpr (NREAL < N) {

@@ -46,88 +46,6 @@ struct FwdArgs {
     int T, d, N, L;
 };
 
-// ---- weighted sums on the matrix pipe (used by the run kernel and, from 32 experts on, by the streaming kernel) ----
-__device__ __forceinline__ void wave_lds_fence()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-typedef __attribute__((ext_vector_type(4))) short bf16x4_bits;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-
-__device__ __forceinline__ uint32_t dword_of(const uint4 &v, int i)
-{
-    return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w;
-}
-
-// B operands of expert quad Q: for each of the lane's 8 columns, the values of experts 4Q .. 4Q+3
-template <int N, int Q>
-__device__ __forceinline__ void quad_columns(bf16x4_bits (&bcol)[8], const uint4 (&r)[N])
-{
-    const uint4 zero = make_uint4(0, 0, 0, 0);
-    const uint4 &r0 = r[4 * Q];
-    const uint4 &r1 = 4 * Q + 1 < N ? r[4 * Q + 1] : zero;
-    const uint4 &r2 = 4 * Q + 2 < N ? r[4 * Q + 2] : zero;
-    const uint4 &r3 = 4 * Q + 3 < N ? r[4 * Q + 3] : zero;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        // column e of the four rows: the low or high halves of dword e/2
-        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-        const uint32_t b01 = __builtin_amdgcn_perm(dword_of(r1, e >> 1), dword_of(r0, e >> 1), sel);
-        const uint32_t b23 = __builtin_amdgcn_perm(dword_of(r3, e >> 1), dword_of(r2, e >> 1), sel);
-        bcol[e] = __builtin_bit_cast(bf16x4_bits, make_uint2(b01, b23));
-    }
-}
-
-// acc[e][i] += sum over the 4 experts of a quad of gate[token i][expert] * row[expert][lane's column e].
-// ga: this lane's A operand (gates of token lane & 3: hi in x, y; lo in z, w).
-__device__ __forceinline__ void quad_products(f32x4 (&acc)[8], const bf16x4_bits (&bcol)[8], const uint4 &ga)
-{
-    const bf16x4_bits ahi = __builtin_bit_cast(bf16x4_bits, make_uint2(ga.x, ga.y));
-    const bf16x4_bits alo = __builtin_bit_cast(bf16x4_bits, make_uint2(ga.z, ga.w));
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-        acc[e] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(ahi, bcol[e], acc[e], 0, 0, 0);
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-        acc[e] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(alo, bcol[e], acc[e], 0, 0, 0);
-}
-
-// Weighted sum of the R row pieces a wave holds (R a multiple of 4) on the matrix pipe, for the lane's columns
-// E0 .. E0+3: sum[c] = sum_j gate_j * row_j[column E0 + c].  Gates of expert quad q at gq[q] as bf16 hi + lo; every
-// lane reads the same piece, so every row of the 4x4 product is the same token's sum and element 0 is taken.
-// Four columns at a time: eight would hold 32 accumulator and 16 operand registers at once.
-template <int R, int E0>
-__device__ __forceinline__ void part_products(float (&acc)[8], const uint4 (&r)[R], const uint4 *gq)
-{
-    f32x4 sum[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-        sum[c] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int q = 0; q < R / 4; ++q) {
-        const uint4 ga = gq[q];
-        const bf16x4_bits ahi = __builtin_bit_cast(bf16x4_bits, make_uint2(ga.x, ga.y));
-        const bf16x4_bits alo = __builtin_bit_cast(bf16x4_bits, make_uint2(ga.z, ga.w));
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int e = E0 + c;
-            // column e of the quad's four rows: the low or high halves of dword e / 2
-            const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-            const uint32_t b01 = __builtin_amdgcn_perm(dword_of(r[4 * q + 1], e >> 1), dword_of(r[4 * q], e >> 1), sel);
-            const uint32_t b23 = __builtin_amdgcn_perm(dword_of(r[4 * q + 3], e >> 1), dword_of(r[4 * q + 2], e >> 1), sel);
-            const bf16x4_bits b = __builtin_bit_cast(bf16x4_bits, make_uint2(b01, b23));
-            sum[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(ahi, b, sum[c], 0, 0, 0);
-            sum[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(alo, b, sum[c], 0, 0, 0);
-        }
-    }
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-        acc[E0 + c] += sum[c][0];
-}
-
 // ------------------------------------------------------------------------------------------
 // bf16 streaming kernel.  The wave's N row registers are a ring: as soon as the rows of the
 // current 512-column chunk have been multiplied in, the same registers are re-loaded with the
@@ -160,18 +78,11 @@ void fwd_bf16_stream_kernel(FwdArgs a)
     extern __shared__ uint4 smem[];
     constexpr int NR = N < 4 ? 4 : N;   // experts the router is computed for (N = 2 is padded to 4)
     constexpr int LPJ = 64 / NR;        // lanes per expert after the fold
-    // row registers: above 16 experts a chunk's rows pass through in parts: of 8 at N = 32, where the budget is 128
-    // registers (four waves per SIMD) and the matrix-pipe accumulators take 32 of them; of 16 at N = 64
-    constexpr int R = N > 16 ? (N == 32 ? 8 : 16) : N;
+    // row registers: above 16 experts a chunk's rows pass through in parts of 16 (of 8 in the N = 32 norm variant,
+    // whose router keeps more values live: with 16 it spills 40 to 80 registers and takes 290 instead of 235 us on
+    // the 16384-token prefill)
+    constexpr int R = N > 16 ? (NORM && N == 32 ? 8 : 16) : N;
     constexpr int H = N / R;
-    // From 32 experts on the kernel is bound by vector-instruction issue, not by memory (two instructions per
-    // table element: conversion and multiply-add).  The weighted sum then runs on the matrix pipe instead:
-    // v_mfma_f32_4x4x4_16b_bf16 takes the bf16 table values as they are (one v_perm_b32 per two elements builds
-    // its operand), the gates enter as bf16 hi + lo pairs (16 significant bits) from a small LDS area per wave.
-    // Every row of the instruction's first operand holds the same token's gates, so every row of the result
-    // is that token's sum; element 0 is used.
-    constexpr bool MMA = N >= 32;
-    constexpr int NQ = NR / 4;
     // NORM: the state is also the residual; below 16 experts its two pieces stay in registers through the
     // combine, from 16 experts on (kernels at their 128-register budget) they are read again (an L2 hit)
     constexpr bool HOLD_X = NORM && N < 16;
@@ -221,8 +132,6 @@ void fwd_bf16_stream_kernel(FwdArgs a)
     if constexpr (NORM)
         fill_norm_lds(smem + router_lds_bytes(d, NR) / 16, static_cast<const uint16_t *>(a.ln_w) + (int64_t)layer * d,
                       kgroups, WPB * 64);
-    // MMA: this wave's gates as NQ pieces of 16 bytes (4 experts x (hi, lo)), behind router and norm weight
-    uint4 *gq = smem + (router_lds_bytes(d, NR) + (NORM ? norm_lds_bytes(d) : 0)) / 16 + wave * NQ;
     __syncthreads();
 
     for (; item < n_items; item += stride) {
@@ -244,19 +153,6 @@ void fwd_bf16_stream_kernel(FwdArgs a)
         const uint4 x0 = h0, x1 = h1;                  // NORM: the residual of chunks 0 and 1
         // the next token's h goes in flight now; its latency hides behind this token's combine
         load_h2<NTA>(h0, h1, hbase + (int64_t)nxt.t * d, d, lane);
-        if constexpr (MMA) {
-            // the previous item's products have read their gates (same wave, program order); publish this item's
-            wave_lds_fence();
-            if ((lane & (LPJ - 1)) == 0) {
-                const int e = lane / LPJ;
-                const uint32_t hi = f32_to_bf16_bits(g);
-                const uint32_t lo = f32_to_bf16_bits(g - __uint_as_float(hi << 16));
-                uint16_t *piece = reinterpret_cast<uint16_t *>(gq) + ((e >> 2) << 3);
-                piece[e & 3] = (uint16_t)hi;
-                piece[4 + (e & 3)] = (uint16_t)lo;
-            }
-            wave_lds_fence();
-        }
         // gates into scalar registers: expert j's gate sits in lane j * (64/N)
         float gs[R];
         if constexpr (H == 1) {
@@ -311,22 +207,14 @@ void fwd_bf16_stream_kernel(FwdArgs a)
                 // N > 16: the chunk's experts pass through the row registers in parts of R
 #pragma unroll
                 for (int hf = 0; hf < H; ++hf) {
-                    if constexpr (MMA) {
-                        if (valid) {
-                            part_products<R, 0>(acc, r, gq + hf * (R / 4));
-                            __builtin_amdgcn_sched_barrier(0);      // the two column halves one after the other
-                            part_products<R, 4>(acc, r, gq + hf * (R / 4));
-                        }
-                    } else {
+#pragma unroll
+                    for (int j = 0; j < R; ++j)
+                        gs[j] = __builtin_bit_cast(
+                            float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, g), (hf * R + j) * LPJ));
+                    if (valid) {
 #pragma unroll
                         for (int j = 0; j < R; ++j)
-                            gs[j] = __builtin_bit_cast(
-                                float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, g), (hf * R + j) * LPJ));
-                        if (valid) {
-#pragma unroll
-                            for (int j = 0; j < R; ++j)
-                                fma8(acc, gs[j], r[j]);
-                        }
+                            fma8(acc, gs[j], r[j]);
                     }
                     // refill: the next half of this chunk, else the next chunk / the wave's next item
                     const bool more_halves = hf + 1 < H;
@@ -374,6 +262,13 @@ void fwd_bf16_stream_kernel(FwdArgs a)
 //     after this item's stores, so both travel while this item and the gates run;
 //   * shared / residual are added and the result is rounded and stored per token, as elsewhere.
 // ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // Row pieces come through buffer loads: base and size of a row block sit in a scalar descriptor, the
 // expert's offset in a scalar register, the lane's column offset is the only vector operand.  Lanes
 // past the end of the block read zeros (ragged last chunk); their results are never stored.
@@ -394,6 +289,47 @@ __device__ __forceinline__ void rows_load_buf(uint4 (&r)[N], __amdgpu_buffer_rsr
         const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, lane_bytes, j * d * 2 + chunk_bytes, NT ? 2 : 0);
         r[j] = make_uint4(v.x, v.y, v.z, v.w);
     }
+}
+
+typedef __attribute__((ext_vector_type(4))) short bf16x4_bits;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+__device__ __forceinline__ uint32_t dword_of(const uint4 &v, int i)
+{
+    return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w;
+}
+
+// B operands of expert quad Q: for each of the lane's 8 columns, the values of experts 4Q .. 4Q+3
+template <int N, int Q>
+__device__ __forceinline__ void quad_columns(bf16x4_bits (&bcol)[8], const uint4 (&r)[N])
+{
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    const uint4 &r0 = r[4 * Q];
+    const uint4 &r1 = 4 * Q + 1 < N ? r[4 * Q + 1] : zero;
+    const uint4 &r2 = 4 * Q + 2 < N ? r[4 * Q + 2] : zero;
+    const uint4 &r3 = 4 * Q + 3 < N ? r[4 * Q + 3] : zero;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        // column e of the four rows: the low or high halves of dword e/2
+        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+        const uint32_t b01 = __builtin_amdgcn_perm(dword_of(r1, e >> 1), dword_of(r0, e >> 1), sel);
+        const uint32_t b23 = __builtin_amdgcn_perm(dword_of(r3, e >> 1), dword_of(r2, e >> 1), sel);
+        bcol[e] = __builtin_bit_cast(bf16x4_bits, make_uint2(b01, b23));
+    }
+}
+
+// acc[e][i] += sum over the 4 experts of a quad of gate[token i][expert] * row[expert][lane's column e].
+// ga: this lane's A operand (gates of token lane & 3: hi in x, y; lo in z, w).
+__device__ __forceinline__ void quad_products(f32x4 (&acc)[8], const bf16x4_bits (&bcol)[8], const uint4 &ga)
+{
+    const bf16x4_bits ahi = __builtin_bit_cast(bf16x4_bits, make_uint2(ga.x, ga.y));
+    const bf16x4_bits alo = __builtin_bit_cast(bf16x4_bits, make_uint2(ga.z, ga.w));
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        acc[e] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(ahi, bcol[e], acc[e], 0, 0, 0);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        acc[e] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(alo, bcol[e], acc[e], 0, 0, 0);
 }
 
 // One item: the products of all expert quads with the held row pieces; each quad's registers are
@@ -891,9 +827,7 @@ int64_t grid_x(int items, int L, size_t lds, int waves_per_cu = N <= 4 ? 32 : (N
 template <int N, int WPB, bool NTA, bool SPLIT, bool NORM>
 mole_status launch_fast(const FwdArgs &a, hipStream_t stream)
 {
-    // router weight, norm weight (NORM), and from 32 experts on each wave's gates for the matrix pipe
-    const size_t lds = router_lds_bytes(a.d, N < 4 ? 4 : N) + (NORM ? norm_lds_bytes(a.d) : 0) +
-                       (N >= 32 ? (size_t)WPB * (N / 4) * 16 : 0);
+    const size_t lds = router_lds_bytes(a.d, N < 4 ? 4 : N) + (NORM ? norm_lds_bytes(a.d) : 0);
     static std::atomic<size_t> lds_seen{0};
     MOLE_HIP_CHECK(ensure_dynamic_lds(
         lds_seen, reinterpret_cast<const void *>(&fwd_bf16_stream_kernel<N, WPB, NTA, SPLIT, NORM>), lds));
@@ -1032,8 +966,7 @@ mole_status forward_impl(const void *table, int64_t table_stride, const int32_t 
     a.T = T; a.d = d; a.N = N; a.L = L;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
-    const size_t lds_fast = router_lds_bytes(d, N < 4 ? 4 : N) + (with_norm ? norm_lds_bytes(d) : 0) +
-                            (N >= 32 ? (size_t)8 * (N / 4) * 16 : 0);
+    const size_t lds_fast = router_lds_bytes(d, N < 4 ? 4 : N) + (with_norm ? norm_lds_bytes(d) : 0);
     const bool fast = dtype == MOLE_BF16 && lds_fast <= LDS_BYTES_PER_CU && knob(KNOB_FWD_GENERIC) != 1;
     if (fast) {
         switch (N) {
