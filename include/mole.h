@@ -88,7 +88,8 @@ int mole_version(void);
  * "MOLE_FWD_WPB" (waves per workgroup of the forward kernels, 4 or 8), "MOLE_FWD_WGS_PER_CU",
  * "MOLE_FWD_NTA" (1 = non-temporal activation loads, 2 = plain), "MOLE_FWD_SPLIT" (1 = one
  * 512-column chunk per work item, 2 = whole tokens), "MOLE_FWD_RUN" (1 / 2 = force / forbid the
- * kernel of MOLE_FLAG_RUNS for planned calls), "MOLE_FWD_GENERIC" (1 = generic forward kernel),
+ * kernel of MOLE_FLAG_RUNS for planned calls), "MOLE_FWD_TILE" (1 / 2 = force / forbid the tile kernel, which
+ * serves N = 32 only), "MOLE_FWD_GENERIC" (1 = generic forward kernel),
  * "MOLE_DEDUP_GENERIC" (1 = generic dedup kernel), "MOLE_BUILD_HIDDEN" (1 = fp16, 2 = bf16 hi/lo
  * hidden activation), "MOLE_BUILD_SMALL_TILE" (1 = the 256 x 128 GEMM).  value 0 restores the
  * library's own choice.  Each knob starts from the environment variable of the same name, read once

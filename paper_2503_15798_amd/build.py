@@ -13,7 +13,7 @@ INCLUDE = os.path.join(ROOT, "include")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmole.so")
 
-SOURCES = ["common.hip", "lookup_forward.hip", "dedup.hip", "offload_fetch.hip", "lut_file.hip",
+SOURCES = ["common.hip", "lookup_forward.hip", "fwd_tile.hip", "dedup.hip", "offload_fetch.hip", "lut_file.hip",
            "build_lut.hip", "nf_quant.hip", "noalloc.hip", "shared_ffn.hip"]
 
 # packed-fp32 instructions are switched off for all device code

@@ -425,5 +425,26 @@ __device__ __forceinline__ uint4 pack8_cvt(const float (&acc)[8])
                       cvt_pk_bf16(acc[6], acc[7]));
 }
 
+// ---- tile kernel of the bf16 forward (fwd_tile.hip): arguments and host-side launcher ----
+struct TileArgs {
+    const void *table;
+    const int32_t *rowsrc;      // slot if given, else ids
+    const void *h;
+    const void *W_r;
+    const void *shared;
+    const void *residual;
+    void *out;
+    float *gates_dbg;
+    int64_t *rows_dbg;
+    int32_t *err_flag;
+    const int32_t *plan;
+    const void *ln_w;           // not NULL: h is the state before the RMSNorm, which is also the residual
+    float ln_eps;
+    int64_t table_stride, act_stride, rows;
+    int T, d;
+};
+bool tile_forward_applies(int N, int d, int T, int L);
+mole_status launch_tile_forward(const TileArgs &a, int N, int L, hipStream_t stream);
+
 }  // namespace mole
 #endif

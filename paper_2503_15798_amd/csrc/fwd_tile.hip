@@ -1,0 +1,353 @@
+// Tile kernel of the forward for large batches and many experts (N = 32, 64).
+//
+// Paper: Sec. 3.2 (router equation) and Sec. 3.3 (inference-layer equation), as in lookup_forward.hip.
+//
+// For a batch of thousands of tokens the router h . W_r is a dense product [T, d] x [d, N], and the streaming
+// kernel, which computes it token by token on the vector ALU (one dot-product instruction per two multiply-adds,
+// then a fold over the 64 lanes), spends almost half of its instructions there.  Here a workgroup of eight
+// waves works on a tile of 32 tokens at a time:
+//   1. router on the matrix pipe: v_mfma_f32_32x32x16_bf16 with the router weight as its first operand (row =
+//      expert) and the tokens' h as its second (row = token); wave w contracts the w-th eighth of d.  Lane l
+//      supplies 8 consecutive k of token l % 32 (one 16-byte load) and the same 8 k of expert l % 32 (eight
+//      2-byte loads from the [d, N] weight, which stays in L1 / L2: 64 KB for the whole launch).  Staging the
+//      weight through LDS instead (16-byte loads, transposed there) measured 3 % slower: what this step waits
+//      for is its h loads, queued behind the row loads of the whole chip.  The eight partial 32 x 32 products
+//      meet in LDS;
+//   2. wave w sums the partials of ITS four tokens, lane = expert, takes the softmax over the 32 lanes of a
+//      half-wave (two tokens per pass), and leaves the gates in LDS;
+//   3. gather and gate-weighted sum exactly as in the streaming kernel: one wave per token, 16-byte row pieces
+//      through a ring of 8 registers that is refilled as it is consumed (the next token's, or the next tile's
+//      first token's, pieces are in flight through steps 1 and 2), gates in scalar registers, shared / residual
+//      added and one rounding at the store.
+// Items are dealt out as in the streaming kernel (round `it`: wave w of workgroup g takes item (it * G + g) * 8 + w
+// of the visiting order); a tile is four rounds of a workgroup.
+// With the RMSNorm inside (NORM), the state times the norm weight enters step 1 exactly, as a bf16 hi + lo pair
+// (two matrix instructions), and 1 / rms scales the logits in step 2.
+#include "fwd_common.h"
+
+namespace {
+using namespace mole;
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int TILE = 32;        // tokens per tile = rows of the matrix instruction's second operand
+constexpr int TILE_WPB = 8;     // waves per workgroup
+constexpr int TPW = TILE / TILE_WPB;
+
+template <int R, bool NT>
+__device__ __forceinline__ void ring_load(uint4 (&r)[R], const uint16_t *base, int d, int col)
+{
+#pragma unroll
+    for (int j = 0; j < R; ++j)
+        r[j] = ld16_row<NT>(base + (int64_t)j * d + col);
+}
+
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int N, bool NORM>
+__global__ __launch_bounds__(TILE_WPB * 64) __attribute__((amdgpu_waves_per_eu(4)))
+void fwd_bf16_tile_kernel(TileArgs a)
+{
+    constexpr int WPB = TILE_WPB;
+    constexpr int R = 8;                // row registers (the ring)
+    constexpr int PB = 4;               // router steps whose loads are issued together
+    constexpr int MB = N / 32;          // blocks of 32 experts
+    constexpr int H = N / R;
+    constexpr int PROW = TILE + 1;      // padded row of the partial-product array
+    __shared__ float part[WPB][N][PROW];    // partial logits [wave = part of d][expert][token of the tile]
+    __shared__ float ssq[NORM ? WPB : 1][64];
+    __shared__ float gl[TILE][N];           // gates of the tile
+
+    const int d = a.d;
+    const int T = a.T;
+    const int layer = blockIdx.y;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int col0 = lane * 8;
+    const int n = lane & 31, half = lane >> 5;
+
+    const uint16_t *table = static_cast<const uint16_t *>(a.table) + (int64_t)layer * a.table_stride;
+    const int64_t act_off = (int64_t)layer * a.act_stride;
+    const uint16_t *hbase = static_cast<const uint16_t *>(a.h) + act_off;
+    const uint16_t *sbase = a.shared ? static_cast<const uint16_t *>(a.shared) + act_off : nullptr;
+    const uint16_t *rbase = NORM ? hbase : (a.residual ? static_cast<const uint16_t *>(a.residual) + act_off : nullptr);
+    uint16_t *obase = static_cast<uint16_t *>(a.out) + act_off;
+    const uint16_t *Wr = static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N;
+    const uint16_t *lnw = NORM ? static_cast<const uint16_t *>(a.ln_w) + (int64_t)layer * d : nullptr;
+    const int32_t *order = nullptr;
+    if (a.plan && plan_ok(a))
+        order = a.plan + plan_layout(T).order;
+
+    const int dlast = d - 8;
+    // Items are dealt out as in the streaming kernel: in round `it` workgroup g's wave w takes item
+    // (it * G + g) * 8 + w of the visiting order, so that at any time the whole grid works on one window of the
+    // order (equal ids meet in L2) and every wave walks through the whole order (waves with cheap, repeated ids
+    // and waves with ids seen once do not end up in different workgroups).  A tile is four rounds: column
+    // 4w + q of the workgroup's k-th tile is the item of wave w in round 4k + q.
+    const int G = gridDim.x, g = blockIdx.x;
+    const int round_items = G * WPB;
+    auto item_of = [&](int it, int w) { return (it * G + g) * WPB + w; };
+
+    // the wave's first token: its first row pieces go in flight before anything else
+    int item = item_of(0, wave);
+    Visit cur = item < T ? visit(order, item) : Visit{0, false};
+    int64_t row = item < T ? (int64_t)__builtin_amdgcn_readfirstlane(a.rowsrc[cur.t]) : -1;
+    bool valid = row >= 0 && row < a.rows;
+    uint4 r[R];
+    auto first_fill = [&]() {
+        if (valid) {
+            const uint16_t *rp0 = table + row * (int64_t)N * d;
+            if (cur.single)
+                ring_load<R, true>(r, rp0, d, min(col0, dlast));
+            else
+                ring_load<R, false>(r, rp0, d, min(col0, dlast));
+        }
+    };
+    first_fill();
+
+    const int npieces = d >> 3;                 // 16-byte pieces per row of h
+    const int steps = (npieces + 1) >> 1;       // matrix instructions over the whole of d (two pieces each)
+    const int spw = (steps + WPB - 1) / WPB;    // per wave
+    const int s_begin = wave * spw, s_end = min(steps, s_begin + spw);
+
+    for (int k = 0; item_of(TPW * k, 0) < T; ++k) {
+        // ---- 1. partial router products of this wave's part of d, all 32 tokens x N experts
+        {
+            const int pitem = item_of(TPW * k + (n & (TPW - 1)), n / TPW);
+            int tok = -1;
+            if (pitem < T)
+                tok = order ? (int)((uint32_t)order[pitem] & ~PLAN_SINGLE) : pitem;
+            const uint16_t *hrow = hbase + (int64_t)max(tok, 0) * d;
+            f32x16 acc[MB];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    acc[mb][e] = 0.f;
+            float ss = 0.f;
+            // the loads of PB steps are issued together (all addresses clamped into the row, what lies past the
+            // end of d is masked to zero afterwards), then the steps' matrix instructions follow
+            for (int s0 = s_begin; s0 < s_end; s0 += PB) {
+                uint4 hv[PB];
+                uint16_t wraw[PB][MB][8];
+                uint4 lw[NORM ? PB : 1];
+#pragma unroll
+                for (int u = 0; u < PB; ++u) {
+                    const int piece = min(2 * (s0 + u) + half, npieces - 1);
+                    const int kp = piece * 8;
+                    hv[u] = *reinterpret_cast<const uint4 *>(hrow + kp);
+                    if constexpr (NORM)
+                        lw[u] = *reinterpret_cast<const uint4 *>(lnw + kp);
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            wraw[u][mb][e] = Wr[(int64_t)(kp + e) * N + mb * 32 + n];
+                }
+#pragma unroll
+                for (int u = 0; u < PB; ++u) {
+                    const bool on = s0 + u < s_end && 2 * (s0 + u) + half < npieces;
+                    const uint32_t mask = on ? 0xffffffffu : 0u;
+                    hv[u].x &= mask; hv[u].y &= mask; hv[u].z &= mask; hv[u].w &= mask;
+                    uint4 wv[MB];
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        wv[mb].x = ((uint32_t)wraw[u][mb][0] | ((uint32_t)wraw[u][mb][1] << 16)) & mask;
+                        wv[mb].y = ((uint32_t)wraw[u][mb][2] | ((uint32_t)wraw[u][mb][3] << 16)) & mask;
+                        wv[mb].z = ((uint32_t)wraw[u][mb][4] | ((uint32_t)wraw[u][mb][5] << 16)) & mask;
+                        wv[mb].w = ((uint32_t)wraw[u][mb][6] | ((uint32_t)wraw[u][mb][7] << 16)) & mask;
+                    }
+                    if constexpr (NORM) {
+                        // x_k * ln_w_k exactly, as a bf16 hi + lo pair (two matrix instructions per block)
+                        ss += sumsq8(hv[u]);
+                        const uint32_t xp[4] = {hv[u].x, hv[u].y, hv[u].z, hv[u].w};
+                        const uint32_t lp[4] = {lw[u].x, lw[u].y, lw[u].z, lw[u].w};
+                        uint32_t ph[4], pl[4];
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const float a0 = bf16lo(xp[q]) * bf16lo(lp[q]), a1 = bf16hi(xp[q]) * bf16hi(lp[q]);
+                            ph[q] = cvt_pk_bf16(a0, a1);
+                            pl[q] = cvt_pk_bf16(a0 - bf16lo(ph[q]), a1 - bf16hi(ph[q]));
+                        }
+                        const uint4 vh = make_uint4(ph[0], ph[1], ph[2], ph[3]), vl = make_uint4(pl[0], pl[1], pl[2], pl[3]);
+#pragma unroll
+                        for (int mb = 0; mb < MB; ++mb) {
+                            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wv[mb]),
+                                                                              __builtin_bit_cast(bf16x8, vh), acc[mb], 0, 0, 0);
+                            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wv[mb]),
+                                                                              __builtin_bit_cast(bf16x8, vl), acc[mb], 0, 0, 0);
+                        }
+                    } else {
+#pragma unroll
+                        for (int mb = 0; mb < MB; ++mb)
+                            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wv[mb]),
+                                                                              __builtin_bit_cast(bf16x8, hv[u]), acc[mb], 0, 0, 0);
+                    }
+                }
+            }
+            // lane l holds token l % 32 and, in elements 4q..4q+3, experts 8q + 4*(l/32) + 0..3 of the block
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        part[wave][mb * 32 + 8 * q + 4 * half + e][n] = acc[mb][4 * q + e];
+            if constexpr (NORM)
+                ssq[wave][lane] = ss;
+        }
+        __syncthreads();
+
+        // ---- 2. gates of this wave's own tokens: lane = expert, two tokens (half-waves) per pass
+#pragma unroll
+        for (int p = 0; p < TPW / 2; ++p) {
+            const int pos = wave * TPW + 2 * p + half;
+            float z[MB];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                z[mb] = 0.f;
+#pragma unroll
+                for (int w = 0; w < WPB; ++w)
+                    z[mb] += part[w][mb * 32 + n][pos];
+            }
+            if constexpr (NORM) {
+                float s2 = 0.f;
+#pragma unroll
+                for (int w = 0; w < WPB; ++w)
+                    s2 += ssq[w][pos] + ssq[w][32 + pos];
+                const float rs = __builtin_amdgcn_rsqf(s2 / (float)d + a.ln_eps);
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+                    z[mb] *= rs;
+            }
+            float m = z[0];
+#pragma unroll
+            for (int mb = 1; mb < MB; ++mb)
+                m = fmaxf(m, z[mb]);
+            m = span_reduce<16, 1, OpMax>(m);
+            float e[MB], s = 0.f;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                e[mb] = __expf(z[mb] - m);
+                s += e[mb];
+            }
+            s = span_reduce<16, 1, OpAdd>(s);
+            const int pitem = item_of(TPW * k + 2 * p + half, wave);
+            int tok = -1;
+            if (pitem < T)
+                tok = order ? (int)((uint32_t)order[pitem] & ~PLAN_SINGLE) : pitem;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                const float g = e[mb] / s;
+                gl[pos][mb * 32 + n] = g;
+                if (a.gates_dbg && tok >= 0)
+                    a.gates_dbg[((int64_t)layer * T + tok) * N + mb * 32 + n] = g;
+            }
+        }
+        wave_lds_fence();
+
+        // ---- 3. gather and gate-weighted sum, one token at a time
+        for (int q = 0; q < TPW; ++q) {
+            if (item >= T)
+                break;
+            const int t = cur.t;
+            const int nitem = item + round_items;
+            const Visit nxt = nitem < T ? visit(order, nitem) : Visit{0, false};
+            const int64_t nrow = nitem < T ? (int64_t)__builtin_amdgcn_readfirstlane(a.rowsrc[nxt.t]) : -1;
+            const bool nvalid = nrow >= 0 && nrow < a.rows;
+            if (!valid && lane == 0 && a.err_flag)
+                atomicOr(a.err_flag, 1);
+            if (a.rows_dbg && layer == 0 && lane == 0)
+                a.rows_dbg[t] = valid ? row : -1;
+            const float g = gl[wave * TPW + q][lane & (N - 1)];
+            const uint16_t *rp = table + (valid ? row : 0) * (int64_t)N * d;
+            const uint16_t *nrp = table + (nvalid ? nrow : 0) * (int64_t)N * d;
+            for (int c0 = 0; c0 < d; c0 += 512) {
+                const int cc = c0 + col0;
+                const bool on = cc < d;
+                const bool last = c0 + 512 >= d;
+                const int64_t off = (int64_t)t * d + cc;
+                uint4 sv = make_uint4(0, 0, 0, 0), rv = make_uint4(0, 0, 0, 0);
+                if (on && sbase)
+                    sv = ld16_stream<false>(sbase + off);
+                if (on && rbase)
+                    rv = ld16_stream<false>(rbase + off);
+                float acc[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    acc[e] = 0.f;
+#pragma unroll
+                for (int hf = 0; hf < H; ++hf) {
+                    float gs[R];
+#pragma unroll
+                    for (int j = 0; j < R; ++j)
+                        gs[j] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, g), hf * R + j));
+                    if (valid) {
+#pragma unroll
+                        for (int j = 0; j < R; ++j)
+                            fma8(acc, gs[j], r[j]);
+                    }
+                    const bool more = hf + 1 < H;
+                    const uint16_t *fb = more ? rp + (int64_t)(hf + 1) * R * d : (last ? nrp : rp);
+                    const int fcol = min(more ? cc : (last ? col0 : cc + 512), dlast);
+                    if (more || !last ? valid : nvalid) {
+                        if (more || !last ? cur.single : nxt.single)
+                            ring_load<R, true>(r, fb, d, fcol);
+                        else
+                            ring_load<R, false>(r, fb, d, fcol);
+                    }
+                }
+                add8(acc, sv);
+                add8(acc, rv);
+                if (on)
+                    st16_stream(obase + off, pack8_cvt(acc));
+            }
+            row = nrow;
+            valid = nvalid;
+            cur = nxt;
+            item = nitem;
+        }
+        __syncthreads();    // the next tile's partial products overwrite what step 2 read
+    }
+}
+
+}  // namespace
+
+namespace mole {
+
+bool tile_forward_applies(int N, int d, int T, int L)
+{
+    // one tile per workgroup slot at least: below that the streaming kernel fills the chip better
+    return N == 32 && d % 8 == 0 && (int64_t)((T + TILE - 1) / TILE) * L >= 2 * (int64_t)num_cus();
+}
+
+mole_status launch_tile_forward(const TileArgs &a, int N, int L, hipStream_t stream)
+{
+    if (N != 32)
+        return fail(MOLE_EUNSUPPORTED, "tile forward: N=%d (only 32)", N);
+    const int ntiles = (a.T + TILE - 1) / TILE;
+    // two workgroups of eight waves per CU (four waves per SIMD), all resident
+    int64_t cap = (int64_t)num_cus() * 2 / L;
+    if (cap < 1)
+        cap = 1;
+    int64_t gx = ntiles;
+    if (gx > cap) {
+        const int64_t per = (ntiles + cap - 1) / cap;
+        gx = (ntiles + per - 1) / per;
+    }
+    const dim3 grid((unsigned)gx, (unsigned)L), block(TILE_WPB * 64);
+    if (a.ln_w)
+        hipLaunchKernelGGL((fwd_bf16_tile_kernel<32, true>), grid, block, 0, stream, a);
+    else
+        hipLaunchKernelGGL((fwd_bf16_tile_kernel<32, false>), grid, block, 0, stream, a);
+    MOLE_HIP_CHECK(hipGetLastError());
+    return MOLE_OK;
+}
+
+}  // namespace mole

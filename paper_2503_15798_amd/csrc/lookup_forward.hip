@@ -884,6 +884,19 @@ mole_status launch_fast_n(const FwdArgs &a, hipStream_t stream, bool long_runs)
             return a.residual ? launch_run<N, 4, false, true>(a, stream) : launch_run<N, 4, false, false>(a, stream);
         }
     }
+    // Large batches at N = 32: the tile kernel (router of 32 tokens at a time on the matrix pipe, fwd_tile.hip).
+    // 16384 tokens, d = 1024, against the streaming kernel: Zipf ids 111 against 117 us, with a plan 96 against
+    // 101 us; with the norm inside 115 against 135 us and 102 against 119 us; uniform ids 222 against 212 us
+    // (187 against 184 us with a plan), with the norm inside 224 against 236 us (189 against 203 us).
+    // MOLE_FWD_TILE = 1 / 2 forces / forbids it.
+    if constexpr (N == 32) {
+        const int want = knob(KNOB_FWD_TILE);
+        if (want == 1 || (want != 2 && tile_forward_applies(N, a.d, a.T, a.L))) {
+            TileArgs t{a.table, a.slot ? a.slot : a.ids, a.h, a.W_r, a.shared, a.residual, a.out, a.gates_dbg, a.rows_dbg,
+                       a.err_flag, a.plan, a.ln_w, a.ln_eps, a.table_stride, a.act_stride, a.rows, a.T, a.d};
+            return launch_tile_forward(t, N, a.L, stream);
+        }
+    }
     // large batches: keep the read-once activations out of the caches (not with a plan: there a token's
     // activation rows are visited in id order and the plain load measures 2.5 % faster)
     const bool nta = knob_or(KNOB_FWD_NTA, (int64_t)a.T * a.L >= 8192 && !a.plan ? 1 : 2) == 1;

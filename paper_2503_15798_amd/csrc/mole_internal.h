@@ -34,6 +34,7 @@ enum Knob {
     KNOB_FWD_NTA,           // MOLE_FWD_NTA          1 = non-temporal activation loads, 2 = plain
     KNOB_FWD_SPLIT,         // MOLE_FWD_SPLIT        1 = one 512-column chunk per work item, 2 = whole tokens
     KNOB_FWD_RUN,           // MOLE_FWD_RUN          1 / 2 = force / forbid the run kernel for planned calls
+    KNOB_FWD_TILE,          // MOLE_FWD_TILE         1 / 2 = force / forbid the tile kernel (N = 32)
     KNOB_FWD_GENERIC,       // MOLE_FWD_GENERIC      1 = the generic forward kernel for every shape
     KNOB_DEDUP_GENERIC,     // MOLE_DEDUP_GENERIC    1 = the generic dedup kernel for every size
     KNOB_BUILD_HIDDEN,      // MOLE_BUILD_HIDDEN     1 (or "f16") / 2 (or "split"): hidden activation of the build

@@ -315,6 +315,45 @@ def test_run_kernel_shapes(tuning, d, N, T, V, dist):
         check_against_oracle(w, table, ids, li, residual=residual, dedup=True)
 
 
+@pytest.mark.parametrize("d,T,V,dist", [
+    (1024, 1, 8, "uniform"),           # one token: 31 empty columns in the tile
+    (1024, 31, 40, "zipf"),            # a ragged single tile
+    (1024, 33, 10, "zipf"),            # one full tile and one token
+    (1024, 1000, 300, "zipf"),         # many tiles, ragged tail
+    (520, 70, 20, "uniform"),          # d / 8 odd: the last router step has one 16-byte piece; ragged chunk
+    (2048, 130, 64, "zipf"),           # four chunks per token
+    (72, 40, 12, "uniform"),           # fewer router steps than waves
+    (1024, 600, 5000, "uniform"),      # mostly distinct ids
+])
+def test_tile_kernel_shapes(tuning, d, T, V, dist):
+    """The tile kernel (N = 32, large batches), forced on small shapes, against the oracle: plain and planned
+    order, with and without a residual, out-of-range ids."""
+    tuning("MOLE_FWD_TILE", "1")
+    w = wl.scaled(wl.CONFIGS["prefill410m"], V=V, d=d, N=32, T=T, L=1, ids=dist, name=f"tile d{d} T{T} V{V}")
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    li["W_r"] = wl.to_storage(wl.storage_to_f64(li["W_r"], w.dtype) * 5.0, w.dtype)
+    ids = ids.copy()
+    if T > 8:
+        ids[[2, T // 2]] = [V + 5, -3]
+    for residual in (False, True):
+        for dedup in (False, True):
+            check_against_oracle(w, table, ids, li, residual=residual, dedup=dedup)
+
+
+def test_tile_kernel_layers_and_slot(tuning):
+    """Several layers in one launch of the tile kernel, rows through the slot indirection."""
+    tuning("MOLE_FWD_TILE", "1")
+    w = wl.scaled(wl.CONFIGS["prefill410m"], V=300, d=1024, N=32, T=200, L=1)
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
+    uniq, inv = np.unique(ids, return_inverse=True)
+    ref_out, ref_g, _, _ = oracle.lookup_forward(table, ids, li["h"], li["W_r"], li["shared"])
+    for dedup in (False, True):
+        got = run_forward(w, np.ascontiguousarray(table[uniq]), ids, li, slot=inv.astype(np.int32), dedup=dedup)
+        np.testing.assert_array_equal(got["rows"], inv)
+        assert_close(wl.storage_to_f64(got["out"], w.dtype), ref_out, w.dtype, "tile kernel, staged rows")
+        np.testing.assert_allclose(got["gates"], ref_g, rtol=2e-5, atol=1e-7)
+
+
 def test_run_kernel_saturated_router_returns_the_row_exactly(tuning):
     """A gate of exactly 1 splits into hi = 1, lo = 0, and 0 into 0 + 0: the row comes back bit for bit."""
     tuning("MOLE_FWD_RUN", "1")
@@ -408,19 +447,23 @@ def _whole_output_check(w, tabs_d, ids, lis, out, what):
 
 @pytest.mark.parametrize("name,mode", [
     ("prefill410m", "plain"), ("prefill410m", "plan"), ("prefill410m", "plan+runs"),
+    ("prefill410m", "plain, streaming kernel"), ("prefill410m", "plan, streaming kernel"),
     ("prefill410m_uniform", "plain"), ("prefill410m_uniform", "plan"),
     ("decode1b_4e", "plain"), ("decode1b_4e", "plan"), ("decode410m_n2", "plain"), ("decode410m_n4", "plan"),
     ("decode410m_n8", "plain")])
-def test_full_size_single_layer(name, mode):
+def test_full_size_single_layer(tuning, name, mode):
     """One layer of the benchmark shapes through the single-layer entry point: all T tokens (16384 for the
-    prefills, whose 3.3 GB table puts row offsets beyond 32 bits) against the oracle."""
+    prefills, whose 3.3 GB table puts row offsets beyond 32 bits) against the oracle.  The prefills take the
+    tile kernel by default; the streaming kernel is forced for two more cases."""
     torch = torch_mod()
+    if "streaming" in mode:
+        tuning("MOLE_FWD_TILE", "2")
     w = wl.scaled(wl.CONFIGS[name], L=1)
     tab_d = wl.device_table(w, 0, "cuda")
     if name.startswith("prefill"):
         assert tab_d.numel() * 2 > 2 ** 31                           # byte offsets beyond 32 bits
     ids, li = wl.token_ids(w), wl.layer_inputs(w)
-    got = run_forward(w, None, ids, li, dedup=mode != "plain", runs=mode == "plan+runs", table_dev=tab_d, want_dbg=True)
+    got = run_forward(w, None, ids, li, dedup=mode.startswith("plan"), runs=mode == "plan+runs", table_dev=tab_d, want_dbg=True)
     np.testing.assert_array_equal(got["rows"], ids)
     assert got["err"] == 0
     _whole_output_check(w, tab_d[None], ids, [li], got["out"][None], f"{name} ({mode})")

@@ -106,6 +106,21 @@ def test_run_kernel(tuning, d, N, T, V):
     check(w, wl.random_table(w), ids, inp, dedup=True, shared=False)
 
 
+@pytest.mark.parametrize("d,T,V", [(1024, 203, 64), (1024, 1, 4), (520, 37, 16), (2048, 70, 500), (72, 33, 9)])
+def test_tile_kernel(tuning, d, T, V):
+    """The tile kernel with the norm inside (state times norm weight as a bf16 hi + lo pair on the matrix pipe,
+    1 / rms on the logits), forced on small shapes."""
+    tuning("MOLE_FWD_TILE", "1")
+    w = wl.scaled(wl.CONFIGS["prefill410m"], V=V, d=d, N=32, T=T, L=1, name=f"norm tile d{d} T{T}")
+    ids = wl.token_ids(w).copy()
+    if T > 2:
+        ids[T // 3] = -2
+    inp = inputs(w)
+    for dedup in (False, True):
+        check(w, wl.random_table(w), ids, inp, dedup=dedup)
+        check(w, wl.random_table(w), ids, inp, dedup=dedup, shared=False)
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_seeded_random_shapes(tuning, seed):
     """Shapes and launch switches drawn from the documented ranges: every dispatch path of the fused-norm
@@ -115,7 +130,7 @@ def test_seeded_random_shapes(tuning, seed):
     N = int(rng.choice([1, 2, 3, 4, 8, 12, 16, 32, 40, 64]))
     T = int(rng.integers(1, 90))
     V = int(rng.integers(max(2, T // 8), 400))
-    for var in ("MOLE_FWD_SPLIT", "MOLE_FWD_NTA", "MOLE_FWD_RUN"):
+    for var in ("MOLE_FWD_SPLIT", "MOLE_FWD_NTA", "MOLE_FWD_RUN", "MOLE_FWD_TILE"):
         tuning(var, str(int(rng.integers(1, 3))))
     tuning("MOLE_FWD_WPB", str(int(rng.choice([4, 8]))))
     w = wl.scaled(wl.CONFIGS["decode410m"], V=V, d=d, N=N, T=T, L=1, ids=str(rng.choice(["zipf", "uniform"])),
