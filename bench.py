@@ -236,7 +236,7 @@ def rates(w, acc, ms, distinct=None):
     return out
 
 
-KERNEL_SOURCES = ("lookup_forward.hip", "fwd_common.h", "mole_internal.h")
+KERNEL_SOURCES = ("lookup_forward.hip", "fwd_tile.hip", "fwd_common.h", "mole_internal.h")
 
 
 def kernel_source_hash():
@@ -368,8 +368,14 @@ def main():
     head = rates(w, acc, ms_step, distinct)
     alg_bytes = acc.forward_bytes_per_token(w.d, w.N, w.elem_bytes) * w.T * w.L
     achieved = alg_bytes / (ms_kernel * 1e-3) / 1e9
-    # the kernel the launcher picks for this call (--runs passes MOLE_FLAG_RUNS: the run kernel for N <= 32)
-    kernel = "fwd_bf16_run_kernel" if args.plan and args.runs and w.N <= 32 else "fwd_bf16_stream_kernel"
+    # the kernel the launcher picks for this call (--runs passes MOLE_FLAG_RUNS: the run kernel for N <= 32; N = 32
+    # with at least two rounds of eight tokens per CU: the tile kernel)
+    if args.plan and args.runs and w.N <= 32:
+        kernel = "fwd_bf16_run_kernel"
+    elif w.N == 32 and ((w.T + 7) // 8) * w.L >= 2 * torch.cuda.get_device_properties(0).multi_processor_count:
+        kernel = "fwd_bf16_tile_kernel"
+    else:
+        kernel = "fwd_bf16_stream_kernel"
     kernel_tag = f"{kernel[:-7]}_{w.name}" + ("_plan" if args.plan else "")
     traffic, traffic_src = read_traffic(kernel_tag)
     moved_bytes = w.L * acc.forward_bytes_moved(w.T, int(round(distinct)), w.d, w.N, w.elem_bytes)

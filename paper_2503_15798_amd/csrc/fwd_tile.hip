@@ -323,24 +323,24 @@ namespace mole {
 
 bool tile_forward_applies(int N, int d, int T, int L)
 {
-    // one tile per workgroup slot at least: below that the streaming kernel fills the chip better
-    return N == 32 && d % 8 == 0 && (int64_t)((T + TILE - 1) / TILE) * L >= 2 * (int64_t)num_cus();
+    // every workgroup slot (two per CU) gets at least one round of eight tokens: below that the streaming
+    // kernel, with its smaller work items, fills the chip better
+    return N == 32 && d % 8 == 0 && (int64_t)((T + TILE_WPB - 1) / TILE_WPB) * L >= 2 * (int64_t)num_cus();
 }
 
 mole_status launch_tile_forward(const TileArgs &a, int N, int L, hipStream_t stream)
 {
     if (N != 32)
         return fail(MOLE_EUNSUPPORTED, "tile forward: N=%d (only 32)", N);
-    const int ntiles = (a.T + TILE - 1) / TILE;
-    // two workgroups of eight waves per CU (four waves per SIMD), all resident
-    int64_t cap = (int64_t)num_cus() * 2 / L;
+    // Two workgroups of eight waves per CU (four waves per SIMD), all resident, and every one of them in every
+    // round of eight items (a last tile of fewer than four rounds is cheaper than CUs with unequal numbers of
+    // workgroups: 12288 tokens as 384 full tiles took 99 us, as 512 workgroups of three rounds 86 us).
+    int64_t cap = (int64_t)num_cus() * knob_or(KNOB_FWD_WGS_PER_CU, 2) / L;
     if (cap < 1)
         cap = 1;
-    int64_t gx = ntiles;
-    if (gx > cap) {
-        const int64_t per = (ntiles + cap - 1) / cap;
-        gx = (ntiles + per - 1) / per;
-    }
+    int64_t gx = (a.T + TILE_WPB - 1) / TILE_WPB;      // one round each at least
+    if (gx > cap)
+        gx = cap;
     const dim3 grid((unsigned)gx, (unsigned)L), block(TILE_WPB * 64);
     if (a.ln_w)
         hipLaunchKernelGGL((fwd_bf16_tile_kernel<32, true>), grid, block, 0, stream, a);

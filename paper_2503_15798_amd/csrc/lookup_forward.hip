@@ -884,10 +884,11 @@ mole_status launch_fast_n(const FwdArgs &a, hipStream_t stream, bool long_runs)
             return a.residual ? launch_run<N, 4, false, true>(a, stream) : launch_run<N, 4, false, false>(a, stream);
         }
     }
-    // Large batches at N = 32: the tile kernel (router of 32 tokens at a time on the matrix pipe, fwd_tile.hip).
-    // 16384 tokens, d = 1024, against the streaming kernel: Zipf ids 111 against 117 us, with a plan 96 against
-    // 101 us; with the norm inside 115 against 135 us and 102 against 119 us; uniform ids 222 against 212 us
-    // (187 against 184 us with a plan), with the norm inside 224 against 236 us (189 against 203 us).
+    // Large batches at N = 32 (at least eight tokens for each of two workgroups per CU): the tile kernel (router of
+    // 32 tokens at a time on the matrix pipe, fwd_tile.hip).  d = 1024, against the streaming kernel, same process:
+    // 16384 tokens with Zipf ids 112 against 119 us, with a plan 96 against 101 us; with the norm inside 115 against
+    // 136 us and 101 against 119 us; 4096 tokens 33 against 35 us; uniform ids: within 2 % either way up to 12288
+    // tokens, 222 against 212 us at 16384 (186 against 183 us with a plan), 272 against 280 us at 20000.
     // MOLE_FWD_TILE = 1 / 2 forces / forbids it.
     if constexpr (N == 32) {
         const int want = knob(KNOB_FWD_TILE);
