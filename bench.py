@@ -422,8 +422,10 @@ def main():
                    "algorithmic_GBps": head["algorithmic_GBps"], "moved_GBps": head["moved_GBps"]},
         "roofline": roofline,
         "cpu_baseline": cpu,
-        "other_ms": {k: round(v["ms"] if isinstance(v, dict) else v, 5) for k, v in other.items()
-                     if not isinstance(v, dict) or "ms" in v},
+        # one number per secondary entry (ms); the small shapes' dedup-kernel times only with --full
+        "other_ms": {k: round(v["ms"] if isinstance(v, dict) else v, 4) for k, v in other.items()
+                     if (not isinstance(v, dict) or "ms" in v)
+                     and not (k.endswith("_dedup_kernel_ms") and not k.startswith(("decode410m_dedup", "prefill410m")))},
     }
     if args.full:
         line["other"] = other
