@@ -445,6 +445,8 @@ struct TileArgs {
 };
 bool tile_forward_applies(int N, int d, int T, int L);
 mole_status launch_tile_forward(const TileArgs &a, int N, int L, hipStream_t stream);
+// steps 1 and 2 of the tile kernel alone: gates [T, N] fp32 = softmax(h . W_r), N = 32
+mole_status launch_tile_router(const void *h, const void *W_r, float *gates, int T, int d, int N, hipStream_t stream);
 
 }  // namespace mole
 #endif

@@ -50,7 +50,8 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int N, bool NORM>
+// GATES: steps 1 and 2 only; the gates go to a.gates_dbg [L, T, N] (the router of mole_shared_ffn_forward)
+template <int N, bool NORM, bool GATES = false>
 __global__ __launch_bounds__(TILE_WPB * 64) __attribute__((amdgpu_waves_per_eu(4)))
 void fwd_bf16_tile_kernel(TileArgs a)
 {
@@ -97,7 +98,7 @@ void fwd_bf16_tile_kernel(TileArgs a)
     // the wave's first token: its first row pieces go in flight before anything else
     int item = item_of(0, wave);
     Visit cur = item < T ? visit(order, item) : Visit{0, false};
-    int64_t row = item < T ? (int64_t)__builtin_amdgcn_readfirstlane(a.rowsrc[cur.t]) : -1;
+    int64_t row = !GATES && item < T ? (int64_t)__builtin_amdgcn_readfirstlane(a.rowsrc[cur.t]) : -1;
     bool valid = row >= 0 && row < a.rows;
     uint4 r[R];
     auto first_fill = [&]() {
@@ -109,7 +110,8 @@ void fwd_bf16_tile_kernel(TileArgs a)
                 ring_load<R, false>(r, rp0, d, min(col0, dlast));
         }
     };
-    first_fill();
+    if constexpr (!GATES)
+        first_fill();
 
     const int npieces = d >> 3;                 // 16-byte pieces per row of h
     const int steps = (npieces + 1) >> 1;       // matrix instructions over the whole of d (two pieces each)
@@ -253,7 +255,7 @@ void fwd_bf16_tile_kernel(TileArgs a)
         wave_lds_fence();
 
         // ---- 3. gather and gate-weighted sum, one token at a time
-        for (int q = 0; q < TPW; ++q) {
+        for (int q = 0; q < (GATES ? 0 : TPW); ++q) {
             if (item >= T)
                 break;
             const int t = cur.t;
@@ -346,6 +348,21 @@ mole_status launch_tile_forward(const TileArgs &a, int N, int L, hipStream_t str
         hipLaunchKernelGGL((fwd_bf16_tile_kernel<32, true>), grid, block, 0, stream, a);
     else
         hipLaunchKernelGGL((fwd_bf16_tile_kernel<32, false>), grid, block, 0, stream, a);
+    MOLE_HIP_CHECK(hipGetLastError());
+    return MOLE_OK;
+}
+
+mole_status launch_tile_router(const void *h, const void *W_r, float *gates, int T, int d, int N, hipStream_t stream)
+{
+    if (N != 32 || d % 8 || !gates)
+        return fail(MOLE_EUNSUPPORTED, "tile router: N=%d, d=%d", N, d);
+    TileArgs a{};
+    a.h = h; a.W_r = W_r; a.gates_dbg = gates; a.T = T; a.d = d; a.rows = 1;
+    int64_t gx = (T + TILE_WPB - 1) / TILE_WPB;
+    const int64_t cap = (int64_t)num_cus() * 2;
+    if (gx > cap)
+        gx = cap;
+    hipLaunchKernelGGL((fwd_bf16_tile_kernel<32, false, true>), dim3((unsigned)gx), dim3(TILE_WPB * 64), 0, stream, a);
     MOLE_HIP_CHECK(hipGetLastError());
     return MOLE_OK;
 }

@@ -340,8 +340,8 @@ def test_tile_kernel_shapes(tuning, d, T, V, dist):
             check_against_oracle(w, table, ids, li, residual=residual, dedup=dedup)
 
 
-def test_tile_kernel_layers_and_slot(tuning):
-    """Several layers in one launch of the tile kernel, rows through the slot indirection."""
+def test_tile_kernel_with_slot_indirection(tuning):
+    """Rows through the slot indirection (offloaded mode), gates and row indices reported."""
     tuning("MOLE_FWD_TILE", "1")
     w = wl.scaled(wl.CONFIGS["prefill410m"], V=300, d=1024, N=32, T=200, L=1)
     table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w)
@@ -384,9 +384,13 @@ def test_run_kernel_with_slot_indirection(tuning):
 
 
 @pytest.mark.parametrize("dedup", [False, True])
-def test_layer_batched_launch_equals_per_layer_calls(dedup):
+@pytest.mark.parametrize("N,tile", [(16, False), (32, False), (32, True)])
+def test_layer_batched_launch_equals_per_layer_calls(tuning, dedup, N, tile):
+    """tile: the tile kernel forced for the batched launch and for the per-layer calls alike."""
     torch = torch_mod()
-    w = wl.scaled(wl.CONFIGS["decode410m"], V=1024, d=512, N=16, T=70, L=3)
+    if tile:
+        tuning("MOLE_FWD_TILE", "1")
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=1024, d=512, N=N, T=70, L=3)
     ids = wl.token_ids(w)
     tabs = [wl.random_table(w, l) for l in range(w.L)]
     lis = [wl.layer_inputs(w, l) for l in range(w.L)]
