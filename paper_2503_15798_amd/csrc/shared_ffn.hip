@@ -177,7 +177,11 @@ extern "C" mole_status mole_shared_ffn_forward(const void *table, const int32_t 
     if (b1)
         hipLaunchKernelGGL(abs_max_kernel, dim3(16), dim3(256), 0, st, static_cast<const uint16_t *>(b1), (int64_t)D_s,
                            bound + 2);
-    hipLaunchKernelGGL(abs_max_kernel, dim3(cap), dim3(256), 0, st, w2, (int64_t)d * D_s, bound + 3);
+    // eight 16-byte pieces per thread: every workgroup ends with a look at one word of memory, and two thousand of
+    // those in a row cost more than the 8 MB read
+    const int64_t w2_blocks = ((int64_t)d * D_s / 8 + 2047) / 2048;
+    hipLaunchKernelGGL(abs_max_kernel, dim3((unsigned)(w2_blocks < cap ? w2_blocks : cap)), dim3(256), 0, st, w2,
+                       (int64_t)d * D_s, bound + 3);
     const int forced = knob(KNOB_BUILD_HIDDEN) == 1 ? MODE_F16 : (knob(KNOB_BUILD_HIDDEN) == 2 ? MODE_SPLIT : 0);
     hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(64), 0, st, bound, mode, forced);
     hipLaunchKernelGGL(bf16_to_f16_rows_kernel, dim3(cap), dim3(256), 0, st, w2, w2f16, (int64_t)d, D_s, (int)lay.ldh);
