@@ -214,7 +214,9 @@ __device__ __forceinline__ void dequant_pair8(float (&acc)[8], half2_t gab, uint
         }
 }
 
-template <int N, int BITS, int WPB, bool NORM>
+// DBG: a.gates_dbg / a.rows_dbg are written (a variant of its own: the two pointers stay out of the scalar
+// registers of the kernel that serves every other call)
+template <int N, int BITS, int WPB, bool NORM, bool DBG>
 __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_bytes)
 {
     extern __shared__ uint4 smem[];
@@ -322,16 +324,19 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
         const bool nvalid = nrow >= 0 && nrow < a.rows;
         if (!valid && lane == 0 && a.err_flag)
             atomicOr(a.err_flag, 1);
-        if (a.rows_dbg && layer == 0 && lane == 0)
+        if (DBG && a.rows_dbg && layer == 0 && lane == 0)
             a.rows_dbg[t] = valid ? row : -1;
 
         const float g = router_gate<NR, false, NORM, N>(router, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1, a.ln_eps, lnw);
-        if (a.gates_dbg && (lane & (LPJ - 1)) == 0 && lane / LPJ < N)
+        if (DBG && a.gates_dbg && (lane & (LPJ - 1)) == 0 && lane / LPJ < N)
             a.gates_dbg[((int64_t)layer * T + t) * N + lane / LPJ] = g;
         load_h2<false>(h0, h1, hbase + (int64_t)nt * d, d, lane);
-        // gates into scalar registers: expert j's gate sits in lane j * LPJ (taken per part when there are several)
+        // gates into scalar registers: expert j's gate sits in lane j * LPJ.  NF4 takes them anew for every part of
+        // every chunk: kept across the chunks they are spilled to vector-register lanes and fetched back, which
+        // costs more than the readlanes (NF3, with fewer scalars live, keeps them)
+        constexpr bool GS_ONCE = H == 1 && BITS == 3;
         float gs[R];
-        if constexpr (H == 1) {
+        if constexpr (GS_ONCE) {
 #pragma unroll
             for (int j = 0; j < N; ++j)
                 gs[j] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, g), j * LPJ));
@@ -353,7 +358,7 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
                 acc[e] = 0.f;
 #pragma unroll
             for (int part = 0; part < H; ++part) {
-                if constexpr (H > 1) {
+                if constexpr (!GS_ONCE) {
 #pragma unroll
                     for (int j = 0; j < R; ++j)
                         gs[j] = __builtin_bit_cast(
@@ -418,15 +423,15 @@ mole_status nf_params_status(int d, int bits, int block, int scale_bytes, const 
     return MOLE_OK;
 }
 
-template <int N, int BITS, bool NORM>
-mole_status launch_nf(const NfArgs &a, int scale_bytes, hipStream_t stream)
+template <int N, int BITS, bool NORM, bool DBG>
+mole_status launch_nf_dbg(const NfArgs &a, int scale_bytes, hipStream_t stream)
 {
     // N >= 32: the router weight (64 KiB at N = 32, d = 1024) leaves room for two workgroups per CU, so the
     // waves that the registers allow (three or four per SIMD) have to come from larger workgroups
     constexpr int WPB = N >= 32 ? 8 : 4;
     const size_t lds = router_lds_bytes(a.d, N < 4 ? 4 : N) + (NORM ? norm_lds_bytes(a.d) : 0) + 64;
     static std::atomic<size_t> lds_seen{0};
-    MOLE_HIP_CHECK(ensure_dynamic_lds(lds_seen, reinterpret_cast<const void *>(&fwd_nf_kernel<N, BITS, WPB, NORM>), lds));
+    MOLE_HIP_CHECK(ensure_dynamic_lds(lds_seen, reinterpret_cast<const void *>(&fwd_nf_kernel<N, BITS, WPB, NORM, DBG>), lds));
     int per_cu = (int)((160 * 1024) / (lds + PAIR_TABLE_LDS));
     constexpr int WG_CAP = N <= 4 ? 8 : 4;       // waves per SIMD the registers allow (four-wave workgroups)
     if (per_cu > WG_CAP)
@@ -445,10 +450,17 @@ mole_status launch_nf(const NfArgs &a, int scale_bytes, hipStream_t stream)
             ipw = (ipw + 1) / 2;
         gx = (a.T + WPB * ipw - 1) / (WPB * ipw);
     }
-    hipLaunchKernelGGL((fwd_nf_kernel<N, BITS, WPB, NORM>), dim3((unsigned)gx, (unsigned)a.L), dim3(WPB * 64), lds, stream,
+    hipLaunchKernelGGL((fwd_nf_kernel<N, BITS, WPB, NORM, DBG>), dim3((unsigned)gx, (unsigned)a.L), dim3(WPB * 64), lds, stream,
                        a, scale_bytes);
     MOLE_HIP_CHECK(hipGetLastError());
     return MOLE_OK;
+}
+
+template <int N, int BITS, bool NORM>
+mole_status launch_nf(const NfArgs &a, int scale_bytes, hipStream_t stream)
+{
+    return a.gates_dbg || a.rows_dbg ? launch_nf_dbg<N, BITS, NORM, true>(a, scale_bytes, stream)
+                                     : launch_nf_dbg<N, BITS, NORM, false>(a, scale_bytes, stream);
 }
 
 template <int BITS, bool NORM>
