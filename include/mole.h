@@ -90,7 +90,7 @@ int mole_version(void);
  * 512-column chunk per work item, 2 = whole tokens), "MOLE_FWD_RUN" (1 / 2 = force / forbid the
  * kernel of MOLE_FLAG_RUNS for planned calls), "MOLE_FWD_TILE" (1 / 2 = force / forbid the tile kernel, which
  * serves N = 32 only), "MOLE_FWD_GENERIC" (1 = generic forward kernel),
- * "MOLE_DEDUP_GENERIC" (1 = generic dedup kernel), "MOLE_BUILD_HIDDEN" (1 = fp16, 2 = bf16 hi/lo
+ * "MOLE_DEDUP_GENERIC" (1 = generic dedup kernel, 2 = never the eight-workgroup kernel), "MOLE_BUILD_HIDDEN" (1 = fp16, 2 = bf16 hi/lo
  * hidden activation), "MOLE_BUILD_SMALL_TILE" (1 = the 256 x 128 GEMM).  value 0 restores the
  * library's own choice.  Each knob starts from the environment variable of the same name, read once
  * when the first knob is looked up.  Process-wide; takes effect for calls issued afterwards.

@@ -36,7 +36,7 @@ enum Knob {
     KNOB_FWD_RUN,           // MOLE_FWD_RUN          1 / 2 = force / forbid the run kernel for planned calls
     KNOB_FWD_TILE,          // MOLE_FWD_TILE         1 / 2 = force / forbid the tile kernel (N = 32)
     KNOB_FWD_GENERIC,       // MOLE_FWD_GENERIC      1 = the generic forward kernel for every shape
-    KNOB_DEDUP_GENERIC,     // MOLE_DEDUP_GENERIC    1 = the generic dedup kernel for every size
+    KNOB_DEDUP_GENERIC,     // MOLE_DEDUP_GENERIC    1 = the generic dedup kernel for every size, 2 = never the split kernel
     KNOB_BUILD_HIDDEN,      // MOLE_BUILD_HIDDEN     1 (or "f16") / 2 (or "split"): hidden activation of the build
     KNOB_BUILD_SMALL_TILE,  // MOLE_BUILD_SMALL_TILE 1 = the 256 x 128 GEMM for every shape
     KNOB_COUNT

@@ -79,14 +79,35 @@ def test_generic_kernel(tuning, T, V, dist):
     check_plan(plan, ids, V, uniq, U)
 
 
+@pytest.mark.parametrize("T,V,dist", [(4097, 50304, "zipf"), (8192, 50304, "uniform"), (16384, 50304, "zipf"),
+                                      (16384, 7, "uniform"), (9000, 200, "zipf"), (12000, 524288, "uniform")])
+@pytest.mark.parametrize("split", [True, False])
+def test_large_batches_one_and_eight_workgroups(tuning, T, V, dist, split):
+    """Batches of more than 4096 tokens take the kernel that spreads the id ranges over eight workgroups;
+    the one-workgroup kernel stays reachable.  Out-of-range ids (the last bucket of the last workgroup), ids at
+    both ends of the range, V smaller than the number of workgroups' words."""
+    if not split:
+        tuning("MOLE_DEDUP_GENERIC", "2")
+    ids = wl.make_ids(T, V, seed=7 * T + V, dist=dist)
+    ids[[1, T // 2, T - 1]] = [V + 3, -1, V]
+    ids[[0, 2]] = [0, V - 1]
+    uniq, inv, U, err, plan = run_dedup(ids, V)
+    r_uniq, r_inv, r_U, r_err = oracle.dedup(ids, V)
+    assert U == r_U and err == r_err == 1
+    np.testing.assert_array_equal(uniq, r_uniq)
+    np.testing.assert_array_equal(inv, r_inv)
+    check_plan(plan, ids, V, uniq, U)
+
+
 @pytest.mark.parametrize("seed", range(16))
 def test_seeded_random_batches(tuning, seed):
     """T, V, the id distribution, the share of out-of-range ids and the kernel drawn at random."""
     rng = np.random.default_rng(4000 + seed)
     T = int(rng.choice([1, 2, 63, 64, 65, 1023, 1024, 1025, 4097, 9000, 16384, 16385, 30000]))
     V = int(rng.choice([1, 2, 31, 32, 33, 1000, 50304, 200000]))
-    if rng.integers(3) == 0:
-        tuning("MOLE_DEDUP_GENERIC", "1")
+    which = int(rng.integers(4))
+    if which < 2:
+        tuning("MOLE_DEDUP_GENERIC", str(which + 1))        # 1: the generic kernel, 2: one workgroup only
     ids = wl.make_ids(T, V, seed=seed, dist=str(rng.choice(["zipf", "uniform"])))
     bad = rng.random(T) < float(rng.choice([0.0, 0.01, 0.5]))
     ids = np.where(bad, rng.choice(np.array([-1, V, V + 7, 2 ** 31 - 1], np.int64), T), ids).astype(np.int32)
