@@ -240,13 +240,18 @@ KERNEL_SOURCES = ("lookup_forward.hip", "fwd_tile.hip", "fwd_common.h", "mole_in
 
 
 def kernel_source_hash():
-    """Hash of the forward kernels' sources: a counter summary under profiles/ records the hash it was taken
-    on, so a summary of an older kernel is recognised as such."""
+    """Hash of the forward kernels' sources (comments and blank lines left out, so that only a change of code
+    counts): a counter summary under profiles/ records the hash it was taken on, so a summary of an older
+    kernel is recognised as such."""
     import hashlib
+    import re
     h = hashlib.sha256()
     for name in KERNEL_SOURCES:
-        with open(os.path.join(ROOT, "paper_2503_15798_amd", "csrc", name), "rb") as f:
-            h.update(f.read())
+        with open(os.path.join(ROOT, "paper_2503_15798_amd", "csrc", name), "r") as f:
+            text = f.read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        lines = [re.sub(r"//.*$", "", ln).rstrip() for ln in text.splitlines()]
+        h.update("\n".join(ln for ln in lines if ln.strip()).encode())
     return h.hexdigest()[:16]
 
 

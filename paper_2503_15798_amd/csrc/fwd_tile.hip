@@ -1,4 +1,4 @@
-// Tile kernel of the forward for large batches and many experts (N = 32, 64).
+// Tile kernel of the forward for large batches at N = 32.
 //
 // Paper: Sec. 3.2 (router equation) and Sec. 3.3 (inference-layer equation), as in lookup_forward.hip.
 //
