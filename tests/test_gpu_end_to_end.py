@@ -184,11 +184,13 @@ def test_foreign_plan_is_flagged_and_ignored(N):
             assert_close(wl.storage_to_f64(to_host(out_d, w.dtype), w.dtype), ref, w.dtype, "foreign plan ignored")
 
 
-def test_hip_graph_replay_matches_eager():
+@pytest.mark.parametrize("N,T", [(16, 96), (32, 5000)])
+def test_hip_graph_replay_matches_eager(N, T):
     """Capture dedup + forward (two layers, per-layer launches) in a HIP graph; every replay, with eager
-    work and synchronisation in between, must equal the eager result."""
+    work and synchronisation in between, must equal the eager result.  (16, 96): the one-workgroup dedup and the
+    streaming kernel; (32, 5000): the eight-workgroup dedup and the tile kernel."""
     import torch
-    w = wl.scaled(wl.CONFIGS["decode410m"], V=2000, d=1024, N=16, T=96, L=2)
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=2000, d=1024, N=N, T=T, L=2)
     tabs = [to_dev(wl.random_table(w, l), w.dtype) for l in range(w.L)]
     lis = [wl.layer_inputs(w, l) for l in range(w.L)]
     hs = [to_dev(li["h"], w.dtype) for li in lis]
