@@ -11,11 +11,17 @@ storage and per-token traffic to 25.3 % and 19.5 %.  Those ratios pin the scale 
 
 The NF-k data type, as the QLoRA paper defines it: 2^k levels that are quantiles of N(0,1) normalised
 to [-1, 1], asymmetric so that 0 is a level: the quantiles of a positive range with 2^(k-1)+1 points
-and of a negative range with 2^(k-1) points are united and the duplicate zero dropped.  The paper does
-not say where the outermost quantile is taken (the quantile of probability 1 is infinite).  Reading
-used here and in the library: the cumulative probabilities of the positive range run evenly from 1/2
-to delta = 1 - 1/(2 * 2^k), those of the negative range evenly from 1/2 down to 1 - delta, and the
-levels are divided by the quantile at delta.
+and of a negative range with 2^(k-1) points are united and the duplicate zero dropped.  The quantile of
+probability 1 is infinite, so the outermost one is taken at delta < 1: the cumulative probabilities of
+the positive range run evenly from 1/2 to delta, those of the negative range evenly from 1/2 down to
+1 - delta, and the levels are divided by the quantile at delta.  delta is half a step short of 1, where
+a step is 1/(2^k - 1) when the zero shared by both halves is counted once and 1/2^k when it is counted
+twice; the data type takes the mean of the two: delta = 1 - (1/(2 (2^k - 1)) + 1/(2 2^k)) / 2
+(0.9677083 for k = 4).  PIN: the QLoRA paper prints the sixteen NF4 values in its appendix on the exact
+values of the data type (tests/golden/nf4_levels.txt); this construction reproduces them to fp32
+rounding, a delta of 1 - 1/(2 2^k) or 1 - 1/(2 (2^k - 1)) alone misses them in the third decimal.  No
+NF3 table is printed anywhere: its values are the same construction at k = 3, PARITY UNPINNED beyond
+the structure (exact -1, 0, +1, 3 negative and 4 positive levels, evenly spaced in probability).
 
 Quantisation rule (both sides take every decision in fp32):
     s    = max |x| over the block (exact; for a bf16 table it is itself a bf16 value, so a 16-bit scale
@@ -40,7 +46,8 @@ def codebook(bits: int) -> np.ndarray:
     if bits not in (2, 3, 4, 5, 6, 7, 8):
         raise ValueError("bits out of range")
     half = 2 ** (bits - 1)
-    delta = 1.0 - 1.0 / (2.0 * 2 ** bits)
+    n = 2 ** bits
+    delta = 1.0 - (1.0 / (2.0 * (n - 1)) + 1.0 / (2.0 * n)) / 2.0
     pos = scipy.stats.norm.ppf(np.linspace(0.5, delta, half + 1))        # 0 ... Q(delta): 2^(k-1)+1 points
     neg = scipy.stats.norm.ppf(np.linspace(1.0 - delta, 0.5, half))[:-1]  # -Q(delta) ... : its zero dropped
     levels = np.concatenate([neg, pos]) / pos[-1]

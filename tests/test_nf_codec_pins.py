@@ -1,13 +1,39 @@
 """Pins of the NF4 / NF3 codec oracle (oracle/nf_codec.py) and of the library's level table -- no GPU.
 The oracle derives its levels from scipy's normal quantile function; the library carries a table from
-its own generator (standard-library inverse CDF).  Neither may be checked against itself."""
+its own generator (standard-library inverse CDF).  Neither may be checked against itself: the NF4 values
+are held against the table the data type's own paper prints (tests/golden/nf4_levels.txt)."""
+import os
+
 import numpy as np
 import pytest
+import scipy.optimize
 import scipy.stats
 
 from oracle import nf_codec as nf
 from paper_2503_15798_amd import binding as mb
 from paper_2503_15798_amd import workloads as wl
+
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "nf4_levels.txt")
+
+
+def printed_nf4_levels():
+    with open(GOLDEN) as f:
+        return np.array([float(line) for line in f if line.strip() and not line.startswith("#")])
+
+
+def test_nf4_levels_are_the_printed_ones():
+    """The data type's own paper prints the sixteen NF4 values; the oracle's construction must land on them
+    (they were produced in float32 there, hence a few float32 roundings of slack, 1e-6).  The two plausible
+    misreadings of the outermost quantile miss them by 2e-3 and more."""
+    printed = printed_nf4_levels()
+    assert printed.shape == (16,)
+    np.testing.assert_allclose(nf.codebook(4).astype(np.float64), printed, rtol=0, atol=1e-6)
+    for delta in (1 - 1 / 32, 1 - 1 / 30):                     # a step of 1/16, or of 1/15, alone
+        pos = scipy.stats.norm.ppf(np.linspace(0.5, delta, 9))
+        neg = scipy.stats.norm.ppf(np.linspace(1 - delta, 0.5, 8))[:-1]
+        wrong = np.concatenate([neg, pos]) / pos[-1]
+        assert np.abs(wrong - printed).max() > 1.5e-3
 
 
 @pytest.mark.parametrize("bits", [4, 3])
@@ -17,13 +43,21 @@ def test_levels_follow_the_definition(bits):
     assert len(lv) == n and (np.diff(lv) > 0).all()
     assert lv[0] == -1.0 and lv[-1] == 1.0 and lv[half - 1] == 0.0           # exact -1, 0, +1
     assert (lv < 0).sum() == half - 1 and (lv > 0).sum() == half            # asymmetric: one more positive level
-    # the levels are evenly spaced in probability on each side (that is what "quantiles" means)
-    top = scipy.stats.norm.ppf(1.0 - 1.0 / (2.0 * n))
+    # the levels are evenly spaced in probability on each side (that is what "quantiles" means); the
+    # outermost probability is not assumed here but recovered from the printed NF4 table: the printed
+    # second-highest level fixes the quantile the levels were divided by
+    printed = printed_nf4_levels()
+    f = lambda top: (scipy.stats.norm.cdf(printed[-2] * top) - 0.5) * 8 / 7 + 0.5 - scipy.stats.norm.cdf(top)
+    top4 = scipy.optimize.brentq(f, 1.0, 3.0)
+    delta4 = scipy.stats.norm.cdf(top4)                                       # 0.96771 from the printed values
+    assert abs(delta4 - (1 - (1 / 30 + 1 / 32) / 2)) < 2e-6
+    delta = 1 - (1 / (2 * (n - 1)) + 1 / (2 * n)) / 2                         # the same rule at this width
+    top = scipy.stats.norm.ppf(delta)
     p = scipy.stats.norm.cdf(lv * top)
-    np.testing.assert_allclose(np.diff(p[half - 1:]), (p[-1] - 0.5) / half, rtol=1e-6)
-    np.testing.assert_allclose(np.diff(p[:half]), (0.5 - p[0]) / (half - 1), rtol=1e-6)
-    np.testing.assert_allclose(p[-1], 1.0 - 1.0 / (2.0 * n), rtol=1e-7)
-    np.testing.assert_allclose(p[0], 1.0 / (2.0 * n), rtol=1e-6)
+    np.testing.assert_allclose(np.diff(p[half - 1:]), (delta - 0.5) / half, rtol=2e-6)
+    np.testing.assert_allclose(np.diff(p[:half]), (delta - 0.5) / (half - 1), rtol=2e-6)
+    np.testing.assert_allclose(p[-1], delta, rtol=1e-7)
+    np.testing.assert_allclose(p[0], 1 - delta, rtol=1e-6)
 
 
 @pytest.mark.parametrize("bits", [4, 3])
