@@ -227,6 +227,31 @@ mole_status mole_layer_forward(const void *table, int64_t table_stride,
                                unsigned flags,
                                const void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Dedup and forward as one call (the lut(input_ids) line of the inference listing, then Sec. 3.2 router equation
+ * and Sec. 3.3 inference-layer equation).  The same results as
+ *     mole_dedup_ids(ids, T, V, uniq, inv, n_uniq, err_flag, workspace, ...) followed by
+ *     mole_lookup_forward_layers(..., MOLE_FLAG_DEDUP, workspace, ...)           (ln_w == NULL) or
+ *     mole_layer_forward(..., x = h, ln_w, ln_eps, ..., MOLE_FLAG_DEDUP, workspace, ...)   (ln_w != NULL),
+ * bit for bit (uniq, inv, n_uniq, out; the plan may list tokens with equal ids in another order).  For large
+ * batches at N = 32 in bf16 (4096 < T <= 16384, L = 1: the prefill shape) the first launch runs the dedup on a
+ * few workgroups and, beside it on all others, the router of every token on the matrix pipe (gates depend on a
+ * token's own h only, not on the plan); a second launch gathers and combines in the plan's order.  The dedup's
+ * time is hidden behind the router's.  Every other shape runs the two calls one after the other.
+ *   h [T,d] dev: the router input, or (ln_w != NULL) the state before the RMSNorm, which is then also the
+ *   residual (residual must be NULL); ln_w [d] dev nullable ([L,d]); uniq, inv [T], n_uniq [1] dev out as in
+ *   mole_dedup_ids; no slot indirection, no debug outputs; strides in elements, ignored for L = 1.
+ *   workspace: dev, mole_dedup_forward_workspace(T, V, N, L) bytes, 16-byte aligned.  After the call its first
+ *   mole_dedup_workspace(T, V) bytes hold the plan, which serves further mole_lookup_forward(MOLE_FLAG_DEDUP)
+ *   calls on the same ids (the other layers of a model); the rest is scratch (the gates). */
+size_t mole_dedup_forward_workspace(int T, int64_t V, int N, int L);
+mole_status mole_dedup_forward(const void *table, int64_t table_stride, const int32_t *ids,
+                               const void *h, const void *ln_w, float ln_eps, const void *W_r,
+                               const void *shared_out, const void *residual,
+                               void *out, int64_t act_stride,
+                               int32_t *uniq, int32_t *inv, int32_t *n_uniq, int32_t *err_flag,
+                               int L, int T, int64_t V, int d, int N, mole_dtype dtype,
+                               void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* The layer with its shared expert evaluated inside the call (Sec. 3.3, inference-layer equation; the
  * "Shared Expert" and "Routed Expert" lines of the inference listing):
  *     s[t,:]   = GELU(h[t,:] . W1^T + b1) . W2^T + b2          FFN_shared(h): two matrices, as a routed expert

@@ -34,7 +34,7 @@ EXPORTS = ("mole_last_error", "mole_version", "mole_build_lut_workspace", "mole_
            "mole_lut_file_read_rows", "mole_lut_file_close", "mole_nf_codebook", "mole_nf_codes_bytes",
            "mole_nf_scales_bytes", "mole_quantize_lut", "mole_lookup_forward_nf", "mole_offload_fetch_nf",
            "mole_layer_forward_nf", "mole_lookup_forward_noalloc", "mole_shared_ffn_workspace",
-           "mole_shared_ffn_forward")
+           "mole_shared_ffn_forward", "mole_dedup_forward_workspace", "mole_dedup_forward")
 
 
 class LutDesc(ctypes.Structure):
@@ -96,6 +96,11 @@ def lib() -> ctypes.CDLL:
     L.mole_layer_forward.argtypes = ([c_void, c_i64, c_void, c_void, c_void, c_void, c_f, c_void, c_void, c_void,
                                       c_i64, c_void, c_void, c_void] +
                                      [c_i32, c_i32, c_i64, c_i32, c_i32, c_i32, c_u, c_void, c_sz, c_void])
+    L.mole_dedup_forward_workspace.restype = c_sz
+    L.mole_dedup_forward_workspace.argtypes = [c_i32, c_i64, c_i32, c_i32]
+    L.mole_dedup_forward.restype = c_i32
+    L.mole_dedup_forward.argtypes = ([c_void, c_i64, c_void, c_void, c_void, c_f, c_void, c_void, c_void, c_void, c_i64] +
+                                     [c_void] * 4 + [c_i32, c_i32, c_i64, c_i32, c_i32, c_i32, c_void, c_sz, c_void])
     L.mole_offload_fetch.restype = c_i32
     L.mole_offload_fetch.argtypes = [c_void, c_i64, c_void, c_void, c_void, c_i64, c_void,
                                      c_i32, c_i32, c_i64, c_i32, c_i32, c_i32, c_void]
@@ -250,6 +255,20 @@ def mole_layer_forward(table, table_stride: int, ids, slot, x, ln_w, ln_eps: flo
                                     _ptr(W_r), _ptr(shared_out), _ptr(out), act_stride, _ptr(gates_dbg),
                                     _ptr(rows_dbg), _ptr(err_flag), L, T, rows, d, N, dtype, flags,
                                     _ptr(workspace), wb, _stream(stream)))
+
+
+def mole_dedup_forward_workspace(T: int, V: int, N: int, L: int = 1) -> int:
+    return lib().mole_dedup_forward_workspace(T, V, N, L)
+
+
+def mole_dedup_forward(table, table_stride: int, ids, h, ln_w, ln_eps: float, W_r, shared_out, residual, out,
+                       act_stride: int, uniq, inv, n_uniq, err_flag, L: int, T: int, V: int, d: int, N: int, dtype: int,
+                       workspace, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().mole_dedup_forward(_ptr(table), table_stride, _ptr(ids), _ptr(h), _ptr(ln_w), ln_eps, _ptr(W_r),
+                                    _ptr(shared_out), _ptr(residual), _ptr(out), act_stride, _ptr(uniq), _ptr(inv),
+                                    _ptr(n_uniq), _ptr(err_flag), L, T, V, d, N, dtype, _ptr(workspace), wb,
+                                    _stream(stream)))
 
 
 def mole_offload_fetch(host_table, host_layer_stride: int, uniq, n_uniq, staging, staging_layer_stride: int,

@@ -14,7 +14,7 @@ OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmole.so")
 
 SOURCES = ["common.hip", "lookup_forward.hip", "fwd_tile.hip", "dedup.hip", "offload_fetch.hip", "lut_file.hip",
-           "build_lut.hip", "nf_quant.hip", "noalloc.hip", "shared_ffn.hip"]
+           "build_lut.hip", "nf_quant.hip", "noalloc.hip", "shared_ffn.hip", "dedup_forward.hip"]
 
 # packed-fp32 instructions are switched off for all device code
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

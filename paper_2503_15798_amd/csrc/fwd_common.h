@@ -445,8 +445,12 @@ struct TileArgs {
 };
 bool tile_forward_applies(int N, int d, int T, int L);
 mole_status launch_tile_forward(const TileArgs &a, int N, int L, hipStream_t stream);
-// steps 1 and 2 of the tile kernel alone: gates [T, N] fp32 = softmax(h . W_r), N = 32
-mole_status launch_tile_router(const void *h, const void *W_r, float *gates, int T, int d, int N, hipStream_t stream);
+// steps 1 and 2 of the tile kernel alone, tokens in their own order: gates [L, T, N] fp32 = softmax(h . W_r), N = 32;
+// ln_w not NULL: h is the state before the RMSNorm the router reads it through
+mole_status launch_tile_router(const void *h, const void *W_r, const void *ln_w, float ln_eps, float *gates, int T,
+                               int d, int N, int L, int64_t act_stride, hipStream_t stream);
+// step 3 alone, gates given (a.gates_dbg is not used), one wave per token in the visiting order
+mole_status launch_tile_gather(const TileArgs &a, const float *gates, int N, int L, hipStream_t stream);
 
 }  // namespace mole
 #endif

@@ -23,7 +23,7 @@
 // of the visiting order); a tile is four rounds of a workgroup.
 // With the RMSNorm inside (NORM), the state times the norm weight enters step 1 exactly, as a bf16 hi + lo pair
 // (two matrix instructions), and 1 / rms scales the logits in step 2.
-#include "fwd_common.h"
+#include "tile_router.h"
 
 namespace {
 using namespace mole;
@@ -50,17 +50,14 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// GATES: steps 1 and 2 only; the gates go to a.gates_dbg [L, T, N] (the router of mole_shared_ffn_forward)
-template <int N, bool NORM, bool GATES = false>
+template <int N, bool NORM>
 __global__ __launch_bounds__(TILE_WPB * 64) __attribute__((amdgpu_waves_per_eu(4)))
 void fwd_bf16_tile_kernel(TileArgs a)
 {
     constexpr int WPB = TILE_WPB;
     constexpr int R = 8;                // row registers (the ring)
-    constexpr int PB = 4;               // router steps whose loads are issued together
-    constexpr int MB = N / 32;          // blocks of 32 experts
     constexpr int H = N / R;
-    constexpr int PROW = TILE + 1;      // padded row of the partial-product array
+    constexpr int PROW = ROUTER_PROW;   // padded row of the partial-product array
     __shared__ float part[WPB][N][PROW];    // partial logits [wave = part of d][expert][token of the tile]
     __shared__ float ssq[NORM ? WPB : 1][64];
     __shared__ float gl[TILE][N];           // gates of the tile
@@ -71,7 +68,6 @@ void fwd_bf16_tile_kernel(TileArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int col0 = lane * 8;
-    const int n = lane & 31, half = lane >> 5;
 
     const uint16_t *table = static_cast<const uint16_t *>(a.table) + (int64_t)layer * a.table_stride;
     const int64_t act_off = (int64_t)layer * a.act_stride;
@@ -98,7 +94,7 @@ void fwd_bf16_tile_kernel(TileArgs a)
     // the wave's first token: its first row pieces go in flight before anything else
     int item = item_of(0, wave);
     Visit cur = item < T ? visit(order, item) : Visit{0, false};
-    int64_t row = !GATES && item < T ? (int64_t)__builtin_amdgcn_readfirstlane(a.rowsrc[cur.t]) : -1;
+    int64_t row = item < T ? (int64_t)__builtin_amdgcn_readfirstlane(a.rowsrc[cur.t]) : -1;
     bool valid = row >= 0 && row < a.rows;
     uint4 r[R];
     auto first_fill = [&]() {
@@ -110,152 +106,26 @@ void fwd_bf16_tile_kernel(TileArgs a)
                 ring_load<R, false>(r, rp0, d, min(col0, dlast));
         }
     };
-    if constexpr (!GATES)
-        first_fill();
-
-    const int npieces = d >> 3;                 // 16-byte pieces per row of h
-    const int steps = (npieces + 1) >> 1;       // matrix instructions over the whole of d (two pieces each)
-    const int spw = (steps + WPB - 1) / WPB;    // per wave
-    const int s_begin = wave * spw, s_end = min(steps, s_begin + spw);
+    first_fill();
 
     for (int k = 0; item_of(TPW * k, 0) < T; ++k) {
-        // ---- 1. partial router products of this wave's part of d, all 32 tokens x N experts
-        {
-            const int pitem = item_of(TPW * k + (n & (TPW - 1)), n / TPW);
-            int tok = -1;
-            if (pitem < T)
-                tok = order ? (int)((uint32_t)order[pitem] & ~PLAN_SINGLE) : pitem;
-            const uint16_t *hrow = hbase + (int64_t)max(tok, 0) * d;
-            f32x16 acc[MB];
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                for (int e = 0; e < 16; ++e)
-                    acc[mb][e] = 0.f;
-            float ss = 0.f;
-            // the loads of PB steps are issued together (all addresses clamped into the row, what lies past the
-            // end of d is masked to zero afterwards), then the steps' matrix instructions follow
-            for (int s0 = s_begin; s0 < s_end; s0 += PB) {
-                uint4 hv[PB];
-                uint16_t wraw[PB][MB][8];
-                uint4 lw[NORM ? PB : 1];
-#pragma unroll
-                for (int u = 0; u < PB; ++u) {
-                    const int piece = min(2 * (s0 + u) + half, npieces - 1);
-                    const int kp = piece * 8;
-                    hv[u] = *reinterpret_cast<const uint4 *>(hrow + kp);
-                    if constexpr (NORM)
-                        lw[u] = *reinterpret_cast<const uint4 *>(lnw + kp);
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            wraw[u][mb][e] = Wr[(int64_t)(kp + e) * N + mb * 32 + n];
-                }
-#pragma unroll
-                for (int u = 0; u < PB; ++u) {
-                    const bool on = s0 + u < s_end && 2 * (s0 + u) + half < npieces;
-                    const uint32_t mask = on ? 0xffffffffu : 0u;
-                    hv[u].x &= mask; hv[u].y &= mask; hv[u].z &= mask; hv[u].w &= mask;
-                    uint4 wv[MB];
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) {
-                        wv[mb].x = ((uint32_t)wraw[u][mb][0] | ((uint32_t)wraw[u][mb][1] << 16)) & mask;
-                        wv[mb].y = ((uint32_t)wraw[u][mb][2] | ((uint32_t)wraw[u][mb][3] << 16)) & mask;
-                        wv[mb].z = ((uint32_t)wraw[u][mb][4] | ((uint32_t)wraw[u][mb][5] << 16)) & mask;
-                        wv[mb].w = ((uint32_t)wraw[u][mb][6] | ((uint32_t)wraw[u][mb][7] << 16)) & mask;
-                    }
-                    if constexpr (NORM) {
-                        // x_k * ln_w_k exactly, as a bf16 hi + lo pair (two matrix instructions per block)
-                        ss += sumsq8(hv[u]);
-                        const uint32_t xp[4] = {hv[u].x, hv[u].y, hv[u].z, hv[u].w};
-                        const uint32_t lp[4] = {lw[u].x, lw[u].y, lw[u].z, lw[u].w};
-                        uint32_t ph[4], pl[4];
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const float a0 = bf16lo(xp[q]) * bf16lo(lp[q]), a1 = bf16hi(xp[q]) * bf16hi(lp[q]);
-                            ph[q] = cvt_pk_bf16(a0, a1);
-                            pl[q] = cvt_pk_bf16(a0 - bf16lo(ph[q]), a1 - bf16hi(ph[q]));
-                        }
-                        const uint4 vh = make_uint4(ph[0], ph[1], ph[2], ph[3]), vl = make_uint4(pl[0], pl[1], pl[2], pl[3]);
-#pragma unroll
-                        for (int mb = 0; mb < MB; ++mb) {
-                            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wv[mb]),
-                                                                              __builtin_bit_cast(bf16x8, vh), acc[mb], 0, 0, 0);
-                            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wv[mb]),
-                                                                              __builtin_bit_cast(bf16x8, vl), acc[mb], 0, 0, 0);
-                        }
-                    } else {
-#pragma unroll
-                        for (int mb = 0; mb < MB; ++mb)
-                            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wv[mb]),
-                                                                              __builtin_bit_cast(bf16x8, hv[u]), acc[mb], 0, 0, 0);
-                    }
-                }
-            }
-            // lane l holds token l % 32 and, in elements 4q..4q+3, experts 8q + 4*(l/32) + 0..3 of the block
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        part[wave][mb * 32 + 8 * q + 4 * half + e][n] = acc[mb][4 * q + e];
-            if constexpr (NORM)
-                ssq[wave][lane] = ss;
-        }
-        __syncthreads();
-
-        // ---- 2. gates of this wave's own tokens: lane = expert, two tokens (half-waves) per pass
-#pragma unroll
-        for (int p = 0; p < TPW / 2; ++p) {
-            const int pos = wave * TPW + 2 * p + half;
-            float z[MB];
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                z[mb] = 0.f;
-#pragma unroll
-                for (int w = 0; w < WPB; ++w)
-                    z[mb] += part[w][mb * 32 + n][pos];
-            }
-            if constexpr (NORM) {
-                float s2 = 0.f;
-#pragma unroll
-                for (int w = 0; w < WPB; ++w)
-                    s2 += ssq[w][pos] + ssq[w][32 + pos];
-                const float rs = __builtin_amdgcn_rsqf(s2 / (float)d + a.ln_eps);
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
-                    z[mb] *= rs;
-            }
-            float m = z[0];
-#pragma unroll
-            for (int mb = 1; mb < MB; ++mb)
-                m = fmaxf(m, z[mb]);
-            m = span_reduce<16, 1, OpMax>(m);
-            float e[MB], s = 0.f;
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                e[mb] = __expf(z[mb] - m);
-                s += e[mb];
-            }
-            s = span_reduce<16, 1, OpAdd>(s);
-            const int pitem = item_of(TPW * k + 2 * p + half, wave);
-            int tok = -1;
-            if (pitem < T)
-                tok = order ? (int)((uint32_t)order[pitem] & ~PLAN_SINGLE) : pitem;
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                const float g = e[mb] / s;
-                gl[pos][mb * 32 + n] = g;
+        // ---- 1. + 2. router of the tile: column c holds the item of wave c / TPW in round TPW * k + c % TPW; the
+        //      gates stay in LDS for step 3
+        router_tile<N, WPB, NORM>(
+            &part[0][0][0], &ssq[0][0], hbase, Wr, lnw, a.ln_eps, d, wave, lane,
+            [&](int c) {
+                const int pitem = item_of(TPW * k + (c & (TPW - 1)), c / TPW);
+                return pitem < T ? (order ? (int)((uint32_t)order[pitem] & ~PLAN_SINGLE) : pitem) : -1;
+            },
+            [&](int c, int tok, int j, float gj) {
+                gl[c][j] = gj;
                 if (a.gates_dbg && tok >= 0)
-                    a.gates_dbg[((int64_t)layer * T + tok) * N + mb * 32 + n] = g;
-            }
-        }
+                    a.gates_dbg[((int64_t)layer * T + tok) * N + j] = gj;
+            });
         wave_lds_fence();
 
         // ---- 3. gather and gate-weighted sum, one token at a time
-        for (int q = 0; q < (GATES ? 0 : TPW); ++q) {
+        for (int q = 0; q < TPW; ++q) {
             if (item >= T)
                 break;
             const int t = cur.t;
@@ -319,6 +189,132 @@ void fwd_bf16_tile_kernel(TileArgs a)
     }
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Steps 1 and 2 alone: gates [L, T, N] fp32 of all tokens, tiles of 32 consecutive tokens dealt round-robin to the
+// workgroups.  Needs no plan, so it can run before (or beside) the dedup.
+// ------------------------------------------------------------------------------------------
+template <int N, bool NORM>
+__global__ __launch_bounds__(TILE_WPB * 64) __attribute__((amdgpu_waves_per_eu(4)))
+void tile_router_kernel(const uint16_t *__restrict__ h, const uint16_t *__restrict__ W_r, const uint16_t *__restrict__ ln_w,
+                        float ln_eps, float *__restrict__ gates, int T, int d, int64_t act_stride)
+{
+    __shared__ float part[TILE_WPB][N][ROUTER_PROW];
+    __shared__ float ssq[NORM ? TILE_WPB : 1][64];
+    const int layer = blockIdx.y;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const uint16_t *hbase = h + (int64_t)layer * act_stride;
+    const uint16_t *Wr = W_r + (int64_t)layer * d * N;
+    const uint16_t *lnw = NORM ? ln_w + (int64_t)layer * d : nullptr;
+    float *gl = gates + (int64_t)layer * T * N;
+    for (int tok0 = blockIdx.x * ROUTER_TILE; tok0 < T; tok0 += gridDim.x * ROUTER_TILE) {
+        router_tile<N, TILE_WPB, NORM>(
+            &part[0][0][0], &ssq[0][0], hbase, Wr, lnw, ln_eps, d, wave, lane,
+            [&](int c) { return tok0 + c < T ? tok0 + c : -1; },
+            [&](int, int tok, int j, float gj) {
+                if (tok >= 0)
+                    gl[(int64_t)tok * N + j] = gj;
+            });
+        __syncthreads();    // the next tile's partial products overwrite what step 2 read
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Gather kernel: step 3 alone, with the gates given ([L, T, N] fp32, written by the GATES variant above).  One wave
+// per token and nothing shared between waves, so the hardware's workgroup dispatcher hands out the tokens: a CU
+// that gets a smaller share of the memory system's bandwidth simply takes fewer tokens (the fused kernel's static
+// partition waits for the slowest CU).  Tokens are taken in the visiting order.  (Giving each of the 8 XCDs one
+// contiguous eighth of the order instead, so that the repeats of a row block meet in one L2, measured 3 % slower
+// with Zipf ids; 8 row registers at eight waves per SIMD instead of 16 at five 2 % slower.)
+// ------------------------------------------------------------------------------------------
+template <int N, int R, int WPB, bool NORM>
+__global__ __launch_bounds__(WPB * 64) __attribute__((amdgpu_waves_per_eu(R <= 8 ? 8 : 4)))
+void fwd_bf16_gather_kernel(TileArgs a, const float *__restrict__ gates)
+{
+    constexpr int H = N / R;
+    const int d = a.d;
+    const int T = a.T;
+    const int layer = blockIdx.y;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int col0 = lane * 8;
+
+    const int item = blockIdx.x * WPB + wave;
+    if (item >= T)
+        return;
+
+    const uint16_t *table = static_cast<const uint16_t *>(a.table) + (int64_t)layer * a.table_stride;
+    const int64_t act_off = (int64_t)layer * a.act_stride;
+    const uint16_t *hbase = static_cast<const uint16_t *>(a.h) + act_off;
+    const uint16_t *sbase = a.shared ? static_cast<const uint16_t *>(a.shared) + act_off : nullptr;
+    const uint16_t *rbase = NORM ? hbase : (a.residual ? static_cast<const uint16_t *>(a.residual) + act_off : nullptr);
+    uint16_t *obase = static_cast<uint16_t *>(a.out) + act_off;
+    const int32_t *order = nullptr;
+    if (a.plan && plan_ok(a))
+        order = a.plan + plan_layout(T).order;
+
+    const int dlast = d - 8;
+    const Visit cur = visit(order, item);
+    const int t = cur.t;
+    const int64_t row = (int64_t)__builtin_amdgcn_readfirstlane(a.rowsrc[t]);
+    const bool valid = row >= 0 && row < a.rows;
+    const float g = gates[((int64_t)layer * T + t) * N + (lane & (N - 1))];
+    const uint16_t *rp = table + (valid ? row : 0) * (int64_t)N * d;
+    uint4 r[R];
+    if (valid) {
+        if (cur.single)
+            ring_load<R, true>(r, rp, d, min(col0, dlast));
+        else
+            ring_load<R, false>(r, rp, d, min(col0, dlast));
+    } else if (lane == 0 && a.err_flag) {
+        atomicOr(a.err_flag, 1);
+    }
+    if (a.rows_dbg && layer == 0 && lane == 0)
+        a.rows_dbg[t] = valid ? row : -1;
+
+    for (int c0 = 0; c0 < d; c0 += 512) {
+        const int cc = c0 + col0;
+        const bool on = cc < d;
+        const bool last = c0 + 512 >= d;
+        const int64_t off = (int64_t)t * d + cc;
+        uint4 sv = make_uint4(0, 0, 0, 0), rv = make_uint4(0, 0, 0, 0);
+        if (on && sbase)
+            sv = ld16_stream<false>(sbase + off);
+        if (on && rbase)
+            rv = ld16_stream<false>(rbase + off);
+        float acc[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            acc[e] = 0.f;
+#pragma unroll
+        for (int hf = 0; hf < H; ++hf) {
+            float gs[R];
+#pragma unroll
+            for (int j = 0; j < R; ++j)
+                gs[j] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, g), hf * R + j));
+            if (valid) {
+#pragma unroll
+                for (int j = 0; j < R; ++j)
+                    fma8(acc, gs[j], r[j]);
+            }
+            const bool more = hf + 1 < H;
+            if (valid && (more || !last)) {
+                const uint16_t *fb = more ? rp + (int64_t)(hf + 1) * R * d : rp;
+                const int fcol = min(more ? cc : cc + 512, dlast);
+                if (cur.single)
+                    ring_load<R, true>(r, fb, d, fcol);
+                else
+                    ring_load<R, false>(r, fb, d, fcol);
+            }
+        }
+        add8(acc, sv);
+        add8(acc, rv);
+        if (on)
+            st16_stream(obase + off, pack8_cvt(acc));
+    }
+}
+
 }  // namespace
 
 namespace mole {
@@ -352,17 +348,39 @@ mole_status launch_tile_forward(const TileArgs &a, int N, int L, hipStream_t str
     return MOLE_OK;
 }
 
-mole_status launch_tile_router(const void *h, const void *W_r, float *gates, int T, int d, int N, hipStream_t stream)
+mole_status launch_tile_router(const void *h, const void *W_r, const void *ln_w, float ln_eps, float *gates, int T,
+                               int d, int N, int L, int64_t act_stride, hipStream_t stream)
 {
     if (N != 32 || d % 8 || !gates)
         return fail(MOLE_EUNSUPPORTED, "tile router: N=%d, d=%d", N, d);
-    TileArgs a{};
-    a.h = h; a.W_r = W_r; a.gates_dbg = gates; a.T = T; a.d = d; a.rows = 1;
-    int64_t gx = (T + TILE_WPB - 1) / TILE_WPB;
-    const int64_t cap = (int64_t)num_cus() * 2;
+    int64_t gx = (T + ROUTER_TILE - 1) / ROUTER_TILE;
+    int64_t cap = (int64_t)num_cus() * 2 / L;
+    if (cap < 1)
+        cap = 1;
     if (gx > cap)
         gx = cap;
-    hipLaunchKernelGGL((fwd_bf16_tile_kernel<32, false, true>), dim3((unsigned)gx), dim3(TILE_WPB * 64), 0, stream, a);
+    const dim3 grid((unsigned)gx, (unsigned)L), block(TILE_WPB * 64);
+    const uint16_t *hp = static_cast<const uint16_t *>(h), *wp = static_cast<const uint16_t *>(W_r);
+    if (ln_w)
+        hipLaunchKernelGGL((tile_router_kernel<32, true>), grid, block, 0, stream, hp, wp, static_cast<const uint16_t *>(ln_w),
+                           ln_eps, gates, T, d, act_stride);
+    else
+        hipLaunchKernelGGL((tile_router_kernel<32, false>), grid, block, 0, stream, hp, wp, nullptr, 0.f, gates, T, d,
+                           act_stride);
+    MOLE_HIP_CHECK(hipGetLastError());
+    return MOLE_OK;
+}
+
+mole_status launch_tile_gather(const TileArgs &a, const float *gates, int N, int L, hipStream_t stream)
+{
+    if (N != 32 || !gates)
+        return fail(MOLE_EUNSUPPORTED, "tile gather: N=%d (only 32) and a gates buffer", N);
+    constexpr int WPB = 4;
+    const dim3 grid((unsigned)((a.T + WPB - 1) / WPB), (unsigned)L);
+    if (a.ln_w)
+        hipLaunchKernelGGL((fwd_bf16_gather_kernel<32, 16, WPB, true>), grid, dim3(WPB * 64), 0, stream, a, gates);
+    else
+        hipLaunchKernelGGL((fwd_bf16_gather_kernel<32, 16, WPB, false>), grid, dim3(WPB * 64), 0, stream, a, gates);
     MOLE_HIP_CHECK(hipGetLastError());
     return MOLE_OK;
 }

@@ -149,7 +149,7 @@ extern "C" mole_status mole_shared_ffn_forward(const void *table, const int32_t 
     // 16384 tokens 8 us against 31 us)
     const bool tile_router = N == 32 && T >= 4096;
     if (tile_router) {
-        rs = launch_tile_router(h, W_r, gates, T, d, N, st);
+        rs = launch_tile_router(h, W_r, nullptr, 0.f, gates, T, d, N, 1, 0, st);
         if (rs == MOLE_OK && gates_dbg)
             MOLE_HIP_CHECK(hipMemcpyAsync(gates_dbg, gates, (size_t)T * N * sizeof(float), hipMemcpyDeviceToDevice, st));
     } else
