@@ -103,6 +103,17 @@ class Layers:
         self.mb.mole_dedup_ids(self.ids[i % N_ID_BATCHES], self.w.T, self.w.V, self.uniq, self.inv, self.n_uniq,
                                self.err, self.plan, stream=stream)
 
+    def dedup_forward(self, i, stream):
+        """mole_dedup_forward: dedup and forward in id order as one call (for large batches at N = 32 the dedup
+        runs beside the router inside one launch; other shapes run the two calls)."""
+        w, mb = self.w, self.mb
+        if not hasattr(self, "ddf_ws"):
+            self.ddf_ws = self.torch.empty((mb.mole_dedup_forward_workspace(w.T, w.V, w.N, w.L) // 4,),
+                                           dtype=self.torch.int32, device="cuda")
+        mb.mole_dedup_forward(self.tabs, w.V * w.N * w.d, self.ids[i % N_ID_BATCHES], self.h, None, 0.0, self.W_r,
+                              self.shared, None, self.out, w.T * w.d, self.uniq, self.inv, self.n_uniq, self.err,
+                              w.L, w.T, w.V, w.d, w.N, self.code, self.ddf_ws, stream=stream)
+
     def make_plans(self, stream):
         """One plan per id batch, computed outside any timed region (a real model computes the plan
         once per batch and reuses it for every MoLE layer)."""
@@ -236,7 +247,7 @@ def rates(w, acc, ms, distinct=None):
     return out
 
 
-KERNEL_SOURCES = ("lookup_forward.hip", "fwd_tile.hip", "fwd_common.h", "mole_internal.h")
+KERNEL_SOURCES = ("lookup_forward.hip", "fwd_tile.hip", "tile_router.h", "fwd_common.h", "mole_internal.h")
 
 
 def kernel_source_hash():
@@ -452,10 +463,10 @@ def also_list(o):
                         "us": round(e["ms"] * 1e3, 2), "bytes": key.split("_")[0]})
     hbm("prefill410m_uniform", "N=32, 16384 tokens, uniform ids (no-reuse control), no plan", "algorithmic_GBps")
     hbm("prefill410m_uniform_forward_with_plan", "the same with the plan of mole_dedup_ids")
-    hbm("prefill410m_uniform_dedup_plus_forward", "the same, dedup inside the timed step")
+    hbm("prefill410m_uniform_dedup_plus_forward", "the same, dedup inside the timed step (mole_dedup_forward)")
     hbm("prefill410m", "N=32, 16384 tokens, Zipf ids, no plan")
     hbm("prefill410m_forward_with_plan", "the same with the plan")
-    hbm("prefill410m_dedup_plus_forward", "the same, dedup inside the timed step")
+    hbm("prefill410m_dedup_plus_forward", "the same, dedup inside the timed step (mole_dedup_forward)")
     hbm("decode410m_forward_with_plan", "headline step with the plan")
     hbm("decode410m_dedup_plus_forward", "headline step, dedup inside the timed step")
     hbm("decode160m", "12 layers x 64 tokens, d=768 (latency regime)")
@@ -493,6 +504,9 @@ def extras(args, torch, mb, wl, acc, stream, L):
     w = L.w
 
     def both(LL):
+        return lambda i: LL.dedup_forward(i, stream)
+
+    def two_calls(LL):
         def f(i):
             LL.dedup(i, stream)
             LL.forward(i, stream, dedup=True)
@@ -600,6 +614,9 @@ def extras(args, torch, mb, wl, acc, stream, L):
         out[name] = rates(ww, acc, ms, LL.distinct())
         ms = time_steps(torch, stream, both(LL), steps, warm)
         out[name + "_dedup_plus_forward"] = rates(ww, acc, ms, LL.distinct())
+        if name.startswith("prefill"):      # mole_dedup_ids, then the planned forward, as two calls
+            ms = time_steps(torch, stream, two_calls(LL), steps, warm)
+            out[name + "_dedup_then_forward_two_calls"] = rates(ww, acc, ms, LL.distinct())
         ms = time_steps(torch, stream, lambda i: LL.dedup(i, stream), steps, warm)
         out[name + "_dedup_kernel_ms"] = ms
         ms = time_steps(torch, stream, planned(LL), steps, warm)

@@ -100,7 +100,7 @@ template <int PER, bool NORM>
 mole_status launch_dedup_route(const DedupArgs &dd, const RouteArgs &ra, hipStream_t stream)
 {
     // the transposed weight in LDS when it fits behind the partial products (d = 1024: 66 of 156 KB)
-    if (ROUTE_LDS_BYTES + router_wt_bytes(ROUTE_N, ra.d) <= DEDUP_LDS_LIMIT && knob(KNOB_FWD_SPLIT) != 2)
+    if (ROUTE_LDS_BYTES + router_wt_bytes(ROUTE_N, ra.d) <= DEDUP_LDS_LIMIT)
         return launch_dedup_route_wt<PER, NORM, true>(dd, ra, stream);
     return launch_dedup_route_wt<PER, NORM, false>(dd, ra, stream);
 }

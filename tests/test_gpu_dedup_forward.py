@@ -111,6 +111,7 @@ def run_fused_two_calls(w, table, ids, li, ni, norm, residual, shared):
     (1024, 32, 50304, 8192, "uniform", False, True, False),   # 8 per thread, few repeats, a residual
     (1024, 32, 2000, 5000, "zipf", True, False, True),        # ragged last tile, the norm inside
     (520, 32, 700, 4100, "zipf", False, False, False),        # ragged second chunk, just above the threshold
+    (1536, 32, 800, 4500, "zipf", False, False, False),       # router weight too large for its transposed LDS copy
     (1024, 32, 3000, 4096, "zipf", False, False, False),      # at the threshold: the two calls
     (1024, 16, 4096, 6000, "zipf", False, True, True),        # N = 16: the two calls
     (768, 16, 2000, 333, "zipf", True, False, False),         # small batch, norm
