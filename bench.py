@@ -51,6 +51,9 @@ def parse_args():
                          "beforehand, one per id batch); for profiling that path")
     ap.add_argument("--runs", action="store_true",
                     help="with --plan: also pass MOLE_FLAG_RUNS (tokens with equal ids summed together on the matrix pipe)")
+    ap.add_argument("--dedup-forward", action="store_true",
+                    help="the timed step is mole_dedup_forward (dedup and forward in id order as one call); for the "
+                         "profiles of the prefill workloads")
     ap.add_argument("--no-extras", action="store_true", help="only the headline workload")
     ap.add_argument("--full", action="store_true", help="also print the complete entries of the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
@@ -369,7 +372,9 @@ def main():
         L.make_plans(stream)
 
     def step(i):
-        if args.plan:
+        if args.dedup_forward:
+            L.dedup_forward(i, stream)
+        elif args.plan:
             L.forward_planned(i, stream, runs=args.runs)
         else:
             L.forward(i, stream)
@@ -386,13 +391,18 @@ def main():
     achieved = alg_bytes / (ms_kernel * 1e-3) / 1e9
     # the kernel the launcher picks for this call (--runs passes MOLE_FLAG_RUNS: the run kernel for N <= 32; N = 32
     # with at least two rounds of eight tokens per CU: the tile kernel)
-    if args.plan and args.runs and w.N <= 32:
+    if args.dedup_forward:
+        # two launches (dedup beside the router, then the gather): the step time stands for both
+        if not (w.N == 32 and w.L == 1 and 4096 < w.T <= 16384):
+            raise SystemExit("--dedup-forward: only workloads the fused launches serve (N = 32, one layer, 4096 < T <= 16384)")
+        kernel = "fwd_bf16_gather_kernel"
+    elif args.plan and args.runs and w.N <= 32:
         kernel = "fwd_bf16_run_kernel"
     elif w.N == 32 and ((w.T + 7) // 8) * w.L >= 2 * torch.cuda.get_device_properties(0).multi_processor_count:
         kernel = "fwd_bf16_tile_kernel"
     else:
         kernel = "fwd_bf16_stream_kernel"
-    kernel_tag = f"{kernel[:-7]}_{w.name}" + ("_plan" if args.plan else "")
+    kernel_tag = f"{kernel[:-7]}_{w.name}" + ("_plan" if args.plan and not args.dedup_forward else "")
     traffic, traffic_src = read_traffic(kernel_tag)
     moved_bytes = w.L * acc.forward_bytes_moved(w.T, int(round(distinct)), w.d, w.N, w.elem_bytes)
     roofline = {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBS,
@@ -433,7 +443,10 @@ def main():
                    "ids": ("zipf(1.1)" if w.ids == "zipf" else w.ids) + ", 16 rotating batches", "mean_distinct_ids": distinct,
                    "table_bytes": table_bytes,
                    "step": "router + softmax + gather + gate-weighted sum + shared add, all layers, one launch"
-                           + (", tokens visited by the plan of mole_dedup_ids (computed beforehand)" if args.plan else ""),
+                           + (", tokens visited by the plan of mole_dedup_ids (computed beforehand)"
+                              if args.plan and not args.dedup_forward else "")
+                           + (", preceded in the same call by the dedup (mole_dedup_forward: two launches)"
+                              if args.dedup_forward else ""),
                    "decode_tokens_per_s": head["tokens_per_s"],
                    "algorithmic_GBps": head["algorithmic_GBps"], "moved_GBps": head["moved_GBps"]},
         "roofline": roofline,
