@@ -412,6 +412,10 @@ def main():
                 "algorithmic_bytes_per_launch": alg_bytes, "moved_bytes_per_launch": moved_bytes,
                 "moved_frac": moved_bytes / (ms_kernel * 1e-3) / 1e9 / HBM_PEAK_GBS, "kernel_ms": ms_kernel}
 
+    if achieved > HBM_PEAK_GBS:
+        # Zipf ids on a large batch: most of the algorithmic bytes are repeats that L2 / Infinity Cache serve
+        roofline["frac_note"] = ("algorithmic bytes count every token's own rows; above 1 it is no fraction of what "
+                                 "HBM delivers: see traffic_frac (counters) and moved_frac (distinct rows once)")
     roofline["launch_us"] = launch_spread(torch, stream, step)
 
     cpu = None
