@@ -176,3 +176,60 @@ def test_host_errors():
     with pytest.raises(mb.MoleError) as e:
         mb.mole_dedup_forward(a, 0, a, a, a, 1e-5, a, None, a, a, 0, a, a, a, None, 1, 100, 1000, 64, 32, mb.MOLE_BF16, a)
     assert e.value.status == mb.MOLE_EINVAL and "residual" in e.value.message
+
+
+def test_hip_graph_replay_of_a_two_layer_step():
+    """A model's use of the call, captured in a HIP graph: layer 0 through mole_dedup_forward (the fused launches),
+    layer 1 through the planned forward on the plan that call left in its workspace.  Every replay, with new ids and
+    eager work in between, must give the bits of the eager two-call path."""
+    import torch
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=2000, d=1024, N=32, T=5000, L=2, seed=9)
+    tabs = [to_dev(wl.random_table(w, l), w.dtype) for l in range(w.L)]
+    lis = [wl.layer_inputs(w, l) for l in range(w.L)]
+    hs, wrs, shs = ([to_dev(li[k], w.dtype) for li in lis] for k in ("h", "W_r", "shared"))
+    ids_d = torch.from_numpy(wl.token_ids(w)).cuda()
+    uq, iv = torch.empty_like(ids_d), torch.empty_like(ids_d)
+    nu = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    err = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    ws = torch.empty((mb.mole_dedup_forward_workspace(w.T, w.V, w.N, 1) // 4,), dtype=torch.int32, device="cuda")
+    nplan = mb.mole_dedup_workspace(w.T, w.V) // 4
+    outs = [torch.zeros_like(h) for h in hs]
+    s = torch.cuda.Stream()
+
+    def step(dst):
+        mb.mole_dedup_forward(tabs[0], 0, ids_d, hs[0], None, 0.0, wrs[0], shs[0], None, dst[0], 0, uq, iv, nu, err, 1,
+                              w.T, w.V, w.d, w.N, DT[w.dtype], ws, stream=s)
+        mb.mole_lookup_forward(tabs[1], ids_d, None, hs[1], wrs[1], shs[1], None, dst[1], None, None, err, w.T, w.V, w.d,
+                               w.N, DT[w.dtype], mb.MOLE_FLAG_DEDUP, ws[:nplan], stream=s)
+
+    with torch.cuda.stream(s):
+        step(outs)
+    s.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            step(outs)
+    plan2 = torch.empty((nplan,), dtype=torch.int32, device="cuda")
+    for rep in range(4):
+        for o in outs:
+            o.zero_()
+        ids_d.copy_(torch.from_numpy(wl.token_ids(w, batch=rep)).cuda())
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        U = int(nu.item())
+        r_uniq, r_inv, r_U, _ = oracle.dedup(ids_d.cpu().numpy(), w.V)
+        assert U == r_U
+        np.testing.assert_array_equal(uq.cpu().numpy()[:U], r_uniq)
+        np.testing.assert_array_equal(iv.cpu().numpy(), r_inv)
+        refs = [torch.zeros_like(o) for o in outs]
+        with torch.cuda.stream(s):
+            mb.mole_dedup_ids(ids_d, w.T, w.V, torch.empty_like(uq), torch.empty_like(iv), torch.zeros_like(nu), err,
+                              plan2, stream=s)
+            for l in range(w.L):
+                mb.mole_lookup_forward(tabs[l], ids_d, None, hs[l], wrs[l], shs[l], None, refs[l], None, None, err, w.T,
+                                       w.V, w.d, w.N, DT[w.dtype], mb.MOLE_FLAG_DEDUP, plan2, stream=s)
+        s.synchronize()
+        for l in range(w.L):
+            assert torch.equal(outs[l].view(torch.int16), refs[l].view(torch.int16)), f"replay {rep}, layer {l}"
+    assert int(err.item()) == 0
