@@ -800,7 +800,8 @@ constexpr size_t LDS_BYTES_PER_CU = 160 * 1024;
 // N <= 4 (asked for: 8; 24 layers x 256 tokens then run one token per wave, 17.5 -> 15.4 us at N = 4,
 // 14.5 -> 12.7 us at N = 2), 4 for N <= 32, 2 above.  Returns the number of workgroups per layer.
 template <int N, int WPB>
-int64_t grid_x(int items, int L, size_t lds, int waves_per_cu = N <= 4 ? 32 : (N <= 32 ? 16 : 8), bool halve_items = false)
+int64_t grid_x(int items, int L, size_t lds, int waves_per_cu = N <= 4 ? 32 : (N <= 32 ? 16 : 8), bool halve_items = false,
+               bool oversubscribe = false)
 {
     int per_cu = (int)(LDS_BYTES_PER_CU / lds);
     const int wave_cap = waves_per_cu / WPB;
@@ -822,6 +823,24 @@ int64_t grid_x(int items, int L, size_t lds, int waves_per_cu = N <= 4 ? 32 : (N
         // 202 us with uniform ids, 116 -> 108 us with Zipf ids; one item per wave is worse again)
         if (halve_items && ipw >= 4 && !knob(KNOB_FWD_WGS_PER_CU))
             ipw = (ipw + 1) / 2;
+        // 8 and 16 experts, tokens in their own order: the all-resident grid is not always the best one.  More than
+        // four items per wave is a static share so long that the launch ends with CUs waiting for the slowest (they
+        // do not get equal shares of the memory system), and a grid that fills less than four fifths of the resident
+        // places (N = 16, 24 x 256 tokens at two per wave: 768 of 1008) leaves wave slots empty for the whole launch.
+        // In both cases: at most four items per wave, and as many as still give a grid of at least 1.4 rounds, the
+        // dispatcher handing out what is not resident at once (just over one round is the worst case: a nearly empty
+        // second one).  24 layers x 256 tokens: 36.8 -> 35.4 us, x 512: 67.1 -> 63.6 us, x 1024: 132 -> 116 us,
+        // x 2048: 248 -> 208 us; N = 8, 24 x 1024: 78.1 -> 75.4 us.  In the order of a plan the all-resident grid
+        // stays (measured 1 to 8 % better there up to 24 x 1024 tokens).
+        if (oversubscribe && !halve_items && N >= 8 && N <= 16 && !knob(KNOB_FWD_WGS_PER_CU)) {
+            auto wgs_at = [&](int64_t c) { return (items + WPB * c - 1) / (WPB * c) * L; };
+            if (ipw > 4 || (N == 16 && ipw >= 2 && wgs_at(ipw) * 5 < resident * 4)) {
+                int64_t c = ipw > 4 ? 4 : ipw - 1;
+                while (c > 1 && wgs_at(c) * 10 < resident * 14)
+                    --c;
+                ipw = c;
+            }
+        }
         gx = (items + WPB * ipw - 1) / (WPB * ipw);
     }
     return gx < 1 ? 1 : gx;
@@ -835,7 +854,8 @@ mole_status launch_fast_dbg(const FwdArgs &a, hipStream_t stream)
     MOLE_HIP_CHECK(ensure_dynamic_lds(
         lds_seen, reinterpret_cast<const void *>(&fwd_bf16_stream_kernel<N, WPB, NTA, SPLIT, NORM, DBG>), lds));
     const int items = SPLIT ? a.T * ((a.d + 511) / 512) : a.T;
-    dim3 grid((unsigned)grid_x<N, WPB>(items, a.L, lds, N <= 4 ? 32 : (N <= 32 ? 16 : 8), N >= 32), (unsigned)a.L);
+    dim3 grid((unsigned)grid_x<N, WPB>(items, a.L, lds, N <= 4 ? 32 : (N <= 32 ? 16 : 8), N >= 32, !SPLIT && !a.plan),
+              (unsigned)a.L);
     hipLaunchKernelGGL((fwd_bf16_stream_kernel<N, WPB, NTA, SPLIT, NORM, DBG>), grid, dim3(WPB * 64), lds, stream, a);
     MOLE_HIP_CHECK(hipGetLastError());
     return MOLE_OK;

@@ -448,6 +448,19 @@ mole_status launch_nf_dbg(const NfArgs &a, int scale_bytes, hipStream_t stream)
         // the tail (T = 16384: 101 -> 92 us); NF3 gains nothing from it
         if (N >= 32 && BITS == 4 && ipw >= 4)
             ipw = (ipw + 1) / 2;
+        // 16 experts, tokens in their own order: more than four tokens per wave is a static share so long that the
+        // launch ends with CUs waiting for the slowest; four per wave (fewer if that grid would be just over one
+        // round of the resident places) and the dispatcher handing out the rest (24 layers x 1024 tokens: NF4
+        // 91.6 -> 77.0 us, NF3 97.4 -> 82.2 us).  Unlike the bf16 forward (lookup_forward.hip, grid_x) a grid that
+        // leaves resident places empty is NOT made finer here: every workgroup builds the pair table and stages the
+        // router weight, and this kernel is bound by instruction issue (24 x 256 at one token per wave: 24.5 -> 27.3 us).
+        if (N == 16 && ipw > 4 && !a.plan && !knob(KNOB_FWD_WGS_PER_CU)) {
+            const int64_t resident = (int64_t)num_cus() * per_cu;
+            int64_t c = 4;
+            while (c > 1 && (a.T + WPB * c - 1) / (WPB * c) * a.L * 10 < resident * 14)
+                --c;
+            ipw = c;
+        }
         gx = (a.T + WPB * ipw - 1) / (WPB * ipw);
     }
     hipLaunchKernelGGL((fwd_nf_kernel<N, BITS, WPB, NORM, DBG>), dim3((unsigned)gx, (unsigned)a.L), dim3(WPB * 64), lds, stream,
