@@ -928,11 +928,17 @@ mole_status launch_fast_n(const FwdArgs &a, hipStream_t stream, bool long_runs)
             return launch_tile_forward(t, N, a.L, stream);
         }
     }
-    // large batches: keep the read-once activations out of the caches (not with a plan: there a token's
-    // activation rows are visited in id order and the plain load measures 2.5 % faster)
-    const bool nta = knob_or(KNOB_FWD_NTA, (int64_t)a.T * a.L >= 8192 && !a.plan ? 1 : 2) == 1;
-    // small launches: one chunk per item (latency regime); never together with the large-batch loads
-    const bool split = knob_or(KNOB_FWD_SPLIT, (int64_t)a.T * a.L <= 2048 ? 1 : 2) == 1 && a.d > 512;
+    // large batches at 32 experts and more: keep the read-once activations out of the caches (uniform ids, 16384
+    // tokens: 201.5 against 204.3 us; not with a plan: there a token's activation rows are visited in id order and
+    // the plain load measures 2.5 % faster).  Up to 16 experts the plain load is level or better at every size
+    // (24 layers x 384 tokens 49.5 against 52.7 us, x 512 62.4 against 65.3, 1 x 16384 62.2 against 63.3).
+    const bool nta = knob_or(KNOB_FWD_NTA, N >= 32 && (int64_t)a.T * a.L >= 8192 && !a.plan ? 1 : 2) == 1;
+    // small launches: one chunk per item (latency regime); never together with the large-batch loads.  Up to 2048
+    // tokens in the launch at 32 experts and more; up to 16 experts whole tokens win earlier (24 layers x 48 tokens:
+    // 15.2 against 16.8 us, x 64: 15.8 against 17.4; 16 x 128 at N = 4, d = 2048: 13.6 against 15.2; one layer of 2048
+    // tokens 14.8 against 15.9, but of 1536 tokens 13.6 against 12.8): up to 1024 tokens, 1536 for a single layer.
+    const int64_t split_max = N >= 32 ? 2048 : (a.L == 1 ? 1536 : 1024);
+    const bool split = knob_or(KNOB_FWD_SPLIT, (int64_t)a.T * a.L <= split_max ? 1 : 2) == 1 && a.d > 512;
     // chunk items of many layers in one launch: eight waves share a staged router weight instead of four
     // (24 layers x 32 tokens: 11.7 -> 11.2 us; a single layer is faster with the smaller workgroups)
     if (split && a.L >= 8 && (int64_t)a.T * ((a.d + 511) / 512) >= 64 && !knob(KNOB_FWD_WPB))
