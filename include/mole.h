@@ -128,7 +128,8 @@ mole_status mole_build_lut(const void *E, const void *W1, const void *b1,
  *     inv[t] = index of ids[t] in uniq, -1 if out of range [T] dev out
  *     *n_uniq = U                                          [1] dev out
  * and, in `workspace`, a plan for mole_lookup_forward(MOLE_FLAG_DEDUP): the token indices sorted
- * by id, each marked if its id occurs once.  One workgroup, presence bitmap in LDS.
+ * by id, each marked if its id occurs once.  Presence bitmap in LDS; one workgroup, eight (each owning an id
+ * range) for batches of more than 4096 tokens.
  * V <= 524288.  err_flag: [1] dev nullable, set to 1 if any id is outside [0, V).
  * workspace: dev, at least mole_dedup_workspace(T, V) bytes.
  * ---------------------------------------------------------------------------------------- */

@@ -6,7 +6,8 @@
 // distinct ids so that each row block crosses the memory fabric once (and, in offloaded mode,
 // the host link once).
 //
-// One workgroup.  A V-bit presence bitmap sits in LDS (V = 50304 -> 6.3 KB): every id sets its
+// One workgroup (eight, each owning an id range, for batches of more than 4096 tokens: dedup_split.h).
+// A V-bit presence bitmap sits in LDS (V = 50304 -> 6.3 KB): every id sets its
 // bit with an LDS atomic OR; a popcount prefix over the bitmap words then gives each present id
 // its rank, which is already the position in ascending order -- no sort.  Tokens are then
 // bucketed by rank with a counting pass (LDS counters when they fit) and scattered, which yields
