@@ -536,3 +536,18 @@ def test_full_size_decode160m_all_layers(plan_mode):
     lis = [wl.layer_inputs(w, l) for l in range(w.L)]
     out = _layers_step(w, tabs, ids, lis, plan_mode)
     _whole_output_check(w, tabs, ids, lis, out, f"decode160m plan={plan_mode}")
+
+
+@pytest.mark.parametrize("N,L,T", [(16, 8, 3000), (16, 24, 512), (16, 24, 200), (8, 8, 3333), (16, 1, 1300), (16, 4, 300)])
+@pytest.mark.parametrize("plan_mode", [False, True])
+def test_oversubscribed_grids(N, L, T, plan_mode):
+    """Launch shapes at 8 and 16 experts whose grid is not the all-resident one (at most four tokens per wave, a
+    finer grid where resident places would stay empty, whole tokens instead of chunks from 1024 tokens on) and, with
+    the plan, the all-resident grid on the same shapes: every output element of every layer against the oracle."""
+    torch = torch_mod()
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=1500, N=N, L=L, T=T, seed=300 + T, name=f"grid N{N} L{L} T{T}")
+    tabs = torch.stack([to_dev(wl.random_table(w, l), w.dtype) for l in range(w.L)])
+    ids = wl.token_ids(w)
+    lis = [wl.layer_inputs(w, l) for l in range(w.L)]
+    out = _layers_step(w, tabs, ids, lis, plan_mode)
+    _whole_output_check(w, tabs, ids, lis, out, f"{w.name} plan={plan_mode}")
