@@ -111,13 +111,24 @@ void fwd_bf16_stream_kernel(FwdArgs a)
     if (a.plan && plan_ok(a))      // a foreign plan: flagged, tokens visited in their own order
         order = a.plan + plan_layout(T).order;
 
-    // the first item's rows go in flight before the router weight is staged.  Lanes past the end
+    // Order of the first requests.  The longest chain is (plan entry ->) id -> rows, so the id is asked for first;
+    // what depends on no id follows while it travels: the first item's router input and the router weight, which
+    // goes to LDS as soon as it is there (its registers are free again before the row registers fill).  Memory
+    // returns a wave's loads in order, so by then the id has arrived too and the rows are requested at once; the
+    // router then runs while they travel.  An earlier version requested the rows first: router input and weight
+    // arrived behind the 16 KB of row pieces, the router could not start before the rows were there, and on a
+    // single-layer call of 256 tokens the waves spent a third of their life waiting that way.  Lanes past the end
     // of a ragged chunk load a clamped (valid) column; their results are never stored.
     const int dlast = d - 8;
     int item = blockIdx.x * WPB + wave;
     Visit cur = item < n_items ? visit(order, SPLIT ? item / nch : item) : Visit{0, false};
     int cbase = SPLIT ? (item % nch) << 9 : 0;      // first column of this item
-    int64_t row = item < n_items ? (int64_t)__builtin_amdgcn_readfirstlane(rowsrc[cur.t]) : -1;
+    const int32_t id_first = item < n_items ? rowsrc[cur.t] : -1;      // requested; used further down
+    uint4 h0, h1;
+    load_h2<NTA>(h0, h1, hbase + (int64_t)cur.t * d, d, lane);
+    fill_router_lds<NR, N>(smem, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
+
+    int64_t row = (int64_t)__builtin_amdgcn_readfirstlane(id_first);
     bool valid = row >= 0 && row < a.rows;
     uint4 r[R];
     if (valid) {
@@ -127,10 +138,6 @@ void fwd_bf16_stream_kernel(FwdArgs a)
         else
             ring_load<R, false>(r, rp0, d, min(cbase + col0, dlast));
     }
-    uint4 h0, h1;
-    load_h2<NTA>(h0, h1, hbase + (int64_t)cur.t * d, d, lane);
-
-    fill_router_lds<NR, N>(smem, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
     const uint4 *lnw = smem + router_lds_bytes(d, NR) / 16;     // NORM: the norm weight behind the router weight
     if constexpr (NORM)
         fill_norm_lds(smem + router_lds_bytes(d, NR) / 16, static_cast<const uint16_t *>(a.ln_w) + (int64_t)layer * d,

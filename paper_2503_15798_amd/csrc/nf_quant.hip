@@ -259,14 +259,21 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
         const half2_t pr = {(_Float16)lv[i & (NLEV - 1)], (_Float16)lv[i >> BITS]};
         cb2[i] = __builtin_bit_cast(uint32_t, pr);
     }
+    // Order of the first requests, as in the bf16 streaming kernel: the id of the wave's first token is asked for
+    // first (the chain id -> code words is the longest), its router input and the router weight follow, the weight
+    // goes to LDS when it is there (by then the id has arrived too: memory returns a wave's loads in order), then the
+    // code words and scales are requested and the router runs while they travel.
+    const int item_first = blockIdx.x * WPB + wave;
+    const int t_first = item_first < T ? visit(order, item_first).t : 0;
+    const int32_t id_first = item_first < T ? rowsrc[t_first] : -1;
+    uint4 h0, h1;
+    load_h2<false>(h0, h1, hbase + (int64_t)t_first * d, d, lane);
     fill_router_lds<NR, N>(router, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
     const uint4 *lnw = smem + router_lds_bytes(d, NR) / 16;     // NORM: the norm weight behind the router weight
     if constexpr (NORM)
         fill_norm_lds(smem + router_lds_bytes(d, NR) / 16, static_cast<const uint16_t *>(a.ln_w) + (int64_t)layer * d,
                       kgroups, WPB * 64);
-    __syncthreads();
 
-    // code words and scales of the wave's first token go in flight before anything else
     // col / block by a multiplication: exact for col < d <= 65535 (col * block < 2^32)
     const uint32_t block_magic = (uint32_t)(0x100000000ull / (uint32_t)a.block) + 1u;
     const int sbytes_is4 = scale_bytes == 4;
@@ -307,15 +314,14 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
         }
     };
     const int dlast = d - 8;
-    int item = blockIdx.x * WPB + wave;
-    int t = item < T ? visit(order, item).t : 0;
-    int64_t row = item < T ? (int64_t)__builtin_amdgcn_readfirstlane(rowsrc[t]) : -1;
+    int item = item_first;
+    int t = t_first;
+    int64_t row = (int64_t)__builtin_amdgcn_readfirstlane(id_first);
     bool valid = row >= 0 && row < a.rows;
     uint32_t cw[R], ch[R], sc[R];
     if (valid)
         load_part(cw, ch, sc, row, min(col0, dlast), 0);
-    uint4 h0, h1;
-    load_h2<false>(h0, h1, hbase + (int64_t)t * d, d, lane);
+    __syncthreads();    // pair table, router weight and norm weight are in LDS
 
     for (; item < T; item += stride) {
         const int nitem = item + stride;
