@@ -15,11 +15,22 @@ struct Visit {
     int t;
     bool single;
 };
+
+// p[i] for a wave-uniform i, read through the scalar cache.  Ids and plan entries are inputs that no kernel of the
+// launch writes, and a wave asks for them one at a time: as vector loads they share the counter of the row loads,
+// memory returns a wave's loads in order, and the wait for the NEXT token's id became a wait for every row piece
+// in flight (the router of a token started only when its rows were there).  Scalar loads are counted apart.
+__device__ __forceinline__ int32_t ld_scalar(const int32_t *p, int i)
+{
+    typedef const __attribute__((address_space(4))) int32_t *const_as_ptr;
+    return reinterpret_cast<const_as_ptr>(reinterpret_cast<uintptr_t>(p))[__builtin_amdgcn_readfirstlane(i)];
+}
+
 __device__ __forceinline__ Visit visit(const int32_t *order, int item)
 {
     Visit v;
     if (order) {
-        const uint32_t o = (uint32_t)__builtin_amdgcn_readfirstlane(order[item]);
+        const uint32_t o = (uint32_t)ld_scalar(order, item);
         v.t = (int)(o & ~PLAN_SINGLE);
         v.single = (o & PLAN_SINGLE) != 0;
     } else {

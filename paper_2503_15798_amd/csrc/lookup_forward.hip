@@ -123,10 +123,27 @@ void fwd_bf16_stream_kernel(FwdArgs a)
     int item = blockIdx.x * WPB + wave;
     Visit cur = item < n_items ? visit(order, SPLIT ? item / nch : item) : Visit{0, false};
     int cbase = SPLIT ? (item % nch) << 9 : 0;      // first column of this item
-    const int32_t id_first = item < n_items ? rowsrc[cur.t] : -1;      // requested; used further down
+    const int32_t id_first = item < n_items ? ld_scalar(rowsrc, cur.t) : -1;      // requested; used further down
     uint4 h0, h1;
     load_h2<NTA>(h0, h1, hbase + (int64_t)cur.t * d, d, lane);
+    // NORM: the norm weight behind the router weight in LDS; it travels with the router weight (asked for behind the
+    // rows it would arrive behind them, and the barrier below would wait for the rows)
+    uint4 *lnw_fill = smem + router_lds_bytes(d, NR) / 16;
+    const uint16_t *lnw_src = static_cast<const uint16_t *>(a.ln_w) + (int64_t)layer * d;
+    uint4 lnw_first = make_uint4(0, 0, 0, 0);
+    if constexpr (NORM)
+        if ((int)threadIdx.x < kgroups)
+            lnw_first = *reinterpret_cast<const uint4 *>(lnw_src + 8 * threadIdx.x);
     fill_router_lds<NR, N>(smem, static_cast<const uint16_t *>(a.W_r) + (int64_t)layer * d * N, kgroups, WPB * 64);
+    if constexpr (NORM) {
+        if ((int)threadIdx.x < kgroups)
+            lnw_fill[threadIdx.x] = lnw_first;
+        for (int i = threadIdx.x + WPB * 64; i < kgroups; i += WPB * 64)
+            lnw_fill[i] = *reinterpret_cast<const uint4 *>(lnw_src + 8 * i);
+    }
+    // every load so far has arrived (the weight's were the last): said out loud, because a lane without a share of the
+    // weight skips the fill's waits, and the compiler would then wait for the router input behind the rows
+    __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0)
 
     int64_t row = (int64_t)__builtin_amdgcn_readfirstlane(id_first);
     bool valid = row >= 0 && row < a.rows;
@@ -138,26 +155,30 @@ void fwd_bf16_stream_kernel(FwdArgs a)
         else
             ring_load<R, false>(r, rp0, d, min(cbase + col0, dlast));
     }
-    const uint4 *lnw = smem + router_lds_bytes(d, NR) / 16;     // NORM: the norm weight behind the router weight
-    if constexpr (NORM)
-        fill_norm_lds(smem + router_lds_bytes(d, NR) / 16, static_cast<const uint16_t *>(a.ln_w) + (int64_t)layer * d,
-                      kgroups, WPB * 64);
+    const uint4 *lnw = lnw_fill;
     __syncthreads();
 
+    // The first item's gates are computed here and every later item's at the bottom of the loop.  At this point the
+    // compiler knows that the router input has arrived (it was waited for before the rows were requested), so the
+    // router runs with the rows in flight.  At the head of a loop it cannot know: loads counted on different paths
+    // meet there, and it waits for every load in flight, the row pieces included.
+    float g = 0.f;
+    if (item < n_items)
+        g = router_gate<NR, NTA, NORM, N>(smem, kgroups, hbase + (int64_t)cur.t * d, d, lane, h0, h1, a.ln_eps, lnw);
+
+    bool bad_seen = false;
     for (; item < n_items; item += stride) {
         const int t = cur.t;
         const int nitem = item + stride;
         const Visit nxt = nitem < n_items ? visit(order, SPLIT ? nitem / nch : nitem) : Visit{0, false};
         const int ncbase = SPLIT ? (nitem % nch) << 9 : 0;
-        const int64_t nrow = nitem < n_items ? (int64_t)__builtin_amdgcn_readfirstlane(rowsrc[nxt.t]) : -1;
+        const int64_t nrow = nitem < n_items ? (int64_t)ld_scalar(rowsrc, nxt.t) : -1;
         const bool nvalid = nrow >= 0 && nrow < a.rows;
         const bool reporter = !SPLIT || cbase == 0;    // one item per token reports flags and debug outputs
-        if (!valid && lane == 0 && a.err_flag)
-            atomicOr(a.err_flag, 1);
+        bad_seen |= !valid;                             // reported once, when the wave is done
         if (DBG && a.rows_dbg && layer == 0 && lane == 0 && reporter)
             a.rows_dbg[t] = valid ? row : -1;
 
-        const float g = router_gate<NR, NTA, NORM, N>(smem, kgroups, hbase + (int64_t)t * d, d, lane, h0, h1, a.ln_eps, lnw);
         if (DBG && a.gates_dbg && reporter && (lane & (LPJ - 1)) == 0 && lane / LPJ < N)
             a.gates_dbg[((int64_t)layer * T + t) * N + lane / LPJ] = g;
         const uint4 x0 = h0, x1 = h1;                  // NORM: the residual of chunks 0 and 1
@@ -243,11 +264,17 @@ void fwd_bf16_stream_kernel(FwdArgs a)
             if (on)
                 st16_stream(obase + off, N >= 32 ? pack8_cvt(acc) : pack8(acc));
         }
+        if (nitem < n_items)        // the next item's gates (its rows are on their way)
+            g = router_gate<NR, NTA, NORM, N>(smem, kgroups, hbase + (int64_t)nxt.t * d, d, lane, h0, h1, a.ln_eps, lnw);
         row = nrow;
         valid = nvalid;
         cur = nxt;
         cbase = ncbase;
     }
+    // an id outside the table: one atomic per wave, here and not in the loop (a memory operation on a branch in
+    // front of the router makes the compiler wait there for every load in flight, the row pieces included)
+    if (bad_seen && lane == 0 && a.err_flag)
+        atomicOr(a.err_flag, 1);
 }
 
 // ------------------------------------------------------------------------------------------
