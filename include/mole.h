@@ -91,7 +91,8 @@ int mole_version(void);
  * kernel of MOLE_FLAG_RUNS for planned calls), "MOLE_FWD_TILE" (1 / 2 = force / forbid the tile kernel, which
  * serves N = 32 only), "MOLE_FWD_GENERIC" (1 = generic forward kernel),
  * "MOLE_DEDUP_GENERIC" (1 = generic dedup kernel, 2 = never the eight-workgroup kernel), "MOLE_BUILD_HIDDEN" (1 = fp16, 2 = bf16 hi/lo
- * hidden activation), "MOLE_BUILD_SMALL_TILE" (1 = the 256 x 128 GEMM).  value 0 restores the
+ * hidden activation), "MOLE_BUILD_SMALL_TILE" (1 = the 256 x 128 GEMM), "MOLE_FFN_GATHER_LAST" (1 = in
+ * mole_shared_ffn_forward every workgroup gathers its table rows behind its main loop).  value 0 restores the
  * library's own choice.  Each knob starts from the environment variable of the same name, read once
  * when the first knob is looked up.  Process-wide; takes effect for calls issued afterwards.
  * MOLE_EINVAL for an unknown name or a negative value. */

@@ -44,7 +44,8 @@ std::atomic<int> g_arch_state[MAX_DEVICES];     // 0 = not checked, 1 = gfx950, 
 
 const char *const KNOB_NAMES[KNOB_COUNT] = {
     "MOLE_FWD_WPB", "MOLE_FWD_WGS_PER_CU", "MOLE_FWD_NTA", "MOLE_FWD_SPLIT", "MOLE_FWD_RUN",
-    "MOLE_FWD_TILE", "MOLE_FWD_GENERIC", "MOLE_DEDUP_GENERIC", "MOLE_BUILD_HIDDEN", "MOLE_BUILD_SMALL_TILE"};
+    "MOLE_FWD_TILE", "MOLE_FWD_GENERIC", "MOLE_DEDUP_GENERIC", "MOLE_BUILD_HIDDEN", "MOLE_BUILD_SMALL_TILE",
+    "MOLE_FFN_GATHER_LAST"};
 std::atomic<int> g_knob[KNOB_COUNT];
 std::once_flag g_knob_once;
 

@@ -51,12 +51,43 @@ struct GemmArgs {
     int64_t table_rows;
     int n_experts;
     int32_t *err_flag;       // nullable
+    int lookup_first;        // 1: every other workgroup (checkerboard over the tile grid) gathers BEFORE its main loop
 };
+
+// acc[0..7] += sum_j gates[t, j] * table[row(t), j, col .. col + 7] (B row pieces in flight at a time); a token whose
+// id is outside the table adds nothing and is flagged by the reporter
+template <int B = 8>
+__device__ __forceinline__ void lookup_rows8(float (&acc)[8], const GemmArgs &g, int t, int col, bool reporter)
+{
+    const int64_t row = g.rowsrc[t];
+    if (row >= 0 && row < g.table_rows) {
+        const int N = g.n_experts;
+        const uint16_t *tp = g.table + (row * N) * (int64_t)g.Nn + col;
+        const float *gp = g.gates + (int64_t)t * N;
+        for (int j0 = 0; j0 < N; j0 += B) {
+            uint4 piece[B];
+            float gj[B];
+#pragma unroll
+            for (int u = 0; u < B; ++u) {
+                const int j = j0 + u < N ? j0 + u : N - 1;
+                piece[u] = *reinterpret_cast<const uint4 *>(tp + (int64_t)j * g.Nn);
+                gj[u] = j0 + u < N ? gp[j] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < B; ++u)
+                fma8(acc, gj[u], piece[u]);
+        }
+    } else if (reporter && g.err_flag) {
+        atomicOr(g.err_flag, 1);
+    }
+}
 
 // Lookup epilogue for one 16-byte piece of the output (8 columns starting at `col` of token `t`): sp holds the
 // tile's fp32 values (product + bias) for these columns.  Adds the residual and the gate-weighted sum of the
-// token's N table rows (8 row pieces in flight at a time), rounds once and stores.
-__device__ __forceinline__ void lookup_piece(const GemmArgs &g, uint16_t *C, const float *sp, int t, int col, bool reporter)
+// token's N table rows, rounds once and stores.
+// with_rows = false: the gate-weighted rows are already part of sp (they were the accumulators' start values)
+__device__ __forceinline__ uint4 lookup_value(const GemmArgs &g, const float *sp, int t, int col, bool reporter,
+                                              bool with_rows = true)
 {
     float acc[8];
 #pragma unroll
@@ -64,28 +95,14 @@ __device__ __forceinline__ void lookup_piece(const GemmArgs &g, uint16_t *C, con
         acc[e] = sp[e];
     if (g.residual)
         add8(acc, *reinterpret_cast<const uint4 *>(g.residual + (int64_t)t * g.ldc + col));
-    const int64_t row = g.rowsrc[t];
-    if (row >= 0 && row < g.table_rows) {
-        const int N = g.n_experts;
-        const uint16_t *tp = g.table + (row * N) * (int64_t)g.Nn + col;
-        const float *gp = g.gates + (int64_t)t * N;
-        for (int j0 = 0; j0 < N; j0 += 8) {
-            uint4 piece[8];
-            float gj[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int j = j0 + u < N ? j0 + u : N - 1;
-                piece[u] = *reinterpret_cast<const uint4 *>(tp + (int64_t)j * g.Nn);
-                gj[u] = j0 + u < N ? gp[j] : 0.f;
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                fma8(acc, gj[u], piece[u]);
-        }
-    } else if (reporter && g.err_flag) {
-        atomicOr(g.err_flag, 1);
-    }
-    *reinterpret_cast<uint4 *>(C + (int64_t)t * g.ldc + col) = pack8(acc);
+    if (with_rows)
+        lookup_rows8(acc, g, t, col, reporter);
+    return pack8(acc);
+}
+
+__device__ __forceinline__ void lookup_piece(const GemmArgs &g, uint16_t *C, const float *sp, int t, int col, bool reporter)
+{
+    *reinterpret_cast<uint4 *>(C + (int64_t)t * g.ldc + col) = lookup_value(g, sp, t, col, reporter);
 }
 
 __device__ __forceinline__ float gelu_f(float x, int act)
@@ -376,6 +393,51 @@ void gemm_nt_direct_kernel(GemmArgs g)
             for (int e = 0; e < 16; ++e)
                 acc[i][j][e] = 0.f;
 
+    // EPI_LOOKUP, g.lookup_first: the workgroups of one colour of a checkerboard over the tile grid gather their
+    // gate-weighted table rows BEFORE the main loop and start the accumulators from them; the others gather behind it.
+    // A tile's rows are 4 MB of memory traffic and its main loop runs on operands from L2: when every workgroup of a
+    // one-round grid gathers at the end, the memory system idles during the main loops and the matrix pipe during the
+    // gathers.  Staging as in the epilogue, the other way round: pieces in row order -> LDS (fp32) -> accumulator layout.
+    bool rows_in_acc = false;
+    if constexpr (EPI == EPI_LOOKUP) {
+        rows_in_acc = g.lookup_first && ((blockIdx.x + blockIdx.y) & 1);
+        if (rows_in_acc) {
+            constexpr int CROW0 = DBN * 4 + 16;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int piece = tid + u * D_THREADS;
+                    const int sr = piece >> 5, sc = piece & 31;
+                    const int row = m0 + (sr >> 5) * 128 + i * 32 + (sr & 31);
+                    float s8[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        s8[e] = 0.f;
+                    if (row < g.M)
+                        lookup_rows8<16>(s8, g, row, n0 + sc * 8, sc == 0);
+                    float *dst = reinterpret_cast<float *>(dsmem + sr * CROW0) + sc * 8;
+                    *reinterpret_cast<float4 *>(dst) = make_float4(s8[0], s8[1], s8[2], s8[3]);
+                    *reinterpret_cast<float4 *>(dst + 4) = make_float4(s8[4], s8[5], s8[6], s8[7]);
+                }
+                __syncthreads();
+                const unsigned char *srow = dsmem + (wm * 32 + (lane & 31)) * CROW0;
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int cl = wn * 64 + j * 32 + 8 * q + 4 * (lane >> 5);
+                        const float4 v = *reinterpret_cast<const float4 *>(srow + cl * 4);
+                        acc[i][j][4 * q + 0] = v.x;
+                        acc[i][j][4 * q + 1] = v.y;
+                        acc[i][j][4 * q + 2] = v.z;
+                        acc[i][j][4 * q + 3] = v.w;
+                    }
+                __syncthreads();
+            }
+        }
+    }
+
     // feed: per K step the tile pair is 64 chunks of 8 rows (A: 0..31, B: 32..63); wave w moves
     // A chunks w, w + 8, w + 16, w + 24 and the same B chunks.  Lane l of a chunk load: row l >> 3,
     // slot l & 7.
@@ -560,21 +622,39 @@ void gemm_nt_direct_kernel(GemmArgs g)
         }
         __syncthreads();
         // write out: 64 rows x 512 bytes per plane = 2048 16-byte pieces, 4 per thread and plane
+        if constexpr (EPI == EPI_LOOKUP) {
+            // values first, stores behind them: a store between two pieces' loads would keep the compiler from
+            // requesting the second piece's rows while the first piece's travel
+            uint4 o[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int piece = tid + u * D_THREADS;
-            const int sr = piece >> 5, sc = piece & 31;
-            const int row = m0 + (sr >> 5) * 128 + i * 32 + (sr & 31);
-            if constexpr (EPI == EPI_LOOKUP) {
+            for (int u = 0; u < 4; ++u) {
+                const int piece = tid + u * D_THREADS;
+                const int sr = piece >> 5, sc = piece & 31;
+                const int row = m0 + (sr >> 5) * 128 + i * 32 + (sr & 31);
+                o[u] = lookup_value(g, reinterpret_cast<const float *>(Cs + sr * CROW) + sc * 8, min(row, g.M - 1), n0 + sc * 8,
+                                    sc == 0, !rows_in_acc);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int piece = tid + u * D_THREADS;
+                const int sr = piece >> 5, sc = piece & 31;
+                const int row = m0 + (sr >> 5) * 128 + i * 32 + (sr & 31);
                 if (row < g.M)
-                    lookup_piece(g, C, reinterpret_cast<const float *>(Cs + sr * CROW) + sc * 8, row, n0 + sc * 8,
-                                 sc == 0);
-            } else if (row < g.M) {
-                uint16_t *cp = C + (int64_t)row * g.ldc + n0 + sc * 8;
-                *reinterpret_cast<u32x4 *>(cp) = *reinterpret_cast<const u32x4 *>(Cs + sr * CROW + sc * 16);
-                if constexpr (EPI == EPI_GELU_SPLIT)
-                    *reinterpret_cast<u32x4 *>(cp + g.c_plane_stride) =
-                        *reinterpret_cast<const u32x4 *>(Cs + CPLANE + sr * CROW + sc * 16);
+                    *reinterpret_cast<uint4 *>(C + (int64_t)row * g.ldc + n0 + sc * 8) = o[u];
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int piece = tid + u * D_THREADS;
+                const int sr = piece >> 5, sc = piece & 31;
+                const int row = m0 + (sr >> 5) * 128 + i * 32 + (sr & 31);
+                if (row < g.M) {
+                    uint16_t *cp = C + (int64_t)row * g.ldc + n0 + sc * 8;
+                    *reinterpret_cast<u32x4 *>(cp) = *reinterpret_cast<const u32x4 *>(Cs + sr * CROW + sc * 16);
+                    if constexpr (EPI == EPI_GELU_SPLIT)
+                        *reinterpret_cast<u32x4 *>(cp + g.c_plane_stride) =
+                            *reinterpret_cast<const u32x4 *>(Cs + CPLANE + sr * CROW + sc * 16);
+                }
             }
         }
         __syncthreads();

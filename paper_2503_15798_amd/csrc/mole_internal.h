@@ -39,6 +39,7 @@ enum Knob {
     KNOB_DEDUP_GENERIC,     // MOLE_DEDUP_GENERIC    1 = the generic dedup kernel for every size, 2 = never the split kernel
     KNOB_BUILD_HIDDEN,      // MOLE_BUILD_HIDDEN     1 (or "f16") / 2 (or "split"): hidden activation of the build
     KNOB_BUILD_SMALL_TILE,  // MOLE_BUILD_SMALL_TILE 1 = the 256 x 128 GEMM for every shape
+    KNOB_FFN_GATHER_LAST,   // MOLE_FFN_GATHER_LAST  1 = shared-FFN call: every workgroup gathers behind its main loop
     KNOB_COUNT
 };
 int knob(Knob k);

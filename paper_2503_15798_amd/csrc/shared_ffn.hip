@@ -200,6 +200,7 @@ extern "C" mole_status mole_shared_ffn_forward(const void *table, const int32_t 
     g2.M = T; g2.Nn = d; g2.K = D_s; g2.epilogue = EPI_LOOKUP; g2.act = (int)act; g2.mode = mode;
     g2.table = static_cast<const uint16_t *>(table); g2.rowsrc = slot ? slot : ids; g2.gates = gates;
     g2.residual = static_cast<const uint16_t *>(residual); g2.table_rows = rows; g2.n_experts = N; g2.err_flag = err_flag;
+    g2.lookup_first = knob(KNOB_FFN_GATHER_LAST) != 1;
 
     g1.epilogue = EPI_GELU_F16; g1.run_mode = MODE_F16; g1.c_plane_stride = 0;
     if (mole_status e = launch_gemm<EPI_GELU_F16, false>(g1, 1, st))

@@ -64,6 +64,20 @@ def test_shapes(tuning, d, D_s, N, T, V, bias, residual, hidden):
     check(w, D_s, table, ids, li, wl.shared_ffn_weights(w, D_s, bias=bias), residual=residual)
 
 
+@pytest.mark.parametrize("gather_last", [0, 1])
+def test_rows_gathered_before_or_behind_the_main_loop(tuning, gather_last):
+    """Every other workgroup of the second product gathers its table rows BEFORE its main loop and starts the
+    accumulators from them (the default), or all gather behind it (MOLE_FFN_GATHER_LAST = 1): both against the
+    oracle, on a tile grid that holds both kinds (3 x 4 tiles, ragged last row tile, an id outside the table in a
+    workgroup of each kind)."""
+    tuning("MOLE_FFN_GATHER_LAST", gather_last)
+    w = wl.scaled(wl.CONFIGS["decode410m"], V=300, d=1024, N=16, T=600, L=1, name=f"shared ffn gather_last={gather_last}")
+    table, li, ids = wl.random_table(w), wl.layer_inputs(w), wl.token_ids(w).copy()
+    ids[10] = -1
+    ids[300] = 300
+    check(w, 512, table, ids, li, wl.shared_ffn_weights(w, 512, bias=True), residual=True)
+
+
 def test_tanh_form_and_large_hidden_values():
     """GELU in its tanh form; then first-layer weights scaled so that pre-activations can leave the fp16 range (the
     bound is then violated and the library must take the hi + lo pair, which has no range limit)."""
