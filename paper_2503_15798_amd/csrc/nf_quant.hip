@@ -348,6 +348,11 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
                 gs[j] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, g), j * LPJ));
         }
 
+        // One block per row (block = d) and all experts in one part: the weights gate x scale are the same for every
+        // chunk of the token, so they are formed for its first chunk only (a tenth of the chunk's vector instructions)
+        half2_t gp[R / 2];
+        float m = 1.f;
+        const bool weights_once = BITS == 4 && H == 1 && nblk == 1;    // NF3 sits at its register limit without it
         for (int c0 = 0; c0 < d; c0 += 512) {
             const int cc = c0 + col0;
             const bool on = cc < d;
@@ -364,29 +369,38 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
                 acc[e] = 0.f;
 #pragma unroll
             for (int part = 0; part < H; ++part) {
-                if constexpr (!GS_ONCE) {
-#pragma unroll
-                    for (int j = 0; j < R; ++j)
-                        gs[j] = __builtin_bit_cast(
-                            float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, g), (part * R + j) * LPJ));
-                }
                 // the products gate x scale as fp16 pairs, then the registers are free for the next part's
                 // words.  They are divided by their largest (m, restored at the end) so that any table scale
                 // fits fp16: the largest weight is 1, and one below 6e-5 of it keeps an absolute error of 3e-8.
                 uint32_t w[R];
-                float gsc[R];
-                float m = 1.17549435e-38f;
 #pragma unroll
-                for (int j = 0; j < R; ++j) {
+                for (int j = 0; j < R; ++j)
                     w[j] = BITS == 4 ? cw[j] : (cw[j] | (ch[j] << 16));
-                    gsc[j] = gs[j] * decode_scale(sc[j], scale_bytes, (j & 1) ? sc_odd ^ (nblk & 1) : sc_odd);
-                    m = fmaxf(m, fabsf(gsc[j]));
-                }
-                const float rm = __builtin_amdgcn_rcpf(m);
-                half2_t gp[R / 2];
+                if (!weights_once || c0 == 0) {
+                    if constexpr (!GS_ONCE) {
 #pragma unroll
-                for (int j = 0; j < R; j += 2)
-                    gp[j / 2] = half2_t{(_Float16)(gsc[j] * rm), (_Float16)(gsc[j + 1] * rm)};
+                        for (int j = 0; j < R; ++j)
+                            gs[j] = __builtin_bit_cast(
+                                float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, g), (part * R + j) * LPJ));
+                    }
+                    float gsc[R];
+                    m = 1.17549435e-38f;
+#pragma unroll
+                    for (int j = 0; j < R; ++j) {
+                        gsc[j] = gs[j] * decode_scale(sc[j], scale_bytes, (j & 1) ? sc_odd ^ (nblk & 1) : sc_odd);
+                        m = fmaxf(m, fabsf(gsc[j]));
+                    }
+                    const float rm = __builtin_amdgcn_rcpf(m);
+#pragma unroll
+                    for (int j = 0; j < R; j += 2) {
+                        // product rounded to fp32, then to fp16, in every variant of the kernel: left to itself the
+                        // compiler fuses some of these into one mixed-precision instruction with a single rounding,
+                        // and not the same ones in every variant
+                        float p0 = gsc[j] * rm, p1 = gsc[j + 1] * rm;
+                        asm volatile("" : "+v"(p0), "+v"(p1));
+                        gp[j / 2] = half2_t{(_Float16)p0, (_Float16)p1};
+                    }
+                }
                 // refill: the next part of this chunk, else the next chunk / the wave's next token
                 const bool more = part + 1 < H;
                 if (more || !last ? valid : nvalid)
