@@ -278,7 +278,12 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
     const uint32_t block_magic = (uint32_t)(0x100000000ull / (uint32_t)a.block) + 1u;
     const int sbytes_is4 = scale_bytes == 4;
     int sc_odd = 0;   // parity of the scale index of row 0 of the chunk held in sc[] (bf16 scales; per lane)
-    auto load_part = [&](uint32_t (&cw)[R], uint32_t (&ch)[R], uint32_t (&sc)[R], int64_t row, int col, int part) {
+    // One block per row (block = d) and all experts in one part: a row's scale serves every chunk of the token, so it
+    // is loaded with the token's first chunk only, and the weights gate x scale are formed there only (a tenth of a
+    // chunk's vector instructions).  NF4 only: NF3 sits at its register limit without the values kept.
+    const bool weights_once = BITS == 4 && H == 1 && nblk == 1;
+    auto load_part = [&](uint32_t (&cw)[R], uint32_t (&ch)[R], uint32_t (&sc)[R], int64_t row, int col, int part,
+                         bool with_scales) {
         const int64_t e_row = row * (int64_t)N + part * R;                              // first expert row of the part
         const uint8_t *rp = codes + e_row * row_bytes;                                  // uniform
         const int64_t s0 = sc_off + e_row * nblk;                                       // uniform: scale index of its block 0
@@ -301,12 +306,14 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
 #pragma unroll
         for (int j = 0; j < R; ++j) {
             load_codes<BITS>(cw[j], ch[j], rp, vc_lo, vc_hi);
-            sc[j] = ld_uniform<uint32_t>(sbase, vs[j & 1]);
             vc_lo += (uint32_t)row_bytes;
-            vs[j & 1] += vs_step;
             // keep these running sums: rewritten as offset + j * step they need a scalar register per product
             asm volatile("" : "+v"(vc_lo));
-            asm volatile("" : "+v"(vs[j & 1]));
+            if (with_scales) {
+                sc[j] = ld_uniform<uint32_t>(sbase, vs[j & 1]);
+                vs[j & 1] += vs_step;
+                asm volatile("" : "+v"(vs[j & 1]));
+            }
             if (BITS == 3) {
                 vc_hi += (uint32_t)row_bytes;
                 asm volatile("" : "+v"(vc_hi));
@@ -320,7 +327,7 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
     bool valid = row >= 0 && row < a.rows;
     uint32_t cw[R], ch[R], sc[R];
     if (valid)
-        load_part(cw, ch, sc, row, min(col0, dlast), 0);
+        load_part(cw, ch, sc, row, min(col0, dlast), 0, true);
     __syncthreads();    // pair table, router weight and norm weight are in LDS
 
     for (; item < T; item += stride) {
@@ -348,11 +355,8 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
                 gs[j] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, g), j * LPJ));
         }
 
-        // One block per row (block = d) and all experts in one part: the weights gate x scale are the same for every
-        // chunk of the token, so they are formed for its first chunk only (a tenth of the chunk's vector instructions)
-        half2_t gp[R / 2];
+        half2_t gp[R / 2];      // weights_once: kept from the token's first chunk
         float m = 1.f;
-        const bool weights_once = BITS == 4 && H == 1 && nblk == 1;    // NF3 sits at its register limit without it
         for (int c0 = 0; c0 < d; c0 += 512) {
             const int cc = c0 + col0;
             const bool on = cc < d;
@@ -405,7 +409,8 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
                 const bool more = part + 1 < H;
                 if (more || !last ? valid : nvalid)
                     load_part(cw, ch, sc, more || !last ? row : nrow,
-                              min(more ? cc : (last ? col0 : cc + 512), dlast), more ? part + 1 : 0);
+                              min(more ? cc : (last ? col0 : cc + 512), dlast), more ? part + 1 : 0,
+                              !weights_once || last);
                 if (valid) {
                     float pa[8];
 #pragma unroll
@@ -419,8 +424,10 @@ __global__ __launch_bounds__(WPB * 64) void fwd_nf_kernel(NfArgs a, int scale_by
                         acc[e] = fmaf(pa[e], m, acc[e]);
                 }
             }
-            add8(acc, sv);
-            add8(acc, rv);
+            if (sbase)                  // wave-uniform: a missing term costs no unpacking and adding of zeros
+                add8(acc, sv);
+            if (NORM || rbase)
+                add8(acc, rv);
             if (on)
                 st16_stream(obase + off, pack8_cvt(acc));
         }
