@@ -195,12 +195,14 @@ __device__ __forceinline__ uint4 ld16_row(const uint16_t *p)
 }
 
 // Router weight [d, N] -> LDS as (W[k,j], W[k+1,j]) bf16 pairs.  The 16-byte piece holding experts
-// 4*jq..4*jq+3 of k-pair q (k = 8*kg + 2*q, +1) of k-group kg sits at index
-// (q*N/4 + jq) * (kgroups + 1) + kg: lanes (consecutive kg) read consecutive pieces, and the one piece
-// of padding per plane spreads the planes over the banks for the fill's writes.
+// 4*jq..4*jq+3 of k-pair q (k = 8*kg + 2*q, +1) of k-group kg sits at index kg * (N + 1) + q*N/4 + jq: the N
+// pieces of a k-group lie together, so a lane (one k-group per piece of h) forms one address and reaches its N
+// pieces through the instruction's constant offset (with the pieces of a plane together instead, every read took a
+// vector add for its address: the plane stride depends on d).  The one piece of padding per k-group makes the
+// lanes' stride 4 dwords modulo the 64 banks: any 16 consecutive lanes' 16-byte reads cover all banks once.
 // The fill reads W_r with consecutive threads on consecutive 8-byte pieces (row pairs are 2*N*2 bytes
 // of contiguous memory) and issues a batch of loads before it touches any of them.
-__host__ __device__ constexpr size_t router_lds_bytes(int d, int N) { return (size_t)N * ((d >> 3) + 1) * 16; }
+__host__ __device__ constexpr size_t router_lds_bytes(int d, int N) { return (size_t)(d >> 3) * (N + 1) * 16; }
 
 // NREAL < N (= 4): the weight has only NREAL (= 2) columns; the missing experts get zero weights here and
 // are removed from the softmax in router_gate.
@@ -235,7 +237,7 @@ __device__ __forceinline__ void fill_router_lds(uint4 *smem, const uint16_t *Wr,
                 v.y = (w0[u].x >> 16) | (w1[u].x & 0xffff0000u);
                 v.z = (w0[u].y & 0xffffu) | (w1[u].y << 16);
                 v.w = (w0[u].y >> 16) | (w1[u].y & 0xffff0000u);
-                smem[((kp & 3) * NQ + jq) * (kgroups + 1) + (kp >> 2)] = v;
+                smem[(kp >> 2) * (N + 1) + (kp & 3) * NQ + jq] = v;
             }
         }
     }
@@ -251,7 +253,7 @@ __device__ __forceinline__ void router_piece(float (&z)[N], const uint4 *smem, i
     for (int q = 0; q < 4; ++q) {
 #pragma unroll
         for (int jq = 0; jq < NQ; ++jq) {
-            const uint4 w = smem[(q * NQ + jq) * (kgroups + 1) + kg];
+            const uint4 w = smem[kg * (N + 1) + q * NQ + jq];
             z[4 * jq + 0] = mac2(z[4 * jq + 0], hp[q], w.x);
             z[4 * jq + 1] = mac2(z[4 * jq + 1], hp[q], w.y);
             z[4 * jq + 2] = mac2(z[4 * jq + 2], hp[q], w.z);
@@ -288,7 +290,7 @@ __device__ __forceinline__ void router_piece_scaled(float (&z)[N], const uint4 *
         const uint32_t lo = cvt_pk_bf16(a0 - bf16lo(hi), a1 - bf16hi(hi));
 #pragma unroll
         for (int jq = 0; jq < NQ; ++jq) {
-            const uint4 w = smem[(q * NQ + jq) * (kgroups + 1) + kg];
+            const uint4 w = smem[kg * (N + 1) + q * NQ + jq];
             z[4 * jq + 0] = mac2(mac2(z[4 * jq + 0], hi, w.x), lo, w.x);
             z[4 * jq + 1] = mac2(mac2(z[4 * jq + 1], hi, w.y), lo, w.y);
             z[4 * jq + 2] = mac2(mac2(z[4 * jq + 2], hi, w.z), lo, w.z);
