@@ -174,7 +174,7 @@ int mole_oracle_layer_forward(const void *table, int table_dtype, const int32_t 
 {
     if (!table || !ids || !x || !ln_w || !W_r || !out || T < 0 || V <= 0 || d <= 0 || N <= 0)
         return 1;
-    double *hn = (double *)malloc(sizeof(double) * (size_t)(T > 0 ? T : 1) * (size_t)d);
+    double *hn = (double *)calloc((size_t)(T > 0 ? T : 1) * (size_t)d, sizeof(double));
     double *gates = (double *)malloc(sizeof(double) * (size_t)(T > 0 ? T : 1) * (size_t)N);
     if (!hn || !gates) {
         free(hn);
